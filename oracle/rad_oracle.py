@@ -1,0 +1,475 @@
+"""CPU oracle for the Randomized-AD (RAD) linear-layer training step.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition of what the
+HIP library computes.  Only tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py may import it.  It shares no code with the HIP
+path and never imports it.
+
+Everything floating point accumulates in fp64 (numpy matmul / einsum as the
+library primitive); values are rounded to the storage dtype (fp32, or bf16 with
+round-to-nearest-even) exactly at the places a layer output or a stored sample
+leaves a kernel.  Integer work (keys, selection, indices) is exact.
+
+Notation follows the paper (Section 3.2 and Section 4.2): a linear layer has
+input x [B, D], weight W [D, N], pre-activation h = x W + b, activation
+y = ReLU(h); the upstream gradient is dy = dL/dy, g = dy * 1[h > 0].  RAD
+replaces the stored x by x~ = x P with E[P] = I_D (Section 3.2, the random
+matrix P), so that dW~ = x~^T g is an unbiased estimate of dW = x^T g, while
+dX = g W^T never touches a sampled quantity (Section 4.2: only dh/dW is
+sampled, so every parameter-to-loss path crosses one sampled Jacobian).
+
+Pins (tests/test_oracle_*.py): Philox against PyTorch's own Philox4_32 engine;
+k = ceil(p d) against the eight worked values of Appendix A; byte accounting
+against Appendix A and Table 1; p = 1 against torch autograd; mean and variance
+over seeds against closed forms; selection against brute force.  Convergence
+curves of the paper (figures only) are not reproducible: parity unpinned there.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+# ----------------------------------------------------------------------------
+# Sampling schemes (values are part of the C ABI; the oracle repeats them).
+# ----------------------------------------------------------------------------
+EXACT = 0               # store everything (the paper's baseline)
+BERNOULLI = 1           # keep each entry with probability p, scale 1/p
+FIXEDK_SHARED = 2       # "same sample": one k-subset for the whole minibatch
+FIXEDK_PER_EXAMPLE = 3  # "different sample": a k-subset per minibatch element
+
+F32 = 0
+BF16 = 1
+
+_M0 = np.uint64(0xD2511F53)
+_M1 = np.uint64(0xCD9E8D57)
+_W0 = 0x9E3779B9
+_W1 = 0xBB67AE85
+_MASK32 = np.uint64(0xFFFFFFFF)
+
+
+# ----------------------------------------------------------------------------
+# Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+# as 1, 2, 3", SC'11).  The paper names no generator; a counter-based one makes
+# the sample a pure function of (seed, tensor, step, element).
+# ----------------------------------------------------------------------------
+def philox4x32_10(c0, c1, c2, c3, k0, k1):
+    """Ten Philox rounds on arrays of 32-bit counter words; returns 4 arrays."""
+    c0 = np.asarray(c0, dtype=np.uint64)
+    c1 = np.asarray(c1, dtype=np.uint64)
+    c2 = np.asarray(c2, dtype=np.uint64)
+    c3 = np.asarray(c3, dtype=np.uint64)
+    k0 = int(k0) & 0xFFFFFFFF
+    k1 = int(k1) & 0xFFFFFFFF
+    for r in range(10):
+        if r > 0:
+            k0 = (k0 + _W0) & 0xFFFFFFFF
+            k1 = (k1 + _W1) & 0xFFFFFFFF
+        p0 = _M0 * c0          # 32x32 -> 64 bit product, exact in uint64
+        p1 = _M1 * c2
+        hi0, lo0 = p0 >> np.uint64(32), p0 & _MASK32
+        hi1, lo1 = p1 >> np.uint64(32), p1 & _MASK32
+        c0, c1, c2, c3 = (hi1 ^ c1 ^ np.uint64(k0), lo1,
+                          hi0 ^ c3 ^ np.uint64(k1), lo0)
+    return (c0.astype(np.uint32), c1.astype(np.uint32),
+            c2.astype(np.uint32), c3.astype(np.uint32))
+
+
+def element_keys(seed, stream_id, step, first, count):
+    """One u32 key for each flat element index f in [first, first+count).
+
+    Addressing (the paper is silent; this is the library's definition):
+    Philox key = (seed low word, seed high word); counter =
+    (floor(f/4) low word, floor(f/4) high word, stream_id, step); the element
+    takes output word f mod 4.  Keys therefore depend on nothing but
+    (seed, stream_id, step, f).
+    """
+    f = np.arange(first, first + count, dtype=np.uint64)
+    q = f >> np.uint64(2)
+    w = (f & np.uint64(3)).astype(np.int64)
+    out = philox4x32_10(q & _MASK32, q >> np.uint64(32),
+                        np.uint64(stream_id & 0xFFFFFFFF),
+                        np.uint64(step & 0xFFFFFFFF),
+                        seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    stacked = np.stack(out, axis=-1)
+    return np.take_along_axis(stacked, w[:, None], axis=1)[:, 0]
+
+
+# ----------------------------------------------------------------------------
+# Selection rules.
+# ----------------------------------------------------------------------------
+def fixed_k(p, d):
+    """Number of stored coordinates: p*d rounded up (Appendix A, memory
+    calculation), kept inside [1, d].  The 1e-9 guards products such as
+    0.1*300 that land an ulp above an integer in binary floating point."""
+    return int(min(d, max(1, math.ceil(p * d - 1e-9))))
+
+
+def bernoulli_threshold(p):
+    """Keep iff key < T with T = round(p * 2^32) held in 64 bits (p = 1 keeps
+    every key)."""
+    return int(round(p * 4294967296.0))
+
+
+def sample_scale(scheme, p, d):
+    """Inverse inclusion probability, as fp32.  Bernoulli: 1/p.  Fixed-k
+    without replacement: d/k (Section 3.2 scales by d/k)."""
+    if scheme == EXACT:
+        return np.float32(1.0)
+    if scheme == BERNOULLI:
+        return np.float32(1.0 / p)
+    return np.float32(float(d) / float(fixed_k(p, d)))
+
+
+def keep_mask(scheme, p, seed, stream_id, step, rows, d):
+    """Boolean [rows, d]: which entries of the sampled tensor are stored.
+
+    Bernoulli: key < T.  Fixed-k: the k smallest (key, j) pairs of the row in
+    lexicographic order (ties go to the lower j), i.e. a uniform k-subset
+    without replacement: the variant the paper says makes fraction 1.0 equal
+    to the baseline (Appendix A, fraction sweep caption).  Shared scheme: the
+    keys of row 0 addressing (f = j) serve every row.
+    """
+    if scheme == EXACT:
+        return np.ones((rows, d), dtype=bool)
+    if scheme == BERNOULLI:
+        keys = element_keys(seed, stream_id, step, 0, rows * d).reshape(rows, d)
+        return keys.astype(np.uint64) < np.uint64(bernoulli_threshold(p))
+    k = fixed_k(p, d)
+    if scheme == FIXEDK_SHARED:
+        keys = element_keys(seed, stream_id, step, 0, d).reshape(1, d)
+    elif scheme == FIXEDK_PER_EXAMPLE:
+        keys = element_keys(seed, stream_id, step, 0, rows * d).reshape(rows, d)
+    else:
+        raise ValueError("unknown scheme")
+    order = np.argsort(keys, axis=1, kind="stable")   # stable: ties by lower j
+    mask = np.zeros(keys.shape, dtype=bool)
+    np.put_along_axis(mask, order[:, :k], True, axis=1)
+    if scheme == FIXEDK_SHARED:
+        mask = np.broadcast_to(mask, (rows, d)).copy()
+    return mask
+
+
+# ----------------------------------------------------------------------------
+# Storage dtype rounding.
+# ----------------------------------------------------------------------------
+def round_bf16(a):
+    """fp32 -> bfloat16 (round to nearest, ties to even) -> fp32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)) << np.uint64(16)
+    out = (r & _MASK32).astype(np.uint32).view(np.float32)
+    return np.where(np.isnan(a), a, out).reshape(a.shape)
+
+
+def to_storage(a, dtype):
+    """Round an fp64/fp32 array to the storage dtype, returned as fp32."""
+    a32 = np.asarray(a, dtype=np.float64).astype(np.float32)
+    return round_bf16(a32) if dtype == BF16 else a32
+
+
+# ----------------------------------------------------------------------------
+# The compressed store.
+# ----------------------------------------------------------------------------
+def sample_pack(x, scheme, p, seed, stream_id, step, dtype=F32):
+    """x [rows, d] (already in storage precision) -> (row_ptr, col, val, xt).
+
+    val = storage(x * scale) for kept entries, ascending column per row; xt is
+    the same thing scattered back into a dense [rows, d] array (x~ = x P of
+    Section 3.2 with P diagonal).  Sampled zeros are stored like any value, so
+    the size never depends on the data.
+    """
+    x = np.asarray(x, dtype=np.float32)
+    rows, d = x.shape
+    mask = keep_mask(scheme, p, seed, stream_id, step, rows, d)
+    scale = sample_scale(scheme, p, d)
+    scaled = to_storage(x * scale, dtype)            # one fp32 multiply, one rounding
+    xt = np.where(mask, scaled, np.float32(0.0))
+    row_ptr = np.zeros(rows + 1, dtype=np.int64)
+    row_ptr[1:] = np.cumsum(mask.sum(axis=1))
+    r, c = np.nonzero(mask)                          # row-major => ascending col per row
+    return row_ptr, c.astype(np.int32), scaled[r, c], xt
+
+
+# ----------------------------------------------------------------------------
+# Linear layer.
+# ----------------------------------------------------------------------------
+def linear_forward(x, W, bias, relu, dtype=F32):
+    """h = x W + b with the exact x (Section 3: the forward pass is the
+    original graph); returns (h fp64, y storage-rounded fp32, bits bool).
+    The ReLU Jacobian is one bit per entry (Section 4.2): bits = h > 0."""
+    h = np.asarray(x, dtype=np.float64) @ np.asarray(W, dtype=np.float64)
+    if bias is not None:
+        h = h + np.asarray(bias, dtype=np.float64)[None, :]
+    if relu:
+        bits = h > 0.0
+        y = np.where(bits, h, 0.0)
+    else:
+        bits = np.ones(h.shape, dtype=bool)
+        y = h
+    return h, to_storage(y, dtype), bits
+
+
+def backward_dW(xt, dy, bits):
+    """dW~ = x~^T (dy * bits): the sampled Jacobian dh/dW of Section 4.2."""
+    g = np.asarray(dy, dtype=np.float64) * bits
+    return np.asarray(xt, dtype=np.float64).T @ g
+
+
+def backward_db(dy, bits):
+    return (np.asarray(dy, dtype=np.float64) * bits).sum(axis=0)
+
+
+def backward_dX(dy, bits, W):
+    """dX = (dy * bits) W^T: exact, independent of p and seed."""
+    g = np.asarray(dy, dtype=np.float64) * bits
+    return g @ np.asarray(W, dtype=np.float64).T
+
+
+# ----------------------------------------------------------------------------
+# Loss: softmax cross-entropy, mean over the batch.  Logits stay dense
+# (Appendix A: the softmax input is not sampled).
+# ----------------------------------------------------------------------------
+def softmax_ce(z, labels):
+    z = np.asarray(z, dtype=np.float64)
+    b = z.shape[0]
+    zs = z - z.max(axis=1, keepdims=True)
+    e = np.exp(zs)
+    s = e.sum(axis=1, keepdims=True)
+    logp = zs - np.log(s)
+    loss = -logp[np.arange(b), labels].mean()
+    dz = e / s
+    dz[np.arange(b), labels] -= 1.0
+    return loss, dz / b
+
+
+# ----------------------------------------------------------------------------
+# Multi-layer perceptron train step (Section 4.2, generalised chain).
+# ----------------------------------------------------------------------------
+def mlp_train_step(x, labels, Ws, bs, scheme, p, seed, stream_base=0, step=0,
+                   dtype=F32, bits_override=None):
+    """Forward with exact activations, storing for each layer only the sample
+    of its input and its ReLU bits; backward from those.
+
+    Layer l samples with stream_id = stream_base + l.  All layers but the last
+    have ReLU.  Returns a dict with loss, per-layer dW/db, stores, bits,
+    activations and the dy chain.  bits_override (list of bool arrays) lets a
+    test rerun the backward with ReLU bits taken from elsewhere.
+    """
+    L = len(Ws)
+    act = to_storage(x, dtype)
+    stores, bits_l, acts = [], [], [act]
+    for l in range(L):
+        stores.append(sample_pack(act, scheme, p, seed, stream_base + l, step, dtype))
+        _, y, bits = linear_forward(act, Ws[l], None if bs is None else bs[l],
+                                    relu=(l < L - 1), dtype=dtype)
+        if bits_override is not None and l < L - 1:
+            bits = bits_override[l]
+        bits_l.append(bits)
+        act = y
+        acts.append(act)
+    loss, dz = softmax_ce(act, labels)
+    dy = to_storage(dz, dtype)
+    dWs, dbs, dys = [None] * L, [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        dys[l] = dy
+        dWs[l] = backward_dW(stores[l][3], dy, bits_l[l])
+        dbs[l] = backward_db(dy, bits_l[l])
+        if l > 0:
+            dy = to_storage(backward_dX(dy, bits_l[l], Ws[l]), dtype)
+    return dict(loss=loss, dW=dWs, db=dbs, stores=stores, bits=bits_l,
+                acts=acts, dy=dys)
+
+
+# ----------------------------------------------------------------------------
+# Convolution (stride 1, zero padding) written as the sum it is; weights are
+# laid out [C_in, KH, KW, C_out] so that the flattened [C_in*KH*KW, C_out]
+# matrix is the W of the equivalent im2col GEMM.  Activations are NCHW.
+# The sampled tensor is the layer input, flattened to [B, C*H*W] (Figure 5:
+# spatial elements of the input are sampled and dH/dW is formed from the
+# sparse tensor).
+# ----------------------------------------------------------------------------
+def conv2d_forward(x, W, bias, pad, relu):
+    x = np.asarray(x, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    b, ci, hh, ww = x.shape
+    _, kh, kw, co = W.shape
+    xp = np.zeros((b, ci, hh + 2 * pad, ww + 2 * pad))
+    xp[:, :, pad:pad + hh, pad:pad + ww] = x
+    ho, wo = hh + 2 * pad - kh + 1, ww + 2 * pad - kw + 1
+    h = np.zeros((b, co, ho, wo))
+    for u in range(kh):
+        for v in range(kw):
+            # h[b,o,y,x] += sum_c xp[b,c,y+u,x+v] * W[c,u,v,o]
+            h += np.einsum("bcyx,co->boyx", xp[:, :, u:u + ho, v:v + wo], W[:, u, v, :])
+    if bias is not None:
+        h = h + np.asarray(bias, dtype=np.float64)[None, :, None, None]
+    if relu:
+        bits = h > 0.0
+        y = np.where(bits, h, 0.0)
+    else:
+        bits = np.ones(h.shape, dtype=bool)
+        y = h
+    return h, y.astype(np.float32), bits
+
+
+def conv2d_dW(xt, g, kh, kw, pad):
+    """dW[c,u,v,o] = sum_{b,y,x} xt_padded[b,c,y+u,x+v] * g[b,o,y,x]."""
+    xt = np.asarray(xt, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    b, ci, hh, ww = xt.shape
+    co, ho, wo = g.shape[1:]
+    xp = np.zeros((b, ci, hh + 2 * pad, ww + 2 * pad))
+    xp[:, :, pad:pad + hh, pad:pad + ww] = xt
+    dW = np.zeros((ci, kh, kw, co))
+    for u in range(kh):
+        for v in range(kw):
+            dW[:, u, v, :] = np.einsum("bcyx,boyx->co", xp[:, :, u:u + ho, v:v + wo], g)
+    return dW
+
+
+def conv2d_dX(g, W, pad, in_hw):
+    """dX[b,c,i,j] = sum_{o,u,v} g[b,o,i-u+pad,j-v+pad] * W[c,u,v,o]."""
+    g = np.asarray(g, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    b, co, ho, wo = g.shape
+    ci, kh, kw, _ = W.shape
+    hh, ww = in_hw
+    dxp = np.zeros((b, ci, hh + 2 * pad, ww + 2 * pad))
+    for u in range(kh):
+        for v in range(kw):
+            dxp[:, :, u:u + ho, v:v + wo] += np.einsum("boyx,co->bcyx", g, W[:, u, v, :])
+    return dxp[:, :, pad:pad + hh, pad:pad + ww]
+
+
+def maxpool2x2_forward(a):
+    """2x2/stride-2 max pool; argmax = first maximum in (dy, dx) row-major
+    order, stored in 2 bits."""
+    a = np.asarray(a)
+    b, c, hh, ww = a.shape
+    win = a.reshape(b, c, hh // 2, 2, ww // 2, 2).transpose(0, 1, 2, 4, 3, 5)
+    win = win.reshape(b, c, hh // 2, ww // 2, 4)
+    arg = np.argmax(win, axis=-1)          # numpy returns the first maximum
+    out = np.take_along_axis(win, arg[..., None], axis=-1)[..., 0]
+    return out, arg.astype(np.uint8)
+
+
+def maxpool2x2_backward(dout, arg):
+    dout = np.asarray(dout, dtype=np.float64)
+    b, c, ho, wo = dout.shape
+    win = np.zeros((b, c, ho, wo, 4))
+    np.put_along_axis(win, arg[..., None].astype(np.int64), dout[..., None], axis=-1)
+    win = win.reshape(b, c, ho, wo, 2, 2).transpose(0, 1, 2, 4, 3, 5)
+    return win.reshape(b, c, ho * 2, wo * 2)
+
+
+def cnn_train_step(x, labels, convs, fc, scheme, p, seed, stream_base=0, step=0):
+    """convs: list of dicts(W [ci,kh,kw,co], b [co], pad, pool bool); every conv
+    is followed by ReLU and, if pool, a 2x2 max pool.  fc = (W [D,10], b).
+    Each conv input and the FC input is sampled (flattened per example)."""
+    act = np.asarray(x, dtype=np.float32)
+    B = act.shape[0]
+    tape, stores = [], []
+    for l, cv in enumerate(convs):
+        st = sample_pack(act.reshape(B, -1), scheme, p, seed, stream_base + l, step)
+        stores.append(st)
+        _, y, bits = conv2d_forward(act, cv["W"], cv["b"], cv["pad"], relu=True)
+        arg = None
+        in_shape = act.shape
+        if cv["pool"]:
+            y, arg = maxpool2x2_forward(y)
+        tape.append((in_shape, bits, arg))
+        act = y.astype(np.float32)
+    flat = act.reshape(B, -1)
+    st_fc = sample_pack(flat, scheme, p, seed, stream_base + len(convs), step)
+    stores.append(st_fc)
+    _, z, _ = linear_forward(flat, fc[0], fc[1], relu=False)
+    loss, dz = softmax_ce(z, labels)
+    dz = dz.astype(np.float32)
+    ones = np.ones(dz.shape, dtype=bool)
+    dW_fc = backward_dW(st_fc[3], dz, ones)
+    db_fc = backward_db(dz, ones)
+    dy = backward_dX(dz, ones, fc[0]).astype(np.float32).reshape(act.shape)
+    dWs, dbs = [None] * len(convs), [None] * len(convs)
+    for l in range(len(convs) - 1, -1, -1):
+        cv = convs[l]
+        in_shape, bits, arg = tape[l]
+        if arg is not None:
+            dy = maxpool2x2_backward(dy, arg)
+        g = np.asarray(dy, dtype=np.float64) * bits
+        kh, kw = cv["W"].shape[1:3]
+        dWs[l] = conv2d_dW(stores[l][3].reshape(in_shape), g, kh, kw, cv["pad"])
+        dbs[l] = g.sum(axis=(0, 2, 3))
+        if l > 0:
+            dy = conv2d_dX(g, cv["W"], cv["pad"], in_shape[2:]).astype(np.float32)
+    return dict(loss=loss, dW=dWs, db=dbs, dW_fc=dW_fc, db_fc=db_fc,
+                stores=stores, logits=z)
+
+
+# ----------------------------------------------------------------------------
+# Vanilla ReLU RNN with BPTT (Appendix A, recurrent architecture):
+# h_t = ReLU(x_t W_ih + h_{t-1} W_hh + b), t = 1..T, h_0 = 0; logits =
+# h_T W_ho + b_o.  A fresh sample of h_{t-1} is stored at every time step
+# (Appendix A, RNN training details); the 1-dimensional x_t is kept whole
+# (ceil(0.1*1) = 1 in Appendix A's count).
+# ----------------------------------------------------------------------------
+def rnn_train_step(x, labels, W_ih, W_hh, b, W_ho, b_o, scheme, p, seed,
+                   stream_base=0):
+    """x [B, T, I].  Sampling of h_{t-1} uses stream_id = stream_base and
+    step = t (t = 1..T; nothing is stored for t = 1 because h_0 = 0); the
+    output layer samples h_T with stream_id = stream_base + 1, step = 0."""
+    x = np.asarray(x, dtype=np.float32)
+    B, T, _ = x.shape
+    H = W_hh.shape[0]
+    h_prev = np.zeros((B, H), dtype=np.float32)
+    xts, bits_t = [None] * (T + 1), [None] * (T + 1)
+    W_ih64 = np.asarray(W_ih, dtype=np.float64)
+    W_hh64 = np.asarray(W_hh, dtype=np.float64)
+    b64 = np.asarray(b, dtype=np.float64)
+    for t in range(1, T + 1):
+        if t > 1:
+            xts[t] = sample_pack(h_prev, scheme, p, seed, stream_base, t)[3]
+        pre = (x[:, t - 1, :].astype(np.float64) @ W_ih64
+               + h_prev.astype(np.float64) @ W_hh64 + b64[None, :])
+        bits_t[t] = pre > 0.0
+        h_prev = np.where(bits_t[t], pre, 0.0).astype(np.float32)
+    st_o = sample_pack(h_prev, scheme, p, seed, stream_base + 1, 0)
+    _, z, _ = linear_forward(h_prev, W_ho, b_o, relu=False)
+    loss, dz = softmax_ce(z, labels)
+    dz = dz.astype(np.float32)
+    ones = np.ones(dz.shape, dtype=bool)
+    dW_ho = backward_dW(st_o[3], dz, ones)
+    db_o = backward_db(dz, ones)
+    dh = backward_dX(dz, ones, W_ho).astype(np.float32)
+    dW_hh = np.zeros((H, H))
+    dW_ih = np.zeros(W_ih64.shape)
+    db = np.zeros(H)
+    for t in range(T, 0, -1):
+        g = dh.astype(np.float64) * bits_t[t]
+        if t > 1:
+            dW_hh += xts[t].astype(np.float64).T @ g
+        dW_ih += x[:, t - 1, :].astype(np.float64).T @ g
+        db += g.sum(axis=0)
+        dh = (g @ W_hh64.T).astype(np.float32)
+    return dict(loss=loss, dW_hh=dW_hh, dW_ih=dW_ih, db=db, dW_ho=dW_ho,
+                db_o=db_o, h_T=h_prev, logits=z)
+
+
+# ----------------------------------------------------------------------------
+# Byte accounting, in the paper's convention (Appendix A, "Calculation of
+# memory saved from RAD"): 32-bit values for the stored (sampled) inputs,
+# ceil(p d) of them per input, one bit per un-reduced ReLU entry, the softmax
+# input unsampled, nothing for pooling and biases; indices are not counted.
+# ----------------------------------------------------------------------------
+def paper_bytes_per_example(sampled_dims, logits, relu_entries, p):
+    if p >= 1.0:
+        return 4.0 * (sum(sampled_dims) + logits)
+    vals = sum(fixed_k(p, d) for d in sampled_dims) + logits
+    return 4.0 * vals + relu_entries / 8.0
+
+
+def paper_total_megabytes(n_params, batch, sampled_dims, logits, relu_entries, p):
+    """Table 1: weights plus batch * per-example bytes, in 10^6-byte MB."""
+    return (4.0 * n_params + batch * paper_bytes_per_example(
+        sampled_dims, logits, relu_entries, p)) / 1e6
