@@ -1,0 +1,244 @@
+/*
+ * rad.h: C ABI of the MI355X (gfx950) library for the hot path of Randomized
+ * Automatic Differentiation (Oktay, McGreivy, Aduol, Beatson, Adams, 2020):
+ * the training step of a linear layer that keeps, instead of its input x, a
+ * random inverse-probability-scaled sample x~ = x P (Section 3.2: E[P] = I)
+ * plus one ReLU bit per output (Section 4.2), and forms the unbiased weight
+ * gradient dW~ = x~^T g from that compressed store while dX = g W^T stays
+ * exact (Section 4.2: only dh/dW is sampled).
+ *
+ * Conventions for every entry point
+ *   - Tensor pointers are DEVICE pointers owned by the caller, row-major and
+ *     contiguous, 16-byte aligned; the library keeps none of them after the
+ *     call returns.  Pointers documented "host" are host memory.
+ *   - x [batch, d_in], W [d_in, d_out], bias [d_out], y and dy [batch, d_out],
+ *     dW [d_in, d_out] (always fp32), dX [batch, d_in].  Element type of
+ *     x, W, y, dy, dX is rad_layer.dtype; bias, dW, dbias are fp32.
+ *   - Work is enqueued on the HIP stream given to rad_ctx_create and is
+ *     asynchronous unless the function is documented to synchronise.
+ *   - Every failure is a status code; rad_last_error(ctx) has the text.  All
+ *     arguments are validated before the first launch, so a failed call has
+ *     no device side effects.  Nothing aborts or throws across this ABI.
+ *   - There is no CPU fallback: without a HIP device rad_ctx_create fails.
+ */
+#ifndef RAD_H_
+#define RAD_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RAD_OK = 0,
+  RAD_ERR_NULL = 1,        /* a required pointer is null */
+  RAD_ERR_SHAPE = 2,       /* negative/oversized/inconsistent dimensions */
+  RAD_ERR_PARAM = 3,       /* p outside (0,1], unknown enum value */
+  RAD_ERR_UNSUPPORTED = 4, /* valid request this build has no kernel for */
+  RAD_ERR_CAPACITY = 5,    /* a Bernoulli draw exceeded the store's capacity */
+  RAD_ERR_DEVICE = 6       /* HIP runtime error */
+} rad_status;
+
+typedef enum { RAD_F32 = 0, RAD_BF16 = 1 } rad_dtype; /* accumulation is always fp32 */
+
+/* Which entries of the layer input are stored (Section 3.2, Section 4.3).
+ * EXACT keeps everything (the baseline).  BERNOULLI keeps each entry with
+ * probability p and scales by 1/p.  The two FIXEDK schemes keep
+ * k = rad_fixed_k(p, d_in) coordinates drawn without replacement and scale
+ * by d_in/k: SHARED uses one index set for the whole minibatch (the paper's
+ * "same sample"), PER_EXAMPLE an independent one per row ("different
+ * sample"). */
+typedef enum {
+  RAD_EXACT = 0,
+  RAD_BERNOULLI = 1,
+  RAD_FIXEDK_SHARED = 2,
+  RAD_FIXEDK_PER_EXAMPLE = 3
+} rad_scheme;
+
+typedef enum { RAD_LINEAR = 0, RAD_CONV2D = 1 } rad_kind;
+
+/* One linear layer (Section 4.2).  For RAD_CONV2D (Figure 5) the layer is a
+ * stride-1 convolution computed as an implicit im2col GEMM: x is NCHW
+ * [batch, c_in, h, w] (d_in = c_in*h*w, the flattened tensor is what is
+ * sampled), W is [c_in, kh, kw, c_out], y is NCHW [batch, c_out, h, w]
+ * (d_out = c_out*h*w; pad must keep the spatial size: 2*pad = kh-1 = kw-1). */
+typedef struct {
+  int32_t kind;     /* rad_kind */
+  int32_t dtype;    /* rad_dtype */
+  int64_t batch;
+  int64_t d_in;
+  int64_t d_out;
+  int32_t relu;     /* y = max(h, 0) and one stored bit per output */
+  int32_t has_bias;
+  int32_t c_in, h, w, c_out, kh, kw, pad; /* RAD_CONV2D only */
+} rad_layer;
+
+/* The random draw.  Keys come from Philox4x32-10 with key = (seed low word,
+ * seed high word) and counter = (floor(f/4) low, floor(f/4) high, stream_id,
+ * step), output word f mod 4, where f = row*d_in + column is the flat index
+ * of the element in the sampled tensor (f = column for RAD_FIXEDK_SHARED).
+ * stream_id separates tensors/layers, step separates RNN time steps. */
+typedef struct {
+  int32_t scheme;   /* rad_scheme */
+  double p;         /* fraction in (0, 1] */
+  uint64_t seed;
+  uint32_t stream_id;
+  uint32_t step;
+} rad_sampling;
+
+typedef struct rad_ctx rad_ctx;     /* stream + workspaces; one per stream */
+typedef struct rad_store rad_store; /* compressed store of one layer */
+typedef struct rad_model rad_model; /* layer list + stores for rad_train_step */
+
+/* Stored bytes of a store, split the way the accounting of Appendix A needs:
+ * values (what the paper counts), indices and offset tables (which the paper
+ * does not count), ReLU bits (1 per output entry, which it does). */
+typedef struct {
+  uint64_t value_bytes;
+  uint64_t index_bytes;
+  uint64_t bit_bytes;
+  uint64_t nnz;          /* stored entries */
+  uint64_t dense_bytes;  /* what storing x itself would take */
+} rad_store_stats;
+
+/* k = ceil(p*d) clamped to [1, d]: "rounded up" in Appendix A's memory
+ * calculation (784->79, 300->30, 16384->1639 at p = 0.1).  Host function. */
+int64_t rad_fixed_k(double p, int64_t d);
+
+/* Creates a context bound to hip_stream (a hipStream_t, borrowed; null = the
+ * default stream) on the current device.  Allocates workspaces lazily. */
+rad_status rad_ctx_create(rad_ctx** out, void* hip_stream);
+rad_status rad_ctx_destroy(rad_ctx* ctx);
+/* Text of the last failure on this context (static string if ctx is null). */
+const char* rad_last_error(const rad_ctx* ctx);
+/* Blocks until everything enqueued on the context's stream has finished. */
+rad_status rad_ctx_synchronize(rad_ctx* ctx);
+
+/* Per-kernel timing with HIP events recorded on the context's stream around
+ * every launch whose name contains `filter` (null = all, "" = off).
+ * rad_ctx_timing_read synchronises, then returns launches and total
+ * milliseconds since the last reset for kernels whose name contains `name`. */
+rad_status rad_ctx_timing(rad_ctx* ctx, const char* filter);
+rad_status rad_ctx_timing_read(rad_ctx* ctx, const char* name, int64_t* launches, double* total_ms);
+rad_status rad_ctx_timing_reset(rad_ctx* ctx);
+
+/* Test hook: keys are shifted right by `shift` bits (and the Bernoulli
+ * threshold likewise) before selection, which makes equal keys frequent and
+ * so exercises the tie rule of the fixed-k draw.  0 restores normal keys. */
+rad_status rad_debug_key_shift(rad_ctx* ctx, int32_t shift);
+
+/* Allocates the store for `layer` under `scheme`/`p`: value and index arrays
+ * sized for batch*k entries (fixed-k), batch*d_in (EXACT), or the Bernoulli
+ * mean plus eight standard deviations; row pointers, per-256-column offsets,
+ * and the ReLU bit array [batch, ceil(d_out/32)] words.  `steps` > 1 makes a
+ * multi-step store for BPTT: steps*batch rows, row t*batch+b drawn with
+ * step = sampling.step + t.  Requires d_in <= 65535 (16-bit indices). */
+rad_status rad_store_create(rad_ctx* ctx, const rad_layer* layer, int32_t scheme, double p,
+                            int32_t steps, rad_store** out);
+rad_status rad_store_destroy(rad_store* store);
+/* Synchronises.  Byte counts of what is currently stored. */
+rad_status rad_store_get_stats(rad_ctx* ctx, const rad_store* store, rad_store_stats* out);
+/* Synchronises.  Canonical export to HOST arrays: row_ptr [rows+1], then for
+ * each row ascending column indices and the stored (already scaled) values
+ * converted to fp32.  col/val must hold `capacity` entries; fails with
+ * RAD_ERR_CAPACITY if the store holds more, or if a Bernoulli draw overflowed
+ * the store when it was written. */
+rad_status rad_store_export_csr(rad_ctx* ctx, const rad_store* store, int64_t* row_ptr,
+                                int32_t* col, float* val, int64_t capacity);
+/* Synchronises.  ReLU bits to a HOST array [rows, ceil(d_out/32)] of words;
+ * bit (n mod 32) of word n/32 is 1[h[b,n] > 0]. */
+rad_status rad_store_export_bits(rad_ctx* ctx, const rad_store* store, uint32_t* words);
+/* Overwrites the ReLU bits from a HOST array (same layout); for tests that
+ * feed one side's bits to the other. */
+rad_status rad_store_import_bits(rad_ctx* ctx, rad_store* store, const uint32_t* words);
+
+/* Sampling alone (Section 3.2 applied to a stored input): draws the keep
+ * set for `sampling`, then writes value = storage(x * scale) and the column
+ * index of every kept entry of x [rows, cols] into `store`, ascending column
+ * within a row.  rows/cols must equal the store's batch/d_in; `step_slot`
+ * selects the block of rows of a multi-step store (0 otherwise). */
+rad_status rad_sample_pack(rad_ctx* ctx, const rad_sampling* sampling, const void* x,
+                           rad_store* store, int32_t step_slot);
+
+/* Forward of one layer with the exact x (Section 3: the forward pass uses the
+ * original graph): y = act(x W + bias); stores the sample of x drawn by
+ * `sampling` and, if layer.relu, the bits 1[h > 0] into `store`.  bias may be
+ * null iff !layer.has_bias. */
+rad_status rad_forward_sample(rad_ctx* ctx, const rad_layer* layer, const rad_sampling* sampling,
+                              const void* x, const void* W, const void* bias, void* y,
+                              rad_store* store);
+
+/* dW = beta*dW + x~^T g with g = dy * bits (g = dy if !layer.relu), from the
+ * compressed store (the sampled Jacobian dh/dW of Section 4.2); dbias (may be
+ * null) = beta*dbias + sum over rows of g.  beta must be 0 or 1 (1 accumulates
+ * over time steps in BPTT).  dW and dbias are fp32. */
+rad_status rad_backward_dW(rad_ctx* ctx, const rad_layer* layer, const rad_store* store,
+                           const void* dy, float* dW, float* dbias, float beta);
+
+/* dX = g W^T, exact: independent of p, scheme and seed (Section 4.2).  The
+ * store is read only for its ReLU bits. */
+rad_status rad_backward_dX(rad_ctx* ctx, const rad_layer* layer, const rad_store* store,
+                           const void* dy, const void* W, void* dX);
+
+/* Mean softmax cross-entropy over `rows` examples and its gradient
+ * dlogits = (softmax - onehot)/rows in the dtype of logits; labels are int32
+ * device values in [0, classes).  loss_dev is one fp32 on the device.  The
+ * softmax input is kept dense (Appendix A). */
+rad_status rad_softmax_ce(rad_ctx* ctx, const void* logits, const int32_t* labels, int64_t rows,
+                          int64_t classes, int32_t dtype, void* dlogits, float* loss_dev);
+
+/* ---- whole training steps ------------------------------------------------
+ * A model owns its stores and transient activation buffers; parameters and
+ * gradients stay with the caller.  `params` / `grads` are HOST arrays of
+ * device pointers in the order documented per model; all gradients are fp32
+ * and are overwritten.  Layer l of a model samples with
+ * stream_id = sampling.stream_id + l.  rad_train_step synchronises to return
+ * the loss in *loss_host. */
+
+/* MLP: n_layers linear layers dims[0] -> dims[1] -> ... -> dims[n_layers],
+ * ReLU after all but the last, softmax cross-entropy on the last output.
+ * params = {W_0, b_0, W_1, b_1, ...} (b_l entries present iff has_bias),
+ * grads likewise. */
+rad_status rad_model_create_mlp(rad_ctx* ctx, int32_t dtype, int64_t batch, int32_t n_layers,
+                                const int64_t* dims, int32_t has_bias, int32_t scheme, double p,
+                                rad_model** out);
+
+/* Vanilla ReLU RNN of Appendix A: h_t = ReLU(x_t W_ih + h_{t-1} W_hh + b),
+ * h_0 = 0, t = 1..T; logits = h_T W_ho + b_o; fp32.  x is [batch, T, d_input].
+ * h_{t-1} is sampled afresh at each step (stream_id, step = t), the output
+ * layer samples h_T with stream_id+1, step 0; x_t is kept whole.
+ * params = {W_ih [d_input, hidden], W_hh [hidden, hidden], b [hidden],
+ * W_ho [hidden, classes], b_o [classes]}, grads likewise. */
+rad_status rad_model_create_rnn(rad_ctx* ctx, int64_t batch, int64_t T, int64_t d_input,
+                                int64_t hidden, int64_t classes, int32_t scheme, double p,
+                                rad_model** out);
+
+/* Small CNN: n_conv stride-1 convolutions (each + bias + ReLU, and a 2x2 max
+ * pool where pool[l] != 0), then one linear layer to `classes`; fp32, NCHW.
+ * channels[0..n_conv] are c_in, c_out_0, ..., ksize is the square kernel size
+ * with pad (ksize-1)/2.  Every conv input and the linear input are sampled.
+ * params = {W_0 [c_in,k,k,c_out], b_0, ..., W_fc [d, classes], b_fc}. */
+rad_status rad_model_create_cnn(rad_ctx* ctx, int64_t batch, int32_t n_conv, const int32_t* channels,
+                                const int32_t* pool, int32_t ksize, int32_t height, int32_t width,
+                                int32_t classes, int32_t scheme, double p, rad_model** out);
+
+rad_status rad_model_destroy(rad_model* model);
+/* Number of stores and borrowed access to store l (for export and stats). */
+int32_t rad_model_num_stores(const rad_model* model);
+rad_store* rad_model_store(rad_model* model, int32_t l);
+/* Device pointer to the logits of the last step ([batch, classes], model dtype). */
+const void* rad_model_logits(const rad_model* model);
+
+/* One training step: forward with exact activations (storing only samples and
+ * bits), loss, backward from the stores.  x is the model input, labels int32
+ * device [batch].  Synchronises; *loss_host receives the mean loss.  Returns
+ * RAD_ERR_CAPACITY if a Bernoulli draw overflowed a store. */
+rad_status rad_train_step(rad_ctx* ctx, rad_model* model, const rad_sampling* sampling,
+                          const void* x, const int32_t* labels, void* const* params,
+                          void* const* grads, float* loss_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAD_H_ */

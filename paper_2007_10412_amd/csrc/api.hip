@@ -1,0 +1,854 @@
+// C ABI of the RAD library (see include/rad.h): argument checking, store and
+// workspace management, and the launch sequences of the entry points.  All
+// arithmetic of the method happens in the kernels this file launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/rad.h"
+#include "kernels.hpp"
+
+using namespace rad;
+
+// --------------------------------------------------------------------- ctx
+struct rad_ctx {
+  hipStream_t stream = nullptr;
+  int device = 0;
+  std::string err;
+  int key_shift = 0;
+  // timing
+  bool timing = false;
+  std::string filter;
+  struct Rec { std::string name; hipEvent_t a, b; };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  // grow-only workspaces
+  void* ws[4] = {nullptr, nullptr, nullptr, nullptr};
+  size_t ws_bytes[4] = {0, 0, 0, 0};
+  float* loss_dev = nullptr;
+};
+
+enum { WS_BITMAP = 0, WS_BITMAP2 = 1, WS_ROWLOSS = 2, WS_COLSUM = 3 };
+
+static const char* kNoCtx = "no context";
+
+static rad_status fail(rad_ctx* c, rad_status s, const std::string& msg) {
+  if (c) c->err = msg;
+  return s;
+}
+static rad_status hip_fail(rad_ctx* c, hipError_t e, const char* what) {
+  return fail(c, RAD_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(ctx, expr)                                        \
+  do {                                                            \
+    hipError_t e__ = (expr);                                      \
+    if (e__ != hipSuccess) return hip_fail(ctx, e__, #expr);      \
+  } while (0)
+#define RAD_TRY(expr)                                             \
+  do {                                                            \
+    rad_status s__ = (expr);                                      \
+    if (s__ != RAD_OK) return s__;                                \
+  } while (0)
+
+static rad_status ws_get(rad_ctx* c, int which, size_t bytes, void** out) {
+  if (bytes > c->ws_bytes[which]) {
+    if (c->ws[which]) {
+      HIP_TRY(c, hipStreamSynchronize(c->stream));
+      HIP_TRY(c, hipFree(c->ws[which]));
+      c->ws[which] = nullptr; c->ws_bytes[which] = 0;
+    }
+    HIP_TRY(c, hipMalloc(&c->ws[which], bytes));
+    c->ws_bytes[which] = bytes;
+  }
+  *out = c->ws[which];
+  return RAD_OK;
+}
+
+// runs `launch` (which enqueues exactly one logical kernel and reports its
+// label through *name), bracketed by events when timing is on
+template <class F>
+static hipError_t timed(rad_ctx* c, const char* fixed_name, F launch) {
+  if (!c->timing) { const char* nm = fixed_name; return launch(&nm); }
+  hipEvent_t a, b;
+  for (hipEvent_t* ev : {&a, &b}) {
+    if (!c->pool.empty()) { *ev = c->pool.back(); c->pool.pop_back(); }
+    else { hipError_t e = hipEventCreate(ev); if (e != hipSuccess) return e; }
+  }
+  hipError_t e = hipEventRecord(a, c->stream);
+  if (e != hipSuccess) return e;
+  const char* nm = fixed_name;
+  e = launch(&nm);
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(b, c->stream);
+  if (e != hipSuccess) return e;
+  if (c->filter.empty() || std::string(nm).find(c->filter) != std::string::npos) c->recs.push_back({nm, a, b});
+  else { c->pool.push_back(a); c->pool.push_back(b); }
+  return hipSuccess;
+}
+
+extern "C" int64_t rad_fixed_k(double p, int64_t d) {
+  int64_t k = (int64_t)std::ceil(p * (double)d - 1e-9);
+  if (k < 1) k = 1;
+  if (k > d) k = d;
+  return k;
+}
+
+extern "C" rad_status rad_ctx_create(rad_ctx** out, void* hip_stream) {
+  if (!out) return RAD_ERR_NULL;
+  *out = nullptr;
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || n < 1) return RAD_ERR_DEVICE;
+  rad_ctx* c = new rad_ctx();
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return RAD_ERR_DEVICE; }
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return RAD_ERR_DEVICE; }
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) { delete c; return RAD_ERR_UNSUPPORTED; }
+  if (hipMalloc(reinterpret_cast<void**>(&c->loss_dev), sizeof(float)) != hipSuccess) { delete c; return RAD_ERR_DEVICE; }
+  *out = c;
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_ctx_destroy(rad_ctx* c) {
+  if (!c) return RAD_ERR_NULL;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto& e : c->pool) (void)hipEventDestroy(e);
+  for (int i = 0; i < 4; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
+  if (c->loss_dev) (void)hipFree(c->loss_dev);
+  delete c;
+  return RAD_OK;
+}
+
+extern "C" const char* rad_last_error(const rad_ctx* c) { return c ? c->err.c_str() : kNoCtx; }
+
+extern "C" rad_status rad_ctx_synchronize(rad_ctx* c) {
+  if (!c) return RAD_ERR_NULL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_ctx_timing(rad_ctx* c, const char* filter) {
+  if (!c) return RAD_ERR_NULL;
+  if (filter && filter[0] == '\0') { c->timing = false; return RAD_OK; }
+  c->timing = true;
+  c->filter = filter ? filter : "";
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_ctx_timing_reset(rad_ctx* c) {
+  if (!c) return RAD_ERR_NULL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (auto& r : c->recs) { c->pool.push_back(r.a); c->pool.push_back(r.b); }
+  c->recs.clear();
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_ctx_timing_read(rad_ctx* c, const char* name, int64_t* launches, double* total_ms) {
+  if (!c || !launches || !total_ms) return RAD_ERR_NULL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  int64_t n = 0; double ms = 0.0;
+  for (auto& r : c->recs) {
+    if (name && r.name.find(name) == std::string::npos) continue;
+    float t = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&t, r.a, r.b));
+    ms += t; ++n;
+  }
+  *launches = n; *total_ms = ms;
+  return RAD_OK;
+}
+
+// test hook: keys are shifted right by `shift` bits before selection, which
+// makes equal keys frequent and so exercises the tie rule of the fixed-k draw
+extern "C" rad_status rad_debug_key_shift(rad_ctx* c, int32_t shift) {
+  if (!c) return RAD_ERR_NULL;
+  if (shift < 0 || shift > 31) return fail(c, RAD_ERR_PARAM, "key shift must be in [0, 31]");
+  c->key_shift = shift;
+  return RAD_OK;
+}
+
+// ------------------------------------------------------------------- store
+struct rad_store {
+  int scheme = 0, dtype = 0;
+  int rows = 0, cols = 0, d_out = 0, steps = 1;
+  int k = 0;
+  double p = 1.0;
+  float scale = 1.f;
+  int64_t capacity = 0;
+  void* values = nullptr;
+  uint16_t* indices = nullptr;
+  uint32_t* row_ptr = nullptr;
+  uint16_t* bucket_off = nullptr;
+  uint32_t* row_cnt = nullptr;
+  uint32_t* bits = nullptr;
+  uint32_t* bitmap = nullptr;     // transient, points into a context workspace after a plan
+  int* overflow = nullptr;
+  int bits_pitch = 0, nb = 0, bm_pitch = 0;
+  int plan_rows_per_step = 0;     // rows (per example / Bernoulli), 1 (shared), 0 (exact)
+  size_t elem() const { return dtype == kBF16 ? 2 : 4; }
+  size_t bitmap_words() const { return (size_t)steps * plan_rows_per_step * bm_pitch; }
+};
+
+static StoreView store_view(const rad_store* s, int slot) {
+  StoreView v;
+  v.values = s->values;
+  v.capacity = s->capacity;
+  v.rows = s->rows; v.cols = s->cols; v.nb = s->nb; v.bm_pitch = s->bm_pitch;
+  v.scale = s->scale;
+  v.plan_row_stride = s->scheme == kFixedKShared ? 0 : 1;
+  v.idx_shared = s->scheme == kFixedKShared ? 1 : 0;
+  v.indices = s->scheme == kFixedKShared ? s->indices + (size_t)slot * s->k : s->indices;
+  v.row_ptr = s->row_ptr ? s->row_ptr + (size_t)slot * s->rows : nullptr;
+  const size_t prow0 = (size_t)slot * s->plan_rows_per_step;
+  v.bucket_off = s->bucket_off ? s->bucket_off + prow0 * (s->nb + 1) : nullptr;
+  v.bitmap = s->bitmap ? s->bitmap + prow0 * s->bm_pitch : nullptr;
+  return v;
+}
+
+static rad_status check_layer(rad_ctx* c, const rad_layer* L) {
+  if (!L) return fail(c, RAD_ERR_NULL, "layer is null");
+  if (L->dtype != RAD_F32 && L->dtype != RAD_BF16) return fail(c, RAD_ERR_PARAM, "unknown dtype");
+  if (L->kind != RAD_LINEAR && L->kind != RAD_CONV2D) return fail(c, RAD_ERR_PARAM, "unknown layer kind");
+  if (L->batch < 1 || L->d_in < 1 || L->d_out < 1) return fail(c, RAD_ERR_SHAPE, "batch, d_in and d_out must be positive");
+  if (L->batch > (1 << 24) || L->d_in > (1 << 24) || L->d_out > (1 << 24))
+    return fail(c, RAD_ERR_SHAPE, "dimension above 2^24");
+  if (L->kind == RAD_CONV2D) {
+    if (L->c_in < 1 || L->c_out < 1 || L->h < 1 || L->w < 1 || L->kh < 1 || L->kw < 1)
+      return fail(c, RAD_ERR_SHAPE, "conv dimensions must be positive");
+    if (2 * L->pad != L->kh - 1 || 2 * L->pad != L->kw - 1) return fail(c, RAD_ERR_SHAPE, "conv must keep the spatial size");
+    if ((int64_t)L->c_in * L->h * L->w != L->d_in || (int64_t)L->c_out * L->h * L->w != L->d_out)
+      return fail(c, RAD_ERR_SHAPE, "d_in/d_out do not match the conv shape");
+    if (L->dtype != RAD_F32) return fail(c, RAD_ERR_UNSUPPORTED, "conv layers are fp32 only");
+  }
+  return RAD_OK;
+}
+
+static rad_status check_scheme(rad_ctx* c, int scheme, double p) {
+  if (scheme < RAD_EXACT || scheme > RAD_FIXEDK_PER_EXAMPLE) return fail(c, RAD_ERR_PARAM, "unknown sampling scheme");
+  if (!(p > 0.0) || p > 1.0) return fail(c, RAD_ERR_PARAM, "p must be in (0, 1]");
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_store_destroy(rad_store* s) {
+  if (!s) return RAD_ERR_NULL;
+  for (void* p : {(void*)s->values, (void*)s->indices, (void*)s->row_ptr, (void*)s->bucket_off, (void*)s->row_cnt,
+                  (void*)s->bits, (void*)s->overflow})
+    if (p) (void)hipFree(p);
+  delete s;
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t scheme, double p, int32_t steps,
+                                       rad_store** out) {
+  if (!c) return RAD_ERR_NULL;
+  if (!out) return fail(c, RAD_ERR_NULL, "out is null");
+  *out = nullptr;
+  RAD_TRY(check_layer(c, L));
+  RAD_TRY(check_scheme(c, scheme, p));
+  if (steps < 1) return fail(c, RAD_ERR_SHAPE, "steps must be >= 1");
+  if (scheme != RAD_EXACT) {
+    if (L->d_in > 65535) return fail(c, RAD_ERR_UNSUPPORTED, "sampled stores need d_in <= 65535 (16-bit indices)");
+    if (L->d_in > plan_max_cols(scheme)) return fail(c, RAD_ERR_UNSUPPORTED, "fixed-k sampling needs d_in <= 16376");
+  }
+  const double total_rows = (double)steps * (double)L->batch;
+  if (total_rows * (double)L->d_in >= 4294967296.0) return fail(c, RAD_ERR_SHAPE, "store above 2^32 entries");
+  rad_store* s = new rad_store();
+  s->scheme = scheme; s->dtype = L->dtype; s->rows = (int)L->batch; s->cols = (int)L->d_in;
+  s->d_out = (int)L->d_out; s->steps = steps; s->p = p;
+  s->k = (int)rad_fixed_k(p, L->d_in);
+  s->nb = (s->cols + kBucket - 1) / kBucket;
+  s->bm_pitch = (s->cols + 31) / 32;
+  const int64_t R = (int64_t)steps * s->rows;
+  const int64_t n = R * s->cols;
+  if (scheme == RAD_EXACT) { s->scale = 1.f; s->capacity = n; s->plan_rows_per_step = 0; }
+  else if (scheme == RAD_BERNOULLI) {
+    s->scale = (float)(1.0 / p);
+    double cap = std::ceil((double)n * p + 8.0 * std::sqrt((double)n * p * (1.0 - p))) + 64.0;
+    s->capacity = cap > (double)n ? n : (int64_t)cap;
+    s->plan_rows_per_step = s->rows;
+  } else {
+    s->scale = (float)((double)s->cols / (double)s->k);
+    s->capacity = R * s->k;
+    s->plan_rows_per_step = scheme == RAD_FIXEDK_SHARED ? 1 : s->rows;
+  }
+  auto alloc = [&](void** ptr, size_t bytes) -> bool {
+    return hipMalloc(ptr, bytes ? bytes : 16) == hipSuccess;
+  };
+  bool ok = alloc(&s->values, (size_t)s->capacity * s->elem());
+  ok = ok && alloc((void**)&s->overflow, sizeof(int));
+  if (scheme != RAD_EXACT) {
+    const size_t n_idx = scheme == RAD_FIXEDK_SHARED ? (size_t)steps * s->k : (size_t)s->capacity;
+    ok = ok && alloc((void**)&s->indices, n_idx * 2);
+    ok = ok && alloc((void**)&s->row_ptr, (size_t)(R + 1) * 4);
+    ok = ok && alloc((void**)&s->bucket_off, (size_t)steps * s->plan_rows_per_step * (s->nb + 1) * 2);
+    if (scheme == RAD_BERNOULLI) ok = ok && alloc((void**)&s->row_cnt, (size_t)R * 4);
+  }
+  if (L->relu) {
+    s->bits_pitch = (s->d_out + 31) / 32;
+    ok = ok && alloc((void**)&s->bits, (size_t)R * s->bits_pitch * 4);
+  }
+  if (ok) ok = hipMemsetAsync(s->overflow, 0, sizeof(int), c->stream) == hipSuccess;
+  if (!ok) { rad_store_destroy(s); return fail(c, RAD_ERR_DEVICE, "store allocation failed"); }
+  *out = s;
+  return RAD_OK;
+}
+
+static rad_status store_nnz(rad_ctx* c, const rad_store* s, int64_t* nnz) {
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (s->scheme == RAD_EXACT) { *nnz = s->capacity; return RAD_OK; }
+  uint32_t last = 0;
+  HIP_TRY(c, hipMemcpy(&last, s->row_ptr + (size_t)s->steps * s->rows, 4, hipMemcpyDeviceToHost));
+  int ov = 0;
+  HIP_TRY(c, hipMemcpy(&ov, s->overflow, sizeof(int), hipMemcpyDeviceToHost));
+  if (ov || (int64_t)last > s->capacity) return fail(c, RAD_ERR_CAPACITY, "a Bernoulli draw exceeded the store's capacity");
+  *nnz = last;
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_store_get_stats(rad_ctx* c, const rad_store* s, rad_store_stats* out) {
+  if (!c) return RAD_ERR_NULL;
+  if (!s || !out) return fail(c, RAD_ERR_NULL, "store or out is null");
+  int64_t nnz = 0;
+  RAD_TRY(store_nnz(c, s, &nnz));
+  const int64_t R = (int64_t)s->steps * s->rows;
+  out->nnz = (uint64_t)nnz;
+  out->value_bytes = (uint64_t)nnz * s->elem();
+  out->dense_bytes = (uint64_t)R * s->cols * s->elem();
+  out->bit_bytes = s->bits ? (uint64_t)R * s->bits_pitch * 4 : 0;
+  if (s->scheme == RAD_EXACT) out->index_bytes = 0;
+  else if (s->scheme == RAD_FIXEDK_SHARED)
+    out->index_bytes = (uint64_t)s->steps * ((uint64_t)s->k * 2 + (uint64_t)(s->nb + 1) * 2);
+  else
+    out->index_bytes = (uint64_t)nnz * 2 + (uint64_t)R * (s->nb + 1) * 2 +
+                       (s->scheme == RAD_BERNOULLI ? (uint64_t)(R + 1) * 4 : 0);
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64_t* row_ptr, int32_t* col, float* val,
+                                           int64_t capacity) {
+  if (!c) return RAD_ERR_NULL;
+  if (!s || !row_ptr || !col || !val) return fail(c, RAD_ERR_NULL, "null argument");
+  int64_t nnz = 0;
+  RAD_TRY(store_nnz(c, s, &nnz));
+  if (nnz > capacity) return fail(c, RAD_ERR_CAPACITY, "export buffers too small");
+  const int64_t R = (int64_t)s->steps * s->rows;
+  std::vector<unsigned char> vraw((size_t)nnz * s->elem());
+  if (nnz) HIP_TRY(c, hipMemcpy(vraw.data(), s->values, vraw.size(), hipMemcpyDeviceToHost));
+  for (int64_t i = 0; i < nnz; ++i) {
+    if (s->dtype == kBF16) {
+      uint32_t u = (uint32_t)reinterpret_cast<uint16_t*>(vraw.data())[i] << 16;
+      std::memcpy(&val[i], &u, 4);
+    } else val[i] = reinterpret_cast<float*>(vraw.data())[i];
+  }
+  if (s->scheme == RAD_EXACT) {
+    for (int64_t r = 0; r <= R; ++r) row_ptr[r] = r * s->cols;
+    for (int64_t i = 0; i < nnz; ++i) col[i] = (int32_t)(i % s->cols);
+    return RAD_OK;
+  }
+  std::vector<uint32_t> rp((size_t)R + 1);
+  HIP_TRY(c, hipMemcpy(rp.data(), s->row_ptr, rp.size() * 4, hipMemcpyDeviceToHost));
+  for (int64_t r = 0; r <= R; ++r) row_ptr[r] = rp[(size_t)r];
+  if (s->scheme == RAD_FIXEDK_SHARED) {
+    std::vector<uint16_t> idx((size_t)s->steps * s->k);
+    HIP_TRY(c, hipMemcpy(idx.data(), s->indices, idx.size() * 2, hipMemcpyDeviceToHost));
+    for (int64_t r = 0; r < R; ++r)
+      for (int j = 0; j < s->k; ++j) col[r * s->k + j] = idx[(size_t)(r / s->rows) * s->k + j];
+  } else {
+    std::vector<uint16_t> idx((size_t)nnz);
+    if (nnz) HIP_TRY(c, hipMemcpy(idx.data(), s->indices, idx.size() * 2, hipMemcpyDeviceToHost));
+    for (int64_t i = 0; i < nnz; ++i) col[i] = idx[(size_t)i];
+  }
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_store_export_bits(rad_ctx* c, const rad_store* s, uint32_t* words) {
+  if (!c) return RAD_ERR_NULL;
+  if (!s || !words) return fail(c, RAD_ERR_NULL, "null argument");
+  if (!s->bits) return fail(c, RAD_ERR_PARAM, "store has no ReLU bits");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(words, s->bits, (size_t)s->steps * s->rows * s->bits_pitch * 4, hipMemcpyDeviceToHost));
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_store_import_bits(rad_ctx* c, rad_store* s, const uint32_t* words) {
+  if (!c) return RAD_ERR_NULL;
+  if (!s || !words) return fail(c, RAD_ERR_NULL, "null argument");
+  if (!s->bits) return fail(c, RAD_ERR_PARAM, "store has no ReLU bits");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(s->bits, words, (size_t)s->steps * s->rows * s->bits_pitch * 4, hipMemcpyHostToDevice));
+  return RAD_OK;
+}
+
+// draws the keep sets of every row and step of `s` into `bitmap`
+static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, uint32_t* bitmap) {
+  if (s->scheme == RAD_EXACT) return RAD_OK;
+  PlanArgs a;
+  a.seed_lo = (uint32_t)sm->seed; a.seed_hi = (uint32_t)(sm->seed >> 32);
+  a.stream_id = sm->stream_id; a.step0 = sm->step;
+  a.scheme = s->scheme;
+  a.plan_rows = s->steps * s->plan_rows_per_step;
+  a.rows_per_step = s->rows;
+  a.cols = s->cols; a.k = s->k;
+  a.thresh = (uint64_t)std::llround(s->p * 4294967296.0) >> c->key_shift;
+  a.key_shift = c->key_shift;
+  a.bitmap = bitmap; a.bm_pitch = s->bm_pitch;
+  a.bucket_off = s->bucket_off; a.nb = s->nb;
+  a.row_cnt = s->row_cnt; a.row_ptr = s->row_ptr;
+  s->bitmap = bitmap;
+  HIP_TRY(c, timed(c, "plan", [&](const char**) { return launch_plan(a, c->stream); }));
+  if (s->scheme == RAD_BERNOULLI) {
+    HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(s->overflow), 0u, 1, c->stream));
+    HIP_TRY(c, timed(c, "row_scan", [&](const char**) {
+      return launch_row_scan(s->row_cnt, s->row_ptr, s->steps * s->rows, s->capacity, s->overflow, c->stream);
+    }));
+  }
+  return RAD_OK;
+}
+
+static rad_status check_sampling(rad_ctx* c, const rad_sampling* sm, const rad_store* s) {
+  if (!sm) return fail(c, RAD_ERR_NULL, "sampling is null");
+  RAD_TRY(check_scheme(c, sm->scheme, sm->p));
+  if (sm->scheme != s->scheme || sm->p != s->p) return fail(c, RAD_ERR_PARAM, "sampling does not match the store");
+  return RAD_OK;
+}
+
+static rad_status store_pack(rad_ctx* c, rad_store* s, const void* x, int slot) {
+  if (s->scheme == RAD_EXACT) {
+    const size_t bytes = (size_t)s->rows * s->cols * s->elem();
+    HIP_TRY(c, hipMemcpyAsync(static_cast<char*>(s->values) + (size_t)slot * bytes, x, bytes, hipMemcpyDeviceToDevice,
+                              c->stream));
+    return RAD_OK;
+  }
+  const StoreView v = store_view(s, slot);
+  HIP_TRY(c, timed(c, s->dtype == kBF16 ? "pack_bf16" : "pack_f32",
+                   [&](const char**) { return launch_pack(x, s->dtype, v, c->stream); }));
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_sample_pack(rad_ctx* c, const rad_sampling* sm, const void* x, rad_store* s,
+                                      int32_t step_slot) {
+  if (!c) return RAD_ERR_NULL;
+  if (!s || !x) return fail(c, RAD_ERR_NULL, "null argument");
+  RAD_TRY(check_sampling(c, sm, s));
+  if (step_slot < 0 || step_slot >= s->steps) return fail(c, RAD_ERR_SHAPE, "step_slot out of range");
+  if (s->steps != 1) return fail(c, RAD_ERR_UNSUPPORTED, "rad_sample_pack draws single-step stores only");
+  void* bm = nullptr;
+  if (s->scheme != RAD_EXACT) RAD_TRY(ws_get(c, WS_BITMAP, s->bitmap_words() * 4, &bm));
+  RAD_TRY(store_plan(c, s, sm, static_cast<uint32_t*>(bm)));
+  return store_pack(c, s, x, step_slot);
+}
+
+// ------------------------------------------------------------ layer calls
+static bool layer_matches(const rad_layer* L, const rad_store* s) {
+  return L->batch == s->rows && L->d_in == s->cols && L->d_out == s->d_out && L->dtype == s->dtype &&
+         (L->relu != 0) == (s->bits != nullptr);
+}
+
+static GemmArgs gemm_zero() { GemmArgs g; std::memset(&g, 0, sizeof(g)); return g; }
+
+static rad_status run_gemm_call(rad_ctx* c, int dtype, int ak, int bk, int epi, const GemmArgs& g) {
+  hipError_t e = timed(c, "gemm", [&](const char** nm) { return launch_gemm(dtype, ak, bk, epi, g, c->stream, nm); });
+  if (e == hipErrorInvalidValue) return fail(c, RAD_ERR_UNSUPPORTED, "no GEMM kernel for this operand combination");
+  if (e != hipSuccess) return hip_fail(c, e, "gemm launch");
+  return RAD_OK;
+}
+
+// y = act(x W + bias [+ u V]); writes ReLU bits and, if `next`, the packed sample of y
+static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const void* x, int64_t ldx, const void* W,
+                               const float* bias, int relu, void* y, uint32_t* bits, int bits_pitch,
+                               const StoreView* next, const float* u, int64_t u_ld, int u_n, const float* V) {
+  GemmArgs g = gemm_zero();
+  g.M = M; g.N = N; g.K = K;
+  g.A = x; g.lda = ldx; g.B = W; g.ldb = N;
+  g.bias = bias; g.relu = relu; g.y = y; g.ldy = N; g.bits = relu ? bits : nullptr; g.bits_pitch = bits_pitch;
+  if (next) { g.pack = 1; g.next = *next; }
+  g.u = u; g.u_ld = u_ld; g.u_n = u_n; g.V = V;
+  return run_gemm_call(c, dtype, kOpK, kOpMN, kEpiFwd, g);
+}
+
+static int sparse_prefetch_for(const rad_store* s, int lanes_per_row) {
+  const double pi = s->scheme == RAD_BERNOULLI ? s->p : (double)s->k / (double)s->cols;
+  const double mean = pi * (s->cols < kBucket ? s->cols : kBucket);
+  return (int)std::ceil((mean + 3.0 * std::sqrt(mean)) / lanes_per_row);
+}
+
+// dW = beta dW + store(slot)^T (dy masked by bits)
+static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* dy, int N, const uint32_t* bits,
+                          int bits_pitch, float* dW, int beta) {
+  GemmArgs g = gemm_zero();
+  g.N = N; g.K = s->rows;
+  g.B = dy; g.ldb = N; g.b_mask = bits; g.b_mask_pitch = bits_pitch;
+  g.C = dW; g.ldc = N; g.beta = beta; g.c_dtype = kF32;
+  if (s->scheme == RAD_EXACT) {
+    g.M = s->cols;
+    g.A = static_cast<const char*>(s->values) + (size_t)slot * s->rows * s->cols * s->elem(); g.lda = s->cols;
+    return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
+  }
+  if (s->scheme == RAD_FIXEDK_SHARED) {
+    // compact problem: only the k sampled rows of dW are touched, the rest is zero
+    if (!beta)
+      HIP_TRY(c, timed(c, "fill", [&](const char**) {
+        return launch_fill_u32(reinterpret_cast<uint32_t*>(dW), 0u, (int64_t)s->cols * N, c->stream);
+      }));
+    g.M = s->k;
+    g.A = static_cast<const char*>(s->values) + (size_t)slot * s->rows * s->k * s->elem(); g.lda = s->k;
+    g.row_map = s->indices + (size_t)slot * s->k;
+    g.beta = 1;
+    return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
+  }
+  g.M = s->cols;
+  g.sa = store_view(s, slot);
+  g.sparse_prefetch = sparse_prefetch_for(s, s->dtype == kBF16 ? 4 : 16);
+  return run_gemm_call(c, s->dtype, kOpSparse, kOpMN, kEpiStore, g);
+}
+
+// dX = (dy masked by bits) W^T
+static rad_status dX_gemm(rad_ctx* c, int dtype, int M, int d_in, int d_out, const void* dy, const uint32_t* bits,
+                          int bits_pitch, const void* W, void* dX) {
+  GemmArgs g = gemm_zero();
+  g.M = M; g.N = d_in; g.K = d_out;
+  g.A = dy; g.lda = d_out; g.a_mask = bits; g.a_mask_pitch = bits_pitch;
+  g.B = W; g.ldb = d_out;
+  g.C = dX; g.ldc = d_in; g.beta = 0; g.c_dtype = dtype;
+  return run_gemm_call(c, dtype, kOpK, kOpK, kEpiStore, g);
+}
+
+static rad_status colsum_call(rad_ctx* c, const void* dy, int dtype, int rows, int N, const uint32_t* bits,
+                              int bits_pitch, const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
+                              int beta) {
+  int splits = rows / 64;
+  if (splits < 1) splits = 1;
+  if (splits > 32) splits = 32;
+  void* part = nullptr;
+  RAD_TRY(ws_get(c, WS_COLSUM, (size_t)splits * (u_n + 1) * N * 4, &part));
+  HIP_TRY(c, timed(c, "colsum", [&](const char**) {
+    return launch_colsum(dy, dtype, rows, N, bits, bits_pitch, u, u_ld, u_n, out_bias, out_u, beta,
+                         static_cast<float*>(part), splits, c->stream);
+  }));
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_forward_sample(rad_ctx* c, const rad_layer* L, const rad_sampling* sm, const void* x,
+                                         const void* W, const void* bias, void* y, rad_store* s) {
+  if (!c) return RAD_ERR_NULL;
+  RAD_TRY(check_layer(c, L));
+  if (!x || !W || !y || !s) return fail(c, RAD_ERR_NULL, "null argument");
+  if ((L->has_bias != 0) != (bias != nullptr)) return fail(c, RAD_ERR_NULL, "bias pointer does not match has_bias");
+  if (!layer_matches(L, s)) return fail(c, RAD_ERR_SHAPE, "store was created for a different layer");
+  if (L->kind != RAD_LINEAR) return fail(c, RAD_ERR_UNSUPPORTED, "stand-alone conv layers are not built yet");
+  RAD_TRY(rad_sample_pack(c, sm, x, s, 0));
+  return forward_gemm(c, L->dtype, (int)L->batch, (int)L->d_out, (int)L->d_in, x, L->d_in, W,
+                      static_cast<const float*>(bias), L->relu, y, s->bits, s->bits_pitch, nullptr, nullptr, 0, 0,
+                      nullptr);
+}
+
+extern "C" rad_status rad_backward_dW(rad_ctx* c, const rad_layer* L, const rad_store* s, const void* dy, float* dW,
+                                      float* dbias, float beta) {
+  if (!c) return RAD_ERR_NULL;
+  RAD_TRY(check_layer(c, L));
+  if (!s || !dy || !dW) return fail(c, RAD_ERR_NULL, "null argument");
+  if (!layer_matches(L, s)) return fail(c, RAD_ERR_SHAPE, "store was created for a different layer");
+  if (beta != 0.f && beta != 1.f) return fail(c, RAD_ERR_PARAM, "beta must be 0 or 1");
+  if (L->kind != RAD_LINEAR) return fail(c, RAD_ERR_UNSUPPORTED, "stand-alone conv layers are not built yet");
+  if (s->steps != 1) return fail(c, RAD_ERR_UNSUPPORTED, "multi-step stores belong to rad_train_step");
+  RAD_TRY(dW_gemm(c, s, 0, dy, (int)L->d_out, s->bits, s->bits_pitch, dW, beta != 0.f));
+  if (dbias)
+    RAD_TRY(colsum_call(c, dy, L->dtype, (int)L->batch, (int)L->d_out, s->bits, s->bits_pitch, nullptr, 0, 0, dbias,
+                        nullptr, beta != 0.f));
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_backward_dX(rad_ctx* c, const rad_layer* L, const rad_store* s, const void* dy,
+                                      const void* W, void* dX) {
+  if (!c) return RAD_ERR_NULL;
+  RAD_TRY(check_layer(c, L));
+  if (!s || !dy || !W || !dX) return fail(c, RAD_ERR_NULL, "null argument");
+  if (!layer_matches(L, s)) return fail(c, RAD_ERR_SHAPE, "store was created for a different layer");
+  if (L->kind != RAD_LINEAR) return fail(c, RAD_ERR_UNSUPPORTED, "stand-alone conv layers are not built yet");
+  return dX_gemm(c, L->dtype, (int)L->batch, (int)L->d_in, (int)L->d_out, dy, s->bits, s->bits_pitch, W, dX);
+}
+
+static rad_status softmax_call(rad_ctx* c, const void* logits, const int32_t* labels, int rows, int classes, int dtype,
+                               void* dlogits, float* loss_dev) {
+  void* rl = nullptr;
+  RAD_TRY(ws_get(c, WS_ROWLOSS, (size_t)rows * 4, &rl));
+  HIP_TRY(c, timed(c, "softmax_ce", [&](const char**) {
+    return launch_softmax_ce(logits, labels, rows, classes, dtype, dlogits, static_cast<float*>(rl), loss_dev,
+                             c->stream);
+  }));
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_softmax_ce(rad_ctx* c, const void* logits, const int32_t* labels, int64_t rows,
+                                     int64_t classes, int32_t dtype, void* dlogits, float* loss_dev) {
+  if (!c) return RAD_ERR_NULL;
+  if (!logits || !labels || !dlogits || !loss_dev) return fail(c, RAD_ERR_NULL, "null argument");
+  if (rows < 1 || classes < 1 || rows > (1 << 24) || classes > (1 << 24)) return fail(c, RAD_ERR_SHAPE, "bad shape");
+  if (dtype != RAD_F32 && dtype != RAD_BF16) return fail(c, RAD_ERR_PARAM, "unknown dtype");
+  return softmax_call(c, logits, labels, (int)rows, (int)classes, dtype, dlogits, loss_dev);
+}
+
+// ------------------------------------------------------------------ models
+enum ModelKind { kMlp = 0, kRnn = 1, kCnn = 2 };
+
+struct rad_model {
+  int kind = kMlp;
+  int dtype = 0, scheme = 0, has_bias = 0;
+  double p = 1.0;
+  int64_t batch = 0;
+  std::vector<int64_t> dims;            // MLP widths
+  std::vector<rad_store*> stores;
+  void* act[2] = {nullptr, nullptr};    // transient dense activations (ping-pong)
+  void* dyb[2] = {nullptr, nullptr};    // transient upstream gradients (ping-pong)
+  void* logits = nullptr;
+  // RNN
+  int64_t T = 0, d_input = 0, hidden = 0, classes = 0;
+  uint32_t* rnn_bits = nullptr;         // [T][batch][hidden/32]
+  uint32_t* bitmap_ws = nullptr;        // keep bitmaps of every step (transient within a step)
+  size_t elem() const { return dtype == kBF16 ? 2 : 4; }
+};
+
+extern "C" rad_status rad_model_destroy(rad_model* m) {
+  if (!m) return RAD_ERR_NULL;
+  for (rad_store* s : m->stores) if (s) rad_store_destroy(s);
+  for (void* p : {m->act[0], m->act[1], m->dyb[0], m->dyb[1], m->logits, (void*)m->rnn_bits, (void*)m->bitmap_ws})
+    if (p) (void)hipFree(p);
+  delete m;
+  return RAD_OK;
+}
+
+extern "C" int32_t rad_model_num_stores(const rad_model* m) { return m ? (int32_t)m->stores.size() : 0; }
+extern "C" rad_store* rad_model_store(rad_model* m, int32_t l) {
+  return (m && l >= 0 && l < (int32_t)m->stores.size()) ? m->stores[(size_t)l] : nullptr;
+}
+extern "C" const void* rad_model_logits(const rad_model* m) { return m ? m->logits : nullptr; }
+
+extern "C" rad_status rad_model_create_mlp(rad_ctx* c, int32_t dtype, int64_t batch, int32_t n_layers,
+                                           const int64_t* dims, int32_t has_bias, int32_t scheme, double p,
+                                           rad_model** out) {
+  if (!c) return RAD_ERR_NULL;
+  if (!out || !dims) return fail(c, RAD_ERR_NULL, "null argument");
+  *out = nullptr;
+  if (n_layers < 1 || n_layers > 64) return fail(c, RAD_ERR_SHAPE, "n_layers must be in [1, 64]");
+  RAD_TRY(check_scheme(c, scheme, p));
+  rad_model* m = new rad_model();
+  m->kind = kMlp; m->dtype = dtype; m->scheme = scheme; m->p = p; m->batch = batch; m->has_bias = has_bias;
+  m->dims.assign(dims, dims + n_layers + 1);
+  int64_t widest = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    rad_layer L; std::memset(&L, 0, sizeof(L));
+    L.kind = RAD_LINEAR; L.dtype = dtype; L.batch = batch; L.d_in = dims[l]; L.d_out = dims[l + 1];
+    L.relu = l < n_layers - 1; L.has_bias = has_bias;
+    rad_store* s = nullptr;
+    rad_status st = rad_store_create(c, &L, scheme, p, 1, &s);
+    if (st != RAD_OK) { rad_model_destroy(m); return st; }
+    m->stores.push_back(s);
+    if (dims[l + 1] > widest) widest = dims[l + 1];
+  }
+  const size_t bytes = (size_t)batch * widest * m->elem();
+  bool ok = true;
+  for (void** p2 : {&m->act[0], &m->act[1], &m->dyb[0], &m->dyb[1]}) ok = ok && hipMalloc(p2, bytes) == hipSuccess;
+  ok = ok && hipMalloc(&m->logits, (size_t)batch * dims[n_layers] * m->elem()) == hipSuccess;
+  if (!ok) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+  *out = m;
+  return RAD_OK;
+}
+
+static rad_status stores_overflowed(rad_ctx* c, rad_model* m) {
+  for (rad_store* s : m->stores) {
+    if (s->scheme != RAD_BERNOULLI) continue;
+    int ov = 0;
+    HIP_TRY(c, hipMemcpy(&ov, s->overflow, sizeof(int), hipMemcpyDeviceToHost));
+    if (ov) return fail(c, RAD_ERR_CAPACITY, "a Bernoulli draw exceeded a store's capacity");
+  }
+  return RAD_OK;
+}
+
+static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, const void* x, const int32_t* labels,
+                           void* const* params, void* const* grads, float* loss_host) {
+  const int Lc = (int)m->stores.size();
+  const int B = (int)m->batch;
+  const int per = m->has_bias ? 2 : 1;
+  for (int i = 0; i < Lc * per; ++i)
+    if (!params[i] || !grads[i]) return fail(c, RAD_ERR_NULL, "null parameter or gradient pointer");
+  auto Wp = [&](int l) { return params[l * per]; };
+  auto bp = [&](int l) { return m->has_bias ? static_cast<const float*>(params[l * per + 1]) : nullptr; };
+  size_t bm_words = 0;
+  for (rad_store* s : m->stores) if (s->bitmap_words() > bm_words) bm_words = s->bitmap_words();
+  void* bm = nullptr;
+  if (bm_words) RAD_TRY(ws_get(c, WS_BITMAP, bm_words * 4, &bm));
+
+  // forward: layer l consumes the dense activation of layer l-1 (kept only
+  // until then) and leaves the packed sample of its own output for layer l+1
+  rad_sampling s0 = *sm;
+  RAD_TRY(store_plan(c, m->stores[0], &s0, static_cast<uint32_t*>(bm)));
+  RAD_TRY(store_pack(c, m->stores[0], x, 0));
+  const void* a_in = x;
+  for (int l = 0; l < Lc; ++l) {
+    const bool last = l == Lc - 1;
+    StoreView nv; const StoreView* next = nullptr;
+    if (!last) {
+      rad_store* sn = m->stores[(size_t)l + 1];
+      if (sn->scheme != RAD_EXACT) {
+        rad_sampling sl = *sm; sl.stream_id = sm->stream_id + (uint32_t)(l + 1);
+        RAD_TRY(store_plan(c, sn, &sl, static_cast<uint32_t*>(bm)));
+        nv = store_view(sn, 0); next = &nv;
+      }
+    }
+    void* y = last ? m->logits : (m->stores[(size_t)l + 1]->scheme == RAD_EXACT ? m->stores[(size_t)l + 1]->values
+                                                                                 : m->act[l & 1]);
+    rad_store* s = m->stores[(size_t)l];
+    RAD_TRY(forward_gemm(c, m->dtype, B, (int)m->dims[(size_t)l + 1], (int)m->dims[(size_t)l], a_in, m->dims[(size_t)l],
+                         Wp(l), bp(l), !last, y, s->bits, s->bits_pitch, next, nullptr, 0, 0, nullptr));
+    a_in = y;
+  }
+  RAD_TRY(softmax_call(c, m->logits, labels, B, (int)m->dims[(size_t)Lc], m->dtype, m->dyb[0], c->loss_dev));
+
+  // backward from the stores
+  int cur = 0;
+  for (int l = Lc - 1; l >= 0; --l) {
+    rad_store* s = m->stores[(size_t)l];
+    const int N = (int)m->dims[(size_t)l + 1], D = (int)m->dims[(size_t)l];
+    RAD_TRY(dW_gemm(c, s, 0, m->dyb[cur], N, s->bits, s->bits_pitch, static_cast<float*>(grads[l * per]), 0));
+    if (m->has_bias)
+      RAD_TRY(colsum_call(c, m->dyb[cur], m->dtype, B, N, s->bits, s->bits_pitch, nullptr, 0, 0,
+                          static_cast<float*>(grads[l * per + 1]), nullptr, 0));
+    if (l > 0) {
+      RAD_TRY(dX_gemm(c, m->dtype, B, D, N, m->dyb[cur], s->bits, s->bits_pitch, Wp(l), m->dyb[cur ^ 1]));
+      cur ^= 1;
+    }
+  }
+  HIP_TRY(c, hipMemcpyAsync(loss_host, c->loss_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return stores_overflowed(c, m);
+}
+
+extern "C" rad_status rad_model_create_rnn(rad_ctx* c, int64_t batch, int64_t T, int64_t d_input, int64_t hidden,
+                                           int64_t classes, int32_t scheme, double p, rad_model** out) {
+  if (!c) return RAD_ERR_NULL;
+  if (!out) return fail(c, RAD_ERR_NULL, "out is null");
+  *out = nullptr;
+  RAD_TRY(check_scheme(c, scheme, p));
+  if (batch < 1 || T < 1 || d_input < 1 || hidden < 1 || classes < 1) return fail(c, RAD_ERR_SHAPE, "bad RNN shape");
+  if (d_input > 8) return fail(c, RAD_ERR_UNSUPPORTED, "RNN input width above 8");
+  if (T > (1 << 20)) return fail(c, RAD_ERR_SHAPE, "T above 2^20");
+  rad_model* m = new rad_model();
+  m->kind = kRnn; m->dtype = kF32; m->scheme = scheme; m->p = p; m->batch = batch;
+  m->T = T; m->d_input = d_input; m->hidden = hidden; m->classes = classes;
+  rad_layer L; std::memset(&L, 0, sizeof(L));
+  L.kind = RAD_LINEAR; L.dtype = RAD_F32; L.batch = batch; L.d_in = hidden; L.d_out = hidden; L.relu = 0;
+  rad_store* s = nullptr;
+  rad_status st = rad_store_create(c, &L, scheme, p, (int32_t)(T > 1 ? T - 1 : 1), &s);
+  if (st != RAD_OK) { rad_model_destroy(m); return st; }
+  m->stores.push_back(s);
+  L.d_out = classes;
+  st = rad_store_create(c, &L, scheme, p, 1, &s);
+  if (st != RAD_OK) { rad_model_destroy(m); return st; }
+  m->stores.push_back(s);
+  const size_t hb = (size_t)batch * hidden * 4;
+  bool ok = true;
+  for (void** p2 : {&m->act[0], &m->act[1], &m->dyb[0], &m->dyb[1]}) ok = ok && hipMalloc(p2, hb) == hipSuccess;
+  ok = ok && hipMalloc(&m->logits, (size_t)batch * classes * 4) == hipSuccess;
+  ok = ok && hipMalloc((void**)&m->rnn_bits, (size_t)T * batch * ((hidden + 31) / 32) * 4) == hipSuccess;
+  const size_t bmw = m->stores[0]->bitmap_words() + m->stores[1]->bitmap_words();
+  if (bmw) ok = ok && hipMalloc((void**)&m->bitmap_ws, bmw * 4) == hipSuccess;
+  if (!ok) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+  *out = m;
+  return RAD_OK;
+}
+
+// BPTT over the unrolled ReLU RNN of Appendix A.  params/grads order:
+// W_ih, W_hh, b, W_ho, b_o.
+static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, const void* x, const int32_t* labels,
+                           void* const* params, void* const* grads, float* loss_host) {
+  for (int i = 0; i < 5; ++i)
+    if (!params[i] || !grads[i]) return fail(c, RAD_ERR_NULL, "null parameter or gradient pointer");
+  const int B = (int)m->batch, H = (int)m->hidden, T = (int)m->T, I = (int)m->d_input, C = (int)m->classes;
+  const float* W_ih = static_cast<const float*>(params[0]);
+  const float* W_hh = static_cast<const float*>(params[1]);
+  const float* b = static_cast<const float*>(params[2]);
+  const float* W_ho = static_cast<const float*>(params[3]);
+  const float* b_o = static_cast<const float*>(params[4]);
+  float* dW_ih = static_cast<float*>(grads[0]);
+  float* dW_hh = static_cast<float*>(grads[1]);
+  float* db = static_cast<float*>(grads[2]);
+  float* dW_ho = static_cast<float*>(grads[3]);
+  float* db_o = static_cast<float*>(grads[4]);
+  const float* xs = static_cast<const float*>(x);
+  rad_store* s_hh = m->stores[0];
+  rad_store* s_ho = m->stores[1];
+  const int bp = (H + 31) / 32;
+
+  // all keep sets of the step up front: they depend on (seed, step) only
+  if (T > 1) {
+    rad_sampling s1 = *sm; s1.step = sm->step + 2;      // slot s holds h_{s+1}, drawn with step = s+2
+    RAD_TRY(store_plan(c, s_hh, &s1, m->bitmap_ws));
+  }
+  rad_sampling s2 = *sm; s2.stream_id = sm->stream_id + 1; s2.step = 0;
+  RAD_TRY(store_plan(c, s_ho, &s2, m->bitmap_ws ? m->bitmap_ws + s_hh->bitmap_words() : nullptr));
+
+  // forward: h_t = ReLU(x_t W_ih + h_{t-1} W_hh + b); h_0 = 0 so step 1 has no contraction
+  for (int t = 1; t <= T; ++t) {
+    StoreView nv; const StoreView* next = nullptr;
+    rad_store* target = t < T ? s_hh : s_ho;
+    void* y = m->act[t & 1];
+    if (target->scheme == RAD_EXACT) {
+      y = static_cast<char*>(target->values) + (t < T ? (size_t)(t - 1) * B * H * 4 : 0);
+    } else { nv = store_view(target, t < T ? t - 1 : 0); next = &nv; }
+    const void* hin = t == 1 ? m->act[0] : (s_hh->scheme == RAD_EXACT
+                          ? static_cast<const void*>(static_cast<char*>(s_hh->values) + (size_t)(t - 2) * B * H * 4)
+                          : m->act[(t - 1) & 1]);
+    RAD_TRY(forward_gemm(c, kF32, B, H, t == 1 ? 0 : H, hin, H, W_hh, b, 1, y, m->rnn_bits + (size_t)(t - 1) * B * bp,
+                         bp, next, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, W_ih));
+    if (t == T && target->scheme == RAD_EXACT) { /* h_T already sits in the output layer's store */ }
+  }
+  const void* hT = s_ho->scheme == RAD_EXACT ? s_ho->values : m->act[T & 1];
+  RAD_TRY(forward_gemm(c, kF32, B, C, H, hT, H, W_ho, b_o, 0, m->logits, nullptr, 0, nullptr, nullptr, 0, 0, nullptr));
+  RAD_TRY(softmax_call(c, m->logits, labels, B, C, kF32, m->dyb[0], c->loss_dev));
+
+  // backward
+  float* dz = static_cast<float*>(m->dyb[0]);
+  RAD_TRY(dW_gemm(c, s_ho, 0, dz, C, nullptr, 0, dW_ho, 0));
+  RAD_TRY(colsum_call(c, dz, kF32, B, C, nullptr, 0, nullptr, 0, 0, db_o, nullptr, 0));
+  RAD_TRY(dX_gemm(c, kF32, B, H, C, dz, nullptr, 0, W_ho, m->dyb[1]));
+  int cur = 1;
+  if (T == 1) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(dW_hh), 0u, (int64_t)H * H, c->stream));
+  for (int t = T; t >= 1; --t) {
+    const uint32_t* bits = m->rnn_bits + (size_t)(t - 1) * B * bp;
+    const int beta = t < T;
+    if (t >= 2) RAD_TRY(dW_gemm(c, s_hh, t - 2, m->dyb[cur], H, bits, bp, dW_hh, beta));
+    RAD_TRY(colsum_call(c, m->dyb[cur], kF32, B, H, bits, bp, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db, dW_ih,
+                        beta));
+    if (t >= 2) {
+      RAD_TRY(dX_gemm(c, kF32, B, H, H, m->dyb[cur], bits, bp, W_hh, m->dyb[cur ^ 1]));
+      cur ^= 1;
+    }
+  }
+  HIP_TRY(c, hipMemcpyAsync(loss_host, c->loss_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return stores_overflowed(c, m);
+}
+
+extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t, int32_t, const int32_t*, const int32_t*, int32_t,
+                                           int32_t, int32_t, int32_t, int32_t, double, rad_model** out) {
+  if (!c) return RAD_ERR_NULL;
+  if (out) *out = nullptr;
+  return fail(c, RAD_ERR_UNSUPPORTED, "the convolutional model is not built yet");
+}
+
+extern "C" rad_status rad_train_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, const void* x,
+                                     const int32_t* labels, void* const* params, void* const* grads,
+                                     float* loss_host) {
+  if (!c) return RAD_ERR_NULL;
+  if (!m || !sm || !x || !labels || !params || !grads || !loss_host) return fail(c, RAD_ERR_NULL, "null argument");
+  RAD_TRY(check_scheme(c, sm->scheme, sm->p));
+  if (sm->scheme != m->scheme || sm->p != m->p) return fail(c, RAD_ERR_PARAM, "sampling does not match the model");
+  if (m->kind == kMlp) return mlp_step(c, m, sm, x, labels, params, grads, loss_host);
+  if (m->kind == kRnn) return rnn_step(c, m, sm, x, labels, params, grads, loss_host);
+  return fail(c, RAD_ERR_UNSUPPORTED, "model kind not built yet");
+}
+

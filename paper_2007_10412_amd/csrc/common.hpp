@@ -1,0 +1,54 @@
+// Shared device-side definitions for the RAD kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rad {
+
+constexpr int kBucket = 256;      // columns per offset-table bucket of a store
+constexpr int kWave = 64;
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+enum Scheme : int { kExact = 0, kBernoulli = 1, kFixedKShared = 2, kFixedKPerExample = 3 };
+enum DType : int { kF32 = 0, kBF16 = 1 };
+
+// fp32 -> bf16 bits, round to nearest even (NaN payload is not preserved; the
+// library never produces NaN from finite inputs).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// lanes of this wave with a lower lane id that have `pred` set
+__device__ __forceinline__ int lanes_below(uint64_t ballot) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32),
+                                   __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0));
+}
+
+// View of a compressed store as kernels see it.  All pointers are device memory.
+struct StoreView {
+  void* values;              // capacity entries, storage dtype
+  uint16_t* indices;         // capacity entries, column of each value
+  uint32_t* row_ptr;         // rows + 1, first entry of every row
+  uint16_t* bucket_off;      // [plan_rows][nb + 1]: entries of the row before column 256*t
+  uint32_t* bitmap;          // transient keep bitmap [plan_rows][bm_pitch] words
+  int64_t capacity;
+  int rows;                  // rows of one step block
+  int cols;
+  int nb;                    // ceil(cols / 256)
+  int bm_pitch;              // words per bitmap row
+  int plan_row_stride;       // 1, or 0 when every row shares one plan row (shared scheme)
+  int idx_shared;            // shared scheme: `indices` holds the k columns once (written by row 0)
+  float scale;
+};
+
+}  // namespace rad

@@ -1,0 +1,628 @@
+// MFMA GEMM engine for gfx950: C[M,N] = A[M,K] * B[K,N], fp32 accumulate.
+//
+// One workgroup of 256 threads (4 waves, 2x2) owns a BM x BN output tile and
+// walks K in slices of BK through a double-buffered LDS stage.  Operands reach
+// LDS through loader objects (global -> registers -> LDS), which lets the same
+// main loop serve every GEMM of the RAD train step:
+//   forward   y  = x W          A: x  K-contiguous   B: W  N-contiguous
+//   dX           = g W^T        A: g  K-contiguous   B: W  K-contiguous
+//   dW (RAD)     = x~^T g       A: compressed store  B: g  N-contiguous
+//   dW (dense)   = x^T g        A: x  M-contiguous   B: g  N-contiguous
+// with g = dy masked by the stored ReLU bits inside the loader.
+//
+// fp32 operands use v_mfma_f32_32x32x2_f32 with LDS tiles laid out [k][row]
+// (one float per lane per operand); bf16 operands use v_mfma_f32_32x32x16_bf16
+// with LDS tiles laid out [row][k] in 16-byte units under an XOR swizzle that
+// keeps both the MFMA fragment reads (32 consecutive rows, one unit column)
+// and the transposing loader's writes (rows 8 apart) spread over the banks.
+#pragma once
+#include "kernels.hpp"
+
+namespace rad {
+
+constexpr int kGemmThreads = 256;
+
+struct F32Tag {};
+struct BF16Tag {};
+
+template <class DT> struct ElemOf;
+template <> struct ElemOf<F32Tag> { typedef float type; };
+template <> struct ElemOf<BF16Tag> { typedef uint16_t type; };
+
+// ------------------------------------------------------------ LDS layouts
+template <int R, int BK> struct LdsF32 {
+  static constexpr int P = R + 4;               // pitch in floats, keeps 16-byte alignment
+  static constexpr int BYTES = BK * P * 4;
+  static __device__ __forceinline__ int at(int row, int k) { return k * P + row; }
+};
+template <int R, int BK> struct LdsBF16 {
+  static constexpr int CH = BK / 8;             // 16-byte units per row
+  static constexpr int BYTES = R * BK * 2;
+  static __device__ __forceinline__ int unit(int row, int kc) {
+    return row * CH + (kc ^ ((row ^ (row >> 3)) & (CH - 1)));
+  }
+};
+
+__device__ __forceinline__ uint32_t mask_bits(const uint32_t* mask, int pitch, int outer, int inner) {
+  return mask[(size_t)outer * pitch + (inner >> 5)] >> (inner & 31);
+}
+
+// =========================================================== fp32 loaders
+// dense, K contiguous: element (row, k) at p[row*ld + k]
+template <int R, int BK> struct F32LoadK {
+  static constexpr int TOTAL = R * BK / 4;
+  static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  typedef LdsF32<R, BK> L;
+  floatx4 v[NCH];
+  __device__ __forceinline__ void bounds(int) {}
+  __device__ __forceinline__ void fetch(const float* p, int64_t ld, const uint32_t* mask, int mp,
+                                        int r0, int k0, int rmax, int K) {
+    const bool vec = (ld & 3) == 0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      floatx4 t = {0.f, 0.f, 0.f, 0.f};
+      if (c < TOTAL) {
+        const int row = c / (BK / 4), k4 = c % (BK / 4);
+        const int gr = r0 + row, gk = k0 + k4 * 4;
+        if (gr < rmax && gk < K) {
+          const float* src = p + (size_t)gr * ld + gk;
+          if (vec && gk + 3 < K) t = *reinterpret_cast<const floatx4*>(src);
+          else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (gk + e < K) t[e] = src[e];
+          }
+          if (mask) {
+            const uint32_t mb = mask_bits(mask, mp, gr, gk);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (!((mb >> e) & 1u)) t[e] = 0.f;
+          }
+        }
+      }
+      v[i] = t;
+    }
+  }
+  __device__ __forceinline__ void commit(float* lds) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      if (c < TOTAL) {
+        const int row = c / (BK / 4), k4 = c % (BK / 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lds[L::at(row, k4 * 4 + e)] = v[i][e];
+      }
+    }
+  }
+};
+
+// dense, M/N contiguous: element (row, k) at p[k*ld + row]
+template <int R, int BK> struct F32LoadMN {
+  static constexpr int TOTAL = R * BK / 4;
+  static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  typedef LdsF32<R, BK> L;
+  floatx4 v[NCH];
+  __device__ __forceinline__ void bounds(int) {}
+  __device__ __forceinline__ void fetch(const float* p, int64_t ld, const uint32_t* mask, int mp,
+                                        int r0, int k0, int rmax, int K) {
+    const bool vec = (ld & 3) == 0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      floatx4 t = {0.f, 0.f, 0.f, 0.f};
+      if (c < TOTAL) {
+        const int k = c / (R / 4), m4 = c % (R / 4);
+        const int gk = k0 + k, gr = r0 + m4 * 4;
+        if (gk < K && gr < rmax) {
+          const float* src = p + (size_t)gk * ld + gr;
+          if (vec && gr + 3 < rmax) t = *reinterpret_cast<const floatx4*>(src);
+          else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (gr + e < rmax) t[e] = src[e];
+          }
+          if (mask) {
+            const uint32_t mb = mask_bits(mask, mp, gk, gr);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (!((mb >> e) & 1u)) t[e] = 0.f;
+          }
+        }
+      }
+      v[i] = t;
+    }
+  }
+  __device__ __forceinline__ void commit(float* lds) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      if (c < TOTAL) {
+        const int k = c / (R / 4), m4 = c % (R / 4);
+        *reinterpret_cast<floatx4*>(&lds[L::at(m4 * 4, k)]) = v[i];
+      }
+    }
+  }
+};
+
+// Segment of a store row that falls into one 256-column bucket.
+__device__ __forceinline__ void store_segment(const StoreView& s, int row, int bucket, int64_t* beg, int64_t* end) {
+  const uint16_t* bo = s.bucket_off + (size_t)(row * s.plan_row_stride) * (s.nb + 1) + bucket;
+  const int64_t base = s.row_ptr[row];
+  int64_t b = base + bo[0], e = base + bo[1];
+  if (e > s.capacity) e = s.capacity;       // an overflowed Bernoulli draw never reads past the arrays
+  if (b > e) b = e;
+  *beg = b; *end = e;
+}
+
+// compressed store as the A operand of dW: K index = store row (example b),
+// M index = column j.  Wave w owns the k rows [w*BK/4, (w+1)*BK/4) of the LDS
+// tile: it clears them and scatters the entries of those store rows whose
+// column falls in [m0, m0+R), so no block barrier sits between clear and scatter.
+template <int R, int BK, int SE> struct F32LoadSparse {
+  typedef LdsF32<R, BK> L;
+  static constexpr int RPW = BK / 4;            // k rows per wave
+  static constexpr int LPR = 64 / RPW;          // lanes per k row
+  float val[SE]; int col[SE];
+  int64_t beg, end, nbeg, nend;
+  __device__ __forceinline__ void bounds(const StoreView& s, int m0, int k0, int K) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int b = k0 + w * RPW + lane / LPR;
+    nbeg = nend = 0;
+    if (b < K) store_segment(s, b, m0 / kBucket, &nbeg, &nend);
+  }
+  __device__ __forceinline__ void fetch(const StoreView& s, int m0) {
+    const int sub = (threadIdx.x & 63) % LPR;
+    beg = nbeg; end = nend;
+    const float* vals = reinterpret_cast<const float*>(s.values);
+#pragma unroll
+    for (int i = 0; i < SE; ++i) {
+      const int64_t e = beg + sub + i * LPR;
+      col[i] = -1; val[i] = 0.f;
+      if (e < end) { col[i] = (int)s.indices[e] - m0; val[i] = vals[e]; }
+    }
+  }
+  __device__ __forceinline__ void commit(float* lds, const StoreView& s, int m0) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const floatx4 z = {0.f, 0.f, 0.f, 0.f};
+    for (int c = lane; c < RPW * (L::P / 4); c += 64)
+      *reinterpret_cast<floatx4*>(&lds[(w * RPW) * L::P + c * 4]) = z;
+    const int kr = w * RPW + lane / LPR, sub = lane % LPR;
+#pragma unroll
+    for (int i = 0; i < SE; ++i)
+      if (col[i] >= 0 && col[i] < R) lds[L::at(col[i], kr)] = val[i];
+    const float* vals = reinterpret_cast<const float*>(s.values);
+    for (int64_t e = beg + sub + (int64_t)SE * LPR; e < end; e += LPR) {
+      const int c = (int)s.indices[e] - m0;
+      if (c >= 0 && c < R) lds[L::at(c, kr)] = vals[e];
+    }
+  }
+};
+
+// =========================================================== bf16 loaders
+// dense, K contiguous
+template <int R, int BK> struct BF16LoadK {
+  typedef LdsBF16<R, BK> L;
+  static constexpr int TOTAL = R * L::CH;
+  static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  u32x4 v[NCH];
+  __device__ __forceinline__ void bounds(int) {}
+  __device__ __forceinline__ void fetch(const uint16_t* p, int64_t ld, const uint32_t* mask, int mp,
+                                        int r0, int k0, int rmax, int K) {
+    const bool vec = (ld & 7) == 0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      u32x4 t = {0u, 0u, 0u, 0u};
+      if (c < TOTAL) {
+        const int row = c / L::CH, kc = c % L::CH;
+        const int gr = r0 + row, gk = k0 + kc * 8;
+        if (gr < rmax && gk < K) {
+          const uint16_t* src = p + (size_t)gr * ld + gk;
+          if (vec && gk + 7 < K) t = *reinterpret_cast<const u32x4*>(src);
+          else {
+            uint16_t* te = reinterpret_cast<uint16_t*>(&t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) if (gk + e < K) te[e] = src[e];
+          }
+          if (mask) {
+            const uint32_t mb = mask_bits(mask, mp, gr, gk);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              uint32_t keep = ((mb >> (2 * e)) & 1u ? 0x0000FFFFu : 0u) | ((mb >> (2 * e + 1)) & 1u ? 0xFFFF0000u : 0u);
+              t[e] &= keep;
+            }
+          }
+        }
+      }
+      v[i] = t;
+    }
+  }
+  __device__ __forceinline__ void commit(uint16_t* lds) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      if (c < TOTAL) {
+        const int row = c / L::CH, kc = c % L::CH;
+        *reinterpret_cast<u32x4*>(&lds[L::unit(row, kc) * 8]) = v[i];
+      }
+    }
+  }
+};
+
+// dense, M/N contiguous: an 8(k) x 8(row) block per thread is transposed in
+// registers so that LDS receives 16-byte units of 8 consecutive k.
+template <int R, int BK> struct BF16LoadMN {
+  typedef LdsBF16<R, BK> L;
+  static constexpr int RB = R / 8, KB = BK / 8;
+  static constexpr int TOTAL = RB * KB;
+  static constexpr int NBL = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  u32x4 v[NBL][8];                               // v[.][kk] = 8 consecutive rows at k = kb*8+kk
+  __device__ __forceinline__ void bounds(int) {}
+  __device__ __forceinline__ void fetch(const uint16_t* p, int64_t ld, const uint32_t* mask, int mp,
+                                        int r0, int k0, int rmax, int K) {
+    const bool vec = (ld & 7) == 0;
+#pragma unroll
+    for (int i = 0; i < NBL; ++i) {
+      const int blk = threadIdx.x + i * kGemmThreads;
+      const int rb = blk % RB, kb = blk / RB;
+      const int gr = r0 + rb * 8;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        u32x4 t = {0u, 0u, 0u, 0u};
+        const int gk = k0 + kb * 8 + kk;
+        if (blk < TOTAL && gk < K && gr < rmax) {
+          const uint16_t* src = p + (size_t)gk * ld + gr;
+          if (vec && gr + 7 < rmax) t = *reinterpret_cast<const u32x4*>(src);
+          else {
+            uint16_t* te = reinterpret_cast<uint16_t*>(&t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) if (gr + e < rmax) te[e] = src[e];
+          }
+          if (mask) {
+            const uint32_t mb = mask_bits(mask, mp, gk, gr);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              uint32_t keep = ((mb >> (2 * e)) & 1u ? 0x0000FFFFu : 0u) | ((mb >> (2 * e + 1)) & 1u ? 0xFFFF0000u : 0u);
+              t[e] &= keep;
+            }
+          }
+        }
+        v[i][kk] = t;
+      }
+    }
+  }
+  __device__ __forceinline__ void commit(uint16_t* lds) {
+#pragma unroll
+    for (int i = 0; i < NBL; ++i) {
+      const int blk = threadIdx.x + i * kGemmThreads;
+      if (blk < TOTAL) {
+        const int rb = blk % RB, kb = blk / RB;
+        // dword d of v[kk] holds rows 2d (low half) and 2d+1 (high half) at k = kk
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          u32x4 lo, hi;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const uint32_t a = v[i][2 * q][d], b = v[i][2 * q + 1][d];
+            lo[q] = __builtin_amdgcn_perm(b, a, 0x05040100u);   // (a.lo, b.lo)
+            hi[q] = __builtin_amdgcn_perm(b, a, 0x07060302u);   // (a.hi, b.hi)
+          }
+          *reinterpret_cast<u32x4*>(&lds[L::unit(rb * 8 + 2 * d, kb) * 8]) = lo;
+          *reinterpret_cast<u32x4*>(&lds[L::unit(rb * 8 + 2 * d + 1, kb) * 8]) = hi;
+        }
+      }
+    }
+  }
+};
+
+// compressed store as A of dW (see F32LoadSparse).  LDS tile is [row j][k b];
+// wave w owns the k columns [w*BK/4, (w+1)*BK/4) = RPW*2 bytes of every row.
+template <int R, int BK, int SE> struct BF16LoadSparse {
+  typedef LdsBF16<R, BK> L;
+  static constexpr int RPW = BK / 4;            // k (store rows) per wave: 16 at BK = 64
+  static constexpr int LPR = 64 / RPW;          // lanes per store row
+  static constexpr int UPW = RPW / 8;           // 16-byte units per tile row owned by a wave
+  uint32_t ent[SE];                              // (value bits << 16) | (column - m0), 0xFFFF = none
+  int64_t beg, end, nbeg, nend;
+  __device__ __forceinline__ void bounds(const StoreView& s, int m0, int k0, int K) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int b = k0 + w * RPW + lane / LPR;
+    nbeg = nend = 0;
+    if (b < K) store_segment(s, b, m0 / kBucket, &nbeg, &nend);
+  }
+  __device__ __forceinline__ void fetch(const StoreView& s, int m0) {
+    const int sub = (threadIdx.x & 63) % LPR;
+    beg = nbeg; end = nend;
+    const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
+#pragma unroll
+    for (int i = 0; i < SE; ++i) {
+      const int64_t e = beg + sub + i * LPR;
+      ent[i] = 0xFFFFu;
+      if (e < end) {
+        const int c = (int)s.indices[e] - m0;
+        if (c >= 0 && c < R) ent[i] = ((uint32_t)vals[e] << 16) | (uint32_t)c;
+      }
+    }
+  }
+  __device__ __forceinline__ void commit(uint16_t* lds, const StoreView& s, int m0) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int c = lane; c < R * UPW; c += 64) {
+      const int row = c / UPW, u = c % UPW;
+      *reinterpret_cast<u32x4*>(&lds[L::unit(row, w * UPW + u) * 8]) = z;
+    }
+    const int kr = w * RPW + lane / LPR, sub = lane % LPR;
+#pragma unroll
+    for (int i = 0; i < SE; ++i) {
+      const uint32_t c = ent[i] & 0xFFFFu;
+      if (c != 0xFFFFu) lds[L::unit((int)c, kr >> 3) * 8 + (kr & 7)] = (uint16_t)(ent[i] >> 16);
+    }
+    const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
+    for (int64_t e = beg + sub + (int64_t)SE * LPR; e < end; e += LPR) {
+      const int c = (int)s.indices[e] - m0;
+      if (c >= 0 && c < R) lds[L::unit(c, kr >> 3) * 8 + (kr & 7)] = vals[e];
+    }
+  }
+};
+
+// ================================================================ operands
+template <class DT, int KIND, int R, int BK, int SE> struct LoaderOf;
+template <int R, int BK, int SE> struct LoaderOf<F32Tag, kOpK, R, BK, SE> { typedef F32LoadK<R, BK> type; };
+template <int R, int BK, int SE> struct LoaderOf<F32Tag, kOpMN, R, BK, SE> { typedef F32LoadMN<R, BK> type; };
+template <int R, int BK, int SE> struct LoaderOf<F32Tag, kOpSparse, R, BK, SE> { typedef F32LoadSparse<R, BK, SE> type; };
+template <int R, int BK, int SE> struct LoaderOf<BF16Tag, kOpK, R, BK, SE> { typedef BF16LoadK<R, BK> type; };
+template <int R, int BK, int SE> struct LoaderOf<BF16Tag, kOpMN, R, BK, SE> { typedef BF16LoadMN<R, BK> type; };
+template <int R, int BK, int SE> struct LoaderOf<BF16Tag, kOpSparse, R, BK, SE> { typedef BF16LoadSparse<R, BK, SE> type; };
+
+template <class DT, int R, int BK> struct LdsOf;
+template <int R, int BK> struct LdsOf<F32Tag, R, BK> { typedef LdsF32<R, BK> type; };
+template <int R, int BK> struct LdsOf<BF16Tag, R, BK> { typedef LdsBF16<R, BK> type; };
+
+// ============================================================== MFMA core
+template <class DT, int BM, int BN, int BK> struct Mma;
+
+template <int BM, int BN, int BK> struct Mma<F32Tag, BM, BN, BK> {
+  static constexpr int TM = BM / 64, TN = BN / 64;
+  typedef LdsF32<BM, BK> LA; typedef LdsF32<BN, BK> LB;
+  static __device__ __forceinline__ void run(const float* As, const float* Bs, floatx16 (&acc)[TM][TN],
+                                             int wm0, int wn0) {
+    const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      float a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a[i] = As[LA::at(wm0 + i * 32 + lr, kk + lk)];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[j] = Bs[LB::at(wn0 + j * 32 + lr, kk + lk)];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  }
+};
+
+template <int BM, int BN, int BK> struct Mma<BF16Tag, BM, BN, BK> {
+  static constexpr int TM = BM / 64, TN = BN / 64;
+  typedef LdsBF16<BM, BK> LA; typedef LdsBF16<BN, BK> LB;
+  static __device__ __forceinline__ void run(const uint16_t* As, const uint16_t* Bs, floatx16 (&acc)[TM][TN],
+                                             int wm0, int wn0) {
+    const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, kk * 2 + lk) * 8]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, kk * 2 + lk) * 8]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  }
+};
+
+// ============================================================== epilogues
+__device__ __forceinline__ void put_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void put_elem(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
+__device__ __forceinline__ float get_elem(const float* p) { return *p; }
+__device__ __forceinline__ float get_elem(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+
+// accumulator element i of a 32x32 block sits at row (i/4)*8 + (lane/32)*4 + i%4, column lane%32
+__device__ __forceinline__ int acc_row(int i, int lane) { return (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3); }
+
+template <int TM, int TN, typename OutT>
+__device__ __forceinline__ void epilogue_store(const GemmArgs& g, floatx16 (&acc)[TM][TN], int m0, int n0,
+                                               int wm0, int wn0) {
+  const int lane = threadIdx.x & 63;
+  OutT* C = reinterpret_cast<OutT*>(g.C);
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn0 + j * 32 + (lane & 31);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm0 + i * 32 + acc_row(e, lane);
+        if (row < g.M && col < g.N) {
+          const int orow = g.row_map ? (int)g.row_map[row] : row;
+          OutT* dst = C + (size_t)orow * g.ldc + col;
+          float v = acc[i][j][e];
+          if (g.beta) v += get_elem(dst);
+          put_elem(dst, v);
+        }
+      }
+    }
+}
+
+// Forward epilogue.  The tile goes through LDS in the storage dtype so that
+// the second phase runs row by row with lane l on columns l, l+64, ...: dense
+// y stores are contiguous, a wave ballot of (y > 0) IS two words of the ReLU
+// bit array, and the keep bits of the next layer's plan give every kept entry
+// its slot in the packed row with a popcount.
+template <typename ElemT, int BM, int BN, int TM, int TN>
+__device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[TM][TN], ElemT* ct, int m0, int n0,
+                                             int wm0, int wn0) {
+  constexpr int CP = BN + (sizeof(ElemT) == 4 ? 1 : 2);   // odd word pitch
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int lc = wn0 + j * 32 + (lane & 31);
+      const int col = n0 + lc;
+      const float bv = (g.bias && col < g.N) ? g.bias[col] : 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int lrow = wm0 + i * 32 + acc_row(e, lane);
+        const int row = m0 + lrow;
+        float h = acc[i][j][e] + bv;
+        if (g.u_n > 0 && row < g.M && col < g.N)
+          for (int q = 0; q < g.u_n; ++q) h += g.u[(size_t)row * g.u_ld + q] * g.V[(size_t)q * g.N + col];
+        if (g.relu) h = h > 0.f ? h : 0.f;
+        put_elem(&ct[lrow * CP + lc], h);
+      }
+    }
+  __syncthreads();
+  ElemT* Y = reinterpret_cast<ElemT*>(g.y);
+  for (int r = w; r < BM; r += 4) {
+    const int row = m0 + r;
+    if (row >= g.M) break;
+    int rel = 0;                       // slot inside the packed row of the next store
+    int64_t base = 0;
+    const uint32_t* bm_row = nullptr;
+    if (g.pack) {
+      const int prow = row * g.next.plan_row_stride;
+      bm_row = g.next.bitmap + (size_t)prow * g.next.bm_pitch;
+      const int bucket = n0 / kBucket;
+      base = (int64_t)g.next.row_ptr[row];
+      rel = g.next.bucket_off[(size_t)prow * (g.next.nb + 1) + bucket];
+      for (int wd = bucket * (kBucket / 32); wd < n0 / 32; ++wd) rel += __popc(bm_row[wd]);
+    }
+#pragma unroll
+    for (int c0 = 0; c0 < BN; c0 += 64) {
+      const int col = n0 + c0 + lane;
+      const ElemT raw = ct[r * CP + c0 + lane];
+      const float yv = get_elem(&raw);
+      if (col < g.N && Y) Y[(size_t)row * g.ldy + col] = raw;
+      if (g.bits) {
+        const uint64_t bal = __ballot(col < g.N && yv > 0.f);
+        const int wi = (n0 + c0) / 32;
+        if (lane == 0 && wi < g.bits_pitch) g.bits[(size_t)row * g.bits_pitch + wi] = (uint32_t)bal;
+        if (lane == 32 && wi + 1 < g.bits_pitch) g.bits[(size_t)row * g.bits_pitch + wi + 1] = (uint32_t)(bal >> 32);
+      }
+      if (g.pack) {
+        const int wi = (n0 + c0) / 32;
+        uint64_t kw = 0;
+        if (wi < g.next.bm_pitch) kw = bm_row[wi];
+        if (wi + 1 < g.next.bm_pitch) kw |= (uint64_t)bm_row[wi + 1] << 32;
+        if ((kw >> lane) & 1ull) {
+          const int r2 = rel + __popcll(kw & ((1ull << lane) - 1ull));
+          const int64_t p = base + r2;
+          if (p < g.next.capacity) {
+            put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv * g.next.scale);
+            if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)col;
+            else if (row == 0) g.next.indices[r2] = (uint16_t)col;
+          }
+        }
+        rel += __popcll(kw);
+      }
+    }
+  }
+}
+
+// ============================================================ the kernel
+template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE>
+struct GemmSmem {
+  typedef typename LdsOf<DT, BM, BK>::type LA;
+  typedef typename LdsOf<DT, BN, BK>::type LB;
+  typedef typename ElemOf<DT>::type ElemT;
+  static constexpr int STAGE = LA::BYTES + LB::BYTES;
+  static constexpr int MAIN = 2 * STAGE;
+  static constexpr int CT = BM * (BN + (sizeof(ElemT) == 4 ? 1 : 2)) * (int)sizeof(ElemT);
+  static constexpr int BYTES = (EPI == kEpiFwd && CT > MAIN) ? CT : MAIN;
+};
+
+template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE>
+__global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
+  typedef typename ElemOf<DT>::type ElemT;
+  typedef GemmSmem<DT, AK, BKIND, EPI, BM, BN, BK, SE> S;
+  typedef typename LoaderOf<DT, AK, BM, BK, SE>::type LoadA;
+  typedef typename LoaderOf<DT, BKIND, BN, BK, SE>::type LoadB;
+  constexpr int TM = BM / 64, TN = BN / 64;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+
+  // tile order: N fastest inside a band of rows, so concurrently resident
+  // workgroups share A rows (and the compressed-store bucket) through L2
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tile = blockIdx.x;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  const int w = threadIdx.x >> 6;
+  const int wm0 = (w >> 1) * (BM / 2), wn0 = (w & 1) * (BN / 2);
+
+  ElemT* stage[2][2];
+  stage[0][0] = reinterpret_cast<ElemT*>(smem_raw);
+  stage[0][1] = reinterpret_cast<ElemT*>(smem_raw + S::LA::BYTES);
+  stage[1][0] = reinterpret_cast<ElemT*>(smem_raw + S::STAGE);
+  stage[1][1] = reinterpret_cast<ElemT*>(smem_raw + S::STAGE + S::LA::BYTES);
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  LoadA la; LoadB lb;
+  const ElemT* Ap = reinterpret_cast<const ElemT*>(g.A);
+  const ElemT* Bp = reinterpret_cast<const ElemT*>(g.B);
+  const int KT = (g.K + BK - 1) / BK;
+
+  auto fetchA = [&](int kt) {
+    if constexpr (AK == kOpSparse) la.fetch(g.sa, m0);
+    else la.fetch(Ap, g.lda, g.a_mask, g.a_mask_pitch, m0, kt * BK, g.M, g.K);
+  };
+  auto boundsA = [&](int kt) {
+    if constexpr (AK == kOpSparse) la.bounds(g.sa, m0, kt * BK, g.K);
+  };
+  auto commitA = [&](ElemT* lds) {
+    if constexpr (AK == kOpSparse) la.commit(lds, g.sa, m0);
+    else la.commit(lds);
+  };
+
+  if (KT > 0) {
+    boundsA(0);
+    fetchA(0);
+    if (KT > 1) boundsA(1);
+    lb.fetch(Bp, g.ldb, g.b_mask, g.b_mask_pitch, n0, 0, g.N, g.K);
+    commitA(stage[0][0]);
+    lb.commit(stage[0][1]);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int cur = kt & 1, nxt = cur ^ 1;
+    if (kt + 1 < KT) {
+      fetchA(kt + 1);                       // uses the bounds loaded one iteration earlier
+      if (kt + 2 < KT) boundsA(kt + 2);
+      lb.fetch(Bp, g.ldb, g.b_mask, g.b_mask_pitch, n0, (kt + 1) * BK, g.N, g.K);
+    }
+    Mma<DT, BM, BN, BK>::run(stage[cur][0], stage[cur][1], acc, wm0, wn0);
+    if (kt + 1 < KT) {
+      commitA(stage[nxt][0]);
+      lb.commit(stage[nxt][1]);
+    }
+    __syncthreads();
+  }
+
+  if constexpr (EPI == kEpiStore) {
+    if (g.c_dtype == kF32) epilogue_store<TM, TN, float>(g, acc, m0, n0, wm0, wn0);
+    else epilogue_store<TM, TN, uint16_t>(g, acc, m0, n0, wm0, wn0);
+  } else {
+    epilogue_fwd<ElemT, BM, BN, TM, TN>(g, acc, reinterpret_cast<ElemT*>(smem_raw), m0, n0, wm0, wn0);
+  }
+}
+
+}  // namespace rad

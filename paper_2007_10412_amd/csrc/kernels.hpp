@@ -1,0 +1,78 @@
+// Host-visible launch interfaces of the RAD kernels.
+#pragma once
+#include "common.hpp"
+
+namespace rad {
+
+struct PlanArgs {
+  uint32_t seed_lo, seed_hi, stream_id, step0;
+  int scheme;          // kBernoulli, kFixedKShared, kFixedKPerExample
+  int plan_rows;       // rows drawn: steps*rows, or steps for the shared scheme
+  int rows_per_step;   // rows of one step block of the store
+  int cols;
+  int k;               // fixed-k schemes
+  uint64_t thresh;     // Bernoulli: keep iff key < thresh
+  int key_shift;       // 0; tests raise it to force equal keys
+  uint32_t* bitmap;    // [plan_rows][bm_pitch]
+  int bm_pitch;
+  uint16_t* bucket_off;  // [plan_rows][nb+1]
+  int nb;
+  uint32_t* row_cnt;   // [plan_rows], Bernoulli only
+  uint32_t* row_ptr;   // [steps*rows + 1], written here for the fixed-k schemes
+};
+
+hipError_t launch_plan(const PlanArgs& a, hipStream_t st);
+int plan_max_cols(int scheme);
+hipError_t launch_row_scan(const uint32_t* row_cnt, uint32_t* row_ptr, int rows, int64_t capacity,
+                           int* overflow, hipStream_t st);
+hipError_t launch_pack(const void* x, int dtype, const StoreView& s, hipStream_t st);
+
+// ---------------------------------------------------------------- GEMM family
+// C[M,N] = A[M,K] * B[K,N] on MFMA with fp32 accumulation.  Operand sources:
+enum OpKind : int {
+  kOpK = 0,      // dense, K contiguous:  A[m*ld + k]   / B[n*ld + k]
+  kOpMN = 1,     // dense, M/N contiguous: A[k*ld + m]  / B[k*ld + n]
+  kOpSparse = 2  // A only: rows of a compressed store are the K index, columns the M index
+};
+enum EpiKind : int {
+  kEpiStore = 0, // C (+= if beta) = acc, optional output row map
+  kEpiFwd = 1    // bias / rank-u addend / ReLU / bits / dense y / pack next store
+};
+
+struct GemmArgs {
+  int M, N, K;
+  const void* A; int64_t lda;
+  const void* B; int64_t ldb;
+  // optional bit mask over a dense operand: element (outer, inner) is zeroed when
+  // bit (inner % 32) of mask[outer * pitch + inner / 32] is 0 (inner = contiguous index)
+  const uint32_t* a_mask; int a_mask_pitch;
+  const uint32_t* b_mask; int b_mask_pitch;
+  StoreView sa;                 // kOpSparse A
+  int sparse_prefetch;          // entries per lane held in registers (host picks)
+  // kEpiStore
+  void* C; int64_t ldc; int beta; int c_dtype;   // c_dtype: kF32 or kBF16
+  const uint16_t* row_map;      // output row of tile row r (null = r)
+  // kEpiFwd
+  const float* bias; int relu;
+  void* y; int64_t ldy;         // dense output, operand dtype
+  uint32_t* bits; int bits_pitch;
+  int pack; StoreView next;     // pack the output tile into `next` (rows = M, cols = N)
+  const float* u; int64_t u_ld; int u_n; const float* V;   // h += sum_i u[m*u_ld+i] * V[i*N+n]
+};
+
+// dtype: operand element type; returns hipErrorInvalidValue for combinations
+// without a kernel.  `name` (out, may be null) receives the kernel's label.
+hipError_t launch_gemm(int dtype, int a_kind, int b_kind, int epi, const GemmArgs& g,
+                       hipStream_t st, const char** name);
+
+// ------------------------------------------------------------- small kernels
+hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows, int classes,
+                             int dtype, void* dlogits, float* row_loss, float* loss, hipStream_t st);
+// out[i*N + n] (+)= sum_b w_i[b] * g[b,n], i = 0..n_w; w_0 = 1 (bias gradient),
+// w_i = u[b*u_ld + i-1]; g = dy masked by bits.  partial: [splits][n_w+1][N] scratch.
+hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint32_t* bits, int bits_pitch,
+                         const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
+                         int beta, float* partial, int splits, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t st);
+
+}  // namespace rad

@@ -1,0 +1,345 @@
+// Sampling plan and stand-alone pack kernels.
+//
+// The keep set of a RAD store (Section 3.2: which coordinates the random
+// matrix P retains) depends only on (seed, stream_id, step, element index),
+// never on data.  plan_kernel therefore draws it once per row, ahead of the
+// kernel that produces the data: it generates the Philox keys of the row,
+// applies the selection rule (Bernoulli threshold, or the k smallest
+// (key, column) pairs for the fixed-k schemes), and leaves a keep bitmap, the
+// per-256-column offsets of the packed row, and the row's entry count.
+// pack_kernel (and the forward GEMM epilogue) then only test bits.
+#include "common.hpp"
+#include "philox.hpp"
+#include "kernels.hpp"
+
+namespace rad {
+
+namespace {
+
+constexpr int kPlanThreads = 256;
+
+// exclusive prefix sum over the 256 threads of a block; *total = block sum
+__device__ __forceinline__ int block_excl_scan(int v, int* total, int* smem) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) smem[w] = inc;
+  __syncthreads();
+  int woff = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < kPlanThreads / 64; ++i) {
+    const int s = smem[i];
+    if (i < w) woff += s;
+    tot += s;
+  }
+  __syncthreads();
+  *total = tot;
+  return woff + inc - v;
+}
+
+// Tail shared by both plan kernels: bitmap row in LDS -> global bitmap,
+// per-bucket offsets, row count / row pointers.
+__device__ __forceinline__ void finish_row(const PlanArgs& a, int prow, const uint32_t* s_bm, int* s_scan) {
+  const int tid = threadIdx.x;
+  uint32_t* bm_out = a.bitmap + (size_t)prow * a.bm_pitch;
+  for (int w = tid; w < a.bm_pitch; w += kPlanThreads) bm_out[w] = s_bm[w];
+
+  int cnt = 0;                          // entries of bucket `tid`
+  if (tid < a.nb) {
+    const int w0 = tid * (kBucket / 32);
+#pragma unroll
+    for (int w = 0; w < kBucket / 32; ++w)
+      if (w0 + w < a.bm_pitch) cnt += __popc(s_bm[w0 + w]);
+  }
+  int total;
+  const int off = block_excl_scan(cnt, &total, s_scan);
+  uint16_t* bo = a.bucket_off + (size_t)prow * (a.nb + 1);
+  if (tid < a.nb) bo[tid] = (uint16_t)off;
+  if (tid == 0) bo[a.nb] = (uint16_t)total;
+
+  if (a.scheme == kBernoulli) {
+    if (tid == 0) a.row_cnt[prow] = (uint32_t)total;
+  } else if (a.scheme == kFixedKPerExample) {
+    if (tid == 0) {
+      a.row_ptr[prow] = (uint32_t)((uint64_t)prow * a.k);
+      if (prow == a.plan_rows - 1) a.row_ptr[a.plan_rows] = (uint32_t)((uint64_t)a.plan_rows * a.k);
+    }
+  } else {  // shared: every store row of this step holds k entries
+    const int r0 = prow * a.rows_per_step;
+    for (int r = tid; r < a.rows_per_step; r += kPlanThreads)
+      a.row_ptr[r0 + r] = (uint32_t)((uint64_t)(r0 + r) * a.k);
+    if (tid == 0 && prow == a.plan_rows - 1)
+      a.row_ptr[a.plan_rows * a.rows_per_step] = (uint32_t)((uint64_t)a.plan_rows * a.rows_per_step * a.k);
+  }
+}
+
+__device__ __forceinline__ void or_nibble(uint32_t* s_bm, uint32_t nib, int j0, int lead) {
+  if (nib == 0) return;
+  if (lead == 0) {
+    atomicOr(&s_bm[j0 >> 5], nib << (j0 & 31));
+  } else {
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      if ((nib >> w) & 1u) { const int j = j0 + w; atomicOr(&s_bm[j >> 5], 1u << (j & 31)); }
+  }
+}
+
+// Bernoulli: keep iff key < T.  Keys are consumed as they are generated.
+__global__ __launch_bounds__(kPlanThreads) void plan_bernoulli_kernel(PlanArgs a) {
+  __shared__ uint32_t s_bm[2048];      // keep bitmap of the row (cols <= 65535)
+  __shared__ int s_scan[8];
+  const int tid = threadIdx.x;
+  const int prow = blockIdx.x;
+  const int t_step = prow / a.rows_per_step, b = prow % a.rows_per_step;
+  const uint32_t step = a.step0 + (uint32_t)t_step;
+  const uint64_t f0 = (uint64_t)b * (uint64_t)a.cols;
+  const uint64_t q0 = f0 >> 2;
+  const int lead = (int)(f0 & 3);
+  const int nq = (int)(((f0 + (uint64_t)a.cols - 1) >> 2) - q0) + 1;
+  for (int w = tid; w < a.bm_pitch; w += kPlanThreads) s_bm[w] = 0;
+  __syncthreads();
+  for (int qi = tid; qi < nq; qi += kPlanThreads) {
+    const u32x4 k4 = element_quad_keys(q0 + (uint64_t)qi, a.stream_id, step, a.seed_lo, a.seed_hi);
+    uint32_t nib = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int j = qi * 4 + w - lead;
+      if (j >= 0 && j < a.cols && (uint64_t)(k4[w] >> a.key_shift) < a.thresh) nib |= 1u << w;
+    }
+    or_nibble(s_bm, nib, qi * 4 - lead, lead);
+  }
+  __syncthreads();
+  finish_row(a, prow, s_bm, s_scan);
+}
+
+// Fixed-k: the k smallest (key, column) pairs of the row.  QPT = Philox calls
+// (groups of four consecutive elements) per thread; the row's keys stay in
+// registers across the radix-select passes.
+template <int QPT>
+__global__ __launch_bounds__(kPlanThreads) void plan_fixedk_kernel(PlanArgs a) {
+  static_assert(QPT <= 16, "keep/valid masks are 64 bits");
+  __shared__ uint32_t s_bm[2048];
+  __shared__ int s_hist[256];
+  __shared__ int s_scan[8];
+  __shared__ int s_sel[3];
+
+  const int tid = threadIdx.x;
+  const int prow = blockIdx.x;         // plan row
+  int t_step, b;
+  if (a.scheme == kFixedKShared) { t_step = prow; b = 0; }
+  else { t_step = prow / a.rows_per_step; b = prow % a.rows_per_step; }
+  const uint32_t step = a.step0 + (uint32_t)t_step;
+
+  const uint64_t f0 = (uint64_t)b * (uint64_t)a.cols;
+  const uint64_t q0 = f0 >> 2;
+  const int lead = (int)(f0 & 3);
+  const int nq = (int)(((f0 + (uint64_t)a.cols - 1) >> 2) - q0) + 1;
+
+  uint32_t key[QPT * 4];
+  uint64_t valid = 0;                  // bit (4i+w): element exists in this row
+#pragma unroll
+  for (int i = 0; i < QPT; ++i) {
+    const int qi = tid + i * kPlanThreads;
+    u32x4 k4 = {0, 0, 0, 0};
+    if (qi < nq) k4 = element_quad_keys(q0 + (uint64_t)qi, a.stream_id, step, a.seed_lo, a.seed_hi);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      key[4 * i + w] = k4[w] >> a.key_shift;
+      const int j = qi * 4 + w - lead;
+      if (qi < nq && j >= 0 && j < a.cols) valid |= 1ull << (4 * i + w);
+    }
+  }
+
+  // k-th smallest key by four 8-bit radix passes, most significant first
+  uint64_t keep = 0;
+  uint32_t prefix = 0, pmask = 0;
+  int kk = a.k;                        // rank (1-based) still to find among matching keys
+  int cnt_eq = 0;
+#pragma unroll 1
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    s_hist[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < QPT * 4; ++e)
+      if (((valid >> e) & 1ull) && (key[e] & pmask) == prefix)
+        atomicAdd(&s_hist[(key[e] >> shift) & 255u], 1);
+    __syncthreads();
+    const int h = s_hist[tid];
+    int tot;
+    const int excl = block_excl_scan(h, &tot, s_scan);
+    if (excl < kk && kk <= excl + h) { s_sel[0] = tid; s_sel[1] = kk - excl; s_sel[2] = h; }
+    __syncthreads();
+    prefix |= (uint32_t)s_sel[0] << shift;
+    pmask |= 255u << shift;
+    kk = s_sel[1];
+    cnt_eq = s_sel[2];
+    __syncthreads();
+  }
+  const uint32_t thr = prefix;         // the k-th smallest key; kk of its cnt_eq copies are kept
+  if (cnt_eq == kk) {
+#pragma unroll
+    for (int e = 0; e < QPT * 4; ++e)
+      if (((valid >> e) & 1ull) && key[e] <= thr) keep |= 1ull << e;
+  } else {
+    // equal keys straddle the cut: the lower columns win.  Column order is
+    // slot-major (i), then thread, then word.
+    int before = 0;
+#pragma unroll
+    for (int i = 0; i < QPT; ++i) {
+      int mine = 0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        if (((valid >> (4 * i + w)) & 1ull) && key[4 * i + w] == thr) ++mine;
+      int tot;
+      int rank = before + block_excl_scan(mine, &tot, s_scan);
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int e = 4 * i + w;
+        if (!((valid >> e) & 1ull)) continue;
+        if (key[e] < thr) keep |= 1ull << e;
+        else if (key[e] == thr) { if (rank < kk) keep |= 1ull << e; ++rank; }
+      }
+      before += tot;
+    }
+  }
+
+  for (int w = tid; w < a.bm_pitch; w += kPlanThreads) s_bm[w] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < QPT; ++i)
+    or_nibble(s_bm, (uint32_t)(keep >> (4 * i)) & 0xFu, (tid + i * kPlanThreads) * 4 - lead, lead);
+  __syncthreads();
+  finish_row(a, prow, s_bm, s_scan);
+}
+
+// row_ptr = exclusive scan of row_cnt (Bernoulli).  One block; flags overflow.
+__global__ __launch_bounds__(1024) void row_scan_kernel(const uint32_t* __restrict__ row_cnt,
+                                                        uint32_t* __restrict__ row_ptr, int rows,
+                                                        int64_t capacity, int* __restrict__ overflow) {
+  __shared__ uint32_t s_w[16];
+  __shared__ uint32_t s_carry;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < rows; base += 1024) {
+    const int r = base + tid;
+    const uint32_t v = r < rows ? row_cnt[r] : 0u;
+    uint32_t inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      uint32_t t = __shfl_up(inc, o);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) s_w[w] = inc;
+    __syncthreads();
+    uint32_t woff = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { const uint32_t s = s_w[i]; if (i < w) woff += s; tot += s; }
+    const uint32_t carry = s_carry;
+    if (r < rows) row_ptr[r] = carry + woff + inc - v;
+    __syncthreads();
+    if (tid == 0) s_carry = carry + tot;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    row_ptr[rows] = s_carry;
+    if ((int64_t)s_carry > capacity) *overflow = 1;
+  }
+}
+
+template <typename T> struct Vec4;
+template <> struct Vec4<float> { typedef floatx4 type; };
+template <> struct Vec4<uint16_t> { typedef u32x2 type; };
+
+__device__ __forceinline__ float load_as_f32(const float* p) { return *p; }
+__device__ __forceinline__ float load_as_f32(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+__device__ __forceinline__ void store_from_f32(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_from_f32(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
+
+// One wave packs one 256-column bucket of one row: lane l owns columns
+// 4l..4l+3 of the bucket (one 16-byte load of fp32, 8 bytes of bf16).
+template <typename T>
+__global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ x, StoreView s) {
+  const int lane = threadIdx.x & 63;
+  const int bucket = blockIdx.y * 4 + (threadIdx.x >> 6);
+  const int row = blockIdx.x;
+  if (bucket >= s.nb) return;
+  const int j0 = bucket * kBucket + lane * 4;
+  const int prow = row * s.plan_row_stride;
+  uint32_t nib = 0;
+  if (j0 < s.cols) nib = (s.bitmap[(size_t)prow * s.bm_pitch + (j0 >> 5)] >> (j0 & 31)) & 0xFu;
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  const T* xr = x + (size_t)row * s.cols;
+  if (j0 < s.cols) {
+    if ((s.cols & 3) == 0) {
+      typename Vec4<T>::type raw = *reinterpret_cast<const typename Vec4<T>::type*>(xr + j0);
+      const T* e = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = load_as_f32(e + i);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) if (j0 + i < s.cols) v[i] = load_as_f32(xr + j0 + i);
+    }
+  }
+  int prefix = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) prefix += lanes_below(__ballot((nib >> e) & 1u));
+  // entries of lower lanes come first, then this lane's own in column order
+  int rel = s.bucket_off[(size_t)prow * (s.nb + 1) + bucket] + prefix;
+  const int64_t base = (int64_t)s.row_ptr[row];
+  T* vals = reinterpret_cast<T*>(s.values);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    if ((nib >> e) & 1u) {
+      const int64_t pos = base + rel;
+      if (pos < s.capacity) {
+        store_from_f32(vals + pos, v[e] * s.scale);
+        if (!s.idx_shared) s.indices[pos] = (uint16_t)(j0 + e);
+        else if (row == 0) s.indices[rel] = (uint16_t)(j0 + e);
+      }
+      ++rel;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_plan(const PlanArgs& a, hipStream_t st) {
+  dim3 grid(a.plan_rows), block(kPlanThreads);
+  if (a.cols < 1 || a.cols > 65535) return hipErrorInvalidValue;
+  if (a.scheme == kBernoulli) {
+    hipLaunchKernelGGL(plan_bernoulli_kernel, grid, block, 0, st, a);
+    return hipGetLastError();
+  }
+  const int nq_max = a.cols / 4 + 2;
+  const int qpt = (nq_max + kPlanThreads - 1) / kPlanThreads;
+  if (qpt <= 1) hipLaunchKernelGGL(plan_fixedk_kernel<1>, grid, block, 0, st, a);
+  else if (qpt <= 4) hipLaunchKernelGGL(plan_fixedk_kernel<4>, grid, block, 0, st, a);
+  else if (qpt <= 16) hipLaunchKernelGGL(plan_fixedk_kernel<16>, grid, block, 0, st, a);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+// widest row the plan kernels handle for a scheme
+int plan_max_cols(int scheme) { return scheme == kBernoulli ? 65535 : 16376; }
+
+hipError_t launch_row_scan(const uint32_t* row_cnt, uint32_t* row_ptr, int rows, int64_t capacity,
+                           int* overflow, hipStream_t st) {
+  hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, st, row_cnt, row_ptr, rows, capacity, overflow);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack(const void* x, int dtype, const StoreView& s, hipStream_t st) {
+  dim3 grid(s.rows, (s.nb + 3) / 4), block(256);
+  if (dtype == kF32)
+    hipLaunchKernelGGL(pack_kernel<float>, grid, block, 0, st, (const float*)x, s);
+  else
+    hipLaunchKernelGGL(pack_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)x, s);
+  return hipGetLastError();
+}
+
+}  // namespace rad

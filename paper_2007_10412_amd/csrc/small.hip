@@ -1,0 +1,156 @@
+// Loss, bias-gradient and fill kernels of the RAD train step.
+#include "kernels.hpp"
+
+namespace rad {
+namespace {
+
+__device__ __forceinline__ float ld_elem(const float* p) { return *p; }
+__device__ __forceinline__ float ld_elem(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+__device__ __forceinline__ void st_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_elem(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// One wave per example: loss_b = -log softmax(z_b)[label_b],
+// dz_b = (softmax(z_b) - onehot(label_b)) / rows.  The logits stay dense
+// (Appendix A: the softmax input is not sampled).
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_ce_kernel(const T* __restrict__ z, const int32_t* __restrict__ labels,
+                                                         int rows, int classes, T* __restrict__ dz,
+                                                         float* __restrict__ row_loss) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* zr = z + (size_t)row * classes;
+  float m = -INFINITY;
+  for (int c = lane; c < classes; c += 64) m = fmaxf(m, ld_elem(zr + c));
+  m = wave_max(m);
+  float s = 0.f;
+  for (int c = lane; c < classes; c += 64) s += expf(ld_elem(zr + c) - m);
+  s = wave_sum(s);
+  const int lab = labels[row];
+  const bool lab_ok = lab >= 0 && lab < classes;     // a bad label poisons the loss instead of the address
+  const float inv = 1.f / s, invb = 1.f / (float)rows;
+  T* dr = dz + (size_t)row * classes;
+  for (int c = lane; c < classes; c += 64) {
+    float p = expf(ld_elem(zr + c) - m) * inv;
+    if (c == lab) p -= 1.f;
+    st_elem(dr + c, p * invb);
+  }
+  if (lane == 0) row_loss[row] = lab_ok ? -(ld_elem(zr + lab) - m - logf(s)) : NAN;
+}
+
+// deterministic mean of the per-example losses
+__global__ __launch_bounds__(256) void loss_mean_kernel(const float* __restrict__ row_loss, int rows,
+                                                        float* __restrict__ loss) {
+  __shared__ float s_w[4];
+  float acc = 0.f;
+  for (int r = threadIdx.x; r < rows; r += 256) acc += row_loss[r];
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) *loss = (s_w[0] + s_w[1] + s_w[2] + s_w[3]) / (float)rows;
+}
+
+constexpr int kMaxU = 8;
+
+// stage 1 of the weighted column sums of g = dy * bits
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ dy, int rows, int N,
+                                                             const uint32_t* __restrict__ bits, int bits_pitch,
+                                                             const float* __restrict__ u, int64_t u_ld, int u_n,
+                                                             float* __restrict__ partial, int splits) {
+  __shared__ float s_red[4][kMaxU + 1][64];
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + cx;
+  const int split = blockIdx.y;
+  const int per = (rows + splits - 1) / splits;
+  const int rbeg = split * per, rend = min(rows, rbeg + per);
+  float acc[kMaxU + 1];
+#pragma unroll
+  for (int i = 0; i <= kMaxU; ++i) acc[i] = 0.f;
+  if (col < N) {
+    for (int r = rbeg + ry; r < rend; r += 4) {
+      float g = ld_elem(dy + (size_t)r * N + col);
+      if (bits && !((bits[(size_t)r * bits_pitch + (col >> 5)] >> (col & 31)) & 1u)) g = 0.f;
+      acc[0] += g;
+#pragma unroll
+      for (int i = 0; i < kMaxU; ++i) if (i < u_n) acc[i + 1] += u[(size_t)r * u_ld + i] * g;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i <= kMaxU; ++i) s_red[ry][i][cx] = acc[i];
+  __syncthreads();
+  if (ry == 0 && col < N) {
+    for (int i = 0; i <= u_n; ++i) {
+      const float v = s_red[0][i][cx] + s_red[1][i][cx] + s_red[2][i][cx] + s_red[3][i][cx];
+      partial[((size_t)split * (u_n + 1) + i) * N + col] = v;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int splits, int N,
+                                                           int u_n, float* __restrict__ out_bias,
+                                                           float* __restrict__ out_u, int beta) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= N) return;
+  for (int i = 0; i <= u_n; ++i) {
+    float v = 0.f;
+    for (int s = 0; s < splits; ++s) v += partial[((size_t)s * (u_n + 1) + i) * N + col];
+    float* dst = i == 0 ? (out_bias ? out_bias + col : nullptr) : (out_u ? out_u + (size_t)(i - 1) * N + col : nullptr);
+    if (dst) *dst = beta ? *dst + v : v;
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p, uint32_t v, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+}  // namespace
+
+hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows, int classes, int dtype,
+                             void* dlogits, float* row_loss, float* loss, hipStream_t st) {
+  dim3 grid((rows + 3) / 4), block(256);
+  if (dtype == kF32)
+    hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, block, 0, st, (const float*)logits, labels, rows, classes,
+                       (float*)dlogits, row_loss);
+  else
+    hipLaunchKernelGGL(softmax_ce_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)logits, labels, rows,
+                       classes, (uint16_t*)dlogits, row_loss);
+  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, st, row_loss, rows, loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint32_t* bits, int bits_pitch,
+                         const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u, int beta,
+                         float* partial, int splits, hipStream_t st) {
+  if (u_n > kMaxU) return hipErrorInvalidValue;
+  dim3 grid((N + 63) / 64, splits), block(256);
+  if (dtype == kF32)
+    hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, block, 0, st, (const float*)dy, rows, N, bits, bits_pitch,
+                       u, u_ld, u_n, partial, splits);
+  else
+    hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)dy, rows, N, bits,
+                       bits_pitch, u, u_ld, u_n, partial, splits);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 255) / 256), dim3(256), 0, st, partial, splits, N, u_n, out_bias,
+                     out_u, beta);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
+  return hipGetLastError();
+}
+
+}  // namespace rad
