@@ -82,6 +82,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("librad_hip.so is missing: run `python -m paper_2007_10412_amd.build` "
                                "(there is no CPU fallback)")
+        # torch ships its own HIP runtime under the same soname; it must be in the
+        # process first so that this library binds to that one and not to a second copy
+        import torch  # noqa: F401
         _lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(_lib, name)

@@ -158,3 +158,20 @@ def test_unbiased_on_gpu(ctx):
         var = (1 / pi - 1) * ((x.astype(np.float64) ** 2).T @ g2).sum()
         err = np.linalg.norm(acc / S - exact)
         assert err < 4 * np.sqrt(var / S) and err > 0.1 * np.sqrt(var / S)
+
+
+@pytest.mark.parametrize("Bt,D,N", [
+    (3072, 320, 2816),     # forward on 256x256 tiles (132 of them), ragged N tail handled by the 11th column
+    (3072, 2816, 328),     # dX on 256x256 tiles
+    (328, 3072, 2816),     # dW on 256x256 tiles, K (= batch) with a ragged tail
+])
+def test_bf16_256_tiles(ctx, Bt, D, N):
+    """Shapes that reach the one-workgroup-per-CU 256x256 kernels config 4 runs on."""
+    from paper_2007_10412_amd import binding as B
+    from paper_2007_10412_amd.synth import bf16_round
+    rng = np.random.default_rng(Bt + D)
+    x = bf16_round(rng.standard_normal((Bt, D)))
+    W = bf16_round(rng.standard_normal((D, N)) / np.sqrt(D))
+    dy = bf16_round(rng.standard_normal((Bt, N)) * 0.01)
+    for scheme, p in ((3, 0.1), (1, 0.5), (3, 0.02), (2, 0.1)):
+        run_layer(ctx, x, W, None, dy, scheme, p, seed=31, dtype=B.RAD_BF16)
