@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the RAD train step on one MI355X.
+
+A step is one rad_train_step: sampling plan + pack, forward GEMMs with fused
+ReLU-bit / sample epilogues, softmax cross-entropy, dW from the compressed
+stores and the exact dX chain.  Default workload: the wide bf16 MLP
+(4096-4096-4096-1000, batch 4096) with per-example fixed-k sampling at p=0.1.
+
+Prints ONE JSON line: whole-job samples/s with inputs resident in HBM, the
+roofline of the dominant kernel (dW from the compressed store) timed with HIP
+events on the library's stream inside the timed region, and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X published
+HBM_PEAK = 8000.0                          # GB/s
+
+WORKLOADS = {
+    # name: (dtype, batch, dims, pixels, has_bias)
+    "mlp4096_bf16": ("bf16", 4096, (4096, 4096, 4096, 1000), False, False),
+    "mlp784_f32": ("f32", 150, (784, 300, 300, 10), True, True),
+}
+SCHEMES = {"per_example": 3, "shared": 2, "bernoulli": 1, "exact": 0}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS))
+    ap.add_argument("--scheme", default="per_example", choices=sorted(SCHEMES))
+    ap.add_argument("--p", type=float, default=0.1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the kernel breakdown and the pack stream")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2007_10412_amd import binding as B, synth
+
+    dtype_name, batch, dims, pixels, has_bias = WORKLOADS[args.workload]
+    dtype = B.RAD_BF16 if dtype_name == "bf16" else B.RAD_F32
+    tdt = torch.bfloat16 if dtype == B.RAD_BF16 else torch.float32
+    scheme = SCHEMES[args.scheme]
+    p = 1.0 if scheme == 0 else args.p
+    L = len(dims) - 1
+    data = synth.mlp(seed=1234, batch=batch, dims=dims, pixels=pixels, bf16=(dtype == B.RAD_BF16))
+
+    ctx = B.rad_ctx_create()
+    model = B.rad_model_create_mlp(ctx, dtype, batch, list(dims), has_bias, scheme, p)
+    params, grads = [], []
+    for l in range(L):
+        params.append(torch.from_numpy(data["Ws"][l]).cuda().to(tdt).contiguous())
+        grads.append(torch.empty(data["Ws"][l].shape, device="cuda", dtype=torch.float32))
+        if has_bias:
+            params.append(torch.from_numpy(data["bs"][l]).cuda())
+            grads.append(torch.empty(data["bs"][l].shape, device="cuda", dtype=torch.float32))
+    x = torch.from_numpy(data["x"]).cuda().to(tdt).contiguous()
+    labels = torch.from_numpy(data["labels"]).cuda()
+
+    def step(i):
+        return B.rad_train_step(ctx, model, B.make_sampling(scheme, p, 1000 + i, 0, 0), x, labels, params, grads)
+
+    for i in range(args.warmup):
+        step(i)
+    # the dominant kernel is bracketed by HIP events on the library's stream during the timed steps
+    dom = {3: "dw_sparse", 1: "dw_sparse", 2: "dw_dense", 0: "dw_dense"}[scheme]
+    dom_filter = "gemm_%s_%s" % (dtype_name, dom)
+    B.rad_ctx_timing(ctx, dom_filter)
+    B.rad_ctx_timing_reset(ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    loss = 0.0
+    for i in range(args.steps):
+        loss = step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = batch * args.steps / elapsed
+
+    # roofline of the dominant kernel: dW of the widest layers
+    big = "%s_256x256" % dom_filter if (dtype == B.RAD_BF16 and dom == "dw_sparse") else dom_filter
+    n_launch, tot_ms = B.rad_ctx_timing_read(ctx, big)
+    B.rad_ctx_timing(ctx, "")
+    D0, N0 = dims[0], dims[1]
+    k0 = B.rad_fixed_k(p, D0) if scheme in (2, 3) else p * D0
+    # launches of that kernel per step: layers whose output is as wide as the first one
+    per_step = max(1, n_launch // max(1, args.steps))
+    alg_flops = 2.0 * batch * k0 * N0
+    exe_flops = 2.0 * batch * (k0 if scheme == 2 else D0) * N0
+    avg_ms = tot_ms / max(1, n_launch)
+    peak = PEAK[dtype_name]
+    roofline = {
+        "kernel": big, "bound": "mfma", "unit": "TFLOP/s",
+        "achieved": alg_flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else None,
+        "peak": peak,
+        "frac": alg_flops / (avg_ms * 1e-3) / 1e12 / peak if avg_ms > 0 else None,
+        "executed": exe_flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else None,
+        "executed_frac": exe_flops / (avg_ms * 1e-3) / 1e12 / peak if avg_ms > 0 else None,
+        "avg_launch_ms": avg_ms, "launches": n_launch, "launches_per_step": per_step,
+        "algorithmic_flops_per_launch": alg_flops, "executed_flops_per_launch": exe_flops,
+        "traffic": None,
+    }
+
+    out = {
+        "metric": "rad_train_step_samples_per_sec", "value": value, "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype_name, "data": "synthetic",
+        "config": {"workload": "%s: MLP %s, batch %d, %s sampling p=%g, softmax-CE, full fwd+bwd train step"
+                   % (args.workload, "-".join(str(d) for d in dims), batch, args.scheme, p),
+                   "batch": batch, "dims": list(dims), "scheme": args.scheme, "p": p},
+        "loss": loss,
+        "roofline": roofline,
+    }
+
+    # stored activation bytes (values / indices+tables / ReLU bits) vs the dense baseline
+    sb = {"value_bytes": 0, "index_bytes": 0, "bit_bytes": 0, "dense_bytes": 0}
+    for l in range(L):
+        st = B.rad_store_get_stats(ctx, B.rad_model_store(model, l))
+        for k_ in sb:
+            sb[k_] += st[k_]
+    sb["stored_total"] = sb["value_bytes"] + sb["index_bytes"] + sb["bit_bytes"]
+    sb["paper_convention"] = sb["value_bytes"] + sb["bit_bytes"]
+    out["stored_activation_bytes"] = sb
+
+    if not args.no_extras:
+        # per-kernel breakdown of one step (separate pass: every launch bracketed by events)
+        B.rad_ctx_timing(ctx, None)
+        B.rad_ctx_timing_reset(ctx)
+        reps = 3
+        for i in range(reps):
+            step(10_000 + i)
+        kern = {}
+        names = ["plan", "row_scan", "pack", "fwd", "dx", "dw_sparse", "dw_dense", "softmax_ce", "colsum", "fill"]
+        for nm in names:
+            n, ms = B.rad_ctx_timing_read(ctx, nm)
+            if n:
+                kern[nm] = {"launches_per_step": n / reps, "ms_per_step": ms / reps}
+        B.rad_ctx_timing(ctx, "")
+        B.rad_ctx_timing_reset(ctx)
+        fl = {"fwd": sum(2.0 * batch * dims[l] * dims[l + 1] for l in range(L)),
+              "dx": sum(2.0 * batch * dims[l] * dims[l + 1] for l in range(1, L)),
+              "dw_sparse": sum(2.0 * batch * dims[l] * dims[l + 1] for l in range(L))}
+        for nm, f in fl.items():
+            if nm in kern and kern[nm]["ms_per_step"] > 0:
+                kern[nm]["executed_tflops"] = f / (kern[nm]["ms_per_step"] * 1e-3) / 1e12
+        out["kernels"] = kern
+        out["pack_stream"] = pack_stream(B, ctx, torch, dtype_name)
+
+    B.rad_model_destroy(model)
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(data, dims, scheme, p, dtype, batch, has_bias)
+
+    B.rad_ctx_destroy(ctx)
+    print(json.dumps(out))
+
+
+def pack_stream(B, ctx, torch, dtype_name):
+    """Sampling kernels on a >= 1 GiB stream of 4096-wide rows (Bernoulli p = 0.1, fp32): the pack kernel
+    is an HBM stream (read x and the keep bitmap, write values and indices); the plan kernel reads nothing
+    and is bound by Philox integer arithmetic."""
+    rows, cols, p = 65536, 4096, 0.1
+    L = B.make_layer(rows, cols, 8, dtype=B.RAD_F32, relu=False)
+    st = B.rad_store_create(ctx, L, B.RAD_BERNOULLI, p)
+    x = torch.randn(rows, cols, device="cuda", dtype=torch.float32)
+    B.rad_ctx_timing(ctx, None)
+    for i in range(2):
+        B.rad_sample_pack(ctx, B.make_sampling(B.RAD_BERNOULLI, p, i), x, st)
+    B.rad_ctx_timing_reset(ctx)
+    reps = 5
+    for i in range(reps):
+        B.rad_sample_pack(ctx, B.make_sampling(B.RAD_BERNOULLI, p, 10 + i), x, st)
+    n_pack, ms_pack = B.rad_ctx_timing_read(ctx, "pack")
+    n_plan, ms_plan = B.rad_ctx_timing_read(ctx, "plan")
+    B.rad_ctx_timing(ctx, "")
+    B.rad_ctx_timing_reset(ctx)
+    nnz = B.rad_store_get_stats(ctx, st)["nnz"]
+    B.rad_store_destroy(st)
+    n = rows * cols
+    pack_bytes = n * 4 + n / 8 + nnz * 6          # x + keep bitmap read, value + index written
+    plan_bytes = n / 8                            # bitmap written
+    t_pack = ms_pack / n_pack * 1e-3
+    t_plan = ms_plan / n_plan * 1e-3
+    return {"rows": rows, "cols": cols, "p": p, "dtype": "f32",
+            "pack": {"bound": "hbm", "ms": t_pack * 1e3, "achieved": pack_bytes / t_pack / 1e9, "peak": HBM_PEAK,
+                     "unit": "GB/s", "frac": pack_bytes / t_pack / 1e9 / HBM_PEAK},
+            "plan": {"bound": "alu", "ms": t_plan * 1e3, "keys_per_s": n / t_plan,
+                     "write_GBps": plan_bytes / t_plan / 1e9}}
+
+
+def cpu_baseline(data, dims, scheme, p, dtype, batch, has_bias):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import rad_oracle as R
+    rows = min(batch, 1024)
+    bs = data["bs"] if has_bias else None
+    t0 = time.perf_counter()
+    R.mlp_train_step(data["x"][:rows], data["labels"][:rows], data["Ws"], bs, scheme, p, seed=1,
+                     dtype=(R.BF16 if dtype == 1 else R.F32))
+    dt = time.perf_counter() - t0
+    cores = os.cpu_count()
+    try:
+        from threadpoolctl import threadpool_info
+        th = [i.get("num_threads") for i in threadpool_info() if i.get("user_api") == "blas"]
+        if th:
+            cores = max(th)
+    except Exception:
+        pass
+    return {"value": rows / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
+            "seconds": dt,
+            "sample": "one oracle train step (numpy fp64) on the first %d of %d rows, full layer widths" % (rows, batch)}
+
+
+if __name__ == "__main__":
+    main()

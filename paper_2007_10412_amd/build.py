@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librad_hip.so")
-SOURCES = ["api.hip", "plan.hip", "small.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_sparse.hip"]
+SOURCES = ["api.hip", "plan.hip", "small.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_fwd.hip",
+           "gemm_bf16_dx.hip", "gemm_bf16_dwd.hip", "gemm_bf16_sparse.hip"]
 # packed fp32 VALU forms are switched off: hipcc -O3 otherwise forms them on its own
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -21,8 +22,19 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src):
+def _stale(src, obj):
+    if not os.path.exists(obj):
+        return True
+    t = os.path.getmtime(obj)
+    deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    deps.append(os.path.join(HERE, "..", "include", "rad.h"))
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
+def _compile(src, force=True):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+    if not force and not _stale(src, obj):
+        return obj, ""
     cmd = [_hipcc()] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(ln for ln in r.stderr.splitlines() if "not a recognized feature" not in ln)
@@ -31,10 +43,11 @@ def _compile(src):
     return obj, err
 
 
-def build(verbose=False, jobs=6):
+def build(verbose=False, jobs=8, force=True):
+    """force=False recompiles only sources older than their object (developer loop)."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        results = list(ex.map(_compile, SOURCES))
+        results = list(ex.map(lambda s: _compile(s, force), SOURCES))
     if verbose:
         for _, err in results:
             if err.strip():
@@ -48,4 +61,4 @@ def build(verbose=False, jobs=6):
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, force="--incremental" not in sys.argv))

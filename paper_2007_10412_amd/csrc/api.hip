@@ -71,8 +71,10 @@ static rad_status ws_get(rad_ctx* c, int which, size_t bytes, void** out) {
 // runs `launch` (which enqueues exactly one logical kernel and reports its
 // label through *name), bracketed by events when timing is on
 template <class F>
-static hipError_t timed(rad_ctx* c, const char* fixed_name, F launch) {
-  if (!c->timing) { const char* nm = fixed_name; return launch(&nm); }
+static hipError_t timed(rad_ctx* c, const char* name, F launch) {
+  const char* nm = name;
+  if (!c->timing || (!c->filter.empty() && std::string(name).find(c->filter) == std::string::npos))
+    return launch(&nm);
   hipEvent_t a, b;
   for (hipEvent_t* ev : {&a, &b}) {
     if (!c->pool.empty()) { *ev = c->pool.back(); c->pool.pop_back(); }
@@ -80,13 +82,11 @@ static hipError_t timed(rad_ctx* c, const char* fixed_name, F launch) {
   }
   hipError_t e = hipEventRecord(a, c->stream);
   if (e != hipSuccess) return e;
-  const char* nm = fixed_name;
   e = launch(&nm);
   if (e != hipSuccess) return e;
   e = hipEventRecord(b, c->stream);
   if (e != hipSuccess) return e;
-  if (c->filter.empty() || std::string(nm).find(c->filter) != std::string::npos) c->recs.push_back({nm, a, b});
-  else { c->pool.push_back(a); c->pool.push_back(b); }
+  c->recs.push_back({nm, a, b});
   return hipSuccess;
 }
 
@@ -451,7 +451,12 @@ static bool layer_matches(const rad_layer* L, const rad_store* s) {
 static GemmArgs gemm_zero() { GemmArgs g; std::memset(&g, 0, sizeof(g)); return g; }
 
 static rad_status run_gemm_call(rad_ctx* c, int dtype, int ak, int bk, int epi, const GemmArgs& g) {
-  hipError_t e = timed(c, "gemm", [&](const char** nm) { return launch_gemm(dtype, ak, bk, epi, g, c->stream, nm); });
+  const char* label = "gemm";
+  if (c->timing) {              // the label decides whether this launch is bracketed by events
+    GemmArgs probe = g; probe.dry_run = 1;
+    if (launch_gemm(dtype, ak, bk, epi, probe, c->stream, &label) != hipSuccess) label = "gemm";
+  }
+  hipError_t e = timed(c, label, [&](const char** nm) { return launch_gemm(dtype, ak, bk, epi, g, c->stream, nm); });
   if (e == hipErrorInvalidValue) return fail(c, RAD_ERR_UNSUPPORTED, "no GEMM kernel for this operand combination");
   if (e != hipSuccess) return hip_fail(c, e, "gemm launch");
   return RAD_OK;

@@ -47,36 +47,48 @@ __device__ __forceinline__ uint32_t mask_bits(const uint32_t* mask, int pitch, i
   return mask[(size_t)outer * pitch + (inner >> 5)] >> (inner & 31);
 }
 
+// Loaders move one operand tile global -> registers (fetch) -> LDS (commit).
+// EDGE = false is the interior variant: the host launches it only when every
+// tile is full and every row 16-byte aligned, so it carries no predicates.
+// Offsets are 32-bit element offsets from the operand base (operands are
+// limited to 2^31 elements by the host).
+
 // =========================================================== fp32 loaders
 // dense, K contiguous: element (row, k) at p[row*ld + k]
-template <int R, int BK> struct F32LoadK {
+template <int R, int BK, bool EDGE, bool MASKED> struct F32LoadK {
   static constexpr int TOTAL = R * BK / 4;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
   typedef LdsF32<R, BK> L;
   floatx4 v[NCH];
+  const float* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
+  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
+                                       int rmax_, int K_, const StoreView&) {
+    p = static_cast<const float*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
+  }
   __device__ __forceinline__ void bounds(int) {}
-  __device__ __forceinline__ void fetch(const float* p, int64_t ld, const uint32_t* mask, int mp,
-                                        int r0, int k0, int rmax, int K) {
+  __device__ __forceinline__ void fetch(int k0) {
     const bool vec = (ld & 3) == 0;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
       floatx4 t = {0.f, 0.f, 0.f, 0.f};
-      if (c < TOTAL) {
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
         const int row = c / (BK / 4), k4 = c % (BK / 4);
         const int gr = r0 + row, gk = k0 + k4 * 4;
-        if (gr < rmax && gk < K) {
-          const float* src = p + (size_t)gr * ld + gk;
+        const float* src = p + ((uint32_t)gr * ld + (uint32_t)gk);
+        if (!EDGE) {
+          t = *reinterpret_cast<const floatx4*>(src);
+        } else if (gr < rmax && gk < K) {
           if (vec && gk + 3 < K) t = *reinterpret_cast<const floatx4*>(src);
           else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) if (gk + e < K) t[e] = src[e];
           }
-          if (mask) {
-            const uint32_t mb = mask_bits(mask, mp, gr, gk);
+        }
+        if (MASKED && (!EDGE || (gr < rmax && gk < K))) {
+          const uint32_t mb = mask_bits(mask, mp, gr, gk);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) if (!((mb >> e) & 1u)) t[e] = 0.f;
-          }
+          for (int e = 0; e < 4; ++e) if (!((mb >> e) & 1u)) t[e] = 0.f;
         }
       }
       v[i] = t;
@@ -86,7 +98,7 @@ template <int R, int BK> struct F32LoadK {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
-      if (c < TOTAL) {
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
         const int row = c / (BK / 4), k4 = c % (BK / 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) lds[L::at(row, k4 * 4 + e)] = v[i][e];
@@ -96,34 +108,40 @@ template <int R, int BK> struct F32LoadK {
 };
 
 // dense, M/N contiguous: element (row, k) at p[k*ld + row]
-template <int R, int BK> struct F32LoadMN {
+template <int R, int BK, bool EDGE, bool MASKED> struct F32LoadMN {
   static constexpr int TOTAL = R * BK / 4;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
   typedef LdsF32<R, BK> L;
   floatx4 v[NCH];
+  const float* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
+  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
+                                       int rmax_, int K_, const StoreView&) {
+    p = static_cast<const float*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
+  }
   __device__ __forceinline__ void bounds(int) {}
-  __device__ __forceinline__ void fetch(const float* p, int64_t ld, const uint32_t* mask, int mp,
-                                        int r0, int k0, int rmax, int K) {
+  __device__ __forceinline__ void fetch(int k0) {
     const bool vec = (ld & 3) == 0;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
       floatx4 t = {0.f, 0.f, 0.f, 0.f};
-      if (c < TOTAL) {
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
         const int k = c / (R / 4), m4 = c % (R / 4);
         const int gk = k0 + k, gr = r0 + m4 * 4;
-        if (gk < K && gr < rmax) {
-          const float* src = p + (size_t)gk * ld + gr;
+        const float* src = p + ((uint32_t)gk * ld + (uint32_t)gr);
+        if (!EDGE) {
+          t = *reinterpret_cast<const floatx4*>(src);
+        } else if (gk < K && gr < rmax) {
           if (vec && gr + 3 < rmax) t = *reinterpret_cast<const floatx4*>(src);
           else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) if (gr + e < rmax) t[e] = src[e];
           }
-          if (mask) {
-            const uint32_t mb = mask_bits(mask, mp, gk, gr);
+        }
+        if (MASKED && (!EDGE || (gk < K && gr < rmax))) {
+          const uint32_t mb = mask_bits(mask, mp, gk, gr);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) if (!((mb >> e) & 1u)) t[e] = 0.f;
-          }
+          for (int e = 0; e < 4; ++e) if (!((mb >> e) & 1u)) t[e] = 0.f;
         }
       }
       v[i] = t;
@@ -133,7 +151,7 @@ template <int R, int BK> struct F32LoadMN {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
-      if (c < TOTAL) {
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
         const int k = c / (R / 4), m4 = c % (R / 4);
         *reinterpret_cast<floatx4*>(&lds[L::at(m4 * 4, k)]) = v[i];
       }
@@ -142,11 +160,12 @@ template <int R, int BK> struct F32LoadMN {
 };
 
 // Segment of a store row that falls into one 256-column bucket.
-__device__ __forceinline__ void store_segment(const StoreView& s, int row, int bucket, int64_t* beg, int64_t* end) {
+__device__ __forceinline__ void store_segment(const StoreView& s, int row, int bucket, uint32_t* beg, uint32_t* end) {
   const uint16_t* bo = s.bucket_off + (size_t)(row * s.plan_row_stride) * (s.nb + 1) + bucket;
-  const int64_t base = s.row_ptr[row];
-  int64_t b = base + bo[0], e = base + bo[1];
-  if (e > s.capacity) e = s.capacity;       // an overflowed Bernoulli draw never reads past the arrays
+  const uint32_t base = s.row_ptr[row];
+  uint32_t b = base + bo[0], e = base + bo[1];
+  const uint32_t cap = (uint32_t)s.capacity;     // an overflowed Bernoulli draw never reads past the arrays
+  if (e > cap) e = cap;
   if (b > e) b = e;
   *beg = b; *end = e;
 }
@@ -160,25 +179,28 @@ template <int R, int BK, int SE> struct F32LoadSparse {
   static constexpr int RPW = BK / 4;            // k rows per wave
   static constexpr int LPR = 64 / RPW;          // lanes per k row
   float val[SE]; int col[SE];
-  int64_t beg, end, nbeg, nend;
-  __device__ __forceinline__ void bounds(const StoreView& s, int m0, int k0, int K) {
+  uint32_t beg, end, nbeg, nend;
+  StoreView s; int m0, K;
+  __device__ __forceinline__ void init(const void*, int64_t, const uint32_t*, int, int r0_, int, int K_,
+                                       const StoreView& sv) { s = sv; m0 = r0_; K = K_; }
+  __device__ __forceinline__ void bounds(int k0) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int b = k0 + w * RPW + lane / LPR;
     nbeg = nend = 0;
     if (b < K) store_segment(s, b, m0 / kBucket, &nbeg, &nend);
   }
-  __device__ __forceinline__ void fetch(const StoreView& s, int m0) {
+  __device__ __forceinline__ void fetch(int) {
     const int sub = (threadIdx.x & 63) % LPR;
     beg = nbeg; end = nend;
     const float* vals = reinterpret_cast<const float*>(s.values);
 #pragma unroll
     for (int i = 0; i < SE; ++i) {
-      const int64_t e = beg + sub + i * LPR;
+      const uint32_t e = beg + sub + i * LPR;
       col[i] = -1; val[i] = 0.f;
       if (e < end) { col[i] = (int)s.indices[e] - m0; val[i] = vals[e]; }
     }
   }
-  __device__ __forceinline__ void commit(float* lds, const StoreView& s, int m0) {
+  __device__ __forceinline__ void commit(float* lds) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const floatx4 z = {0.f, 0.f, 0.f, 0.f};
     for (int c = lane; c < RPW * (L::P / 4); c += 64)
@@ -188,7 +210,7 @@ template <int R, int BK, int SE> struct F32LoadSparse {
     for (int i = 0; i < SE; ++i)
       if (col[i] >= 0 && col[i] < R) lds[L::at(col[i], kr)] = val[i];
     const float* vals = reinterpret_cast<const float*>(s.values);
-    for (int64_t e = beg + sub + (int64_t)SE * LPR; e < end; e += LPR) {
+    for (uint32_t e = beg + sub + SE * LPR; e < end; e += LPR) {
       const int c = (int)s.indices[e] - m0;
       if (c >= 0 && c < R) lds[L::at(c, kr)] = vals[e];
     }
@@ -196,40 +218,47 @@ template <int R, int BK, int SE> struct F32LoadSparse {
 };
 
 // =========================================================== bf16 loaders
+__device__ __forceinline__ void mask_bf16x8(u32x4& t, uint32_t mb) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const uint32_t keep = ((mb >> (2 * e)) & 1u ? 0x0000FFFFu : 0u) | ((mb >> (2 * e + 1)) & 1u ? 0xFFFF0000u : 0u);
+    t[e] &= keep;
+  }
+}
+
 // dense, K contiguous
-template <int R, int BK> struct BF16LoadK {
+template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadK {
   typedef LdsBF16<R, BK> L;
   static constexpr int TOTAL = R * L::CH;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
   u32x4 v[NCH];
+  const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
+  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
+                                       int rmax_, int K_, const StoreView&) {
+    p = static_cast<const uint16_t*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
+  }
   __device__ __forceinline__ void bounds(int) {}
-  __device__ __forceinline__ void fetch(const uint16_t* p, int64_t ld, const uint32_t* mask, int mp,
-                                        int r0, int k0, int rmax, int K) {
+  __device__ __forceinline__ void fetch(int k0) {
     const bool vec = (ld & 7) == 0;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
       u32x4 t = {0u, 0u, 0u, 0u};
-      if (c < TOTAL) {
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
         const int row = c / L::CH, kc = c % L::CH;
         const int gr = r0 + row, gk = k0 + kc * 8;
-        if (gr < rmax && gk < K) {
-          const uint16_t* src = p + (size_t)gr * ld + gk;
+        const uint16_t* src = p + ((uint32_t)gr * ld + (uint32_t)gk);
+        if (!EDGE) {
+          t = *reinterpret_cast<const u32x4*>(src);
+        } else if (gr < rmax && gk < K) {
           if (vec && gk + 7 < K) t = *reinterpret_cast<const u32x4*>(src);
           else {
             uint16_t* te = reinterpret_cast<uint16_t*>(&t);
 #pragma unroll
             for (int e = 0; e < 8; ++e) if (gk + e < K) te[e] = src[e];
           }
-          if (mask) {
-            const uint32_t mb = mask_bits(mask, mp, gr, gk);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              uint32_t keep = ((mb >> (2 * e)) & 1u ? 0x0000FFFFu : 0u) | ((mb >> (2 * e + 1)) & 1u ? 0xFFFF0000u : 0u);
-              t[e] &= keep;
-            }
-          }
         }
+        if (MASKED && (!EDGE || (gr < rmax && gk < K))) mask_bf16x8(t, mask_bits(mask, mp, gr, gk));
       }
       v[i] = t;
     }
@@ -238,7 +267,7 @@ template <int R, int BK> struct BF16LoadK {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
-      if (c < TOTAL) {
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
         const int row = c / L::CH, kc = c % L::CH;
         *reinterpret_cast<u32x4*>(&lds[L::unit(row, kc) * 8]) = v[i];
       }
@@ -248,15 +277,19 @@ template <int R, int BK> struct BF16LoadK {
 
 // dense, M/N contiguous: an 8(k) x 8(row) block per thread is transposed in
 // registers so that LDS receives 16-byte units of 8 consecutive k.
-template <int R, int BK> struct BF16LoadMN {
+template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadMN {
   typedef LdsBF16<R, BK> L;
   static constexpr int RB = R / 8, KB = BK / 8;
   static constexpr int TOTAL = RB * KB;
   static constexpr int NBL = (TOTAL + kGemmThreads - 1) / kGemmThreads;
   u32x4 v[NBL][8];                               // v[.][kk] = 8 consecutive rows at k = kb*8+kk
+  const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
+  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
+                                       int rmax_, int K_, const StoreView&) {
+    p = static_cast<const uint16_t*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
+  }
   __device__ __forceinline__ void bounds(int) {}
-  __device__ __forceinline__ void fetch(const uint16_t* p, int64_t ld, const uint32_t* mask, int mp,
-                                        int r0, int k0, int rmax, int K) {
+  __device__ __forceinline__ void fetch(int k0) {
     const bool vec = (ld & 7) == 0;
 #pragma unroll
     for (int i = 0; i < NBL; ++i) {
@@ -267,22 +300,19 @@ template <int R, int BK> struct BF16LoadMN {
       for (int kk = 0; kk < 8; ++kk) {
         u32x4 t = {0u, 0u, 0u, 0u};
         const int gk = k0 + kb * 8 + kk;
-        if (blk < TOTAL && gk < K && gr < rmax) {
-          const uint16_t* src = p + (size_t)gk * ld + gr;
-          if (vec && gr + 7 < rmax) t = *reinterpret_cast<const u32x4*>(src);
-          else {
-            uint16_t* te = reinterpret_cast<uint16_t*>(&t);
+        if (TOTAL % kGemmThreads == 0 || blk < TOTAL) {
+          const uint16_t* src = p + ((uint32_t)gk * ld + (uint32_t)gr);
+          if (!EDGE) {
+            t = *reinterpret_cast<const u32x4*>(src);
+          } else if (gk < K && gr < rmax) {
+            if (vec && gr + 7 < rmax) t = *reinterpret_cast<const u32x4*>(src);
+            else {
+              uint16_t* te = reinterpret_cast<uint16_t*>(&t);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) if (gr + e < rmax) te[e] = src[e];
-          }
-          if (mask) {
-            const uint32_t mb = mask_bits(mask, mp, gk, gr);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              uint32_t keep = ((mb >> (2 * e)) & 1u ? 0x0000FFFFu : 0u) | ((mb >> (2 * e + 1)) & 1u ? 0xFFFF0000u : 0u);
-              t[e] &= keep;
+              for (int e = 0; e < 8; ++e) if (gr + e < rmax) te[e] = src[e];
             }
           }
+          if (MASKED && (!EDGE || (gk < K && gr < rmax))) mask_bf16x8(t, mask_bits(mask, mp, gk, gr));
         }
         v[i][kk] = t;
       }
@@ -292,7 +322,7 @@ template <int R, int BK> struct BF16LoadMN {
 #pragma unroll
     for (int i = 0; i < NBL; ++i) {
       const int blk = threadIdx.x + i * kGemmThreads;
-      if (blk < TOTAL) {
+      if (TOTAL % kGemmThreads == 0 || blk < TOTAL) {
         const int rb = blk % RB, kb = blk / RB;
         // dword d of v[kk] holds rows 2d (low half) and 2d+1 (high half) at k = kk
 #pragma unroll
@@ -320,20 +350,23 @@ template <int R, int BK, int SE> struct BF16LoadSparse {
   static constexpr int LPR = 64 / RPW;          // lanes per store row
   static constexpr int UPW = RPW / 8;           // 16-byte units per tile row owned by a wave
   uint32_t ent[SE];                              // (value bits << 16) | (column - m0), 0xFFFF = none
-  int64_t beg, end, nbeg, nend;
-  __device__ __forceinline__ void bounds(const StoreView& s, int m0, int k0, int K) {
+  uint32_t beg, end, nbeg, nend;
+  StoreView s; int m0, K;
+  __device__ __forceinline__ void init(const void*, int64_t, const uint32_t*, int, int r0_, int, int K_,
+                                       const StoreView& sv) { s = sv; m0 = r0_; K = K_; }
+  __device__ __forceinline__ void bounds(int k0) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int b = k0 + w * RPW + lane / LPR;
     nbeg = nend = 0;
     if (b < K) store_segment(s, b, m0 / kBucket, &nbeg, &nend);
   }
-  __device__ __forceinline__ void fetch(const StoreView& s, int m0) {
+  __device__ __forceinline__ void fetch(int) {
     const int sub = (threadIdx.x & 63) % LPR;
     beg = nbeg; end = nend;
     const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
 #pragma unroll
     for (int i = 0; i < SE; ++i) {
-      const int64_t e = beg + sub + i * LPR;
+      const uint32_t e = beg + sub + i * LPR;
       ent[i] = 0xFFFFu;
       if (e < end) {
         const int c = (int)s.indices[e] - m0;
@@ -341,9 +374,10 @@ template <int R, int BK, int SE> struct BF16LoadSparse {
       }
     }
   }
-  __device__ __forceinline__ void commit(uint16_t* lds, const StoreView& s, int m0) {
+  __device__ __forceinline__ void commit(uint16_t* lds) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
     for (int c = lane; c < R * UPW; c += 64) {
       const int row = c / UPW, u = c % UPW;
       *reinterpret_cast<u32x4*>(&lds[L::unit(row, w * UPW + u) * 8]) = z;
@@ -355,7 +389,7 @@ template <int R, int BK, int SE> struct BF16LoadSparse {
       if (c != 0xFFFFu) lds[L::unit((int)c, kr >> 3) * 8 + (kr & 7)] = (uint16_t)(ent[i] >> 16);
     }
     const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
-    for (int64_t e = beg + sub + (int64_t)SE * LPR; e < end; e += LPR) {
+    for (uint32_t e = beg + sub + SE * LPR; e < end; e += LPR) {
       const int c = (int)s.indices[e] - m0;
       if (c >= 0 && c < R) lds[L::unit(c, kr >> 3) * 8 + (kr & 7)] = vals[e];
     }
@@ -363,63 +397,82 @@ template <int R, int BK, int SE> struct BF16LoadSparse {
 };
 
 // ================================================================ operands
-template <class DT, int KIND, int R, int BK, int SE> struct LoaderOf;
-template <int R, int BK, int SE> struct LoaderOf<F32Tag, kOpK, R, BK, SE> { typedef F32LoadK<R, BK> type; };
-template <int R, int BK, int SE> struct LoaderOf<F32Tag, kOpMN, R, BK, SE> { typedef F32LoadMN<R, BK> type; };
-template <int R, int BK, int SE> struct LoaderOf<F32Tag, kOpSparse, R, BK, SE> { typedef F32LoadSparse<R, BK, SE> type; };
-template <int R, int BK, int SE> struct LoaderOf<BF16Tag, kOpK, R, BK, SE> { typedef BF16LoadK<R, BK> type; };
-template <int R, int BK, int SE> struct LoaderOf<BF16Tag, kOpMN, R, BK, SE> { typedef BF16LoadMN<R, BK> type; };
-template <int R, int BK, int SE> struct LoaderOf<BF16Tag, kOpSparse, R, BK, SE> { typedef BF16LoadSparse<R, BK, SE> type; };
+template <class DT, int KIND, int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf;
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpK, R, BK, SE, EDGE, MASKED> { typedef F32LoadK<R, BK, EDGE, MASKED> type; };
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpMN, R, BK, SE, EDGE, MASKED> { typedef F32LoadMN<R, BK, EDGE, MASKED> type; };
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpSparse, R, BK, SE, EDGE, MASKED> { typedef F32LoadSparse<R, BK, SE> type; };
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<BF16Tag, kOpK, R, BK, SE, EDGE, MASKED> { typedef BF16LoadK<R, BK, EDGE, MASKED> type; };
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<BF16Tag, kOpMN, R, BK, SE, EDGE, MASKED> { typedef BF16LoadMN<R, BK, EDGE, MASKED> type; };
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<BF16Tag, kOpSparse, R, BK, SE, EDGE, MASKED> { typedef BF16LoadSparse<R, BK, SE> type; };
 
 template <class DT, int R, int BK> struct LdsOf;
 template <int R, int BK> struct LdsOf<F32Tag, R, BK> { typedef LdsF32<R, BK> type; };
 template <int R, int BK> struct LdsOf<BF16Tag, R, BK> { typedef LdsBF16<R, BK> type; };
 
 // ============================================================== MFMA core
+// Fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run
+// (two fragment sets), since one wave per SIMD has nobody else to hide the
+// LDS latency behind.
 template <class DT, int BM, int BN, int BK> struct Mma;
 
 template <int BM, int BN, int BK> struct Mma<F32Tag, BM, BN, BK> {
-  static constexpr int TM = BM / 64, TN = BN / 64;
+  static constexpr int TM = BM / 64, TN = BN / 64, KS = BK / 2;
   typedef LdsF32<BM, BK> LA; typedef LdsF32<BN, BK> LB;
   static __device__ __forceinline__ void run(const float* As, const float* Bs, floatx16 (&acc)[TM][TN],
                                              int wm0, int wn0) {
     const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+    float a[2][TM], b[2][TN];
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
-      float a[TM], b[TN];
+    for (int i = 0; i < TM; ++i) a[0][i] = As[LA::at(wm0 + i * 32 + lr, lk)];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[i] = As[LA::at(wm0 + i * 32 + lr, kk + lk)];
+    for (int j = 0; j < TN; ++j) b[0][j] = Bs[LB::at(wn0 + j * 32 + lr, lk)];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[j] = Bs[LB::at(wn0 + j * 32 + lr, kk + lk)];
+    for (int s = 0; s < KS; ++s) {
+      const int c = s & 1, n = c ^ 1;
+      if (s + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[n][i] = As[LA::at(wm0 + i * 32 + lr, (s + 1) * 2 + lk)];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[n][j] = Bs[LB::at(wn0 + j * 32 + lr, (s + 1) * 2 + lk)];
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
     }
   }
 };
 
 template <int BM, int BN, int BK> struct Mma<BF16Tag, BM, BN, BK> {
-  static constexpr int TM = BM / 64, TN = BN / 64;
+  static constexpr int TM = BM / 64, TN = BN / 64, KS = BK / 16;
   typedef LdsBF16<BM, BK> LA; typedef LdsBF16<BN, BK> LB;
   static __device__ __forceinline__ void run(const uint16_t* As, const uint16_t* Bs, floatx16 (&acc)[TM][TN],
                                              int wm0, int wn0) {
     const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+    bf16x8 a[2][TM], b[2][TN];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 a[TM], b[TN];
+    for (int i = 0; i < TM; ++i)
+      a[0][i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, lk) * 8]);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        a[i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, kk * 2 + lk) * 8]);
+    for (int j = 0; j < TN; ++j)
+      b[0][j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, lk) * 8]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        b[j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, kk * 2 + lk) * 8]);
+    for (int s = 0; s < KS; ++s) {
+      const int c = s & 1, n = c ^ 1;
+      if (s + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          a[n][i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, (s + 1) * 2 + lk) * 8]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          b[n][j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, (s + 1) * 2 + lk) * 8]);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
     }
   }
 };
@@ -545,12 +598,23 @@ struct GemmSmem {
   static constexpr int BYTES = (EPI == kEpiFwd && CT > MAIN) ? CT : MAIN;
 };
 
-template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE>
+// Pipeline of one K slice (registers always hold the slice after the one in
+// LDS): write slice kt+1 from registers into the idle LDS stage, start the
+// global loads of slice kt+2 into the same registers, run the MFMAs of slice
+// kt from the other stage, barrier.  Global latency is hidden behind a whole
+// slice of MFMAs, LDS writes overlap them as well.
+// FLAGS: kFlagEdge = guarded loads for ragged shapes, kFlagMaskA / kFlagMaskB =
+// the dense A / B operand is masked by stored ReLU bits.  Compile-time, so the
+// K loop stays one basic block the scheduler can interleave.
+constexpr int kFlagEdge = 1, kFlagMaskA = 2, kFlagMaskB = 4;
+
+template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE, int FLAGS>
 __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
+  constexpr bool EDGE = (FLAGS & kFlagEdge) != 0;
   typedef typename ElemOf<DT>::type ElemT;
   typedef GemmSmem<DT, AK, BKIND, EPI, BM, BN, BK, SE> S;
-  typedef typename LoaderOf<DT, AK, BM, BK, SE>::type LoadA;
-  typedef typename LoaderOf<DT, BKIND, BN, BK, SE>::type LoadB;
+  typedef typename LoaderOf<DT, AK, BM, BK, SE, EDGE, (FLAGS & kFlagMaskA) != 0>::type LoadA;
+  typedef typename LoaderOf<DT, BKIND, BN, BK, SE, EDGE, (FLAGS & kFlagMaskB) != 0>::type LoadB;
   constexpr int TM = BM / 64, TN = BN / 64;
   extern __shared__ __align__(16) unsigned char smem_raw[];
 
@@ -562,11 +626,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
   const int w = threadIdx.x >> 6;
   const int wm0 = (w >> 1) * (BM / 2), wn0 = (w & 1) * (BN / 2);
 
-  ElemT* stage[2][2];
-  stage[0][0] = reinterpret_cast<ElemT*>(smem_raw);
-  stage[0][1] = reinterpret_cast<ElemT*>(smem_raw + S::LA::BYTES);
-  stage[1][0] = reinterpret_cast<ElemT*>(smem_raw + S::STAGE);
-  stage[1][1] = reinterpret_cast<ElemT*>(smem_raw + S::STAGE + S::LA::BYTES);
+  // LDS is addressed as offsets from the one dynamic-LDS symbol so that every
+  // access stays in the LDS address space (ds_* instructions, own wait counter)
+  ElemT* const smem = reinterpret_cast<ElemT*>(smem_raw);
+  constexpr int kStageElems = S::STAGE / (int)sizeof(ElemT);
+  constexpr int kAElems = S::LA::BYTES / (int)sizeof(ElemT);
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -577,43 +641,37 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   LoadA la; LoadB lb;
-  const ElemT* Ap = reinterpret_cast<const ElemT*>(g.A);
-  const ElemT* Bp = reinterpret_cast<const ElemT*>(g.B);
+  la.init(g.A, g.lda, g.a_mask, g.a_mask_pitch, m0, g.M, g.K, g.sa);
+  lb.init(g.B, g.ldb, g.b_mask, g.b_mask_pitch, n0, g.N, g.K, g.sa);
   const int KT = (g.K + BK - 1) / BK;
 
-  auto fetchA = [&](int kt) {
-    if constexpr (AK == kOpSparse) la.fetch(g.sa, m0);
-    else la.fetch(Ap, g.lda, g.a_mask, g.a_mask_pitch, m0, kt * BK, g.M, g.K);
-  };
-  auto boundsA = [&](int kt) {
-    if constexpr (AK == kOpSparse) la.bounds(g.sa, m0, kt * BK, g.K);
-  };
-  auto commitA = [&](ElemT* lds) {
-    if constexpr (AK == kOpSparse) la.commit(lds, g.sa, m0);
-    else la.commit(lds);
-  };
-
   if (KT > 0) {
-    boundsA(0);
-    fetchA(0);
-    if (KT > 1) boundsA(1);
-    lb.fetch(Bp, g.ldb, g.b_mask, g.b_mask_pitch, n0, 0, g.N, g.K);
-    commitA(stage[0][0]);
-    lb.commit(stage[0][1]);
+    la.bounds(0);
+    la.fetch(0);
+    lb.fetch(0);
+    if (KT > 1) la.bounds(BK);
+    la.commit(smem);
+    lb.commit(smem + kAElems);
+    if (KT > 1) {
+      la.fetch(BK);
+      lb.fetch(BK);
+      if (KT > 2) la.bounds(2 * BK);
+    }
   }
   __syncthreads();
   for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1, nxt = cur ^ 1;
+    ElemT* const cur = smem + (kt & 1) * kStageElems;
+    ElemT* const nxt = smem + ((kt & 1) ^ 1) * kStageElems;
     if (kt + 1 < KT) {
-      fetchA(kt + 1);                       // uses the bounds loaded one iteration earlier
-      if (kt + 2 < KT) boundsA(kt + 2);
-      lb.fetch(Bp, g.ldb, g.b_mask, g.b_mask_pitch, n0, (kt + 1) * BK, g.N, g.K);
+      la.commit(nxt);
+      lb.commit(nxt + kAElems);
     }
-    Mma<DT, BM, BN, BK>::run(stage[cur][0], stage[cur][1], acc, wm0, wn0);
-    if (kt + 1 < KT) {
-      commitA(stage[nxt][0]);
-      lb.commit(stage[nxt][1]);
+    if (kt + 2 < KT) {
+      la.fetch((kt + 2) * BK);
+      lb.fetch((kt + 2) * BK);
+      if (kt + 3 < KT) la.bounds((kt + 3) * BK);
     }
+    Mma<DT, BM, BN, BK>::run(cur, cur + kAElems, acc, wm0, wn0);
     __syncthreads();
   }
 
@@ -621,7 +679,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
     if (g.c_dtype == kF32) epilogue_store<TM, TN, float>(g, acc, m0, n0, wm0, wn0);
     else epilogue_store<TM, TN, uint16_t>(g, acc, m0, n0, wm0, wn0);
   } else {
-    epilogue_fwd<ElemT, BM, BN, TM, TN>(g, acc, reinterpret_cast<ElemT*>(smem_raw), m0, n0, wm0, wn0);
+    epilogue_fwd<ElemT, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
   }
 }
 

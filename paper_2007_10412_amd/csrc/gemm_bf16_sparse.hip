@@ -12,14 +12,14 @@ hipError_t launch_gemm_bf16_sparse(const GemmArgs& g, hipStream_t st, const char
   const int se = g.sparse_prefetch;
   if (big) {
     nm = "gemm_bf16_dw_sparse_256x256";
-    if (se <= 4) e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 256, 64, 4>(g, st);
-    else if (se <= 12) e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 256, 64, 12>(g, st);
-    else e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 256, 64, 40>(g, st);
+    if (se <= 4) e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 256, 64, 4, false, true>(g, st);
+    else if (se <= 12) e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 256, 64, 12, false, true>(g, st);
+    else e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 256, 64, 40, false, true>(g, st);
   } else {
     nm = "gemm_bf16_dw_sparse_256x128";
-    if (se <= 4) e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 128, 64, 4>(g, st);
-    else if (se <= 12) e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 128, 64, 12>(g, st);
-    else e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 128, 64, 40>(g, st);
+    if (se <= 4) e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 128, 64, 4, false, true, false>(g, st);
+    else if (se <= 12) e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 128, 64, 12, false, true, false>(g, st);
+    else e = run_gemm<BF16Tag, kOpSparse, kOpMN, kEpiStore, 256, 128, 64, 40, false, true, false>(g, st);
   }
   if (name) *name = nm;
   return e;

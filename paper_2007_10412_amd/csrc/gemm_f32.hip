@@ -9,22 +9,22 @@ hipError_t launch_gemm_f32(int a_kind, int b_kind, int epi, const GemmArgs& g, h
   // 128x128 tiles once they alone fill the chip, 64x64 otherwise
   const bool big = tiles_of(g, 128, 128) >= 192;
   if (a_kind == kOpK && b_kind == kOpMN && epi == kEpiFwd) {
-    if (big) { nm = "gemm_f32_fwd_128"; e = run_gemm<F32Tag, kOpK, kOpMN, kEpiFwd, 128, 128, 16, 0>(g, st); }
-    else { nm = "gemm_f32_fwd_64"; e = run_gemm<F32Tag, kOpK, kOpMN, kEpiFwd, 64, 64, 16, 0>(g, st); }
+    if (big) { nm = "gemm_f32_fwd_128"; e = run_gemm<F32Tag, kOpK, kOpMN, kEpiFwd, 128, 128, 16, 0, false, false>(g, st); }
+    else { nm = "gemm_f32_fwd_64"; e = run_gemm<F32Tag, kOpK, kOpMN, kEpiFwd, 64, 64, 16, 0, false, false>(g, st); }
   } else if (a_kind == kOpK && b_kind == kOpK && epi == kEpiStore) {
-    if (big) { nm = "gemm_f32_dx_128"; e = run_gemm<F32Tag, kOpK, kOpK, kEpiStore, 128, 128, 16, 0>(g, st); }
-    else { nm = "gemm_f32_dx_64"; e = run_gemm<F32Tag, kOpK, kOpK, kEpiStore, 64, 64, 16, 0>(g, st); }
+    if (big) { nm = "gemm_f32_dx_128"; e = run_gemm<F32Tag, kOpK, kOpK, kEpiStore, 128, 128, 16, 0, true, false>(g, st); }
+    else { nm = "gemm_f32_dx_64"; e = run_gemm<F32Tag, kOpK, kOpK, kEpiStore, 64, 64, 16, 0, true, false>(g, st); }
   } else if (a_kind == kOpMN && b_kind == kOpMN && epi == kEpiStore) {
-    if (big) { nm = "gemm_f32_dw_dense_128"; e = run_gemm<F32Tag, kOpMN, kOpMN, kEpiStore, 128, 128, 16, 0>(g, st); }
-    else { nm = "gemm_f32_dw_dense_64"; e = run_gemm<F32Tag, kOpMN, kOpMN, kEpiStore, 64, 64, 16, 0>(g, st); }
+    if (big) { nm = "gemm_f32_dw_dense_128"; e = run_gemm<F32Tag, kOpMN, kOpMN, kEpiStore, 128, 128, 16, 0, false, true>(g, st); }
+    else { nm = "gemm_f32_dw_dense_64"; e = run_gemm<F32Tag, kOpMN, kOpMN, kEpiStore, 64, 64, 16, 0, false, true>(g, st); }
   } else if (a_kind == kOpSparse && b_kind == kOpMN && epi == kEpiStore) {
     const bool wide = g.sparse_prefetch > 4;
     if (big) {
-      if (wide) { nm = "gemm_f32_dw_sparse_128"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 128, 128, 16, 16>(g, st); }
-      else { nm = "gemm_f32_dw_sparse_128"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 128, 128, 16, 4>(g, st); }
+      if (wide) { nm = "gemm_f32_dw_sparse_128"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 128, 128, 16, 16, false, true, false>(g, st); }
+      else { nm = "gemm_f32_dw_sparse_128"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 128, 128, 16, 4, false, true, false>(g, st); }
     } else {
-      if (wide) { nm = "gemm_f32_dw_sparse_64"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 64, 64, 16, 16>(g, st); }
-      else { nm = "gemm_f32_dw_sparse_64"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 64, 64, 16, 4>(g, st); }
+      if (wide) { nm = "gemm_f32_dw_sparse_64"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 64, 64, 16, 16, false, true, false>(g, st); }
+      else { nm = "gemm_f32_dw_sparse_64"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 64, 64, 16, 4, false, true, false>(g, st); }
     }
   }
   if (name) *name = nm;

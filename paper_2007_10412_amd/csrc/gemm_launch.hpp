@@ -4,9 +4,9 @@
 
 namespace rad {
 
-template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE>
-hipError_t run_gemm(const GemmArgs& g, hipStream_t st) {
-  auto kern = gemm_kernel<DT, AK, BKIND, EPI, BM, BN, BK, SE>;
+template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE, int FLAGS>
+hipError_t run_gemm_variant(const GemmArgs& g, hipStream_t st) {
+  auto kern = gemm_kernel<DT, AK, BKIND, EPI, BM, BN, BK, SE, FLAGS>;
   constexpr int smem = GemmSmem<DT, AK, BKIND, EPI, BM, BN, BK, SE>::BYTES;
   static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
   static bool prepared = false;   // one host thread drives a context
@@ -20,6 +20,34 @@ hipError_t run_gemm(const GemmArgs& g, hipStream_t st) {
   if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(kGemmThreads), smem, st, g);
   return hipGetLastError();
+}
+
+// true when every tile is full and every operand row is 16-byte aligned: the
+// interior (unguarded) kernel variant may run
+template <class DT, int AK, int BM, int BN, int BK>
+bool gemm_is_full(const GemmArgs& g) {
+  const int vec = sizeof(typename ElemOf<DT>::type) == 2 ? 8 : 4;
+  bool full = g.M % BM == 0 && g.N % BN == 0 && g.K % BK == 0 && g.K > 0;
+  if (AK != kOpSparse) full = full && g.lda % vec == 0 && (reinterpret_cast<uintptr_t>(g.A) & 15) == 0;
+  return full && g.ldb % vec == 0 && (reinterpret_cast<uintptr_t>(g.B) & 15) == 0;
+}
+
+// MASK_A / MASK_B: whether this GEMM family can carry a ReLU-bit mask on that
+// operand; BOTH_EDGE: build the interior variant too (else guarded only).
+template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE, bool MASK_A, bool MASK_B,
+          bool BOTH_EDGE = true>
+hipError_t run_gemm(const GemmArgs& g, hipStream_t st) {
+  if (g.dry_run) return hipSuccess;   // the caller only wanted the kernel's label
+  const bool full = BOTH_EDGE && gemm_is_full<DT, AK, BM, BN, BK>(g);
+  const bool ma = MASK_A && g.a_mask != nullptr, mb = MASK_B && g.b_mask != nullptr;
+  if ((g.a_mask && !MASK_A) || (g.b_mask && !MASK_B)) return hipErrorInvalidValue;
+  constexpr int FA = MASK_A ? kFlagMaskA : 0, FB = MASK_B ? kFlagMaskB : 0;
+  if (BOTH_EDGE && full) {
+    if (ma || mb) return run_gemm_variant<DT, AK, BKIND, EPI, BM, BN, BK, SE, FA | FB>(g, st);
+    return run_gemm_variant<DT, AK, BKIND, EPI, BM, BN, BK, SE, 0>(g, st);
+  }
+  if (ma || mb) return run_gemm_variant<DT, AK, BKIND, EPI, BM, BN, BK, SE, kFlagEdge | FA | FB>(g, st);
+  return run_gemm_variant<DT, AK, BKIND, EPI, BM, BN, BK, SE, kFlagEdge>(g, st);
 }
 
 hipError_t launch_gemm_f32(int a_kind, int b_kind, int epi, const GemmArgs& g, hipStream_t st, const char** name);

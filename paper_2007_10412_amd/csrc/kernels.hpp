@@ -40,6 +40,7 @@ enum EpiKind : int {
 };
 
 struct GemmArgs {
+  int dry_run;                  // select the kernel and report its label, launch nothing
   int M, N, K;
   const void* A; int64_t lda;
   const void* B; int64_t ldb;
