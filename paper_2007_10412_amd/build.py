@@ -9,7 +9,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librad_hip.so")
 SOURCES = ["api.hip", "plan.hip", "small.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_fwd.hip",
-           "gemm_bf16_dx.hip", "gemm_bf16_dwd.hip", "gemm_bf16_sparse.hip"]
+           "gemm_bf16_dx.hip", "gemm_bf16_dwd.hip", "gemm_bf16_sparse.hip", "gemm_bf16_sparse3.hip",
+           "gemm_bf16_sparse7.hip"]
 # packed fp32 VALU forms are switched off: hipcc -O3 otherwise forms them on its own
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -43,7 +44,7 @@ def _compile(src, force=True):
     return obj, err
 
 
-def build(verbose=False, jobs=8, force=True):
+def build(verbose=False, jobs=10, force=True):
     """force=False recompiles only sources older than their object (developer loop)."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:

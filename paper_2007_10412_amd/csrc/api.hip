@@ -32,7 +32,7 @@ struct rad_ctx {
   float* loss_dev = nullptr;
 };
 
-enum { WS_BITMAP = 0, WS_BITMAP2 = 1, WS_ROWLOSS = 2, WS_COLSUM = 3 };
+enum { WS_BITMAP = 0, WS_DENSE = 1, WS_ROWLOSS = 2, WS_COLSUM = 3 };
 
 static const char* kNoCtx = "no context";
 
@@ -279,7 +279,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
     return hipMalloc(ptr, bytes ? bytes : 16) == hipSuccess;
   };
   bool ok = alloc(&s->values, (size_t)s->capacity * s->elem());
-  ok = ok && alloc((void**)&s->overflow, sizeof(int));
+  ok = ok && alloc((void**)&s->overflow, 2 * sizeof(int));   // [0] capacity overflow flag, [1] longest bucket segment
   if (scheme != RAD_EXACT) {
     const size_t n_idx = scheme == RAD_FIXEDK_SHARED ? (size_t)steps * s->k : (size_t)s->capacity;
     ok = ok && alloc((void**)&s->indices, n_idx * 2);
@@ -291,7 +291,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
     s->bits_pitch = (s->d_out + 31) / 32;
     ok = ok && alloc((void**)&s->bits, (size_t)R * s->bits_pitch * 4);
   }
-  if (ok) ok = hipMemsetAsync(s->overflow, 0, sizeof(int), c->stream) == hipSuccess;
+  if (ok) ok = hipMemsetAsync(s->overflow, 0, 2 * sizeof(int), c->stream) == hipSuccess;
   if (!ok) { rad_store_destroy(s); return fail(c, RAD_ERR_DEVICE, "store allocation failed"); }
   *out = s;
   return RAD_OK;
@@ -398,10 +398,11 @@ static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, u
   a.bitmap = bitmap; a.bm_pitch = s->bm_pitch;
   a.bucket_off = s->bucket_off; a.nb = s->nb;
   a.row_cnt = s->row_cnt; a.row_ptr = s->row_ptr;
+  a.max_seg = s->overflow + 1;
   s->bitmap = bitmap;
+  HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(s->overflow), 0u, 2, c->stream));
   HIP_TRY(c, timed(c, "plan", [&](const char**) { return launch_plan(a, c->stream); }));
   if (s->scheme == RAD_BERNOULLI) {
-    HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(s->overflow), 0u, 1, c->stream));
     HIP_TRY(c, timed(c, "row_scan", [&](const char**) {
       return launch_row_scan(s->row_cnt, s->row_ptr, s->steps * s->rows, s->capacity, s->overflow, c->stream);
     }));
@@ -478,7 +479,7 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
 static int sparse_prefetch_for(const rad_store* s, int lanes_per_row) {
   const double pi = s->scheme == RAD_BERNOULLI ? s->p : (double)s->k / (double)s->cols;
   const double mean = pi * (s->cols < kBucket ? s->cols : kBucket);
-  return (int)std::ceil((mean + 3.0 * std::sqrt(mean)) / lanes_per_row);
+  return (int)std::ceil((mean + 6.0 * std::sqrt(mean)) / lanes_per_row);   // overflow beyond this is rare and handled apart
 }
 
 // dW = beta dW + store(slot)^T (dy masked by bits)
@@ -507,18 +508,39 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
   }
   g.M = s->cols;
   g.sa = store_view(s, slot);
-  g.sparse_prefetch = sparse_prefetch_for(s, s->dtype == kBF16 ? 4 : 16);
-  return run_gemm_call(c, s->dtype, kOpSparse, kOpMN, kEpiStore, g);
+  g.sparse_prefetch = sparse_prefetch_for(s, s->dtype == kBF16 ? 8 : 16);
+  if (s->dtype == kBF16 && g.sparse_prefetch > gemm_bf16_sparse_max_prefetch()) {
+    // dense enough that scattering into LDS loses to a plain contraction: rebuild x~ as a transient dense
+    // operand (one layer's worth, reused) and run the dense dW kernel
+    void* dense = nullptr;
+    RAD_TRY(ws_get(c, WS_DENSE, (size_t)s->rows * s->cols * s->elem(), &dense));
+    HIP_TRY(c, timed(c, "unpack", [&](const char**) { return launch_unpack(g.sa, s->dtype, dense, c->stream); }));
+    g.A = dense; g.lda = s->cols;
+    return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
+  }
+  RAD_TRY(run_gemm_call(c, s->dtype, kOpSparse, kOpMN, kEpiStore, g));
+  if (s->dtype == kBF16) {
+    // the bf16 kernel keeps a fixed number of entries per (row, bucket) in registers; the rest, if any, here
+    const int cap = gemm_bf16_sparse_cap(g.sparse_prefetch);
+    HIP_TRY(c, timed(c, "dw_overflow", [&](const char**) {
+      return launch_dw_overflow(g.sa, s->rows, dy, s->dtype, N, bits, bits_pitch, dW, cap, s->overflow + 1, c->stream);
+    }));
+  }
+  return RAD_OK;
 }
 
 // dX = (dy masked by bits) W^T
+// (dy masked by bits) W^T, optionally masked on the way out by the ReLU bits of the layer below, so that
+// the chain hands g = dL/dh to the next dW and dX without loader masks
 static rad_status dX_gemm(rad_ctx* c, int dtype, int M, int d_in, int d_out, const void* dy, const uint32_t* bits,
-                          int bits_pitch, const void* W, void* dX) {
+                          int bits_pitch, const void* W, void* dX, const uint32_t* out_bits = nullptr,
+                          int out_pitch = 0) {
   GemmArgs g = gemm_zero();
   g.M = M; g.N = d_in; g.K = d_out;
   g.A = dy; g.lda = d_out; g.a_mask = bits; g.a_mask_pitch = bits_pitch;
   g.B = W; g.ldb = d_out;
   g.C = dX; g.ldc = d_in; g.beta = 0; g.c_dtype = dtype;
+  g.c_mask = out_bits; g.c_mask_pitch = out_pitch;
   return run_gemm_call(c, dtype, kOpK, kOpK, kEpiStore, g);
 }
 
@@ -713,17 +735,21 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   }
   RAD_TRY(softmax_call(c, m->logits, labels, B, (int)m->dims[(size_t)Lc], m->dtype, m->dyb[0], c->loss_dev));
 
-  // backward from the stores
+  // backward from the stores.  dyb holds g = dL/dh of the layer at hand: the loss gradient for the last
+  // layer (no ReLU), and below it the dX of the layer above, masked by this layer's ReLU bits in that
+  // GEMM's epilogue.
   int cur = 0;
   for (int l = Lc - 1; l >= 0; --l) {
     rad_store* s = m->stores[(size_t)l];
     const int N = (int)m->dims[(size_t)l + 1], D = (int)m->dims[(size_t)l];
-    RAD_TRY(dW_gemm(c, s, 0, m->dyb[cur], N, s->bits, s->bits_pitch, static_cast<float*>(grads[l * per]), 0));
+    RAD_TRY(dW_gemm(c, s, 0, m->dyb[cur], N, nullptr, 0, static_cast<float*>(grads[l * per]), 0));
     if (m->has_bias)
-      RAD_TRY(colsum_call(c, m->dyb[cur], m->dtype, B, N, s->bits, s->bits_pitch, nullptr, 0, 0,
+      RAD_TRY(colsum_call(c, m->dyb[cur], m->dtype, B, N, nullptr, 0, nullptr, 0, 0,
                           static_cast<float*>(grads[l * per + 1]), nullptr, 0));
     if (l > 0) {
-      RAD_TRY(dX_gemm(c, m->dtype, B, D, N, m->dyb[cur], s->bits, s->bits_pitch, Wp(l), m->dyb[cur ^ 1]));
+      rad_store* below = m->stores[(size_t)l - 1];
+      RAD_TRY(dX_gemm(c, m->dtype, B, D, N, m->dyb[cur], nullptr, 0, Wp(l), m->dyb[cur ^ 1], below->bits,
+                      below->bits_pitch));
       cur ^= 1;
     }
   }
@@ -819,17 +845,19 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   float* dz = static_cast<float*>(m->dyb[0]);
   RAD_TRY(dW_gemm(c, s_ho, 0, dz, C, nullptr, 0, dW_ho, 0));
   RAD_TRY(colsum_call(c, dz, kF32, B, C, nullptr, 0, nullptr, 0, 0, db_o, nullptr, 0));
-  RAD_TRY(dX_gemm(c, kF32, B, H, C, dz, nullptr, 0, W_ho, m->dyb[1]));
+  // dyb holds g_t = dL/dh_t masked by the ReLU bits of step t (applied in the epilogue of the GEMM that
+  // produces it)
+  RAD_TRY(dX_gemm(c, kF32, B, H, C, dz, nullptr, 0, W_ho, m->dyb[1], m->rnn_bits + (size_t)(T - 1) * B * bp, bp));
   int cur = 1;
   if (T == 1) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(dW_hh), 0u, (int64_t)H * H, c->stream));
   for (int t = T; t >= 1; --t) {
-    const uint32_t* bits = m->rnn_bits + (size_t)(t - 1) * B * bp;
     const int beta = t < T;
-    if (t >= 2) RAD_TRY(dW_gemm(c, s_hh, t - 2, m->dyb[cur], H, bits, bp, dW_hh, beta));
-    RAD_TRY(colsum_call(c, m->dyb[cur], kF32, B, H, bits, bp, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db, dW_ih,
-                        beta));
+    if (t >= 2) RAD_TRY(dW_gemm(c, s_hh, t - 2, m->dyb[cur], H, nullptr, 0, dW_hh, beta));
+    RAD_TRY(colsum_call(c, m->dyb[cur], kF32, B, H, nullptr, 0, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db,
+                        dW_ih, beta));
     if (t >= 2) {
-      RAD_TRY(dX_gemm(c, kF32, B, H, H, m->dyb[cur], bits, bp, W_hh, m->dyb[cur ^ 1]));
+      RAD_TRY(dX_gemm(c, kF32, B, H, H, m->dyb[cur], nullptr, 0, W_hh, m->dyb[cur ^ 1],
+                      m->rnn_bits + (size_t)(t - 2) * B * bp, bp));
       cur ^= 1;
     }
   }

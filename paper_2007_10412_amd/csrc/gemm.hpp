@@ -231,7 +231,9 @@ template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadK {
   typedef LdsBF16<R, BK> L;
   static constexpr int TOTAL = R * L::CH;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  static constexpr int kDsWrites = NCH, kVmemReads = NCH * (MASKED ? 2 : 1);
   u32x4 v[NCH];
+  uint32_t mb[MASKED ? NCH : 1];                 // ReLU bits of each chunk, applied at commit
   const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
   __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
                                        int rmax_, int K_, const StoreView&) {
@@ -244,6 +246,7 @@ template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadK {
     for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
       u32x4 t = {0u, 0u, 0u, 0u};
+      if (MASKED) mb[i] = 0u;
       if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
         const int row = c / L::CH, kc = c % L::CH;
         const int gr = r0 + row, gk = k0 + kc * 8;
@@ -258,20 +261,25 @@ template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadK {
             for (int e = 0; e < 8; ++e) if (gk + e < K) te[e] = src[e];
           }
         }
-        if (MASKED && (!EDGE || (gr < rmax && gk < K))) mask_bf16x8(t, mask_bits(mask, mp, gr, gk));
+        if (MASKED && (!EDGE || (gr < rmax && gk < K))) mb[i] = mask_bits(mask, mp, gr, gk);
       }
       v[i] = t;
     }
   }
-  __device__ __forceinline__ void commit(uint16_t* lds) {
+  // the commit in four steps, so the caller can alternate them with its own LDS reads
+  template <int STEP> __device__ __forceinline__ void commit_step(uint16_t* lds) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
+    for (int i = STEP; i < NCH; i += 4) {
       const int c = threadIdx.x + i * kGemmThreads;
       if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
         const int row = c / L::CH, kc = c % L::CH;
+        if (MASKED) mask_bf16x8(v[i], mb[i]);
         *reinterpret_cast<u32x4*>(&lds[L::unit(row, kc) * 8]) = v[i];
       }
     }
+  }
+  __device__ __forceinline__ void commit(uint16_t* lds) {
+    commit_step<0>(lds); commit_step<1>(lds); commit_step<2>(lds); commit_step<3>(lds);
   }
 };
 
@@ -282,7 +290,9 @@ template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadMN {
   static constexpr int RB = R / 8, KB = BK / 8;
   static constexpr int TOTAL = RB * KB;
   static constexpr int NBL = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  static constexpr int kDsWrites = NBL * 8, kVmemReads = NBL * 8 * (MASKED ? 2 : 1);
   u32x4 v[NBL][8];                               // v[.][kk] = 8 consecutive rows at k = kb*8+kk
+  uint32_t mb[MASKED ? NBL : 1][8];
   const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
   __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
                                        int rmax_, int K_, const StoreView&) {
@@ -300,6 +310,7 @@ template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadMN {
       for (int kk = 0; kk < 8; ++kk) {
         u32x4 t = {0u, 0u, 0u, 0u};
         const int gk = k0 + kb * 8 + kk;
+        if (MASKED) mb[i][kk] = 0u;
         if (TOTAL % kGemmThreads == 0 || blk < TOTAL) {
           const uint16_t* src = p + ((uint32_t)gk * ld + (uint32_t)gr);
           if (!EDGE) {
@@ -312,33 +323,38 @@ template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadMN {
               for (int e = 0; e < 8; ++e) if (gr + e < rmax) te[e] = src[e];
             }
           }
-          if (MASKED && (!EDGE || (gk < K && gr < rmax))) mask_bf16x8(t, mask_bits(mask, mp, gk, gr));
+          if (MASKED && (!EDGE || (gk < K && gr < rmax))) mb[i][kk] = mask_bits(mask, mp, gk, gr);
         }
         v[i][kk] = t;
       }
     }
   }
-  __device__ __forceinline__ void commit(uint16_t* lds) {
+  // step d transposes dword d of the block: rows 2d and 2d+1 of the 8 x 8 block
+  template <int D> __device__ __forceinline__ void commit_step(uint16_t* lds) {
 #pragma unroll
     for (int i = 0; i < NBL; ++i) {
       const int blk = threadIdx.x + i * kGemmThreads;
       if (TOTAL % kGemmThreads == 0 || blk < TOTAL) {
         const int rb = blk % RB, kb = blk / RB;
-        // dword d of v[kk] holds rows 2d (low half) and 2d+1 (high half) at k = kk
+        if (MASKED && D == 0) {
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          u32x4 lo, hi;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const uint32_t a = v[i][2 * q][d], b = v[i][2 * q + 1][d];
-            lo[q] = __builtin_amdgcn_perm(b, a, 0x05040100u);   // (a.lo, b.lo)
-            hi[q] = __builtin_amdgcn_perm(b, a, 0x07060302u);   // (a.hi, b.hi)
-          }
-          *reinterpret_cast<u32x4*>(&lds[L::unit(rb * 8 + 2 * d, kb) * 8]) = lo;
-          *reinterpret_cast<u32x4*>(&lds[L::unit(rb * 8 + 2 * d + 1, kb) * 8]) = hi;
+          for (int kk = 0; kk < 8; ++kk) mask_bf16x8(v[i][kk], mb[i][kk]);
         }
+        // dword D of v[kk] holds rows 2D (low half) and 2D+1 (high half) at k = kk
+        u32x4 lo, hi;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t a = v[i][2 * q][D], b = v[i][2 * q + 1][D];
+          lo[q] = __builtin_amdgcn_perm(b, a, 0x05040100u);   // (a.lo, b.lo)
+          hi[q] = __builtin_amdgcn_perm(b, a, 0x07060302u);   // (a.hi, b.hi)
+        }
+        *reinterpret_cast<u32x4*>(&lds[L::unit(rb * 8 + 2 * D, kb) * 8]) = lo;
+        *reinterpret_cast<u32x4*>(&lds[L::unit(rb * 8 + 2 * D + 1, kb) * 8]) = hi;
       }
     }
+  }
+  __device__ __forceinline__ void commit(uint16_t* lds) {
+    commit_step<0>(lds); commit_step<1>(lds); commit_step<2>(lds); commit_step<3>(lds);
   }
 };
 
@@ -349,6 +365,7 @@ template <int R, int BK, int SE> struct BF16LoadSparse {
   static constexpr int RPW = BK / 4;            // k (store rows) per wave: 16 at BK = 64
   static constexpr int LPR = 64 / RPW;          // lanes per store row
   static constexpr int UPW = RPW / 8;           // 16-byte units per tile row owned by a wave
+  static constexpr int kDsWrites = R * UPW / 64 + SE, kVmemReads = 2 * SE + 3;
   uint32_t ent[SE];                              // (value bits << 16) | (column - m0), 0xFFFF = none
   uint32_t beg, end, nbeg, nend;
   StoreView s; int m0, K;
@@ -374,25 +391,37 @@ template <int R, int BK, int SE> struct BF16LoadSparse {
       }
     }
   }
-  __device__ __forceinline__ void commit(uint16_t* lds) {
+  // steps 0 and 1 clear the wave's stripe of the tile, steps 2 and 3 scatter the entries into it
+  template <int STEP> __device__ __forceinline__ void commit_step(uint16_t* lds) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const u32x4 z = {0u, 0u, 0u, 0u};
+    constexpr int NZ = R * UPW / 64;               // clearing stores per lane
+    if (STEP < 2) {
+      const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int c = lane; c < R * UPW; c += 64) {
-      const int row = c / UPW, u = c % UPW;
-      *reinterpret_cast<u32x4*>(&lds[L::unit(row, w * UPW + u) * 8]) = z;
-    }
-    const int kr = w * RPW + lane / LPR, sub = lane % LPR;
+      for (int q = STEP * (NZ / 2); q < (STEP + 1) * (NZ / 2); ++q) {
+        const int c = lane + q * 64;
+        const int row = c / UPW, u = c % UPW;
+        *reinterpret_cast<u32x4*>(&lds[L::unit(row, w * UPW + u) * 8]) = z;
+      }
+    } else {
+      const int kr = w * RPW + lane / LPR, sub = lane % LPR;
+      constexpr int H = (SE + 1) / 2;
 #pragma unroll
-    for (int i = 0; i < SE; ++i) {
-      const uint32_t c = ent[i] & 0xFFFFu;
-      if (c != 0xFFFFu) lds[L::unit((int)c, kr >> 3) * 8 + (kr & 7)] = (uint16_t)(ent[i] >> 16);
+      for (int i = (STEP - 2) * H; i < (STEP == 2 ? H : SE); ++i) {
+        const uint32_t c = ent[i] & 0xFFFFu;
+        if (c != 0xFFFFu) lds[L::unit((int)c, kr >> 3) * 8 + (kr & 7)] = (uint16_t)(ent[i] >> 16);
+      }
+      if (STEP == 3) {
+        const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
+        for (uint32_t e = beg + sub + SE * LPR; e < end; e += LPR) {
+          const int c = (int)s.indices[e] - m0;
+          if (c >= 0 && c < R) lds[L::unit(c, kr >> 3) * 8 + (kr & 7)] = vals[e];
+        }
+      }
     }
-    const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
-    for (uint32_t e = beg + sub + SE * LPR; e < end; e += LPR) {
-      const int c = (int)s.indices[e] - m0;
-      if (c >= 0 && c < R) lds[L::unit(c, kr >> 3) * 8 + (kr & 7)] = vals[e];
-    }
+  }
+  __device__ __forceinline__ void commit(uint16_t* lds) {
+    commit_step<0>(lds); commit_step<1>(lds); commit_step<2>(lds); commit_step<3>(lds);
   }
 };
 
@@ -486,7 +515,11 @@ __device__ __forceinline__ float get_elem(const uint16_t* p) { return bf16_bits_
 // accumulator element i of a 32x32 block sits at row (i/4)*8 + (lane/32)*4 + i%4, column lane%32
 __device__ __forceinline__ int acc_row(int i, int lane) { return (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3); }
 
-template <int TM, int TN, typename OutT>
+// Plain store epilogue.  Everything that varies per call is a template flag so that each copy is straight
+// code over the 16*TM*TN accumulator registers (runtime branches per element made the register allocator
+// spill the accumulators): EDGE guards ragged tiles, MASK zeroes outputs whose ReLU bit is 0, BETA adds to
+// what is there, MAP sends tile row r to output row row_map[r].
+template <int TM, int TN, typename OutT, bool EDGE, bool MASK, bool BETA, bool MAP>
 __device__ __forceinline__ void epilogue_store(const GemmArgs& g, floatx16 (&acc)[TM][TN], int m0, int n0,
                                                int wm0, int wn0) {
   const int lane = threadIdx.x & 63;
@@ -494,20 +527,39 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& g, floatx16 (&acc
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn0 + j * 32 + (lane & 31);
+    for (int e = 0; e < 16; ++e) {
+      const int row = m0 + wm0 + i * 32 + acc_row(e, lane);
+      int orow = row;
+      if (MAP) orow = (!EDGE || row < g.M) ? (int)g.row_map[row] : 0;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm0 + i * 32 + acc_row(e, lane);
-        if (row < g.M && col < g.N) {
-          const int orow = g.row_map ? (int)g.row_map[row] : row;
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn0 + j * 32 + (lane & 31);
+        if (!EDGE || (row < g.M && col < g.N)) {
           OutT* dst = C + (size_t)orow * g.ldc + col;
           float v = acc[i][j][e];
-          if (g.beta) v += get_elem(dst);
+          if (MASK && !((g.c_mask[(size_t)orow * g.c_mask_pitch + (col >> 5)] >> (col & 31)) & 1u)) v = 0.f;
+          if (BETA) v += get_elem(dst);
           put_elem(dst, v);
         }
       }
     }
+}
+
+// picks the copy for this call; which flags can occur depends on the GEMM family
+template <int AK, int TM, int TN, typename DxT, bool EDGE>
+__device__ __forceinline__ void epilogue_store_dispatch(const GemmArgs& g, floatx16 (&acc)[TM][TN], int m0, int n0,
+                                                        int wm0, int wn0) {
+  if constexpr (AK == kOpK) {            // dX: operand dtype out, optional ReLU mask of the layer below
+    if (g.c_mask) epilogue_store<TM, TN, DxT, EDGE, true, false, false>(g, acc, m0, n0, wm0, wn0);
+    else epilogue_store<TM, TN, DxT, EDGE, false, false, false>(g, acc, m0, n0, wm0, wn0);
+  } else if constexpr (AK == kOpSparse) { // dW from the compressed store: fp32 out, optional accumulate
+    if (g.beta) epilogue_store<TM, TN, float, EDGE, false, true, false>(g, acc, m0, n0, wm0, wn0);
+    else epilogue_store<TM, TN, float, EDGE, false, false, false>(g, acc, m0, n0, wm0, wn0);
+  } else {                                // dW from a dense or compact store: row map for the shared scheme
+    if (g.row_map) epilogue_store<TM, TN, float, EDGE, false, true, true>(g, acc, m0, n0, wm0, wn0);
+    else if (g.beta) epilogue_store<TM, TN, float, EDGE, false, true, false>(g, acc, m0, n0, wm0, wn0);
+    else epilogue_store<TM, TN, float, EDGE, false, false, false>(g, acc, m0, n0, wm0, wn0);
+  }
 }
 
 // Forward epilogue.  The tile goes through LDS in the storage dtype so that
@@ -676,11 +728,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
   }
 
   if constexpr (EPI == kEpiStore) {
-    if (g.c_dtype == kF32) epilogue_store<TM, TN, float>(g, acc, m0, n0, wm0, wn0);
-    else epilogue_store<TM, TN, uint16_t>(g, acc, m0, n0, wm0, wn0);
+    epilogue_store_dispatch<AK, TM, TN, ElemT, EDGE>(g, acc, m0, n0, wm0, wn0);
   } else {
     epilogue_fwd<ElemT, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
   }
 }
+
 
 }  // namespace rad

@@ -1,0 +1,416 @@
+// bf16 GEMM kernels for gfx950: ring pipeline over three LDS stages of
+// BK = 32 with the slice after them in flight in registers.
+//
+// At iteration kt the workgroup
+//   - runs the 2 x TM x TN MFMAs (v_mfma_f32_32x32x16_bf16) of slice kt from
+//     LDS stage kt%3,
+//   - moves slice kt+2 from registers into stage (kt+2)%3, last read before
+//     the previous barrier,
+//   - starts the global loads of slice kt+3 into the registers just freed,
+//   - reads the first fragments of slice kt+1 (complete since the previous
+//     barrier), so nothing waits on LDS after the one barrier per iteration.
+// The loop is unrolled three times so stages and slots are compile-time, and
+// the steady state is a single basic block in which sched_group_barrier
+// spreads LDS and global instructions between the MFMAs.  LDS loads and
+// stores are written in the alternating order wanted, because the compiler
+// keeps the relative order of LDS accesses it cannot prove disjoint.
+#pragma once
+#include <type_traits>
+
+#include "gemm.hpp"
+
+namespace rad {
+
+// K slices in flight in registers.  Three (fetch distance of three iterations) measured slower than one:
+// the compiler's wait-count pass drains every load in flight at the loop header, so the extra slots only
+// cost registers.
+constexpr int kSlots = 1;
+constexpr int kBK3 = 32;
+
+// ------------------------------------------------------------------ loaders
+// dense, K contiguous: element (row, k) at p[row*ld + k]
+template <int R, bool EDGE, bool MASKED> struct RingLoadK {
+  typedef LdsBF16<R, kBK3> L;
+  static constexpr int TOTAL = R * L::CH;
+  static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  static constexpr int kDsWrites = NCH, kVmemReads = NCH * (MASKED ? 2 : 1);
+  u32x4 v[kSlots][NCH];
+  uint32_t mb[MASKED ? kSlots : 1][MASKED ? NCH : 1];   // ReLU bits of each chunk, applied at commit
+  const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
+  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
+                                       int rmax_, int K_, const StoreView&) {
+    p = static_cast<const uint16_t*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
+  }
+  __device__ __forceinline__ void bounds(int) {}
+  __device__ __forceinline__ void configure(int) {}
+  template <int SLOT> __device__ __forceinline__ void fetch(int k0) {
+    const bool vec = (ld & 7) == 0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      u32x4 t = {0u, 0u, 0u, 0u};
+      if (MASKED) mb[SLOT][i] = 0u;
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
+        const int row = c / L::CH, kc = c % L::CH;
+        const int gr = r0 + row, gk = k0 + kc * 8;
+        const uint16_t* src = p + ((uint32_t)gr * ld + (uint32_t)gk);
+        if (!EDGE) {
+          t = *reinterpret_cast<const u32x4*>(src);
+        } else if (gr < rmax && gk < K) {
+          if (vec && gk + 7 < K) t = *reinterpret_cast<const u32x4*>(src);
+          else {
+            uint16_t* te = reinterpret_cast<uint16_t*>(&t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) if (gk + e < K) te[e] = src[e];
+          }
+        }
+        if (MASKED && (!EDGE || (gr < rmax && gk < K))) mb[SLOT][i] = mask_bits(mask, mp, gr, gk);
+      }
+      v[SLOT][i] = t;
+    }
+  }
+  // the commit in four steps, so the caller can alternate them with its own LDS reads
+  template <int SLOT, int STEP> __device__ __forceinline__ void commit_step(uint16_t* lds) {
+#pragma unroll
+    for (int i = STEP; i < NCH; i += 4) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
+        const int row = c / L::CH, kc = c % L::CH;
+        if (MASKED) mask_bf16x8(v[SLOT][i], mb[SLOT][i]);
+        *reinterpret_cast<u32x4*>(&lds[L::unit(row, kc) * 8]) = v[SLOT][i];
+      }
+    }
+  }
+};
+
+// dense, M/N contiguous: element (row, k) at p[k*ld + row].  Every thread owns a KPT(k) x 8(row) block
+// (KPT = 4 for 256-row tiles, 2 for 128-row tiles, so that all 256 threads have one and the code is free
+// of predicates) and transposes it in registers: LDS receives, for each of the 8 rows, KPT consecutive k.
+template <int R, bool EDGE, bool MASKED> struct RingLoadMN {
+  typedef LdsBF16<R, kBK3> L;
+  static constexpr int RB = R / 8;               // row blocks
+  static constexpr int KPT = R / 64;             // k rows per thread
+  static_assert(RB * (kBK3 / KPT) == kGemmThreads, "one block per thread");
+  static constexpr int kDsWrites = 8, kVmemReads = KPT * (MASKED ? 2 : 1);
+  u32x4 v[kSlots][KPT];                          // v[..][kk] = 8 consecutive rows at k = kq*KPT + kk
+  uint32_t mb[MASKED ? kSlots : 1][MASKED ? KPT : 1];
+  const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
+  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
+                                       int rmax_, int K_, const StoreView&) {
+    p = static_cast<const uint16_t*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
+  }
+  __device__ __forceinline__ void bounds(int) {}
+  __device__ __forceinline__ void configure(int) {}
+  template <int SLOT> __device__ __forceinline__ void fetch(int k0) {
+    const bool vec = (ld & 7) == 0;
+    const int rb = threadIdx.x % RB, kq = threadIdx.x / RB;
+    const int gr = r0 + rb * 8;
+#pragma unroll
+    for (int kk = 0; kk < KPT; ++kk) {
+      u32x4 t = {0u, 0u, 0u, 0u};
+      const int gk = k0 + kq * KPT + kk;
+      if (MASKED) mb[SLOT][kk] = 0u;
+      const uint16_t* src = p + ((uint32_t)gk * ld + (uint32_t)gr);
+      if (!EDGE) {
+        t = *reinterpret_cast<const u32x4*>(src);
+      } else if (gk < K && gr < rmax) {
+        if (vec && gr + 7 < rmax) t = *reinterpret_cast<const u32x4*>(src);
+        else {
+          uint16_t* te = reinterpret_cast<uint16_t*>(&t);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) if (gr + e < rmax) te[e] = src[e];
+        }
+      }
+      if (MASKED && (!EDGE || (gk < K && gr < rmax))) mb[SLOT][kk] = mask_bits(mask, mp, gk, gr);
+      v[SLOT][kk] = t;
+    }
+  }
+  // step D transposes dword D of the block: rows 2D (low halves) and 2D+1 (high halves)
+  template <int SLOT, int D> __device__ __forceinline__ void commit_step(uint16_t* lds) {
+    const int rb = threadIdx.x % RB, kq = threadIdx.x / RB;
+    if (MASKED && D == 0) {
+#pragma unroll
+      for (int kk = 0; kk < KPT; ++kk) mask_bf16x8(v[SLOT][kk], mb[SLOT][kk]);
+    }
+    const int kfirst = kq * KPT;                   // first k of this thread inside the slice
+    uint16_t* dlo = &lds[L::unit(rb * 8 + 2 * D, kfirst >> 3) * 8 + (kfirst & 7)];
+    uint16_t* dhi = &lds[L::unit(rb * 8 + 2 * D + 1, kfirst >> 3) * 8 + (kfirst & 7)];
+    if constexpr (KPT == 4) {
+      u32x2 lo, hi;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const uint32_t a = v[SLOT][2 * q][D], b = v[SLOT][2 * q + 1][D];
+        lo[q] = __builtin_amdgcn_perm(b, a, 0x05040100u);   // (a.lo, b.lo)
+        hi[q] = __builtin_amdgcn_perm(b, a, 0x07060302u);   // (a.hi, b.hi)
+      }
+      *reinterpret_cast<u32x2*>(dlo) = lo;
+      *reinterpret_cast<u32x2*>(dhi) = hi;
+    } else {
+      const uint32_t a = v[SLOT][0][D], b = v[SLOT][1][D];
+      *reinterpret_cast<uint32_t*>(dlo) = __builtin_amdgcn_perm(b, a, 0x05040100u);
+      *reinterpret_cast<uint32_t*>(dhi) = __builtin_amdgcn_perm(b, a, 0x07060302u);
+    }
+  }
+};
+
+// compressed store as the A operand of dW: K index = store row (example b),
+// M index = column j.  The LDS tile is [row j][k b]; wave w owns the k columns
+// [8w, 8w+8), one 16-byte unit of every tile row: it clears them and scatters
+// into them the entries of its eight store rows (eight lanes per store row),
+// so no block barrier is needed between clearing and scattering.
+template <int R, int SE> struct RingLoadSparse {
+  typedef LdsBF16<R, kBK3> L;
+  static constexpr int RPW = kBK3 / 4;          // store rows per wave
+  static constexpr int LPR = 64 / RPW;          // lanes per store row
+  static constexpr int NZ = R / 64;             // clearing stores per lane
+  static constexpr int kCap = SE * LPR;         // entries of one (store row, bucket) segment held in registers
+  static constexpr int kDsWrites = NZ + SE, kVmemReads = 2 * SE + 3;
+  uint32_t ent[kSlots][SE];                      // (value bits << 16) | (column - m0), column 0xFFFF = none
+  uint32_t nbeg, nend;
+  StoreView s; int m0, K, dummy;
+  __device__ __forceinline__ void init(const void*, int64_t, const uint32_t*, int, int r0_, int, int K_,
+                                       const StoreView& sv) { s = sv; m0 = r0_; K = K_; dummy = 0; }
+  // LDS element offset (from the A tile) of 64 spare bytes that absorb the stores of empty register entries
+  __device__ __forceinline__ void configure(int dummy_elems) { dummy = dummy_elems + (threadIdx.x & 31); }
+  // segment of the next slice's store row inside this tile's 256-column bucket
+  __device__ __forceinline__ void bounds(int k0) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int b = k0 + w * RPW + lane / LPR;
+    // no branch: rows past K read row K-1 and get an empty segment
+    store_segment(s, b < K ? b : K - 1, m0 / kBucket, &nbeg, &nend);
+    if (b >= K) nend = nbeg;
+  }
+  // Entries beyond kCap of a segment are not handled here: the host runs the overflow kernel after this
+  // GEMM, which adds them to dW (it exits at once unless the plan saw a segment that long).
+  template <int SLOT> __device__ __forceinline__ void fetch(int) {
+    const int sub = (threadIdx.x & 63) % LPR;
+    const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
+#pragma unroll
+    for (int i = 0; i < SE; ++i) {
+      // no branch: a register entry past the segment reads entry 0 of the store and is discarded
+      const uint32_t e = nbeg + sub + i * LPR;
+      const bool in_seg = e < nend;
+      const uint32_t ee = in_seg ? e : 0u;
+      const int c = (int)s.indices[ee] - m0;
+      const uint32_t v = vals[ee];
+      ent[SLOT][i] = (in_seg && c >= 0 && c < R) ? ((v << 16) | (uint32_t)c) : 0xFFFFu;
+    }
+  }
+  // steps 0 and 1 clear the wave's unit column of the tile, steps 2 and 3 scatter the entries into it
+  template <int SLOT, int STEP> __device__ __forceinline__ void commit_step(uint16_t* lds) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (STEP < 2) {
+      const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int q = STEP * (NZ / 2); q < (STEP + 1) * (NZ / 2); ++q)
+        *reinterpret_cast<u32x4*>(&lds[L::unit(lane + q * 64, w) * 8]) = z;
+    } else {
+      const int kr = w * RPW + lane / LPR;
+      constexpr int H = (SE + 1) / 2;
+#pragma unroll
+      for (int i = (STEP - 2) * H; i < (STEP == 2 ? H : SE); ++i) {
+        const uint32_t c = ent[SLOT][i] & 0xFFFFu;
+        // no branch: an empty entry stores into the spare bytes instead
+        const int off = c != 0xFFFFu ? L::unit((int)c, kr >> 3) * 8 + (kr & 7) : dummy;
+        lds[off] = (uint16_t)(ent[SLOT][i] >> 16);
+      }
+    }
+  }
+};
+
+template <int KIND, int R, int SE, bool EDGE, bool MASKED> struct RingLoaderOf;
+template <int R, int SE, bool EDGE, bool MASKED> struct RingLoaderOf<kOpK, R, SE, EDGE, MASKED> { typedef RingLoadK<R, EDGE, MASKED> type; };
+template <int R, int SE, bool EDGE, bool MASKED> struct RingLoaderOf<kOpMN, R, SE, EDGE, MASKED> { typedef RingLoadMN<R, EDGE, MASKED> type; };
+template <int R, int SE, bool EDGE, bool MASKED> struct RingLoaderOf<kOpSparse, R, SE, EDGE, MASKED> { typedef RingLoadSparse<R, SE> type; };
+
+template <class LD, int SLOT> __device__ __forceinline__ void commit_all(LD& l, uint16_t* lds) {
+  l.template commit_step<SLOT, 0>(lds); l.template commit_step<SLOT, 1>(lds);
+  l.template commit_step<SLOT, 2>(lds); l.template commit_step<SLOT, 3>(lds);
+}
+
+// ------------------------------------------------------------------ MFMA side
+template <int TM, int TN, int BM, int BN>
+__device__ __forceinline__ void load_frags32(const uint16_t* As, const uint16_t* Bs, int ks, int wm0, int wn0,
+                                             bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
+  typedef LdsBF16<BM, kBK3> LA; typedef LdsBF16<BN, kBK3> LB;
+  const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+    a[i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, ks * 2 + lk) * 8]);
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+    b[j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, ks * 2 + lk) * 8]);
+}
+
+// fragments of k-step 1 of the current stage, alternated with the four commit
+// steps of each loader into the stage being refilled
+template <int SLOT, int TM, int TN, int BM, int BN, class LA_, class LB_>
+__device__ __forceinline__ void interleave_reads_commits(const uint16_t* As, const uint16_t* Bs, uint16_t* Aw,
+                                                         uint16_t* Bw, int wm0, int wn0, bf16x8 (&a)[TM],
+                                                         bf16x8 (&b)[TN], LA_& la, LB_& lb) {
+  typedef LdsBF16<BM, kBK3> LA; typedef LdsBF16<BN, kBK3> LB;
+  const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+  auto ra = [&](int i) { if (i < TM) a[i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, 2 + lk) * 8]); };
+  auto rb = [&](int j) { if (j < TN) b[j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, 2 + lk) * 8]); };
+  ra(0); la.template commit_step<SLOT, 0>(Aw);
+  rb(0); lb.template commit_step<SLOT, 0>(Bw);
+  ra(1); la.template commit_step<SLOT, 1>(Aw);
+  rb(1); lb.template commit_step<SLOT, 1>(Bw);
+  ra(2); la.template commit_step<SLOT, 2>(Aw);
+  rb(2); lb.template commit_step<SLOT, 2>(Bw);
+  ra(3); la.template commit_step<SLOT, 3>(Aw);
+  rb(3); lb.template commit_step<SLOT, 3>(Bw);
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void mfma_step(const bf16x8 (&a)[TM], const bf16x8 (&b)[TN], floatx16 (&acc)[TM][TN]) {
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+}
+
+template <int EPI, int BM, int BN>
+struct Gemm3Smem {
+  static constexpr int STAGE = (BM + BN) * kBK3 * 2 + 128;   // + spare bytes for the sparse loader
+  static constexpr int MAIN = 3 * STAGE;
+  static constexpr int CT = BM * (BN + 2) * 2;
+  static constexpr int BYTES = (EPI == kEpiFwd && CT > MAIN) ? CT : MAIN;
+};
+
+template <int V> using IntC = std::integral_constant<int, V>;
+
+template <int AK, int BKIND, int EPI, int BM, int BN, int SE, int FLAGS>
+__global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
+  constexpr bool EDGE = (FLAGS & kFlagEdge) != 0;
+  constexpr int BK = kBK3;
+  typedef Gemm3Smem<EPI, BM, BN> S;
+  typedef typename RingLoaderOf<AK, BM, SE, EDGE, (FLAGS & kFlagMaskA) != 0>::type LoadA;
+  typedef typename RingLoaderOf<BKIND, BN, SE, EDGE, (FLAGS & kFlagMaskB) != 0>::type LoadB;
+  constexpr int TM = BM / 64, TN = BN / 64;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  uint16_t* const smem = reinterpret_cast<uint16_t*>(smem_raw);
+  constexpr int kStageElems = S::STAGE / 2;
+  constexpr int kAElems = BM * BK;
+
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tile = blockIdx.x;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  const int w = threadIdx.x >> 6;
+  const int wm0 = (w >> 1) * (BM / 2), wn0 = (w & 1) * (BN / 2);
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  LoadA la; LoadB lb;
+  la.init(g.A, g.lda, g.a_mask, g.a_mask_pitch, m0, g.M, g.K, g.sa);
+  lb.init(g.B, g.ldb, g.b_mask, g.b_mask_pitch, n0, g.N, g.K, g.sa);
+  la.configure((BM + BN) * BK);
+  const int KT = (g.K + BK - 1) / BK;
+
+  // prologue: slices 0 and 1 into stages 0 and 1, slice 2 into the registers.  The long-K path is
+  // written without conditions so that the steady loop is entered with a known set of loads in flight.
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  const bool long_k = KT > 5;
+  if (long_k) {
+    la.bounds(0);
+    la.template fetch<0>(0); lb.template fetch<0>(0);
+    la.bounds(BK);
+    commit_all<LoadA, 0>(la, smem); commit_all<LoadB, 0>(lb, smem + kAElems);
+    la.template fetch<0>(BK); lb.template fetch<0>(BK);
+    la.bounds(2 * BK);
+    commit_all<LoadA, 0>(la, smem + kStageElems); commit_all<LoadB, 0>(lb, smem + kStageElems + kAElems);
+    la.template fetch<0>(2 * BK); lb.template fetch<0>(2 * BK); la.bounds(3 * BK);
+    __syncthreads();
+    load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
+  } else {
+    if (KT > 0) {
+      la.bounds(0);
+      la.template fetch<0>(0); lb.template fetch<0>(0);
+      la.bounds(BK);
+      commit_all<LoadA, 0>(la, smem); commit_all<LoadB, 0>(lb, smem + kAElems);
+    }
+    if (KT > 1) {
+      la.template fetch<0>(BK); lb.template fetch<0>(BK);
+      la.bounds(2 * BK);
+      commit_all<LoadA, 0>(la, smem + kStageElems); commit_all<LoadB, 0>(lb, smem + kStageElems + kAElems);
+    }
+    if (KT > 2) { la.template fetch<0>(2 * BK); lb.template fetch<0>(2 * BK); la.bounds(3 * BK); }
+    __syncthreads();
+    if (KT > 0) load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
+  }
+
+  // one iteration; R_ = kt % 3 fixes the LDS stages at compile time
+  auto body = [&](auto R_, auto STEADY_, int kt) {
+    constexpr int r = decltype(R_)::value;
+    constexpr bool steady = decltype(STEADY_)::value;
+    constexpr int s_nxt = (r + 1) % 3, s_wr = (r + 2) % 3;
+    uint16_t* const cur = smem + r * kStageElems;
+    uint16_t* const nxt = smem + s_nxt * kStageElems;
+    uint16_t* const wr = smem + s_wr * kStageElems;
+    if constexpr (steady) {
+      interleave_reads_commits<0, TM, TN, BM, BN>(cur, cur + kAElems, wr, wr + kAElems, wm0, wn0, fa1, fb1, la, lb);
+      mfma_step<TM, TN>(fa0, fb0, acc);
+      la.template fetch<0>((kt + 3) * BK); lb.template fetch<0>((kt + 3) * BK);
+      la.bounds((kt + 4) * BK);
+      load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
+      mfma_step<TM, TN>(fa1, fb1, acc);
+      constexpr int kPairs = TM * TN / 2;             // MFMA pairs per half
+      constexpr int kDsw = (LoadA::kDsWrites + LoadB::kDsWrites + kPairs - 1) / kPairs;
+      constexpr int kVm = (LoadA::kVmemReads + LoadB::kVmemReads + kPairs - 1) / kPairs;
+      constexpr int kDsr = (TM + TN + kPairs - 1) / kPairs;
+#pragma unroll
+      for (int i = 0; i < kPairs; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      // 2 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, kDsr, 0);   // LDS reads (fragments of k-step 1)
+        __builtin_amdgcn_sched_group_barrier(0x200, kDsw, 0);   // LDS writes (slice kt+2)
+      }
+#pragma unroll
+      for (int i = 0; i < kPairs; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      // 2 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x020, kVm, 0);    // global loads (slice kt+3)
+        __builtin_amdgcn_sched_group_barrier(0x100, kDsr, 0);   // LDS reads (first fragments of slice kt+1)
+      }
+    } else {
+      load_frags32<TM, TN, BM, BN>(cur, cur + kAElems, 1, wm0, wn0, fa1, fb1);
+      if (kt + 2 < KT) { commit_all<LoadA, 0>(la, wr); commit_all<LoadB, 0>(lb, wr + kAElems); }
+      mfma_step<TM, TN>(fa0, fb0, acc);
+      if (kt + 3 < KT) {
+        la.template fetch<0>((kt + 3) * BK); lb.template fetch<0>((kt + 3) * BK);
+        la.bounds((kt + 4) * BK);
+      }
+      if (kt + 1 < KT) load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
+      mfma_step<TM, TN>(fa1, fb1, acc);
+    }
+    __syncthreads();
+  };
+
+  int kt = 0;
+  if (long_k) {
+    do {                                // all three iterations fetch a real slice (kt+2+3 < KT)
+      body(IntC<0>(), std::true_type(), kt);
+      body(IntC<1>(), std::true_type(), kt + 1);
+      body(IntC<2>(), std::true_type(), kt + 2);
+      kt += 3;
+    } while (kt + 5 < KT);
+  }
+  for (; kt < KT; kt += 3) {          // drain; kt is a multiple of 3 here
+    body(IntC<0>(), std::false_type(), kt);
+    if (kt + 1 < KT) body(IntC<1>(), std::false_type(), kt + 1);
+    if (kt + 2 < KT) body(IntC<2>(), std::false_type(), kt + 2);
+  }
+
+  if constexpr (EPI == kEpiStore) {
+    epilogue_store_dispatch<AK, TM, TN, uint16_t, EDGE>(g, acc, m0, n0, wm0, wn0);
+  } else {
+    epilogue_fwd<uint16_t, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
+  }
+}
+
+}  // namespace rad

@@ -1,0 +1,15 @@
+// bf16 dW from the compressed store, kernels that keep 7 entries per lane (56 per store row and bucket) in
+// registers: A tiles are unpacked into LDS and contracted on v_mfma_f32_32x32x16_bf16.  The A tile is always
+// one whole 256-column bucket of the store.
+#include "gemm_launch.hpp"
+
+namespace rad {
+
+hipError_t launch_gemm_bf16_sparse7(const GemmArgs& g, hipStream_t st, const char** name) {
+  const bool big = tiles_of(g, 256, 256) >= 128;
+  if (name) *name = big ? "gemm_bf16_dw_sparse_256x256" : "gemm_bf16_dw_sparse_256x128";
+  if (big) return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 256, 7, false, true>(g, st);
+  return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 128, 7, false, true, false>(g, st);
+}
+
+}  // namespace rad

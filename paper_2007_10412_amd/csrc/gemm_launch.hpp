@@ -1,6 +1,6 @@
 // Launch helper shared by the GEMM instantiation files.
 #pragma once
-#include "gemm.hpp"
+#include "gemm_bf16.hpp"
 
 namespace rad {
 
@@ -48,6 +48,38 @@ hipError_t run_gemm(const GemmArgs& g, hipStream_t st) {
   }
   if (ma || mb) return run_gemm_variant<DT, AK, BKIND, EPI, BM, BN, BK, SE, kFlagEdge | FA | FB>(g, st);
   return run_gemm_variant<DT, AK, BKIND, EPI, BM, BN, BK, SE, kFlagEdge>(g, st);
+}
+
+// ---- bf16 ring-pipeline kernels (BK = 32, three LDS stages)
+template <int AK, int BKIND, int EPI, int BM, int BN, int SE, int FLAGS>
+hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
+  auto kern = gemm3_bf16_kernel<AK, BKIND, EPI, BM, BN, SE, FLAGS>;
+  constexpr int smem = Gemm3Smem<EPI, BM, BN>::BYTES;
+  static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
+  static bool prepared = false;   // one host thread drives a context
+  if (!prepared) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    prepared = true;
+  }
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(kGemmThreads), smem, st, g);
+  return hipGetLastError();
+}
+
+// Variants built per family: interior + guarded without a loader mask, and guarded with one (loader masks
+// serve the stand-alone entry points; the train steps mask in the producing epilogue instead).
+template <int AK, int BKIND, int EPI, int BM, int BN, int SE, bool MASK_A, bool MASK_B, bool BOTH_EDGE = true>
+hipError_t run_gemm3(const GemmArgs& g, hipStream_t st) {
+  if (g.dry_run) return hipSuccess;
+  const bool ma = MASK_A && g.a_mask != nullptr, mb = MASK_B && g.b_mask != nullptr;
+  if ((g.a_mask && !MASK_A) || (g.b_mask && !MASK_B)) return hipErrorInvalidValue;
+  constexpr int FA = MASK_A ? kFlagMaskA : 0, FB = MASK_B ? kFlagMaskB : 0;
+  if (ma || mb) return run_gemm3_variant<AK, BKIND, EPI, BM, BN, SE, kFlagEdge | FA | FB>(g, st);
+  if (BOTH_EDGE && gemm_is_full<BF16Tag, AK, BM, BN, 32>(g)) return run_gemm3_variant<AK, BKIND, EPI, BM, BN, SE, 0>(g, st);
+  return run_gemm3_variant<AK, BKIND, EPI, BM, BN, SE, kFlagEdge>(g, st);
 }
 
 hipError_t launch_gemm_f32(int a_kind, int b_kind, int epi, const GemmArgs& g, hipStream_t st, const char** name);

@@ -19,6 +19,7 @@ struct PlanArgs {
   int nb;
   uint32_t* row_cnt;   // [plan_rows], Bernoulli only
   uint32_t* row_ptr;   // [steps*rows + 1], written here for the fixed-k schemes
+  int* max_seg;        // running maximum of entries per (row, 256-column bucket)
 };
 
 hipError_t launch_plan(const PlanArgs& a, hipStream_t st);
@@ -53,6 +54,7 @@ struct GemmArgs {
   // kEpiStore
   void* C; int64_t ldc; int beta; int c_dtype;   // c_dtype: kF32 or kBF16
   const uint16_t* row_map;      // output row of tile row r (null = r)
+  const uint32_t* c_mask; int c_mask_pitch;      // kEpiStore: zero C[m,n] where bit n%32 of c_mask[m*pitch + n/32] is 0
   // kEpiFwd
   const float* bias; int relu;
   void* y; int64_t ldy;         // dense output, operand dtype
@@ -75,5 +77,14 @@ hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint3
                          const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
                          int beta, float* partial, int splits, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t st);
+// Adds to dW the entries of (row, bucket) segments beyond the first `cap`, which the MFMA kernel leaves out;
+// exits at once when *max_seg <= cap (the plan's running maximum), which is the normal case.
+hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int dtype, int N, const uint32_t* bits,
+                              int bits_pitch, float* dW, int cap, const int* max_seg, hipStream_t st);
+// entries per (row, bucket) the bf16 sparse dW kernel chosen for `sparse_prefetch` handles itself
+int gemm_bf16_sparse_cap(int sparse_prefetch);
+int gemm_bf16_sparse_max_prefetch();
+// dense[rows, cols] = the store's rows scattered back (zeros elsewhere): x~ as a dense operand
+hipError_t launch_unpack(const StoreView& s, int dtype, void* dense, hipStream_t st);
 
 }  // namespace rad

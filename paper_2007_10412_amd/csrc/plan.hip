@@ -55,6 +55,7 @@ __device__ __forceinline__ void finish_row(const PlanArgs& a, int prow, const ui
     for (int w = 0; w < kBucket / 32; ++w)
       if (w0 + w < a.bm_pitch) cnt += __popc(s_bm[w0 + w]);
   }
+  if (a.max_seg && tid < a.nb && cnt > 0) atomicMax(a.max_seg, cnt);
   int total;
   const int off = block_excl_scan(cnt, &total, s_scan);
   uint16_t* bo = a.bucket_off + (size_t)prow * (a.nb + 1);
@@ -306,7 +307,26 @@ __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ x, Stor
   }
 }
 
+// One workgroup per store row: clear the dense row, then scatter the row's entries into it.
+template <typename T>
+__global__ __launch_bounds__(256) void unpack_kernel(StoreView s, T* __restrict__ dense) {
+  const int row = blockIdx.x;
+  T* out = dense + (size_t)row * s.cols;
+  for (int j = threadIdx.x; j < s.cols; j += 256) out[j] = T(0);
+  __syncthreads();
+  int64_t beg = s.row_ptr[row], end = s.row_ptr[row + 1];
+  if (end > s.capacity) end = s.capacity;
+  const T* vals = reinterpret_cast<const T*>(s.values);
+  for (int64_t e = beg + threadIdx.x; e < end; e += 256) out[s.indices[e]] = vals[e];
+}
+
 }  // namespace
+
+hipError_t launch_unpack(const StoreView& s, int dtype, void* dense, hipStream_t st) {
+  if (dtype == kF32) hipLaunchKernelGGL(unpack_kernel<float>, dim3(s.rows), dim3(256), 0, st, s, (float*)dense);
+  else hipLaunchKernelGGL(unpack_kernel<uint16_t>, dim3(s.rows), dim3(256), 0, st, s, (uint16_t*)dense);
+  return hipGetLastError();
+}
 
 hipError_t launch_plan(const PlanArgs& a, hipStream_t st) {
   dim3 grid(a.plan_rows), block(kPlanThreads);
@@ -315,7 +335,8 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(plan_bernoulli_kernel, grid, block, 0, st, a);
     return hipGetLastError();
   }
-  const int nq_max = a.cols / 4 + 2;
+  // rows start on a Philox call boundary when cols is a multiple of 4
+  const int nq_max = (a.cols % 4 == 0) ? a.cols / 4 : a.cols / 4 + 2;
   const int qpt = (nq_max + kPlanThreads - 1) / kPlanThreads;
   if (qpt <= 1) hipLaunchKernelGGL(plan_fixedk_kernel<1>, grid, block, 0, st, a);
   else if (qpt <= 4) hipLaunchKernelGGL(plan_fixedk_kernel<4>, grid, block, 0, st, a);

@@ -111,6 +111,36 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
   }
 }
 
+// Entries of a (store row, bucket) segment beyond the first `cap` are left out by the MFMA dW kernel,
+// whose registers hold `cap` of them; this kernel adds their contribution dW[j, :] += value * g[b, :].
+// One wave per segment.  *max_seg is the plan's running maximum segment length: the kernel leaves at once
+// when no segment is that long, which is the normal case (cap sits six standard deviations above the mean).
+template <typename T>
+__global__ __launch_bounds__(256) void dw_overflow_kernel(StoreView s, int rows, const T* __restrict__ dy, int N,
+                                                          const uint32_t* __restrict__ bits, int bits_pitch,
+                                                          float* __restrict__ dW, int cap,
+                                                          const int* __restrict__ max_seg) {
+  if (*max_seg <= cap) return;
+  const int lane = threadIdx.x & 63;
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg >= rows * s.nb) return;
+  const int b = seg / s.nb, t = seg % s.nb;
+  const uint16_t* bo = s.bucket_off + (size_t)(b * s.plan_row_stride) * (s.nb + 1) + t;
+  const int64_t base = s.row_ptr[b];
+  int64_t beg = base + bo[0], end = base + bo[1];
+  if (end > s.capacity) end = s.capacity;
+  const T* vals = reinterpret_cast<const T*>(s.values);
+  for (int64_t e = beg + cap; e < end; ++e) {
+    const int j = s.indices[e];
+    const float v = ld_elem(vals + e);
+    for (int n = lane; n < N; n += 64) {
+      float g = ld_elem(dy + (size_t)b * N + n);
+      if (bits && !((bits[(size_t)b * bits_pitch + (n >> 5)] >> (n & 31)) & 1u)) g = 0.f;
+      atomicAdd(&dW[(size_t)j * N + n], v * g);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p, uint32_t v, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = v;
@@ -144,6 +174,19 @@ hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint3
                        bits_pitch, u, u_ld, u_n, partial, splits);
   hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 255) / 256), dim3(256), 0, st, partial, splits, N, u_n, out_bias,
                      out_u, beta);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int dtype, int N, const uint32_t* bits,
+                              int bits_pitch, float* dW, int cap, const int* max_seg, hipStream_t st) {
+  const int segs = rows * s.nb;
+  dim3 grid((segs + 3) / 4), block(256);
+  if (dtype == kF32)
+    hipLaunchKernelGGL(dw_overflow_kernel<float>, grid, block, 0, st, s, rows, (const float*)dy, N, bits, bits_pitch,
+                       dW, cap, max_seg);
+  else
+    hipLaunchKernelGGL(dw_overflow_kernel<uint16_t>, grid, block, 0, st, s, rows, (const uint16_t*)dy, N, bits,
+                       bits_pitch, dW, cap, max_seg);
   return hipGetLastError();
 }
 
