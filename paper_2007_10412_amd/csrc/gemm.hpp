@@ -566,12 +566,39 @@ __device__ __forceinline__ void epilogue_store_dispatch(const GemmArgs& g, float
 // the second phase runs row by row with lane l on columns l, l+64, ...: dense
 // y stores are contiguous, a wave ballot of (y > 0) IS two words of the ReLU
 // bit array, and the keep bits of the next layer's plan give every kept entry
-// its slot in the packed row with a popcount.
+// its slot in the packed row with a popcount.  Wave w owns tile rows w, w+4,
+// ...; lane l fetches the plan data (row start, keep words) of the l-th of
+// them up front, in one round of loads, and the row loop reads them back with
+// v_readlane, so no global latency sits inside the loop.
 template <typename ElemT, int BM, int BN, int TM, int TN>
 __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[TM][TN], ElemT* ct, int m0, int n0,
                                              int wm0, int wn0) {
   constexpr int CP = BN + (sizeof(ElemT) == 4 ? 1 : 2);   // odd word pitch
+  constexpr int RPWV = BM / 4;                            // rows per wave (<= 64)
+  constexpr int NW = BN / 32;                             // keep words per tile row
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+
+  // plan data of row w + 4*lane
+  uint32_t kw[NW];
+  int rel_l = 0;
+  uint32_t base_l = 0;
+#pragma unroll
+  for (int q = 0; q < NW; ++q) kw[q] = 0u;
+  if (g.pack) {
+    const int row = m0 + w + 4 * lane;
+    if (lane < RPWV && row < g.M) {
+      const int prow = row * g.next.plan_row_stride;
+      const uint32_t* bm_row = g.next.bitmap + (size_t)prow * g.next.bm_pitch;
+      const int bucket = n0 / kBucket;
+      base_l = g.next.row_ptr[row];
+      rel_l = g.next.bucket_off[(size_t)prow * (g.next.nb + 1) + bucket];
+      for (int wd = bucket * (kBucket / 32); wd < n0 / 32; ++wd) rel_l += __popc(bm_row[wd]);
+#pragma unroll
+      for (int q = 0; q < NW; ++q)
+        if (n0 / 32 + q < g.next.bm_pitch) kw[q] = bm_row[n0 / 32 + q];
+    }
+  }
+
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -592,20 +619,12 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
     }
   __syncthreads();
   ElemT* Y = reinterpret_cast<ElemT*>(g.y);
-  for (int r = w; r < BM; r += 4) {
+  for (int ri = 0; ri < RPWV; ++ri) {
+    const int r = w + 4 * ri;
     const int row = m0 + r;
     if (row >= g.M) break;
-    int rel = 0;                       // slot inside the packed row of the next store
-    int64_t base = 0;
-    const uint32_t* bm_row = nullptr;
-    if (g.pack) {
-      const int prow = row * g.next.plan_row_stride;
-      bm_row = g.next.bitmap + (size_t)prow * g.next.bm_pitch;
-      const int bucket = n0 / kBucket;
-      base = (int64_t)g.next.row_ptr[row];
-      rel = g.next.bucket_off[(size_t)prow * (g.next.nb + 1) + bucket];
-      for (int wd = bucket * (kBucket / 32); wd < n0 / 32; ++wd) rel += __popc(bm_row[wd]);
-    }
+    int rel = __builtin_amdgcn_readlane(rel_l, ri);       // slot inside the packed row of the next store
+    const int64_t base = (int64_t)(uint32_t)__builtin_amdgcn_readlane((int)base_l, ri);
 #pragma unroll
     for (int c0 = 0; c0 < BN; c0 += 64) {
       const int col = n0 + c0 + lane;
@@ -619,12 +638,11 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
         if (lane == 32 && wi + 1 < g.bits_pitch) g.bits[(size_t)row * g.bits_pitch + wi + 1] = (uint32_t)(bal >> 32);
       }
       if (g.pack) {
-        const int wi = (n0 + c0) / 32;
-        uint64_t kw = 0;
-        if (wi < g.next.bm_pitch) kw = bm_row[wi];
-        if (wi + 1 < g.next.bm_pitch) kw |= (uint64_t)bm_row[wi + 1] << 32;
-        if ((kw >> lane) & 1ull) {
-          const int r2 = rel + __popcll(kw & ((1ull << lane) - 1ull));
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)kw[c0 / 32], ri);
+        const uint32_t hi = (c0 / 32 + 1 < NW) ? (uint32_t)__builtin_amdgcn_readlane((int)kw[(c0 / 32 + 1) % NW], ri) : 0u;
+        const uint64_t kw64 = (uint64_t)lo | ((uint64_t)hi << 32);
+        if ((kw64 >> lane) & 1ull) {
+          const int r2 = rel + __popcll(kw64 & ((1ull << lane) - 1ull));
           const int64_t p = base + r2;
           if (p < g.next.capacity) {
             put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv * g.next.scale);
@@ -632,7 +650,7 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
             else if (row == 0) g.next.indices[r2] = (uint16_t)col;
           }
         }
-        rel += __popcll(kw);
+        rel += __popcll(kw64);
       }
     }
   }

@@ -1,0 +1,78 @@
+"""GPU parity of rad_train_step on the ReLU RNN (config 5): forward, BPTT from
+per-step sampled hidden states, every gradient against the oracle."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import rad_oracle as R
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2007_10412_amd import binding as B
+    c = B.rad_ctx_create()
+    yield c
+    B.rad_ctx_destroy(c)
+
+
+def run_rnn(ctx, d, scheme, p, seed, check_store=True):
+    from paper_2007_10412_amd import binding as B
+    from tests.gpu_util import dev, host, empty, rel_err
+    Bt, T, I = d["x"].shape
+    H, C = d["W_ho"].shape
+    print("rnn B=%d T=%d I=%d H=%d scheme=%d p=%g" % (Bt, T, I, H, scheme, p), flush=True)
+    m = B.rad_model_create_rnn(ctx, Bt, T, I, H, C, scheme, p)
+    try:
+        names = ["W_ih", "W_hh", "b", "W_ho", "b_o"]
+        params = [dev(d[n]) for n in names]
+        grads = [empty(d[n].shape) for n in names]
+        loss = B.rad_train_step(ctx, m, B.make_sampling(scheme, p, seed, 20, 0), dev(d["x"]), dev(d["labels"]),
+                                params, grads)
+        ref = R.rnn_train_step(d["x"], d["labels"], d["W_ih"], d["W_hh"], d["b"], d["W_ho"], d["b_o"],
+                               scheme, p, seed, stream_base=20)
+        assert abs(loss - ref["loss"]) < 1e-5 * max(1.0, abs(ref["loss"])), (loss, ref["loss"])
+        if check_store and scheme != 0 and T > 1:
+            # sampling decisions of every step: rows t*B..(t+1)*B-1 of the multi-step store hold step t+2
+            rp, col, val = B.rad_store_export_csr(ctx, B.rad_model_store(m, 0), (T - 1) * Bt)
+            for t in (2, T):      # first and last stored step
+                mask = R.keep_mask(scheme, p, seed, 20, t, Bt, H)
+                s = t - 2
+                for b in (0, Bt - 1):
+                    r = s * Bt + b
+                    assert np.array_equal(col[rp[r]:rp[r + 1]], np.nonzero(mask[b])[0]), (t, b)
+        out = {}
+        for n, key in zip(names, ["dW_ih", "dW_hh", "db", "dW_ho", "db_o"]):
+            e = rel_err(host(grads[names.index(n)]), ref[key])
+            out[key] = e
+            assert e < 1e-4, (key, e)
+        return out
+    finally:
+        B.rad_model_destroy(m)
+
+
+@pytest.mark.parametrize("scheme,p", [(1, 0.1), (3, 0.25), (2, 0.25), (0, 1.0), (1, 1.0)])
+def test_rnn_small_general_weights(ctx, scheme, p):
+    from paper_2007_10412_amd import synth
+    d = synth.rnn(seed=3, batch=20, T=9, d_input=1, hidden=96, classes=10, identity=False)
+    run_rnn(ctx, d, scheme, p, seed=8)
+
+
+def test_rnn_two_inputs_ragged(ctx):
+    from paper_2007_10412_amd import synth
+    d = synth.rnn(seed=4, batch=7, T=5, d_input=2, hidden=70, classes=6, identity=False)
+    run_rnn(ctx, d, 1, 0.3, seed=2)
+
+
+def test_rnn_single_step(ctx):
+    from paper_2007_10412_amd import synth
+    d = synth.rnn(seed=5, batch=9, T=1, d_input=1, hidden=64, classes=10, identity=False)
+    run_rnn(ctx, d, 1, 0.5, seed=2, check_store=False)
+
+
+def test_config5_reduced_length(ctx):
+    """Config 5's widths (batch 128, hidden 1024, identity W_hh) with T = 48: the oracle's 784-step
+    BPTT in fp64 takes minutes, the structure of every step is the same."""
+    from paper_2007_10412_amd import synth
+    d = synth.rnn(seed=1234, batch=128, T=48, d_input=1, hidden=1024, classes=10, identity=True)
+    run_rnn(ctx, d, 1, 0.1, seed=5)
