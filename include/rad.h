@@ -227,6 +227,10 @@ rad_status rad_model_destroy(rad_model* model);
 /* Number of stores and borrowed access to store l (for export and stats). */
 int32_t rad_model_num_stores(const rad_model* model);
 rad_store* rad_model_store(rad_model* model, int32_t l);
+/* Synchronises.  CNN models: the 2-bit max-pool window positions (dy*2+dx of the first maximum) kept for
+ * conv layer l, one byte per pooled output, to a HOST array [batch*c_out*(h/2)*(w/2)]; RAD_ERR_PARAM if the
+ * layer has no pool. */
+rad_status rad_model_export_pool_arg(rad_ctx* ctx, const rad_model* model, int32_t l, uint8_t* out);
 /* Device pointer to the logits of the last step ([batch, classes], model dtype). */
 const void* rad_model_logits(const rad_model* model);
 

@@ -364,10 +364,14 @@ def maxpool2x2_backward(dout, arg):
     return win.reshape(b, c, ho * 2, wo * 2)
 
 
-def cnn_train_step(x, labels, convs, fc, scheme, p, seed, stream_base=0, step=0):
+def cnn_train_step(x, labels, convs, fc, scheme, p, seed, stream_base=0, step=0,
+                   bits_override=None, arg_override=None):
     """convs: list of dicts(W [ci,kh,kw,co], b [co], pad, pool bool); every conv
     is followed by ReLU and, if pool, a 2x2 max pool.  fc = (W [D,10], b).
-    Each conv input and the FC input is sampled (flattened per example)."""
+    Each conv input and the FC input is sampled (flattened per example).
+    bits_override / arg_override (lists, entries may be None) replace the ReLU
+    bits / pool positions used in the backward pass, for tests that feed one
+    side's near-tie decisions to the other."""
     act = np.asarray(x, dtype=np.float32)
     B = act.shape[0]
     tape, stores = [], []
@@ -379,6 +383,10 @@ def cnn_train_step(x, labels, convs, fc, scheme, p, seed, stream_base=0, step=0)
         in_shape = act.shape
         if cv["pool"]:
             y, arg = maxpool2x2_forward(y)
+        if bits_override is not None and bits_override[l] is not None:
+            bits = bits_override[l]
+        if arg_override is not None and arg_override[l] is not None:
+            arg = arg_override[l]
         tape.append((in_shape, bits, arg))
         act = y.astype(np.float32)
     flat = act.reshape(B, -1)
@@ -404,7 +412,7 @@ def cnn_train_step(x, labels, convs, fc, scheme, p, seed, stream_base=0, step=0)
         if l > 0:
             dy = conv2d_dX(g, cv["W"], cv["pad"], in_shape[2:]).astype(np.float32)
     return dict(loss=loss, dW=dWs, db=dbs, dW_fc=dW_fc, db_fc=db_fc,
-                stores=stores, logits=z)
+                stores=stores, logits=z, tape=tape)
 
 
 # ----------------------------------------------------------------------------

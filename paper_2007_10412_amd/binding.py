@@ -68,6 +68,7 @@ SIGNATURES = {
     "rad_model_num_stores": (C.c_int32, [P]),
     "rad_model_store": (P, [P, C.c_int32]),
     "rad_model_logits": (P, [P]),
+    "rad_model_export_pool_arg": (C.c_int, [P, P, C.c_int32, P]),
     "rad_train_step": (C.c_int, [P, P, C.POINTER(rad_sampling), P, P, C.POINTER(P), C.POINTER(P),
                                  C.POINTER(C.c_float)]),
 }
@@ -257,6 +258,12 @@ def rad_model_num_stores(model):
 
 def rad_model_store(model, l):
     return C.c_void_p(lib().rad_model_store(model, l))
+
+
+def rad_model_export_pool_arg(ctx, model, l, n):
+    out = np.zeros(n, dtype=np.uint8)
+    _check(ctx, lib().rad_model_export_pool_arg(ctx, model, l, out.ctypes.data))
+    return out
 
 
 def rad_model_logits(model):

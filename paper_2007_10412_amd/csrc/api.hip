@@ -27,12 +27,12 @@ struct rad_ctx {
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
   // grow-only workspaces
-  void* ws[4] = {nullptr, nullptr, nullptr, nullptr};
-  size_t ws_bytes[4] = {0, 0, 0, 0};
+  void* ws[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  size_t ws_bytes[6] = {0, 0, 0, 0, 0, 0};
   float* loss_dev = nullptr;
 };
 
-enum { WS_BITMAP = 0, WS_DENSE = 1, WS_ROWLOSS = 2, WS_COLSUM = 3 };
+enum { WS_BITMAP = 0, WS_DENSE = 1, WS_ROWLOSS = 2, WS_COLSUM = 3, WS_SPLITK = 4, WS_WT = 5 };
 
 static const char* kNoCtx = "no context";
 
@@ -118,7 +118,7 @@ extern "C" rad_status rad_ctx_destroy(rad_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   for (auto& e : c->pool) (void)hipEventDestroy(e);
-  for (int i = 0; i < 4; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
+  for (int i = 0; i < 6; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
   if (c->loss_dev) (void)hipFree(c->loss_dev);
   delete c;
   return RAD_OK;
@@ -252,7 +252,8 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   if (steps < 1) return fail(c, RAD_ERR_SHAPE, "steps must be >= 1");
   if (scheme != RAD_EXACT) {
     if (L->d_in > 65535) return fail(c, RAD_ERR_UNSUPPORTED, "sampled stores need d_in <= 65535 (16-bit indices)");
-    if (L->d_in > plan_max_cols(scheme)) return fail(c, RAD_ERR_UNSUPPORTED, "fixed-k sampling needs d_in <= 16376");
+    if (L->d_in > plan_max_cols(scheme) || (scheme != RAD_BERNOULLI && L->d_in > 16376 && L->d_in % 4 != 0))
+      return fail(c, RAD_ERR_UNSUPPORTED, "fixed-k sampling needs d_in <= 16384 (16376 unless a multiple of 4)");
   }
   const double total_rows = (double)steps * (double)L->batch;
   if (total_rows * (double)L->d_in >= 4294967296.0) return fail(c, RAD_ERR_SHAPE, "store above 2^32 entries");
@@ -636,14 +637,21 @@ struct rad_model {
   int64_t T = 0, d_input = 0, hidden = 0, classes = 0;
   uint32_t* rnn_bits = nullptr;         // [T][batch][hidden/32]
   uint32_t* bitmap_ws = nullptr;        // keep bitmaps of every step (transient within a step)
+  // CNN
+  struct Conv { int ci, co, h, w, pool; uint32_t* arg; };
+  std::vector<Conv> convs;
+  int ksize = 0, fc_in = 0;
+  void* buf[3] = {nullptr, nullptr, nullptr};   // transient dense activations / gradients
   size_t elem() const { return dtype == kBF16 ? 2 : 4; }
 };
 
 extern "C" rad_status rad_model_destroy(rad_model* m) {
   if (!m) return RAD_ERR_NULL;
   for (rad_store* s : m->stores) if (s) rad_store_destroy(s);
-  for (void* p : {m->act[0], m->act[1], m->dyb[0], m->dyb[1], m->logits, (void*)m->rnn_bits, (void*)m->bitmap_ws})
+  for (void* p : {m->act[0], m->act[1], m->dyb[0], m->dyb[1], m->logits, (void*)m->rnn_bits, (void*)m->bitmap_ws,
+                  m->buf[0], m->buf[1], m->buf[2]})
     if (p) (void)hipFree(p);
+  for (auto& cv : m->convs) if (cv.arg) (void)hipFree(cv.arg);
   delete m;
   return RAD_OK;
 }
@@ -653,6 +661,19 @@ extern "C" rad_store* rad_model_store(rad_model* m, int32_t l) {
   return (m && l >= 0 && l < (int32_t)m->stores.size()) ? m->stores[(size_t)l] : nullptr;
 }
 extern "C" const void* rad_model_logits(const rad_model* m) { return m ? m->logits : nullptr; }
+
+extern "C" rad_status rad_model_export_pool_arg(rad_ctx* c, const rad_model* m, int32_t l, uint8_t* out) {
+  if (!c) return RAD_ERR_NULL;
+  if (!m || !out) return fail(c, RAD_ERR_NULL, "null argument");
+  if (l < 0 || l >= (int32_t)m->convs.size() || !m->convs[(size_t)l].arg) return fail(c, RAD_ERR_PARAM, "layer has no pool");
+  const rad_model::Conv& cv = m->convs[(size_t)l];
+  const size_t n = (size_t)m->batch * cv.co * (cv.h / 2) * (cv.w / 2);
+  std::vector<uint32_t> words((n + 15) / 16);
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(words.data(), cv.arg, words.size() * 4, hipMemcpyDeviceToHost));
+  for (size_t q = 0; q < n; ++q) out[q] = (uint8_t)((words[q / 16] >> (2 * (q % 16))) & 3u);
+  return RAD_OK;
+}
 
 extern "C" rad_status rad_model_create_mlp(rad_ctx* c, int32_t dtype, int64_t batch, int32_t n_layers,
                                            const int64_t* dims, int32_t has_bias, int32_t scheme, double p,
@@ -866,11 +887,171 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   return stores_overflowed(c, m);
 }
 
-extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t, int32_t, const int32_t*, const int32_t*, int32_t,
-                                           int32_t, int32_t, int32_t, int32_t, double, rad_model** out) {
+extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t batch, int32_t n_conv, const int32_t* channels,
+                                           const int32_t* pool, int32_t ksize, int32_t height, int32_t width,
+                                           int32_t classes, int32_t scheme, double p, rad_model** out) {
   if (!c) return RAD_ERR_NULL;
-  if (out) *out = nullptr;
-  return fail(c, RAD_ERR_UNSUPPORTED, "the convolutional model is not built yet");
+  if (!out || !channels || !pool) return fail(c, RAD_ERR_NULL, "null argument");
+  *out = nullptr;
+  RAD_TRY(check_scheme(c, scheme, p));
+  if (n_conv < 1 || n_conv > 32 || batch < 1 || classes < 1 || ksize < 1 || (ksize & 1) == 0)
+    return fail(c, RAD_ERR_SHAPE, "bad CNN shape (odd kernel size, at least one conv)");
+  rad_model* m = new rad_model();
+  m->kind = kCnn; m->dtype = kF32; m->scheme = scheme; m->p = p; m->batch = batch; m->ksize = ksize;
+  m->classes = classes; m->has_bias = 1;
+  int h = height, w = width;
+  size_t widest = (size_t)channels[0] * h * w;
+  for (int l = 0; l < n_conv; ++l) {
+    if (channels[l] < 1 || channels[l + 1] < 1 || h < 1 || w < 1 || (h * w) % 64 != 0 || channels[l + 1] > 64) {
+      rad_model_destroy(m);
+      return fail(c, RAD_ERR_UNSUPPORTED, "conv layers need H*W a multiple of 64 and at most 64 output channels");
+    }
+    rad_layer L; std::memset(&L, 0, sizeof(L));
+    L.kind = RAD_CONV2D; L.dtype = RAD_F32; L.batch = batch;
+    L.c_in = channels[l]; L.c_out = channels[l + 1]; L.h = h; L.w = w; L.kh = L.kw = ksize; L.pad = (ksize - 1) / 2;
+    L.d_in = (int64_t)L.c_in * h * w; L.d_out = (int64_t)L.c_out * h * w; L.relu = 1; L.has_bias = 1;
+    rad_store* s = nullptr;
+    rad_status st = rad_store_create(c, &L, scheme, p, 1, &s);
+    if (st != RAD_OK) { rad_model_destroy(m); return st; }
+    m->stores.push_back(s);
+    rad_model::Conv cv{channels[l], channels[l + 1], h, w, pool[l] ? 1 : 0, nullptr};
+    if ((size_t)L.d_out > widest) widest = (size_t)L.d_out;
+    if (cv.pool) {
+      if ((h & 1) || (w & 1)) { rad_model_destroy(m); return fail(c, RAD_ERR_SHAPE, "pooled layers need even H and W"); }
+      const size_t words = ((size_t)batch * cv.co * (h / 2) * (w / 2) + 15) / 16;
+      if (hipMalloc((void**)&cv.arg, words * 4) != hipSuccess) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+      h /= 2; w /= 2;
+    }
+    m->convs.push_back(cv);
+  }
+  m->fc_in = channels[n_conv] * h * w;
+  rad_layer L; std::memset(&L, 0, sizeof(L));
+  L.kind = RAD_LINEAR; L.dtype = RAD_F32; L.batch = batch; L.d_in = m->fc_in; L.d_out = classes; L.has_bias = 1;
+  rad_store* s = nullptr;
+  rad_status st = rad_store_create(c, &L, scheme, p, 1, &s);
+  if (st != RAD_OK) { rad_model_destroy(m); return st; }
+  m->stores.push_back(s);
+  bool ok = true;
+  for (int i = 0; i < 3; ++i) ok = ok && hipMalloc(&m->buf[i], (size_t)batch * widest * 4) == hipSuccess;
+  ok = ok && hipMalloc(&m->logits, (size_t)batch * classes * 4) == hipSuccess;
+  ok = ok && hipMalloc(&m->dyb[0], (size_t)batch * classes * 4) == hipSuccess;
+  if (!ok) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+  *out = m;
+  return RAD_OK;
+}
+
+// conv as implicit im2col GEMM: y[B,co,h,w] = act(conv(src[B,ci,h,w], W[(ci,k,k)][co]) + bias)
+static rad_status conv_gemm(rad_ctx* c, int B, int ci, int co, int h, int w, int ks, const float* src, const float* W,
+                            const float* bias, int relu, float* y, uint32_t* bits, int bits_pitch) {
+  GemmArgs g = gemm_zero();
+  g.M = B * h * w; g.N = co; g.K = ci * ks * ks;
+  g.A = src; g.B = W; g.ldb = co;
+  g.cv_C = ci; g.cv_H = h; g.cv_W = w; g.cv_KH = ks; g.cv_KW = ks; g.cv_pad = (ks - 1) / 2; g.cv_N = co;
+  g.bias = bias; g.relu = relu; g.y = y; g.bits = relu ? bits : nullptr; g.bits_pitch = bits_pitch;
+  return run_gemm_call(c, kF32, kOpIm2colRows, kOpMN, kEpiConv, g);
+}
+
+// params/grads order: W_0, b_0, ..., W_{n-1}, b_{n-1}, W_fc, b_fc
+static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, const void* x, const int32_t* labels,
+                           void* const* params, void* const* grads, float* loss_host) {
+  const int nc = (int)m->convs.size();
+  const int B = (int)m->batch, ks = m->ksize, C = (int)m->classes;
+  for (int i = 0; i < 2 * (nc + 1); ++i)
+    if (!params[i] || !grads[i]) return fail(c, RAD_ERR_NULL, "null parameter or gradient pointer");
+  size_t bm_words = 0;
+  for (rad_store* s : m->stores) if (s->bitmap_words() > bm_words) bm_words = s->bitmap_words();
+  void* bm = nullptr;
+  if (bm_words) RAD_TRY(ws_get(c, WS_BITMAP, bm_words * 4, &bm));
+
+  // forward: every conv input is sampled (flattened per example), then convolved exactly
+  const float* act = static_cast<const float*>(x);
+  int in_buf = -1;                    // buffer index holding `act` (-1: caller's x)
+  for (int l = 0; l < nc; ++l) {
+    const rad_model::Conv& cv = m->convs[(size_t)l];
+    rad_store* s = m->stores[(size_t)l];
+    rad_sampling sl = *sm; sl.stream_id = sm->stream_id + (uint32_t)l;
+    RAD_TRY(store_plan(c, s, &sl, static_cast<uint32_t*>(bm)));
+    RAD_TRY(store_pack(c, s, act, 0));
+    const int yb = (in_buf + 1 + 3) % 3, pb = (in_buf + 2 + 3) % 3;
+    RAD_TRY(conv_gemm(c, B, cv.ci, cv.co, cv.h, cv.w, ks, act, static_cast<const float*>(params[2 * l]),
+                      static_cast<const float*>(params[2 * l + 1]), 1, static_cast<float*>(m->buf[yb]), s->bits,
+                      s->bits_pitch));
+    if (cv.pool) {
+      HIP_TRY(c, timed(c, "maxpool", [&](const char**) {
+        return launch_maxpool_fwd(static_cast<const float*>(m->buf[yb]), B * cv.co, cv.h, cv.w,
+                                  static_cast<float*>(m->buf[pb]), cv.arg, c->stream);
+      }));
+      act = static_cast<const float*>(m->buf[pb]); in_buf = pb;
+    } else { act = static_cast<const float*>(m->buf[yb]); in_buf = yb; }
+  }
+  rad_store* sfc = m->stores[(size_t)nc];
+  {
+    rad_sampling sl = *sm; sl.stream_id = sm->stream_id + (uint32_t)nc;
+    RAD_TRY(store_plan(c, sfc, &sl, static_cast<uint32_t*>(bm)));
+    RAD_TRY(store_pack(c, sfc, act, 0));
+  }
+  RAD_TRY(forward_gemm(c, kF32, B, C, m->fc_in, act, m->fc_in, params[2 * nc], static_cast<const float*>(params[2 * nc + 1]),
+                       0, m->logits, nullptr, 0, nullptr, nullptr, 0, 0, nullptr));
+  RAD_TRY(softmax_call(c, m->logits, labels, B, C, kF32, m->dyb[0], c->loss_dev));
+
+  // backward
+  RAD_TRY(dW_gemm(c, sfc, 0, m->dyb[0], C, nullptr, 0, static_cast<float*>(grads[2 * nc]), 0));
+  RAD_TRY(colsum_call(c, m->dyb[0], kF32, B, C, nullptr, 0, nullptr, 0, 0, static_cast<float*>(grads[2 * nc + 1]),
+                      nullptr, 0));
+  int db_ = (in_buf + 1) % 3;          // upstream gradient buffer; the forward activations are dead by now
+  RAD_TRY(dX_gemm(c, kF32, B, m->fc_in, C, m->dyb[0], nullptr, 0, params[2 * nc], m->buf[db_]));
+  for (int l = nc - 1; l >= 0; --l) {
+    const rad_model::Conv& cv = m->convs[(size_t)l];
+    rad_store* s = m->stores[(size_t)l];
+    const int HW = cv.h * cv.w;
+    const int gb = (db_ + 1) % 3, nb_ = (db_ + 2) % 3;
+    float* g = static_cast<float*>(m->buf[gb]);
+    // g = dL/dh of this layer: route through the pool, then the 1-bit ReLU Jacobian (Section 4.2)
+    HIP_TRY(c, timed(c, "unpool_mask", [&](const char**) {
+      return launch_unpool_mask(static_cast<const float*>(m->buf[db_]), B, cv.co, cv.h, cv.w, cv.arg, s->bits,
+                                s->bits_pitch, g, c->stream);
+    }));
+    // dW from the sampled input (Figure 5): x~ scattered back to a dense transient, contracted with g
+    const void* xt = s->values;
+    if (s->scheme != RAD_EXACT) {
+      void* dense = nullptr;
+      RAD_TRY(ws_get(c, WS_DENSE, (size_t)B * s->cols * 4, &dense));
+      const StoreView v = store_view(s, 0);
+      HIP_TRY(c, timed(c, "unpack", [&](const char**) { return launch_unpack(v, kF32, dense, c->stream); }));
+      xt = dense;
+    }
+    GemmArgs a = gemm_zero();
+    a.M = cv.ci * ks * ks; a.N = cv.co; a.K = B * HW;
+    a.A = xt; a.B = g;
+    a.cv_C = cv.ci; a.cv_H = cv.h; a.cv_W = cv.w; a.cv_KH = ks; a.cv_KW = ks; a.cv_pad = (ks - 1) / 2; a.cv_N = cv.co;
+    a.k_split = 1024; a.k_splits = (a.K + a.k_split - 1) / a.k_split;
+    void* part = nullptr;
+    RAD_TRY(ws_get(c, WS_SPLITK, (size_t)a.k_splits * a.M * a.N * 4, &part));
+    a.C = part; a.ldc = a.N;
+    RAD_TRY(run_gemm_call(c, kF32, kOpIm2colK, kOpKBatched, kEpiSplitK, a));
+    HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
+      return launch_splitk_reduce(static_cast<const float*>(part), a.k_splits, (int64_t)a.M * a.N,
+                                  static_cast<float*>(grads[2 * l]), 0, c->stream);
+    }));
+    HIP_TRY(c, timed(c, "channel_sum", [&](const char**) {
+      return launch_channel_sum(g, B, cv.co, HW, static_cast<float*>(grads[2 * l + 1]), c->stream);
+    }));
+    if (l > 0) {
+      // dX: the transposed convolution, exact (never sampled)
+      void* wt = nullptr;
+      RAD_TRY(ws_get(c, WS_WT, (size_t)cv.co * ks * ks * cv.ci * 4, &wt));
+      HIP_TRY(c, timed(c, "flip_weights", [&](const char**) {
+        return launch_flip_weights(static_cast<const float*>(params[2 * l]), cv.ci, ks, ks, cv.co, static_cast<float*>(wt),
+                                   c->stream);
+      }));
+      RAD_TRY(conv_gemm(c, B, cv.co, cv.ci, cv.h, cv.w, ks, g, static_cast<const float*>(wt), nullptr, 0,
+                        static_cast<float*>(m->buf[nb_]), nullptr, 0));
+      db_ = nb_;
+    }
+  }
+  HIP_TRY(c, hipMemcpyAsync(loss_host, c->loss_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return stores_overflowed(c, m);
 }
 
 extern "C" rad_status rad_train_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, const void* x,
@@ -882,6 +1063,6 @@ extern "C" rad_status rad_train_step(rad_ctx* c, rad_model* m, const rad_samplin
   if (sm->scheme != m->scheme || sm->p != m->p) return fail(c, RAD_ERR_PARAM, "sampling does not match the model");
   if (m->kind == kMlp) return mlp_step(c, m, sm, x, labels, params, grads, loss_host);
   if (m->kind == kRnn) return rnn_step(c, m, sm, x, labels, params, grads, loss_host);
-  return fail(c, RAD_ERR_UNSUPPORTED, "model kind not built yet");
+  return cnn_step(c, m, sm, x, labels, params, grads, loss_host);
 }
 

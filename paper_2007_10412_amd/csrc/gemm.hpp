@@ -62,7 +62,7 @@ template <int R, int BK, bool EDGE, bool MASKED> struct F32LoadK {
   floatx4 v[NCH];
   const float* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
   __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
-                                       int rmax_, int K_, const StoreView&) {
+                                       int rmax_, int K_, const StoreView&, const GemmArgs&) {
     p = static_cast<const float*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
   }
   __device__ __forceinline__ void bounds(int) {}
@@ -115,7 +115,7 @@ template <int R, int BK, bool EDGE, bool MASKED> struct F32LoadMN {
   floatx4 v[NCH];
   const float* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
   __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
-                                       int rmax_, int K_, const StoreView&) {
+                                       int rmax_, int K_, const StoreView&, const GemmArgs&) {
     p = static_cast<const float*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
   }
   __device__ __forceinline__ void bounds(int) {}
@@ -182,7 +182,7 @@ template <int R, int BK, int SE> struct F32LoadSparse {
   uint32_t beg, end, nbeg, nend;
   StoreView s; int m0, K;
   __device__ __forceinline__ void init(const void*, int64_t, const uint32_t*, int, int r0_, int, int K_,
-                                       const StoreView& sv) { s = sv; m0 = r0_; K = K_; }
+                                       const StoreView& sv, const GemmArgs&) { s = sv; m0 = r0_; K = K_; }
   __device__ __forceinline__ void bounds(int k0) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int b = k0 + w * RPW + lane / LPR;
@@ -217,7 +217,7 @@ template <int R, int BK, int SE> struct F32LoadSparse {
   }
 };
 
-// =========================================================== bf16 loaders
+// =========================================================== bf16 helper
 __device__ __forceinline__ void mask_bf16x8(u32x4& t, uint32_t mb) {
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -226,202 +226,145 @@ __device__ __forceinline__ void mask_bf16x8(u32x4& t, uint32_t mb) {
   }
 }
 
-// dense, K contiguous
-template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadK {
-  typedef LdsBF16<R, BK> L;
-  static constexpr int TOTAL = R * L::CH;
+// ========================================================= im2col loaders
+// position index gm = b*H*W + y*W + x; reduction index gk = (c*KH + u)*KW + v;
+// element = src[b][c][y+u-pad][x+v-pad], zero outside the image.
+__device__ __forceinline__ float im2col_at(const float* src, const GemmArgs& g, int gm, int gk) {
+  const int HW = g.cv_H * g.cv_W;
+  const int b = gm / HW, yx = gm - b * HW;
+  const int y = yx / g.cv_W, x = yx - y * g.cv_W;
+  const int c = gk / (g.cv_KH * g.cv_KW), uv = gk - c * (g.cv_KH * g.cv_KW);
+  const int u = uv / g.cv_KW, v = uv - u * g.cv_KW;
+  const int yy = y + u - g.cv_pad, xx = x + v - g.cv_pad;
+  if (yy < 0 || yy >= g.cv_H || xx < 0 || xx >= g.cv_W) return 0.f;
+  return src[((size_t)(b * g.cv_C + c) * g.cv_H + yy) * g.cv_W + xx];
+}
+
+// A of the forward / dX convolution: tile rows are positions, LDS layout [k][row]
+template <int R, int BK> struct F32LoadIm2colRows {
+  static constexpr int TOTAL = R * BK / 4;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
-  static constexpr int kDsWrites = NCH, kVmemReads = NCH * (MASKED ? 2 : 1);
-  u32x4 v[NCH];
-  uint32_t mb[MASKED ? NCH : 1];                 // ReLU bits of each chunk, applied at commit
-  const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
-  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
-                                       int rmax_, int K_, const StoreView&) {
-    p = static_cast<const uint16_t*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
+  typedef LdsF32<R, BK> L;
+  floatx4 v[NCH];
+  const float* p; int r0, rmax, K; const GemmArgs* ga;
+  __device__ __forceinline__ void init(const void* ptr, int64_t, const uint32_t*, int, int r0_, int rmax_, int K_,
+                                       const StoreView&, const GemmArgs& g) {
+    p = static_cast<const float*>(ptr); r0 = r0_; rmax = rmax_; K = K_; ga = &g;
   }
   __device__ __forceinline__ void bounds(int) {}
   __device__ __forceinline__ void fetch(int k0) {
-    const bool vec = (ld & 7) == 0;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
-      u32x4 t = {0u, 0u, 0u, 0u};
-      if (MASKED) mb[i] = 0u;
+      floatx4 t = {0.f, 0.f, 0.f, 0.f};
       if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
-        const int row = c / L::CH, kc = c % L::CH;
-        const int gr = r0 + row, gk = k0 + kc * 8;
-        const uint16_t* src = p + ((uint32_t)gr * ld + (uint32_t)gk);
-        if (!EDGE) {
-          t = *reinterpret_cast<const u32x4*>(src);
-        } else if (gr < rmax && gk < K) {
-          if (vec && gk + 7 < K) t = *reinterpret_cast<const u32x4*>(src);
-          else {
-            uint16_t* te = reinterpret_cast<uint16_t*>(&t);
+        const int k = c / (R / 4), m4 = c % (R / 4);
+        const int gk = k0 + k;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) if (gk + e < K) te[e] = src[e];
-          }
+        for (int e = 0; e < 4; ++e) {
+          const int gm = r0 + m4 * 4 + e;
+          if (gk < K && gm < rmax) t[e] = im2col_at(p, *ga, gm, gk);
         }
-        if (MASKED && (!EDGE || (gr < rmax && gk < K))) mb[i] = mask_bits(mask, mp, gr, gk);
       }
       v[i] = t;
     }
   }
-  // the commit in four steps, so the caller can alternate them with its own LDS reads
-  template <int STEP> __device__ __forceinline__ void commit_step(uint16_t* lds) {
+  __device__ __forceinline__ void commit(float* lds) {
 #pragma unroll
-    for (int i = STEP; i < NCH; i += 4) {
+    for (int i = 0; i < NCH; ++i) {
       const int c = threadIdx.x + i * kGemmThreads;
       if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
-        const int row = c / L::CH, kc = c % L::CH;
-        if (MASKED) mask_bf16x8(v[i], mb[i]);
-        *reinterpret_cast<u32x4*>(&lds[L::unit(row, kc) * 8]) = v[i];
+        const int k = c / (R / 4), m4 = c % (R / 4);
+        *reinterpret_cast<floatx4*>(&lds[L::at(m4 * 4, k)]) = v[i];
       }
     }
   }
-  __device__ __forceinline__ void commit(uint16_t* lds) {
-    commit_step<0>(lds); commit_step<1>(lds); commit_step<2>(lds); commit_step<3>(lds);
-  }
 };
 
-// dense, M/N contiguous: an 8(k) x 8(row) block per thread is transposed in
-// registers so that LDS receives 16-byte units of 8 consecutive k.
-template <int R, int BK, bool EDGE, bool MASKED> struct BF16LoadMN {
-  typedef LdsBF16<R, BK> L;
-  static constexpr int RB = R / 8, KB = BK / 8;
-  static constexpr int TOTAL = RB * KB;
-  static constexpr int NBL = (TOTAL + kGemmThreads - 1) / kGemmThreads;
-  static constexpr int kDsWrites = NBL * 8, kVmemReads = NBL * 8 * (MASKED ? 2 : 1);
-  u32x4 v[NBL][8];                               // v[.][kk] = 8 consecutive rows at k = kb*8+kk
-  uint32_t mb[MASKED ? NBL : 1][8];
-  const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
-  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
-                                       int rmax_, int K_, const StoreView&) {
-    p = static_cast<const uint16_t*>(ptr); ld = (uint32_t)ld_; mask = mask_; mp = mp_; r0 = r0_; rmax = rmax_; K = K_;
+// A of the convolution dW: tile rows are (c,u,v), the K index is the position
+template <int R, int BK> struct F32LoadIm2colK {
+  static constexpr int TOTAL = R * BK / 4;
+  static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  typedef LdsF32<R, BK> L;
+  floatx4 v[NCH];
+  const float* p; int r0, rmax, K; const GemmArgs* ga;
+  __device__ __forceinline__ void init(const void* ptr, int64_t, const uint32_t*, int, int r0_, int rmax_, int K_,
+                                       const StoreView&, const GemmArgs& g) {
+    p = static_cast<const float*>(ptr); r0 = r0_; rmax = rmax_; K = K_; ga = &g;
   }
   __device__ __forceinline__ void bounds(int) {}
   __device__ __forceinline__ void fetch(int k0) {
-    const bool vec = (ld & 7) == 0;
 #pragma unroll
-    for (int i = 0; i < NBL; ++i) {
-      const int blk = threadIdx.x + i * kGemmThreads;
-      const int rb = blk % RB, kb = blk / RB;
-      const int gr = r0 + rb * 8;
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      floatx4 t = {0.f, 0.f, 0.f, 0.f};
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
+        const int row = c / (BK / 4), k4 = c % (BK / 4);
+        const int gr = r0 + row;
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        u32x4 t = {0u, 0u, 0u, 0u};
-        const int gk = k0 + kb * 8 + kk;
-        if (MASKED) mb[i][kk] = 0u;
-        if (TOTAL % kGemmThreads == 0 || blk < TOTAL) {
-          const uint16_t* src = p + ((uint32_t)gk * ld + (uint32_t)gr);
-          if (!EDGE) {
-            t = *reinterpret_cast<const u32x4*>(src);
-          } else if (gk < K && gr < rmax) {
-            if (vec && gr + 7 < rmax) t = *reinterpret_cast<const u32x4*>(src);
-            else {
-              uint16_t* te = reinterpret_cast<uint16_t*>(&t);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) if (gr + e < rmax) te[e] = src[e];
-            }
-          }
-          if (MASKED && (!EDGE || (gk < K && gr < rmax))) mb[i][kk] = mask_bits(mask, mp, gk, gr);
+        for (int e = 0; e < 4; ++e) {
+          const int gk = k0 + k4 * 4 + e;
+          if (gr < rmax && gk < K) t[e] = im2col_at(p, *ga, gk, gr);
         }
-        v[i][kk] = t;
       }
+      v[i] = t;
     }
   }
-  // step d transposes dword d of the block: rows 2d and 2d+1 of the 8 x 8 block
-  template <int D> __device__ __forceinline__ void commit_step(uint16_t* lds) {
+  __device__ __forceinline__ void commit(float* lds) {
 #pragma unroll
-    for (int i = 0; i < NBL; ++i) {
-      const int blk = threadIdx.x + i * kGemmThreads;
-      if (TOTAL % kGemmThreads == 0 || blk < TOTAL) {
-        const int rb = blk % RB, kb = blk / RB;
-        if (MASKED && D == 0) {
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
+        const int row = c / (BK / 4), k4 = c % (BK / 4);
 #pragma unroll
-          for (int kk = 0; kk < 8; ++kk) mask_bf16x8(v[i][kk], mb[i][kk]);
-        }
-        // dword D of v[kk] holds rows 2D (low half) and 2D+1 (high half) at k = kk
-        u32x4 lo, hi;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const uint32_t a = v[i][2 * q][D], b = v[i][2 * q + 1][D];
-          lo[q] = __builtin_amdgcn_perm(b, a, 0x05040100u);   // (a.lo, b.lo)
-          hi[q] = __builtin_amdgcn_perm(b, a, 0x07060302u);   // (a.hi, b.hi)
-        }
-        *reinterpret_cast<u32x4*>(&lds[L::unit(rb * 8 + 2 * D, kb) * 8]) = lo;
-        *reinterpret_cast<u32x4*>(&lds[L::unit(rb * 8 + 2 * D + 1, kb) * 8]) = hi;
+        for (int e = 0; e < 4; ++e) lds[L::at(row, k4 * 4 + e)] = v[i][e];
       }
     }
-  }
-  __device__ __forceinline__ void commit(uint16_t* lds) {
-    commit_step<0>(lds); commit_step<1>(lds); commit_step<2>(lds); commit_step<3>(lds);
   }
 };
 
-// compressed store as A of dW (see F32LoadSparse).  LDS tile is [row j][k b];
-// wave w owns the k columns [w*BK/4, (w+1)*BK/4) = RPW*2 bytes of every row.
-template <int R, int BK, int SE> struct BF16LoadSparse {
-  typedef LdsBF16<R, BK> L;
-  static constexpr int RPW = BK / 4;            // k (store rows) per wave: 16 at BK = 64
-  static constexpr int LPR = 64 / RPW;          // lanes per store row
-  static constexpr int UPW = RPW / 8;           // 16-byte units per tile row owned by a wave
-  static constexpr int kDsWrites = R * UPW / 64 + SE, kVmemReads = 2 * SE + 3;
-  uint32_t ent[SE];                              // (value bits << 16) | (column - m0), 0xFFFF = none
-  uint32_t beg, end, nbeg, nend;
-  StoreView s; int m0, K;
-  __device__ __forceinline__ void init(const void*, int64_t, const uint32_t*, int, int r0_, int, int K_,
-                                       const StoreView& sv) { s = sv; m0 = r0_; K = K_; }
-  __device__ __forceinline__ void bounds(int k0) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int b = k0 + w * RPW + lane / LPR;
-    nbeg = nend = 0;
-    if (b < K) store_segment(s, b, m0 / kBucket, &nbeg, &nend);
+// B of the convolution dW: rows are channels n of an NCHW tensor [B][cv_N][HW], the K index is (b,yx)
+template <int R, int BK> struct F32LoadKBatched {
+  static constexpr int TOTAL = R * BK / 4;
+  static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
+  typedef LdsF32<R, BK> L;
+  floatx4 v[NCH];
+  const float* p; int r0, rmax, K, HW, CN;
+  __device__ __forceinline__ void init(const void* ptr, int64_t, const uint32_t*, int, int r0_, int rmax_, int K_,
+                                       const StoreView&, const GemmArgs& g) {
+    p = static_cast<const float*>(ptr); r0 = r0_; rmax = rmax_; K = K_; HW = g.cv_H * g.cv_W; CN = g.cv_N;
   }
-  __device__ __forceinline__ void fetch(int) {
-    const int sub = (threadIdx.x & 63) % LPR;
-    beg = nbeg; end = nend;
-    const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
+  __device__ __forceinline__ void bounds(int) {}
+  __device__ __forceinline__ void fetch(int k0) {
 #pragma unroll
-    for (int i = 0; i < SE; ++i) {
-      const uint32_t e = beg + sub + i * LPR;
-      ent[i] = 0xFFFFu;
-      if (e < end) {
-        const int c = (int)s.indices[e] - m0;
-        if (c >= 0 && c < R) ent[i] = ((uint32_t)vals[e] << 16) | (uint32_t)c;
-      }
-    }
-  }
-  // steps 0 and 1 clear the wave's stripe of the tile, steps 2 and 3 scatter the entries into it
-  template <int STEP> __device__ __forceinline__ void commit_step(uint16_t* lds) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    constexpr int NZ = R * UPW / 64;               // clearing stores per lane
-    if (STEP < 2) {
-      const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      floatx4 t = {0.f, 0.f, 0.f, 0.f};
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
+        const int row = c / (BK / 4), k4 = c % (BK / 4);
+        const int gr = r0 + row;
 #pragma unroll
-      for (int q = STEP * (NZ / 2); q < (STEP + 1) * (NZ / 2); ++q) {
-        const int c = lane + q * 64;
-        const int row = c / UPW, u = c % UPW;
-        *reinterpret_cast<u32x4*>(&lds[L::unit(row, w * UPW + u) * 8]) = z;
-      }
-    } else {
-      const int kr = w * RPW + lane / LPR, sub = lane % LPR;
-      constexpr int H = (SE + 1) / 2;
-#pragma unroll
-      for (int i = (STEP - 2) * H; i < (STEP == 2 ? H : SE); ++i) {
-        const uint32_t c = ent[i] & 0xFFFFu;
-        if (c != 0xFFFFu) lds[L::unit((int)c, kr >> 3) * 8 + (kr & 7)] = (uint16_t)(ent[i] >> 16);
-      }
-      if (STEP == 3) {
-        const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
-        for (uint32_t e = beg + sub + SE * LPR; e < end; e += LPR) {
-          const int c = (int)s.indices[e] - m0;
-          if (c >= 0 && c < R) lds[L::unit(c, kr >> 3) * 8 + (kr & 7)] = vals[e];
+        for (int e = 0; e < 4; ++e) {
+          const int gk = k0 + k4 * 4 + e;
+          if (gr < rmax && gk < K) {
+            const int b = gk / HW, yx = gk - b * HW;
+            t[e] = p[((size_t)b * CN + gr) * HW + yx];
+          }
         }
       }
+      v[i] = t;
     }
   }
-  __device__ __forceinline__ void commit(uint16_t* lds) {
-    commit_step<0>(lds); commit_step<1>(lds); commit_step<2>(lds); commit_step<3>(lds);
+  __device__ __forceinline__ void commit(float* lds) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = threadIdx.x + i * kGemmThreads;
+      if (TOTAL % kGemmThreads == 0 || c < TOTAL) {
+        const int row = c / (BK / 4), k4 = c % (BK / 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lds[L::at(row, k4 * 4 + e)] = v[i][e];
+      }
+    }
   }
 };
 
@@ -430,9 +373,10 @@ template <class DT, int KIND, int R, int BK, int SE, bool EDGE, bool MASKED> str
 template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpK, R, BK, SE, EDGE, MASKED> { typedef F32LoadK<R, BK, EDGE, MASKED> type; };
 template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpMN, R, BK, SE, EDGE, MASKED> { typedef F32LoadMN<R, BK, EDGE, MASKED> type; };
 template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpSparse, R, BK, SE, EDGE, MASKED> { typedef F32LoadSparse<R, BK, SE> type; };
-template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<BF16Tag, kOpK, R, BK, SE, EDGE, MASKED> { typedef BF16LoadK<R, BK, EDGE, MASKED> type; };
-template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<BF16Tag, kOpMN, R, BK, SE, EDGE, MASKED> { typedef BF16LoadMN<R, BK, EDGE, MASKED> type; };
-template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<BF16Tag, kOpSparse, R, BK, SE, EDGE, MASKED> { typedef BF16LoadSparse<R, BK, SE> type; };
+
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpIm2colRows, R, BK, SE, EDGE, MASKED> { typedef F32LoadIm2colRows<R, BK> type; };
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpIm2colK, R, BK, SE, EDGE, MASKED> { typedef F32LoadIm2colK<R, BK> type; };
+template <int R, int BK, int SE, bool EDGE, bool MASKED> struct LoaderOf<F32Tag, kOpKBatched, R, BK, SE, EDGE, MASKED> { typedef F32LoadKBatched<R, BK> type; };
 
 template <class DT, int R, int BK> struct LdsOf;
 template <int R, int BK> struct LdsOf<F32Tag, R, BK> { typedef LdsF32<R, BK> type; };
@@ -469,39 +413,6 @@ template <int BM, int BN, int BK> struct Mma<F32Tag, BM, BN, BK> {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
-    }
-  }
-};
-
-template <int BM, int BN, int BK> struct Mma<BF16Tag, BM, BN, BK> {
-  static constexpr int TM = BM / 64, TN = BN / 64, KS = BK / 16;
-  typedef LdsBF16<BM, BK> LA; typedef LdsBF16<BN, BK> LB;
-  static __device__ __forceinline__ void run(const uint16_t* As, const uint16_t* Bs, floatx16 (&acc)[TM][TN],
-                                             int wm0, int wn0) {
-    const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
-    bf16x8 a[2][TM], b[2][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-      a[0][i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, lk) * 8]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-      b[0][j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, lk) * 8]);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      const int c = s & 1, n = c ^ 1;
-      if (s + 1 < KS) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-          a[n][i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, (s + 1) * 2 + lk) * 8]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          b[n][j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, (s + 1) * 2 + lk) * 8]);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
     }
   }
 };
@@ -656,6 +567,52 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
   }
 }
 
+// Convolution epilogue: tile rows are positions (b,yx) of one image (H*W is a multiple of BM), tile columns
+// are output channels; the output is NCHW.  The tile goes through LDS transposed, so that a wave walks one
+// channel at a time with lanes on consecutive positions: stores are contiguous and a ballot of (y > 0) is
+// two words of the ReLU bit array of the example (bit index = c*H*W + yx).
+template <int BM, int BN, int TM, int TN>
+__device__ __forceinline__ void epilogue_conv(const GemmArgs& g, floatx16 (&acc)[TM][TN], float* ct, int m0, int n0,
+                                              int wm0, int wn0) {
+  constexpr int CP = BM + 1;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int lc = wn0 + j * 32 + (lane & 31);
+      const int col = n0 + lc;
+      const float bv = (g.bias && col < g.N) ? g.bias[col] : 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int lrow = wm0 + i * 32 + acc_row(e, lane);
+        float h = acc[i][j][e] + bv;
+        if (g.relu) h = h > 0.f ? h : 0.f;
+        ct[lc * CP + lrow] = h;
+      }
+    }
+  __syncthreads();
+  const int HW = g.cv_H * g.cv_W;
+  const int b = m0 / HW, yx0 = m0 - b * HW;
+  float* Y = reinterpret_cast<float*>(g.y);
+  for (int c = w; c < BN; c += 4) {
+    const int co = n0 + c;
+    if (co >= g.N) break;
+#pragma unroll
+    for (int p0 = 0; p0 < BM; p0 += 64) {
+      const int pos = m0 + p0 + lane;
+      const float yv = ct[c * CP + p0 + lane];
+      if (pos < g.M) Y[((size_t)b * g.N + co) * HW + yx0 + p0 + lane] = yv;
+      if (g.bits) {
+        const uint64_t bal = __ballot(pos < g.M && yv > 0.f);
+        const int wi = (co * HW + yx0 + p0) / 32;
+        if (lane == 0 && wi < g.bits_pitch) g.bits[(size_t)b * g.bits_pitch + wi] = (uint32_t)bal;
+        if (lane == 32 && wi + 1 < g.bits_pitch) g.bits[(size_t)b * g.bits_pitch + wi + 1] = (uint32_t)(bal >> 32);
+      }
+    }
+  }
+}
+
 // ============================================================ the kernel
 template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE>
 struct GemmSmem {
@@ -665,7 +622,8 @@ struct GemmSmem {
   static constexpr int STAGE = LA::BYTES + LB::BYTES;
   static constexpr int MAIN = 2 * STAGE;
   static constexpr int CT = BM * (BN + (sizeof(ElemT) == 4 ? 1 : 2)) * (int)sizeof(ElemT);
-  static constexpr int BYTES = (EPI == kEpiFwd && CT > MAIN) ? CT : MAIN;
+  static constexpr int CTC = BN * (BM + 1) * 4;
+  static constexpr int BYTES = (EPI == kEpiFwd && CT > MAIN) ? CT : (EPI == kEpiConv && CTC > MAIN) ? CTC : MAIN;
 };
 
 // Pipeline of one K slice (registers always hold the slice after the one in
@@ -711,21 +669,24 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   LoadA la; LoadB lb;
-  la.init(g.A, g.lda, g.a_mask, g.a_mask_pitch, m0, g.M, g.K, g.sa);
-  lb.init(g.B, g.ldb, g.b_mask, g.b_mask_pitch, n0, g.N, g.K, g.sa);
-  const int KT = (g.K + BK - 1) / BK;
+  // split-K: blockIdx.y owns the K range [kbeg, kend)
+  const int kbeg = g.k_splits > 1 ? (int)blockIdx.y * g.k_split : 0;
+  const int kend = g.k_splits > 1 ? min(g.K, kbeg + g.k_split) : g.K;
+  la.init(g.A, g.lda, g.a_mask, g.a_mask_pitch, m0, g.M, kend, g.sa, g);
+  lb.init(g.B, g.ldb, g.b_mask, g.b_mask_pitch, n0, g.N, kend, g.sa, g);
+  const int KT = (kend - kbeg + BK - 1) / BK;
 
   if (KT > 0) {
-    la.bounds(0);
-    la.fetch(0);
-    lb.fetch(0);
-    if (KT > 1) la.bounds(BK);
+    la.bounds(kbeg);
+    la.fetch(kbeg);
+    lb.fetch(kbeg);
+    if (KT > 1) la.bounds(kbeg + BK);
     la.commit(smem);
     lb.commit(smem + kAElems);
     if (KT > 1) {
-      la.fetch(BK);
-      lb.fetch(BK);
-      if (KT > 2) la.bounds(2 * BK);
+      la.fetch(kbeg + BK);
+      lb.fetch(kbeg + BK);
+      if (KT > 2) la.bounds(kbeg + 2 * BK);
     }
   }
   __syncthreads();
@@ -737,9 +698,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
       lb.commit(nxt + kAElems);
     }
     if (kt + 2 < KT) {
-      la.fetch((kt + 2) * BK);
-      lb.fetch((kt + 2) * BK);
-      if (kt + 3 < KT) la.bounds((kt + 3) * BK);
+      la.fetch(kbeg + (kt + 2) * BK);
+      lb.fetch(kbeg + (kt + 2) * BK);
+      if (kt + 3 < KT) la.bounds(kbeg + (kt + 3) * BK);
     }
     Mma<DT, BM, BN, BK>::run(cur, cur + kAElems, acc, wm0, wn0);
     __syncthreads();
@@ -747,6 +708,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {
 
   if constexpr (EPI == kEpiStore) {
     epilogue_store_dispatch<AK, TM, TN, ElemT, EDGE>(g, acc, m0, n0, wm0, wn0);
+  } else if constexpr (EPI == kEpiSplitK) {
+    GemmArgs gs = g;
+    gs.C = static_cast<float*>(g.C) + (size_t)blockIdx.y * g.M * g.N;
+    epilogue_store<TM, TN, float, true, false, false, false>(gs, acc, m0, n0, wm0, wn0);
+  } else if constexpr (EPI == kEpiConv) {
+    epilogue_conv<BM, BN, TM, TN>(g, acc, reinterpret_cast<float*>(smem), m0, n0, wm0, wn0);
   } else {
     epilogue_fwd<ElemT, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
   }

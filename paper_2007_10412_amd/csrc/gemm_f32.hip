@@ -27,6 +27,13 @@ hipError_t launch_gemm_f32(int a_kind, int b_kind, int epi, const GemmArgs& g, h
       else { nm = "gemm_f32_dw_sparse_64"; e = run_gemm<F32Tag, kOpSparse, kOpMN, kEpiStore, 64, 64, 16, 4, false, true, false>(g, st); }
     }
   }
+  else if (a_kind == kOpIm2colRows && b_kind == kOpMN && epi == kEpiConv) {
+    // convolution forward / dX: positions x channels, channels fit one 64-wide tile column
+    nm = "gemm_f32_conv_64"; e = run_gemm<F32Tag, kOpIm2colRows, kOpMN, kEpiConv, 64, 64, 16, 0, false, false, false>(g, st);
+  } else if (a_kind == kOpIm2colK && b_kind == kOpKBatched && epi == kEpiSplitK) {
+    // convolution dW: (c,u,v) x channels with the positions as a split K
+    nm = "gemm_f32_conv_dw_64"; e = run_gemm<F32Tag, kOpIm2colK, kOpKBatched, kEpiSplitK, 64, 64, 16, 0, false, false, false>(g, st);
+  }
   if (name) *name = nm;
   return e;
 }

@@ -33,11 +33,17 @@ hipError_t launch_pack(const void* x, int dtype, const StoreView& s, hipStream_t
 enum OpKind : int {
   kOpK = 0,      // dense, K contiguous:  A[m*ld + k]   / B[n*ld + k]
   kOpMN = 1,     // dense, M/N contiguous: A[k*ld + m]  / B[k*ld + n]
-  kOpSparse = 2  // A only: rows of a compressed store are the K index, columns the M index
+  kOpSparse = 2, // A only: rows of a compressed store are the K index, columns the M index
+  // convolution as an implicit im2col GEMM over an NCHW tensor [B][cv_C][cv_H][cv_W] (stride 1, zero pad):
+  kOpIm2colRows = 3,  // A: tile rows are output positions (b,y,x), K index is (c,u,v): forward and dX
+  kOpIm2colK = 4,     // A: tile rows are (c,u,v), K index is the position (b,y,x): dW
+  kOpKBatched = 5     // B: rows are channels n, K index is the position (b,yx): element at B[(b*cv_N + n)*HW + yx]
 };
 enum EpiKind : int {
   kEpiStore = 0, // C (+= if beta) = acc, optional output row map
-  kEpiFwd = 1    // bias / rank-u addend / ReLU / bits / dense y / pack next store
+  kEpiFwd = 1,   // bias / rank-u addend / ReLU / bits / dense y / pack next store
+  kEpiConv = 2,  // rows are positions (b,yx), columns channels: bias / ReLU / bits, NCHW output
+  kEpiSplitK = 3 // plain store of the split's partial sums to C + split*M*N
 };
 
 struct GemmArgs {
@@ -61,6 +67,9 @@ struct GemmArgs {
   uint32_t* bits; int bits_pitch;
   int pack; StoreView next;     // pack the output tile into `next` (rows = M, cols = N)
   const float* u; int64_t u_ld; int u_n; const float* V;   // h += sum_i u[m*u_ld+i] * V[i*N+n]
+  // convolution geometry (im2col operand kinds, kEpiConv) and split-K
+  int cv_C, cv_H, cv_W, cv_KH, cv_KW, cv_pad, cv_N;   // cv_N: channels of the kOpKBatched / kEpiConv tensor
+  int k_split, k_splits;       // K range per blockIdx.y (multiple of the K slice), number of splits (0/1 = none)
 };
 
 // dtype: operand element type; returns hipErrorInvalidValue for combinations
@@ -77,6 +86,18 @@ hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint3
                          const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
                          int beta, float* partial, int splits, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t st);
+// out[i] (+)= sum over `splits` partial arrays of n elements
+hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st);
+// 2x2/stride-2 max pool over NCHW planes; arg packs the 2-bit window position (dy*2+dx of the first maximum)
+// of 16 consecutive outputs per word
+hipError_t launch_maxpool_fwd(const float* y, int planes, int H, int W, float* pooled, uint32_t* arg, hipStream_t st);
+// g[b,c,y,x] = upstream gradient routed through the pool (if arg) and masked by the ReLU bits of the layer
+hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, const uint32_t* arg,
+                              const uint32_t* bits, int bits_pitch, float* g, hipStream_t st);
+// db[c] = sum over b, y, x of g[b,c,y,x]
+hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* db, hipStream_t st);
+// Wt[(o,u,v)][c] = W[c][KH-1-u][KW-1-v][o]: the weight operand of the transposed convolution (dX)
+hipError_t launch_flip_weights(const float* W, int Ci, int KH, int KW, int Co, float* Wt, hipStream_t st);
 // Adds to dW the entries of (row, bucket) segments beyond the first `cap`, which the MFMA kernel leaves out;
 // exits at once when *max_seg <= cap (the plan's running maximum), which is the normal case.
 hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int dtype, int N, const uint32_t* bits,

@@ -317,7 +317,8 @@ __global__ __launch_bounds__(256) void unpack_kernel(StoreView s, T* __restrict_
   int64_t beg = s.row_ptr[row], end = s.row_ptr[row + 1];
   if (end > s.capacity) end = s.capacity;
   const T* vals = reinterpret_cast<const T*>(s.values);
-  for (int64_t e = beg + threadIdx.x; e < end; e += 256) out[s.indices[e]] = vals[e];
+  // shared scheme: the k columns are stored once
+  for (int64_t e = beg + threadIdx.x; e < end; e += 256) out[s.indices[s.idx_shared ? e - beg : e]] = vals[e];
 }
 
 }  // namespace
@@ -346,7 +347,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t st) {
 }
 
 // widest row the plan kernels handle for a scheme
-int plan_max_cols(int scheme) { return scheme == kBernoulli ? 65535 : 16376; }
+int plan_max_cols(int scheme) { return scheme == kBernoulli ? 65535 : 16384; }
 
 hipError_t launch_row_scan(const uint32_t* row_cnt, uint32_t* row_ptr, int rows, int64_t capacity,
                            int* overflow, hipStream_t st) {

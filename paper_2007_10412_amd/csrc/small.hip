@@ -141,6 +141,93 @@ __global__ __launch_bounds__(256) void dw_overflow_kernel(StoreView s, int rows,
   }
 }
 
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int64_t n,
+                                                            float* __restrict__ out, int beta) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float v = 0.f;
+  for (int s = 0; s < splits; ++s) v += partial[(size_t)s * n + i];
+  out[i] = beta ? out[i] + v : v;
+}
+
+// 2x2 max pool, stride 2.  One thread produces 16 consecutive outputs of a plane row-major and the word of
+// their 2-bit window positions; the first maximum in (dy, dx) row-major order wins.
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float* __restrict__ y, int planes, int H, int W,
+                                                          float* __restrict__ pooled, uint32_t* __restrict__ arg) {
+  const int Ho = H / 2, Wo = W / 2;
+  const int64_t total = (int64_t)planes * Ho * Wo;
+  const int64_t q0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 16;
+  if (q0 >= total) return;
+  uint32_t word = 0;
+  for (int e = 0; e < 16; ++e) {
+    const int64_t q = q0 + e;
+    if (q >= total) break;
+    const int64_t pl = q / (Ho * Wo);
+    const int r = (int)(q - pl * (Ho * Wo));
+    const int oy = r / Wo, ox = r - oy * Wo;
+    const float* src = y + (size_t)pl * H * W + (size_t)(2 * oy) * W + 2 * ox;
+    float best = src[0]; uint32_t pos = 0;
+    if (src[1] > best) { best = src[1]; pos = 1; }
+    if (src[W] > best) { best = src[W]; pos = 2; }
+    if (src[W + 1] > best) { best = src[W + 1]; pos = 3; }
+    pooled[q] = best;
+    word |= pos << (2 * e);
+  }
+  arg[q0 / 16] = word;
+}
+
+// g = (dy routed back through the pool, if any) masked by the ReLU bits of the layer output [B][C*H*W]
+__global__ __launch_bounds__(256) void unpool_mask_kernel(const float* __restrict__ dy, int batch, int C, int H, int W,
+                                                          const uint32_t* __restrict__ arg,
+                                                          const uint32_t* __restrict__ bits, int bits_pitch,
+                                                          float* __restrict__ g) {
+  const int64_t per = (int64_t)C * H * W;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= batch * per) return;
+  const int b = (int)(i / per);
+  const int64_t f = i - (int64_t)b * per;
+  float v;
+  if (arg) {
+    const int Ho = H / 2, Wo = W / 2;
+    const int c = (int)(f / (H * W)), yx = (int)(f - (int64_t)c * H * W);
+    const int y = yx / W, x = yx - y * W;
+    const int64_t q = ((int64_t)(b * C + c) * Ho + y / 2) * Wo + x / 2;
+    const uint32_t pos = (arg[q / 16] >> (2 * (q % 16))) & 3u;
+    v = (pos == (uint32_t)((y & 1) * 2 + (x & 1))) ? dy[q] : 0.f;
+  } else {
+    v = dy[i];
+  }
+  if (bits && !((bits[(size_t)b * bits_pitch + (f >> 5)] >> (f & 31)) & 1u)) v = 0.f;
+  g[i] = v;
+}
+
+// db[c] = sum_{b,yx} g[b,c,yx]; one workgroup per channel, fixed summation order
+__global__ __launch_bounds__(256) void channel_sum_kernel(const float* __restrict__ g, int batch, int C, int HW,
+                                                          float* __restrict__ db) {
+  __shared__ float s_w[4];
+  const int c = blockIdx.x;
+  float acc = 0.f;
+  for (int b = 0; b < batch; ++b) {
+    const float* src = g + ((size_t)b * C + c) * HW;
+    for (int i = threadIdx.x; i < HW; i += 256) acc += src[i];
+  }
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) db[c] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+__global__ __launch_bounds__(256) void flip_weights_kernel(const float* __restrict__ W, int Ci, int KH, int KW, int Co,
+                                                           float* __restrict__ Wt) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= Ci * KH * KW * Co) return;
+  // i indexes Wt[(o,u,v)][c]
+  const int c = i % Ci, ouv = i / Ci;
+  const int v = ouv % KW, ou = ouv / KW;
+  const int u = ou % KH, o = ou / KH;
+  Wt[i] = W[(((size_t)c * KH + (KH - 1 - u)) * KW + (KW - 1 - v)) * Co + o];
+}
+
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p, uint32_t v, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = v;
@@ -187,6 +274,39 @@ hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int 
   else
     hipLaunchKernelGGL(dw_overflow_kernel<uint16_t>, grid, block, 0, st, s, rows, (const uint16_t*)dy, N, bits,
                        bits_pitch, dW, cap, max_seg);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st) {
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, partial, splits, n, out,
+                     beta);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_fwd(const float* y, int planes, int H, int W, float* pooled, uint32_t* arg, hipStream_t st) {
+  const int64_t total = (int64_t)planes * (H / 2) * (W / 2);
+  const int64_t threads = (total + 15) / 16;
+  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, y, planes, H, W,
+                     pooled, arg);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, const uint32_t* arg,
+                              const uint32_t* bits, int bits_pitch, float* g, hipStream_t st) {
+  const int64_t n = (int64_t)batch * C * H * W;
+  hipLaunchKernelGGL(unpool_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dy, batch, C, H, W, arg,
+                     bits, bits_pitch, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* db, hipStream_t st) {
+  hipLaunchKernelGGL(channel_sum_kernel, dim3(C), dim3(256), 0, st, g, batch, C, HW, db);
+  return hipGetLastError();
+}
+
+hipError_t launch_flip_weights(const float* W, int Ci, int KH, int KW, int Co, float* Wt, hipStream_t st) {
+  const int n = Ci * KH * KW * Co;
+  hipLaunchKernelGGL(flip_weights_kernel, dim3((n + 255) / 256), dim3(256), 0, st, W, Ci, KH, KW, Co, Wt);
   return hipGetLastError();
 }
 
