@@ -635,6 +635,9 @@ struct GemmSmem {
 // the dense A / B operand is masked by stored ReLU bits.  Compile-time, so the
 // K loop stays one basic block the scheduler can interleave.
 constexpr int kFlagEdge = 1, kFlagMaskA = 2, kFlagMaskB = 4;
+// bf16 ring kernels only: ragged tiles whose operand rows are still whole 16-byte vectors (row pitch, K and
+// the contiguous extent multiples of 8): loads are predicated by address clamping instead of branches
+constexpr int kFlagEdgeVec = 8;
 
 template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE, int FLAGS>
 __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs g) {

@@ -29,7 +29,9 @@ constexpr int kBK3 = 32;
 
 // ------------------------------------------------------------------ loaders
 // dense, K contiguous: element (row, k) at p[row*ld + k]
-template <int R, bool EDGE, bool MASKED> struct RingLoadK {
+// EMODE: 0 = interior (no guards), 1 = ragged but every access a whole in-bounds or out-of-bounds 16-byte
+// vector (guard by clamping the address and zeroing), 2 = generic element-wise guards.
+template <int R, int EMODE, bool MASKED> struct RingLoadK {
   typedef LdsBF16<R, kBK3> L;
   static constexpr int TOTAL = R * L::CH;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
@@ -54,8 +56,14 @@ template <int R, bool EDGE, bool MASKED> struct RingLoadK {
         const int row = c / L::CH, kc = c % L::CH;
         const int gr = r0 + row, gk = k0 + kc * 8;
         const uint16_t* src = p + ((uint32_t)gr * ld + (uint32_t)gk);
-        if (!EDGE) {
+        if (EMODE == 0) {
           t = *reinterpret_cast<const u32x4*>(src);
+          if (MASKED) mb[SLOT][i] = mask_bits(mask, mp, gr, gk);
+        } else if (EMODE == 1) {
+          const bool ok = gr < rmax && gk < K;
+          t = *reinterpret_cast<const u32x4*>(ok ? src : p);
+          if (!ok) t = u32x4{0u, 0u, 0u, 0u};
+          if (MASKED) mb[SLOT][i] = mask_bits(mask, mp, ok ? gr : 0, ok ? gk : 0);
         } else if (gr < rmax && gk < K) {
           if (vec && gk + 7 < K) t = *reinterpret_cast<const u32x4*>(src);
           else {
@@ -63,8 +71,8 @@ template <int R, bool EDGE, bool MASKED> struct RingLoadK {
 #pragma unroll
             for (int e = 0; e < 8; ++e) if (gk + e < K) te[e] = src[e];
           }
+          if (MASKED) mb[SLOT][i] = mask_bits(mask, mp, gr, gk);
         }
-        if (MASKED && (!EDGE || (gr < rmax && gk < K))) mb[SLOT][i] = mask_bits(mask, mp, gr, gk);
       }
       v[SLOT][i] = t;
     }
@@ -86,7 +94,7 @@ template <int R, bool EDGE, bool MASKED> struct RingLoadK {
 // dense, M/N contiguous: element (row, k) at p[k*ld + row].  Every thread owns a KPT(k) x 8(row) block
 // (KPT = 4 for 256-row tiles, 2 for 128-row tiles, so that all 256 threads have one and the code is free
 // of predicates) and transposes it in registers: LDS receives, for each of the 8 rows, KPT consecutive k.
-template <int R, bool EDGE, bool MASKED> struct RingLoadMN {
+template <int R, int EMODE, bool MASKED> struct RingLoadMN {
   typedef LdsBF16<R, kBK3> L;
   static constexpr int RB = R / 8;               // row blocks
   static constexpr int KPT = R / 64;             // k rows per thread
@@ -111,8 +119,14 @@ template <int R, bool EDGE, bool MASKED> struct RingLoadMN {
       const int gk = k0 + kq * KPT + kk;
       if (MASKED) mb[SLOT][kk] = 0u;
       const uint16_t* src = p + ((uint32_t)gk * ld + (uint32_t)gr);
-      if (!EDGE) {
+      if (EMODE == 0) {
         t = *reinterpret_cast<const u32x4*>(src);
+        if (MASKED) mb[SLOT][kk] = mask_bits(mask, mp, gk, gr);
+      } else if (EMODE == 1) {
+        const bool ok = gk < K && gr < rmax;
+        t = *reinterpret_cast<const u32x4*>(ok ? src : p);
+        if (!ok) t = u32x4{0u, 0u, 0u, 0u};
+        if (MASKED) mb[SLOT][kk] = mask_bits(mask, mp, ok ? gk : 0, ok ? gr : 0);
       } else if (gk < K && gr < rmax) {
         if (vec && gr + 7 < rmax) t = *reinterpret_cast<const u32x4*>(src);
         else {
@@ -120,8 +134,8 @@ template <int R, bool EDGE, bool MASKED> struct RingLoadMN {
 #pragma unroll
           for (int e = 0; e < 8; ++e) if (gr + e < rmax) te[e] = src[e];
         }
+        if (MASKED) mb[SLOT][kk] = mask_bits(mask, mp, gk, gr);
       }
-      if (MASKED && (!EDGE || (gk < K && gr < rmax))) mb[SLOT][kk] = mask_bits(mask, mp, gk, gr);
       v[SLOT][kk] = t;
     }
   }
@@ -145,10 +159,14 @@ template <int R, bool EDGE, bool MASKED> struct RingLoadMN {
       }
       *reinterpret_cast<u32x2*>(dlo) = lo;
       *reinterpret_cast<u32x2*>(dhi) = hi;
-    } else {
+    } else if constexpr (KPT == 2) {
       const uint32_t a = v[SLOT][0][D], b = v[SLOT][1][D];
       *reinterpret_cast<uint32_t*>(dlo) = __builtin_amdgcn_perm(b, a, 0x05040100u);
       *reinterpret_cast<uint32_t*>(dhi) = __builtin_amdgcn_perm(b, a, 0x07060302u);
+    } else {
+      const uint32_t a = v[SLOT][0][D];
+      *dlo = (uint16_t)a;
+      *dhi = (uint16_t)(a >> 16);
     }
   }
 };
@@ -218,10 +236,10 @@ template <int R, int SE> struct RingLoadSparse {
   }
 };
 
-template <int KIND, int R, int SE, bool EDGE, bool MASKED> struct RingLoaderOf;
-template <int R, int SE, bool EDGE, bool MASKED> struct RingLoaderOf<kOpK, R, SE, EDGE, MASKED> { typedef RingLoadK<R, EDGE, MASKED> type; };
-template <int R, int SE, bool EDGE, bool MASKED> struct RingLoaderOf<kOpMN, R, SE, EDGE, MASKED> { typedef RingLoadMN<R, EDGE, MASKED> type; };
-template <int R, int SE, bool EDGE, bool MASKED> struct RingLoaderOf<kOpSparse, R, SE, EDGE, MASKED> { typedef RingLoadSparse<R, SE> type; };
+template <int KIND, int R, int SE, int EMODE, bool MASKED> struct RingLoaderOf;
+template <int R, int SE, int EMODE, bool MASKED> struct RingLoaderOf<kOpK, R, SE, EMODE, MASKED> { typedef RingLoadK<R, EMODE, MASKED> type; };
+template <int R, int SE, int EMODE, bool MASKED> struct RingLoaderOf<kOpMN, R, SE, EMODE, MASKED> { typedef RingLoadMN<R, EMODE, MASKED> type; };
+template <int R, int SE, int EMODE, bool MASKED> struct RingLoaderOf<kOpSparse, R, SE, EMODE, MASKED> { typedef RingLoadSparse<R, SE> type; };
 
 template <class LD, int SLOT> __device__ __forceinline__ void commit_all(LD& l, uint16_t* lds) {
   l.template commit_step<SLOT, 0>(lds); l.template commit_step<SLOT, 1>(lds);
@@ -283,11 +301,12 @@ template <int V> using IntC = std::integral_constant<int, V>;
 
 template <int AK, int BKIND, int EPI, int BM, int BN, int SE, int FLAGS>
 __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
-  constexpr bool EDGE = (FLAGS & kFlagEdge) != 0;
+  constexpr bool EDGE = (FLAGS & (kFlagEdge | kFlagEdgeVec)) != 0;
+  constexpr int EMODE = (FLAGS & kFlagEdge) ? 2 : (FLAGS & kFlagEdgeVec) ? 1 : 0;
   constexpr int BK = kBK3;
   typedef Gemm3Smem<EPI, BM, BN> S;
-  typedef typename RingLoaderOf<AK, BM, SE, EDGE, (FLAGS & kFlagMaskA) != 0>::type LoadA;
-  typedef typename RingLoaderOf<BKIND, BN, SE, EDGE, (FLAGS & kFlagMaskB) != 0>::type LoadB;
+  typedef typename RingLoaderOf<AK, BM, SE, EMODE, (FLAGS & kFlagMaskA) != 0>::type LoadA;
+  typedef typename RingLoaderOf<BKIND, BN, SE, EMODE, (FLAGS & kFlagMaskB) != 0>::type LoadB;
   constexpr int TM = BM / 64, TN = BN / 64;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   uint16_t* const smem = reinterpret_cast<uint16_t*>(smem_raw);

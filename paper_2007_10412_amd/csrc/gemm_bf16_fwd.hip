@@ -1,13 +1,20 @@
-// bf16 GEMM family: forward y = act(x W + b) with the fused bits / pack epilogue.
+// bf16 GEMM family "fwd" (see gemm.hpp for the operand kinds).
 #include "gemm_launch.hpp"
 
 namespace rad {
 
 hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t st, const char** name) {
-  // 256x256 tiles (one workgroup per CU) when they give at least half a wave of workgroups
-  const bool big = tiles_of(g, 256, 256) >= 128;
-  if (name) *name = big ? "gemm_bf16_fwd_256" : "gemm_bf16_fwd_128";
-  if (big) return run_gemm3<kOpK, kOpMN, kEpiFwd, 256, 256, 0, false, false>(g, st);
+  // 256x256 tiles (one workgroup per CU) when they give at least half a wave of workgroups; otherwise the
+  // widest tile that still gives every CU a workgroup
+  if (tiles_of(g, 256, 256) >= 128) {
+    if (name) *name = "gemm_bf16_fwd_256";
+    return run_gemm3<kOpK, kOpMN, kEpiFwd, 256, 256, 0, false, false>(g, st);
+  }
+  if (tiles_of(g, 256, 64) >= 192 && tiles_of(g, 128, 128) < 2 * tiles_of(g, 256, 64)) {
+    if (name) *name = "gemm_bf16_fwd_256x64";
+    return run_gemm3<kOpK, kOpMN, kEpiFwd, 256, 64, 0, false, false, false>(g, st);
+  }
+  if (name) *name = "gemm_bf16_fwd_128";
   return run_gemm3<kOpK, kOpMN, kEpiFwd, 128, 128, 0, false, false>(g, st);
 }
 

@@ -6,10 +6,16 @@
 namespace rad {
 
 hipError_t launch_gemm_bf16_sparse7(const GemmArgs& g, hipStream_t st, const char** name) {
-  const bool big = tiles_of(g, 256, 256) >= 128;
-  if (name) *name = big ? "gemm_bf16_dw_sparse_256x256" : "gemm_bf16_dw_sparse_256x128";
-  if (big) return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 256, 7, false, true>(g, st);
-  return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 128, 7, false, true, false>(g, st);
+  if (tiles_of(g, 256, 256) >= 128) {
+    if (name) *name = "gemm_bf16_dw_sparse_256x256";
+    return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 256, 7, false, true>(g, st);
+  }
+  if (tiles_of(g, 256, 128) >= 192) {
+    if (name) *name = "gemm_bf16_dw_sparse_256x128";
+    return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 128, 7, false, true, false>(g, st);
+  }
+  if (name) *name = "gemm_bf16_dw_sparse_256x64";
+  return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 64, 7, false, true, false>(g, st);
 }
 
 }  // namespace rad

@@ -69,8 +69,21 @@ hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
   return hipGetLastError();
 }
 
-// Variants built per family: interior + guarded without a loader mask, and guarded with one (loader masks
-// serve the stand-alone entry points; the train steps mask in the producing epilogue instead).
+// ragged shapes whose every operand access is still a whole 16-byte vector: pitches, K and the extent along
+// the contiguous axis are multiples of 8 elements
+template <int AK, int BKIND>
+bool gemm_is_vec_edge(const GemmArgs& g) {
+  bool ok = g.K > 0 && (reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && g.ldb % 8 == 0;
+  if (AK != kOpSparse) ok = ok && (reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && g.lda % 8 == 0;
+  if (AK == kOpK || BKIND == kOpK) ok = ok && g.K % 8 == 0;
+  if (AK == kOpMN) ok = ok && g.M % 8 == 0;
+  if (BKIND == kOpMN) ok = ok && g.N % 8 == 0;
+  return ok;
+}
+
+// Variants built per family: interior, vector-predicated ragged and generic ragged without a loader mask;
+// generic ragged with one (loader masks serve the stand-alone entry points; the train steps mask in the
+// producing epilogue instead).
 template <int AK, int BKIND, int EPI, int BM, int BN, int SE, bool MASK_A, bool MASK_B, bool BOTH_EDGE = true>
 hipError_t run_gemm3(const GemmArgs& g, hipStream_t st) {
   if (g.dry_run) return hipSuccess;
@@ -79,6 +92,7 @@ hipError_t run_gemm3(const GemmArgs& g, hipStream_t st) {
   constexpr int FA = MASK_A ? kFlagMaskA : 0, FB = MASK_B ? kFlagMaskB : 0;
   if (ma || mb) return run_gemm3_variant<AK, BKIND, EPI, BM, BN, SE, kFlagEdge | FA | FB>(g, st);
   if (BOTH_EDGE && gemm_is_full<BF16Tag, AK, BM, BN, 32>(g)) return run_gemm3_variant<AK, BKIND, EPI, BM, BN, SE, 0>(g, st);
+  if (gemm_is_vec_edge<AK, BKIND>(g)) return run_gemm3_variant<AK, BKIND, EPI, BM, BN, SE, kFlagEdgeVec>(g, st);
   return run_gemm3_variant<AK, BKIND, EPI, BM, BN, SE, kFlagEdge>(g, st);
 }
 
