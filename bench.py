@@ -22,6 +22,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X published
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy kernel),
+# see profiles/train_step_mlp4096_bf16_hbm_traffic.txt; only for the default workload and kernel
+MEASURED_TRAFFIC = {("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_dw_sparse_256x256"): 156.2e6}
 HBM_PEAK = 8000.0                          # GB/s
 
 WORKLOADS = {
@@ -112,7 +115,7 @@ def main():
         "executed_frac": exe_flops / (avg_ms * 1e-3) / 1e12 / peak if avg_ms > 0 else None,
         "avg_launch_ms": avg_ms, "launches": n_launch, "launches_per_step": per_step,
         "algorithmic_flops_per_launch": alg_flops, "executed_flops_per_launch": exe_flops,
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC.get((args.workload, args.scheme, p, big)),
     }
 
     out = {
@@ -160,6 +163,7 @@ def main():
                 kern[nm]["executed_tflops"] = f / (kern[nm]["ms_per_step"] * 1e-3) / 1e12
         out["kernels"] = kern
         out["pack_stream"] = pack_stream(B, ctx, torch, dtype_name)
+        out["other_configs"] = other_configs(B, ctx, torch, synth)
 
     B.rad_model_destroy(model)
 
@@ -168,6 +172,76 @@ def main():
 
     B.rad_ctx_destroy(ctx)
     print(json.dumps(out))
+
+
+def other_configs(B, ctx, torch, synth):
+    """samples/s of the train step on the remaining configurations (small, latency bound), a few steps each."""
+    import numpy as np
+    res = {}
+
+    def timed(fn, steps, batch):
+        fn(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(1 + i)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        return {"ms_per_step": 1e3 * dt, "samples_per_s": batch / dt}
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    # config 1: single layer 784 -> 300, batch 150, Bernoulli p = 0.1: forward+sample, dW, dX
+    d = synth.single_layer()
+    L = B.make_layer(150, 784, 300)
+    st = B.rad_store_create(ctx, L, B.RAD_BERNOULLI, 0.1)
+    x, W, dy = dev(d["x"]), dev(d["W"]), dev(d["dy"])
+    y = torch.empty(150, 300, device="cuda"); dW = torch.empty(784, 300, device="cuda"); dX = torch.empty(150, 784, device="cuda")
+
+    def c1(i):
+        B.rad_forward_sample(ctx, L, B.make_sampling(B.RAD_BERNOULLI, 0.1, i), x, W, None, y, st)
+        B.rad_backward_dW(ctx, L, st, dy, dW, None, 0.0)
+        B.rad_backward_dX(ctx, L, st, dy, W, dX)
+        B.rad_ctx_synchronize(ctx)
+    res["config1_layer_784x300_f32_bernoulli"] = timed(c1, 50, 150)
+    B.rad_store_destroy(st)
+
+    # config 2: MLP 784-300-300-10, batch 150, per-example fixed-k
+    dims = (784, 300, 300, 10)
+    d = synth.mlp(seed=1234, batch=150, dims=dims)
+    m = B.rad_model_create_mlp(ctx, B.RAD_F32, 150, list(dims), True, B.RAD_FIXEDK_PER_EXAMPLE, 0.1)
+    params, grads = [], []
+    for Wl, bl in zip(d["Ws"], d["bs"]):
+        params += [dev(Wl), dev(bl)]; grads += [torch.empty(Wl.shape, device="cuda"), torch.empty(bl.shape, device="cuda")]
+    x, lab = dev(d["x"]), dev(d["labels"])
+    res["config2_mlp_784_300_300_10_f32_per_example"] = timed(
+        lambda i: B.rad_train_step(ctx, m, B.make_sampling(B.RAD_FIXEDK_PER_EXAMPLE, 0.1, i), x, lab, params, grads), 50, 150)
+    B.rad_model_destroy(m)
+
+    # config 3: CNN 3-16-32-64 @32x32, batch 150, Bernoulli
+    ch, pool = (3, 16, 32, 64), (0, 1, 1)
+    d = synth.cnn(seed=1234, batch=150, channels=ch, pool=pool)
+    m = B.rad_model_create_cnn(ctx, 150, list(ch), list(pool), 3, 32, 32, 10, B.RAD_BERNOULLI, 0.1)
+    params, grads = [], []
+    for cv in d["convs"]:
+        params += [dev(cv["W"]), dev(cv["b"])]; grads += [torch.empty(cv["W"].shape, device="cuda"), torch.empty(cv["b"].shape, device="cuda")]
+    params += [dev(d["fc"][0]), dev(d["fc"][1])]; grads += [torch.empty(d["fc"][0].shape, device="cuda"), torch.empty(10, device="cuda")]
+    x, lab = dev(d["x"]), dev(d["labels"])
+    res["config3_cnn_f32_bernoulli"] = timed(
+        lambda i: B.rad_train_step(ctx, m, B.make_sampling(B.RAD_BERNOULLI, 0.1, i), x, lab, params, grads), 10, 150)
+    B.rad_model_destroy(m)
+
+    # config 5: ReLU RNN hidden 1024, T 784, batch 128, Bernoulli per step
+    d = synth.rnn(seed=1234)
+    m = B.rad_model_create_rnn(ctx, 128, 784, 1, 1024, 10, B.RAD_BERNOULLI, 0.1)
+    names = ["W_ih", "W_hh", "b", "W_ho", "b_o"]
+    params = [dev(d[n]) for n in names]; grads = [torch.empty(d[n].shape, device="cuda") for n in names]
+    x, lab = dev(d["x"]), dev(d["labels"])
+    res["config5_rnn_h1024_T784_f32_bernoulli"] = timed(
+        lambda i: B.rad_train_step(ctx, m, B.make_sampling(B.RAD_BERNOULLI, 0.1, i), x, lab, params, grads), 3, 128)
+    B.rad_model_destroy(m)
+    return res
 
 
 def pack_stream(B, ctx, torch, dtype_name):
@@ -207,7 +281,7 @@ def cpu_baseline(data, dims, scheme, p, dtype, batch, has_bias):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     import numpy as np
     from oracle import rad_oracle as R
-    rows = min(batch, 1024)
+    rows = min(batch, 2048)
     bs = data["bs"] if has_bias else None
     t0 = time.perf_counter()
     R.mlp_train_step(data["x"][:rows], data["labels"][:rows], data["Ws"], bs, scheme, p, seed=1,

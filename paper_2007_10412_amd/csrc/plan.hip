@@ -55,9 +55,21 @@ __device__ __forceinline__ void finish_row(const PlanArgs& a, int prow, const ui
     for (int w = 0; w < kBucket / 32; ++w)
       if (w0 + w < a.bm_pitch) cnt += __popc(s_bm[w0 + w]);
   }
-  if (a.max_seg && tid < a.nb && cnt > 0) atomicMax(a.max_seg, cnt);
   int total;
   const int off = block_excl_scan(cnt, &total, s_scan);
+  // running maximum of entries per bucket over the whole store: one atomic per row at most, and only when
+  // the row raises it (a plain read first keeps the common case free of atomics)
+  if (a.max_seg) {
+    int mx = cnt;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = max(mx, __shfl_xor(mx, o));
+    if ((tid & 63) == 0) s_scan[4 + (tid >> 6)] = mx;
+    __syncthreads();
+    if (tid == 0) {
+      mx = max(max(s_scan[4], s_scan[5]), max(s_scan[6], s_scan[7]));
+      if (mx > *reinterpret_cast<volatile int*>(a.max_seg)) atomicMax(a.max_seg, mx);
+    }
+  }
   uint16_t* bo = a.bucket_off + (size_t)prow * (a.nb + 1);
   if (tid < a.nb) bo[tid] = (uint16_t)off;
   if (tid == 0) bo[a.nb] = (uint16_t)total;
@@ -155,14 +167,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fixedk_kernel(PlanArgs a) {
     }
   }
 
-  // k-th smallest key by four 8-bit radix passes, most significant first
+  // k-th smallest key: an 8-bit radix pass on the top byte, then (the usual case: a handful of keys share
+  // that byte) an exact rank among those candidates; else three more radix passes
+  __shared__ uint32_t s_cand[256];
+  __shared__ int s_ncand;
   uint64_t keep = 0;
   uint32_t prefix = 0, pmask = 0;
   int kk = a.k;                        // rank (1-based) still to find among matching keys
   int cnt_eq = 0;
+  int shift = 24;
 #pragma unroll 1
-  for (int shift = 24; shift >= 0; shift -= 8) {
+  for (; shift >= 0; shift -= 8) {
     s_hist[tid] = 0;
+    if (tid == 0) s_ncand = 0;
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < QPT * 4; ++e)
@@ -179,6 +196,26 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fixedk_kernel(PlanArgs a) {
     kk = s_sel[1];
     cnt_eq = s_sel[2];
     __syncthreads();
+    if (shift > 0 && cnt_eq <= 256) {
+      // candidates: keys matching the prefix so far (any order)
+#pragma unroll
+      for (int e = 0; e < QPT * 4; ++e)
+        if (((valid >> e) & 1ull) && (key[e] & pmask) == prefix) s_cand[atomicAdd(&s_ncand, 1)] = key[e];
+      __syncthreads();
+      const int n = s_ncand;
+      if (tid < n) {
+        const uint32_t v = s_cand[tid];
+        int less = 0, leq = 0;
+        for (int i = 0; i < n; ++i) { const uint32_t o = s_cand[i]; less += o < v; leq += o <= v; }
+        if (less < kk && kk <= leq) { s_sel[0] = (int)v; s_sel[1] = kk - less; s_sel[2] = leq - less; }
+      }
+      __syncthreads();
+      prefix = (uint32_t)s_sel[0];
+      kk = s_sel[1];
+      cnt_eq = s_sel[2];
+      __syncthreads();
+      break;
+    }
   }
   const uint32_t thr = prefix;         // the k-th smallest key; kk of its cnt_eq copies are kept
   if (cnt_eq == kk) {
@@ -261,49 +298,66 @@ __device__ __forceinline__ float load_as_f32(const uint16_t* p) { return bf16_bi
 __device__ __forceinline__ void store_from_f32(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_from_f32(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
 
-// One wave packs one 256-column bucket of one row: lane l owns columns
-// 4l..4l+3 of the bucket (one 16-byte load of fp32, 8 bytes of bf16).
+// One workgroup packs one row.  Wave w takes the 256-column buckets w, w+4, w+8, ... four at a time, so a
+// lane has four 16-byte loads in flight; lane l owns columns 4l..4l+3 of a bucket.
 template <typename T>
 __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ x, StoreView s) {
-  const int lane = threadIdx.x & 63;
-  const int bucket = blockIdx.y * 4 + (threadIdx.x >> 6);
-  const int row = blockIdx.x;
-  if (bucket >= s.nb) return;
-  const int j0 = bucket * kBucket + lane * 4;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  T* vals = reinterpret_cast<T*>(s.values);
+  const bool vec = (s.cols & 3) == 0;
+  for (int row = blockIdx.x; row < s.rows; row += gridDim.x) {     // a few thousand workgroups walk all rows
   const int prow = row * s.plan_row_stride;
-  uint32_t nib = 0;
-  if (j0 < s.cols) nib = (s.bitmap[(size_t)prow * s.bm_pitch + (j0 >> 5)] >> (j0 & 31)) & 0xFu;
-  float v[4] = {0.f, 0.f, 0.f, 0.f};
   const T* xr = x + (size_t)row * s.cols;
-  if (j0 < s.cols) {
-    if ((s.cols & 3) == 0) {
-      typename Vec4<T>::type raw = *reinterpret_cast<const typename Vec4<T>::type*>(xr + j0);
-      const T* e = reinterpret_cast<const T*>(&raw);
+  const uint32_t* bm = s.bitmap + (size_t)prow * s.bm_pitch;
+  const uint16_t* bo = s.bucket_off + (size_t)prow * (s.nb + 1);
+  const int64_t base = (int64_t)s.row_ptr[row];
+  for (int b0 = w; b0 < s.nb; b0 += 16) {
+    float v[4][4];
+    uint32_t nib[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) v[i] = load_as_f32(e + i);
-    } else {
+    for (int u = 0; u < 4; ++u) {
+      const int bucket = b0 + 4 * u;
+      const int j0 = bucket * kBucket + lane * 4;
+      nib[u] = 0;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) if (j0 + i < s.cols) v[i] = load_as_f32(xr + j0 + i);
+      for (int i = 0; i < 4; ++i) v[u][i] = 0.f;
+      if (bucket < s.nb && j0 < s.cols) {
+        nib[u] = (bm[j0 >> 5] >> (j0 & 31)) & 0xFu;
+        if (vec) {
+          typename Vec4<T>::type raw = *reinterpret_cast<const typename Vec4<T>::type*>(xr + j0);
+          const T* e = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[u][i] = load_as_f32(e + i);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) if (j0 + i < s.cols) v[u][i] = load_as_f32(xr + j0 + i);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int bucket = b0 + 4 * u;
+      if (bucket >= s.nb) break;
+      const int j0 = bucket * kBucket + lane * 4;
+      int prefix = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) prefix += lanes_below(__ballot((nib[u] >> e) & 1u));
+      // entries of lower lanes come first, then this lane's own in column order
+      int rel = bo[bucket] + prefix;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if ((nib[u] >> e) & 1u) {
+          const int64_t pos = base + rel;
+          if (pos < s.capacity) {
+            store_from_f32(vals + pos, v[u][e] * s.scale);
+            if (!s.idx_shared) s.indices[pos] = (uint16_t)(j0 + e);
+            else if (row == 0) s.indices[rel] = (uint16_t)(j0 + e);
+          }
+          ++rel;
+        }
+      }
     }
   }
-  int prefix = 0;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) prefix += lanes_below(__ballot((nib >> e) & 1u));
-  // entries of lower lanes come first, then this lane's own in column order
-  int rel = s.bucket_off[(size_t)prow * (s.nb + 1) + bucket] + prefix;
-  const int64_t base = (int64_t)s.row_ptr[row];
-  T* vals = reinterpret_cast<T*>(s.values);
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    if ((nib >> e) & 1u) {
-      const int64_t pos = base + rel;
-      if (pos < s.capacity) {
-        store_from_f32(vals + pos, v[e] * s.scale);
-        if (!s.idx_shared) s.indices[pos] = (uint16_t)(j0 + e);
-        else if (row == 0) s.indices[rel] = (uint16_t)(j0 + e);
-      }
-      ++rel;
-    }
   }
 }
 
@@ -356,7 +410,7 @@ hipError_t launch_row_scan(const uint32_t* row_cnt, uint32_t* row_ptr, int rows,
 }
 
 hipError_t launch_pack(const void* x, int dtype, const StoreView& s, hipStream_t st) {
-  dim3 grid(s.rows, (s.nb + 3) / 4), block(256);
+  dim3 grid(s.rows), block(256);
   if (dtype == kF32)
     hipLaunchKernelGGL(pack_kernel<float>, grid, block, 0, st, (const float*)x, s);
   else
