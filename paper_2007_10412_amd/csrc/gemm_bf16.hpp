@@ -313,9 +313,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
   constexpr int kStageElems = S::STAGE / 2;
   constexpr int kAElems = BM * BK;
 
-  const int tiles_n = (g.N + BN - 1) / BN;
-  const int tile = blockIdx.x;
-  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  // Tile order.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2, so ids are first
+  // regrouped into 8 contiguous chunks (one per XCD); within the sequence, tiles are walked in groups of
+  // 4 tile rows, column by column, so that the 32 workgroups resident on one XCD cover a 4 x 8 block of
+  // tiles and share their operand slices through that L2.
+  const int tiles_n = (g.N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
+  const int T = tiles_m * tiles_n;
+  int lin = blockIdx.x;
+  if ((T & 7) == 0) lin = (lin & 7) * (T >> 3) + (lin >> 3);
+  constexpr int GM = 4;
+  const int grp = lin / (GM * tiles_n), within = lin - grp * (GM * tiles_n);
+  const int gh = min(GM, tiles_m - grp * GM);      // rows in this (possibly last, shorter) group
+  const int tm = grp * GM + within % gh, tn = within / gh;
+  const int m0 = tm * BM, n0 = tn * BN;
   const int w = threadIdx.x >> 6;
   const int wm0 = (w >> 1) * (BM / 2), wn0 = (w & 1) * (BN / 2);
 
