@@ -190,6 +190,8 @@ struct rad_store {
   int bits_pitch = 0, nb = 0, bm_pitch = 0;
   int plan_rows_per_step = 0;     // rows (per example / Bernoulli), 1 (shared), 0 (exact)
   size_t elem() const { return dtype == kBF16 ? 2 : 4; }
+  // bf16 stores with per-entry draws keep (value, column) in one 32-bit entry
+  bool paired() const { return dtype == kBF16 && (scheme == kBernoulli || scheme == kFixedKPerExample); }
   size_t bitmap_words() const { return (size_t)steps * plan_rows_per_step * bm_pitch; }
 };
 
@@ -201,6 +203,7 @@ static StoreView store_view(const rad_store* s, int slot) {
   v.scale = s->scale;
   v.plan_row_stride = s->scheme == kFixedKShared ? 0 : 1;
   v.idx_shared = s->scheme == kFixedKShared ? 1 : 0;
+  v.paired = s->paired() ? 1 : 0;
   v.indices = s->scheme == kFixedKShared ? s->indices + (size_t)slot * s->k : s->indices;
   v.row_ptr = s->row_ptr ? s->row_ptr + (size_t)slot * s->rows : nullptr;
   const size_t prow0 = (size_t)slot * s->plan_rows_per_step;
@@ -279,11 +282,11 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   auto alloc = [&](void** ptr, size_t bytes) -> bool {
     return hipMalloc(ptr, bytes ? bytes : 16) == hipSuccess;
   };
-  bool ok = alloc(&s->values, (size_t)s->capacity * s->elem());
+  bool ok = alloc(&s->values, s->paired() ? (size_t)(s->capacity + kPairPad) * 4 : (size_t)s->capacity * s->elem());
   ok = ok && alloc((void**)&s->overflow, 2 * sizeof(int));   // [0] capacity overflow flag, [1] longest bucket segment
   if (scheme != RAD_EXACT) {
     const size_t n_idx = scheme == RAD_FIXEDK_SHARED ? (size_t)steps * s->k : (size_t)s->capacity;
-    ok = ok && alloc((void**)&s->indices, n_idx * 2);
+    if (!s->paired()) ok = ok && alloc((void**)&s->indices, n_idx * 2);
     ok = ok && alloc((void**)&s->row_ptr, (size_t)(R + 1) * 4);
     ok = ok && alloc((void**)&s->bucket_off, (size_t)steps * s->plan_rows_per_step * (s->nb + 1) * 2);
     if (scheme == RAD_BERNOULLI) ok = ok && alloc((void**)&s->row_cnt, (size_t)R * 4);
@@ -337,10 +340,13 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
   RAD_TRY(store_nnz(c, s, &nnz));
   if (nnz > capacity) return fail(c, RAD_ERR_CAPACITY, "export buffers too small");
   const int64_t R = (int64_t)s->steps * s->rows;
-  std::vector<unsigned char> vraw((size_t)nnz * s->elem());
+  std::vector<unsigned char> vraw((size_t)nnz * (s->paired() ? 4 : s->elem()));
   if (nnz) HIP_TRY(c, hipMemcpy(vraw.data(), s->values, vraw.size(), hipMemcpyDeviceToHost));
   for (int64_t i = 0; i < nnz; ++i) {
-    if (s->dtype == kBF16) {
+    if (s->paired()) {
+      uint32_t u = reinterpret_cast<uint32_t*>(vraw.data())[i] & 0xFFFF0000u;
+      std::memcpy(&val[i], &u, 4);
+    } else if (s->dtype == kBF16) {
       uint32_t u = (uint32_t)reinterpret_cast<uint16_t*>(vraw.data())[i] << 16;
       std::memcpy(&val[i], &u, 4);
     } else val[i] = reinterpret_cast<float*>(vraw.data())[i];
@@ -358,6 +364,17 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
     HIP_TRY(c, hipMemcpy(idx.data(), s->indices, idx.size() * 2, hipMemcpyDeviceToHost));
     for (int64_t r = 0; r < R; ++r)
       for (int j = 0; j < s->k; ++j) col[r * s->k + j] = idx[(size_t)(r / s->rows) * s->k + j];
+  } else if (s->paired()) {
+    // the bucket of an entry follows from its position in the row
+    std::vector<uint16_t> bo((size_t)R * (s->nb + 1));
+    HIP_TRY(c, hipMemcpy(bo.data(), s->bucket_off, bo.size() * 2, hipMemcpyDeviceToHost));
+    const uint32_t* ent = reinterpret_cast<const uint32_t*>(vraw.data());
+    for (int64_t r = 0; r < R; ++r) {
+      const uint16_t* b = bo.data() + (size_t)r * (s->nb + 1);
+      for (int t = 0; t < s->nb; ++t)
+        for (int64_t e = (int64_t)rp[(size_t)r] + b[t]; e < (int64_t)rp[(size_t)r] + b[t + 1] && e < nnz; ++e)
+          col[e] = pair_col(ent[e], t);
+    }
   } else {
     std::vector<uint16_t> idx((size_t)nnz);
     if (nnz) HIP_TRY(c, hipMemcpy(idx.data(), s->indices, idx.size() * 2, hipMemcpyDeviceToHost));
@@ -643,6 +660,8 @@ struct rad_model {
   int ksize = 0, fc_in = 0;
   void* buf[3] = {nullptr, nullptr, nullptr};   // transient dense activations / gradients
   size_t elem() const { return dtype == kBF16 ? 2 : 4; }
+  // bf16 stores with per-entry draws keep (value, column) in one 32-bit entry
+  bool paired() const { return dtype == kBF16 && (scheme == kBernoulli || scheme == kFixedKPerExample); }
 };
 
 extern "C" rad_status rad_model_destroy(rad_model* m) {

@@ -48,7 +48,23 @@ struct StoreView {
   int bm_pitch;              // words per bitmap row
   int plan_row_stride;       // 1, or 0 when every row shares one plan row (shared scheme)
   int idx_shared;            // shared scheme: `indices` holds the k columns once (written by row 0)
+  int paired;                // bf16 per-entry draws: `values` holds 32-bit (value, column) entries, no `indices`
   float scale;
 };
+
+// Entry of a paired bf16 store: the bf16 value bits in the high half; in the low half the column inside
+// its 256-column bucket, written as the byte offset of that column's 64-byte row in the XOR-swizzled
+// 32-deep LDS tile the dW kernel scatters into (column << 6, swizzle term of the row in bits 4..5).  The
+// kernel gets the LDS address of an entry with one XOR; everything else decodes the column back.
+constexpr int kPairPad = 64;     // entries allocated past the capacity, so a lane may read beyond a segment
+__host__ __device__ __forceinline__ constexpr uint32_t pair_code(int col_in_bucket) {
+  return ((uint32_t)col_in_bucket << 6) | ((uint32_t)((col_in_bucket ^ (col_in_bucket >> 3)) & 3) << 4);
+}
+__host__ __device__ __forceinline__ constexpr uint32_t pair_make(uint32_t bf16_bits, int col) {
+  return (bf16_bits << 16) | pair_code(col & (kBucket - 1));
+}
+__host__ __device__ __forceinline__ constexpr int pair_col(uint32_t entry, int bucket) {
+  return bucket * kBucket + (int)((entry >> 6) & (uint32_t)(kBucket - 1));
+}
 
 }  // namespace rad

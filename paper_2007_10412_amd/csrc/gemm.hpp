@@ -38,10 +38,13 @@ template <int R, int BK> struct LdsF32 {
 template <int R, int BK> struct LdsBF16 {
   static constexpr int CH = BK / 8;             // 16-byte units per row
   static constexpr int BYTES = R * BK * 2;
-  static __device__ __forceinline__ int unit(int row, int kc) {
+  static __host__ __device__ __forceinline__ constexpr int unit(int row, int kc) {
     return row * CH + (kc ^ ((row ^ (row >> 3)) & (CH - 1)));
   }
 };
+// the paired store entries carry this layout's row offset
+static_assert(LdsBF16<256, 32>::unit(0xB5, 2) * 16 == (int)(pair_code(0xB5) ^ (2u << 4)), "pair_code / LDS layout");
+static_assert(LdsBF16<256, 32>::unit(0x4E, 1) * 16 == (int)(pair_code(0x4E) ^ (1u << 4)), "pair_code / LDS layout");
 
 __device__ __forceinline__ uint32_t mask_bits(const uint32_t* mask, int pitch, int outer, int inner) {
   return mask[(size_t)outer * pitch + (inner >> 5)] >> (inner & 31);
@@ -556,9 +559,13 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
           const int r2 = rel + __popcll(kw64 & ((1ull << lane) - 1ull));
           const int64_t p = base + r2;
           if (p < g.next.capacity) {
-            put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv * g.next.scale);
-            if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)col;
-            else if (row == 0) g.next.indices[r2] = (uint16_t)col;
+            if (g.next.paired) {
+              reinterpret_cast<uint32_t*>(g.next.values)[p] = pair_make(f32_to_bf16_bits(yv * g.next.scale), col);
+            } else {
+              put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv * g.next.scale);
+              if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)col;
+              else if (row == 0) g.next.indices[r2] = (uint16_t)col;
+            }
           }
         }
         rel += __popcll(kw64);

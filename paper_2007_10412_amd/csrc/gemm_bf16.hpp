@@ -5,15 +5,16 @@
 //   - runs the 2 x TM x TN MFMAs (v_mfma_f32_32x32x16_bf16) of slice kt from
 //     LDS stage kt%3,
 //   - moves slice kt+2 from registers into stage (kt+2)%3, last read before
-//     the previous barrier,
-//   - starts the global loads of slice kt+3 into the registers just freed,
+//     the previous barrier, during the first half of the MFMAs,
+//   - starts the global loads of slice kt+3 into each register as soon as it
+//     is free, so a load has almost a whole iteration to arrive,
 //   - reads the first fragments of slice kt+1 (complete since the previous
 //     barrier), so nothing waits on LDS after the one barrier per iteration.
 // The loop is unrolled three times so stages and slots are compile-time, and
 // the steady state is a single basic block in which sched_group_barrier
-// spreads LDS and global instructions between the MFMAs.  LDS loads and
-// stores are written in the alternating order wanted, because the compiler
-// keeps the relative order of LDS accesses it cannot prove disjoint.
+// spreads LDS, global and address instructions between the MFMAs.  LDS loads
+// and stores are written in the alternating order wanted, because the
+// compiler keeps the relative order of LDS accesses it cannot prove disjoint.
 #pragma once
 #include <type_traits>
 
@@ -36,6 +37,7 @@ template <int R, int EMODE, bool MASKED> struct RingLoadK {
   static constexpr int TOTAL = R * L::CH;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
   static constexpr int kDsWrites = NCH, kVmemReads = NCH * (MASKED ? 2 : 1);
+  static constexpr int kValuCommit = 0, kValuFetch = 0;   // vector ALU work worth spreading between MFMAs
   u32x4 v[kSlots][NCH];
   uint32_t mb[MASKED ? kSlots : 1][MASKED ? NCH : 1];   // ReLU bits of each chunk, applied at commit
   const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
@@ -100,6 +102,7 @@ template <int R, int EMODE, bool MASKED> struct RingLoadMN {
   static constexpr int KPT = R / 64;             // k rows per thread
   static_assert(RB * (kBK3 / KPT) == kGemmThreads, "one block per thread");
   static constexpr int kDsWrites = 8, kVmemReads = KPT * (MASKED ? 2 : 1);
+  static constexpr int kValuCommit = 40, kValuFetch = 8;
   u32x4 v[kSlots][KPT];                          // v[..][kk] = 8 consecutive rows at k = kq*KPT + kk
   uint32_t mb[MASKED ? kSlots : 1][MASKED ? KPT : 1];
   const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
@@ -177,42 +180,52 @@ template <int R, int EMODE, bool MASKED> struct RingLoadMN {
 // into them the entries of its eight store rows (eight lanes per store row),
 // so no block barrier is needed between clearing and scattering.
 template <int R, int SE> struct RingLoadSparse {
+  static_assert(R == kBucket && kBK3 == 32, "a tile is one bucket of the store; entries carry the 32-deep tile layout");
   typedef LdsBF16<R, kBK3> L;
   static constexpr int RPW = kBK3 / 4;          // store rows per wave
   static constexpr int LPR = 64 / RPW;          // lanes per store row
   static constexpr int NZ = R / 64;             // clearing stores per lane
   static constexpr int kCap = SE * LPR;         // entries of one (store row, bucket) segment held in registers
-  static constexpr int kDsWrites = NZ + SE, kVmemReads = 2 * SE + 3;
-  uint32_t ent[kSlots][SE];                      // (value bits << 16) | (column - m0), column 0xFFFF = none
+  static constexpr int kDsWrites = NZ + SE, kVmemReads = SE + 3;
+  static constexpr int kValuCommit = 4 * SE, kValuFetch = 16;
+  uint32_t ent[kSlots][SE];                      // paired store entries: value bits << 16 | row offset in the tile
+  int rem[kSlots];                               // entries left in the segment from this lane's first one on
   uint32_t nbeg, nend;
+  uint32_t raw_base; uint16_t raw_b0, raw_b1;    // loaded by bounds(), turned into [nbeg, nend) by the next fetch
   StoreView s; int m0, K, dummy;
   __device__ __forceinline__ void init(const void*, int64_t, const uint32_t*, int, int r0_, int, int K_,
                                        const StoreView& sv) { s = sv; m0 = r0_; K = K_; dummy = 0; }
-  // LDS element offset (from the A tile) of 64 spare bytes that absorb the stores of empty register entries
-  __device__ __forceinline__ void configure(int dummy_elems) { dummy = dummy_elems + (threadIdx.x & 31); }
-  // segment of the next slice's store row inside this tile's 256-column bucket
+  // LDS byte offset (from the A tile) of 64 spare bytes that absorb the stores of empty register entries
+  __device__ __forceinline__ void configure(int dummy_elems) { dummy = (dummy_elems + (threadIdx.x & 31)) * 2; }
+  // Segment of the next slice's store row inside this tile's 256-column bucket.  Only the loads are issued
+  // here; the arithmetic on them waits until the next fetch, one whole iteration later.
   __device__ __forceinline__ void bounds(int k0) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int b = k0 + w * RPW + lane / LPR;
     // no branch: rows past K read row K-1 and get an empty segment
-    store_segment(s, b < K ? b : K - 1, m0 / kBucket, &nbeg, &nend);
-    if (b >= K) nend = nbeg;
+    const int row = b < K ? b : K - 1;
+    const uint16_t* bo = s.bucket_off + (size_t)(row * s.plan_row_stride) * (s.nb + 1) + m0 / kBucket;
+    raw_base = s.row_ptr[row];
+    raw_b0 = bo[0];
+    raw_b1 = b < K ? bo[1] : (uint16_t)0;
   }
-  // Entries beyond kCap of a segment are not handled here: the host runs the overflow kernel after this
-  // GEMM, which adds them to dW (it exits at once unless the plan saw a segment that long).
+  __device__ __forceinline__ void segment() {
+    const uint32_t cap = (uint32_t)s.capacity;     // an overflowed Bernoulli draw never reads past the arrays
+    uint32_t b = raw_base + raw_b0, e = raw_base + raw_b1;
+    e = e > cap ? cap : e;
+    nbeg = b > e ? e : b; nend = e;
+  }
+  // A lane reads its SE entries without looking at the segment end (the store is allocated kPairPad
+  // entries past its capacity); entries beyond the end are dropped at commit time.  Entries beyond kCap
+  // of a segment are not handled here: the host runs the overflow kernel after this GEMM, which adds them
+  // to dW (it exits at once unless the plan saw a segment that long).
   template <int SLOT> __device__ __forceinline__ void fetch(int) {
-    const int sub = (threadIdx.x & 63) % LPR;
-    const uint16_t* vals = reinterpret_cast<const uint16_t*>(s.values);
+    segment();
+    const uint32_t e0 = nbeg + (threadIdx.x & 63) % LPR;
+    const uint32_t* ents = reinterpret_cast<const uint32_t*>(s.values) + e0;
+    rem[SLOT] = (int)(nend - e0);
 #pragma unroll
-    for (int i = 0; i < SE; ++i) {
-      // no branch: a register entry past the segment reads entry 0 of the store and is discarded
-      const uint32_t e = nbeg + sub + i * LPR;
-      const bool in_seg = e < nend;
-      const uint32_t ee = in_seg ? e : 0u;
-      const int c = (int)s.indices[ee] - m0;
-      const uint32_t v = vals[ee];
-      ent[SLOT][i] = (in_seg && c >= 0 && c < R) ? ((v << 16) | (uint32_t)c) : 0xFFFFu;
-    }
+    for (int i = 0; i < SE; ++i) ent[SLOT][i] = ents[i * LPR];
   }
   // steps 0 and 1 clear the wave's unit column of the tile, steps 2 and 3 scatter the entries into it
   template <int SLOT, int STEP> __device__ __forceinline__ void commit_step(uint16_t* lds) {
@@ -224,13 +237,15 @@ template <int R, int SE> struct RingLoadSparse {
         *reinterpret_cast<u32x4*>(&lds[L::unit(lane + q * 64, w) * 8]) = z;
     } else {
       const int kr = w * RPW + lane / LPR;
+      const uint32_t kpart = (uint32_t)(((kr >> 3) << 4) | ((kr & 7) << 1));   // byte offset of k inside a tile row
       constexpr int H = (SE + 1) / 2;
+      unsigned char* const base = reinterpret_cast<unsigned char*>(lds);
 #pragma unroll
       for (int i = (STEP - 2) * H; i < (STEP == 2 ? H : SE); ++i) {
-        const uint32_t c = ent[SLOT][i] & 0xFFFFu;
-        // no branch: an empty entry stores into the spare bytes instead
-        const int off = c != 0xFFFFu ? L::unit((int)c, kr >> 3) * 8 + (kr & 7) : dummy;
-        lds[off] = (uint16_t)(ent[SLOT][i] >> 16);
+        // both offsets are computed first so that the choice is a select, not a predicated region
+        const uint32_t off_real = (ent[SLOT][i] & 0xFFFFu) ^ kpart;
+        const uint32_t off = rem[SLOT] > i * LPR ? off_real : (uint32_t)dummy;
+        *reinterpret_cast<uint16_t*>(base + off) = (uint16_t)(ent[SLOT][i] >> 16);
       }
     }
   }
@@ -385,25 +400,29 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
     uint16_t* const wr = smem + s_wr * kStageElems;
     if constexpr (steady) {
       interleave_reads_commits<0, TM, TN, BM, BN>(cur, cur + kAElems, wr, wr + kAElems, wm0, wn0, fa1, fb1, la, lb);
-      mfma_step<TM, TN>(fa0, fb0, acc);
+      // the registers are free again: the loads of slice kt+3 start now and have until the top of the next
+      // iteration to arrive
       la.template fetch<0>((kt + 3) * BK); lb.template fetch<0>((kt + 3) * BK);
       la.bounds((kt + 4) * BK);
+      mfma_step<TM, TN>(fa0, fb0, acc);
       load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
       mfma_step<TM, TN>(fa1, fb1, acc);
       constexpr int kPairs = TM * TN / 2;             // MFMA pairs per half
       constexpr int kDsw = (LoadA::kDsWrites + LoadB::kDsWrites + kPairs - 1) / kPairs;
       constexpr int kVm = (LoadA::kVmemReads + LoadB::kVmemReads + kPairs - 1) / kPairs;
       constexpr int kDsr = (TM + TN + kPairs - 1) / kPairs;
+      constexpr int kVc = (LoadA::kValuCommit + LoadB::kValuCommit + LoadA::kValuFetch + LoadB::kValuFetch + kPairs - 1) / kPairs;
 #pragma unroll
       for (int i = 0; i < kPairs; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      // 2 MFMA
+        if (kVc > 0) __builtin_amdgcn_sched_group_barrier(0x002, kVc, 0);   // address / unpack arithmetic
         __builtin_amdgcn_sched_group_barrier(0x100, kDsr, 0);   // LDS reads (fragments of k-step 1)
         __builtin_amdgcn_sched_group_barrier(0x200, kDsw, 0);   // LDS writes (slice kt+2)
+        __builtin_amdgcn_sched_group_barrier(0x020, kVm, 0);    // global loads (slice kt+3)
       }
 #pragma unroll
       for (int i = 0; i < kPairs; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      // 2 MFMA
-        __builtin_amdgcn_sched_group_barrier(0x020, kVm, 0);    // global loads (slice kt+3)
         __builtin_amdgcn_sched_group_barrier(0x100, kDsr, 0);   // LDS reads (first fragments of slice kt+1)
       }
     } else {

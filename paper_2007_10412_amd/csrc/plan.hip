@@ -349,9 +349,13 @@ __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ x, Stor
         if ((nib[u] >> e) & 1u) {
           const int64_t pos = base + rel;
           if (pos < s.capacity) {
-            store_from_f32(vals + pos, v[u][e] * s.scale);
-            if (!s.idx_shared) s.indices[pos] = (uint16_t)(j0 + e);
-            else if (row == 0) s.indices[rel] = (uint16_t)(j0 + e);
+            if (s.paired) {
+              reinterpret_cast<uint32_t*>(s.values)[pos] = pair_make(f32_to_bf16_bits(v[u][e] * s.scale), j0 + e);
+            } else {
+              store_from_f32(vals + pos, v[u][e] * s.scale);
+              if (!s.idx_shared) s.indices[pos] = (uint16_t)(j0 + e);
+              else if (row == 0) s.indices[rel] = (uint16_t)(j0 + e);
+            }
           }
           ++rel;
         }
@@ -370,6 +374,19 @@ __global__ __launch_bounds__(256) void unpack_kernel(StoreView s, T* __restrict_
   __syncthreads();
   int64_t beg = s.row_ptr[row], end = s.row_ptr[row + 1];
   if (end > s.capacity) end = s.capacity;
+  if (s.paired) {
+    // the bucket of an entry follows from its position: walk the row bucket by bucket (at most 256 entries each)
+    const uint32_t* ent = reinterpret_cast<const uint32_t*>(s.values);
+    const uint16_t* bo = s.bucket_off + (size_t)(row * s.plan_row_stride) * (s.nb + 1);
+    for (int t = 0; t < s.nb; ++t) {
+      const int64_t e = beg + bo[t] + threadIdx.x;
+      if (e < beg + bo[t + 1] && e < end) {
+        const uint32_t u = ent[e];
+        reinterpret_cast<uint16_t*>(out)[pair_col(u, t)] = (uint16_t)(u >> 16);
+      }
+    }
+    return;
+  }
   const T* vals = reinterpret_cast<const T*>(s.values);
   // shared scheme: the k columns are stored once
   for (int64_t e = beg + threadIdx.x; e < end; e += 256) out[s.indices[s.idx_shared ? e - beg : e]] = vals[e];

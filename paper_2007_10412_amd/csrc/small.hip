@@ -131,8 +131,13 @@ __global__ __launch_bounds__(256) void dw_overflow_kernel(StoreView s, int rows,
   if (end > s.capacity) end = s.capacity;
   const T* vals = reinterpret_cast<const T*>(s.values);
   for (int64_t e = beg + cap; e < end; ++e) {
-    const int j = s.indices[e];
-    const float v = ld_elem(vals + e);
+    int j; float v;
+    if (s.paired) {
+      const uint32_t u = reinterpret_cast<const uint32_t*>(s.values)[e];
+      j = pair_col(u, t); v = __uint_as_float(u & 0xFFFF0000u);
+    } else {
+      j = s.indices[e]; v = ld_elem(vals + e);
+    }
     for (int n = lane; n < N; n += 64) {
       float g = ld_elem(dy + (size_t)b * N + n);
       if (bits && !((bits[(size_t)b * bits_pitch + (n >> 5)] >> (n & 31)) & 1u)) g = 0.f;
