@@ -22,24 +22,26 @@
 
 namespace rad {
 
-// K slices in flight in registers.  Three (fetch distance of three iterations) measured slower than one:
-// the compiler's wait-count pass drains every load in flight at the loop header, so the extra slots only
-// cost registers.
-constexpr int kSlots = 1;
+// NS = K slices in flight in registers (1 or 3).  With three, a global load has three iterations to
+// arrive; the 256x256 tile has no registers left for that and keeps one.
 constexpr int kBK3 = 32;
+
+// 16 bytes of zeros in device memory: what an out-of-bounds vector load of the ragged variants reads
+static __device__ __align__(16) const uint32_t kZeroChunk[4] = {0u, 0u, 0u, 0u};
 
 // ------------------------------------------------------------------ loaders
 // dense, K contiguous: element (row, k) at p[row*ld + k]
 // EMODE: 0 = interior (no guards), 1 = ragged but every access a whole in-bounds or out-of-bounds 16-byte
 // vector (guard by clamping the address and zeroing), 2 = generic element-wise guards.
-template <int R, int EMODE, bool MASKED> struct RingLoadK {
+template <int R, int EMODE, bool MASKED, int NS> struct RingLoadK {
   typedef LdsBF16<R, kBK3> L;
   static constexpr int TOTAL = R * L::CH;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
   static constexpr int kDsWrites = NCH, kVmemReads = NCH * (MASKED ? 2 : 1);
-  static constexpr int kValuCommit = 0, kValuFetch = 0;   // vector ALU work worth spreading between MFMAs
-  u32x4 v[kSlots][NCH];
-  uint32_t mb[MASKED ? kSlots : 1][MASKED ? NCH : 1];   // ReLU bits of each chunk, applied at commit
+  // vector ALU work worth spreading between MFMAs
+  static constexpr int kValuCommit = 0, kValuFetch = 0;
+  u32x4 v[NS][NCH];
+  uint32_t mb[MASKED ? NS : 1][MASKED ? NCH : 1];   // ReLU bits of each chunk, applied at commit
   const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
   __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
                                        int rmax_, int K_, const StoreView&) {
@@ -47,7 +49,8 @@ template <int R, int EMODE, bool MASKED> struct RingLoadK {
   }
   __device__ __forceinline__ void bounds(int) {}
   __device__ __forceinline__ void configure(int) {}
-  template <int SLOT> __device__ __forceinline__ void fetch(int k0) {
+  // KTAIL = false promises that the whole slice lies below K (every slice but the last)
+  template <int SLOT, bool KTAIL = true> __device__ __forceinline__ void fetch(int k0) {
     const bool vec = (ld & 7) == 0;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
@@ -62,10 +65,14 @@ template <int R, int EMODE, bool MASKED> struct RingLoadK {
           t = *reinterpret_cast<const u32x4*>(src);
           if (MASKED) mb[SLOT][i] = mask_bits(mask, mp, gr, gk);
         } else if (EMODE == 1) {
-          const bool ok = gr < rmax && gk < K;
-          t = *reinterpret_cast<const u32x4*>(ok ? src : p);
-          if (!ok) t = u32x4{0u, 0u, 0u, 0u};
-          if (MASKED) mb[SLOT][i] = mask_bits(mask, mp, ok ? gr : 0, ok ? gk : 0);
+          // Rows past the edge read the last valid row instead: they only feed output elements that are
+          // never stored.  A chunk past K must be zero and is read from a block of zeros, so nothing here
+          // waits for a load.
+          const int grc = min(gr, rmax - 1);
+          const uint16_t* srcc = p + ((uint32_t)grc * ld + (uint32_t)gk);
+          const bool ok = !KTAIL || gk < K;
+          t = *reinterpret_cast<const u32x4*>(ok ? srcc : reinterpret_cast<const uint16_t*>(kZeroChunk));
+          if (MASKED) mb[SLOT][i] = mask_bits(mask, mp, grc, ok ? gk : 0);
         } else if (gr < rmax && gk < K) {
           if (vec && gk + 7 < K) t = *reinterpret_cast<const u32x4*>(src);
           else {
@@ -96,15 +103,15 @@ template <int R, int EMODE, bool MASKED> struct RingLoadK {
 // dense, M/N contiguous: element (row, k) at p[k*ld + row].  Every thread owns a KPT(k) x 8(row) block
 // (KPT = 4 for 256-row tiles, 2 for 128-row tiles, so that all 256 threads have one and the code is free
 // of predicates) and transposes it in registers: LDS receives, for each of the 8 rows, KPT consecutive k.
-template <int R, int EMODE, bool MASKED> struct RingLoadMN {
+template <int R, int EMODE, bool MASKED, int NS> struct RingLoadMN {
   typedef LdsBF16<R, kBK3> L;
   static constexpr int RB = R / 8;               // row blocks
   static constexpr int KPT = R / 64;             // k rows per thread
   static_assert(RB * (kBK3 / KPT) == kGemmThreads, "one block per thread");
   static constexpr int kDsWrites = 8, kVmemReads = KPT * (MASKED ? 2 : 1);
   static constexpr int kValuCommit = 40, kValuFetch = 8;
-  u32x4 v[kSlots][KPT];                          // v[..][kk] = 8 consecutive rows at k = kq*KPT + kk
-  uint32_t mb[MASKED ? kSlots : 1][MASKED ? KPT : 1];
+  u32x4 v[NS][KPT];                          // v[..][kk] = 8 consecutive rows at k = kq*KPT + kk
+  uint32_t mb[MASKED ? NS : 1][MASKED ? KPT : 1];
   const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
   __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t* mask_, int mp_, int r0_,
                                        int rmax_, int K_, const StoreView&) {
@@ -112,7 +119,7 @@ template <int R, int EMODE, bool MASKED> struct RingLoadMN {
   }
   __device__ __forceinline__ void bounds(int) {}
   __device__ __forceinline__ void configure(int) {}
-  template <int SLOT> __device__ __forceinline__ void fetch(int k0) {
+  template <int SLOT, bool KTAIL = true> __device__ __forceinline__ void fetch(int k0) {
     const bool vec = (ld & 7) == 0;
     const int rb = threadIdx.x % RB, kq = threadIdx.x / RB;
     const int gr = r0 + rb * 8;
@@ -126,10 +133,12 @@ template <int R, int EMODE, bool MASKED> struct RingLoadMN {
         t = *reinterpret_cast<const u32x4*>(src);
         if (MASKED) mb[SLOT][kk] = mask_bits(mask, mp, gk, gr);
       } else if (EMODE == 1) {
-        const bool ok = gk < K && gr < rmax;
-        t = *reinterpret_cast<const u32x4*>(ok ? src : p);
-        if (!ok) t = u32x4{0u, 0u, 0u, 0u};
-        if (MASKED) mb[SLOT][kk] = mask_bits(mask, mp, ok ? gk : 0, ok ? gr : 0);
+        // as in the K-contiguous loader: blocks past the edge read the last valid block, rows past K read zeros
+        const int grc = min(gr, rmax - 8);
+        const uint16_t* srcc = p + ((uint32_t)gk * ld + (uint32_t)grc);
+        const bool ok = !KTAIL || gk < K;
+        t = *reinterpret_cast<const u32x4*>(ok ? srcc : reinterpret_cast<const uint16_t*>(kZeroChunk));
+        if (MASKED) mb[SLOT][kk] = mask_bits(mask, mp, ok ? gk : 0, grc);
       } else if (gk < K && gr < rmax) {
         if (vec && gr + 7 < rmax) t = *reinterpret_cast<const u32x4*>(src);
         else {
@@ -179,7 +188,7 @@ template <int R, int EMODE, bool MASKED> struct RingLoadMN {
 // [8w, 8w+8), one 16-byte unit of every tile row: it clears them and scatters
 // into them the entries of its eight store rows (eight lanes per store row),
 // so no block barrier is needed between clearing and scattering.
-template <int R, int SE> struct RingLoadSparse {
+template <int R, int SE, int NS> struct RingLoadSparse {
   static_assert(R == kBucket && kBK3 == 32, "a tile is one bucket of the store; entries carry the 32-deep tile layout");
   typedef LdsBF16<R, kBK3> L;
   static constexpr int RPW = kBK3 / 4;          // store rows per wave
@@ -188,8 +197,8 @@ template <int R, int SE> struct RingLoadSparse {
   static constexpr int kCap = SE * LPR;         // entries of one (store row, bucket) segment held in registers
   static constexpr int kDsWrites = NZ + SE, kVmemReads = SE + 3;
   static constexpr int kValuCommit = 4 * SE, kValuFetch = 16;
-  uint32_t ent[kSlots][SE];                      // paired store entries: value bits << 16 | row offset in the tile
-  int rem[kSlots];                               // entries left in the segment from this lane's first one on
+  uint32_t ent[NS][SE];                      // paired store entries: value bits << 16 | row offset in the tile
+  int rem[NS];                               // entries left in the segment from this lane's first one on
   uint32_t nbeg, nend;
   uint32_t raw_base; uint16_t raw_b0, raw_b1;    // loaded by bounds(), turned into [nbeg, nend) by the next fetch
   StoreView s; int m0, K, dummy;
@@ -219,7 +228,7 @@ template <int R, int SE> struct RingLoadSparse {
   // entries past its capacity); entries beyond the end are dropped at commit time.  Entries beyond kCap
   // of a segment are not handled here: the host runs the overflow kernel after this GEMM, which adds them
   // to dW (it exits at once unless the plan saw a segment that long).
-  template <int SLOT> __device__ __forceinline__ void fetch(int) {
+  template <int SLOT, bool KTAIL = true> __device__ __forceinline__ void fetch(int) {
     segment();
     const uint32_t e0 = nbeg + (threadIdx.x & 63) % LPR;
     const uint32_t* ents = reinterpret_cast<const uint32_t*>(s.values) + e0;
@@ -251,10 +260,10 @@ template <int R, int SE> struct RingLoadSparse {
   }
 };
 
-template <int KIND, int R, int SE, int EMODE, bool MASKED> struct RingLoaderOf;
-template <int R, int SE, int EMODE, bool MASKED> struct RingLoaderOf<kOpK, R, SE, EMODE, MASKED> { typedef RingLoadK<R, EMODE, MASKED> type; };
-template <int R, int SE, int EMODE, bool MASKED> struct RingLoaderOf<kOpMN, R, SE, EMODE, MASKED> { typedef RingLoadMN<R, EMODE, MASKED> type; };
-template <int R, int SE, int EMODE, bool MASKED> struct RingLoaderOf<kOpSparse, R, SE, EMODE, MASKED> { typedef RingLoadSparse<R, SE> type; };
+template <int KIND, int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf;
+template <int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf<kOpK, R, SE, EMODE, MASKED, NS> { typedef RingLoadK<R, EMODE, MASKED, NS> type; };
+template <int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf<kOpMN, R, SE, EMODE, MASKED, NS> { typedef RingLoadMN<R, EMODE, MASKED, NS> type; };
+template <int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf<kOpSparse, R, SE, EMODE, MASKED, NS> { typedef RingLoadSparse<R, SE, NS> type; };
 
 template <class LD, int SLOT> __device__ __forceinline__ void commit_all(LD& l, uint16_t* lds) {
   l.template commit_step<SLOT, 0>(lds); l.template commit_step<SLOT, 1>(lds);
@@ -320,8 +329,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
   constexpr int EMODE = (FLAGS & kFlagEdge) ? 2 : (FLAGS & kFlagEdgeVec) ? 1 : 0;
   constexpr int BK = kBK3;
   typedef Gemm3Smem<EPI, BM, BN> S;
-  typedef typename RingLoaderOf<AK, BM, SE, EMODE, (FLAGS & kFlagMaskA) != 0>::type LoadA;
-  typedef typename RingLoaderOf<BKIND, BN, SE, EMODE, (FLAGS & kFlagMaskB) != 0>::type LoadB;
+  constexpr int NS = (BM * BN >= 256 * 256) ? 1 : 3;
+  typedef typename RingLoaderOf<AK, BM, SE, EMODE, (FLAGS & kFlagMaskA) != 0, NS>::type LoadA;
+  typedef typename RingLoaderOf<BKIND, BN, SE, EMODE, (FLAGS & kFlagMaskB) != 0, NS>::type LoadB;
   constexpr int TM = BM / 64, TN = BN / 64;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   uint16_t* const smem = reinterpret_cast<uint16_t*>(smem_raw);
@@ -358,52 +368,21 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
   la.configure((BM + BN) * BK);
   const int KT = (g.K + BK - 1) / BK;
 
-  // prologue: slices 0 and 1 into stages 0 and 1, slice 2 into the registers.  The long-K path is
-  // written without conditions so that the steady loop is entered with a known set of loads in flight.
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  const bool long_k = KT > 5;
-  if (long_k) {
-    la.bounds(0);
-    la.template fetch<0>(0); lb.template fetch<0>(0);
-    la.bounds(BK);
-    commit_all<LoadA, 0>(la, smem); commit_all<LoadB, 0>(lb, smem + kAElems);
-    la.template fetch<0>(BK); lb.template fetch<0>(BK);
-    la.bounds(2 * BK);
-    commit_all<LoadA, 0>(la, smem + kStageElems); commit_all<LoadB, 0>(lb, smem + kStageElems + kAElems);
-    la.template fetch<0>(2 * BK); lb.template fetch<0>(2 * BK); la.bounds(3 * BK);
-    __syncthreads();
-    load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
-  } else {
-    if (KT > 0) {
-      la.bounds(0);
-      la.template fetch<0>(0); lb.template fetch<0>(0);
-      la.bounds(BK);
-      commit_all<LoadA, 0>(la, smem); commit_all<LoadB, 0>(lb, smem + kAElems);
-    }
-    if (KT > 1) {
-      la.template fetch<0>(BK); lb.template fetch<0>(BK);
-      la.bounds(2 * BK);
-      commit_all<LoadA, 0>(la, smem + kStageElems); commit_all<LoadB, 0>(lb, smem + kStageElems + kAElems);
-    }
-    if (KT > 2) { la.template fetch<0>(2 * BK); lb.template fetch<0>(2 * BK); la.bounds(3 * BK); }
-    __syncthreads();
-    if (KT > 0) load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
-  }
-
   // one iteration; R_ = kt % 3 fixes the LDS stages at compile time
   auto body = [&](auto R_, auto STEADY_, int kt) {
     constexpr int r = decltype(R_)::value;
     constexpr bool steady = decltype(STEADY_)::value;
     constexpr int s_nxt = (r + 1) % 3, s_wr = (r + 2) % 3;
+    constexpr int sl = NS == 3 ? r : 0;              // register slot that holds slice kt+2
     uint16_t* const cur = smem + r * kStageElems;
     uint16_t* const nxt = smem + s_nxt * kStageElems;
     uint16_t* const wr = smem + s_wr * kStageElems;
     if constexpr (steady) {
-      interleave_reads_commits<0, TM, TN, BM, BN>(cur, cur + kAElems, wr, wr + kAElems, wm0, wn0, fa1, fb1, la, lb);
-      // the registers are free again: the loads of slice kt+3 start now and have until the top of the next
-      // iteration to arrive
-      la.template fetch<0>((kt + 3) * BK); lb.template fetch<0>((kt + 3) * BK);
-      la.bounds((kt + 4) * BK);
+      interleave_reads_commits<sl, TM, TN, BM, BN>(cur, cur + kAElems, wr, wr + kAElems, wm0, wn0, fa1, fb1, la, lb);
+      // the slot is free again: the loads of slice kt+2+NS start now and have NS iterations to arrive
+      la.template fetch<sl, false>((kt + 2 + NS) * BK); lb.template fetch<sl, false>((kt + 2 + NS) * BK);
+      la.bounds((kt + 3 + NS) * BK);
       mfma_step<TM, TN>(fa0, fb0, acc);
       load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
       mfma_step<TM, TN>(fa1, fb1, acc);
@@ -427,27 +406,77 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       }
     } else {
       load_frags32<TM, TN, BM, BN>(cur, cur + kAElems, 1, wm0, wn0, fa1, fb1);
-      if (kt + 2 < KT) { commit_all<LoadA, 0>(la, wr); commit_all<LoadB, 0>(lb, wr + kAElems); }
+      if (kt + 2 < KT) { commit_all<LoadA, sl>(la, wr); commit_all<LoadB, sl>(lb, wr + kAElems); }
       mfma_step<TM, TN>(fa0, fb0, acc);
-      if (kt + 3 < KT) {
-        la.template fetch<0>((kt + 3) * BK); lb.template fetch<0>((kt + 3) * BK);
-        la.bounds((kt + 4) * BK);
+      if (kt + 2 + NS < KT) {
+        la.template fetch<sl>((kt + 2 + NS) * BK); lb.template fetch<sl>((kt + 2 + NS) * BK);
+        la.bounds((kt + 3 + NS) * BK);
       }
       if (kt + 1 < KT) load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
       mfma_step<TM, TN>(fa1, fb1, acc);
     }
     __syncthreads();
+    // each iteration is scheduled on its own: the group pipeline above then sees exactly one iteration
+    if constexpr (steady) __builtin_amdgcn_sched_barrier(0);
   };
 
+  // prologue: slices 0 and 1 into stages 0 and 1, slices 2 .. 1+NS into the register slots (slice s lives
+  // in slot (s - 2) % NS).  The long-K path is written without conditions so that the steady loop is
+  // entered with a known set of loads in flight.
+  // the steady loop never fetches the last slice of a ragged K: its loads carry no K predicate
+  const int KTs = (EMODE == 1 && g.K % BK != 0) ? KT - 1 : KT;
+  const bool long_k = KTs > 4 + NS;
   int kt = 0;
   if (long_k) {
-    do {                                // all three iterations fetch a real slice (kt+2+3 < KT)
+    la.bounds(0);
+    la.template fetch<0>(0); lb.template fetch<0>(0);
+    la.bounds(BK);
+    commit_all<LoadA, 0>(la, smem); commit_all<LoadB, 0>(lb, smem + kAElems);
+    la.template fetch<0>(BK); lb.template fetch<0>(BK);
+    la.bounds(2 * BK);
+    commit_all<LoadA, 0>(la, smem + kStageElems); commit_all<LoadB, 0>(lb, smem + kStageElems + kAElems);
+    // The loads left in flight must be issued in the order the loop issues them (slot by slot, A before
+    // B): the wait counts inside the loop are fixed at compile time from the worse of the two orders.
+    __builtin_amdgcn_sched_barrier(0);
+    la.template fetch<0>(2 * BK); lb.template fetch<0>(2 * BK); la.bounds(3 * BK);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (NS == 3) {
+      la.template fetch<1>(3 * BK); lb.template fetch<1>(3 * BK); la.bounds(4 * BK);
+      __builtin_amdgcn_sched_barrier(0);
+      la.template fetch<2>(4 * BK); lb.template fetch<2>(4 * BK); la.bounds(5 * BK);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
+    // steady state, inside this branch so that the loop is entered only with the loads of the
+    // prologue above in flight (the wait counts in the loop are fixed from every path that reaches it)
+    do {                                // all three iterations fetch a whole slice (kt+2+2+NS < KTs)
       body(IntC<0>(), std::true_type(), kt);
       body(IntC<1>(), std::true_type(), kt + 1);
       body(IntC<2>(), std::true_type(), kt + 2);
       kt += 3;
-    } while (kt + 5 < KT);
+    } while (kt + 4 + NS < KTs);
+  } else {
+    if (KT > 0) {
+      la.bounds(0);
+      la.template fetch<0>(0); lb.template fetch<0>(0);
+      la.bounds(BK);
+      commit_all<LoadA, 0>(la, smem); commit_all<LoadB, 0>(lb, smem + kAElems);
+    }
+    if (KT > 1) {
+      la.template fetch<0>(BK); lb.template fetch<0>(BK);
+      la.bounds(2 * BK);
+      commit_all<LoadA, 0>(la, smem + kStageElems); commit_all<LoadB, 0>(lb, smem + kStageElems + kAElems);
+    }
+    if (KT > 2) { la.template fetch<0>(2 * BK); lb.template fetch<0>(2 * BK); la.bounds(3 * BK); }
+    if constexpr (NS == 3) {
+      if (KT > 3) { la.template fetch<1>(3 * BK); lb.template fetch<1>(3 * BK); la.bounds(4 * BK); }
+      if (KT > 4) { la.template fetch<2>(4 * BK); lb.template fetch<2>(4 * BK); la.bounds(5 * BK); }
+    }
+    __syncthreads();
+    if (KT > 0) load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
   }
+
   for (; kt < KT; kt += 3) {          // drain; kt is a multiple of 3 here
     body(IntC<0>(), std::false_type(), kt);
     if (kt + 1 < KT) body(IntC<1>(), std::false_type(), kt + 1);
