@@ -313,13 +313,50 @@ __device__ __forceinline__ void mfma_step(const bf16x8 (&a)[TM], const bf16x8 (&
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
 }
 
-template <int EPI, int BM, int BN>
+// STAGED: the store epilogue passes the bf16 output tile through LDS (dX family)
+template <int EPI, int BM, int BN, bool STAGED>
 struct Gemm3Smem {
   static constexpr int STAGE = (BM + BN) * kBK3 * 2 + 128;   // + spare bytes for the sparse loader
   static constexpr int MAIN = 3 * STAGE;
-  static constexpr int CT = BM * (BN + 2) * 2;
-  static constexpr int BYTES = (EPI == kEpiFwd && CT > MAIN) ? CT : MAIN;
+  static constexpr int CT = EPI == kEpiFwd ? BM * (BN + 2) * 2 : STAGED ? BM * (BN + 8) * 2 : 0;
+  static constexpr int BYTES = CT > MAIN ? CT : MAIN;
 };
+
+// Store epilogue of the dX family: the tile goes through LDS as bf16 so that global memory is written in
+// whole 16-byte vectors (a lane's accumulators are 4 rows of one column, which would be 2-byte stores), and
+// the ReLU bits of the layer below are applied eight columns at a time from one mask word per vector.
+template <int BM, int BN, int TM, int TN>
+__device__ __forceinline__ void epilogue_dx_staged(const GemmArgs& g, floatx16 (&acc)[TM][TN], uint16_t* ct,
+                                                   int m0, int n0, int wm0, int wn0) {
+  constexpr int CP = BN + 8;               // row pitch in elements: rows stay 16-byte aligned, banks shift by 4
+  const int lane = threadIdx.x & 63;
+  // the main loop ended with a barrier: no wave reads the operand stages any more
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        ct[(wm0 + i * 32 + acc_row(e, lane)) * CP + wn0 + j * 32 + (lane & 31)] = f32_to_bf16_bits(acc[i][j][e]);
+  __syncthreads();
+  constexpr int CPR = BN / 8;              // 16-byte vectors per tile row
+  uint16_t* C = reinterpret_cast<uint16_t*>(g.C);
+  const bool vec = (g.ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(g.C) & 15) == 0;
+  for (int c = threadIdx.x; c < BM * CPR; c += kGemmThreads) {
+    const int r = c / CPR, ch = c % CPR;
+    const int row = m0 + r, col = n0 + ch * 8;
+    if (row >= g.M || col >= g.N) continue;
+    u32x4 v = *reinterpret_cast<const u32x4*>(&ct[r * CP + ch * 8]);
+    if (g.c_mask) mask_bf16x8(v, g.c_mask[(size_t)row * g.c_mask_pitch + (col >> 5)] >> (col & 31));
+    uint16_t* dst = C + (size_t)row * g.ldc + col;
+    if (vec && col + 8 <= g.N) {
+      *reinterpret_cast<u32x4*>(dst) = v;
+    } else {
+      const uint16_t* ve = reinterpret_cast<const uint16_t*>(&v);
+      for (int e = 0; e < 8 && col + e < g.N; ++e) dst[e] = ve[e];
+    }
+  }
+}
 
 template <int V> using IntC = std::integral_constant<int, V>;
 
@@ -328,7 +365,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
   constexpr bool EDGE = (FLAGS & (kFlagEdge | kFlagEdgeVec)) != 0;
   constexpr int EMODE = (FLAGS & kFlagEdge) ? 2 : (FLAGS & kFlagEdgeVec) ? 1 : 0;
   constexpr int BK = kBK3;
-  typedef Gemm3Smem<EPI, BM, BN> S;
+  constexpr bool kStaged = EPI == kEpiStore && AK == kOpK;
+  typedef Gemm3Smem<EPI, BM, BN, kStaged> S;
   constexpr int NS = (BM * BN >= 256 * 256) ? 1 : 3;
   typedef typename RingLoaderOf<AK, BM, SE, EMODE, (FLAGS & kFlagMaskA) != 0, NS>::type LoadA;
   typedef typename RingLoaderOf<BKIND, BN, SE, EMODE, (FLAGS & kFlagMaskB) != 0, NS>::type LoadB;
@@ -483,7 +521,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
     if (kt + 2 < KT) body(IntC<2>(), std::false_type(), kt + 2);
   }
 
-  if constexpr (EPI == kEpiStore) {
+  if constexpr (kStaged) {
+    epilogue_dx_staged<BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
+  } else if constexpr (EPI == kEpiStore) {
     epilogue_store_dispatch<AK, TM, TN, uint16_t, EDGE>(g, acc, m0, n0, wm0, wn0);
   } else {
     epilogue_fwd<uint16_t, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);

@@ -54,7 +54,7 @@ hipError_t run_gemm(const GemmArgs& g, hipStream_t st) {
 template <int AK, int BKIND, int EPI, int BM, int BN, int SE, int FLAGS>
 hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
   auto kern = gemm3_bf16_kernel<AK, BKIND, EPI, BM, BN, SE, FLAGS>;
-  constexpr int smem = Gemm3Smem<EPI, BM, BN>::BYTES;
+  constexpr int smem = Gemm3Smem<EPI, BM, BN, EPI == kEpiStore && AK == kOpK>::BYTES;
   static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
   static bool prepared = false;   // one host thread drives a context
   if (!prepared) {
