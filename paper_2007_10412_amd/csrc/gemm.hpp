@@ -476,40 +476,54 @@ __device__ __forceinline__ void epilogue_store_dispatch(const GemmArgs& g, float
   }
 }
 
-// Forward epilogue.  The tile goes through LDS in the storage dtype so that
-// the second phase runs row by row with lane l on columns l, l+64, ...: dense
-// y stores are contiguous, a wave ballot of (y > 0) IS two words of the ReLU
-// bit array, and the keep bits of the next layer's plan give every kept entry
-// its slot in the packed row with a popcount.  Wave w owns tile rows w, w+4,
-// ...; lane l fetches the plan data (row start, keep words) of the l-th of
-// them up front, in one round of loads, and the row loop reads them back with
-// v_readlane, so no global latency sits inside the loop.
+// LDS of the forward epilogue: the output tile in the storage dtype (row pitch padded by one 16-byte vector,
+// which keeps rows aligned and shifts banks) followed by the plan table of the tile rows.
+template <typename ElemT, int BM, int BN> struct FwdEpiLds {
+  static constexpr int VPL = 16 / (int)sizeof(ElemT);     // columns per 16-byte vector
+  static constexpr int CP = BN + VPL;
+  static constexpr int NW = BN / 32;                      // keep words per tile row
+  static constexpr int CT_BYTES = BM * CP * (int)sizeof(ElemT);
+  static constexpr int BYTES = CT_BYTES + BM * NW * 8;
+};
+
+// Forward epilogue.  The tile goes through LDS in the storage dtype, then every thread handles 16-byte
+// vectors of it (8 bf16 or 4 fp32 columns of one row): dense y is stored as whole vectors, the (y > 0) bits
+// of the vector are merged with those of the neighbouring lanes into one word of the ReLU bit array, and the
+// entries the next layer's plan keeps are written straight into its packed store.  For the latter a table
+// in LDS holds, for every tile row and 32-column word, the keep word and the store position of its first
+// kept entry (row start + entries of the row before that word), built by one thread per row before the
+// barrier; the slot of an entry is that position plus a popcount of the keep bits below it.
 template <typename ElemT, int BM, int BN, int TM, int TN>
 __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[TM][TN], ElemT* ct, int m0, int n0,
                                              int wm0, int wn0) {
-  constexpr int CP = BN + (sizeof(ElemT) == 4 ? 1 : 2);   // odd word pitch
-  constexpr int RPWV = BM / 4;                            // rows per wave (<= 64)
-  constexpr int NW = BN / 32;                             // keep words per tile row
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  typedef FwdEpiLds<ElemT, BM, BN> E;
+  constexpr int CP = E::CP, NW = E::NW, VPL = E::VPL;
+  constexpr int LPR = BN / VPL;                           // lanes per tile row
+  constexpr int LPW = 32 / VPL;                           // lanes per 32-column word
+  static_assert(BM <= kGemmThreads, "one thread per tile row builds the plan table");
+  const int lane = threadIdx.x & 63;
+  u32x2* const ptab = reinterpret_cast<u32x2*>(reinterpret_cast<unsigned char*>(ct) + E::CT_BYTES);
 
-  // plan data of row w + 4*lane
-  uint32_t kw[NW];
-  int rel_l = 0;
-  uint32_t base_l = 0;
+  if (g.pack && threadIdx.x < BM) {
+    const int r = threadIdx.x, row = m0 + r;
+    uint32_t kw[NW];
 #pragma unroll
-  for (int q = 0; q < NW; ++q) kw[q] = 0u;
-  if (g.pack) {
-    const int row = m0 + w + 4 * lane;
-    if (lane < RPWV && row < g.M) {
+    for (int q = 0; q < NW; ++q) kw[q] = 0u;
+    uint32_t pos = 0u;
+    if (row < g.M) {
       const int prow = row * g.next.plan_row_stride;
       const uint32_t* bm_row = g.next.bitmap + (size_t)prow * g.next.bm_pitch;
       const int bucket = n0 / kBucket;
-      base_l = g.next.row_ptr[row];
-      rel_l = g.next.bucket_off[(size_t)prow * (g.next.nb + 1) + bucket];
-      for (int wd = bucket * (kBucket / 32); wd < n0 / 32; ++wd) rel_l += __popc(bm_row[wd]);
+      pos = g.next.row_ptr[row] + g.next.bucket_off[(size_t)prow * (g.next.nb + 1) + bucket];
+      for (int wd = bucket * (kBucket / 32); wd < n0 / 32; ++wd) pos += __popc(bm_row[wd]);
 #pragma unroll
       for (int q = 0; q < NW; ++q)
         if (n0 / 32 + q < g.next.bm_pitch) kw[q] = bm_row[n0 / 32 + q];
+    }
+#pragma unroll
+    for (int q = 0; q < NW; ++q) {
+      ptab[r * NW + q] = u32x2{kw[q], pos};
+      pos += __popc(kw[q]);
     }
   }
 
@@ -532,43 +546,50 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
       }
     }
   __syncthreads();
+
   ElemT* Y = reinterpret_cast<ElemT*>(g.y);
-  for (int ri = 0; ri < RPWV; ++ri) {
-    const int r = w + 4 * ri;
-    const int row = m0 + r;
-    if (row >= g.M) break;
-    int rel = __builtin_amdgcn_readlane(rel_l, ri);       // slot inside the packed row of the next store
-    const int64_t base = (int64_t)(uint32_t)__builtin_amdgcn_readlane((int)base_l, ri);
+  const bool yvec = Y && (g.ldy % VPL) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
+  for (int c = threadIdx.x; c < BM * LPR; c += kGemmThreads) {      // same trip count for every lane
+    const int r = c / LPR, ch = c % LPR;
+    const int row = m0 + r, col = n0 + ch * VPL;
+    const bool live = row < g.M && col < g.N;
+    const int valid = live ? min(VPL, g.N - col) : 0;                // columns of this vector inside the output
+    const u32x4 raw = *reinterpret_cast<const u32x4*>(&ct[r * CP + ch * VPL]);
+    const ElemT* re = reinterpret_cast<const ElemT*>(&raw);
+    if (Y && valid > 0) {
+      ElemT* dst = Y + (size_t)row * g.ldy + col;
+      if (yvec && valid == VPL) *reinterpret_cast<u32x4*>(dst) = raw;
+      else for (int e = 0; e < valid; ++e) dst[e] = re[e];
+    }
+    if (g.bits) {
+      uint32_t pos = 0u;
 #pragma unroll
-    for (int c0 = 0; c0 < BN; c0 += 64) {
-      const int col = n0 + c0 + lane;
-      const ElemT raw = ct[r * CP + c0 + lane];
-      const float yv = get_elem(&raw);
-      if (col < g.N && Y) Y[(size_t)row * g.ldy + col] = raw;
-      if (g.bits) {
-        const uint64_t bal = __ballot(col < g.N && yv > 0.f);
-        const int wi = (n0 + c0) / 32;
-        if (lane == 0 && wi < g.bits_pitch) g.bits[(size_t)row * g.bits_pitch + wi] = (uint32_t)bal;
-        if (lane == 32 && wi + 1 < g.bits_pitch) g.bits[(size_t)row * g.bits_pitch + wi + 1] = (uint32_t)(bal >> 32);
-      }
-      if (g.pack) {
-        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)kw[c0 / 32], ri);
-        const uint32_t hi = (c0 / 32 + 1 < NW) ? (uint32_t)__builtin_amdgcn_readlane((int)kw[(c0 / 32 + 1) % NW], ri) : 0u;
-        const uint64_t kw64 = (uint64_t)lo | ((uint64_t)hi << 32);
-        if ((kw64 >> lane) & 1ull) {
-          const int r2 = rel + __popcll(kw64 & ((1ull << lane) - 1ull));
-          const int64_t p = base + r2;
-          if (p < g.next.capacity) {
-            if (g.next.paired) {
-              reinterpret_cast<uint32_t*>(g.next.values)[p] = pair_make(f32_to_bf16_bits(yv * g.next.scale), col);
-            } else {
-              put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv * g.next.scale);
-              if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)col;
-              else if (row == 0) g.next.indices[r2] = (uint16_t)col;
-            }
+      for (int e = 0; e < VPL; ++e) pos |= (e < valid && get_elem(re + e) > 0.f) ? (1u << e) : 0u;
+      uint32_t word = pos << (VPL * (ch % LPW));
+#pragma unroll
+      for (int d = 1; d < LPW; d <<= 1) word |= (uint32_t)__shfl_xor((int)word, d);
+      const int wi = col >> 5;
+      if ((ch % LPW) == 0 && row < g.M && wi < g.bits_pitch) g.bits[(size_t)row * g.bits_pitch + wi] = word;
+    }
+    if (g.pack && valid > 0) {
+      const u32x2 pe = ptab[r * NW + ch / LPW];
+      const int sh = VPL * (ch % LPW);
+      uint32_t kb = (pe[0] >> sh) & ((1u << valid) - 1u);
+      uint32_t p = pe[1] + __popc(pe[0] & ((1u << sh) - 1u));
+      while (kb) {
+        const int e = __ffs(kb) - 1;
+        kb &= kb - 1u;
+        if ((int64_t)p < g.next.capacity) {
+          const float yv = get_elem(re + e) * g.next.scale;
+          if (g.next.paired) {
+            reinterpret_cast<uint32_t*>(g.next.values)[p] = pair_make(f32_to_bf16_bits(yv), col + e);
+          } else {
+            put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv);
+            if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)(col + e);
+            else if (row == 0) g.next.indices[p - g.next.row_ptr[0]] = (uint16_t)(col + e);
           }
         }
-        rel += __popcll(kw64);
+        ++p;
       }
     }
   }
@@ -628,7 +649,7 @@ struct GemmSmem {
   typedef typename ElemOf<DT>::type ElemT;
   static constexpr int STAGE = LA::BYTES + LB::BYTES;
   static constexpr int MAIN = 2 * STAGE;
-  static constexpr int CT = BM * (BN + (sizeof(ElemT) == 4 ? 1 : 2)) * (int)sizeof(ElemT);
+  static constexpr int CT = FwdEpiLds<ElemT, BM, BN>::BYTES;
   static constexpr int CTC = BN * (BM + 1) * 4;
   static constexpr int BYTES = (EPI == kEpiFwd && CT > MAIN) ? CT : (EPI == kEpiConv && CTC > MAIN) ? CTC : MAIN;
 };

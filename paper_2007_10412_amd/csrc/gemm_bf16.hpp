@@ -318,7 +318,7 @@ template <int EPI, int BM, int BN, bool STAGED>
 struct Gemm3Smem {
   static constexpr int STAGE = (BM + BN) * kBK3 * 2 + 128;   // + spare bytes for the sparse loader
   static constexpr int MAIN = 3 * STAGE;
-  static constexpr int CT = EPI == kEpiFwd ? BM * (BN + 2) * 2 : STAGED ? BM * (BN + 8) * 2 : 0;
+  static constexpr int CT = EPI == kEpiFwd ? FwdEpiLds<uint16_t, BM, BN>::BYTES : STAGED ? BM * (BN + 8) * 2 : 0;
   static constexpr int BYTES = CT > MAIN ? CT : MAIN;
 };
 
