@@ -7,8 +7,9 @@ stores and the exact dX chain.  Default workload: the wide bf16 MLP
 (4096-4096-4096-1000, batch 4096) with per-example fixed-k sampling at p=0.1.
 
 Prints ONE JSON line: whole-job samples/s with inputs resident in HBM, the
-roofline of the dominant kernel (dW from the compressed store) timed with HIP
-events on the library's stream inside the timed region, and the CPU oracle
+roofline of the dominant kernel (the GEMM variant with the largest share of
+the step, found in two warm-up steps) timed with HIP events on the library's
+stream inside the timed region, and the CPU oracle
 timed on a bounded sample of the same workload.
 """
 import argparse
@@ -78,10 +79,23 @@ def main():
 
     for i in range(args.warmup):
         step(i)
-    # the dominant kernel is bracketed by HIP events on the library's stream during the timed steps
-    dom = {3: "dw_sparse", 1: "dw_sparse", 2: "dw_dense", 0: "dw_dense"}[scheme]
-    dom_filter = "gemm_%s_%s" % (dtype_name, dom)
-    B.rad_ctx_timing(ctx, dom_filter)
+    # Which kernel dominates the step: two untimed steps with every launch bracketed by events.  The timed
+    # region then brackets only that kernel (events around every launch would add gaps between all of them).
+    B.rad_ctx_timing(ctx, None)
+    B.rad_ctx_timing_reset(ctx)
+    for i in range(2):
+        step(500 + i)
+    labels_ms = {}
+    for fam in ("fwd", "dx", "dw_sparse", "dw_dense"):
+        for tile in ("64", "128", "256", "256x64", "256x128", "256x256"):
+            nm = "gemm_%s_%s_%s" % (dtype_name, fam, tile)
+            n, ms = B.rad_ctx_timing_read(ctx, nm)
+            # a name may be a prefix of another (…_256 of …_256x64): keep exact matches only
+            longer = sum(B.rad_ctx_timing_read(ctx, nm + "x" + t)[1] for t in ("64", "128", "256")) if "x" not in tile else 0.0
+            if n and ms - longer > 0:
+                labels_ms[nm] = ms - longer
+    big = max(labels_ms, key=labels_ms.get)
+    B.rad_ctx_timing(ctx, big)
     B.rad_ctx_timing_reset(ctx)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -94,16 +108,19 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     value = batch * args.steps / elapsed
 
-    # roofline of the dominant kernel: dW of the widest layers
-    big = "%s_256x256" % dom_filter if (dtype == B.RAD_BF16 and dom == "dw_sparse") else dom_filter
-    n_launch, tot_ms = B.rad_ctx_timing_read(ctx, big)
+    # roofline of that kernel from the events of the timed region; flops as the library counted them per launch
+    n_all, ms_all = B.rad_ctx_timing_read(ctx, big)
+    alg_all, exe_all = B.rad_ctx_timing_read_flops(ctx, big)
+    n_long = ms_long = alg_long = exe_long = 0
+    if "x" not in big.rsplit("_", 1)[1]:
+        for t in ("64", "128", "256"):
+            n_, ms_ = B.rad_ctx_timing_read(ctx, big + "x" + t)
+            a_, x_ = B.rad_ctx_timing_read_flops(ctx, big + "x" + t)
+            n_long += n_; ms_long += ms_; alg_long += a_; exe_long += x_
+    n_launch, tot_ms = n_all - n_long, ms_all - ms_long
+    alg_flops, exe_flops = (alg_all - alg_long) / max(1, n_launch), (exe_all - exe_long) / max(1, n_launch)
     B.rad_ctx_timing(ctx, "")
-    D0, N0 = dims[0], dims[1]
-    k0 = B.rad_fixed_k(p, D0) if scheme in (2, 3) else p * D0
-    # launches of that kernel per step: layers whose output is as wide as the first one
-    per_step = max(1, n_launch // max(1, args.steps))
-    alg_flops = 2.0 * batch * k0 * N0
-    exe_flops = 2.0 * batch * (k0 if scheme == 2 else D0) * N0
+    per_step = n_launch / max(1, args.steps)
     avg_ms = tot_ms / max(1, n_launch)
     peak = PEAK[dtype_name]
     roofline = {
@@ -114,8 +131,10 @@ def main():
         "executed": exe_flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else None,
         "executed_frac": exe_flops / (avg_ms * 1e-3) / 1e12 / peak if avg_ms > 0 else None,
         "avg_launch_ms": avg_ms, "launches": n_launch, "launches_per_step": per_step,
+        "share_of_step": avg_ms * per_step / ms_per_step if ms_per_step > 0 else None,
         "algorithmic_flops_per_launch": alg_flops, "executed_flops_per_launch": exe_flops,
         "traffic": MEASURED_TRAFFIC.get((args.workload, args.scheme, p, big)),
+        "step_share_by_kernel_ms": {k_: v_ / 2 for k_, v_ in sorted(labels_ms.items())},
     }
 
     out = {
@@ -281,12 +300,14 @@ def cpu_baseline(data, dims, scheme, p, dtype, batch, has_bias):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     import numpy as np
     from oracle import rad_oracle as R
-    rows = min(batch, 2048)
+    rows = batch
+    reps = 2
     bs = data["bs"] if has_bias else None
     t0 = time.perf_counter()
-    R.mlp_train_step(data["x"][:rows], data["labels"][:rows], data["Ws"], bs, scheme, p, seed=1,
-                     dtype=(R.BF16 if dtype == 1 else R.F32))
-    dt = time.perf_counter() - t0
+    for _ in range(reps):
+        R.mlp_train_step(data["x"][:rows], data["labels"][:rows], data["Ws"], bs, scheme, p, seed=1,
+                         dtype=(R.BF16 if dtype == 1 else R.F32))
+    dt = (time.perf_counter() - t0) / reps
     cores = os.cpu_count()
     try:
         from threadpoolctl import threadpool_info
@@ -296,8 +317,8 @@ def cpu_baseline(data, dims, scheme, p, dtype, batch, has_bias):
     except Exception:
         pass
     return {"value": rows / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
-            "seconds": dt,
-            "sample": "one oracle train step (numpy fp64) on the first %d of %d rows, full layer widths" % (rows, batch)}
+            "seconds": dt * reps,
+            "sample": "%d oracle train steps (numpy fp64) on all %d rows of the batch, full layer widths" % (reps, rows)}
 
 
 if __name__ == "__main__":

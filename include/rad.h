@@ -122,6 +122,12 @@ rad_status rad_ctx_synchronize(rad_ctx* ctx);
 rad_status rad_ctx_timing(rad_ctx* ctx, const char* filter);
 rad_status rad_ctx_timing_read(rad_ctx* ctx, const char* name, int64_t* launches, double* total_ms);
 rad_status rad_ctx_timing_reset(rad_ctx* ctx);
+/* Floating-point operations of the timed GEMM launches whose name contains
+ * `name` since the last reset: `executed` counts 2 M N K of each launch,
+ * `algorithmic` what the operation needs by definition (for dW from a sampled
+ * store, 2 d_out per kept entry; elsewhere the same as executed).  Kernels that
+ * are not GEMMs count zero. */
+rad_status rad_ctx_timing_read_flops(rad_ctx* ctx, const char* name, double* algorithmic, double* executed);
 
 /* Test hook: keys are shifted right by `shift` bits (and the Bernoulli
  * threshold likewise) before selection, which makes equal keys frequent and

@@ -44,6 +44,7 @@ SIGNATURES = {
     "rad_ctx_synchronize": (C.c_int, [P]),
     "rad_ctx_timing": (C.c_int, [P, C.c_char_p]),
     "rad_ctx_timing_read": (C.c_int, [P, C.c_char_p, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
+    "rad_ctx_timing_read_flops": (C.c_int, [P, C.c_char_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "rad_ctx_timing_reset": (C.c_int, [P]),
     "rad_debug_key_shift": (C.c_int, [P, C.c_int32]),
     "rad_store_create": (C.c_int, [P, C.POINTER(rad_layer), C.c_int32, C.c_double, C.c_int32, C.POINTER(P)]),
@@ -158,6 +159,12 @@ def rad_ctx_timing_read(ctx, name):
     n, ms = C.c_int64(), C.c_double()
     _check(ctx, lib().rad_ctx_timing_read(ctx, None if name is None else name.encode(), C.byref(n), C.byref(ms)))
     return n.value, ms.value
+
+
+def rad_ctx_timing_read_flops(ctx, name):
+    a, x = C.c_double(), C.c_double()
+    _check(ctx, lib().rad_ctx_timing_read_flops(ctx, None if name is None else name.encode(), C.byref(a), C.byref(x)))
+    return a.value, x.value
 
 
 def rad_debug_key_shift(ctx, shift):

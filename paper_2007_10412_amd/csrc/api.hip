@@ -23,7 +23,7 @@ struct rad_ctx {
   // timing
   bool timing = false;
   std::string filter;
-  struct Rec { std::string name; hipEvent_t a, b; };
+  struct Rec { std::string name; hipEvent_t a, b; double alg_flops, exe_flops; };
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
   // grow-only workspaces
@@ -86,7 +86,7 @@ static hipError_t timed(rad_ctx* c, const char* name, F launch) {
   if (e != hipSuccess) return e;
   e = hipEventRecord(b, c->stream);
   if (e != hipSuccess) return e;
-  c->recs.push_back({nm, a, b});
+  c->recs.push_back({nm, a, b, 0.0, 0.0});
   return hipSuccess;
 }
 
@@ -159,6 +159,17 @@ extern "C" rad_status rad_ctx_timing_read(rad_ctx* c, const char* name, int64_t*
     ms += t; ++n;
   }
   *launches = n; *total_ms = ms;
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_ctx_timing_read_flops(rad_ctx* c, const char* name, double* algorithmic, double* executed) {
+  if (!c || !algorithmic || !executed) return RAD_ERR_NULL;
+  double a = 0.0, x = 0.0;
+  for (auto& r : c->recs) {
+    if (name && r.name.find(name) == std::string::npos) continue;
+    a += r.alg_flops; x += r.exe_flops;
+  }
+  *algorithmic = a; *executed = x;
   return RAD_OK;
 }
 
@@ -469,13 +480,21 @@ static bool layer_matches(const rad_layer* L, const rad_store* s) {
 
 static GemmArgs gemm_zero() { GemmArgs g; std::memset(&g, 0, sizeof(g)); return g; }
 
-static rad_status run_gemm_call(rad_ctx* c, int dtype, int ak, int bk, int epi, const GemmArgs& g) {
+// alg_flops: what the operation needs by its definition when that is less than the 2 M N K the kernel
+// executes (dW from a sampled store); 0 = the same
+static rad_status run_gemm_call(rad_ctx* c, int dtype, int ak, int bk, int epi, const GemmArgs& g,
+                                double alg_flops = 0.0) {
   const char* label = "gemm";
   if (c->timing) {              // the label decides whether this launch is bracketed by events
     GemmArgs probe = g; probe.dry_run = 1;
     if (launch_gemm(dtype, ak, bk, epi, probe, c->stream, &label) != hipSuccess) label = "gemm";
   }
+  const size_t n_rec = c->recs.size();
   hipError_t e = timed(c, label, [&](const char** nm) { return launch_gemm(dtype, ak, bk, epi, g, c->stream, nm); });
+  if (c->recs.size() > n_rec) {
+    c->recs.back().exe_flops = 2.0 * g.M * g.N * g.K;
+    c->recs.back().alg_flops = alg_flops > 0.0 ? alg_flops : c->recs.back().exe_flops;
+  }
   if (e == hipErrorInvalidValue) return fail(c, RAD_ERR_UNSUPPORTED, "no GEMM kernel for this operand combination");
   if (e != hipSuccess) return hip_fail(c, e, "gemm launch");
   return RAD_OK;
@@ -527,6 +546,9 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
   g.M = s->cols;
   g.sa = store_view(s, slot);
   g.sparse_prefetch = sparse_prefetch_for(s, s->dtype == kBF16 ? 8 : 16);
+  // 2 N flops per kept entry (expected number for Bernoulli draws)
+  const double kept = s->scheme == RAD_BERNOULLI ? s->p * (double)s->rows * s->cols : (double)s->rows * s->k;
+  const double alg = 2.0 * kept * N;
   if (s->dtype == kBF16 && g.sparse_prefetch > gemm_bf16_sparse_max_prefetch()) {
     // dense enough that scattering into LDS loses to a plain contraction: rebuild x~ as a transient dense
     // operand (one layer's worth, reused) and run the dense dW kernel
@@ -534,9 +556,9 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     RAD_TRY(ws_get(c, WS_DENSE, (size_t)s->rows * s->cols * s->elem(), &dense));
     HIP_TRY(c, timed(c, "unpack", [&](const char**) { return launch_unpack(g.sa, s->dtype, dense, c->stream); }));
     g.A = dense; g.lda = s->cols;
-    return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
+    return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g, alg);
   }
-  RAD_TRY(run_gemm_call(c, s->dtype, kOpSparse, kOpMN, kEpiStore, g));
+  RAD_TRY(run_gemm_call(c, s->dtype, kOpSparse, kOpMN, kEpiStore, g, alg));
   if (s->dtype == kBF16) {
     // the bf16 kernel keeps a fixed number of entries per (row, bucket) in registers; the rest, if any, here
     const int cap = gemm_bf16_sparse_cap(g.sparse_prefetch);
