@@ -242,8 +242,12 @@ const void* rad_model_logits(const rad_model* model);
 
 /* One training step: forward with exact activations (storing only samples and
  * bits), loss, backward from the stores.  x is the model input, labels int32
- * device [batch].  Synchronises; *loss_host receives the mean loss.  Returns
- * RAD_ERR_CAPACITY if a Bernoulli draw overflowed a store. */
+ * device [batch].  With loss_host the call synchronises, *loss_host (HOST)
+ * receives the mean loss, and RAD_ERR_CAPACITY is returned if a Bernoulli draw
+ * overflowed a store in this step or in an earlier one that was only enqueued.
+ * With loss_host null the step is only enqueued on the context's stream:
+ * nothing is read back, the mean loss is not formed and the call does not
+ * wait; gradients are complete once the stream has been synchronised. */
 rad_status rad_train_step(rad_ctx* ctx, rad_model* model, const rad_sampling* sampling,
                           const void* x, const int32_t* labels, void* const* params,
                           void* const* grads, float* loss_host);

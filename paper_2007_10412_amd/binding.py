@@ -277,11 +277,15 @@ def rad_model_logits(model):
     return lib().rad_model_logits(model)
 
 
-def rad_train_step(ctx, model, sampling, x, labels, params, grads):
-    """params/grads: lists of torch tensors in the model's documented order.  Returns the loss (float)."""
+def rad_train_step(ctx, model, sampling, x, labels, params, grads, want_loss=True):
+    """params/grads: lists of torch tensors in the model's documented order.  Returns the loss (float), or
+    None with want_loss=False: the step is then only enqueued (loss_host = null)."""
     n = len(params)
     pa = (P * n)(*[p.data_ptr() for p in params])
     ga = (P * n)(*[g.data_ptr() for g in grads])
+    if not want_loss:
+        _check(ctx, lib().rad_train_step(ctx, model, C.byref(sampling), _ptr(x), _ptr(labels), pa, ga, None))
+        return None
     loss = C.c_float()
     _check(ctx, lib().rad_train_step(ctx, model, C.byref(sampling), _ptr(x), _ptr(labels), pa, ga, C.byref(loss)))
     return loss.value

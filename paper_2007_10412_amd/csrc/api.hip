@@ -197,7 +197,9 @@ struct rad_store {
   uint32_t* row_cnt = nullptr;
   uint32_t* bits = nullptr;
   uint32_t* bitmap = nullptr;     // transient, points into a context workspace after a plan
-  int* overflow = nullptr;
+  int* overflow = nullptr;        // sticky flag: a Bernoulli draw exceeded the capacity (stays set until read)
+  int* max_seg = nullptr;         // longest (row, bucket) segment of the last plan
+  bool flags_external = false;    // both live in the owning model's flag array
   int bits_pitch = 0, nb = 0, bm_pitch = 0;
   int plan_rows_per_step = 0;     // rows (per example / Bernoulli), 1 (shared), 0 (exact)
   size_t elem() const { return dtype == kBF16 ? 2 : 4; }
@@ -250,7 +252,7 @@ static rad_status check_scheme(rad_ctx* c, int scheme, double p) {
 extern "C" rad_status rad_store_destroy(rad_store* s) {
   if (!s) return RAD_ERR_NULL;
   for (void* p : {(void*)s->values, (void*)s->indices, (void*)s->row_ptr, (void*)s->bucket_off, (void*)s->row_cnt,
-                  (void*)s->bits, (void*)s->overflow})
+                  (void*)s->bits, s->flags_external ? nullptr : (void*)s->overflow})
     if (p) (void)hipFree(p);
   delete s;
   return RAD_OK;
@@ -295,6 +297,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   };
   bool ok = alloc(&s->values, s->paired() ? (size_t)(s->capacity + kPairPad) * 4 : (size_t)s->capacity * s->elem());
   ok = ok && alloc((void**)&s->overflow, 2 * sizeof(int));   // [0] capacity overflow flag, [1] longest bucket segment
+  s->max_seg = s->overflow ? s->overflow + 1 : nullptr;
   if (scheme != RAD_EXACT) {
     const size_t n_idx = scheme == RAD_FIXEDK_SHARED ? (size_t)steps * s->k : (size_t)s->capacity;
     if (!s->paired()) ok = ok && alloc((void**)&s->indices, n_idx * 2);
@@ -319,6 +322,7 @@ static rad_status store_nnz(rad_ctx* c, const rad_store* s, int64_t* nnz) {
   HIP_TRY(c, hipMemcpy(&last, s->row_ptr + (size_t)s->steps * s->rows, 4, hipMemcpyDeviceToHost));
   int ov = 0;
   HIP_TRY(c, hipMemcpy(&ov, s->overflow, sizeof(int), hipMemcpyDeviceToHost));
+  if (ov) HIP_TRY(c, hipMemset(s->overflow, 0, sizeof(int)));      // reported once
   if (ov || (int64_t)last > s->capacity) return fail(c, RAD_ERR_CAPACITY, "a Bernoulli draw exceeded the store's capacity");
   *nnz = last;
   return RAD_OK;
@@ -413,7 +417,9 @@ extern "C" rad_status rad_store_import_bits(rad_ctx* c, rad_store* s, const uint
 }
 
 // draws the keep sets of every row and step of `s` into `bitmap`
-static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, uint32_t* bitmap) {
+// clear_max_seg = false when the caller has already zeroed the segment maxima of all its stores at once
+static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, uint32_t* bitmap,
+                             bool clear_max_seg = true) {
   if (s->scheme == RAD_EXACT) return RAD_OK;
   PlanArgs a;
   a.seed_lo = (uint32_t)sm->seed; a.seed_hi = (uint32_t)(sm->seed >> 32);
@@ -427,9 +433,9 @@ static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, u
   a.bitmap = bitmap; a.bm_pitch = s->bm_pitch;
   a.bucket_off = s->bucket_off; a.nb = s->nb;
   a.row_cnt = s->row_cnt; a.row_ptr = s->row_ptr;
-  a.max_seg = s->overflow + 1;
+  a.max_seg = s->max_seg;
   s->bitmap = bitmap;
-  HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(s->overflow), 0u, 2, c->stream));
+  if (clear_max_seg) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(s->max_seg), 0u, 1, c->stream));
   HIP_TRY(c, timed(c, "plan", [&](const char**) { return launch_plan(a, c->stream); }));
   if (s->scheme == RAD_BERNOULLI) {
     HIP_TRY(c, timed(c, "row_scan", [&](const char**) {
@@ -563,7 +569,7 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     // the bf16 kernel keeps a fixed number of entries per (row, bucket) in registers; the rest, if any, here
     const int cap = gemm_bf16_sparse_cap(g.sparse_prefetch);
     HIP_TRY(c, timed(c, "dw_overflow", [&](const char**) {
-      return launch_dw_overflow(g.sa, s->rows, dy, s->dtype, N, bits, bits_pitch, dW, cap, s->overflow + 1, c->stream);
+      return launch_dw_overflow(g.sa, s->rows, dy, s->dtype, N, bits, bits_pitch, dW, cap, s->max_seg, c->stream);
     }));
   }
   return RAD_OK;
@@ -672,6 +678,7 @@ struct rad_model {
   void* act[2] = {nullptr, nullptr};    // transient dense activations (ping-pong)
   void* dyb[2] = {nullptr, nullptr};    // transient upstream gradients (ping-pong)
   void* logits = nullptr;
+  int* flags = nullptr;                 // [n stores] overflow flags, then [n stores] segment maxima
   // RNN
   int64_t T = 0, d_input = 0, hidden = 0, classes = 0;
   uint32_t* rnn_bits = nullptr;         // [T][batch][hidden/32]
@@ -686,10 +693,12 @@ struct rad_model {
   bool paired() const { return dtype == kBF16 && (scheme == kBernoulli || scheme == kFixedKPerExample); }
 };
 
+static rad_status model_share_flags(rad_ctx* c, rad_model* m);
+
 extern "C" rad_status rad_model_destroy(rad_model* m) {
   if (!m) return RAD_ERR_NULL;
   for (rad_store* s : m->stores) if (s) rad_store_destroy(s);
-  for (void* p : {m->act[0], m->act[1], m->dyb[0], m->dyb[1], m->logits, (void*)m->rnn_bits, (void*)m->bitmap_ws,
+  for (void* p : {m->act[0], m->act[1], m->dyb[0], m->dyb[1], m->logits, (void*)m->flags, (void*)m->rnn_bits, (void*)m->bitmap_ws,
                   m->buf[0], m->buf[1], m->buf[2]})
     if (p) (void)hipFree(p);
   for (auto& cv : m->convs) if (cv.arg) (void)hipFree(cv.arg);
@@ -743,17 +752,48 @@ extern "C" rad_status rad_model_create_mlp(rad_ctx* c, int32_t dtype, int64_t ba
   for (void** p2 : {&m->act[0], &m->act[1], &m->dyb[0], &m->dyb[1]}) ok = ok && hipMalloc(p2, bytes) == hipSuccess;
   ok = ok && hipMalloc(&m->logits, (size_t)batch * dims[n_layers] * m->elem()) == hipSuccess;
   if (!ok) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+  { rad_status fs = model_share_flags(c, m); if (fs != RAD_OK) { rad_model_destroy(m); return fs; } }
   *out = m;
   return RAD_OK;
 }
 
-static rad_status stores_overflowed(rad_ctx* c, rad_model* m) {
-  for (rad_store* s : m->stores) {
-    if (s->scheme != RAD_BERNOULLI) continue;
-    int ov = 0;
-    HIP_TRY(c, hipMemcpy(&ov, s->overflow, sizeof(int), hipMemcpyDeviceToHost));
-    if (ov) return fail(c, RAD_ERR_CAPACITY, "a Bernoulli draw exceeded a store's capacity");
+// The stores of a model keep their flags in one array of the model, so that a step clears the segment
+// maxima of all of them with one launch and reads all overflow flags with one copy.
+static rad_status model_share_flags(rad_ctx* c, rad_model* m) {
+  const size_t n = m->stores.size();
+  if (hipMalloc(reinterpret_cast<void**>(&m->flags), 2 * n * sizeof(int)) != hipSuccess)
+    return fail(c, RAD_ERR_DEVICE, "model allocation failed");
+  HIP_TRY(c, hipMemsetAsync(m->flags, 0, 2 * n * sizeof(int), c->stream));
+  for (size_t l = 0; l < n; ++l) {
+    rad_store* s = m->stores[l];
+    if (s->overflow && !s->flags_external) (void)hipFree(s->overflow);
+    s->overflow = m->flags + l; s->max_seg = m->flags + n + l; s->flags_external = true;
   }
+  return RAD_OK;
+}
+
+static rad_status model_clear_max_seg(rad_ctx* c, rad_model* m) {
+  const size_t n = m->stores.size();
+  HIP_TRY(c, timed(c, "fill", [&](const char**) {
+    return launch_fill_u32(reinterpret_cast<uint32_t*>(m->flags + n), 0u, (int64_t)n, c->stream);
+  }));
+  return RAD_OK;
+}
+
+// end of a step: with loss_host the step is waited for, the loss read back and a capacity overflow (also
+// one left by earlier steps that were only enqueued) reported once; without it nothing waits
+static rad_status step_finish(rad_ctx* c, rad_model* m, float* loss_host) {
+  if (!loss_host) return RAD_OK;
+  HIP_TRY(c, hipMemcpyAsync(loss_host, c->loss_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (m->scheme != RAD_BERNOULLI) return RAD_OK;
+  std::vector<int> ov(m->stores.size(), 0);
+  HIP_TRY(c, hipMemcpy(ov.data(), m->flags, ov.size() * sizeof(int), hipMemcpyDeviceToHost));
+  for (int v : ov)
+    if (v) {
+      HIP_TRY(c, hipMemset(m->flags, 0, ov.size() * sizeof(int)));
+      return fail(c, RAD_ERR_CAPACITY, "a Bernoulli draw exceeded a store's capacity");
+    }
   return RAD_OK;
 }
 
@@ -773,8 +813,9 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
 
   // forward: layer l consumes the dense activation of layer l-1 (kept only
   // until then) and leaves the packed sample of its own output for layer l+1
+  RAD_TRY(model_clear_max_seg(c, m));
   rad_sampling s0 = *sm;
-  RAD_TRY(store_plan(c, m->stores[0], &s0, static_cast<uint32_t*>(bm)));
+  RAD_TRY(store_plan(c, m->stores[0], &s0, static_cast<uint32_t*>(bm), false));
   RAD_TRY(store_pack(c, m->stores[0], x, 0));
   const void* a_in = x;
   for (int l = 0; l < Lc; ++l) {
@@ -784,7 +825,7 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
       rad_store* sn = m->stores[(size_t)l + 1];
       if (sn->scheme != RAD_EXACT) {
         rad_sampling sl = *sm; sl.stream_id = sm->stream_id + (uint32_t)(l + 1);
-        RAD_TRY(store_plan(c, sn, &sl, static_cast<uint32_t*>(bm)));
+        RAD_TRY(store_plan(c, sn, &sl, static_cast<uint32_t*>(bm), false));
         nv = store_view(sn, 0); next = &nv;
       }
     }
@@ -795,7 +836,7 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
                          Wp(l), bp(l), !last, y, s->bits, s->bits_pitch, next, nullptr, 0, 0, nullptr));
     a_in = y;
   }
-  RAD_TRY(softmax_call(c, m->logits, labels, B, (int)m->dims[(size_t)Lc], m->dtype, m->dyb[0], c->loss_dev));
+  RAD_TRY(softmax_call(c, m->logits, labels, B, (int)m->dims[(size_t)Lc], m->dtype, m->dyb[0], loss_host ? c->loss_dev : nullptr));
 
   // backward from the stores.  dyb holds g = dL/dh of the layer at hand: the loss gradient for the last
   // layer (no ReLU), and below it the dX of the layer above, masked by this layer's ReLU bits in that
@@ -815,9 +856,7 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
       cur ^= 1;
     }
   }
-  HIP_TRY(c, hipMemcpyAsync(loss_host, c->loss_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
-  return stores_overflowed(c, m);
+  return step_finish(c, m, loss_host);
 }
 
 extern "C" rad_status rad_model_create_rnn(rad_ctx* c, int64_t batch, int64_t T, int64_t d_input, int64_t hidden,
@@ -850,6 +889,7 @@ extern "C" rad_status rad_model_create_rnn(rad_ctx* c, int64_t batch, int64_t T,
   const size_t bmw = m->stores[0]->bitmap_words() + m->stores[1]->bitmap_words();
   if (bmw) ok = ok && hipMalloc((void**)&m->bitmap_ws, bmw * 4) == hipSuccess;
   if (!ok) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+  { rad_status fs = model_share_flags(c, m); if (fs != RAD_OK) { rad_model_destroy(m); return fs; } }
   *out = m;
   return RAD_OK;
 }
@@ -877,12 +917,13 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   const int bp = (H + 31) / 32;
 
   // all keep sets of the step up front: they depend on (seed, step) only
+  RAD_TRY(model_clear_max_seg(c, m));
   if (T > 1) {
     rad_sampling s1 = *sm; s1.step = sm->step + 2;      // slot s holds h_{s+1}, drawn with step = s+2
-    RAD_TRY(store_plan(c, s_hh, &s1, m->bitmap_ws));
+    RAD_TRY(store_plan(c, s_hh, &s1, m->bitmap_ws, false));
   }
   rad_sampling s2 = *sm; s2.stream_id = sm->stream_id + 1; s2.step = 0;
-  RAD_TRY(store_plan(c, s_ho, &s2, m->bitmap_ws ? m->bitmap_ws + s_hh->bitmap_words() : nullptr));
+  RAD_TRY(store_plan(c, s_ho, &s2, m->bitmap_ws ? m->bitmap_ws + s_hh->bitmap_words() : nullptr, false));
 
   // forward: h_t = ReLU(x_t W_ih + h_{t-1} W_hh + b); h_0 = 0 so step 1 has no contraction
   for (int t = 1; t <= T; ++t) {
@@ -901,7 +942,7 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   }
   const void* hT = s_ho->scheme == RAD_EXACT ? s_ho->values : m->act[T & 1];
   RAD_TRY(forward_gemm(c, kF32, B, C, H, hT, H, W_ho, b_o, 0, m->logits, nullptr, 0, nullptr, nullptr, 0, 0, nullptr));
-  RAD_TRY(softmax_call(c, m->logits, labels, B, C, kF32, m->dyb[0], c->loss_dev));
+  RAD_TRY(softmax_call(c, m->logits, labels, B, C, kF32, m->dyb[0], loss_host ? c->loss_dev : nullptr));
 
   // backward
   float* dz = static_cast<float*>(m->dyb[0]);
@@ -923,9 +964,7 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
       cur ^= 1;
     }
   }
-  HIP_TRY(c, hipMemcpyAsync(loss_host, c->loss_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
-  return stores_overflowed(c, m);
+  return step_finish(c, m, loss_host);
 }
 
 extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t batch, int32_t n_conv, const int32_t* channels,
@@ -977,6 +1016,7 @@ extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t batch, int32_t n_
   ok = ok && hipMalloc(&m->logits, (size_t)batch * classes * 4) == hipSuccess;
   ok = ok && hipMalloc(&m->dyb[0], (size_t)batch * classes * 4) == hipSuccess;
   if (!ok) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+  { rad_status fs = model_share_flags(c, m); if (fs != RAD_OK) { rad_model_destroy(m); return fs; } }
   *out = m;
   return RAD_OK;
 }
@@ -1003,6 +1043,7 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   for (rad_store* s : m->stores) if (s->bitmap_words() > bm_words) bm_words = s->bitmap_words();
   void* bm = nullptr;
   if (bm_words) RAD_TRY(ws_get(c, WS_BITMAP, bm_words * 4, &bm));
+  RAD_TRY(model_clear_max_seg(c, m));
 
   // forward: every conv input is sampled (flattened per example), then convolved exactly
   const float* act = static_cast<const float*>(x);
@@ -1011,7 +1052,7 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
     const rad_model::Conv& cv = m->convs[(size_t)l];
     rad_store* s = m->stores[(size_t)l];
     rad_sampling sl = *sm; sl.stream_id = sm->stream_id + (uint32_t)l;
-    RAD_TRY(store_plan(c, s, &sl, static_cast<uint32_t*>(bm)));
+    RAD_TRY(store_plan(c, s, &sl, static_cast<uint32_t*>(bm), false));
     RAD_TRY(store_pack(c, s, act, 0));
     const int yb = (in_buf + 1 + 3) % 3, pb = (in_buf + 2 + 3) % 3;
     RAD_TRY(conv_gemm(c, B, cv.ci, cv.co, cv.h, cv.w, ks, act, static_cast<const float*>(params[2 * l]),
@@ -1028,12 +1069,12 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   rad_store* sfc = m->stores[(size_t)nc];
   {
     rad_sampling sl = *sm; sl.stream_id = sm->stream_id + (uint32_t)nc;
-    RAD_TRY(store_plan(c, sfc, &sl, static_cast<uint32_t*>(bm)));
+    RAD_TRY(store_plan(c, sfc, &sl, static_cast<uint32_t*>(bm), false));
     RAD_TRY(store_pack(c, sfc, act, 0));
   }
   RAD_TRY(forward_gemm(c, kF32, B, C, m->fc_in, act, m->fc_in, params[2 * nc], static_cast<const float*>(params[2 * nc + 1]),
                        0, m->logits, nullptr, 0, nullptr, nullptr, 0, 0, nullptr));
-  RAD_TRY(softmax_call(c, m->logits, labels, B, C, kF32, m->dyb[0], c->loss_dev));
+  RAD_TRY(softmax_call(c, m->logits, labels, B, C, kF32, m->dyb[0], loss_host ? c->loss_dev : nullptr));
 
   // backward
   RAD_TRY(dW_gemm(c, sfc, 0, m->dyb[0], C, nullptr, 0, static_cast<float*>(grads[2 * nc]), 0));
@@ -1090,16 +1131,14 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
       db_ = nb_;
     }
   }
-  HIP_TRY(c, hipMemcpyAsync(loss_host, c->loss_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
-  return stores_overflowed(c, m);
+  return step_finish(c, m, loss_host);
 }
 
 extern "C" rad_status rad_train_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, const void* x,
                                      const int32_t* labels, void* const* params, void* const* grads,
                                      float* loss_host) {
   if (!c) return RAD_ERR_NULL;
-  if (!m || !sm || !x || !labels || !params || !grads || !loss_host) return fail(c, RAD_ERR_NULL, "null argument");
+  if (!m || !sm || !x || !labels || !params || !grads) return fail(c, RAD_ERR_NULL, "null argument");
   RAD_TRY(check_scheme(c, sm->scheme, sm->p));
   if (sm->scheme != m->scheme || sm->p != m->p) return fail(c, RAD_ERR_PARAM, "sampling does not match the model");
   if (m->kind == kMlp) return mlp_step(c, m, sm, x, labels, params, grads, loss_host);

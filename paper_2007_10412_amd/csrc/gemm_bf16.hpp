@@ -378,13 +378,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
 
   // Tile order.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2, so ids are first
   // regrouped into 8 contiguous chunks (one per XCD); within the sequence, tiles are walked in groups of
-  // 4 tile rows, column by column, so that the 32 workgroups resident on one XCD cover a 4 x 8 block of
+  // GM tile rows, column by column, so that the 32 workgroups resident on one XCD cover a GM x 32/GM block of
   // tiles and share their operand slices through that L2.
   const int tiles_n = (g.N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
   const int T = tiles_m * tiles_n;
   int lin = blockIdx.x;
   if ((T & 7) == 0) lin = (lin & 7) * (T >> 3) + (lin >> 3);
-  constexpr int GM = 4;
+  // a tile of the compressed store is a fraction of a dense operand tile, so the dW-from-store kernels
+  // group tall: one XCD then streams 2 tile columns of dy instead of 8
+  constexpr int GM = AK == kOpSparse ? 16 : 4;
   const int grp = lin / (GM * tiles_n), within = lin - grp * (GM * tiles_n);
   const int gh = min(GM, tiles_m - grp * GM);      // rows in this (possibly last, shorter) group
   const int tm = grp * GM + within % gh, tn = within / gh;

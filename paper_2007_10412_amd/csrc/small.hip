@@ -122,8 +122,7 @@ __global__ __launch_bounds__(256) void dw_overflow_kernel(StoreView s, int rows,
                                                           const int* __restrict__ max_seg) {
   if (*max_seg <= cap) return;
   const int lane = threadIdx.x & 63;
-  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (seg >= rows * s.nb) return;
+  for (int seg = blockIdx.x * 4 + (threadIdx.x >> 6); seg < rows * s.nb; seg += gridDim.x * 4) {
   const int b = seg / s.nb, t = seg % s.nb;
   const uint16_t* bo = s.bucket_off + (size_t)(b * s.plan_row_stride) * (s.nb + 1) + t;
   const int64_t base = s.row_ptr[b];
@@ -143,6 +142,7 @@ __global__ __launch_bounds__(256) void dw_overflow_kernel(StoreView s, int rows,
       if (bits && !((bits[(size_t)b * bits_pitch + (n >> 5)] >> (n & 31)) & 1u)) g = 0.f;
       atomicAdd(&dW[(size_t)j * N + n], v * g);
     }
+  }
   }
 }
 
@@ -249,7 +249,7 @@ hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows
   else
     hipLaunchKernelGGL(softmax_ce_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)logits, labels, rows,
                        classes, (uint16_t*)dlogits, row_loss);
-  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, st, row_loss, rows, loss);
+  if (loss) hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, st, row_loss, rows, loss);   // null: gradient only
   return hipGetLastError();
 }
 
@@ -271,8 +271,11 @@ hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint3
 
 hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int dtype, int N, const uint32_t* bits,
                               int bits_pitch, float* dW, int cap, const int* max_seg, hipStream_t st) {
+  // almost always the kernel only reads *max_seg and leaves: a small grid keeps that cheap, and the
+  // workgroups walk the segments in strides when there is work
   const int segs = rows * s.nb;
-  dim3 grid((segs + 3) / 4), block(256);
+  const int blocks = (segs + 3) / 4;
+  dim3 grid(blocks < 1024 ? blocks : 1024), block(256);
   if (dtype == kF32)
     hipLaunchKernelGGL(dw_overflow_kernel<float>, grid, block, 0, st, s, rows, (const float*)dy, N, bits, bits_pitch,
                        dW, cap, max_seg);

@@ -99,3 +99,37 @@ def test_bf16_mlp_reduced(ctx, scheme, p):
     dims = (1024, 768, 512, 1000)
     data = synth.mlp(seed=3, batch=512, dims=dims, pixels=False, bf16=True)
     run_mlp(ctx, data, dims, scheme, p, seed=6, dtype=B.RAD_BF16, has_bias=False)
+
+
+@pytest.mark.parametrize("scheme", [1, 3])
+def test_enqueue_only_steps_match_waited_steps(ctx, scheme):
+    """loss_host = null only enqueues the step: same stores and gradients as the waited step, no loss."""
+    import torch
+    from paper_2007_10412_amd import binding as B, synth
+    from tests.gpu_util import dev, host, empty
+    dims, Bt, p = (512, 384, 256, 100), 256, 0.1
+    data = synth.mlp(seed=11, batch=Bt, dims=dims, pixels=False, bf16=True)
+    m = B.rad_model_create_mlp(ctx, B.RAD_BF16, Bt, list(dims), False, scheme, p)
+    try:
+        params = [dev(w, B.RAD_BF16) for w in data["Ws"]]
+        grads = [empty(w.shape) for w in data["Ws"]]
+        x, labels = dev(data["x"], B.RAD_BF16), dev(data["labels"])
+        loss = B.rad_train_step(ctx, m, B.make_sampling(scheme, p, 77, 0, 0), x, labels, params, grads)
+        assert np.isfinite(loss)
+        want = [host(g).copy() for g in grads]
+        csr = [B.rad_store_export_csr(ctx, B.rad_model_store(m, l), Bt) for l in range(3)]
+        for seed in (5, 6, 77):     # the last one repeats the waited step's draw
+            for g in grads:
+                g.fill_(float("nan"))
+            torch.cuda.synchronize()   # the fills run on torch's stream, the step on the library's
+            assert B.rad_train_step(ctx, m, B.make_sampling(scheme, p, seed, 0, 0), x, labels, params, grads,
+                                    want_loss=False) is None
+        B.rad_ctx_synchronize(ctx)
+        for g, w in zip(grads, want):
+            np.testing.assert_array_equal(host(g), w)
+        for l in range(3):
+            got = B.rad_store_export_csr(ctx, B.rad_model_store(m, l), Bt)
+            for a, b in zip(got, csr[l]):
+                np.testing.assert_array_equal(a, b)
+    finally:
+        B.rad_model_destroy(m)
