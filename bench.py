@@ -96,6 +96,23 @@ def main():
             if n and ms - longer > 0:
                 labels_ms[nm] = ms - longer
     big = max(labels_ms, key=labels_ms.get)
+    # the dW kernel of the widest layers (BASELINE's second number), from the same two steps
+    dw_labels = [k_ for k_ in labels_ms if "_dw_" in k_]
+    dw_kernel = None
+    if dw_labels:
+        dwl = max(dw_labels, key=labels_ms.get)
+        n_, ms_ = B.rad_ctx_timing_read(ctx, dwl)
+        a_, x_ = B.rad_ctx_timing_read_flops(ctx, dwl)
+        if "x" not in dwl.rsplit("_", 1)[1]:
+            for t in ("64", "128", "256"):
+                n2, ms2 = B.rad_ctx_timing_read(ctx, dwl + "x" + t)
+                a2, x2 = B.rad_ctx_timing_read_flops(ctx, dwl + "x" + t)
+                n_ -= n2; ms_ -= ms2; a_ -= a2; x_ -= x2
+        if n_ and ms_ > 0:
+            dw_kernel = {"kernel": dwl, "avg_launch_ms": ms_ / n_, "launches_per_step": n_ / 2,
+                         "executed_tflops": x_ / (ms_ * 1e-3) / 1e12, "algorithmic_tflops": a_ / (ms_ * 1e-3) / 1e12,
+                         "executed_frac_of_peak": x_ / (ms_ * 1e-3) / 1e12 / PEAK[dtype_name],
+                         "note": "executed = 2 B D N on zero-filled tiles (MFMA utilisation); algorithmic = 2 N per kept entry"}
     B.rad_ctx_timing(ctx, big)
     B.rad_ctx_timing_reset(ctx)
     torch.cuda.synchronize()
@@ -149,6 +166,7 @@ def main():
                    "batch": batch, "dims": list(dims), "scheme": args.scheme, "p": p},
         "loss": loss,
         "roofline": roofline,
+        "dw_kernel": dw_kernel,
     }
 
     # stored activation bytes (values / indices+tables / ReLU bits) vs the dense baseline
@@ -185,6 +203,8 @@ def main():
         out["kernels"] = kern
         out["pack_stream"] = pack_stream(B, ctx, torch, dtype_name)
         out["other_configs"] = other_configs(B, ctx, torch, synth)
+        if args.workload == "mlp4096_bf16":
+            out["config4_variants"] = config4_variants(B, ctx, torch, data, dims, batch)
 
     B.rad_model_destroy(model)
 
@@ -193,6 +213,30 @@ def main():
 
     B.rad_ctx_destroy(ctx)
     print(json.dumps(out))
+
+
+def config4_variants(B, ctx, torch, data, dims, batch):
+    """ms/step of the wide bf16 MLP at the other fractions and sampling schemes (steps enqueued back to back)."""
+    res = {}
+    params = [torch.from_numpy(w).cuda().to(torch.bfloat16).contiguous() for w in data["Ws"]]
+    grads = [torch.empty(w.shape, device="cuda", dtype=torch.float32) for w in data["Ws"]]
+    x = torch.from_numpy(data["x"]).cuda().to(torch.bfloat16).contiguous()
+    labels = torch.from_numpy(data["labels"]).cuda()
+    for name, scheme in (("per_example", 3), ("shared", 2)):
+        for p in (0.5, 0.1, 0.02):
+            model = B.rad_model_create_mlp(ctx, B.RAD_BF16, batch, list(dims), False, scheme, p)
+            for i in range(3):
+                B.rad_train_step(ctx, model, B.make_sampling(scheme, p, 50 + i, 0, 0), x, labels, params, grads, False)
+            torch.cuda.synchronize()
+            steps = 10
+            t0 = time.perf_counter()
+            for i in range(steps):
+                B.rad_train_step(ctx, model, B.make_sampling(scheme, p, 60 + i, 0, 0), x, labels, params, grads, False)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / steps
+            res["%s_p%g" % (name, p)] = {"ms_per_step": 1e3 * dt, "samples_per_s": batch / dt}
+            B.rad_model_destroy(model)
+    return res
 
 
 def other_configs(B, ctx, torch, synth):

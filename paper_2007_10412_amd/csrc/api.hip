@@ -187,6 +187,7 @@ struct rad_store {
   int scheme = 0, dtype = 0;
   int rows = 0, cols = 0, d_out = 0, steps = 1;
   int k = 0;
+  int k_pitch = 0;                // shared scheme: row pitch of the compact values, k rounded up to 8 (padding stays zero)
   double p = 1.0;
   float scale = 1.f;
   int64_t capacity = 0;
@@ -218,6 +219,7 @@ static StoreView store_view(const rad_store* s, int slot) {
   v.idx_shared = s->scheme == kFixedKShared ? 1 : 0;
   v.paired = s->paired() ? 1 : 0;
   v.indices = s->scheme == kFixedKShared ? s->indices + (size_t)slot * s->k : s->indices;
+  v.shared_k = s->scheme == kFixedKShared ? s->k : 0;
   v.row_ptr = s->row_ptr ? s->row_ptr + (size_t)slot * s->rows : nullptr;
   const size_t prow0 = (size_t)slot * s->plan_rows_per_step;
   v.bucket_off = s->bucket_off ? s->bucket_off + prow0 * (s->nb + 1) : nullptr;
@@ -277,6 +279,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   s->scheme = scheme; s->dtype = L->dtype; s->rows = (int)L->batch; s->cols = (int)L->d_in;
   s->d_out = (int)L->d_out; s->steps = steps; s->p = p;
   s->k = (int)rad_fixed_k(p, L->d_in);
+  s->k_pitch = scheme == RAD_FIXEDK_SHARED ? (s->k + 7) / 8 * 8 : s->k;
   s->nb = (s->cols + kBucket - 1) / kBucket;
   s->bm_pitch = (s->cols + 31) / 32;
   const int64_t R = (int64_t)steps * s->rows;
@@ -289,7 +292,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
     s->plan_rows_per_step = s->rows;
   } else {
     s->scale = (float)((double)s->cols / (double)s->k);
-    s->capacity = R * s->k;
+    s->capacity = R * s->k_pitch;
     s->plan_rows_per_step = scheme == RAD_FIXEDK_SHARED ? 1 : s->rows;
   }
   auto alloc = [&](void** ptr, size_t bytes) -> bool {
@@ -310,6 +313,9 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
     ok = ok && alloc((void**)&s->bits, (size_t)R * s->bits_pitch * 4);
   }
   if (ok) ok = hipMemsetAsync(s->overflow, 0, 2 * sizeof(int), c->stream) == hipSuccess;
+  // the padding columns of the compact layout are read by the dW GEMM and never written
+  if (ok && scheme == RAD_FIXEDK_SHARED && s->k_pitch != s->k)
+    ok = hipMemsetAsync(s->values, 0, (size_t)s->capacity * s->elem(), c->stream) == hipSuccess;
   if (!ok) { rad_store_destroy(s); return fail(c, RAD_ERR_DEVICE, "store allocation failed"); }
   *out = s;
   return RAD_OK;
@@ -318,6 +324,8 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
 static rad_status store_nnz(rad_ctx* c, const rad_store* s, int64_t* nnz) {
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   if (s->scheme == RAD_EXACT) { *nnz = s->capacity; return RAD_OK; }
+  // shared: k entries per row by construction (the rows of the compact layout may be padded apart)
+  if (s->scheme == RAD_FIXEDK_SHARED) { *nnz = (int64_t)s->steps * s->rows * s->k; return RAD_OK; }
   uint32_t last = 0;
   HIP_TRY(c, hipMemcpy(&last, s->row_ptr + (size_t)s->steps * s->rows, 4, hipMemcpyDeviceToHost));
   int ov = 0;
@@ -335,7 +343,7 @@ extern "C" rad_status rad_store_get_stats(rad_ctx* c, const rad_store* s, rad_st
   RAD_TRY(store_nnz(c, s, &nnz));
   const int64_t R = (int64_t)s->steps * s->rows;
   out->nnz = (uint64_t)nnz;
-  out->value_bytes = (uint64_t)nnz * s->elem();
+  out->value_bytes = (uint64_t)nnz * s->elem();   // entries; the shared scheme's row padding (< 8 per row) is not counted
   out->dense_bytes = (uint64_t)R * s->cols * s->elem();
   out->bit_bytes = s->bits ? (uint64_t)R * s->bits_pitch * 4 : 0;
   if (s->scheme == RAD_EXACT) out->index_bytes = 0;
@@ -355,16 +363,19 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
   RAD_TRY(store_nnz(c, s, &nnz));
   if (nnz > capacity) return fail(c, RAD_ERR_CAPACITY, "export buffers too small");
   const int64_t R = (int64_t)s->steps * s->rows;
-  std::vector<unsigned char> vraw((size_t)nnz * (s->paired() ? 4 : s->elem()));
-  if (nnz) HIP_TRY(c, hipMemcpy(vraw.data(), s->values, vraw.size(), hipMemcpyDeviceToHost));
+  const bool shared = s->scheme == RAD_FIXEDK_SHARED;
+  const int64_t n_raw = shared ? R * s->k_pitch : nnz;          // entries held, padding included
+  std::vector<unsigned char> vraw((size_t)n_raw * (s->paired() ? 4 : s->elem()));
+  if (n_raw) HIP_TRY(c, hipMemcpy(vraw.data(), s->values, vraw.size(), hipMemcpyDeviceToHost));
   for (int64_t i = 0; i < nnz; ++i) {
+    const int64_t src = shared ? (i / s->k) * s->k_pitch + i % s->k : i;
     if (s->paired()) {
-      uint32_t u = reinterpret_cast<uint32_t*>(vraw.data())[i] & 0xFFFF0000u;
+      uint32_t u = reinterpret_cast<uint32_t*>(vraw.data())[src] & 0xFFFF0000u;
       std::memcpy(&val[i], &u, 4);
     } else if (s->dtype == kBF16) {
-      uint32_t u = (uint32_t)reinterpret_cast<uint16_t*>(vraw.data())[i] << 16;
+      uint32_t u = (uint32_t)reinterpret_cast<uint16_t*>(vraw.data())[src] << 16;
       std::memcpy(&val[i], &u, 4);
-    } else val[i] = reinterpret_cast<float*>(vraw.data())[i];
+    } else val[i] = reinterpret_cast<float*>(vraw.data())[src];
   }
   if (s->scheme == RAD_EXACT) {
     for (int64_t r = 0; r <= R; ++r) row_ptr[r] = r * s->cols;
@@ -373,7 +384,7 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
   }
   std::vector<uint32_t> rp((size_t)R + 1);
   HIP_TRY(c, hipMemcpy(rp.data(), s->row_ptr, rp.size() * 4, hipMemcpyDeviceToHost));
-  for (int64_t r = 0; r <= R; ++r) row_ptr[r] = rp[(size_t)r];
+  for (int64_t r = 0; r <= R; ++r) row_ptr[r] = shared ? r * s->k : (int64_t)rp[(size_t)r];
   if (s->scheme == RAD_FIXEDK_SHARED) {
     std::vector<uint16_t> idx((size_t)s->steps * s->k);
     HIP_TRY(c, hipMemcpy(idx.data(), s->indices, idx.size() * 2, hipMemcpyDeviceToHost));
@@ -427,7 +438,7 @@ static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, u
   a.scheme = s->scheme;
   a.plan_rows = s->steps * s->plan_rows_per_step;
   a.rows_per_step = s->rows;
-  a.cols = s->cols; a.k = s->k;
+  a.cols = s->cols; a.k = s->k; a.k_pitch = s->k_pitch;
   a.thresh = (uint64_t)std::llround(s->p * 4294967296.0) >> c->key_shift;
   a.key_shift = c->key_shift;
   a.bitmap = bitmap; a.bm_pitch = s->bm_pitch;
@@ -543,8 +554,8 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
       HIP_TRY(c, timed(c, "fill", [&](const char**) {
         return launch_fill_u32(reinterpret_cast<uint32_t*>(dW), 0u, (int64_t)s->cols * N, c->stream);
       }));
-    g.M = s->k;
-    g.A = static_cast<const char*>(s->values) + (size_t)slot * s->rows * s->k * s->elem(); g.lda = s->k;
+    g.M = s->k; g.m_load = s->k_pitch;     // the operand is readable (zeros) up to the padded width
+    g.A = static_cast<const char*>(s->values) + (size_t)slot * s->rows * s->k_pitch * s->elem(); g.lda = s->k_pitch;
     g.row_map = s->indices + (size_t)slot * s->k;
     g.beta = 1;
     return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);

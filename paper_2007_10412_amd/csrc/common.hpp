@@ -48,6 +48,7 @@ struct StoreView {
   int bm_pitch;              // words per bitmap row
   int plan_row_stride;       // 1, or 0 when every row shares one plan row (shared scheme)
   int idx_shared;            // shared scheme: `indices` holds the k columns once (written by row 0)
+  int shared_k;              // shared scheme: entries per row (rows are k rounded up to 8 apart); else 0
   int paired;                // bf16 per-entry draws: `values` holds 32-bit (value, column) entries, no `indices`
   float scale;
 };

@@ -403,7 +403,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   LoadA la; LoadB lb;
-  la.init(g.A, g.lda, g.a_mask, g.a_mask_pitch, m0, g.M, g.K, g.sa);
+  la.init(g.A, g.lda, g.a_mask, g.a_mask_pitch, m0, g.m_load > g.M ? g.m_load : g.M, g.K, g.sa);
   lb.init(g.B, g.ldb, g.b_mask, g.b_mask_pitch, n0, g.N, g.K, g.sa);
   la.configure((BM + BN) * BK);
   const int KT = (g.K + BK - 1) / BK;

@@ -76,7 +76,7 @@ bool gemm_is_vec_edge(const GemmArgs& g) {
   bool ok = g.K > 0 && (reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && g.ldb % 8 == 0;
   if (AK != kOpSparse) ok = ok && (reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && g.lda % 8 == 0;
   if (AK == kOpK || BKIND == kOpK) ok = ok && g.K % 8 == 0;
-  if (AK == kOpMN) ok = ok && g.M % 8 == 0;
+  if (AK == kOpMN) ok = ok && (g.m_load > g.M ? g.m_load : g.M) % 8 == 0;
   if (BKIND == kOpMN) ok = ok && g.N % 8 == 0;
   return ok;
 }

@@ -11,6 +11,7 @@ struct PlanArgs {
   int rows_per_step;   // rows of one step block of the store
   int cols;
   int k;               // fixed-k schemes
+  int k_pitch;         // shared scheme: entries between consecutive rows of the compact values (>= k)
   uint64_t thresh;     // Bernoulli: keep iff key < thresh
   int key_shift;       // 0; tests raise it to force equal keys
   uint32_t* bitmap;    // [plan_rows][bm_pitch]
@@ -49,6 +50,7 @@ enum EpiKind : int {
 struct GemmArgs {
   int dry_run;                  // select the kernel and report its label, launch nothing
   int M, N, K;
+  int m_load;                   // 0, or > M: operand A is readable (as zeros) up to this many rows
   const void* A; int64_t lda;
   const void* B; int64_t ldb;
   // optional bit mask over a dense operand: element (outer, inner) is zeroed when

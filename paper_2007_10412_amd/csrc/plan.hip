@@ -81,12 +81,12 @@ __device__ __forceinline__ void finish_row(const PlanArgs& a, int prow, const ui
       a.row_ptr[prow] = (uint32_t)((uint64_t)prow * a.k);
       if (prow == a.plan_rows - 1) a.row_ptr[a.plan_rows] = (uint32_t)((uint64_t)a.plan_rows * a.k);
     }
-  } else {  // shared: every store row of this step holds k entries
+  } else {  // shared: every store row of this step holds k entries, rows k_pitch apart
     const int r0 = prow * a.rows_per_step;
     for (int r = tid; r < a.rows_per_step; r += kPlanThreads)
-      a.row_ptr[r0 + r] = (uint32_t)((uint64_t)(r0 + r) * a.k);
+      a.row_ptr[r0 + r] = (uint32_t)((uint64_t)(r0 + r) * a.k_pitch);
     if (tid == 0 && prow == a.plan_rows - 1)
-      a.row_ptr[a.plan_rows * a.rows_per_step] = (uint32_t)((uint64_t)a.plan_rows * a.rows_per_step * a.k);
+      a.row_ptr[a.plan_rows * a.rows_per_step] = (uint32_t)((uint64_t)a.plan_rows * a.rows_per_step * a.k_pitch);
   }
 }
 
@@ -131,8 +131,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_bernoulli_kernel(PlanArgs a
 
 // Fixed-k: the k smallest (key, column) pairs of the row.  QPT = Philox calls
 // (groups of four consecutive elements) per thread; the row's keys stay in
-// registers across the radix-select passes.
-template <int QPT>
+// registers across the radix-select passes.  FULL: the row is exactly
+// QPT * 4 * 256 columns and starts on a Philox call boundary, so every register
+// slot holds an element and the per-element validity tests fold away.
+template <int QPT, bool FULL>
 __global__ __launch_bounds__(kPlanThreads) void plan_fixedk_kernel(PlanArgs a) {
   static_assert(QPT <= 16, "keep/valid masks are 64 bits");
   __shared__ uint32_t s_bm[2048];
@@ -153,17 +155,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fixedk_kernel(PlanArgs a) {
   const int nq = (int)(((f0 + (uint64_t)a.cols - 1) >> 2) - q0) + 1;
 
   uint32_t key[QPT * 4];
-  uint64_t valid = 0;                  // bit (4i+w): element exists in this row
+  uint64_t valid = FULL ? ~0ull : 0ull;   // bit (4i+w): element exists in this row
 #pragma unroll
   for (int i = 0; i < QPT; ++i) {
     const int qi = tid + i * kPlanThreads;
     u32x4 k4 = {0, 0, 0, 0};
-    if (qi < nq) k4 = element_quad_keys(q0 + (uint64_t)qi, a.stream_id, step, a.seed_lo, a.seed_hi);
+    if (FULL || qi < nq) k4 = element_quad_keys(q0 + (uint64_t)qi, a.stream_id, step, a.seed_lo, a.seed_hi);
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       key[4 * i + w] = k4[w] >> a.key_shift;
       const int j = qi * 4 + w - lead;
-      if (qi < nq && j >= 0 && j < a.cols) valid |= 1ull << (4 * i + w);
+      if (!FULL && qi < nq && j >= 0 && j < a.cols) valid |= 1ull << (4 * i + w);
     }
   }
 
@@ -388,7 +390,8 @@ __global__ __launch_bounds__(256) void unpack_kernel(StoreView s, T* __restrict_
     return;
   }
   const T* vals = reinterpret_cast<const T*>(s.values);
-  // shared scheme: the k columns are stored once
+  // shared scheme: the k columns are stored once, and a row holds k entries (its pitch may be padded)
+  if (s.idx_shared && end > beg + s.shared_k) end = beg + s.shared_k;
   for (int64_t e = beg + threadIdx.x; e < end; e += 256) out[s.indices[s.idx_shared ? e - beg : e]] = vals[e];
 }
 
@@ -410,10 +413,17 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t st) {
   // rows start on a Philox call boundary when cols is a multiple of 4
   const int nq_max = (a.cols % 4 == 0) ? a.cols / 4 : a.cols / 4 + 2;
   const int qpt = (nq_max + kPlanThreads - 1) / kPlanThreads;
-  if (qpt <= 1) hipLaunchKernelGGL(plan_fixedk_kernel<1>, grid, block, 0, st, a);
-  else if (qpt <= 4) hipLaunchKernelGGL(plan_fixedk_kernel<4>, grid, block, 0, st, a);
-  else if (qpt <= 16) hipLaunchKernelGGL(plan_fixedk_kernel<16>, grid, block, 0, st, a);
-  else return hipErrorInvalidValue;
+  const bool full = a.cols == qpt * 4 * kPlanThreads;     // then also a multiple of 4: rows start on a call boundary
+  if (qpt <= 1) {
+    if (full) hipLaunchKernelGGL((plan_fixedk_kernel<1, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((plan_fixedk_kernel<1, false>), grid, block, 0, st, a);
+  } else if (qpt <= 4) {
+    if (full && qpt == 4) hipLaunchKernelGGL((plan_fixedk_kernel<4, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((plan_fixedk_kernel<4, false>), grid, block, 0, st, a);
+  } else if (qpt <= 16) {
+    if (full && qpt == 16) hipLaunchKernelGGL((plan_fixedk_kernel<16, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((plan_fixedk_kernel<16, false>), grid, block, 0, st, a);
+  } else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
