@@ -558,6 +558,19 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     g.A = static_cast<const char*>(s->values) + (size_t)slot * s->rows * s->k_pitch * s->elem(); g.lda = s->k_pitch;
     g.row_map = s->indices + (size_t)slot * s->k;
     g.beta = 1;
+    if (s->dtype == kBF16 && s->rows >= 512) {
+      // k rows of dW give few tiles: split the batch (the K dimension) over several workgroups per tile,
+      // which add their partial sums atomically into the zeroed / accumulating dW
+      const int tiles = ((g.M + 127) / 128) * ((N + 127) / 128);
+      if (tiles < 192) {
+        int splits = (512 + tiles - 1) / tiles;
+        if (splits > 8) splits = 8;
+        int ks = ((s->rows + splits - 1) / splits + 31) / 32 * 32;
+        if (ks < 256) ks = 256;
+        splits = (s->rows + ks - 1) / ks;
+        if (splits > 1) { g.k_split = ks; g.k_splits = splits; }
+      }
+    }
     return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
   }
   g.M = s->cols;

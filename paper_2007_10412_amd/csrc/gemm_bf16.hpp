@@ -402,11 +402,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // split K: blockIdx.y takes the K range [kbeg, kend) and the epilogue adds its partial result atomically
+  const int kbeg = g.k_splits > 1 ? (int)blockIdx.y * g.k_split : 0;
+  const int kend = g.k_splits > 1 ? min(g.K, kbeg + g.k_split) : g.K;
   LoadA la; LoadB lb;
-  la.init(g.A, g.lda, g.a_mask, g.a_mask_pitch, m0, g.m_load > g.M ? g.m_load : g.M, g.K, g.sa);
-  lb.init(g.B, g.ldb, g.b_mask, g.b_mask_pitch, n0, g.N, g.K, g.sa);
+  la.init(g.A, g.lda, g.a_mask, g.a_mask_pitch, m0, g.m_load > g.M ? g.m_load : g.M, kend, g.sa);
+  lb.init(g.B, g.ldb, g.b_mask, g.b_mask_pitch, n0, g.N, kend, g.sa);
   la.configure((BM + BN) * BK);
-  const int KT = (g.K + BK - 1) / BK;
+  const int KT = (kend - kbeg + BK - 1) / BK;
 
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
   // one iteration; R_ = kt % 3 fixes the LDS stages at compile time
@@ -421,8 +424,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
     if constexpr (steady) {
       interleave_reads_commits<sl, TM, TN, BM, BN>(cur, cur + kAElems, wr, wr + kAElems, wm0, wn0, fa1, fb1, la, lb);
       // the slot is free again: the loads of slice kt+2+NS start now and have NS iterations to arrive
-      la.template fetch<sl, false>((kt + 2 + NS) * BK); lb.template fetch<sl, false>((kt + 2 + NS) * BK);
-      la.bounds((kt + 3 + NS) * BK);
+      la.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); lb.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK);
+      la.bounds(kbeg + (kt + 3 + NS) * BK);
       mfma_step<TM, TN>(fa0, fb0, acc);
       load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
       mfma_step<TM, TN>(fa1, fb1, acc);
@@ -449,8 +452,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       if (kt + 2 < KT) { commit_all<LoadA, sl>(la, wr); commit_all<LoadB, sl>(lb, wr + kAElems); }
       mfma_step<TM, TN>(fa0, fb0, acc);
       if (kt + 2 + NS < KT) {
-        la.template fetch<sl>((kt + 2 + NS) * BK); lb.template fetch<sl>((kt + 2 + NS) * BK);
-        la.bounds((kt + 3 + NS) * BK);
+        la.template fetch<sl>(kbeg + (kt + 2 + NS) * BK); lb.template fetch<sl>(kbeg + (kt + 2 + NS) * BK);
+        la.bounds(kbeg + (kt + 3 + NS) * BK);
       }
       if (kt + 1 < KT) load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
       mfma_step<TM, TN>(fa1, fb1, acc);
@@ -464,26 +467,26 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
   // in slot (s - 2) % NS).  The long-K path is written without conditions so that the steady loop is
   // entered with a known set of loads in flight.
   // the steady loop never fetches the last slice of a ragged K: its loads carry no K predicate
-  const int KTs = (EMODE == 1 && g.K % BK != 0) ? KT - 1 : KT;
+  const int KTs = (EMODE == 1 && (kend - kbeg) % BK != 0) ? KT - 1 : KT;
   const bool long_k = KTs > 4 + NS;
   int kt = 0;
   if (long_k) {
-    la.bounds(0);
-    la.template fetch<0>(0); lb.template fetch<0>(0);
-    la.bounds(BK);
+    la.bounds(kbeg + 0);
+    la.template fetch<0>(kbeg + 0); lb.template fetch<0>(kbeg + 0);
+    la.bounds(kbeg + BK);
     commit_all<LoadA, 0>(la, smem); commit_all<LoadB, 0>(lb, smem + kAElems);
-    la.template fetch<0>(BK); lb.template fetch<0>(BK);
-    la.bounds(2 * BK);
+    la.template fetch<0>(kbeg + BK); lb.template fetch<0>(kbeg + BK);
+    la.bounds(kbeg + 2 * BK);
     commit_all<LoadA, 0>(la, smem + kStageElems); commit_all<LoadB, 0>(lb, smem + kStageElems + kAElems);
     // The loads left in flight must be issued in the order the loop issues them (slot by slot, A before
     // B): the wait counts inside the loop are fixed at compile time from the worse of the two orders.
     __builtin_amdgcn_sched_barrier(0);
-    la.template fetch<0>(2 * BK); lb.template fetch<0>(2 * BK); la.bounds(3 * BK);
+    la.template fetch<0>(kbeg + 2 * BK); lb.template fetch<0>(kbeg + 2 * BK); la.bounds(kbeg + 3 * BK);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (NS == 3) {
-      la.template fetch<1>(3 * BK); lb.template fetch<1>(3 * BK); la.bounds(4 * BK);
+      la.template fetch<1>(kbeg + 3 * BK); lb.template fetch<1>(kbeg + 3 * BK); la.bounds(kbeg + 4 * BK);
       __builtin_amdgcn_sched_barrier(0);
-      la.template fetch<2>(4 * BK); lb.template fetch<2>(4 * BK); la.bounds(5 * BK);
+      la.template fetch<2>(kbeg + 4 * BK); lb.template fetch<2>(kbeg + 4 * BK); la.bounds(kbeg + 5 * BK);
       __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
@@ -498,20 +501,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
     } while (kt + 4 + NS < KTs);
   } else {
     if (KT > 0) {
-      la.bounds(0);
-      la.template fetch<0>(0); lb.template fetch<0>(0);
-      la.bounds(BK);
+      la.bounds(kbeg + 0);
+      la.template fetch<0>(kbeg + 0); lb.template fetch<0>(kbeg + 0);
+      la.bounds(kbeg + BK);
       commit_all<LoadA, 0>(la, smem); commit_all<LoadB, 0>(lb, smem + kAElems);
     }
     if (KT > 1) {
-      la.template fetch<0>(BK); lb.template fetch<0>(BK);
-      la.bounds(2 * BK);
+      la.template fetch<0>(kbeg + BK); lb.template fetch<0>(kbeg + BK);
+      la.bounds(kbeg + 2 * BK);
       commit_all<LoadA, 0>(la, smem + kStageElems); commit_all<LoadB, 0>(lb, smem + kStageElems + kAElems);
     }
-    if (KT > 2) { la.template fetch<0>(2 * BK); lb.template fetch<0>(2 * BK); la.bounds(3 * BK); }
+    if (KT > 2) { la.template fetch<0>(kbeg + 2 * BK); lb.template fetch<0>(kbeg + 2 * BK); la.bounds(kbeg + 3 * BK); }
     if constexpr (NS == 3) {
-      if (KT > 3) { la.template fetch<1>(3 * BK); lb.template fetch<1>(3 * BK); la.bounds(4 * BK); }
-      if (KT > 4) { la.template fetch<2>(4 * BK); lb.template fetch<2>(4 * BK); la.bounds(5 * BK); }
+      if (KT > 3) { la.template fetch<1>(kbeg + 3 * BK); lb.template fetch<1>(kbeg + 3 * BK); la.bounds(kbeg + 4 * BK); }
+      if (KT > 4) { la.template fetch<2>(kbeg + 4 * BK); lb.template fetch<2>(kbeg + 4 * BK); la.bounds(kbeg + 5 * BK); }
     }
     __syncthreads();
     if (KT > 0) load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);

@@ -65,7 +65,7 @@ hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
   }
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(kGemmThreads), smem, st, g);
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, g.k_splits > 1 ? g.k_splits : 1), dim3(kGemmThreads), smem, st, g);
   return hipGetLastError();
 }
 
