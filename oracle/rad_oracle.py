@@ -18,6 +18,12 @@ matrix P), so that dW~ = x~^T g is an unbiased estimate of dW = x^T g, while
 dX = g W^T never touches a sampled quantity (Section 4.2: only dh/dW is
 sampled, so every parameter-to-loss path crosses one sampled Jacobian).
 
+The with-replacement schemes are the matrix P of Section 3.2 as printed:
+P = (d/k) sum_s e_{i_s} e_{i_s}^T with k indices i_s drawn uniformly and
+independently, so coordinate j carries the weight m_j d/k, m_j being how often j
+was drawn (pins: multiplicities sum to k and are Binomial(k, 1/d); the
+closed-form variance ((d-1)/k) sum_b x^2 g^2; k = d does not give the baseline).
+
 Pins (tests/test_oracle_*.py): Philox against PyTorch's own Philox4_32 engine;
 k = ceil(p d) against the eight worked values of Appendix A; byte accounting
 against Appendix A and Table 1; p = 1 against torch autograd; mean and variance
@@ -37,6 +43,8 @@ EXACT = 0               # store everything (the paper's baseline)
 BERNOULLI = 1           # keep each entry with probability p, scale 1/p
 FIXEDK_SHARED = 2       # "same sample": one k-subset for the whole minibatch
 FIXEDK_PER_EXAMPLE = 3  # "different sample": a k-subset per minibatch element
+REPLACE_SHARED = 4      # k draws WITH replacement, one set for the whole minibatch
+REPLACE_PER_EXAMPLE = 5  # k draws WITH replacement per minibatch element
 
 F32 = 0
 BF16 = 1
@@ -113,12 +121,42 @@ def bernoulli_threshold(p):
 
 def sample_scale(scheme, p, d):
     """Inverse inclusion probability, as fp32.  Bernoulli: 1/p.  Fixed-k
-    without replacement: d/k (Section 3.2 scales by d/k)."""
+    (with or without replacement): d/k (Section 3.2 scales by d/k)."""
     if scheme == EXACT:
         return np.float32(1.0)
     if scheme == BERNOULLI:
         return np.float32(1.0 / p)
     return np.float32(float(d) / float(fixed_k(p, d)))
+
+
+def replace_draws(scheme, p, seed, stream_id, step, rows, d):
+    """Indices i_s of the k uniform draws with replacement (Section 3.2: each
+    P_s is sampled uniformly from {P_1 .. P_d}), [rows, k].
+
+    Draw s of row b takes the key of flat index f = b k + s (f = s for the
+    shared scheme) in the element_keys addressing and maps it to
+    i = floor(key * d / 2^32): every index owns floor or ceil of 2^32/d keys.
+    """
+    k = fixed_k(p, d)
+    if scheme == REPLACE_SHARED:
+        keys = element_keys(seed, stream_id, step, 0, k).reshape(1, k)
+    elif scheme == REPLACE_PER_EXAMPLE:
+        keys = element_keys(seed, stream_id, step, 0, rows * k).reshape(rows, k)
+    else:
+        raise ValueError("not a with-replacement scheme")
+    idx = (keys.astype(np.uint64) * np.uint64(d)) >> np.uint64(32)
+    if scheme == REPLACE_SHARED:
+        idx = np.broadcast_to(idx, (rows, k))
+    return idx.astype(np.int64)
+
+
+def multiplicity(scheme, p, seed, stream_id, step, rows, d):
+    """m [rows, d]: how often each coordinate was drawn; rows sum to k."""
+    idx = replace_draws(scheme, p, seed, stream_id, step, rows, d)
+    m = np.zeros((rows, d), dtype=np.int64)
+    for b in range(rows):
+        np.add.at(m[b], idx[b], 1)
+    return m
 
 
 def keep_mask(scheme, p, seed, stream_id, step, rows, d):
@@ -135,6 +173,8 @@ def keep_mask(scheme, p, seed, stream_id, step, rows, d):
     if scheme == BERNOULLI:
         keys = element_keys(seed, stream_id, step, 0, rows * d).reshape(rows, d)
         return keys.astype(np.uint64) < np.uint64(bernoulli_threshold(p))
+    if scheme in (REPLACE_SHARED, REPLACE_PER_EXAMPLE):
+        return multiplicity(scheme, p, seed, stream_id, step, rows, d) > 0
     k = fixed_k(p, d)
     if scheme == FIXEDK_SHARED:
         keys = element_keys(seed, stream_id, step, 0, d).reshape(1, d)
@@ -182,9 +222,17 @@ def sample_pack(x, scheme, p, seed, stream_id, step, dtype=F32):
     """
     x = np.asarray(x, dtype=np.float32)
     rows, d = x.shape
-    mask = keep_mask(scheme, p, seed, stream_id, step, rows, d)
     scale = sample_scale(scheme, p, d)
-    scaled = to_storage(x * scale, dtype)            # one fp32 multiply, one rounding
+    if scheme in (REPLACE_SHARED, REPLACE_PER_EXAMPLE):
+        # weight of coordinate j is m_j d/k: the fp32 product of the count and the fp32 scale, then one fp32
+        # multiply with x and one rounding (a coordinate drawn once is scaled exactly as in the other schemes)
+        m = multiplicity(scheme, p, seed, stream_id, step, rows, d)
+        mask = m > 0
+        weight = (m.astype(np.float32) * scale).astype(np.float32)
+        scaled = to_storage(x * weight, dtype)
+    else:
+        mask = keep_mask(scheme, p, seed, stream_id, step, rows, d)
+        scaled = to_storage(x * scale, dtype)            # one fp32 multiply, one rounding
     xt = np.where(mask, scaled, np.float32(0.0))
     row_ptr = np.zeros(rows + 1, dtype=np.int64)
     row_ptr[1:] = np.cumsum(mask.sum(axis=1))
