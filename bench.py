@@ -25,7 +25,8 @@ if ROOT not in sys.path:
 PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy kernel),
 # see profiles/train_step_mlp4096_bf16_hbm_traffic.txt; only for the default workload and kernel
-MEASURED_TRAFFIC = {("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_dw_sparse_256x256"): 156.2e6}
+MEASURED_TRAFFIC = {("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_fwd_256"): 248.5e6,
+                    ("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_dw_sparse_256x256"): 156.0e6}
 HBM_PEAK = 8000.0                          # GB/s
 
 WORKLOADS = {
@@ -33,7 +34,8 @@ WORKLOADS = {
     "mlp4096_bf16": ("bf16", 4096, (4096, 4096, 4096, 1000), False, False),
     "mlp784_f32": ("f32", 150, (784, 300, 300, 10), True, True),
 }
-SCHEMES = {"per_example": 3, "shared": 2, "bernoulli": 1, "exact": 0}
+SCHEMES = {"per_example": 3, "shared": 2, "bernoulli": 1, "exact": 0,
+           "replace_per_example": 5, "replace_shared": 4}      # the last two draw with replacement
 
 
 def main():
@@ -222,8 +224,8 @@ def config4_variants(B, ctx, torch, data, dims, batch):
     grads = [torch.empty(w.shape, device="cuda", dtype=torch.float32) for w in data["Ws"]]
     x = torch.from_numpy(data["x"]).cuda().to(torch.bfloat16).contiguous()
     labels = torch.from_numpy(data["labels"]).cuda()
-    for name, scheme in (("per_example", 3), ("shared", 2)):
-        for p in (0.5, 0.1, 0.02):
+    for name, scheme in (("per_example", 3), ("shared", 2), ("replace_per_example", 5), ("replace_shared", 4)):
+        for p in ((0.5, 0.1, 0.02) if scheme in (2, 3) else (0.1,)):
             model = B.rad_model_create_mlp(ctx, B.RAD_BF16, batch, list(dims), False, scheme, p)
             for i in range(3):
                 B.rad_train_step(ctx, model, B.make_sampling(scheme, p, 50 + i, 0, 0), x, labels, params, grads, False)

@@ -48,12 +48,19 @@ typedef enum { RAD_F32 = 0, RAD_BF16 = 1 } rad_dtype; /* accumulation is always 
  * k = rad_fixed_k(p, d_in) coordinates drawn without replacement and scale
  * by d_in/k: SHARED uses one index set for the whole minibatch (the paper's
  * "same sample"), PER_EXAMPLE an independent one per row ("different
- * sample"). */
+ * sample").  The two REPLACE schemes are the matrix P of Section 3.2 as
+ * printed: k indices drawn uniformly WITH replacement (draw s of row b maps
+ * the key of flat index b k + s, or s for SHARED, to floor(key d_in / 2^32));
+ * a coordinate drawn m times is stored once with the weight m d_in/k, so a
+ * row holds between 1 and k entries.  Their stores are always kept as
+ * per-row (value, column) lists. */
 typedef enum {
   RAD_EXACT = 0,
   RAD_BERNOULLI = 1,
   RAD_FIXEDK_SHARED = 2,
-  RAD_FIXEDK_PER_EXAMPLE = 3
+  RAD_FIXEDK_PER_EXAMPLE = 3,
+  RAD_REPLACE_SHARED = 4,
+  RAD_REPLACE_PER_EXAMPLE = 5
 } rad_scheme;
 
 typedef enum { RAD_LINEAR = 0, RAD_CONV2D = 1 } rad_kind;

@@ -196,6 +196,7 @@ struct rad_store {
   uint32_t* row_ptr = nullptr;
   uint16_t* bucket_off = nullptr;
   uint32_t* row_cnt = nullptr;
+  uint16_t* mult = nullptr;       // with-replacement draws: draw counts, [steps * plan rows][k] in entry order
   uint32_t* bits = nullptr;
   uint32_t* bitmap = nullptr;     // transient, points into a context workspace after a plan
   int* overflow = nullptr;        // sticky flag: a Bernoulli draw exceeded the capacity (stays set until read)
@@ -205,7 +206,10 @@ struct rad_store {
   int plan_rows_per_step = 0;     // rows (per example / Bernoulli), 1 (shared), 0 (exact)
   size_t elem() const { return dtype == kBF16 ? 2 : 4; }
   // bf16 stores with per-entry draws keep (value, column) in one 32-bit entry
-  bool paired() const { return dtype == kBF16 && (scheme == kBernoulli || scheme == kFixedKPerExample); }
+  bool paired() const { return dtype == kBF16 && (scheme == kBernoulli || scheme == kFixedKPerExample || replace()); }
+  bool replace() const { return scheme == kReplaceShared || scheme == kReplacePerExample; }
+  // rows hold a number of entries that only the plan kernel knows
+  bool counted_rows() const { return scheme == kBernoulli || replace(); }
   size_t bitmap_words() const { return (size_t)steps * plan_rows_per_step * bm_pitch; }
 };
 
@@ -215,11 +219,13 @@ static StoreView store_view(const rad_store* s, int slot) {
   v.capacity = s->capacity;
   v.rows = s->rows; v.cols = s->cols; v.nb = s->nb; v.bm_pitch = s->bm_pitch;
   v.scale = s->scale;
-  v.plan_row_stride = s->scheme == kFixedKShared ? 0 : 1;
+  v.plan_row_stride = (s->scheme == kFixedKShared || s->scheme == kReplaceShared) ? 0 : 1;
   v.idx_shared = s->scheme == kFixedKShared ? 1 : 0;
   v.paired = s->paired() ? 1 : 0;
   v.indices = s->scheme == kFixedKShared ? s->indices + (size_t)slot * s->k : s->indices;
   v.shared_k = s->scheme == kFixedKShared ? s->k : 0;
+  v.mult = s->mult ? s->mult + (size_t)slot * s->plan_rows_per_step * s->k : nullptr;
+  v.mult_pitch = s->k;
   v.row_ptr = s->row_ptr ? s->row_ptr + (size_t)slot * s->rows : nullptr;
   const size_t prow0 = (size_t)slot * s->plan_rows_per_step;
   v.bucket_off = s->bucket_off ? s->bucket_off + prow0 * (s->nb + 1) : nullptr;
@@ -246,14 +252,14 @@ static rad_status check_layer(rad_ctx* c, const rad_layer* L) {
 }
 
 static rad_status check_scheme(rad_ctx* c, int scheme, double p) {
-  if (scheme < RAD_EXACT || scheme > RAD_FIXEDK_PER_EXAMPLE) return fail(c, RAD_ERR_PARAM, "unknown sampling scheme");
+  if (scheme < RAD_EXACT || scheme > RAD_REPLACE_PER_EXAMPLE) return fail(c, RAD_ERR_PARAM, "unknown sampling scheme");
   if (!(p > 0.0) || p > 1.0) return fail(c, RAD_ERR_PARAM, "p must be in (0, 1]");
   return RAD_OK;
 }
 
 extern "C" rad_status rad_store_destroy(rad_store* s) {
   if (!s) return RAD_ERR_NULL;
-  for (void* p : {(void*)s->values, (void*)s->indices, (void*)s->row_ptr, (void*)s->bucket_off, (void*)s->row_cnt,
+  for (void* p : {(void*)s->values, (void*)s->indices, (void*)s->row_ptr, (void*)s->bucket_off, (void*)s->row_cnt, (void*)s->mult,
                   (void*)s->bits, s->flags_external ? nullptr : (void*)s->overflow})
     if (p) (void)hipFree(p);
   delete s;
@@ -293,7 +299,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   } else {
     s->scale = (float)((double)s->cols / (double)s->k);
     s->capacity = R * s->k_pitch;
-    s->plan_rows_per_step = scheme == RAD_FIXEDK_SHARED ? 1 : s->rows;
+    s->plan_rows_per_step = (scheme == RAD_FIXEDK_SHARED || scheme == RAD_REPLACE_SHARED) ? 1 : s->rows;
   }
   auto alloc = [&](void** ptr, size_t bytes) -> bool {
     return hipMalloc(ptr, bytes ? bytes : 16) == hipSuccess;
@@ -306,7 +312,8 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
     if (!s->paired()) ok = ok && alloc((void**)&s->indices, n_idx * 2);
     ok = ok && alloc((void**)&s->row_ptr, (size_t)(R + 1) * 4);
     ok = ok && alloc((void**)&s->bucket_off, (size_t)steps * s->plan_rows_per_step * (s->nb + 1) * 2);
-    if (scheme == RAD_BERNOULLI) ok = ok && alloc((void**)&s->row_cnt, (size_t)R * 4);
+    if (s->counted_rows()) ok = ok && alloc((void**)&s->row_cnt, (size_t)R * 4);
+    if (s->replace()) ok = ok && alloc((void**)&s->mult, (size_t)steps * s->plan_rows_per_step * s->k * 2);
   }
   if (L->relu) {
     s->bits_pitch = (s->d_out + 31) / 32;
@@ -351,7 +358,7 @@ extern "C" rad_status rad_store_get_stats(rad_ctx* c, const rad_store* s, rad_st
     out->index_bytes = (uint64_t)s->steps * ((uint64_t)s->k * 2 + (uint64_t)(s->nb + 1) * 2);
   else
     out->index_bytes = (uint64_t)nnz * 2 + (uint64_t)R * (s->nb + 1) * 2 +
-                       (s->scheme == RAD_BERNOULLI ? (uint64_t)(R + 1) * 4 : 0);
+                       (s->counted_rows() ? (uint64_t)(R + 1) * 4 : 0);
   return RAD_OK;
 }
 
@@ -392,11 +399,13 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
       for (int j = 0; j < s->k; ++j) col[r * s->k + j] = idx[(size_t)(r / s->rows) * s->k + j];
   } else if (s->paired()) {
     // the bucket of an entry follows from its position in the row
-    std::vector<uint16_t> bo((size_t)R * (s->nb + 1));
+    std::vector<uint16_t> bo((size_t)s->steps * s->plan_rows_per_step * (s->nb + 1));
     HIP_TRY(c, hipMemcpy(bo.data(), s->bucket_off, bo.size() * 2, hipMemcpyDeviceToHost));
     const uint32_t* ent = reinterpret_cast<const uint32_t*>(vraw.data());
     for (int64_t r = 0; r < R; ++r) {
-      const uint16_t* b = bo.data() + (size_t)r * (s->nb + 1);
+      // one plan row per store row, or per step when every row of the step shares the draw
+      const int64_t prow = s->plan_rows_per_step == s->rows ? r : r / s->rows;
+      const uint16_t* b = bo.data() + (size_t)prow * (s->nb + 1);
       for (int t = 0; t < s->nb; ++t)
         for (int64_t e = (int64_t)rp[(size_t)r] + b[t]; e < (int64_t)rp[(size_t)r] + b[t + 1] && e < nnz; ++e)
           col[e] = pair_col(ent[e], t);
@@ -445,10 +454,11 @@ static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, u
   a.bucket_off = s->bucket_off; a.nb = s->nb;
   a.row_cnt = s->row_cnt; a.row_ptr = s->row_ptr;
   a.max_seg = s->max_seg;
+  a.mult = s->mult;
   s->bitmap = bitmap;
   if (clear_max_seg) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(s->max_seg), 0u, 1, c->stream));
   HIP_TRY(c, timed(c, "plan", [&](const char**) { return launch_plan(a, c->stream); }));
-  if (s->scheme == RAD_BERNOULLI) {
+  if (s->counted_rows()) {
     HIP_TRY(c, timed(c, "row_scan", [&](const char**) {
       return launch_row_scan(s->row_cnt, s->row_ptr, s->steps * s->rows, s->capacity, s->overflow, c->stream);
     }));
@@ -713,8 +723,6 @@ struct rad_model {
   int ksize = 0, fc_in = 0;
   void* buf[3] = {nullptr, nullptr, nullptr};   // transient dense activations / gradients
   size_t elem() const { return dtype == kBF16 ? 2 : 4; }
-  // bf16 stores with per-entry draws keep (value, column) in one 32-bit entry
-  bool paired() const { return dtype == kBF16 && (scheme == kBernoulli || scheme == kFixedKPerExample); }
 };
 
 static rad_status model_share_flags(rad_ctx* c, rad_model* m);

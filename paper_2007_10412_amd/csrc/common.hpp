@@ -14,7 +14,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-enum Scheme : int { kExact = 0, kBernoulli = 1, kFixedKShared = 2, kFixedKPerExample = 3 };
+enum Scheme : int { kExact = 0, kBernoulli = 1, kFixedKShared = 2, kFixedKPerExample = 3, kReplaceShared = 4,
+                    kReplacePerExample = 5 };
 enum DType : int { kF32 = 0, kBF16 = 1 };
 
 // fp32 -> bf16 bits, round to nearest even (NaN payload is not preserved; the
@@ -48,6 +49,8 @@ struct StoreView {
   int bm_pitch;              // words per bitmap row
   int plan_row_stride;       // 1, or 0 when every row shares one plan row (shared scheme)
   int idx_shared;            // shared scheme: `indices` holds the k columns once (written by row 0)
+  const uint16_t* mult;      // with-replacement draws: how often each entry's column was drawn, [plan_rows][mult_pitch]
+  int mult_pitch;            //   in entry order of the row; null otherwise (every weight is 1)
   int shared_k;              // shared scheme: entries per row (rows are k rounded up to 8 apart); else 0
   int paired;                // bf16 per-entry draws: `values` holds 32-bit (value, column) entries, no `indices`
   float scale;

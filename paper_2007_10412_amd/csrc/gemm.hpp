@@ -491,7 +491,8 @@ template <typename ElemT, int BM, int BN> struct FwdEpiLds {
   static constexpr int CP = BN + VPL;
   static constexpr int NW = BN / 32;                      // keep words per tile row
   static constexpr int CT_BYTES = BM * CP * (int)sizeof(ElemT);
-  static constexpr int BYTES = CT_BYTES + BM * NW * 8;
+  static constexpr int TAB_BYTES = BM * NW * 8;           // per row and keep word: the word, position of its first entry
+  static constexpr int BYTES = CT_BYTES + TAB_BYTES + BM * 4;   // + first position of every row
 };
 
 // Forward epilogue.  The tile goes through LDS in the storage dtype, then every thread handles 16-byte
@@ -511,6 +512,7 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
   static_assert(BM <= kGemmThreads, "one thread per tile row builds the plan table");
   const int lane = threadIdx.x & 63;
   u32x2* const ptab = reinterpret_cast<u32x2*>(reinterpret_cast<unsigned char*>(ct) + E::CT_BYTES);
+  uint32_t* const rbase = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(ct) + E::CT_BYTES + E::TAB_BYTES);
 
   if (g.pack && threadIdx.x < BM) {
     const int r = threadIdx.x, row = m0 + r;
@@ -518,6 +520,7 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
 #pragma unroll
     for (int q = 0; q < NW; ++q) kw[q] = 0u;
     uint32_t pos = 0u;
+    rbase[r] = row < g.M ? g.next.row_ptr[row] : 0u;
     if (row < g.M) {
       const int prow = row * g.next.plan_row_stride;
       const uint32_t* bm_row = g.next.bitmap + (size_t)prow * g.next.bm_pitch;
@@ -588,7 +591,11 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
         const int e = __ffs(kb) - 1;
         kb &= kb - 1u;
         if ((int64_t)p < g.next.capacity) {
-          const float yv = get_elem(re + e) * g.next.scale;
+          // weight: the scale, times the draw count of the column for draws with replacement
+          const float wgt = g.next.mult
+              ? (float)g.next.mult[(size_t)(row * g.next.plan_row_stride) * g.next.mult_pitch + (p - rbase[r])] * g.next.scale
+              : g.next.scale;
+          const float yv = get_elem(re + e) * wgt;
           if (g.next.paired) {
             reinterpret_cast<uint32_t*>(g.next.values)[p] = pair_make(f32_to_bf16_bits(yv), col + e);
           } else {

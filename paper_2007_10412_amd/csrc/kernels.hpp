@@ -21,6 +21,7 @@ struct PlanArgs {
   uint32_t* row_cnt;   // [plan_rows], Bernoulli only
   uint32_t* row_ptr;   // [steps*rows + 1], written here for the fixed-k schemes
   int* max_seg;        // running maximum of entries per (row, 256-column bucket)
+  uint16_t* mult;      // with-replacement draws: draw counts of the kept columns, [plan_rows][k] in entry order
 };
 
 hipError_t launch_plan(const PlanArgs& a, hipStream_t st);

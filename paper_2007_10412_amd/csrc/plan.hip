@@ -74,8 +74,11 @@ __device__ __forceinline__ void finish_row(const PlanArgs& a, int prow, const ui
   if (tid < a.nb) bo[tid] = (uint16_t)off;
   if (tid == 0) bo[a.nb] = (uint16_t)total;
 
-  if (a.scheme == kBernoulli) {
+  if (a.scheme == kBernoulli || a.scheme == kReplacePerExample) {
     if (tid == 0) a.row_cnt[prow] = (uint32_t)total;
+  } else if (a.scheme == kReplaceShared) {       // every store row of this step holds the same entries
+    const int r0 = prow * a.rows_per_step;
+    for (int r = tid; r < a.rows_per_step; r += kPlanThreads) a.row_cnt[r0 + r] = (uint32_t)total;
   } else if (a.scheme == kFixedKPerExample) {
     if (tid == 0) {
       a.row_ptr[prow] = (uint32_t)((uint64_t)prow * a.k);
@@ -256,6 +259,54 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fixedk_kernel(PlanArgs a) {
   finish_row(a, prow, s_bm, s_scan);
 }
 
+// With replacement (Section 3.2, the matrix P as printed): draw s of the row maps its key to the column
+// floor(key * cols / 2^32).  The draws are counted per column in LDS (16-bit counters: a count cannot
+// exceed k <= cols <= 16384); a column with a non-zero count is kept once, and its count goes to
+// mult[row][entry] in the entry order of the row, so that whoever packs the row scales entry e by
+// mult[e] * cols/k.
+__global__ __launch_bounds__(kPlanThreads) void plan_replace_kernel(PlanArgs a) {
+  __shared__ uint32_t s_bm[512];       // cols <= 16384
+  __shared__ uint32_t s_cnt[8192];     // two 16-bit counters per word
+  __shared__ int s_scan[8];
+  const int tid = threadIdx.x;
+  const int prow = blockIdx.x;
+  int t_step, b;
+  if (a.scheme == kReplaceShared) { t_step = prow; b = 0; }
+  else { t_step = prow / a.rows_per_step; b = prow % a.rows_per_step; }
+  const uint32_t step = a.step0 + (uint32_t)t_step;
+  const uint64_t f0 = (uint64_t)b * (uint64_t)a.k;       // flat index of the row's first draw
+  const uint64_t q0 = f0 >> 2;
+  const int lead = (int)(f0 & 3);
+  const int nq = (int)(((f0 + (uint64_t)a.k - 1) >> 2) - q0) + 1;
+
+  for (int w = tid; w < (a.cols + 1) / 2; w += kPlanThreads) s_cnt[w] = 0;
+  for (int w = tid; w < a.bm_pitch; w += kPlanThreads) s_bm[w] = 0;
+  __syncthreads();
+  for (int qi = tid; qi < nq; qi += kPlanThreads) {
+    const u32x4 k4 = element_quad_keys(q0 + (uint64_t)qi, a.stream_id, step, a.seed_lo, a.seed_hi);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int sdraw = qi * 4 + w - lead;
+      if (sdraw >= 0 && sdraw < a.k) {
+        const uint32_t j = (uint32_t)(((uint64_t)k4[w] * (uint64_t)(uint32_t)a.cols) >> 32);
+        atomicAdd(&s_cnt[j >> 1], 1u << (16 * (j & 1u)));
+        atomicOr(&s_bm[j >> 5], 1u << (j & 31u));          // keep bitmap: the column was drawn at least once
+      }
+    }
+  }
+  __syncthreads();
+  auto count_of = [&](int j) { return (s_cnt[j >> 1] >> (16 * (j & 1))) & 0xFFFFu; };
+  // entry index of the first kept column of words 2t, 2t+1, then the counts in entry order
+  const int w0 = 2 * tid, w1 = 2 * tid + 1;
+  const uint32_t b0 = w0 < a.bm_pitch ? s_bm[w0] : 0u, b1 = w1 < a.bm_pitch ? s_bm[w1] : 0u;
+  int tot;
+  int rel = block_excl_scan(__popc(b0) + __popc(b1), &tot, s_scan);
+  uint16_t* mrow = a.mult + (size_t)prow * a.k;
+  for (uint32_t bits = b0; bits; bits &= bits - 1) mrow[rel++] = (uint16_t)count_of(w0 * 32 + (__ffs(bits) - 1));
+  for (uint32_t bits = b1; bits; bits &= bits - 1) mrow[rel++] = (uint16_t)count_of(w1 * 32 + (__ffs(bits) - 1));
+  finish_row(a, prow, s_bm, s_scan);
+}
+
 // row_ptr = exclusive scan of row_cnt (Bernoulli).  One block; flags overflow.
 __global__ __launch_bounds__(1024) void row_scan_kernel(const uint32_t* __restrict__ row_cnt,
                                                         uint32_t* __restrict__ row_ptr, int rows,
@@ -351,10 +402,12 @@ __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ x, Stor
         if ((nib[u] >> e) & 1u) {
           const int64_t pos = base + rel;
           if (pos < s.capacity) {
+            // weight of the entry: the scale, times the draw count of its column for draws with replacement
+            const float wgt = s.mult ? (float)s.mult[(size_t)prow * s.mult_pitch + rel] * s.scale : s.scale;
             if (s.paired) {
-              reinterpret_cast<uint32_t*>(s.values)[pos] = pair_make(f32_to_bf16_bits(v[u][e] * s.scale), j0 + e);
+              reinterpret_cast<uint32_t*>(s.values)[pos] = pair_make(f32_to_bf16_bits(v[u][e] * wgt), j0 + e);
             } else {
-              store_from_f32(vals + pos, v[u][e] * s.scale);
+              store_from_f32(vals + pos, v[u][e] * wgt);
               if (!s.idx_shared) s.indices[pos] = (uint16_t)(j0 + e);
               else if (row == 0) s.indices[rel] = (uint16_t)(j0 + e);
             }
@@ -408,6 +461,11 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t st) {
   if (a.cols < 1 || a.cols > 65535) return hipErrorInvalidValue;
   if (a.scheme == kBernoulli) {
     hipLaunchKernelGGL(plan_bernoulli_kernel, grid, block, 0, st, a);
+    return hipGetLastError();
+  }
+  if (a.scheme == kReplaceShared || a.scheme == kReplacePerExample) {
+    if (a.cols > 16384 || !a.mult) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(plan_replace_kernel, grid, block, 0, st, a);
     return hipGetLastError();
   }
   // rows start on a Philox call boundary when cols is a multiple of 4
