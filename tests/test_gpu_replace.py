@@ -125,3 +125,29 @@ def test_unbiased_over_seeds(ctx):
     var_cf = (D - 1) / k * (x.astype(np.float64) ** 2).T @ dy.astype(np.float64) ** 2
     err = np.linalg.norm(acc / S - exact)
     assert 0 < err < 4 * np.sqrt(var_cf.sum() / S)
+
+
+@pytest.mark.parametrize("scheme", [4, 5])
+def test_cnn_small(ctx, scheme):
+    from paper_2007_10412_amd import synth
+    from tests.test_gpu_cnn import run_cnn
+    ch, pool = (3, 8, 12, 16), (0, 1, 1)
+    d = synth.cnn(seed=7, batch=6, channels=ch, pool=pool, ksize=3, hw=16, classes=10)
+    run_cnn(ctx, d, ch, pool, 3, 16, 10, scheme, 0.25, seed=3)
+
+
+@pytest.mark.parametrize("scheme", [4, 5])
+def test_rnn_small(ctx, scheme):
+    """A multi-step store: the draw counts of every time step are written by one plan launch."""
+    from paper_2007_10412_amd import synth
+    from tests.test_gpu_rnn import run_rnn
+    d = synth.rnn(seed=3, batch=20, T=9, d_input=1, hidden=96, classes=10, identity=False)
+    run_rnn(ctx, d, scheme, 0.25, seed=8)
+
+
+def test_config4_full_with_replacement(ctx):
+    """Config 4 at full size with the paper's own draw, every output compared."""
+    from paper_2007_10412_amd import binding as B, synth
+    dims = (4096, 4096, 4096, 1000)
+    data = synth.mlp(seed=1234, batch=4096, dims=dims, pixels=False, bf16=True)
+    run_mlp(ctx, data, dims, 5, 0.1, seed=1000, dtype=B.RAD_BF16, has_bias=False)
