@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fixedk_kernel(PlanArgs a) {
 // mult[e] * cols/k.
 __global__ __launch_bounds__(kPlanThreads) void plan_replace_kernel(PlanArgs a) {
   __shared__ uint32_t s_bm[512];       // cols <= 16384
-  __shared__ uint32_t s_cnt[8192];     // two 16-bit counters per word
+  extern __shared__ uint32_t s_cnt[];  // two 16-bit counters per word: (cols + 1) / 2 words, sized at launch
   __shared__ int s_scan[8];
   const int tid = threadIdx.x;
   const int prow = blockIdx.x;
@@ -465,7 +465,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t st) {
   }
   if (a.scheme == kReplaceShared || a.scheme == kReplacePerExample) {
     if (a.cols > 16384 || !a.mult) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(plan_replace_kernel, grid, block, 0, st, a);
+    hipLaunchKernelGGL(plan_replace_kernel, grid, block, (size_t)((a.cols + 1) / 2) * 4, st, a);
     return hipGetLastError();
   }
   // rows start on a Philox call boundary when cols is a multiple of 4
