@@ -24,6 +24,12 @@ independently, so coordinate j carries the weight m_j d/k, m_j being how often j
 was drawn (pins: multiplicities sum to k and are Binomial(k, 1/d); the
 closed-form variance ((d-1)/k) sum_b x^2 g^2; k = d does not give the baseline).
 
+The projection scheme is the other P of Section 3.2 / Appendix "Random
+projections for RAD": P = R R^T / k with R [d, k] independent signs, so the
+store is z = x R / sqrt(k) (k numbers per row, no indices) and the backward
+pass uses x~ = z R^T / sqrt(k) (pins: E[P] = I, the closed-form variance
+(|dW[:, n]|^2 - dW[j, n]^2) / k, sign balance and independence).
+
 Pins (tests/test_oracle_*.py): Philox against PyTorch's own Philox4_32 engine;
 k = ceil(p d) against the eight worked values of Appendix A; byte accounting
 against Appendix A and Table 1; p = 1 against torch autograd; mean and variance
@@ -45,6 +51,7 @@ FIXEDK_SHARED = 2       # "same sample": one k-subset for the whole minibatch
 FIXEDK_PER_EXAMPLE = 3  # "different sample": a k-subset per minibatch element
 REPLACE_SHARED = 4      # k draws WITH replacement, one set for the whole minibatch
 REPLACE_PER_EXAMPLE = 5  # k draws WITH replacement per minibatch element
+PROJECT_SHARED = 6      # "project": x R / sqrt(k) with one Rademacher matrix R [d, k]
 
 F32 = 0
 BF16 = 1
@@ -159,6 +166,33 @@ def multiplicity(scheme, p, seed, stream_id, step, rows, d):
     return m
 
 
+def rademacher_matrix(p, seed, stream_id, step, d):
+    """R [d, k] with entries +1 / -1 (Appendix, random projections: a matrix of
+    independent Rademacher variables).  Entry (j, s) takes bit (f mod 32) of
+    the key of flat index floor(f / 32), f = j k + s, in the element_keys
+    addressing; a clear bit is +1, a set bit -1.
+    """
+    k = fixed_k(p, d)
+    n = d * k
+    words = element_keys(seed, stream_id, step, 0, (n + 31) // 32)
+    f = np.arange(n, dtype=np.int64)
+    bit = (words[f >> 5] >> (f & 31).astype(np.uint32)) & np.uint32(1)
+    return (1.0 - 2.0 * bit.astype(np.float64)).reshape(d, k)
+
+
+def project_store(x, p, seed, stream_id, step, dtype=F32):
+    """z = storage(x R * fp32(1/sqrt(k))) [rows, k] and the backward operand
+    x~ = z R^T / sqrt(k) [rows, d] (fp64), so that x~ = x P with P = R R^T / k."""
+    x = np.asarray(x, dtype=np.float32)
+    d = x.shape[1]
+    R = rademacher_matrix(p, seed, stream_id, step, d)
+    k = R.shape[1]
+    inv = np.float64(np.float32(1.0 / math.sqrt(k)))
+    z = to_storage((x.astype(np.float64) @ R) * inv, dtype)
+    xt = (z.astype(np.float64) @ R.T) * inv
+    return z, xt
+
+
 def keep_mask(scheme, p, seed, stream_id, step, rows, d):
     """Boolean [rows, d]: which entries of the sampled tensor are stored.
 
@@ -222,6 +256,13 @@ def sample_pack(x, scheme, p, seed, stream_id, step, dtype=F32):
     """
     x = np.asarray(x, dtype=np.float32)
     rows, d = x.shape
+    if scheme == PROJECT_SHARED:
+        # the store is the dense projection z: listed as k "columns" 0..k-1 per row
+        z, xt = project_store(x, p, seed, stream_id, step, dtype)
+        k = z.shape[1]
+        row_ptr = np.arange(rows + 1, dtype=np.int64) * k
+        col = np.tile(np.arange(k, dtype=np.int32), rows)
+        return row_ptr, col, z.reshape(-1), xt
     scale = sample_scale(scheme, p, d)
     if scheme in (REPLACE_SHARED, REPLACE_PER_EXAMPLE):
         # weight of coordinate j is m_j d/k: the fp32 product of the count and the fp32 scale, then one fp32
