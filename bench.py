@@ -35,7 +35,8 @@ WORKLOADS = {
     "mlp784_f32": ("f32", 150, (784, 300, 300, 10), True, True),
 }
 SCHEMES = {"per_example": 3, "shared": 2, "bernoulli": 1, "exact": 0,
-           "replace_per_example": 5, "replace_shared": 4}      # the last two draw with replacement
+           "replace_per_example": 5, "replace_shared": 4,      # draws with replacement
+           "project": 6}                                       # Rademacher projection, one R per layer and step
 
 
 def main():
@@ -224,7 +225,8 @@ def config4_variants(B, ctx, torch, data, dims, batch):
     grads = [torch.empty(w.shape, device="cuda", dtype=torch.float32) for w in data["Ws"]]
     x = torch.from_numpy(data["x"]).cuda().to(torch.bfloat16).contiguous()
     labels = torch.from_numpy(data["labels"]).cuda()
-    for name, scheme in (("per_example", 3), ("shared", 2), ("replace_per_example", 5), ("replace_shared", 4)):
+    for name, scheme in (("per_example", 3), ("shared", 2), ("replace_per_example", 5), ("replace_shared", 4),
+                         ("project", 6)):
         for p in ((0.5, 0.1, 0.02) if scheme in (2, 3) else (0.1,)):
             model = B.rad_model_create_mlp(ctx, B.RAD_BF16, batch, list(dims), False, scheme, p)
             for i in range(3):

@@ -53,14 +53,21 @@ typedef enum { RAD_F32 = 0, RAD_BF16 = 1 } rad_dtype; /* accumulation is always 
  * the key of flat index b k + s, or s for SHARED, to floor(key d_in / 2^32));
  * a coordinate drawn m times is stored once with the weight m d_in/k, so a
  * row holds between 1 and k entries.  Their stores are always kept as
- * per-row (value, column) lists. */
+ * per-row (value, column) lists.  PROJECT_SHARED is the other P of Section 3.2
+ * (Appendix, "Random projections for RAD"): P = R R^T / k with R [d_in, k] a
+ * matrix of independent signs drawn once per layer and step (entry (j, s) is
+ * bit (j k + s) of the key stream; clear = +1).  The store is the dense
+ * z = x R / sqrt(k), k numbers per row and no indices; dW is
+ * R (z^T g) / sqrt(k), with R regenerated from the sampling parameters.
+ * Linear layers and MLP models only. */
 typedef enum {
   RAD_EXACT = 0,
   RAD_BERNOULLI = 1,
   RAD_FIXEDK_SHARED = 2,
   RAD_FIXEDK_PER_EXAMPLE = 3,
   RAD_REPLACE_SHARED = 4,
-  RAD_REPLACE_PER_EXAMPLE = 5
+  RAD_REPLACE_PER_EXAMPLE = 5,
+  RAD_PROJECT_SHARED = 6
 } rad_scheme;
 
 typedef enum { RAD_LINEAR = 0, RAD_CONV2D = 1 } rad_kind;

@@ -27,12 +27,13 @@ struct rad_ctx {
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
   // grow-only workspaces
-  void* ws[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-  size_t ws_bytes[6] = {0, 0, 0, 0, 0, 0};
+  void* ws[9] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  size_t ws_bytes[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
   float* loss_dev = nullptr;
 };
 
-enum { WS_BITMAP = 0, WS_DENSE = 1, WS_ROWLOSS = 2, WS_COLSUM = 3, WS_SPLITK = 4, WS_WT = 5 };
+enum { WS_BITMAP = 0, WS_DENSE = 1, WS_ROWLOSS = 2, WS_COLSUM = 3, WS_SPLITK = 4, WS_WT = 5, WS_PROJ_R = 6, WS_PROJ_T = 7,
+       WS_PROJ_TB = 8 };
 
 static const char* kNoCtx = "no context";
 
@@ -118,7 +119,7 @@ extern "C" rad_status rad_ctx_destroy(rad_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   for (auto& e : c->pool) (void)hipEventDestroy(e);
-  for (int i = 0; i < 6; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
+  for (int i = 0; i < 9; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
   if (c->loss_dev) (void)hipFree(c->loss_dev);
   delete c;
   return RAD_OK;
@@ -196,6 +197,9 @@ struct rad_store {
   uint32_t* row_ptr = nullptr;
   uint16_t* bucket_off = nullptr;
   uint32_t* row_cnt = nullptr;
+  uint64_t proj_seed = 0;         // projection scheme: the sampling parameters of the last forward, from which the
+  uint32_t proj_stream = 0, proj_step = 0;   //   backward pass regenerates R
+  bool proj_valid = false;
   uint16_t* mult = nullptr;       // with-replacement draws: draw counts, [steps * plan rows][k] in entry order
   uint32_t* bits = nullptr;
   uint32_t* bitmap = nullptr;     // transient, points into a context workspace after a plan
@@ -208,6 +212,8 @@ struct rad_store {
   // bf16 stores with per-entry draws keep (value, column) in one 32-bit entry
   bool paired() const { return dtype == kBF16 && (scheme == kBernoulli || scheme == kFixedKPerExample || replace()); }
   bool replace() const { return scheme == kReplaceShared || scheme == kReplacePerExample; }
+  bool project() const { return scheme == kProjectShared; }
+  bool compact() const { return scheme == kFixedKShared || project(); }   // values are [rows][k_pitch]
   // rows hold a number of entries that only the plan kernel knows
   bool counted_rows() const { return scheme == kBernoulli || replace(); }
   size_t bitmap_words() const { return (size_t)steps * plan_rows_per_step * bm_pitch; }
@@ -252,7 +258,7 @@ static rad_status check_layer(rad_ctx* c, const rad_layer* L) {
 }
 
 static rad_status check_scheme(rad_ctx* c, int scheme, double p) {
-  if (scheme < RAD_EXACT || scheme > RAD_REPLACE_PER_EXAMPLE) return fail(c, RAD_ERR_PARAM, "unknown sampling scheme");
+  if (scheme < RAD_EXACT || scheme > RAD_PROJECT_SHARED) return fail(c, RAD_ERR_PARAM, "unknown sampling scheme");
   if (!(p > 0.0) || p > 1.0) return fail(c, RAD_ERR_PARAM, "p must be in (0, 1]");
   return RAD_OK;
 }
@@ -274,7 +280,9 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   RAD_TRY(check_layer(c, L));
   RAD_TRY(check_scheme(c, scheme, p));
   if (steps < 1) return fail(c, RAD_ERR_SHAPE, "steps must be >= 1");
-  if (scheme != RAD_EXACT) {
+  if (scheme == RAD_PROJECT_SHARED && (steps != 1 || L->kind != RAD_LINEAR))
+    return fail(c, RAD_ERR_UNSUPPORTED, "the projection scheme serves single-step linear layers only");
+  if (scheme != RAD_EXACT && scheme != RAD_PROJECT_SHARED) {
     if (L->d_in > 65535) return fail(c, RAD_ERR_UNSUPPORTED, "sampled stores need d_in <= 65535 (16-bit indices)");
     if (L->d_in > plan_max_cols(scheme) || (scheme != RAD_BERNOULLI && L->d_in > 16376 && L->d_in % 4 != 0))
       return fail(c, RAD_ERR_UNSUPPORTED, "fixed-k sampling needs d_in <= 16384 (16376 unless a multiple of 4)");
@@ -285,7 +293,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   s->scheme = scheme; s->dtype = L->dtype; s->rows = (int)L->batch; s->cols = (int)L->d_in;
   s->d_out = (int)L->d_out; s->steps = steps; s->p = p;
   s->k = (int)rad_fixed_k(p, L->d_in);
-  s->k_pitch = scheme == RAD_FIXEDK_SHARED ? (s->k + 7) / 8 * 8 : s->k;
+  s->k_pitch = (scheme == RAD_FIXEDK_SHARED || scheme == RAD_PROJECT_SHARED) ? (s->k + 7) / 8 * 8 : s->k;
   s->nb = (s->cols + kBucket - 1) / kBucket;
   s->bm_pitch = (s->cols + 31) / 32;
   const int64_t R = (int64_t)steps * s->rows;
@@ -296,6 +304,10 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
     double cap = std::ceil((double)n * p + 8.0 * std::sqrt((double)n * p * (1.0 - p))) + 64.0;
     s->capacity = cap > (double)n ? n : (int64_t)cap;
     s->plan_rows_per_step = s->rows;
+  } else if (scheme == RAD_PROJECT_SHARED) {
+    s->scale = (float)(1.0 / std::sqrt((double)s->k));
+    s->capacity = R * s->k_pitch;
+    s->plan_rows_per_step = 0;
   } else {
     s->scale = (float)((double)s->cols / (double)s->k);
     s->capacity = R * s->k_pitch;
@@ -307,7 +319,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   bool ok = alloc(&s->values, s->paired() ? (size_t)(s->capacity + kPairPad) * 4 : (size_t)s->capacity * s->elem());
   ok = ok && alloc((void**)&s->overflow, 2 * sizeof(int));   // [0] capacity overflow flag, [1] longest bucket segment
   s->max_seg = s->overflow ? s->overflow + 1 : nullptr;
-  if (scheme != RAD_EXACT) {
+  if (scheme != RAD_EXACT && scheme != RAD_PROJECT_SHARED) {
     const size_t n_idx = scheme == RAD_FIXEDK_SHARED ? (size_t)steps * s->k : (size_t)s->capacity;
     if (!s->paired()) ok = ok && alloc((void**)&s->indices, n_idx * 2);
     ok = ok && alloc((void**)&s->row_ptr, (size_t)(R + 1) * 4);
@@ -332,7 +344,7 @@ static rad_status store_nnz(rad_ctx* c, const rad_store* s, int64_t* nnz) {
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   if (s->scheme == RAD_EXACT) { *nnz = s->capacity; return RAD_OK; }
   // shared: k entries per row by construction (the rows of the compact layout may be padded apart)
-  if (s->scheme == RAD_FIXEDK_SHARED) { *nnz = (int64_t)s->steps * s->rows * s->k; return RAD_OK; }
+  if (s->compact()) { *nnz = (int64_t)s->steps * s->rows * s->k; return RAD_OK; }
   uint32_t last = 0;
   HIP_TRY(c, hipMemcpy(&last, s->row_ptr + (size_t)s->steps * s->rows, 4, hipMemcpyDeviceToHost));
   int ov = 0;
@@ -353,7 +365,7 @@ extern "C" rad_status rad_store_get_stats(rad_ctx* c, const rad_store* s, rad_st
   out->value_bytes = (uint64_t)nnz * s->elem();   // entries; the shared scheme's row padding (< 8 per row) is not counted
   out->dense_bytes = (uint64_t)R * s->cols * s->elem();
   out->bit_bytes = s->bits ? (uint64_t)R * s->bits_pitch * 4 : 0;
-  if (s->scheme == RAD_EXACT) out->index_bytes = 0;
+  if (s->scheme == RAD_EXACT || s->project()) out->index_bytes = 0;
   else if (s->scheme == RAD_FIXEDK_SHARED)
     out->index_bytes = (uint64_t)s->steps * ((uint64_t)s->k * 2 + (uint64_t)(s->nb + 1) * 2);
   else
@@ -370,7 +382,7 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
   RAD_TRY(store_nnz(c, s, &nnz));
   if (nnz > capacity) return fail(c, RAD_ERR_CAPACITY, "export buffers too small");
   const int64_t R = (int64_t)s->steps * s->rows;
-  const bool shared = s->scheme == RAD_FIXEDK_SHARED;
+  const bool shared = s->compact();
   const int64_t n_raw = shared ? R * s->k_pitch : nnz;          // entries held, padding included
   std::vector<unsigned char> vraw((size_t)n_raw * (s->paired() ? 4 : s->elem()));
   if (n_raw) HIP_TRY(c, hipMemcpy(vraw.data(), s->values, vraw.size(), hipMemcpyDeviceToHost));
@@ -387,6 +399,11 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
   if (s->scheme == RAD_EXACT) {
     for (int64_t r = 0; r <= R; ++r) row_ptr[r] = r * s->cols;
     for (int64_t i = 0; i < nnz; ++i) col[i] = (int32_t)(i % s->cols);
+    return RAD_OK;
+  }
+  if (s->project()) {                      // the k numbers of a row are listed as "columns" 0 .. k-1
+    for (int64_t r = 0; r <= R; ++r) row_ptr[r] = r * s->k;
+    for (int64_t i = 0; i < nnz; ++i) col[i] = (int32_t)(i % s->k);
     return RAD_OK;
   }
   std::vector<uint32_t> rp((size_t)R + 1);
@@ -440,7 +457,7 @@ extern "C" rad_status rad_store_import_bits(rad_ctx* c, rad_store* s, const uint
 // clear_max_seg = false when the caller has already zeroed the segment maxima of all its stores at once
 static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, uint32_t* bitmap,
                              bool clear_max_seg = true) {
-  if (s->scheme == RAD_EXACT) return RAD_OK;
+  if (s->scheme == RAD_EXACT || s->project()) return RAD_OK;
   PlanArgs a;
   a.seed_lo = (uint32_t)sm->seed; a.seed_hi = (uint32_t)(sm->seed >> 32);
   a.stream_id = sm->stream_id; a.step0 = sm->step;
@@ -486,6 +503,8 @@ static rad_status store_pack(rad_ctx* c, rad_store* s, const void* x, int slot) 
   return RAD_OK;
 }
 
+static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* sm, const void* x);
+
 extern "C" rad_status rad_sample_pack(rad_ctx* c, const rad_sampling* sm, const void* x, rad_store* s,
                                       int32_t step_slot) {
   if (!c) return RAD_ERR_NULL;
@@ -493,6 +512,7 @@ extern "C" rad_status rad_sample_pack(rad_ctx* c, const rad_sampling* sm, const 
   RAD_TRY(check_sampling(c, sm, s));
   if (step_slot < 0 || step_slot >= s->steps) return fail(c, RAD_ERR_SHAPE, "step_slot out of range");
   if (s->steps != 1) return fail(c, RAD_ERR_UNSUPPORTED, "rad_sample_pack draws single-step stores only");
+  if (s->project()) return project_forward(c, s, sm, x);
   void* bm = nullptr;
   if (s->scheme != RAD_EXACT) RAD_TRY(ws_get(c, WS_BITMAP, s->bitmap_words() * 4, &bm));
   RAD_TRY(store_plan(c, s, sm, static_cast<uint32_t*>(bm)));
@@ -540,6 +560,86 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
   return run_gemm_call(c, dtype, kOpK, kOpMN, kEpiFwd, g);
 }
 
+// A k x N output gives few tiles when k is a small fraction of the layer width: split the K dimension (the
+// batch) over several workgroups per tile, which add their partial sums atomically into an output that the
+// caller has zeroed or is accumulating into (bf16 ring kernels only).
+static void split_k_for_few_tiles(GemmArgs* g) {
+  if (g->K < 512) return;
+  const int tiles = ((g->M + 127) / 128) * ((g->N + 127) / 128);
+  if (tiles >= 192) return;
+  int splits = (512 + tiles - 1) / tiles;
+  if (splits > 8) splits = 8;
+  int ks = ((g->K + splits - 1) / splits + 31) / 32 * 32;
+  if (ks < 256) ks = 256;
+  splits = (g->K + ks - 1) / ks;
+  if (splits > 1) { g->k_split = ks; g->k_splits = splits; }
+}
+
+// ---- projection scheme (Section 3.2, P = R R^T / k; Appendix "Random projections for RAD")
+// R [cols][k_pitch] and its transpose [k_pitch][cols] as +1 / -1 in the store's dtype, regenerated from the
+// sampling parameters whenever they are needed (they are never kept: that is the memory saving)
+static rad_status project_signs(rad_ctx* c, const rad_store* s, uint64_t seed, uint32_t stream_id, uint32_t step,
+                                void** Rm, void** Rt) {
+  const size_t bytes = (size_t)s->cols * s->k_pitch * s->elem();
+  void* base = nullptr;
+  RAD_TRY(ws_get(c, WS_PROJ_R, 2 * bytes, &base));
+  HIP_TRY(c, timed(c, "fill", [&](const char**) {
+    return launch_fill_u32(static_cast<uint32_t*>(base), 0u, (int64_t)(2 * bytes / 4), c->stream);
+  }));
+  *Rm = base; *Rt = static_cast<char*>(base) + bytes;
+  HIP_TRY(c, timed(c, "sign_matrix", [&](const char**) {
+    return launch_sign_matrix(*Rm, *Rt, s->dtype, s->cols, s->k, s->k_pitch, (uint32_t)seed, (uint32_t)(seed >> 32),
+                              stream_id, step, c->stream);
+  }));
+  return RAD_OK;
+}
+
+// store <- z = x R / sqrt(k): one more forward-family GEMM per layer
+static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* sm, const void* x) {
+  void *Rm = nullptr, *Rt = nullptr;
+  RAD_TRY(project_signs(c, s, sm->seed, sm->stream_id, sm->step, &Rm, &Rt));
+  GemmArgs g = gemm_zero();
+  g.M = s->rows; g.N = s->k_pitch; g.K = s->cols;
+  g.A = x; g.lda = s->cols; g.B = Rm; g.ldb = s->k_pitch;
+  g.y = s->values; g.ldy = s->k_pitch; g.out_scale = s->scale;
+  RAD_TRY(run_gemm_call(c, s->dtype, kOpK, kOpMN, kEpiFwd, g));
+  s->proj_seed = sm->seed; s->proj_stream = sm->stream_id; s->proj_step = sm->step; s->proj_valid = true;
+  return RAD_OK;
+}
+
+// dW = beta dW + R (z^T g) / sqrt(k): the k x N product first, then R times it
+static rad_status project_dW(rad_ctx* c, const rad_store* s, const void* dy, int N, const uint32_t* bits,
+                             int bits_pitch, float* dW, int beta) {
+  if (!s->proj_valid) return fail(c, RAD_ERR_PARAM, "the store holds no projection yet");
+  void *Rm = nullptr, *Rt = nullptr;
+  RAD_TRY(project_signs(c, s, s->proj_seed, s->proj_stream, s->proj_step, &Rm, &Rt));
+  void *T = nullptr, *Tb = nullptr;
+  RAD_TRY(ws_get(c, WS_PROJ_T, (size_t)s->k_pitch * N * 4, &T));
+  RAD_TRY(ws_get(c, WS_PROJ_TB, (size_t)s->k_pitch * N * s->elem(), &Tb));
+  GemmArgs g = gemm_zero();
+  g.M = s->k_pitch; g.N = N; g.K = s->rows;
+  g.A = s->values; g.lda = s->k_pitch;
+  g.B = dy; g.ldb = N; g.b_mask = bits; g.b_mask_pitch = bits_pitch;
+  g.C = T; g.ldc = N; g.beta = 0; g.c_dtype = kF32;
+  if (s->dtype == kBF16) split_k_for_few_tiles(&g);
+  if (g.k_splits > 1) {                    // partial sums are added atomically: start from zero
+    g.beta = 1;
+    HIP_TRY(c, timed(c, "fill", [&](const char**) {
+      return launch_fill_u32(static_cast<uint32_t*>(T), 0u, (int64_t)s->k_pitch * N, c->stream);
+    }));
+  }
+  RAD_TRY(run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g));
+  HIP_TRY(c, timed(c, "scale_cast", [&](const char**) {
+    return launch_scale_cast(static_cast<const float*>(T), Tb, s->dtype, (int64_t)s->k_pitch * N, s->scale, c->stream);
+  }));
+  GemmArgs h = gemm_zero();
+  h.M = s->cols; h.N = N; h.K = s->k_pitch;
+  h.A = Rt; h.lda = s->cols;
+  h.B = Tb; h.ldb = N;
+  h.C = dW; h.ldc = N; h.beta = beta; h.c_dtype = kF32;
+  return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, h);
+}
+
 static int sparse_prefetch_for(const rad_store* s, int lanes_per_row) {
   const double pi = s->scheme == RAD_BERNOULLI ? s->p : (double)s->k / (double)s->cols;
   const double mean = pi * (s->cols < kBucket ? s->cols : kBucket);
@@ -549,6 +649,7 @@ static int sparse_prefetch_for(const rad_store* s, int lanes_per_row) {
 // dW = beta dW + store(slot)^T (dy masked by bits)
 static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* dy, int N, const uint32_t* bits,
                           int bits_pitch, float* dW, int beta) {
+  if (s->project()) return project_dW(c, s, dy, N, bits, bits_pitch, dW, beta);
   GemmArgs g = gemm_zero();
   g.N = N; g.K = s->rows;
   g.B = dy; g.ldb = N; g.b_mask = bits; g.b_mask_pitch = bits_pitch;
@@ -568,19 +669,7 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     g.A = static_cast<const char*>(s->values) + (size_t)slot * s->rows * s->k_pitch * s->elem(); g.lda = s->k_pitch;
     g.row_map = s->indices + (size_t)slot * s->k;
     g.beta = 1;
-    if (s->dtype == kBF16 && s->rows >= 512) {
-      // k rows of dW give few tiles: split the batch (the K dimension) over several workgroups per tile,
-      // which add their partial sums atomically into the zeroed / accumulating dW
-      const int tiles = ((g.M + 127) / 128) * ((N + 127) / 128);
-      if (tiles < 192) {
-        int splits = (512 + tiles - 1) / tiles;
-        if (splits > 8) splits = 8;
-        int ks = ((s->rows + splits - 1) / splits + 31) / 32 * 32;
-        if (ks < 256) ks = 256;
-        splits = (s->rows + ks - 1) / ks;
-        if (splits > 1) { g.k_split = ks; g.k_splits = splits; }
-      }
-    }
+    if (s->dtype == kBF16) split_k_for_few_tiles(&g);
     return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
   }
   g.M = s->cols;
@@ -846,14 +935,20 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   // forward: layer l consumes the dense activation of layer l-1 (kept only
   // until then) and leaves the packed sample of its own output for layer l+1
   RAD_TRY(model_clear_max_seg(c, m));
+  const bool proj = m->scheme == RAD_PROJECT_SHARED;
   rad_sampling s0 = *sm;
-  RAD_TRY(store_plan(c, m->stores[0], &s0, static_cast<uint32_t*>(bm), false));
-  RAD_TRY(store_pack(c, m->stores[0], x, 0));
+  if (!proj) {
+    RAD_TRY(store_plan(c, m->stores[0], &s0, static_cast<uint32_t*>(bm), false));
+    RAD_TRY(store_pack(c, m->stores[0], x, 0));
+  }
   const void* a_in = x;
   for (int l = 0; l < Lc; ++l) {
     const bool last = l == Lc - 1;
     StoreView nv; const StoreView* next = nullptr;
-    if (!last) {
+    if (proj) {          // the layer input is projected by a GEMM of its own; nothing is fused into the epilogue
+      rad_sampling sl = *sm; sl.stream_id = sm->stream_id + (uint32_t)l;
+      RAD_TRY(project_forward(c, m->stores[(size_t)l], &sl, a_in));
+    } else if (!last) {
       rad_store* sn = m->stores[(size_t)l + 1];
       if (sn->scheme != RAD_EXACT) {
         rad_sampling sl = *sm; sl.stream_id = sm->stream_id + (uint32_t)(l + 1);
@@ -898,6 +993,7 @@ extern "C" rad_status rad_model_create_rnn(rad_ctx* c, int64_t batch, int64_t T,
   *out = nullptr;
   RAD_TRY(check_scheme(c, scheme, p));
   if (batch < 1 || T < 1 || d_input < 1 || hidden < 1 || classes < 1) return fail(c, RAD_ERR_SHAPE, "bad RNN shape");
+  if (scheme == RAD_PROJECT_SHARED) return fail(c, RAD_ERR_UNSUPPORTED, "the projection scheme serves MLP models only");
   if (d_input > 8) return fail(c, RAD_ERR_UNSUPPORTED, "RNN input width above 8");
   if (T > (1 << 20)) return fail(c, RAD_ERR_SHAPE, "T above 2^20");
   rad_model* m = new rad_model();
@@ -1008,6 +1104,7 @@ extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t batch, int32_t n_
   RAD_TRY(check_scheme(c, scheme, p));
   if (n_conv < 1 || n_conv > 32 || batch < 1 || classes < 1 || ksize < 1 || (ksize & 1) == 0)
     return fail(c, RAD_ERR_SHAPE, "bad CNN shape (odd kernel size, at least one conv)");
+  if (scheme == RAD_PROJECT_SHARED) return fail(c, RAD_ERR_UNSUPPORTED, "the projection scheme serves MLP models only");
   rad_model* m = new rad_model();
   m->kind = kCnn; m->dtype = kF32; m->scheme = scheme; m->p = p; m->batch = batch; m->ksize = ksize;
   m->classes = classes; m->has_bias = 1;

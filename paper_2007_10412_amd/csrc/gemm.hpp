@@ -549,7 +549,7 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
       for (int e = 0; e < 16; ++e) {
         const int lrow = wm0 + i * 32 + acc_row(e, lane);
         const int row = m0 + lrow;
-        float h = acc[i][j][e] + bv;
+        float h = (g.out_scale != 0.f ? acc[i][j][e] * g.out_scale : acc[i][j][e]) + bv;
         if (g.u_n > 0 && row < g.M && col < g.N)
           for (int q = 0; q < g.u_n; ++q) h += g.u[(size_t)row * g.u_ld + q] * g.V[(size_t)q * g.N + col];
         if (g.relu) h = h > 0.f ? h : 0.f;

@@ -51,6 +51,7 @@ enum EpiKind : int {
 struct GemmArgs {
   int dry_run;                  // select the kernel and report its label, launch nothing
   int M, N, K;
+  float out_scale;              // forward epilogue: accumulators are multiplied by this first (0 = no scaling)
   int m_load;                   // 0, or > M: operand A is readable (as zeros) up to this many rows
   const void* A; int64_t lda;
   const void* B; int64_t ldb;
@@ -89,6 +90,12 @@ hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint3
                          const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
                          int beta, float* partial, int splits, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t st);
+// Rademacher matrix of the projection scheme: R [d][kp] and its transpose Rt [kp][d] in the given dtype, +1 / -1
+// from the key stream (entry (j, s) = bit j*k + s), zero in the padding columns s >= k (both must be zeroed first)
+hipError_t launch_sign_matrix(void* R, void* Rt, int dtype, int d, int k, int kp, uint32_t seed_lo, uint32_t seed_hi,
+                              uint32_t stream_id, uint32_t step, hipStream_t st);
+// out[i] = in[i] * scale, stored in the given dtype
+hipError_t launch_scale_cast(const float* in, void* out, int dtype, int64_t n, float scale, hipStream_t st);
 // out[i] (+)= sum over `splits` partial arrays of n elements
 hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st);
 // 2x2/stride-2 max pool over NCHW planes; arg packs the 2-bit window position (dy*2+dx of the first maximum)

@@ -1,4 +1,5 @@
 // Loss, bias-gradient and fill kernels of the RAD train step.
+#include "philox.hpp"
 #include "kernels.hpp"
 
 namespace rad {
@@ -315,6 +316,59 @@ hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* d
 hipError_t launch_flip_weights(const float* W, int Ci, int KH, int KW, int Co, float* Wt, hipStream_t st) {
   const int n = Ci * KH * KW * Co;
   hipLaunchKernelGGL(flip_weights_kernel, dim3((n + 255) / 256), dim3(256), 0, st, W, Ci, KH, KW, Co, Wt);
+  return hipGetLastError();
+}
+
+// One Philox call per thread = 128 consecutive entries of R in row-major [d][k] order.
+template <typename T>
+__global__ __launch_bounds__(256) void sign_matrix_kernel(T* __restrict__ R, T* __restrict__ Rt, int d, int k, int kp,
+                                                          uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
+                                                          uint32_t step) {
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t n = (int64_t)d * k;
+  int64_t f = q * 128;
+  if (f >= n) return;
+  const u32x4 k4 = element_quad_keys((uint64_t)q, stream_id, step, seed_lo, seed_hi);
+  int j = (int)(f / k), sc = (int)(f % k);
+  T plus, minus;
+  if (sizeof(T) == 2) { plus = (T)0x3F80u; minus = (T)0xBF80u; }              // bf16 bits of +1 and -1
+  else { const float a = 1.f, b = -1.f; plus = *reinterpret_cast<const T*>(&a); minus = *reinterpret_cast<const T*>(&b); }
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    for (int b = 0; b < 32 && f < n; ++b, ++f) {
+      const T v = ((k4[w] >> b) & 1u) ? minus : plus;
+      R[(size_t)j * kp + sc] = v;
+      Rt[(size_t)sc * d + j] = v;
+      if (++sc == k) { sc = 0; ++j; }
+    }
+}
+
+hipError_t launch_sign_matrix(void* R, void* Rt, int dtype, int d, int k, int kp, uint32_t seed_lo, uint32_t seed_hi,
+                              uint32_t stream_id, uint32_t step, hipStream_t st) {
+  const int64_t calls = ((int64_t)d * k + 127) / 128;
+  dim3 grid((unsigned)((calls + 255) / 256)), block(256);
+  if (dtype == kF32)
+    hipLaunchKernelGGL(sign_matrix_kernel<uint32_t>, grid, block, 0, st, (uint32_t*)R, (uint32_t*)Rt, d, k, kp, seed_lo,
+                       seed_hi, stream_id, step);
+  else
+    hipLaunchKernelGGL(sign_matrix_kernel<uint16_t>, grid, block, 0, st, (uint16_t*)R, (uint16_t*)Rt, d, k, kp, seed_lo,
+                       seed_hi, stream_id, step);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void scale_cast_kernel(const float* __restrict__ in, void* __restrict__ out, int bf16,
+                                                         int64_t n, float scale) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const float v = in[i] * scale;
+  if (bf16) reinterpret_cast<uint16_t*>(out)[i] = f32_to_bf16_bits(v);
+  else reinterpret_cast<float*>(out)[i] = v;
+}
+
+hipError_t launch_scale_cast(const float* in, void* out, int dtype, int64_t n, float scale, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(scale_cast_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, in, out, dtype == kBF16 ? 1 : 0,
+                     n, scale);
   return hipGetLastError();
 }
 
