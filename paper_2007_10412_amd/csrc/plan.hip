@@ -420,6 +420,81 @@ __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ x, Stor
   }
 }
 
+// The same for rows that are whole 16-byte vectors: a wave packs 1024 consecutive columns at a time and the
+// work is organised by OUTPUT entry instead of by input column, so the cost per input element is a load and
+// an LDS store.  The raw span goes to LDS with contiguous 16-byte loads; lanes 0..31 fetch the span's 32
+// keep words and scan their popcounts; then output slot t finds its column by rank: a binary search for the
+// word that holds the t-th kept entry, then that word's (t - entries before it)-th set bit.  Consecutive
+// lanes write consecutive entries.  (Walking the set bits per input lane instead measured slower.)
+template <typename T>
+__global__ __launch_bounds__(256) void pack_span_kernel(const T* __restrict__ x, StoreView s) {
+  constexpr int kSpan = 1024;
+  constexpr int EPL = 16 / (int)sizeof(T);       // elements per 16-byte load
+  constexpr int NLD = kSpan / (64 * EPL);        // loads per lane and span
+  __shared__ __align__(16) T s_x[4][kSpan];
+  __shared__ uint32_t s_word[4][32];
+  __shared__ uint16_t s_cum[4][32];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  T* vals = reinterpret_cast<T*>(s.values);
+  const int nspan = (s.cols + kSpan - 1) / kSpan;
+  for (int row = blockIdx.x; row < s.rows; row += gridDim.x) {
+    const int prow = row * s.plan_row_stride;
+    const T* xr = x + (size_t)row * s.cols;
+    const uint32_t* bm = s.bitmap + (size_t)prow * s.bm_pitch;
+    const uint16_t* bo = s.bucket_off + (size_t)prow * (s.nb + 1);
+    const int64_t base = (int64_t)s.row_ptr[row];
+    for (int sp = w; sp < nspan; sp += 4) {
+      const int c0 = sp * kSpan;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int lc = (i * 64 + lane) * EPL;
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        if (c0 + lc < s.cols) raw = *reinterpret_cast<const u32x4*>(xr + c0 + lc);
+        *reinterpret_cast<u32x4*>(&s_x[w][lc]) = raw;
+      }
+      uint32_t word = 0u;
+      const int wg = c0 / 32 + lane;
+      if (lane < 32 && wg < s.bm_pitch) word = bm[wg];
+      const int cnt = __popc(word);
+      int incl = cnt;
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) {           // lanes 32..63 hold zero counts
+        const int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+      }
+      if (lane < 32) { s_word[w][lane] = word; s_cum[w][lane] = (uint16_t)(incl - cnt); }
+      const int total = __shfl(incl, 31);
+      const int rel0 = bo[c0 / kBucket];           // entries of the row before this span
+      __builtin_amdgcn_wave_barrier();
+      for (int t = lane; t < total; t += 64) {
+        int wi = 0;
+#pragma unroll
+        for (int step = 16; step > 0; step >>= 1)
+          if ((int)s_cum[w][wi + step] <= t) wi += step;
+        uint32_t wd = s_word[w][wi];
+        for (int r = t - (int)s_cum[w][wi]; r > 0; --r) wd &= wd - 1u;     // drop the lower kept entries of the word
+        const int lc = wi * 32 + (__ffs(wd) - 1);
+        const int col = c0 + lc;
+        const int rel = rel0 + t;
+        const int64_t pos = base + rel;
+        if (pos < s.capacity) {
+          // weight of the entry: the scale, times the draw count of its column for draws with replacement
+          const float wgt = s.mult ? (float)s.mult[(size_t)prow * s.mult_pitch + rel] * s.scale : s.scale;
+          const float val = load_as_f32(&s_x[w][lc]) * wgt;
+          if (s.paired) {
+            reinterpret_cast<uint32_t*>(s.values)[pos] = pair_make(f32_to_bf16_bits(val), col);
+          } else {
+            store_from_f32(vals + pos, val);
+            if (!s.idx_shared) s.indices[pos] = (uint16_t)col;
+            else if (row == 0) s.indices[rel] = (uint16_t)col;
+          }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();             // the wave's LDS area is reused by its next span
+    }
+  }
+}
+
 // One workgroup per store row: clear the dense row, then scatter the row's entries into it.
 template <typename T>
 __global__ __launch_bounds__(256) void unpack_kernel(StoreView s, T* __restrict__ dense) {
@@ -496,6 +571,12 @@ hipError_t launch_row_scan(const uint32_t* row_cnt, uint32_t* row_ptr, int rows,
 
 hipError_t launch_pack(const void* x, int dtype, const StoreView& s, hipStream_t st) {
   dim3 grid(s.rows), block(256);
+  const size_t row_bytes = (size_t)s.cols * (dtype == kF32 ? 4 : 2);
+  if (row_bytes % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {     // every row is whole 16-byte vectors
+    if (dtype == kF32) hipLaunchKernelGGL(pack_span_kernel<float>, grid, block, 0, st, (const float*)x, s);
+    else hipLaunchKernelGGL(pack_span_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)x, s);
+    return hipGetLastError();
+  }
   if (dtype == kF32)
     hipLaunchKernelGGL(pack_kernel<float>, grid, block, 0, st, (const float*)x, s);
   else
