@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS))
     ap.add_argument("--scheme", default="per_example", choices=sorted(SCHEMES))
     ap.add_argument("--p", type=float, default=0.1)
+    ap.add_argument("--index-free", action="store_true",
+                    help="stores keep values only; columns are drawn again in the backward pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the kernel breakdown and the pack stream")
     args = ap.parse_args()
@@ -67,6 +69,8 @@ def main():
 
     ctx = B.rad_ctx_create()
     model = B.rad_model_create_mlp(ctx, dtype, batch, list(dims), has_bias, scheme, p)
+    if args.index_free:
+        B.rad_model_set_index_free(ctx, model, True)
     params, grads = [], []
     for l in range(L):
         params.append(torch.from_numpy(data["Ws"][l]).cuda().to(tdt).contiguous())
@@ -166,7 +170,8 @@ def main():
         "dtype": dtype_name, "data": "synthetic",
         "config": {"workload": "%s: MLP %s, batch %d, %s sampling p=%g, softmax-CE, full fwd+bwd train step"
                    % (args.workload, "-".join(str(d) for d in dims), batch, args.scheme, p),
-                   "batch": batch, "dims": list(dims), "scheme": args.scheme, "p": p},
+                   "batch": batch, "dims": list(dims), "scheme": args.scheme, "p": p,
+                   "index_free": bool(args.index_free)},
         "loss": loss,
         "roofline": roofline,
         "dw_kernel": dw_kernel,
@@ -190,7 +195,8 @@ def main():
         for i in range(reps):
             step(10_000 + i)
         kern = {}
-        names = ["plan", "row_scan", "pack", "fwd", "dx", "dw_sparse", "dw_dense", "softmax_ce", "colsum", "fill"]
+        names = ["plan", "row_scan", "pack", "reindex", "sign_matrix", "scale_cast", "unpack", "fwd", "dx", "dw_sparse",
+                 "dw_dense", "dw_overflow", "softmax_ce", "colsum", "fill"]
         for nm in names:
             n, ms = B.rad_ctx_timing_read(ctx, nm)
             if n:
@@ -226,9 +232,12 @@ def config4_variants(B, ctx, torch, data, dims, batch):
     x = torch.from_numpy(data["x"]).cuda().to(torch.bfloat16).contiguous()
     labels = torch.from_numpy(data["labels"]).cuda()
     for name, scheme in (("per_example", 3), ("shared", 2), ("replace_per_example", 5), ("replace_shared", 4),
-                         ("project", 6)):
-        for p in ((0.5, 0.1, 0.02) if scheme in (2, 3) else (0.1,)):
+                         ("project", 6), ("per_example_index_free", 3)):
+        for p in ((0.5, 0.1, 0.02) if name in ("per_example", "shared") else
+                  (0.5, 0.1) if name.endswith("index_free") else (0.1,)):
             model = B.rad_model_create_mlp(ctx, B.RAD_BF16, batch, list(dims), False, scheme, p)
+            if name.endswith("index_free"):
+                B.rad_model_set_index_free(ctx, model, True)
             for i in range(3):
                 B.rad_train_step(ctx, model, B.make_sampling(scheme, p, 50 + i, 0, 0), x, labels, params, grads, False)
             torch.cuda.synchronize()
@@ -238,7 +247,12 @@ def config4_variants(B, ctx, torch, data, dims, batch):
                 B.rad_train_step(ctx, model, B.make_sampling(scheme, p, 60 + i, 0, 0), x, labels, params, grads, False)
             torch.cuda.synchronize()
             dt = (time.perf_counter() - t0) / steps
-            res["%s_p%g" % (name, p)] = {"ms_per_step": 1e3 * dt, "samples_per_s": batch / dt}
+            stored = 0
+            for l in range(len(dims) - 1):
+                st_ = B.rad_store_get_stats(ctx, B.rad_model_store(model, l))
+                stored += st_["value_bytes"] + st_["index_bytes"] + st_["bit_bytes"]
+            res["%s_p%g" % (name, p)] = {"ms_per_step": 1e3 * dt, "samples_per_s": batch / dt,
+                                         "stored_activation_bytes": stored}
             B.rad_model_destroy(model)
     return res
 

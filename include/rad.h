@@ -244,6 +244,14 @@ rad_status rad_model_create_cnn(rad_ctx* ctx, int64_t batch, int32_t n_conv, con
                                 int32_t classes, int32_t scheme, double p, rad_model** out);
 
 rad_status rad_model_destroy(rad_model* model);
+/* Index-free storage (MLP models; stores of the Bernoulli, per-example fixed-k and with-replacement
+ * schemes): only the values of the kept entries stay in the store, which is then the size the paper's
+ * accounting gives (Appendix A: k values per sampled row plus the ReLU bits).  The columns are a pure
+ * function of the sampling parameters, so the backward pass draws the keep sets again and rebuilds the
+ * (value, column) entries of one layer at a time in a context workspace.  Costs one more plan and one
+ * small kernel per layer and step.  Synchronises and reallocates; contents of the store are lost. */
+rad_status rad_store_set_index_free(rad_ctx* ctx, rad_store* store, int32_t on);
+rad_status rad_model_set_index_free(rad_ctx* ctx, rad_model* model, int32_t on);
 /* Number of stores and borrowed access to store l (for export and stats). */
 int32_t rad_model_num_stores(const rad_model* model);
 rad_store* rad_model_store(rad_model* model, int32_t l);

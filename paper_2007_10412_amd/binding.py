@@ -69,6 +69,8 @@ SIGNATURES = {
     "rad_model_destroy": (C.c_int, [P]),
     "rad_model_num_stores": (C.c_int32, [P]),
     "rad_model_store": (P, [P, C.c_int32]),
+    "rad_store_set_index_free": (C.c_int, [P, P, C.c_int32]),
+    "rad_model_set_index_free": (C.c_int, [P, P, C.c_int32]),
     "rad_model_logits": (P, [P]),
     "rad_model_export_pool_arg": (C.c_int, [P, P, C.c_int32, P]),
     "rad_train_step": (C.c_int, [P, P, C.POINTER(rad_sampling), P, P, C.POINTER(P), C.POINTER(P),
@@ -272,6 +274,14 @@ def rad_model_export_pool_arg(ctx, model, l, n):
     out = np.zeros(n, dtype=np.uint8)
     _check(ctx, lib().rad_model_export_pool_arg(ctx, model, l, out.ctypes.data))
     return out
+
+
+def rad_store_set_index_free(ctx, store, on=True):
+    _check(ctx, lib().rad_store_set_index_free(ctx, store, 1 if on else 0))
+
+
+def rad_model_set_index_free(ctx, model, on=True):
+    _check(ctx, lib().rad_model_set_index_free(ctx, model, 1 if on else 0))
 
 
 def rad_model_logits(model):

@@ -27,13 +27,13 @@ struct rad_ctx {
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
   // grow-only workspaces
-  void* ws[9] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-  size_t ws_bytes[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+  void* ws[10] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  size_t ws_bytes[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   float* loss_dev = nullptr;
 };
 
 enum { WS_BITMAP = 0, WS_DENSE = 1, WS_ROWLOSS = 2, WS_COLSUM = 3, WS_SPLITK = 4, WS_WT = 5, WS_PROJ_R = 6, WS_PROJ_T = 7,
-       WS_PROJ_TB = 8 };
+       WS_PROJ_TB = 8, WS_REINDEX = 9 };
 
 static const char* kNoCtx = "no context";
 
@@ -119,7 +119,7 @@ extern "C" rad_status rad_ctx_destroy(rad_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   for (auto& e : c->pool) (void)hipEventDestroy(e);
-  for (int i = 0; i < 9; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
+  for (int i = 0; i < 10; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
   if (c->loss_dev) (void)hipFree(c->loss_dev);
   delete c;
   return RAD_OK;
@@ -197,6 +197,9 @@ struct rad_store {
   uint32_t* row_ptr = nullptr;
   uint16_t* bucket_off = nullptr;
   uint32_t* row_cnt = nullptr;
+  bool index_free = false;        // keep values only; columns are drawn again before the backward pass
+  rad_sampling last_plan{};       // sampling parameters of the last plan (what an index-free store is rebuilt from)
+  bool planned = false;
   uint64_t proj_seed = 0;         // projection scheme: the sampling parameters of the last forward, from which the
   uint32_t proj_stream = 0, proj_step = 0;   //   backward pass regenerates R
   bool proj_valid = false;
@@ -210,7 +213,8 @@ struct rad_store {
   int plan_rows_per_step = 0;     // rows (per example / Bernoulli), 1 (shared), 0 (exact)
   size_t elem() const { return dtype == kBF16 ? 2 : 4; }
   // bf16 stores with per-entry draws keep (value, column) in one 32-bit entry
-  bool paired() const { return dtype == kBF16 && (scheme == kBernoulli || scheme == kFixedKPerExample || replace()); }
+  bool per_entry() const { return scheme == kBernoulli || scheme == kFixedKPerExample || replace(); }
+  bool paired() const { return dtype == kBF16 && per_entry() && !index_free; }
   bool replace() const { return scheme == kReplaceShared || scheme == kReplacePerExample; }
   bool project() const { return scheme == kProjectShared; }
   bool compact() const { return scheme == kFixedKShared || project(); }   // values are [rows][k_pitch]
@@ -369,10 +373,12 @@ extern "C" rad_status rad_store_get_stats(rad_ctx* c, const rad_store* s, rad_st
   else if (s->scheme == RAD_FIXEDK_SHARED)
     out->index_bytes = (uint64_t)s->steps * ((uint64_t)s->k * 2 + (uint64_t)(s->nb + 1) * 2);
   else
-    out->index_bytes = (uint64_t)nnz * 2 + (uint64_t)R * (s->nb + 1) * 2 +
+    out->index_bytes = (s->index_free ? 0 : (uint64_t)nnz * 2) + (uint64_t)R * (s->nb + 1) * 2 +
                        (s->counted_rows() ? (uint64_t)(R + 1) * 4 : 0);
   return RAD_OK;
 }
+
+static rad_status backward_view(rad_ctx* c, const rad_store* cs, int slot, StoreView* out);
 
 extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64_t* row_ptr, int32_t* col, float* val,
                                            int64_t capacity) {
@@ -383,12 +389,22 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
   if (nnz > capacity) return fail(c, RAD_ERR_CAPACITY, "export buffers too small");
   const int64_t R = (int64_t)s->steps * s->rows;
   const bool shared = s->compact();
+  // an index-free store is exported from the rebuild the backward pass would read
+  const void* vsrc = s->values;
+  const uint16_t* isrc = s->indices;
+  bool paired = s->paired();
+  if (s->index_free) {
+    StoreView bv;
+    RAD_TRY(backward_view(c, s, 0, &bv));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    vsrc = bv.values; isrc = bv.indices; paired = bv.paired != 0;
+  }
   const int64_t n_raw = shared ? R * s->k_pitch : nnz;          // entries held, padding included
-  std::vector<unsigned char> vraw((size_t)n_raw * (s->paired() ? 4 : s->elem()));
-  if (n_raw) HIP_TRY(c, hipMemcpy(vraw.data(), s->values, vraw.size(), hipMemcpyDeviceToHost));
+  std::vector<unsigned char> vraw((size_t)n_raw * (paired ? 4 : s->elem()));
+  if (n_raw) HIP_TRY(c, hipMemcpy(vraw.data(), vsrc, vraw.size(), hipMemcpyDeviceToHost));
   for (int64_t i = 0; i < nnz; ++i) {
     const int64_t src = shared ? (i / s->k) * s->k_pitch + i % s->k : i;
-    if (s->paired()) {
+    if (paired) {
       uint32_t u = reinterpret_cast<uint32_t*>(vraw.data())[src] & 0xFFFF0000u;
       std::memcpy(&val[i], &u, 4);
     } else if (s->dtype == kBF16) {
@@ -414,7 +430,7 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
     HIP_TRY(c, hipMemcpy(idx.data(), s->indices, idx.size() * 2, hipMemcpyDeviceToHost));
     for (int64_t r = 0; r < R; ++r)
       for (int j = 0; j < s->k; ++j) col[r * s->k + j] = idx[(size_t)(r / s->rows) * s->k + j];
-  } else if (s->paired()) {
+  } else if (paired) {
     // the bucket of an entry follows from its position in the row
     std::vector<uint16_t> bo((size_t)s->steps * s->plan_rows_per_step * (s->nb + 1));
     HIP_TRY(c, hipMemcpy(bo.data(), s->bucket_off, bo.size() * 2, hipMemcpyDeviceToHost));
@@ -429,7 +445,7 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
     }
   } else {
     std::vector<uint16_t> idx((size_t)nnz);
-    if (nnz) HIP_TRY(c, hipMemcpy(idx.data(), s->indices, idx.size() * 2, hipMemcpyDeviceToHost));
+    if (nnz) HIP_TRY(c, hipMemcpy(idx.data(), isrc, idx.size() * 2, hipMemcpyDeviceToHost));
     for (int64_t i = 0; i < nnz; ++i) col[i] = idx[(size_t)i];
   }
   return RAD_OK;
@@ -472,6 +488,7 @@ static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, u
   a.row_cnt = s->row_cnt; a.row_ptr = s->row_ptr;
   a.max_seg = s->max_seg;
   a.mult = s->mult;
+  s->last_plan = *sm; s->planned = true;
   s->bitmap = bitmap;
   if (clear_max_seg) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(s->max_seg), 0u, 1, c->stream));
   HIP_TRY(c, timed(c, "plan", [&](const char**) { return launch_plan(a, c->stream); }));
@@ -640,6 +657,50 @@ static rad_status project_dW(rad_ctx* c, const rad_store* s, const void* dy, int
   return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, h);
 }
 
+// What the backward kernels read: the store itself, or, for an index-free store, its transient rebuild: the
+// keep bitmap is drawn again from the recorded sampling parameters and the (value, column) entries (bf16) or
+// the columns (fp32) are written to a context workspace that lives until the next rebuild.
+static rad_status backward_view(rad_ctx* c, const rad_store* cs, int slot, StoreView* out) {
+  *out = store_view(cs, slot);
+  if (!cs->index_free) return RAD_OK;
+  rad_store* s = const_cast<rad_store*>(cs);       // the plan tables are rewritten with the values they hold
+  if (!s->planned) return fail(c, RAD_ERR_PARAM, "the index-free store has not been sampled yet");
+  void* bm = nullptr;
+  RAD_TRY(ws_get(c, WS_BITMAP, s->bitmap_words() * 4, &bm));
+  const rad_sampling sm = s->last_plan;
+  RAD_TRY(store_plan(c, s, &sm, static_cast<uint32_t*>(bm), false));
+  *out = store_view(s, slot);
+  void* ws = nullptr;
+  const size_t bytes = s->dtype == kBF16 ? (size_t)(s->capacity + kPairPad) * 4 : (size_t)s->capacity * 2;
+  RAD_TRY(ws_get(c, WS_REINDEX, bytes, &ws));
+  const StoreView v = *out;
+  HIP_TRY(c, timed(c, "reindex", [&](const char**) {
+    return launch_reindex(v, s->dtype, static_cast<uint32_t*>(ws), static_cast<uint16_t*>(ws), c->stream);
+  }));
+  if (s->dtype == kBF16) { out->values = ws; out->paired = 1; }
+  else out->indices = static_cast<uint16_t*>(ws);
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_store_set_index_free(rad_ctx* c, rad_store* s, int32_t on) {
+  if (!c) return RAD_ERR_NULL;
+  if (!s) return fail(c, RAD_ERR_NULL, "store is null");
+  if (!s->per_entry() || s->steps != 1)
+    return fail(c, RAD_ERR_UNSUPPORTED, "index-free storage serves single-step stores with per-entry columns");
+  if ((on != 0) == s->index_free) return RAD_OK;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (s->values) (void)hipFree(s->values);
+  if (s->indices) (void)hipFree(s->indices);
+  s->values = nullptr; s->indices = nullptr;
+  s->index_free = on != 0; s->planned = false;
+  const size_t vbytes = s->paired() ? (size_t)(s->capacity + kPairPad) * 4 : (size_t)s->capacity * s->elem();
+  if (hipMalloc(&s->values, vbytes ? vbytes : 16) != hipSuccess) return fail(c, RAD_ERR_DEVICE, "store allocation failed");
+  if (!s->paired() && !s->index_free &&
+      hipMalloc(reinterpret_cast<void**>(&s->indices), (size_t)s->capacity * 2 + 16) != hipSuccess)
+    return fail(c, RAD_ERR_DEVICE, "store allocation failed");
+  return RAD_OK;
+}
+
 static int sparse_prefetch_for(const rad_store* s, int lanes_per_row) {
   const double pi = s->scheme == RAD_BERNOULLI ? s->p : (double)s->k / (double)s->cols;
   const double mean = pi * (s->cols < kBucket ? s->cols : kBucket);
@@ -673,7 +734,7 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
   }
   g.M = s->cols;
-  g.sa = store_view(s, slot);
+  RAD_TRY(backward_view(c, s, slot, &g.sa));
   g.sparse_prefetch = sparse_prefetch_for(s, s->dtype == kBF16 ? 8 : 16);
   // 2 N flops per kept entry (expected number for Bernoulli draws)
   const double kept = s->scheme == RAD_BERNOULLI ? s->p * (double)s->rows * s->cols : (double)s->rows * s->k;
@@ -824,6 +885,15 @@ extern "C" rad_status rad_model_destroy(rad_model* m) {
     if (p) (void)hipFree(p);
   for (auto& cv : m->convs) if (cv.arg) (void)hipFree(cv.arg);
   delete m;
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_model_set_index_free(rad_ctx* c, rad_model* m, int32_t on) {
+  if (!c) return RAD_ERR_NULL;
+  if (!m) return fail(c, RAD_ERR_NULL, "model is null");
+  if (m->kind != kMlp) return fail(c, RAD_ERR_UNSUPPORTED, "index-free storage serves MLP models only");
+  for (rad_store* s : m->stores)
+    if (s->per_entry()) RAD_TRY(rad_store_set_index_free(c, s, on));
   return RAD_OK;
 }
 

@@ -600,7 +600,8 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
             reinterpret_cast<uint32_t*>(g.next.values)[p] = pair_make(f32_to_bf16_bits(yv), col + e);
           } else {
             put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv);
-            if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)(col + e);
+            if (!g.next.indices) {}
+            else if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)(col + e);
             else if (row == 0) g.next.indices[p - g.next.row_ptr[0]] = (uint16_t)(col + e);
           }
         }

@@ -408,7 +408,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ x, Stor
               reinterpret_cast<uint32_t*>(s.values)[pos] = pair_make(f32_to_bf16_bits(v[u][e] * wgt), j0 + e);
             } else {
               store_from_f32(vals + pos, v[u][e] * wgt);
-              if (!s.idx_shared) s.indices[pos] = (uint16_t)(j0 + e);
+              if (!s.indices) {}
+              else if (!s.idx_shared) s.indices[pos] = (uint16_t)(j0 + e);
               else if (row == 0) s.indices[rel] = (uint16_t)(j0 + e);
             }
           }
@@ -485,12 +486,65 @@ __global__ __launch_bounds__(256) void pack_span_kernel(const T* __restrict__ x,
             reinterpret_cast<uint32_t*>(s.values)[pos] = pair_make(f32_to_bf16_bits(val), col);
           } else {
             store_from_f32(vals + pos, val);
-            if (!s.idx_shared) s.indices[pos] = (uint16_t)col;
+            if (!s.indices) {}
+            else if (!s.idx_shared) s.indices[pos] = (uint16_t)col;
             else if (row == 0) s.indices[rel] = (uint16_t)col;
           }
         }
       }
       __builtin_amdgcn_wave_barrier();             // the wave's LDS area is reused by its next span
+    }
+  }
+}
+
+// Index-free stores keep only the values of the kept entries; before the backward pass the keep bitmap is
+// drawn again and this kernel rebuilds what the dW kernels read: for bf16 the 32-bit (value, column) entries,
+// for fp32 the 16-bit column of every entry.  Same walk as pack_span_kernel, without the input.
+template <typename T>
+__global__ __launch_bounds__(256) void reindex_span_kernel(StoreView s, uint32_t* __restrict__ out_pairs,
+                                                           uint16_t* __restrict__ out_idx) {
+  constexpr int kSpan = 1024;
+  __shared__ uint32_t s_word[4][32];
+  __shared__ uint16_t s_cum[4][32];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const T* vals = reinterpret_cast<const T*>(s.values);
+  const int nspan = (s.cols + kSpan - 1) / kSpan;
+  for (int row = blockIdx.x; row < s.rows; row += gridDim.x) {
+    const int prow = row * s.plan_row_stride;
+    const uint32_t* bm = s.bitmap + (size_t)prow * s.bm_pitch;
+    const uint16_t* bo = s.bucket_off + (size_t)prow * (s.nb + 1);
+    const int64_t base = (int64_t)s.row_ptr[row];
+    for (int sp = w; sp < nspan; sp += 4) {
+      const int c0 = sp * kSpan;
+      uint32_t word = 0u;
+      const int wg = c0 / 32 + lane;
+      if (lane < 32 && wg < s.bm_pitch) word = bm[wg];
+      const int cnt = __popc(word);
+      int incl = cnt;
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+      }
+      if (lane < 32) { s_word[w][lane] = word; s_cum[w][lane] = (uint16_t)(incl - cnt); }
+      const int total = __shfl(incl, 31);
+      const int rel0 = bo[c0 / kBucket];
+      __builtin_amdgcn_wave_barrier();
+      for (int t = lane; t < total; t += 64) {
+        int wi = 0;
+#pragma unroll
+        for (int step = 16; step > 0; step >>= 1)
+          if ((int)s_cum[w][wi + step] <= t) wi += step;
+        uint32_t wd = s_word[w][wi];
+        for (int r = t - (int)s_cum[w][wi]; r > 0; --r) wd &= wd - 1u;
+        const int col = c0 + wi * 32 + (__ffs(wd) - 1);
+        const int64_t pos = base + rel0 + t;
+        if (pos < s.capacity) {
+          if (sizeof(T) == 2) out_pairs[pos] = pair_make((uint32_t)reinterpret_cast<const uint16_t*>(vals)[pos], col);
+          else out_idx[pos] = (uint16_t)col;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
@@ -581,6 +635,13 @@ hipError_t launch_pack(const void* x, int dtype, const StoreView& s, hipStream_t
     hipLaunchKernelGGL(pack_kernel<float>, grid, block, 0, st, (const float*)x, s);
   else
     hipLaunchKernelGGL(pack_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)x, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_reindex(const StoreView& s, int dtype, uint32_t* out_pairs, uint16_t* out_idx, hipStream_t st) {
+  dim3 grid(s.rows), block(256);
+  if (dtype == kF32) hipLaunchKernelGGL(reindex_span_kernel<float>, grid, block, 0, st, s, out_pairs, out_idx);
+  else hipLaunchKernelGGL(reindex_span_kernel<uint16_t>, grid, block, 0, st, s, out_pairs, out_idx);
   return hipGetLastError();
 }
 
