@@ -56,19 +56,30 @@ struct StoreView {
   float scale;
 };
 
+// LDS layout of a 32-deep bf16 operand tile (64-byte rows of four 16-byte units): row r is kept at row
+// tile_row(r) and its unit kc at position kc ^ tile_swz(r).  The row permutation moves rows that are 8
+// apart (what the lanes of the transposing loader write in one instruction) into different 64-byte bank
+// windows, and the unit swizzle spreads the rest, so that the MFMA fragment reads (consecutive rows, one
+// unit), the 16-byte writes of the K-contiguous loader (4 rows x 4 units) and the 8-byte writes of the
+// transposing loader (rows 8 apart) all touch every LDS bank once per pass.
+__host__ __device__ __forceinline__ constexpr int tile_row(int r) { return r ^ ((r >> 3) & 3); }   // an involution
+__host__ __device__ __forceinline__ constexpr int tile_swz(int r) {
+  return (((r >> 2) & 1) | (((r >> 3) & 1) << 1)) ^ ((r >> 5) & 3);
+}
+
 // Entry of a paired bf16 store: the bf16 value bits in the high half; in the low half the column inside
-// its 256-column bucket, written as the byte offset of that column's 64-byte row in the XOR-swizzled
-// 32-deep LDS tile the dW kernel scatters into (column << 6, swizzle term of the row in bits 4..5).  The
-// kernel gets the LDS address of an entry with one XOR; everything else decodes the column back.
+// its 256-column bucket, written as the byte offset of that column's row in the LDS tile the dW kernel
+// scatters into (tile_row(column) << 6, swizzle term of the row in bits 4..5).  The kernel gets the LDS
+// address of an entry with one XOR; everything else decodes the column back.
 constexpr int kPairPad = 64;     // entries allocated past the capacity, so a lane may read beyond a segment
 __host__ __device__ __forceinline__ constexpr uint32_t pair_code(int col_in_bucket) {
-  return ((uint32_t)col_in_bucket << 6) | ((uint32_t)((col_in_bucket ^ (col_in_bucket >> 3)) & 3) << 4);
+  return ((uint32_t)tile_row(col_in_bucket) << 6) | ((uint32_t)tile_swz(col_in_bucket) << 4);
 }
 __host__ __device__ __forceinline__ constexpr uint32_t pair_make(uint32_t bf16_bits, int col) {
   return (bf16_bits << 16) | pair_code(col & (kBucket - 1));
 }
 __host__ __device__ __forceinline__ constexpr int pair_col(uint32_t entry, int bucket) {
-  return bucket * kBucket + (int)((entry >> 6) & (uint32_t)(kBucket - 1));
+  return bucket * kBucket + tile_row((int)((entry >> 6) & (uint32_t)(kBucket - 1)));
 }
 
 }  // namespace rad

@@ -38,8 +38,9 @@ template <int R, int BK> struct LdsF32 {
 template <int R, int BK> struct LdsBF16 {
   static constexpr int CH = BK / 8;             // 16-byte units per row
   static constexpr int BYTES = R * BK * 2;
+  static_assert(CH == 4, "the layout functions are written for 32-deep tiles");
   static __host__ __device__ __forceinline__ constexpr int unit(int row, int kc) {
-    return row * CH + (kc ^ ((row ^ (row >> 3)) & (CH - 1)));
+    return tile_row(row) * CH + (kc ^ tile_swz(row));
   }
 };
 // the paired store entries carry this layout's row offset

@@ -110,6 +110,13 @@ template <int R, int EMODE, bool MASKED, int NS> struct RingLoadMN {
   static_assert(RB * (kBK3 / KPT) == kGemmThreads, "one block per thread");
   static constexpr int kDsWrites = 8, kVmemReads = KPT * (MASKED ? 2 : 1);
   static constexpr int kValuCommit = 40, kValuFetch = 8;
+  // Which block a thread owns: the SUB threads that share one 16-byte unit (k sub-positions) are neighbours,
+  // the row blocks follow, and a wave fills unit column w; one write instruction then covers rows 8 apart
+  // at every k sub-position, which the tile layout spreads over all banks.
+  static constexpr int SUB = 8 / KPT;
+  static_assert(RB * SUB == 64, "a wave covers every row block at one unit column");
+  static __device__ __forceinline__ int block_rb() { return (threadIdx.x & 63) / SUB; }
+  static __device__ __forceinline__ int block_kq() { return (threadIdx.x >> 6) * SUB + (threadIdx.x & 63) % SUB; }
   u32x4 v[NS][KPT];                          // v[..][kk] = 8 consecutive rows at k = kq*KPT + kk
   uint32_t mb[MASKED ? NS : 1][MASKED ? KPT : 1];
   const uint16_t* p; const uint32_t* mask; uint32_t ld; int mp, r0, rmax, K;
@@ -121,7 +128,7 @@ template <int R, int EMODE, bool MASKED, int NS> struct RingLoadMN {
   __device__ __forceinline__ void configure(int) {}
   template <int SLOT, bool KTAIL = true> __device__ __forceinline__ void fetch(int k0) {
     const bool vec = (ld & 7) == 0;
-    const int rb = threadIdx.x % RB, kq = threadIdx.x / RB;
+    const int rb = block_rb(), kq = block_kq();
     const int gr = r0 + rb * 8;
 #pragma unroll
     for (int kk = 0; kk < KPT; ++kk) {
@@ -153,7 +160,7 @@ template <int R, int EMODE, bool MASKED, int NS> struct RingLoadMN {
   }
   // step D transposes dword D of the block: rows 2D (low halves) and 2D+1 (high halves)
   template <int SLOT, int D> __device__ __forceinline__ void commit_step(uint16_t* lds) {
-    const int rb = threadIdx.x % RB, kq = threadIdx.x / RB;
+    const int rb = block_rb(), kq = block_kq();
     if (MASKED && D == 0) {
 #pragma unroll
       for (int kk = 0; kk < KPT; ++kk) mask_bf16x8(v[SLOT][kk], mb[SLOT][kk]);
