@@ -232,6 +232,7 @@ static StoreView store_view(const rad_store* s, int slot) {
   v.plan_row_stride = (s->scheme == kFixedKShared || s->scheme == kReplaceShared) ? 0 : 1;
   v.idx_shared = s->scheme == kFixedKShared ? 1 : 0;
   v.paired = s->paired() ? 1 : 0;
+  v.may_overflow = s->scheme == kBernoulli ? 1 : 0;
   v.indices = s->scheme == kFixedKShared ? s->indices + (size_t)slot * s->k : s->indices;
   v.shared_k = s->scheme == kFixedKShared ? s->k : 0;
   v.mult = s->mult ? s->mult + (size_t)slot * s->plan_rows_per_step * s->k : nullptr;

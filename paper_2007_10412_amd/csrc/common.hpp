@@ -52,6 +52,7 @@ struct StoreView {
   const uint16_t* mult;      // with-replacement draws: how often each entry's column was drawn, [plan_rows][mult_pitch]
   int mult_pitch;            //   in entry order of the row; null otherwise (every weight is 1)
   int shared_k;              // shared scheme: entries per row (rows are k rounded up to 8 apart); else 0
+  int may_overflow;          // Bernoulli draws: an entry position may lie beyond `capacity` and must be checked
   int paired;                // bf16 per-entry draws: `values` holds 32-bit (value, column) entries, no `indices`
   float scale;
 };

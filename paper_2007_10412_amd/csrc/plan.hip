@@ -427,7 +427,12 @@ __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ x, Stor
 // keep words and scan their popcounts; then output slot t finds its column by rank: a binary search for the
 // word that holds the t-th kept entry, then that word's (t - entries before it)-th set bit.  Consecutive
 // lanes write consecutive entries.  (Walking the set bits per input lane instead measured slower.)
-template <typename T>
+// MODE: what an entry is written as (kPackIdx: value + 16-bit column; kPackPaired: one 32-bit entry;
+// kPackShared: value, columns once by row 0; kPackValue: value only, for index-free stores).  MULT: draw-count
+// weights.  CAPCHK: positions are checked against the capacity (Bernoulli draws).  Compile-time, so the
+// per-entry loop carries no branches on the store's kind.
+enum { kPackIdx = 0, kPackPaired = 1, kPackShared = 2, kPackValue = 3 };
+template <typename T, int MODE, bool MULT, bool CAPCHK>
 __global__ __launch_bounds__(256) void pack_span_kernel(const T* __restrict__ x, StoreView s) {
   constexpr int kSpan = 1024;
   constexpr int EPL = 16 / (int)sizeof(T);       // elements per 16-byte load
@@ -478,17 +483,16 @@ __global__ __launch_bounds__(256) void pack_span_kernel(const T* __restrict__ x,
         const int col = c0 + lc;
         const int rel = rel0 + t;
         const int64_t pos = base + rel;
-        if (pos < s.capacity) {
+        if (!CAPCHK || pos < s.capacity) {
           // weight of the entry: the scale, times the draw count of its column for draws with replacement
-          const float wgt = s.mult ? (float)s.mult[(size_t)prow * s.mult_pitch + rel] * s.scale : s.scale;
+          const float wgt = MULT ? (float)s.mult[(size_t)prow * s.mult_pitch + rel] * s.scale : s.scale;
           const float val = load_as_f32(&s_x[w][lc]) * wgt;
-          if (s.paired) {
+          if (MODE == kPackPaired) {
             reinterpret_cast<uint32_t*>(s.values)[pos] = pair_make(f32_to_bf16_bits(val), col);
           } else {
             store_from_f32(vals + pos, val);
-            if (!s.indices) {}
-            else if (!s.idx_shared) s.indices[pos] = (uint16_t)col;
-            else if (row == 0) s.indices[rel] = (uint16_t)col;
+            if (MODE == kPackIdx) s.indices[pos] = (uint16_t)col;
+            else if (MODE == kPackShared && row == 0) s.indices[rel] = (uint16_t)col;
           }
         }
       }
@@ -627,9 +631,27 @@ hipError_t launch_pack(const void* x, int dtype, const StoreView& s, hipStream_t
   dim3 grid(s.rows), block(256);
   const size_t row_bytes = (size_t)s.cols * (dtype == kF32 ? 4 : 2);
   if (row_bytes % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {     // every row is whole 16-byte vectors
-    if (dtype == kF32) hipLaunchKernelGGL(pack_span_kernel<float>, grid, block, 0, st, (const float*)x, s);
-    else hipLaunchKernelGGL(pack_span_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)x, s);
-    return hipGetLastError();
+    const int mode = s.paired ? kPackPaired : s.idx_shared ? kPackShared : s.indices ? kPackIdx : kPackValue;
+    const bool mult = s.mult != nullptr, chk = s.may_overflow != 0;
+#define RAD_PACK_CASE(T_, MODE_, MULT_, CHK_)                                                                   \
+  if (mode == MODE_ && mult == MULT_ && chk == CHK_) {                                                          \
+    hipLaunchKernelGGL((pack_span_kernel<T_, MODE_, MULT_, CHK_>), grid, block, 0, st, (const T_*)x, s);        \
+    return hipGetLastError();                                                                                   \
+  }
+    // draw-count weights and the capacity check never occur together (Bernoulli draws have no counts)
+    if (dtype == kF32) {
+      RAD_PACK_CASE(float, kPackIdx, false, false) RAD_PACK_CASE(float, kPackIdx, false, true)
+      RAD_PACK_CASE(float, kPackIdx, true, false) RAD_PACK_CASE(float, kPackShared, false, false)
+      RAD_PACK_CASE(float, kPackValue, false, false) RAD_PACK_CASE(float, kPackValue, false, true)
+      RAD_PACK_CASE(float, kPackValue, true, false)
+    } else {
+      RAD_PACK_CASE(uint16_t, kPackPaired, false, false) RAD_PACK_CASE(uint16_t, kPackPaired, false, true)
+      RAD_PACK_CASE(uint16_t, kPackPaired, true, false) RAD_PACK_CASE(uint16_t, kPackShared, false, false)
+      RAD_PACK_CASE(uint16_t, kPackValue, false, false) RAD_PACK_CASE(uint16_t, kPackValue, false, true)
+      RAD_PACK_CASE(uint16_t, kPackValue, true, false)
+    }
+#undef RAD_PACK_CASE
+    // any other combination takes the general kernel below
   }
   if (dtype == kF32)
     hipLaunchKernelGGL(pack_kernel<float>, grid, block, 0, st, (const float*)x, s);
