@@ -320,6 +320,16 @@ __device__ __forceinline__ void mfma_step(const bf16x8 (&a)[TM], const bf16x8 (&
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
 }
 
+// The MFMAs of one half iteration are issued in eight pieces, each followed by its share of the other work;
+// piece P takes the MFMAs m with m*8/(TM*TN) == P, in row-major (i, j) order.
+template <int P, int TM, int TN>
+__device__ __forceinline__ void mfma_piece(const bf16x8 (&a)[TM], const bf16x8 (&b)[TN], floatx16 (&acc)[TM][TN]) {
+  constexpr int CNT = TM * TN, LO = P * CNT / 8, HI = (P + 1) * CNT / 8;
+#pragma unroll
+  for (int m = LO; m < HI; ++m)
+    acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m / TN], b[m % TN], acc[m / TN][m % TN], 0, 0, 0);
+}
+
 // STAGED: the store epilogue passes the bf16 output tile through LDS (dX family)
 template <int EPI, int BM, int BN, bool STAGED>
 struct Gemm3Smem {
@@ -428,7 +438,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
     uint16_t* const cur = smem + r * kStageElems;
     uint16_t* const nxt = smem + s_nxt * kStageElems;
     uint16_t* const wr = smem + s_wr * kStageElems;
-    if constexpr (steady) {
+    if constexpr (steady && AK == kOpK && BKIND == kOpK) {
+      // two K-contiguous operands: little besides loads and stores to place, and group hints measured best
       interleave_reads_commits<sl, TM, TN, BM, BN>(cur, cur + kAElems, wr, wr + kAElems, wm0, wn0, fa1, fb1, la, lb);
       // the slot is free again: the loads of slice kt+2+NS start now and have NS iterations to arrive
       la.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); lb.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK);
@@ -454,6 +465,42 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      // 2 MFMA
         __builtin_amdgcn_sched_group_barrier(0x100, kDsr, 0);   // LDS reads (first fragments of slice kt+1)
       }
+    } else if constexpr (steady) {
+      // Written out piece by piece, with a scheduling fence after each, so that every pair of MFMAs is
+      // followed by its share of LDS reads, LDS writes, address arithmetic and global loads whatever the
+      // loaders look like (group hints alone left the commit work of the transposing and sparse loaders in
+      // one burst with no MFMA in flight).
+      typedef LdsBF16<BM, kBK3> LYA; typedef LdsBF16<BN, kBK3> LYB;
+      const int lane_ = threadIdx.x & 63, lr_ = lane_ & 31, lk_ = lane_ >> 5;
+      const uint16_t* const curA = cur; const uint16_t* const curB = cur + kAElems;
+      const uint16_t* const nxtA = nxt; const uint16_t* const nxtB = nxt + kAElems;
+      auto ra1 = [&](int i) { if (i < TM) fa1[i] = *reinterpret_cast<const bf16x8*>(&curA[LYA::unit(wm0 + i * 32 + lr_, 2 + lk_) * 8]); };
+      auto rb1 = [&](int j) { if (j < TN) fb1[j] = *reinterpret_cast<const bf16x8*>(&curB[LYB::unit(wn0 + j * 32 + lr_, 2 + lk_) * 8]); };
+      auto ra0 = [&](int i) { if (i < TM) fa0[i] = *reinterpret_cast<const bf16x8*>(&nxtA[LYA::unit(wm0 + i * 32 + lr_, lk_) * 8]); };
+      auto rb0 = [&](int j) { if (j < TN) fb0[j] = *reinterpret_cast<const bf16x8*>(&nxtB[LYB::unit(wn0 + j * 32 + lr_, lk_) * 8]); };
+      uint16_t* const wrA = wr; uint16_t* const wrB = wr + kAElems;
+#define RAD_FENCE() __builtin_amdgcn_sched_barrier(0)
+      // first half: MFMAs of k-step 0; fragments of k-step 1; slice kt+2 into its stage; loads of slice kt+2+NS
+      mfma_piece<0, TM, TN>(fa0, fb0, acc); ra1(0); la.template commit_step<sl, 0>(wrA); RAD_FENCE();
+      mfma_piece<1, TM, TN>(fa0, fb0, acc); rb1(0); lb.template commit_step<sl, 0>(wrB); RAD_FENCE();
+      mfma_piece<2, TM, TN>(fa0, fb0, acc); ra1(1); la.template commit_step<sl, 1>(wrA); RAD_FENCE();
+      mfma_piece<3, TM, TN>(fa0, fb0, acc); rb1(1); lb.template commit_step<sl, 1>(wrB); RAD_FENCE();
+      mfma_piece<4, TM, TN>(fa0, fb0, acc); ra1(2); la.template commit_step<sl, 2>(wrA); RAD_FENCE();
+      mfma_piece<5, TM, TN>(fa0, fb0, acc); rb1(2); lb.template commit_step<sl, 2>(wrB); RAD_FENCE();
+      mfma_piece<6, TM, TN>(fa0, fb0, acc); ra1(3); la.template commit_step<sl, 3>(wrA);
+      la.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); RAD_FENCE();
+      mfma_piece<7, TM, TN>(fa0, fb0, acc); rb1(3); lb.template commit_step<sl, 3>(wrB);
+      lb.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); la.bounds(kbeg + (kt + 3 + NS) * BK); RAD_FENCE();
+      // second half: MFMAs of k-step 1; first fragments of slice kt+1
+      mfma_piece<0, TM, TN>(fa1, fb1, acc); ra0(0); RAD_FENCE();
+      mfma_piece<1, TM, TN>(fa1, fb1, acc); rb0(0); RAD_FENCE();
+      mfma_piece<2, TM, TN>(fa1, fb1, acc); ra0(1); RAD_FENCE();
+      mfma_piece<3, TM, TN>(fa1, fb1, acc); rb0(1); RAD_FENCE();
+      mfma_piece<4, TM, TN>(fa1, fb1, acc); ra0(2); RAD_FENCE();
+      mfma_piece<5, TM, TN>(fa1, fb1, acc); rb0(2); RAD_FENCE();
+      mfma_piece<6, TM, TN>(fa1, fb1, acc); ra0(3); RAD_FENCE();
+      mfma_piece<7, TM, TN>(fa1, fb1, acc); rb0(3); RAD_FENCE();
+#undef RAD_FENCE
     } else {
       load_frags32<TM, TN, BM, BN>(cur, cur + kAElems, 1, wm0, wn0, fa1, fb1);
       if (kt + 2 < KT) { commit_all<LoadA, sl>(la, wr); commit_all<LoadB, sl>(lb, wr + kAElems); }
