@@ -480,17 +480,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       auto rb0 = [&](int j) { if (j < TN) fb0[j] = *reinterpret_cast<const bf16x8*>(&nxtB[LYB::unit(wn0 + j * 32 + lr_, lk_) * 8]); };
       uint16_t* const wrA = wr; uint16_t* const wrB = wr + kAElems;
 #define RAD_FENCE() __builtin_amdgcn_sched_barrier(0)
-      // first half: MFMAs of k-step 0; fragments of k-step 1; slice kt+2 into its stage; loads of slice kt+2+NS
-      mfma_piece<0, TM, TN>(fa0, fb0, acc); ra1(0); la.template commit_step<sl, 0>(wrA); RAD_FENCE();
-      mfma_piece<1, TM, TN>(fa0, fb0, acc); rb1(0); lb.template commit_step<sl, 0>(wrB); RAD_FENCE();
-      mfma_piece<2, TM, TN>(fa0, fb0, acc); ra1(1); la.template commit_step<sl, 1>(wrA); RAD_FENCE();
-      mfma_piece<3, TM, TN>(fa0, fb0, acc); rb1(1); lb.template commit_step<sl, 1>(wrB); RAD_FENCE();
-      mfma_piece<4, TM, TN>(fa0, fb0, acc); ra1(2); la.template commit_step<sl, 2>(wrA); RAD_FENCE();
-      mfma_piece<5, TM, TN>(fa0, fb0, acc); rb1(2); lb.template commit_step<sl, 2>(wrB); RAD_FENCE();
-      mfma_piece<6, TM, TN>(fa0, fb0, acc); ra1(3); la.template commit_step<sl, 3>(wrA);
-      la.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); RAD_FENCE();
-      mfma_piece<7, TM, TN>(fa0, fb0, acc); rb1(3); lb.template commit_step<sl, 3>(wrB);
-      lb.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); la.bounds(kbeg + (kt + 3 + NS) * BK); RAD_FENCE();
+      // first half: MFMAs of k-step 0; fragments of k-step 1; slice kt+2 into its stage; loads of slice kt+2+NS.
+      // B goes first: it is the transposing loader here, whose first step needs all of its loads, so its
+      // registers are refilled at once after its last step and have the rest of the iteration to arrive.
+      mfma_piece<0, TM, TN>(fa0, fb0, acc); ra1(0); lb.template commit_step<sl, 0>(wrB); RAD_FENCE();
+      mfma_piece<1, TM, TN>(fa0, fb0, acc); rb1(0); lb.template commit_step<sl, 1>(wrB); RAD_FENCE();
+      mfma_piece<2, TM, TN>(fa0, fb0, acc); ra1(1); lb.template commit_step<sl, 2>(wrB); RAD_FENCE();
+      mfma_piece<3, TM, TN>(fa0, fb0, acc); rb1(1); lb.template commit_step<sl, 3>(wrB);
+      lb.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); RAD_FENCE();
+      mfma_piece<4, TM, TN>(fa0, fb0, acc); ra1(2); la.template commit_step<sl, 0>(wrA); RAD_FENCE();
+      mfma_piece<5, TM, TN>(fa0, fb0, acc); rb1(2); la.template commit_step<sl, 1>(wrA); RAD_FENCE();
+      mfma_piece<6, TM, TN>(fa0, fb0, acc); ra1(3); la.template commit_step<sl, 2>(wrA); RAD_FENCE();
+      mfma_piece<7, TM, TN>(fa0, fb0, acc); rb1(3); la.template commit_step<sl, 3>(wrA);
+      la.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); la.bounds(kbeg + (kt + 3 + NS) * BK); RAD_FENCE();
       // second half: MFMAs of k-step 1; first fragments of slice kt+1
       mfma_piece<0, TM, TN>(fa1, fb1, acc); ra0(0); RAD_FENCE();
       mfma_piece<1, TM, TN>(fa1, fb1, acc); rb0(0); RAD_FENCE();
