@@ -320,14 +320,56 @@ __device__ __forceinline__ void mfma_step(const bf16x8 (&a)[TM], const bf16x8 (&
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
 }
 
+// Order of the TM x TN MFMAs of one k-step and of the TM + TN fragment reads that feed them.  Fragments are
+// read a0, b0, b1, a1, b2, a2, ... and the MFMAs walk the tile in growing squares -- (0,0); (0,1), (1,0),
+// (1,1); (0,2), (1,2), (2,0), (2,1), (2,2); ... -- so the q-th fragment is first needed about as many MFMAs
+// into the k-step as it was read into the previous one: every LDS read has most of a k-step to arrive, where
+// a row-major walk needs all of b within its first TN MFMAs.
+template <int TM, int TN> struct MfmaOrder {
+  static constexpr int CNT = TM * TN, NF = TM + TN;
+  // m-th MFMA: returns i * TN + j
+  static constexpr int at(int m) {
+    if (m == 0) return 0;
+    int n = 1;
+    for (int s = 1; s < (TM > TN ? TM : TN); ++s) {
+      if (s < TN) for (int i = 0; i < (s < TM ? s : TM); ++i) { if (n == m) return i * TN + s; ++n; }
+      if (s < TM) for (int j = 0; j < (s + 1 < TN ? s + 1 : TN); ++j) { if (n == m) return s * TN + j; ++n; }
+    }
+    return 0;
+  }
+  // q-th fragment read: returns 2 * index + (1 for b, 0 for a); -1 past the last
+  static constexpr int frag(int q) {
+    if (q == 0) return 0;
+    if (q == 1) return 1;
+    int n = 2;
+    for (int s = 1; s < (TM > TN ? TM : TN); ++s) {
+      if (s < TN) { if (n == q) return 2 * s + 1; ++n; }
+      if (s < TM) { if (n == q) return 2 * s; ++n; }
+    }
+    return -1;
+  }
+};
+static_assert(MfmaOrder<4, 4>::at(4) == 0 * 4 + 2 && MfmaOrder<4, 4>::at(9) == 0 * 4 + 3 && MfmaOrder<4, 4>::at(15) == 15, "");
+static_assert(MfmaOrder<4, 4>::frag(2) == 3 && MfmaOrder<4, 4>::frag(3) == 2 && MfmaOrder<4, 4>::frag(7) == 6, "");
+static_assert(MfmaOrder<4, 1>::at(3) == 3 && MfmaOrder<4, 1>::frag(4) == 6 && MfmaOrder<4, 1>::frag(5) == -1, "");
+static_assert(MfmaOrder<4, 2>::at(1) == 1 && MfmaOrder<4, 2>::at(2) == 2 && MfmaOrder<4, 2>::at(7) == 7, "");
+
 // The MFMAs of one half iteration are issued in eight pieces, each followed by its share of the other work;
-// piece P takes the MFMAs m with m*8/(TM*TN) == P, in row-major (i, j) order.
+// piece P takes the MFMAs m with m*8/(TM*TN) == P of that order.
 template <int P, int TM, int TN>
 __device__ __forceinline__ void mfma_piece(const bf16x8 (&a)[TM], const bf16x8 (&b)[TN], floatx16 (&acc)[TM][TN]) {
   constexpr int CNT = TM * TN, LO = P * CNT / 8, HI = (P + 1) * CNT / 8;
+  typedef MfmaOrder<TM, TN> O;
 #pragma unroll
-  for (int m = LO; m < HI; ++m)
-    acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m / TN], b[m % TN], acc[m / TN][m % TN], 0, 0, 0);
+  for (int m = LO; m < HI; ++m) {
+    const int i = O::at(m) / TN, j = O::at(m) % TN;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+}
+// the Q-th fragment read of a k-step: ra(i) or rb(j)
+template <int Q, int TM, int TN, class RA, class RB> __device__ __forceinline__ void frag_read(RA&& ra, RB&& rb) {
+  constexpr int f = MfmaOrder<TM, TN>::frag(Q);
+  if constexpr (f >= 0) { if constexpr (f & 1) rb(f >> 1); else ra(f >> 1); }
 }
 
 // STAGED: the store epilogue passes the bf16 output tile through LDS (dX family)
@@ -483,25 +525,25 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       // first half: MFMAs of k-step 0; fragments of k-step 1; slice kt+2 into its stage; loads of slice kt+2+NS.
       // B goes first: it is the transposing loader here, whose first step needs all of its loads, so its
       // registers are refilled at once after its last step and have the rest of the iteration to arrive.
-      mfma_piece<0, TM, TN>(fa0, fb0, acc); ra1(0); lb.template commit_step<sl, 0>(wrB); RAD_FENCE();
-      mfma_piece<1, TM, TN>(fa0, fb0, acc); rb1(0); lb.template commit_step<sl, 1>(wrB); RAD_FENCE();
-      mfma_piece<2, TM, TN>(fa0, fb0, acc); ra1(1); lb.template commit_step<sl, 2>(wrB); RAD_FENCE();
-      mfma_piece<3, TM, TN>(fa0, fb0, acc); rb1(1); lb.template commit_step<sl, 3>(wrB);
+      mfma_piece<0, TM, TN>(fa0, fb0, acc); frag_read<0, TM, TN>(ra1, rb1); lb.template commit_step<sl, 0>(wrB); RAD_FENCE();
+      mfma_piece<1, TM, TN>(fa0, fb0, acc); frag_read<1, TM, TN>(ra1, rb1); lb.template commit_step<sl, 1>(wrB); RAD_FENCE();
+      mfma_piece<2, TM, TN>(fa0, fb0, acc); frag_read<2, TM, TN>(ra1, rb1); lb.template commit_step<sl, 2>(wrB); RAD_FENCE();
+      mfma_piece<3, TM, TN>(fa0, fb0, acc); frag_read<3, TM, TN>(ra1, rb1); lb.template commit_step<sl, 3>(wrB);
       lb.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); RAD_FENCE();
-      mfma_piece<4, TM, TN>(fa0, fb0, acc); ra1(2); la.template commit_step<sl, 0>(wrA); RAD_FENCE();
-      mfma_piece<5, TM, TN>(fa0, fb0, acc); rb1(2); la.template commit_step<sl, 1>(wrA); RAD_FENCE();
-      mfma_piece<6, TM, TN>(fa0, fb0, acc); ra1(3); la.template commit_step<sl, 2>(wrA); RAD_FENCE();
-      mfma_piece<7, TM, TN>(fa0, fb0, acc); rb1(3); la.template commit_step<sl, 3>(wrA);
+      mfma_piece<4, TM, TN>(fa0, fb0, acc); frag_read<4, TM, TN>(ra1, rb1); la.template commit_step<sl, 0>(wrA); RAD_FENCE();
+      mfma_piece<5, TM, TN>(fa0, fb0, acc); frag_read<5, TM, TN>(ra1, rb1); la.template commit_step<sl, 1>(wrA); RAD_FENCE();
+      mfma_piece<6, TM, TN>(fa0, fb0, acc); frag_read<6, TM, TN>(ra1, rb1); la.template commit_step<sl, 2>(wrA); RAD_FENCE();
+      mfma_piece<7, TM, TN>(fa0, fb0, acc); frag_read<7, TM, TN>(ra1, rb1); la.template commit_step<sl, 3>(wrA);
       la.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); la.bounds(kbeg + (kt + 3 + NS) * BK); RAD_FENCE();
       // second half: MFMAs of k-step 1; first fragments of slice kt+1
-      mfma_piece<0, TM, TN>(fa1, fb1, acc); ra0(0); RAD_FENCE();
-      mfma_piece<1, TM, TN>(fa1, fb1, acc); rb0(0); RAD_FENCE();
-      mfma_piece<2, TM, TN>(fa1, fb1, acc); ra0(1); RAD_FENCE();
-      mfma_piece<3, TM, TN>(fa1, fb1, acc); rb0(1); RAD_FENCE();
-      mfma_piece<4, TM, TN>(fa1, fb1, acc); ra0(2); RAD_FENCE();
-      mfma_piece<5, TM, TN>(fa1, fb1, acc); rb0(2); RAD_FENCE();
-      mfma_piece<6, TM, TN>(fa1, fb1, acc); ra0(3); RAD_FENCE();
-      mfma_piece<7, TM, TN>(fa1, fb1, acc); rb0(3); RAD_FENCE();
+      mfma_piece<0, TM, TN>(fa1, fb1, acc); frag_read<0, TM, TN>(ra0, rb0); RAD_FENCE();
+      mfma_piece<1, TM, TN>(fa1, fb1, acc); frag_read<1, TM, TN>(ra0, rb0); RAD_FENCE();
+      mfma_piece<2, TM, TN>(fa1, fb1, acc); frag_read<2, TM, TN>(ra0, rb0); RAD_FENCE();
+      mfma_piece<3, TM, TN>(fa1, fb1, acc); frag_read<3, TM, TN>(ra0, rb0); RAD_FENCE();
+      mfma_piece<4, TM, TN>(fa1, fb1, acc); frag_read<4, TM, TN>(ra0, rb0); RAD_FENCE();
+      mfma_piece<5, TM, TN>(fa1, fb1, acc); frag_read<5, TM, TN>(ra0, rb0); RAD_FENCE();
+      mfma_piece<6, TM, TN>(fa1, fb1, acc); frag_read<6, TM, TN>(ra0, rb0); RAD_FENCE();
+      mfma_piece<7, TM, TN>(fa1, fb1, acc); frag_read<7, TM, TN>(ra0, rb0); RAD_FENCE();
 #undef RAD_FENCE
     } else {
       load_frags32<TM, TN, BM, BN>(cur, cur + kAElems, 1, wm0, wn0, fa1, fb1);

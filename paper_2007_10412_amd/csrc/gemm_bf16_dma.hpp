@@ -1,0 +1,520 @@
+// bf16 GEMM for two K-contiguous operands whose tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4): no staging registers, no LDS store instructions, no address arithmetic in
+// the loop.
+//
+// A load instruction writes the 64 x 16 bytes of its wave to consecutive LDS addresses starting at M0,
+// so the tile layout is produced by choosing which global chunk each lane asks for: lane l of the load
+// that fills LDS units [u0, u0 + 64) fetches the (row, k chunk) whose place in the layout is unit u0 + l.
+// Per thread that is a constant 32-bit offset from a wave-uniform base that advances by one slice per
+// iteration on the scalar unit.
+//
+// Ring of four LDS stages of BK = 32.  At iteration kt the workgroup
+//   - runs the MFMAs of slice kt from stage kt%4,
+//   - issues the loads of slice kt+3 into stage (kt+3)%4 (= stage (kt-1)%4, last read before the previous
+//     barrier),
+//   - reads the first fragments of slice kt+1,
+//   - waits until its own loads of slice kt+2 have landed (the loads of slice kt+3 stay in flight) and
+//     meets the others at the one barrier of the iteration.
+// The compiler does not see these loads (they are inline assembly), so the waits on them are written out.
+#pragma once
+#include "gemm_bf16.hpp"
+
+namespace rad {
+
+constexpr int kDmaStages = 4;
+
+template <int EPI, int BM, int BN> struct GemmDmaSmem {
+  static constexpr int STAGE = (BM + BN) * kBK3 * 2;
+  static constexpr int MAIN = kDmaStages * STAGE;
+  static constexpr int CT = EPI == kEpiFwd ? FwdEpiLds<uint16_t, BM, BN>::BYTES : BM * (BN + 8) * 2;
+  static constexpr int BYTES = CT > MAIN ? CT : MAIN;
+};
+
+// 16 bytes per lane from gbase + voff to LDS address lds + 16 * lane; gbase and lds are wave-uniform
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds) {
+#ifndef RAD_DMA_MOD
+#define RAD_DMA_MOD ""
+#endif
+#ifdef RAD_DMA_NONOP
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" RAD_DMA_MOD
+#else
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" RAD_DMA_MOD
+#endif
+               :: "v"(voff), "s"(gbase), "s"(lds) : "memory");
+}
+// The same in two parts, for callers that put at least one other instruction between them (an M0 write
+// needs one wait state before the load that reads it; the combined form spends a nop on it).  Nothing else in
+// these kernels uses M0.
+__device__ __forceinline__ void dma16_aim(uint32_t lds) { asm volatile("s_mov_b32 m0, %0" :: "s"(lds) : "memory"); }
+__device__ __forceinline__ void dma16_go(const void* gbase, uint32_t voff) {
+  asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(voff), "s"(gbase) : "memory");
+}
+template <int N> __device__ __forceinline__ void dma_wait() {   // at most N of this wave's loads still in flight
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// One operand tile of R rows x 32 k = 4R units of 16 bytes; load I of thread t fills unit I*256 + t.
+template <int R> struct DmaOperandK {
+  typedef LdsBF16<R, kBK3> L;
+  static constexpr int NI = R / 64;
+  uint32_t voff[NI];
+  const unsigned char* base;      // wave-uniform: first element of the tile's rows at the first slice
+  uint32_t wave_lds;              // wave-uniform: 1024 * wave
+  __device__ __forceinline__ void init(const void* p, int64_t ld, int r0, int kbeg) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int u = i * kGemmThreads + (int)threadIdx.x;
+      const int row = tile_row(u >> 2), kc = (u & 3) ^ tile_swz(row);    // inverse of L::unit
+      voff[i] = (uint32_t)row * (uint32_t)ld * 2u + (uint32_t)kc * 16u;
+#ifdef RAD_ABL
+      if (RAD_ABL & 64) voff[i] = (uint32_t)(u >> 3) * (uint32_t)ld * 2u + (uint32_t)(u & 7) * 16u;   // timing only
+#endif
+    }
+    base = static_cast<const unsigned char*>(p) + ((int64_t)r0 * ld + kbeg) * 2;
+    wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) * 1024u;
+  }
+  // load I of the slice that starts k elements after the first, into the tile at LDS address lds
+  template <int I> __device__ __forceinline__ void issue(uint32_t lds, int k) const {
+    if constexpr (I < NI) dma16(base + (int64_t)k * 2, voff[I], lds + wave_lds + (uint32_t)I * 4096u);
+  }
+};
+
+template <int EPI, int BM, int BN>
+__global__ __launch_bounds__(kGemmThreads) void gemm_dma_bf16_kernel(GemmArgs g) {
+  constexpr int BK = kBK3, TM = BM / 64, TN = BN / 64;
+  typedef GemmDmaSmem<EPI, BM, BN> S;
+  typedef LdsBF16<BM, BK> LYA; typedef LdsBF16<BN, BK> LYB;
+  typedef DmaOperandK<BM> LoadA; typedef DmaOperandK<BN> LoadB;
+  constexpr int kLoads = LoadA::NI + LoadB::NI;        // per thread and slice
+  static_assert(kLoads <= 8, "one load per MFMA piece");
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  uint16_t* const smem = reinterpret_cast<uint16_t*>(smem_raw);
+  const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw);   // low half of a flat LDS address
+  constexpr int kStageElems = S::STAGE / 2, kAElems = BM * BK;
+
+  // tile order: as in the register-staged kernels (XCD chunks, groups of 4 tile rows)
+  const int tiles_n = g.N / BN, tiles_m = g.M / BM;
+  const int T = tiles_m * tiles_n;
+  int lin = blockIdx.x;
+  if ((T & 7) == 0) lin = (lin & 7) * (T >> 3) + (lin >> 3);
+  constexpr int GM = 4;
+  const int grp = lin / (GM * tiles_n), within = lin - grp * (GM * tiles_n);
+  const int gh = min(GM, tiles_m - grp * GM);
+  const int tm = grp * GM + within % gh, tn = within / gh;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int w = threadIdx.x >> 6;
+  const int wm0 = (w >> 1) * (BM / 2), wn0 = (w & 1) * (BN / 2);
+  const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int kbeg = g.k_splits > 1 ? (int)blockIdx.y * g.k_split : 0;
+  const int kend = g.k_splits > 1 ? min(g.K, kbeg + g.k_split) : g.K;
+  const int KT = (kend - kbeg) / BK;                   // the host sends only K ranges that are whole slices
+  LoadA la; LoadB lb;
+  la.init(g.A, g.lda, m0, kbeg);
+  lb.init(g.B, g.ldb, n0, kbeg);
+
+  // load number Q (0 .. 7) of slice s into stage st
+  auto issue = [&](auto Q_, int st, int s) {
+    constexpr int Q = decltype(Q_)::value;
+    const uint32_t a_lds = smem_lds + (uint32_t)st * S::STAGE;
+#ifndef RAD_ABL
+#define RAD_ABL 0
+#endif
+    if (RAD_ABL & 16) s = 0;
+    if (RAD_ABL & 32) s = s & 7;
+    if constexpr (Q < LoadA::NI) la.template issue<Q>(a_lds, s * BK);
+    else lb.template issue<Q - LoadA::NI>(a_lds + kAElems * 2, s * BK);
+  };
+  auto issue_all = [&](int st, int s) {
+    issue(IntC<0>(), st, s); issue(IntC<1>(), st, s); issue(IntC<2>(), st, s); issue(IntC<3>(), st, s);
+    issue(IntC<4>(), st, s); issue(IntC<5>(), st, s); issue(IntC<6>(), st, s); issue(IntC<7>(), st, s);
+  };
+
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  auto body = [&](auto R_, auto STEADY_, int kt) {
+    constexpr int r = decltype(R_)::value;
+    constexpr bool steady = decltype(STEADY_)::value;
+    constexpr int s_nxt = (r + 1) % kDmaStages, s_fill = (r + 3) % kDmaStages;
+    const uint16_t* const curA = smem + r * kStageElems; const uint16_t* const curB = curA + kAElems;
+    const uint16_t* const nxtA = smem + s_nxt * kStageElems; const uint16_t* const nxtB = nxtA + kAElems;
+    auto ra1 = [&](int i) { if (i < TM && !(steady && (RAD_ABL & 4))) fa1[i] = *reinterpret_cast<const bf16x8*>(&curA[LYA::unit(wm0 + i * 32 + lr, 2 + lk) * 8]); };
+    auto rb1 = [&](int j) { if (j < TN && !(steady && (RAD_ABL & 4))) fb1[j] = *reinterpret_cast<const bf16x8*>(&curB[LYB::unit(wn0 + j * 32 + lr, 2 + lk) * 8]); };
+    auto ra0 = [&](int i) { if (i < TM) fa0[i] = *reinterpret_cast<const bf16x8*>(&nxtA[LYA::unit(wm0 + i * 32 + lr, lk) * 8]); };
+    auto rb0 = [&](int j) { if (j < TN) fb0[j] = *reinterpret_cast<const bf16x8*>(&nxtB[LYB::unit(wn0 + j * 32 + lr, lk) * 8]); };
+#ifndef RAD_ABL
+#define RAD_ABL 0
+#endif
+    const bool fill = (steady && !(RAD_ABL & 2)) || (!steady && kt + 3 < KT);
+    const bool more = (steady && !(RAD_ABL & 4)) || (!steady && kt + 1 < KT);
+#define RAD_FENCE() __builtin_amdgcn_sched_barrier(0)
+    // MFMAs of k-step 0 with the fragments of k-step 1, then MFMAs of k-step 1 with the first fragments of
+    // slice kt+1; the loads of slice kt+3 are spread over the whole iteration, one per two pieces, so the
+    // four waves do not queue at the one texture-address unit of the CU
+    mfma_piece<0, TM, TN>(fa0, fb0, acc); frag_read<0, TM, TN>(ra1, rb1); if (fill) issue(IntC<0>(), s_fill, kt + 3); RAD_FENCE();
+    mfma_piece<1, TM, TN>(fa0, fb0, acc); frag_read<1, TM, TN>(ra1, rb1); RAD_FENCE();
+    mfma_piece<2, TM, TN>(fa0, fb0, acc); frag_read<2, TM, TN>(ra1, rb1); if (fill) issue(IntC<1>(), s_fill, kt + 3); RAD_FENCE();
+    mfma_piece<3, TM, TN>(fa0, fb0, acc); frag_read<3, TM, TN>(ra1, rb1); RAD_FENCE();
+    mfma_piece<4, TM, TN>(fa0, fb0, acc); frag_read<4, TM, TN>(ra1, rb1); if (fill) issue(IntC<2>(), s_fill, kt + 3); RAD_FENCE();
+    mfma_piece<5, TM, TN>(fa0, fb0, acc); frag_read<5, TM, TN>(ra1, rb1); RAD_FENCE();
+    mfma_piece<6, TM, TN>(fa0, fb0, acc); frag_read<6, TM, TN>(ra1, rb1); if (fill) issue(IntC<3>(), s_fill, kt + 3); RAD_FENCE();
+    mfma_piece<7, TM, TN>(fa0, fb0, acc); frag_read<7, TM, TN>(ra1, rb1); RAD_FENCE();
+    mfma_piece<0, TM, TN>(fa1, fb1, acc); if (more) frag_read<0, TM, TN>(ra0, rb0); if (fill) issue(IntC<4>(), s_fill, kt + 3); RAD_FENCE();
+    mfma_piece<1, TM, TN>(fa1, fb1, acc); if (more) frag_read<1, TM, TN>(ra0, rb0); RAD_FENCE();
+    mfma_piece<2, TM, TN>(fa1, fb1, acc); if (more) frag_read<2, TM, TN>(ra0, rb0); if (fill) issue(IntC<5>(), s_fill, kt + 3); RAD_FENCE();
+    mfma_piece<3, TM, TN>(fa1, fb1, acc); if (more) frag_read<3, TM, TN>(ra0, rb0); RAD_FENCE();
+    mfma_piece<4, TM, TN>(fa1, fb1, acc); if (more) frag_read<4, TM, TN>(ra0, rb0); if (fill) issue(IntC<6>(), s_fill, kt + 3); RAD_FENCE();
+    mfma_piece<5, TM, TN>(fa1, fb1, acc); if (more) frag_read<5, TM, TN>(ra0, rb0); RAD_FENCE();
+    mfma_piece<6, TM, TN>(fa1, fb1, acc); if (more) frag_read<6, TM, TN>(ra0, rb0); if (fill) issue(IntC<7>(), s_fill, kt + 3); RAD_FENCE();
+    mfma_piece<7, TM, TN>(fa1, fb1, acc); if (more) frag_read<7, TM, TN>(ra0, rb0); RAD_FENCE();
+#undef RAD_FENCE
+    // slice kt+2 must have landed before the barrier; the loads of slice kt+3, if any, stay in flight
+    if (steady && (RAD_ABL & 2)) dma_wait<0>(); else if (fill) { if (!(steady && (RAD_ABL & 8))) dma_wait<kLoads>(); } else dma_wait<0>();
+    if (!(steady && (RAD_ABL & 1))) __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // prologue: slices 0, 1, 2 on their way into stages 0, 1, 2; slices 0 and 1 landed
+  if (KT > 0) issue_all(0, 0);
+  if (KT > 1) issue_all(1, 1);
+  if (KT > 2) { issue_all(2, 2); dma_wait<kLoads>(); } else dma_wait<0>();
+  __syncthreads();
+  if (KT > 0) load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
+  __builtin_amdgcn_sched_barrier(0);
+
+  int kt = 0;
+  if (KT > 6) {
+    do {                                   // every iteration below loads a slice: kt + 3 + 3 < KT
+      body(IntC<0>(), std::true_type(), kt);
+      body(IntC<1>(), std::true_type(), kt + 1);
+      body(IntC<2>(), std::true_type(), kt + 2);
+      body(IntC<3>(), std::true_type(), kt + 3);
+      kt += 4;
+    } while (kt + 6 < KT);
+  }
+  for (; kt < KT; kt += 4) {               // drain; kt is a multiple of 4 here
+    body(IntC<0>(), std::false_type(), kt);
+    if (kt + 1 < KT) body(IntC<1>(), std::false_type(), kt + 1);
+    if (kt + 2 < KT) body(IntC<2>(), std::false_type(), kt + 2);
+    if (kt + 3 < KT) body(IntC<3>(), std::false_type(), kt + 3);
+  }
+
+  if constexpr (EPI == kEpiStore) {
+    epilogue_dx_staged<BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
+  } else {
+    epilogue_fwd<uint16_t, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
+  }
+}
+
+// ------------------------------------------------------------------ 64-deep slices, two stages
+// The same idea with K slices of 64 (whole 128-byte lines per row and load, half as many barriers per
+// flop) in two LDS stages of 64 KB.  Iteration kt runs four k-steps of 16 on stage kt%2:
+//   k-step 0: MFMAs | fragments of k-step 1 | second half of the loads of slice kt+1 into the other stage
+//   k-step 1: MFMAs | fragments of k-step 2
+//   k-step 2: MFMAs | fragments of k-step 3
+//   wait for the loads of slice kt+1 and for the fragment reads; barrier
+//   k-step 3: MFMAs | first fragments of slice kt+1 | first half of the loads of slice kt+2 into this
+//             stage, which every wave has finished reading
+template <int R> struct Lds64 {
+  // 16-byte unit of (row, k chunk 0..7): rows are 128 bytes; the chunk is swizzled with bits 1..3 of the
+  // row so that 16 consecutive rows at one chunk touch every bank once
+  static __host__ __device__ __forceinline__ constexpr int unit(int row, int kc) { return row * 8 + (kc ^ ((row >> 1) & 7)); }
+};
+
+template <int R> struct DmaOperandK64 {
+  static constexpr int NI = R / 32;     // loads per thread and slice: R rows x 8 units over 256 threads
+  uint32_t voff[NI];
+  const unsigned char* base;
+  uint32_t wave_lds;
+  __device__ __forceinline__ void init(const void* p, int64_t ld, int r0, int kbeg) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int u = i * kGemmThreads + (int)threadIdx.x;
+      const int row = u >> 3, kc = (u & 7) ^ ((row >> 1) & 7);          // inverse of Lds64::unit
+      voff[i] = (uint32_t)row * (uint32_t)ld * 2u + (uint32_t)kc * 16u;
+    }
+    base = static_cast<const unsigned char*>(p) + ((int64_t)r0 * ld + kbeg) * 2;
+    wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) * 1024u;
+  }
+  template <int I> __device__ __forceinline__ void issue(uint32_t lds, int k) const {
+    if constexpr (I < NI) dma16(base + (int64_t)k * 2, voff[I], lds + wave_lds + (uint32_t)I * 4096u);
+  }
+  template <int I> __device__ __forceinline__ void aim(uint32_t lds) const {
+    if constexpr (I < NI) dma16_aim(lds + wave_lds + (uint32_t)I * 4096u);
+  }
+  template <int I> __device__ __forceinline__ void go(int k) const {
+    if constexpr (I < NI) dma16_go(base + (int64_t)k * 2, voff[I]);
+  }
+};
+
+// An operand stored with its M/N index contiguous (element (row, k) at p[k*ld + row]) goes to LDS as it lies
+// in memory, k-row by k-row, and is transposed on the way to the registers by ds_read_b64_tr_b16: within 16
+// lanes, lane j receives in element e what lane 4e + j/4 addressed as its element j%4.  With source lane s
+// pointing at k-row s/4, rows 4(s%4) .. 4(s%4)+3 of a 16-row block, lane j ends up with rows j, k = 0 .. 3:
+// two such reads give the 8 consecutive k of an MFMA fragment.
+//   LDS tile: [64 k][R rows], a k-row is R*2 bytes = R/8 chunks of 16 bytes; chunk c of k-row k sits at
+// position c ^ 4(k%4), so the four k-rows one read touches fall into different 64-byte bank windows.
+// A load instruction fills two k-rows (1 KB); load I of wave w fills k-rows 2(4I + w), 2(4I + w) + 1.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+template <int R> struct LdsMN64 {
+  static_assert(R == 256, "a k-row is 32 chunks: two k-rows per load instruction");
+  static __host__ __device__ __forceinline__ constexpr int byte_of(int row, int k) {
+    return k * (R * 2) + (((row >> 3) ^ (4 * (k & 3))) << 4) + (row & 7) * 2;
+  }
+};
+
+template <int R> struct DmaOperandMN64 {
+  static constexpr int NI = 8;
+  uint32_t voff[NI];
+  const unsigned char* base;
+  int64_t slice_bytes;            // 64 k-rows
+  uint32_t wave_lds;
+  __device__ __forceinline__ void init(const void* p, int64_t ld, int r0, int kbeg) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int k = 2 * (4 * i + w) + (lane >> 5);
+      const int c = (lane & 31) ^ (4 * (k & 3));                       // logical chunk at this LDS position
+      voff[i] = (uint32_t)k * (uint32_t)ld * 2u + (uint32_t)c * 16u;
+    }
+    base = static_cast<const unsigned char*>(p) + ((int64_t)kbeg * ld + r0) * 2;
+    slice_bytes = 64 * ld * 2;
+    wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) * 1024u;
+  }
+  template <int I> __device__ __forceinline__ void issue(uint32_t lds, int k) const {
+    dma16(base + (int64_t)(k >> 6) * slice_bytes, voff[I], lds + wave_lds + (uint32_t)I * 4096u);
+  }
+  template <int I> __device__ __forceinline__ void aim(uint32_t lds) const { dma16_aim(lds + wave_lds + (uint32_t)I * 4096u); }
+  template <int I> __device__ __forceinline__ void go(int k) const { dma16_go(base + (int64_t)(k >> 6) * slice_bytes, voff[I]); }
+};
+
+// fragment j of k-step ks from an [64 k][R rows] tile: byte offset of this lane's first read (the second is
+// 4 k-rows further)
+template <int R> __device__ __forceinline__ uint32_t mn_frag_byte(int row0, int lane) {
+  const int s = lane & 15, grp = lane >> 4;
+  return (uint32_t)LdsMN64<R>::byte_of(row0 + 16 * (grp & 1) + 4 * (s & 3), 8 * (grp >> 1) + (s >> 2));
+}
+__device__ __forceinline__ bf16x8 mn_frag_read(const unsigned char* tile, uint32_t lane_byte, int ks, int R2) {
+  typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+  const unsigned char* p = tile + lane_byte + ks * 16 * R2;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * R2));
+  union { struct { s16x4 l, h; } s; bf16x8 v; } u;
+  u.s.l = lo; u.s.h = hi;
+  return u.v;
+}
+
+template <int EPI, int BM, int BN> struct GemmDma64Smem {
+  static constexpr int STAGE = (BM + BN) * 64 * 2;
+  static constexpr int MAIN = 2 * STAGE;
+  static constexpr int CT = EPI == kEpiFwd ? FwdEpiLds<uint16_t, BM, BN>::BYTES : BM * (BN + 8) * 2;
+  static constexpr int BYTES = CT > MAIN ? CT : MAIN;
+};
+
+template <int BKIND, int EPI, int BM, int BN>
+__global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs g) {
+  constexpr int BK = 64, TM = BM / 64, TN = BN / 64;
+  constexpr bool kBT = BKIND == kOpMN;                 // B is M/N contiguous: transposing fragment reads
+  typedef GemmDma64Smem<EPI, BM, BN> S;
+  typedef Lds64<BM> LYA; typedef Lds64<BN> LYB;
+  typedef DmaOperandK64<BM> LoadA;
+  typedef typename std::conditional<kBT, DmaOperandMN64<BN>, DmaOperandK64<BN>>::type LoadB;
+  static_assert(LoadA::NI == 8 && LoadB::NI == 8, "the schedule below places 8 + 8 loads");
+  // every piece that aims a load also reads a fragment between aiming and issuing: the M0 wait state
+  static_assert(TM + TN == 8, "one fragment read per piece");
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  uint16_t* const smem = reinterpret_cast<uint16_t*>(smem_raw);
+  const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw);
+  constexpr int kStageElems = S::STAGE / 2, kAElems = BM * BK;
+
+  const int tiles_n = g.N / BN, tiles_m = g.M / BM;
+  const int T = tiles_m * tiles_n;
+  int lin = blockIdx.x;
+  if ((T & 7) == 0) lin = (lin & 7) * (T >> 3) + (lin >> 3);
+  constexpr int GM = 4;
+  const int grp = lin / (GM * tiles_n), within = lin - grp * (GM * tiles_n);
+  const int gh = min(GM, tiles_m - grp * GM);
+  const int tm = grp * GM + within % gh, tn = within / gh;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int w = threadIdx.x >> 6;
+  const int wm0 = (w >> 1) * (BM / 2), wn0 = (w & 1) * (BN / 2);
+  const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int kbeg = g.k_splits > 1 ? (int)blockIdx.y * g.k_split : 0;
+  const int kend = g.k_splits > 1 ? min(g.K, kbeg + g.k_split) : g.K;
+  const int KT = (kend - kbeg) / BK;                   // the host sends only K ranges that are whole slices
+  LoadA la; LoadB lb;
+  la.init(g.A, g.lda, m0, kbeg);
+  lb.init(g.B, g.ldb, n0, kbeg);
+
+  // load number Q (0 .. 15) of slice s into stage st: A and B alternate
+  auto issue = [&](auto Q_, int st, int s) {
+    constexpr int Q = decltype(Q_)::value;
+    const uint32_t a_lds = smem_lds + (uint32_t)st * S::STAGE;
+    if constexpr ((Q & 1) == 0) la.template issue<Q / 2>(a_lds, s * BK);
+    else lb.template issue<Q / 2>(a_lds + kAElems * 2, s * BK);
+  };
+
+#ifndef RAD_DMA_PLACE
+#define RAD_DMA_PLACE 0
+#endif
+#if RAD_DMA_PLACE == 0      // half in k-step 3, half in k-step 0 of the next iteration
+#define RAD_K0_AIM(Q) if (more) aim(IntC<Q>(), r ^ 1);
+#define RAD_K0_DMA(Q) if (more) go(IntC<Q>(), kt + 1);
+#define RAD_K3_AIM(Q) if (more2) aim(IntC<Q>(), r);
+#define RAD_K3_DMA(Q) if (more2) go(IntC<Q>(), kt + 2);
+#else                       // all sixteen in k-step 3
+#define RAD_K0_AIM(Q)
+#define RAD_K3_AIM(Q)
+#define RAD_K0_DMA(Q)
+#define RAD_K3_DMA(Q) if (more2) { issue(IntC<2 * Q>(), r, kt + 2); issue(IntC<2 * Q + 1>(), r, kt + 2); }
+#endif
+  uint32_t bfrag[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bfrag[j] = kBT ? mn_frag_byte<BN>(wn0 + j * 32, lane) : 0u;
+  auto aim = [&](auto Q_, int st) {
+    constexpr int Q = decltype(Q_)::value;
+    const uint32_t a_lds = smem_lds + (uint32_t)st * S::STAGE;
+    if constexpr ((Q & 1) == 0) la.template aim<Q / 2>(a_lds); else lb.template aim<Q / 2>(a_lds + kAElems * 2);
+  };
+  auto go = [&](auto Q_, int s) {
+    constexpr int Q = decltype(Q_)::value;
+    if constexpr ((Q & 1) == 0) la.template go<Q / 2>(s * BK); else lb.template go<Q / 2>(s * BK);
+  };
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+#define RAD_FENCE() __builtin_amdgcn_sched_barrier(0)
+  auto body = [&](auto R_, auto STEADY_, int kt) {
+    constexpr int r = decltype(R_)::value;
+    constexpr bool steady = decltype(STEADY_)::value;
+    const uint16_t* const curA = smem + r * kStageElems; const uint16_t* const curB = curA + kAElems;
+    const uint16_t* const nxtA = smem + (r ^ 1) * kStageElems; const uint16_t* const nxtB = nxtA + kAElems;
+    // fragment readers: FA/FB destination set, stage, k-step
+    auto rd = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], const uint16_t* A_, const uint16_t* B_, int ks) {
+      return std::make_pair(
+          [&, A_, ks](int i) { if (i < TM) fa[i] = *reinterpret_cast<const bf16x8*>(&A_[LYA::unit(wm0 + i * 32 + lr, 2 * ks + lk) * 8]); },
+          [&, B_, ks](int j) {
+            if (j < TN) {
+              if constexpr (kBT) fb[j] = mn_frag_read(reinterpret_cast<const unsigned char*>(B_), bfrag[j], ks, BN * 2);
+              else fb[j] = *reinterpret_cast<const bf16x8*>(&B_[LYB::unit(wn0 + j * 32 + lr, 2 * ks + lk) * 8]);
+            }
+          });
+    };
+    const bool more = steady || kt + 1 < KT;     // slice kt+1 exists
+    const bool more2 = steady || kt + 2 < KT;    // slice kt+2 exists
+    {  // k-step 0
+      auto f = rd(fa1, fb1, curA, curB, 1);
+      RAD_K0_AIM(8) mfma_piece<0, TM, TN>(fa0, fb0, acc); frag_read<0, TM, TN>(f.first, f.second); RAD_K0_DMA(8) RAD_FENCE();
+      RAD_K0_AIM(9) mfma_piece<1, TM, TN>(fa0, fb0, acc); frag_read<1, TM, TN>(f.first, f.second); RAD_K0_DMA(9) RAD_FENCE();
+      RAD_K0_AIM(10) mfma_piece<2, TM, TN>(fa0, fb0, acc); frag_read<2, TM, TN>(f.first, f.second); RAD_K0_DMA(10) RAD_FENCE();
+      RAD_K0_AIM(11) mfma_piece<3, TM, TN>(fa0, fb0, acc); frag_read<3, TM, TN>(f.first, f.second); RAD_K0_DMA(11) RAD_FENCE();
+      RAD_K0_AIM(12) mfma_piece<4, TM, TN>(fa0, fb0, acc); frag_read<4, TM, TN>(f.first, f.second); RAD_K0_DMA(12) RAD_FENCE();
+      RAD_K0_AIM(13) mfma_piece<5, TM, TN>(fa0, fb0, acc); frag_read<5, TM, TN>(f.first, f.second); RAD_K0_DMA(13) RAD_FENCE();
+      RAD_K0_AIM(14) mfma_piece<6, TM, TN>(fa0, fb0, acc); frag_read<6, TM, TN>(f.first, f.second); RAD_K0_DMA(14) RAD_FENCE();
+      RAD_K0_AIM(15) mfma_piece<7, TM, TN>(fa0, fb0, acc); frag_read<7, TM, TN>(f.first, f.second); RAD_K0_DMA(15) RAD_FENCE();
+    }
+    {  // k-step 1
+      auto f = rd(fa0, fb0, curA, curB, 2);
+      mfma_piece<0, TM, TN>(fa1, fb1, acc); frag_read<0, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<1, TM, TN>(fa1, fb1, acc); frag_read<1, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<2, TM, TN>(fa1, fb1, acc); frag_read<2, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<3, TM, TN>(fa1, fb1, acc); frag_read<3, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<4, TM, TN>(fa1, fb1, acc); frag_read<4, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<5, TM, TN>(fa1, fb1, acc); frag_read<5, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<6, TM, TN>(fa1, fb1, acc); frag_read<6, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<7, TM, TN>(fa1, fb1, acc); frag_read<7, TM, TN>(f.first, f.second); RAD_FENCE();
+    }
+    {  // k-step 2: its fragment reads are the last of this stage and go first, two per piece
+      auto f = rd(fa1, fb1, curA, curB, 3);
+      mfma_piece<0, TM, TN>(fa0, fb0, acc); frag_read<0, TM, TN>(f.first, f.second); frag_read<1, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<1, TM, TN>(fa0, fb0, acc); frag_read<2, TM, TN>(f.first, f.second); frag_read<3, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<2, TM, TN>(fa0, fb0, acc); frag_read<4, TM, TN>(f.first, f.second); frag_read<5, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<3, TM, TN>(fa0, fb0, acc); frag_read<6, TM, TN>(f.first, f.second); frag_read<7, TM, TN>(f.first, f.second); RAD_FENCE();
+      mfma_piece<4, TM, TN>(fa0, fb0, acc); RAD_FENCE();
+      mfma_piece<5, TM, TN>(fa0, fb0, acc); RAD_FENCE();
+      mfma_piece<6, TM, TN>(fa0, fb0, acc); RAD_FENCE();
+      mfma_piece<7, TM, TN>(fa0, fb0, acc); RAD_FENCE();
+    }
+    // slice kt+1 has landed (this thread's part) and this stage is read for the last time
+    dma_wait<0>();
+    __syncthreads();
+    RAD_FENCE();
+    {  // k-step 3
+      auto f = rd(fa0, fb0, nxtA, nxtB, 0);
+      RAD_K3_AIM(0) mfma_piece<0, TM, TN>(fa1, fb1, acc); if (more) frag_read<0, TM, TN>(f.first, f.second); RAD_K3_DMA(0) RAD_FENCE();
+      RAD_K3_AIM(1) mfma_piece<1, TM, TN>(fa1, fb1, acc); if (more) frag_read<1, TM, TN>(f.first, f.second); RAD_K3_DMA(1) RAD_FENCE();
+      RAD_K3_AIM(2) mfma_piece<2, TM, TN>(fa1, fb1, acc); if (more) frag_read<2, TM, TN>(f.first, f.second); RAD_K3_DMA(2) RAD_FENCE();
+      RAD_K3_AIM(3) mfma_piece<3, TM, TN>(fa1, fb1, acc); if (more) frag_read<3, TM, TN>(f.first, f.second); RAD_K3_DMA(3) RAD_FENCE();
+      RAD_K3_AIM(4) mfma_piece<4, TM, TN>(fa1, fb1, acc); if (more) frag_read<4, TM, TN>(f.first, f.second); RAD_K3_DMA(4) RAD_FENCE();
+      RAD_K3_AIM(5) mfma_piece<5, TM, TN>(fa1, fb1, acc); if (more) frag_read<5, TM, TN>(f.first, f.second); RAD_K3_DMA(5) RAD_FENCE();
+      RAD_K3_AIM(6) mfma_piece<6, TM, TN>(fa1, fb1, acc); if (more) frag_read<6, TM, TN>(f.first, f.second); RAD_K3_DMA(6) RAD_FENCE();
+      RAD_K3_AIM(7) mfma_piece<7, TM, TN>(fa1, fb1, acc); if (more) frag_read<7, TM, TN>(f.first, f.second); RAD_K3_DMA(7) RAD_FENCE();
+    }
+  };
+
+  // prologue: slice 0 into stage 0; its first fragments; the first half of the loads of slice 1
+  if (KT > 0) {
+    issue(IntC<0>(), 0, 0); issue(IntC<1>(), 0, 0); issue(IntC<2>(), 0, 0); issue(IntC<3>(), 0, 0);
+    issue(IntC<4>(), 0, 0); issue(IntC<5>(), 0, 0); issue(IntC<6>(), 0, 0); issue(IntC<7>(), 0, 0);
+    issue(IntC<8>(), 0, 0); issue(IntC<9>(), 0, 0); issue(IntC<10>(), 0, 0); issue(IntC<11>(), 0, 0);
+    issue(IntC<12>(), 0, 0); issue(IntC<13>(), 0, 0); issue(IntC<14>(), 0, 0); issue(IntC<15>(), 0, 0);
+  }
+  dma_wait<0>();
+  __syncthreads();
+  RAD_FENCE();
+  if (KT > 0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa0[i] = *reinterpret_cast<const bf16x8*>(&smem[LYA::unit(wm0 + i * 32 + lr, lk) * 8]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      if constexpr (kBT) fb0[j] = mn_frag_read(reinterpret_cast<const unsigned char*>(smem + kAElems), bfrag[j], 0, BN * 2);
+      else fb0[j] = *reinterpret_cast<const bf16x8*>(&smem[kAElems + LYB::unit(wn0 + j * 32 + lr, lk) * 8]);
+    }
+  }
+  if (KT > 1) {
+    issue(IntC<0>(), 1, 1); issue(IntC<1>(), 1, 1); issue(IntC<2>(), 1, 1); issue(IntC<3>(), 1, 1);
+    issue(IntC<4>(), 1, 1); issue(IntC<5>(), 1, 1); issue(IntC<6>(), 1, 1); issue(IntC<7>(), 1, 1);
+#if RAD_DMA_PLACE != 0
+    issue(IntC<8>(), 1, 1); issue(IntC<9>(), 1, 1); issue(IntC<10>(), 1, 1); issue(IntC<11>(), 1, 1);
+    issue(IntC<12>(), 1, 1); issue(IntC<13>(), 1, 1); issue(IntC<14>(), 1, 1); issue(IntC<15>(), 1, 1);
+#endif
+  }
+  RAD_FENCE();
+
+  int kt = 0;
+  if (KT > 3) {
+    do {                                   // both iterations find slices kt+1 and kt+2: kt + 1 + 2 < KT
+      body(IntC<0>(), std::true_type(), kt);
+      body(IntC<1>(), std::true_type(), kt + 1);
+      kt += 2;
+    } while (kt + 3 < KT);
+  }
+  for (; kt < KT; kt += 2) {               // drain; kt is even here
+    body(IntC<0>(), std::false_type(), kt);
+    if (kt + 1 < KT) body(IntC<1>(), std::false_type(), kt + 1);
+  }
+#undef RAD_FENCE
+  // every wave is past the last barrier only after all its reads of the stages; nothing is in flight
+  __syncthreads();
+  if constexpr (EPI == kEpiStore) {
+    epilogue_dx_staged<BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
+  } else {
+    epilogue_fwd<uint16_t, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
+  }
+}
+
+}  // namespace rad

@@ -1,6 +1,7 @@
 // Launch helper shared by the GEMM instantiation files.
 #pragma once
 #include "gemm_bf16.hpp"
+#include "gemm_bf16_dma.hpp"
 
 namespace rad {
 
@@ -66,6 +67,41 @@ hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, g.k_splits > 1 ? g.k_splits : 1), dim3(kGemmThreads), smem, st, g);
+  return hipGetLastError();
+}
+
+// ---- bf16 kernels whose K-contiguous operands go from global memory straight into LDS.  Interior shapes only:
+// whole tiles, K a whole number of slices, rows 16-byte aligned, no loader masks.
+template <int BKIND, int BM, int BN>
+bool gemm_dma_ok(const GemmArgs& g) {
+  if (g.a_mask || g.b_mask || !gemm_is_full<BF16Tag, kOpK, BM, BN, 32>(g)) return false;
+  if (g.k_splits > 1 && g.k_split % 32 != 0) return false;
+  if (BKIND == kOpMN && (g.K % 64 != 0 || (g.k_splits > 1 && g.k_split % 64 != 0))) return false;
+  // per-thread offsets inside a tile are 32-bit byte offsets
+  const int64_t b_rows = BKIND == kOpMN ? 64 : BN;
+  return (int64_t)BM * g.lda * 2 < (int64_t(1) << 32) && b_rows * g.ldb * 2 < (int64_t(1) << 32);
+}
+template <int BKIND, int EPI, int BM, int BN>
+hipError_t run_gemm_dma(const GemmArgs& g, hipStream_t st) {
+  if (g.dry_run) return hipSuccess;
+  // 64-deep slices when every K range is a whole number of them (always, for an M/N-contiguous B)
+  const bool deep = BKIND == kOpMN || (g.K % 64 == 0 && (g.k_splits <= 1 || g.k_split % 64 == 0));
+  void (*kern)(GemmArgs) = gemm_dma64_bf16_kernel<BKIND, EPI, BM, BN>;
+  int smem = GemmDma64Smem<EPI, BM, BN>::BYTES;
+  if constexpr (BKIND == kOpK) {
+    if (!deep) { kern = gemm_dma_bf16_kernel<EPI, BM, BN>; smem = GemmDmaSmem<EPI, BM, BN>::BYTES; }
+  }
+  static_assert(GemmDma64Smem<EPI, BM, BN>::BYTES <= 160 * 1024 && GemmDmaSmem<EPI, BM, BN>::BYTES <= 160 * 1024,
+                "tile does not fit the 160 KB LDS of a gfx950 CU");
+  static bool prepared[2] = {false, false};   // one host thread drives a context
+  if (!prepared[deep]) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    prepared[deep] = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((g.M / BM) * (g.N / BN), g.k_splits > 1 ? g.k_splits : 1), dim3(kGemmThreads), smem,
+                     st, g);
   return hipGetLastError();
 }
 
