@@ -29,12 +29,45 @@ constexpr int kBK3 = 32;
 // 16 bytes of zeros in device memory: what an out-of-bounds vector load of the ragged variants reads
 static __device__ __align__(16) const uint32_t kZeroChunk[4] = {0u, 0u, 0u, 0u};
 
+// An operand stored with its M/N index contiguous (element (row, k) at p[k*ld + row]) goes to LDS as it lies
+// in memory, k-row by k-row, and is transposed on the way to the registers by ds_read_b64_tr_b16: within 16
+// lanes, lane j receives in element e what lane 4e + j/4 addressed as its element j%4.  With source lane s
+// pointing at k-row s/4, rows 4(s%4) .. 4(s%4)+3 of a 16-row block, lane j ends up with rows j, k = 0 .. 3:
+// two such reads give the 8 consecutive k of an MFMA fragment.
+//   LDS tile: [k][R rows], a k-row is R*2 bytes = R/8 chunks of 16 bytes; chunk c of k-row k sits at
+// position c ^ 4(k%4), so the four k-rows one read touches fall into different 64-byte bank windows.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+template <int R> struct LdsMN {
+  static_assert(R == 256, "a k-row is 32 chunks: two k-rows per load instruction");
+  static __host__ __device__ __forceinline__ constexpr int byte_of(int row, int k) {
+    return k * (R * 2) + (((row >> 3) ^ (4 * (k & 3))) << 4) + (row & 7) * 2;
+  }
+};
+
+// fragment of k-step ks from a [k][R rows] tile: byte offset of this lane's first read (the second is
+// 4 k-rows further)
+template <int R> __device__ __forceinline__ uint32_t mn_frag_byte(int row0, int lane) {
+  const int s = lane & 15, grp = lane >> 4;
+  return (uint32_t)LdsMN<R>::byte_of(row0 + 16 * (grp & 1) + 4 * (s & 3), 8 * (grp >> 1) + (s >> 2));
+}
+__device__ __forceinline__ bf16x8 mn_frag_read(const unsigned char* tile, uint32_t lane_byte, int ks, int R2) {
+  typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+  const unsigned char* p = tile + lane_byte + ks * 16 * R2;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * R2));
+  union { struct { s16x4 l, h; } s; bf16x8 v; } u;
+  u.s.l = lo; u.s.h = hi;
+  return u.v;
+}
+
+
 // ------------------------------------------------------------------ loaders
 // dense, K contiguous: element (row, k) at p[row*ld + k]
 // EMODE: 0 = interior (no guards), 1 = ragged but every access a whole in-bounds or out-of-bounds 16-byte
 // vector (guard by clamping the address and zeroing), 2 = generic element-wise guards.
 template <int R, int EMODE, bool MASKED, int NS> struct RingLoadK {
   typedef LdsBF16<R, kBK3> L;
+  static constexpr bool kTr = false;
   static constexpr int TOTAL = R * L::CH;
   static constexpr int NCH = (TOTAL + kGemmThreads - 1) / kGemmThreads;
   static constexpr int kDsWrites = NCH, kVmemReads = NCH * (MASKED ? 2 : 1);
@@ -105,6 +138,7 @@ template <int R, int EMODE, bool MASKED, int NS> struct RingLoadK {
 // of predicates) and transposes it in registers: LDS receives, for each of the 8 rows, KPT consecutive k.
 template <int R, int EMODE, bool MASKED, int NS> struct RingLoadMN {
   typedef LdsBF16<R, kBK3> L;
+  static constexpr bool kTr = false;
   static constexpr int RB = R / 8;               // row blocks
   static constexpr int KPT = R / 64;             // k rows per thread
   static_assert(RB * (kBK3 / KPT) == kGemmThreads, "one block per thread");
@@ -190,6 +224,43 @@ template <int R, int EMODE, bool MASKED, int NS> struct RingLoadMN {
   }
 };
 
+// dense, M/N contiguous, kept in LDS as it lies in memory (LdsMN) and transposed by the fragment reads: no
+// transposition in registers, four 16-byte LDS writes per thread and slice.  256-row tiles, whole vectors only.
+template <int R, int EMODE, int NS> struct RingLoadMNT {
+  static_assert(R == 256 && EMODE < 2, "interior and vector-predicated variants of 256-row tiles");
+  static constexpr bool kTr = true;
+  static constexpr int NCH = 4;                  // 32 k-rows x 32 chunks over 256 threads
+  static constexpr int kDsWrites = NCH, kVmemReads = NCH, kValuCommit = 0, kValuFetch = 0;
+  u32x4 v[NS][NCH];
+  const uint16_t* p; uint32_t ld; int r0, rmax, K;
+  __device__ __forceinline__ void init(const void* ptr, int64_t ld_, const uint32_t*, int, int r0_, int rmax_, int K_,
+                                       const StoreView&) {
+    p = static_cast<const uint16_t*>(ptr); ld = (uint32_t)ld_; r0 = r0_; rmax = rmax_; K = K_;
+  }
+  __device__ __forceinline__ void bounds(int) {}
+  __device__ __forceinline__ void configure(int) {}
+  template <int SLOT, bool KTAIL = true> __device__ __forceinline__ void fetch(int k0) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int q = i * kGemmThreads + (int)threadIdx.x;
+      const int gk = k0 + (q >> 5), gr = r0 + (q & 31) * 8;
+      if (EMODE == 0) {
+        v[SLOT][i] = *reinterpret_cast<const u32x4*>(p + ((uint32_t)gk * ld + (uint32_t)gr));
+      } else {
+        // as in the K-contiguous loader: chunks past the edge read the last valid chunk, k-rows past K read zeros
+        const int grc = min(gr, rmax - 8);
+        const bool ok = !KTAIL || gk < K;
+        const uint16_t* src = p + ((uint32_t)gk * ld + (uint32_t)grc);
+        v[SLOT][i] = *reinterpret_cast<const u32x4*>(ok ? src : reinterpret_cast<const uint16_t*>(kZeroChunk));
+      }
+    }
+  }
+  template <int SLOT, int STEP> __device__ __forceinline__ void commit_step(uint16_t* lds) {
+    const int q = STEP * kGemmThreads + (int)threadIdx.x;
+    *reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(lds) + LdsMN<R>::byte_of((q & 31) * 8, q >> 5)) = v[SLOT][STEP];
+  }
+};
+
 // compressed store as the A operand of dW: K index = store row (example b),
 // M index = column j.  The LDS tile is [row j][k b]; wave w owns the k columns
 // [8w, 8w+8), one 16-byte unit of every tile row: it clears them and scatters
@@ -198,6 +269,7 @@ template <int R, int EMODE, bool MASKED, int NS> struct RingLoadMN {
 template <int R, int SE, int NS> struct RingLoadSparse {
   static_assert(R == kBucket && kBK3 == 32, "a tile is one bucket of the store; entries carry the 32-deep tile layout");
   typedef LdsBF16<R, kBK3> L;
+  static constexpr bool kTr = false;
   static constexpr int RPW = kBK3 / 4;          // store rows per wave
   static constexpr int LPR = 64 / RPW;          // lanes per store row
   static constexpr int NZ = R / 64;             // clearing stores per lane
@@ -269,7 +341,13 @@ template <int R, int SE, int NS> struct RingLoadSparse {
 
 template <int KIND, int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf;
 template <int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf<kOpK, R, SE, EMODE, MASKED, NS> { typedef RingLoadK<R, EMODE, MASKED, NS> type; };
-template <int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf<kOpMN, R, SE, EMODE, MASKED, NS> { typedef RingLoadMN<R, EMODE, MASKED, NS> type; };
+template <int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf<kOpMN, R, SE, EMODE, MASKED, NS> {
+  static constexpr bool kT = R == 256 && EMODE < 2 && !MASKED;
+  // (the transposing-read loader is only named when it is the one chosen: its static_asserts)
+  template <bool T, int DUMMY = 0> struct Pick { typedef RingLoadMN<R, EMODE, MASKED, NS> type; };
+  template <int DUMMY> struct Pick<true, DUMMY> { typedef RingLoadMNT<R, EMODE < 2 ? EMODE : 0, NS> type; };
+  typedef typename Pick<kT>::type type;
+};
 template <int R, int SE, int EMODE, bool MASKED, int NS> struct RingLoaderOf<kOpSparse, R, SE, EMODE, MASKED, NS> { typedef RingLoadSparse<R, SE, NS> type; };
 
 template <class LD, int SLOT> __device__ __forceinline__ void commit_all(LD& l, uint16_t* lds) {
@@ -278,17 +356,22 @@ template <class LD, int SLOT> __device__ __forceinline__ void commit_all(LD& l, 
 }
 
 // ------------------------------------------------------------------ MFMA side
-template <int TM, int TN, int BM, int BN>
+// one 32 x 16 fragment of k-step ks (0 or 1) of a 32-deep tile of R rows: a 16-byte read from the K-contiguous
+// layout, or two transposing reads from the M/N-contiguous one (tr_byte: this lane's offset for the fragment)
+template <bool TR, int R>
+__device__ __forceinline__ bf16x8 read_frag32(const uint16_t* tile, int row0, uint32_t tr_byte, int ks, int lr, int lk) {
+  if constexpr (TR) return mn_frag_read(reinterpret_cast<const unsigned char*>(tile), tr_byte, ks, R * 2);
+  else return *reinterpret_cast<const bf16x8*>(&tile[LdsBF16<R, kBK3>::unit(row0 + lr, ks * 2 + lk) * 8]);
+}
+template <int TM, int TN, int BM, int BN, bool AT = false, bool BT = false>
 __device__ __forceinline__ void load_frags32(const uint16_t* As, const uint16_t* Bs, int ks, int wm0, int wn0,
-                                             bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
-  typedef LdsBF16<BM, kBK3> LA; typedef LdsBF16<BN, kBK3> LB;
+                                             bf16x8 (&a)[TM], bf16x8 (&b)[TN], const uint32_t* atr = nullptr,
+                                             const uint32_t* btr = nullptr) {
   const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
-    a[i] = *reinterpret_cast<const bf16x8*>(&As[LA::unit(wm0 + i * 32 + lr, ks * 2 + lk) * 8]);
+  for (int i = 0; i < TM; ++i) a[i] = read_frag32<AT, BM>(As, wm0 + i * 32, AT ? atr[i] : 0u, ks, lr, lk);
 #pragma unroll
-  for (int j = 0; j < TN; ++j)
-    b[j] = *reinterpret_cast<const bf16x8*>(&Bs[LB::unit(wn0 + j * 32 + lr, ks * 2 + lk) * 8]);
+  for (int j = 0; j < TN; ++j) b[j] = read_frag32<BT, BN>(Bs, wn0 + j * 32, BT ? btr[j] : 0u, ks, lr, lk);
 }
 
 // fragments of k-step 1 of the current stage, alternated with the four commit
@@ -430,6 +513,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
   typedef typename RingLoaderOf<AK, BM, SE, EMODE, (FLAGS & kFlagMaskA) != 0, NS>::type LoadA;
   typedef typename RingLoaderOf<BKIND, BN, SE, EMODE, (FLAGS & kFlagMaskB) != 0, NS>::type LoadB;
   constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr bool kAT = LoadA::kTr, kBT = LoadB::kTr;   // fragments of that operand come from transposing reads
   extern __shared__ __align__(16) unsigned char smem_raw[];
   uint16_t* const smem = reinterpret_cast<uint16_t*>(smem_raw);
   constexpr int kStageElems = S::STAGE / 2;
@@ -452,6 +536,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
   const int m0 = tm * BM, n0 = tn * BN;
   const int w = threadIdx.x >> 6;
   const int wm0 = (w >> 1) * (BM / 2), wn0 = (w & 1) * (BN / 2);
+  uint32_t atr[TM], btr[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { if constexpr (kAT) atr[i] = mn_frag_byte<BM>(wm0 + i * 32, (int)(threadIdx.x & 63)); else atr[i] = 0u; }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) { if constexpr (kBT) btr[j] = mn_frag_byte<BN>(wn0 + j * 32, (int)(threadIdx.x & 63)); else btr[j] = 0u; }
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -487,7 +576,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       la.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK); lb.template fetch<sl, false>(kbeg + (kt + 2 + NS) * BK);
       la.bounds(kbeg + (kt + 3 + NS) * BK);
       mfma_step<TM, TN>(fa0, fb0, acc);
-      load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
+      load_frags32<TM, TN, BM, BN, kAT, kBT>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0, atr, btr);
       mfma_step<TM, TN>(fa1, fb1, acc);
       constexpr int kPairs = TM * TN / 2;             // MFMA pairs per half
       constexpr int kDsw = (LoadA::kDsWrites + LoadB::kDsWrites + kPairs - 1) / kPairs;
@@ -512,14 +601,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       // followed by its share of LDS reads, LDS writes, address arithmetic and global loads whatever the
       // loaders look like (group hints alone left the commit work of the transposing and sparse loaders in
       // one burst with no MFMA in flight).
-      typedef LdsBF16<BM, kBK3> LYA; typedef LdsBF16<BN, kBK3> LYB;
       const int lane_ = threadIdx.x & 63, lr_ = lane_ & 31, lk_ = lane_ >> 5;
       const uint16_t* const curA = cur; const uint16_t* const curB = cur + kAElems;
       const uint16_t* const nxtA = nxt; const uint16_t* const nxtB = nxt + kAElems;
-      auto ra1 = [&](int i) { if (i < TM) fa1[i] = *reinterpret_cast<const bf16x8*>(&curA[LYA::unit(wm0 + i * 32 + lr_, 2 + lk_) * 8]); };
-      auto rb1 = [&](int j) { if (j < TN) fb1[j] = *reinterpret_cast<const bf16x8*>(&curB[LYB::unit(wn0 + j * 32 + lr_, 2 + lk_) * 8]); };
-      auto ra0 = [&](int i) { if (i < TM) fa0[i] = *reinterpret_cast<const bf16x8*>(&nxtA[LYA::unit(wm0 + i * 32 + lr_, lk_) * 8]); };
-      auto rb0 = [&](int j) { if (j < TN) fb0[j] = *reinterpret_cast<const bf16x8*>(&nxtB[LYB::unit(wn0 + j * 32 + lr_, lk_) * 8]); };
+      auto ra1 = [&](int i) { if (i < TM) fa1[i] = read_frag32<kAT, BM>(curA, wm0 + i * 32, atr[i < TM ? i : 0], 1, lr_, lk_); };
+      auto rb1 = [&](int j) { if (j < TN) fb1[j] = read_frag32<kBT, BN>(curB, wn0 + j * 32, btr[j < TN ? j : 0], 1, lr_, lk_); };
+      auto ra0 = [&](int i) { if (i < TM) fa0[i] = read_frag32<kAT, BM>(nxtA, wm0 + i * 32, atr[i < TM ? i : 0], 0, lr_, lk_); };
+      auto rb0 = [&](int j) { if (j < TN) fb0[j] = read_frag32<kBT, BN>(nxtB, wn0 + j * 32, btr[j < TN ? j : 0], 0, lr_, lk_); };
       uint16_t* const wrA = wr; uint16_t* const wrB = wr + kAElems;
 #define RAD_FENCE() __builtin_amdgcn_sched_barrier(0)
       // first half: MFMAs of k-step 0; fragments of k-step 1; slice kt+2 into its stage; loads of slice kt+2+NS.
@@ -546,14 +634,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       mfma_piece<7, TM, TN>(fa1, fb1, acc); frag_read<7, TM, TN>(ra0, rb0); RAD_FENCE();
 #undef RAD_FENCE
     } else {
-      load_frags32<TM, TN, BM, BN>(cur, cur + kAElems, 1, wm0, wn0, fa1, fb1);
+      load_frags32<TM, TN, BM, BN, kAT, kBT>(cur, cur + kAElems, 1, wm0, wn0, fa1, fb1, atr, btr);
       if (kt + 2 < KT) { commit_all<LoadA, sl>(la, wr); commit_all<LoadB, sl>(lb, wr + kAElems); }
       mfma_step<TM, TN>(fa0, fb0, acc);
       if (kt + 2 + NS < KT) {
         la.template fetch<sl>(kbeg + (kt + 2 + NS) * BK); lb.template fetch<sl>(kbeg + (kt + 2 + NS) * BK);
         la.bounds(kbeg + (kt + 3 + NS) * BK);
       }
-      if (kt + 1 < KT) load_frags32<TM, TN, BM, BN>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0);
+      if (kt + 1 < KT) load_frags32<TM, TN, BM, BN, kAT, kBT>(nxt, nxt + kAElems, 0, wm0, wn0, fa0, fb0, atr, btr);
       mfma_step<TM, TN>(fa1, fb1, acc);
     }
     __syncthreads();
@@ -588,7 +676,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
-    load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
+    load_frags32<TM, TN, BM, BN, kAT, kBT>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0, atr, btr);
     // steady state, inside this branch so that the loop is entered only with the loads of the
     // prologue above in flight (the wait counts in the loop are fixed from every path that reaches it)
     do {                                // all three iterations fetch a whole slice (kt+2+2+NS < KTs)
@@ -615,7 +703,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
       if (KT > 4) { la.template fetch<2>(kbeg + 4 * BK); lb.template fetch<2>(kbeg + 4 * BK); la.bounds(kbeg + 5 * BK); }
     }
     __syncthreads();
-    if (KT > 0) load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
+    if (KT > 0) load_frags32<TM, TN, BM, BN, kAT, kBT>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0, atr, btr);
   }
 
   for (; kt < KT; kt += 3) {          // drain; kt is a multiple of 3 here

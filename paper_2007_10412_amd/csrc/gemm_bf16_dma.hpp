@@ -254,22 +254,8 @@ template <int R> struct DmaOperandK64 {
   }
 };
 
-// An operand stored with its M/N index contiguous (element (row, k) at p[k*ld + row]) goes to LDS as it lies
-// in memory, k-row by k-row, and is transposed on the way to the registers by ds_read_b64_tr_b16: within 16
-// lanes, lane j receives in element e what lane 4e + j/4 addressed as its element j%4.  With source lane s
-// pointing at k-row s/4, rows 4(s%4) .. 4(s%4)+3 of a 16-row block, lane j ends up with rows j, k = 0 .. 3:
-// two such reads give the 8 consecutive k of an MFMA fragment.
-//   LDS tile: [64 k][R rows], a k-row is R*2 bytes = R/8 chunks of 16 bytes; chunk c of k-row k sits at
-// position c ^ 4(k%4), so the four k-rows one read touches fall into different 64-byte bank windows.
-// A load instruction fills two k-rows (1 KB); load I of wave w fills k-rows 2(4I + w), 2(4I + w) + 1.
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-template <int R> struct LdsMN64 {
-  static_assert(R == 256, "a k-row is 32 chunks: two k-rows per load instruction");
-  static __host__ __device__ __forceinline__ constexpr int byte_of(int row, int k) {
-    return k * (R * 2) + (((row >> 3) ^ (4 * (k & 3))) << 4) + (row & 7) * 2;
-  }
-};
-
+// M/N-contiguous operand (LdsMN layout, 64 k-rows): a load instruction fills two k-rows (1 KB); load I of
+// wave w fills k-rows 2(4I + w) and 2(4I + w) + 1.
 template <int R> struct DmaOperandMN64 {
   static constexpr int NI = 8;
   uint32_t voff[NI];
@@ -294,22 +280,6 @@ template <int R> struct DmaOperandMN64 {
   template <int I> __device__ __forceinline__ void aim(uint32_t lds) const { dma16_aim(lds + wave_lds + (uint32_t)I * 4096u); }
   template <int I> __device__ __forceinline__ void go(int k) const { dma16_go(base + (int64_t)(k >> 6) * slice_bytes, voff[I]); }
 };
-
-// fragment j of k-step ks from an [64 k][R rows] tile: byte offset of this lane's first read (the second is
-// 4 k-rows further)
-template <int R> __device__ __forceinline__ uint32_t mn_frag_byte(int row0, int lane) {
-  const int s = lane & 15, grp = lane >> 4;
-  return (uint32_t)LdsMN64<R>::byte_of(row0 + 16 * (grp & 1) + 4 * (s & 3), 8 * (grp >> 1) + (s >> 2));
-}
-__device__ __forceinline__ bf16x8 mn_frag_read(const unsigned char* tile, uint32_t lane_byte, int ks, int R2) {
-  typedef __attribute__((address_space(3))) s16x4* lds_ptr;
-  const unsigned char* p = tile + lane_byte + ks * 16 * R2;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * R2));
-  union { struct { s16x4 l, h; } s; bf16x8 v; } u;
-  u.s.l = lo; u.s.h = hi;
-  return u.v;
-}
 
 template <int EPI, int BM, int BN> struct GemmDma64Smem {
   static constexpr int STAGE = (BM + BN) * 64 * 2;
@@ -386,7 +356,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
 #endif
   uint32_t bfrag[TN];
 #pragma unroll
-  for (int j = 0; j < TN; ++j) bfrag[j] = kBT ? mn_frag_byte<BN>(wn0 + j * 32, lane) : 0u;
+  for (int j = 0; j < TN; ++j) { if constexpr (kBT) bfrag[j] = mn_frag_byte<BN>(wn0 + j * 32, lane); else bfrag[j] = 0u; }
   auto aim = [&](auto Q_, int st) {
     constexpr int Q = decltype(Q_)::value;
     const uint32_t a_lds = smem_lds + (uint32_t)st * S::STAGE;

@@ -1,0 +1,74 @@
+"""GPU parity of the bf16 GEMM kernels that load global memory straight into LDS: wide interior shapes of
+rad_forward_sample (K-contiguous x, M/N-contiguous W read through transposing LDS reads) and of
+rad_backward_dX (two K-contiguous operands) against the oracle, over contraction lengths that end the
+pipeline at every point: one slice, odd and even slice counts, 32- and 64-deep slices."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import rad_oracle as R
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2007_10412_amd import binding as B
+    c = B.rad_ctx_create()
+    yield c
+    B.rad_ctx_destroy(c)
+
+
+def bf16_data(rng, shape, scale=1.0):
+    # values exactly representable in bf16, so that both sides start from the same numbers
+    return R.round_bf16((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+@pytest.mark.parametrize("d_in", [64, 128, 192, 320, 1024])
+@pytest.mark.parametrize("relu", [False, True])
+def test_forward_wide_layer(ctx, d_in, relu):
+    """128 output tiles of 256 x 256: y, and the ReLU bits, of a 2048 x d_in x 4096 layer."""
+    from paper_2007_10412_amd import binding as B
+    from tests.gpu_util import dev, host, empty, unpack_bits, rel_err, assert_bits_match, TOL
+    Bt, N = 2048, 4096
+    rng = np.random.default_rng(100 + d_in)
+    x = bf16_data(rng, (Bt, d_in))
+    W = bf16_data(rng, (d_in, N), 1.0 / np.sqrt(d_in))
+    bias = rng.standard_normal(N).astype(np.float32)
+    print("forward B=%d D=%d N=%d relu=%d" % (Bt, d_in, N, relu), flush=True)
+    L = B.make_layer(Bt, d_in, N, dtype=B.RAD_BF16, relu=relu, has_bias=True)
+    st = B.rad_store_create(ctx, L, B.RAD_FIXEDK_PER_EXAMPLE, 0.25)
+    try:
+        y = empty((Bt, N), B.RAD_BF16)
+        B.rad_forward_sample(ctx, L, B.make_sampling(B.RAD_FIXEDK_PER_EXAMPLE, 0.25, 7), dev(x, B.RAD_BF16),
+                             dev(W, B.RAD_BF16), dev(bias), y, st)
+        h, oy, _ = R.linear_forward(x, W, bias, relu, B.RAD_BF16)
+        assert rel_err(host(y), oy) < TOL[B.RAD_BF16]
+        # element by element: bf16 rounding of an fp32 sum of d_in products
+        assert np.max(np.abs(host(y) - oy)) <= 2.0 ** -7 * max(1.0, np.max(np.abs(oy)))
+        if relu:
+            bits = unpack_bits(B.rad_store_export_bits(ctx, st, Bt, N), N)
+            assert_bits_match(bits, h, "relu bits")
+    finally:
+        B.rad_store_destroy(st)
+
+
+@pytest.mark.parametrize("d_out", [32, 64, 96, 128, 160, 192, 256, 288, 448])
+def test_dX_wide_layer(ctx, d_out):
+    """128 output tiles of 256 x 256: dX = dy W^T for a 2048 x 4096 x d_out layer without ReLU."""
+    from paper_2007_10412_amd import binding as B
+    from tests.gpu_util import dev, host, empty, rel_err, TOL
+    Bt, D = 2048, 4096
+    rng = np.random.default_rng(200 + d_out)
+    dy = bf16_data(rng, (Bt, d_out))
+    W = bf16_data(rng, (D, d_out), 1.0 / np.sqrt(d_out))
+    print("dX B=%d D=%d N=%d" % (Bt, D, d_out), flush=True)
+    L = B.make_layer(Bt, D, d_out, dtype=B.RAD_BF16, relu=False)
+    st = B.rad_store_create(ctx, L, B.RAD_FIXEDK_PER_EXAMPLE, 0.1)
+    try:
+        dX = empty((Bt, D), B.RAD_BF16)
+        B.rad_backward_dX(ctx, L, st, dev(dy, B.RAD_BF16), dev(W, B.RAD_BF16), dX)
+        want = R.backward_dX(dy, np.ones((Bt, d_out), dtype=bool), W)
+        assert rel_err(host(dX), want) < TOL[B.RAD_BF16]
+        assert np.max(np.abs(host(dX) - want)) <= 2.0 ** -7 * max(1.0, np.max(np.abs(want)))
+    finally:
+        B.rad_store_destroy(st)
