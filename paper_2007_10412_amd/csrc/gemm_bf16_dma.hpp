@@ -1,6 +1,9 @@
-// bf16 GEMM for two K-contiguous operands whose tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4): no staging registers, no LDS store instructions, no address arithmetic in
-// the loop.
+// bf16 GEMMs whose operand tiles go from global memory straight into LDS (global_load_lds_dwordx4): no
+// staging registers, no LDS store instructions, no address arithmetic in the loop.  Interior shapes of
+// 256 x 256 tiles only; everything else takes the register-staged ring kernels.  Two kernels: the main one
+// further down walks K in slices of 64 through two stages and takes K- and M/N-contiguous operands; the one
+// right below walks two K-contiguous operands in slices of 32 through four stages and serves contraction
+// lengths that are an odd multiple of 32.
 //
 // A load instruction writes the 64 x 16 bytes of its wave to consecutive LDS addresses starting at M0,
 // so the tile layout is produced by choosing which global chunk each lane asks for: lane l of the load
@@ -32,14 +35,7 @@ template <int EPI, int BM, int BN> struct GemmDmaSmem {
 
 // 16 bytes per lane from gbase + voff to LDS address lds + 16 * lane; gbase and lds are wave-uniform
 __device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds) {
-#ifndef RAD_DMA_MOD
-#define RAD_DMA_MOD ""
-#endif
-#ifdef RAD_DMA_NONOP
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" RAD_DMA_MOD
-#else
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" RAD_DMA_MOD
-#endif
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(voff), "s"(gbase), "s"(lds) : "memory");
 }
 // The same in two parts, for callers that put at least one other instruction between them (an M0 write
@@ -66,9 +62,6 @@ template <int R> struct DmaOperandK {
       const int u = i * kGemmThreads + (int)threadIdx.x;
       const int row = tile_row(u >> 2), kc = (u & 3) ^ tile_swz(row);    // inverse of L::unit
       voff[i] = (uint32_t)row * (uint32_t)ld * 2u + (uint32_t)kc * 16u;
-#ifdef RAD_ABL
-      if (RAD_ABL & 64) voff[i] = (uint32_t)(u >> 3) * (uint32_t)ld * 2u + (uint32_t)(u & 7) * 16u;   // timing only
-#endif
     }
     base = static_cast<const unsigned char*>(p) + ((int64_t)r0 * ld + kbeg) * 2;
     wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) * 1024u;
@@ -125,11 +118,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma_bf16_kernel(GemmArgs g)
   auto issue = [&](auto Q_, int st, int s) {
     constexpr int Q = decltype(Q_)::value;
     const uint32_t a_lds = smem_lds + (uint32_t)st * S::STAGE;
-#ifndef RAD_ABL
-#define RAD_ABL 0
-#endif
-    if (RAD_ABL & 16) s = 0;
-    if (RAD_ABL & 32) s = s & 7;
     if constexpr (Q < LoadA::NI) la.template issue<Q>(a_lds, s * BK);
     else lb.template issue<Q - LoadA::NI>(a_lds + kAElems * 2, s * BK);
   };
@@ -145,15 +133,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma_bf16_kernel(GemmArgs g)
     constexpr int s_nxt = (r + 1) % kDmaStages, s_fill = (r + 3) % kDmaStages;
     const uint16_t* const curA = smem + r * kStageElems; const uint16_t* const curB = curA + kAElems;
     const uint16_t* const nxtA = smem + s_nxt * kStageElems; const uint16_t* const nxtB = nxtA + kAElems;
-    auto ra1 = [&](int i) { if (i < TM && !(steady && (RAD_ABL & 4))) fa1[i] = *reinterpret_cast<const bf16x8*>(&curA[LYA::unit(wm0 + i * 32 + lr, 2 + lk) * 8]); };
-    auto rb1 = [&](int j) { if (j < TN && !(steady && (RAD_ABL & 4))) fb1[j] = *reinterpret_cast<const bf16x8*>(&curB[LYB::unit(wn0 + j * 32 + lr, 2 + lk) * 8]); };
+    auto ra1 = [&](int i) { if (i < TM) fa1[i] = *reinterpret_cast<const bf16x8*>(&curA[LYA::unit(wm0 + i * 32 + lr, 2 + lk) * 8]); };
+    auto rb1 = [&](int j) { if (j < TN) fb1[j] = *reinterpret_cast<const bf16x8*>(&curB[LYB::unit(wn0 + j * 32 + lr, 2 + lk) * 8]); };
     auto ra0 = [&](int i) { if (i < TM) fa0[i] = *reinterpret_cast<const bf16x8*>(&nxtA[LYA::unit(wm0 + i * 32 + lr, lk) * 8]); };
     auto rb0 = [&](int j) { if (j < TN) fb0[j] = *reinterpret_cast<const bf16x8*>(&nxtB[LYB::unit(wn0 + j * 32 + lr, lk) * 8]); };
-#ifndef RAD_ABL
-#define RAD_ABL 0
-#endif
-    const bool fill = (steady && !(RAD_ABL & 2)) || (!steady && kt + 3 < KT);
-    const bool more = (steady && !(RAD_ABL & 4)) || (!steady && kt + 1 < KT);
+    const bool fill = steady || kt + 3 < KT;
+    const bool more = steady || kt + 1 < KT;
 #define RAD_FENCE() __builtin_amdgcn_sched_barrier(0)
     // MFMAs of k-step 0 with the fragments of k-step 1, then MFMAs of k-step 1 with the first fragments of
     // slice kt+1; the loads of slice kt+3 are spread over the whole iteration, one per two pieces, so the
@@ -176,8 +161,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma_bf16_kernel(GemmArgs g)
     mfma_piece<7, TM, TN>(fa1, fb1, acc); if (more) frag_read<7, TM, TN>(ra0, rb0); RAD_FENCE();
 #undef RAD_FENCE
     // slice kt+2 must have landed before the barrier; the loads of slice kt+3, if any, stay in flight
-    if (steady && (RAD_ABL & 2)) dma_wait<0>(); else if (fill) { if (!(steady && (RAD_ABL & 8))) dma_wait<kLoads>(); } else dma_wait<0>();
-    if (!(steady && (RAD_ABL & 1))) __syncthreads();
+    if (fill) dma_wait<kLoads>(); else dma_wait<0>();
+    __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -288,13 +273,13 @@ template <int EPI, int BM, int BN> struct GemmDma64Smem {
   static constexpr int BYTES = CT > MAIN ? CT : MAIN;
 };
 
-template <int BKIND, int EPI, int BM, int BN>
+template <int AKIND, int BKIND, int EPI, int BM, int BN>
 __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs g) {
   constexpr int BK = 64, TM = BM / 64, TN = BN / 64;
-  constexpr bool kBT = BKIND == kOpMN;                 // B is M/N contiguous: transposing fragment reads
+  constexpr bool kAT = AKIND == kOpMN, kBT = BKIND == kOpMN;   // M/N contiguous: transposing fragment reads
   typedef GemmDma64Smem<EPI, BM, BN> S;
   typedef Lds64<BM> LYA; typedef Lds64<BN> LYB;
-  typedef DmaOperandK64<BM> LoadA;
+  typedef typename std::conditional<kAT, DmaOperandMN64<BM>, DmaOperandK64<BM>>::type LoadA;
   typedef typename std::conditional<kBT, DmaOperandMN64<BN>, DmaOperandK64<BN>>::type LoadB;
   static_assert(LoadA::NI == 8 && LoadB::NI == 8, "the schedule below places 8 + 8 loads");
   // every piece that aims a load also reads a fragment between aiming and issuing: the M0 wait state
@@ -340,21 +325,16 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
     else lb.template issue<Q / 2>(a_lds + kAElems * 2, s * BK);
   };
 
-#ifndef RAD_DMA_PLACE
-#define RAD_DMA_PLACE 0
-#endif
-#if RAD_DMA_PLACE == 0      // half in k-step 3, half in k-step 0 of the next iteration
+  // One load per piece: the first eight of a slice during k-step 3 of the iteration before, the other eight
+  // during k-step 0 (two per piece, all in k-step 3, measured 6 % slower).  M0 is aimed before the piece's
+  // MFMAs and the load issued after its fragment read.
 #define RAD_K0_AIM(Q) if (more) aim(IntC<Q>(), r ^ 1);
 #define RAD_K0_DMA(Q) if (more) go(IntC<Q>(), kt + 1);
 #define RAD_K3_AIM(Q) if (more2) aim(IntC<Q>(), r);
 #define RAD_K3_DMA(Q) if (more2) go(IntC<Q>(), kt + 2);
-#else                       // all sixteen in k-step 3
-#define RAD_K0_AIM(Q)
-#define RAD_K3_AIM(Q)
-#define RAD_K0_DMA(Q)
-#define RAD_K3_DMA(Q) if (more2) { issue(IntC<2 * Q>(), r, kt + 2); issue(IntC<2 * Q + 1>(), r, kt + 2); }
-#endif
-  uint32_t bfrag[TN];
+  uint32_t afrag[TM], bfrag[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { if constexpr (kAT) afrag[i] = mn_frag_byte<BM>(wm0 + i * 32, lane); else afrag[i] = 0u; }
 #pragma unroll
   for (int j = 0; j < TN; ++j) { if constexpr (kBT) bfrag[j] = mn_frag_byte<BN>(wn0 + j * 32, lane); else bfrag[j] = 0u; }
   auto aim = [&](auto Q_, int st) {
@@ -376,7 +356,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
     // fragment readers: FA/FB destination set, stage, k-step
     auto rd = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], const uint16_t* A_, const uint16_t* B_, int ks) {
       return std::make_pair(
-          [&, A_, ks](int i) { if (i < TM) fa[i] = *reinterpret_cast<const bf16x8*>(&A_[LYA::unit(wm0 + i * 32 + lr, 2 * ks + lk) * 8]); },
+          [&, A_, ks](int i) {
+            if (i < TM) {
+              if constexpr (kAT) fa[i] = mn_frag_read(reinterpret_cast<const unsigned char*>(A_), afrag[i], ks, BM * 2);
+              else fa[i] = *reinterpret_cast<const bf16x8*>(&A_[LYA::unit(wm0 + i * 32 + lr, 2 * ks + lk) * 8]);
+            }
+          },
           [&, B_, ks](int j) {
             if (j < TN) {
               if constexpr (kBT) fb[j] = mn_frag_read(reinterpret_cast<const unsigned char*>(B_), bfrag[j], ks, BN * 2);
@@ -448,7 +433,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
   RAD_FENCE();
   if (KT > 0) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa0[i] = *reinterpret_cast<const bf16x8*>(&smem[LYA::unit(wm0 + i * 32 + lr, lk) * 8]);
+    for (int i = 0; i < TM; ++i) {
+      if constexpr (kAT) fa0[i] = mn_frag_read(reinterpret_cast<const unsigned char*>(smem), afrag[i], 0, BM * 2);
+      else fa0[i] = *reinterpret_cast<const bf16x8*>(&smem[LYA::unit(wm0 + i * 32 + lr, lk) * 8]);
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       if constexpr (kBT) fb0[j] = mn_frag_read(reinterpret_cast<const unsigned char*>(smem + kAElems), bfrag[j], 0, BN * 2);
@@ -458,10 +446,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
   if (KT > 1) {
     issue(IntC<0>(), 1, 1); issue(IntC<1>(), 1, 1); issue(IntC<2>(), 1, 1); issue(IntC<3>(), 1, 1);
     issue(IntC<4>(), 1, 1); issue(IntC<5>(), 1, 1); issue(IntC<6>(), 1, 1); issue(IntC<7>(), 1, 1);
-#if RAD_DMA_PLACE != 0
-    issue(IntC<8>(), 1, 1); issue(IntC<9>(), 1, 1); issue(IntC<10>(), 1, 1); issue(IntC<11>(), 1, 1);
-    issue(IntC<12>(), 1, 1); issue(IntC<13>(), 1, 1); issue(IntC<14>(), 1, 1); issue(IntC<15>(), 1, 1);
-#endif
   }
   RAD_FENCE();
 
@@ -478,9 +462,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
     if (kt + 1 < KT) body(IntC<1>(), std::false_type(), kt + 1);
   }
 #undef RAD_FENCE
+#undef RAD_K0_AIM
+#undef RAD_K0_DMA
+#undef RAD_K3_AIM
+#undef RAD_K3_DMA
   // every wave is past the last barrier only after all its reads of the stages; nothing is in flight
   __syncthreads();
-  if constexpr (EPI == kEpiStore) {
+  if constexpr (EPI == kEpiStore && AKIND == kOpMN) {      // dW from a dense store: fp32 out
+    epilogue_store_dispatch<kOpMN, TM, TN, uint16_t, false>(g, acc, m0, n0, wm0, wn0);
+  } else if constexpr (EPI == kEpiStore) {
     epilogue_dx_staged<BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
   } else {
     epilogue_fwd<uint16_t, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);

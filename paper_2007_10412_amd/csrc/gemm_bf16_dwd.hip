@@ -7,6 +7,10 @@ hipError_t launch_gemm_bf16_dwd(const GemmArgs& g, hipStream_t st, const char** 
   // 256x256 tiles (one workgroup per CU) when they give at least half a wave of workgroups; otherwise the
   // widest tile that still gives every CU a workgroup
   if (tiles_of(g, 256, 256) >= 128) {
+    if (gemm_dma_ok<kOpMN, kOpMN, 256, 256>(g)) {
+      if (name) *name = "gemm_bf16_dw_dense_dma_256";
+      return run_gemm_dma<kOpMN, kOpMN, kEpiStore, 256, 256>(g, st);
+    }
     if (name) *name = "gemm_bf16_dw_dense_256";
     return run_gemm3<kOpMN, kOpMN, kEpiStore, 256, 256, 0, false, true>(g, st);
   }

@@ -7,9 +7,9 @@ hipError_t launch_gemm_bf16_dx(const GemmArgs& g, hipStream_t st, const char** n
   // 256x256 tiles (one workgroup per CU) when they give at least half a wave of workgroups; otherwise the
   // widest tile that still gives every CU a workgroup
   if (tiles_of(g, 256, 256) >= 128) {
-    if (gemm_dma_ok<kOpK, 256, 256>(g)) {
+    if (gemm_dma_ok<kOpK, kOpK, 256, 256>(g)) {
       if (name) *name = "gemm_bf16_dx_dma_256";
-      return run_gemm_dma<kOpK, kEpiStore, 256, 256>(g, st);
+      return run_gemm_dma<kOpK, kOpK, kEpiStore, 256, 256>(g, st);
     }
     if (name) *name = "gemm_bf16_dx_256";
     return run_gemm3<kOpK, kOpK, kEpiStore, 256, 256, 0, true, false>(g, st);

@@ -72,23 +72,25 @@ hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
 
 // ---- bf16 kernels whose K-contiguous operands go from global memory straight into LDS.  Interior shapes only:
 // whole tiles, K a whole number of slices, rows 16-byte aligned, no loader masks.
-template <int BKIND, int BM, int BN>
+template <int AKIND, int BKIND, int BM, int BN>
 bool gemm_dma_ok(const GemmArgs& g) {
-  if (g.a_mask || g.b_mask || !gemm_is_full<BF16Tag, kOpK, BM, BN, 32>(g)) return false;
+  if (g.a_mask || g.b_mask || g.row_map || g.m_load > g.M || !gemm_is_full<BF16Tag, AKIND, BM, BN, 32>(g)) return false;
   if (g.k_splits > 1 && g.k_split % 32 != 0) return false;
-  if (BKIND == kOpMN && (g.K % 64 != 0 || (g.k_splits > 1 && g.k_split % 64 != 0))) return false;
+  // an M/N-contiguous operand only has the 64-deep kernel
+  if ((AKIND == kOpMN || BKIND == kOpMN) && (g.K % 64 != 0 || (g.k_splits > 1 && g.k_split % 64 != 0))) return false;
   // per-thread offsets inside a tile are 32-bit byte offsets
-  const int64_t b_rows = BKIND == kOpMN ? 64 : BN;
-  return (int64_t)BM * g.lda * 2 < (int64_t(1) << 32) && b_rows * g.ldb * 2 < (int64_t(1) << 32);
+  const int64_t a_rows = AKIND == kOpMN ? 64 : BM, b_rows = BKIND == kOpMN ? 64 : BN;
+  return a_rows * g.lda * 2 < (int64_t(1) << 32) && b_rows * g.ldb * 2 < (int64_t(1) << 32);
 }
-template <int BKIND, int EPI, int BM, int BN>
+template <int AKIND, int BKIND, int EPI, int BM, int BN>
 hipError_t run_gemm_dma(const GemmArgs& g, hipStream_t st) {
   if (g.dry_run) return hipSuccess;
-  // 64-deep slices when every K range is a whole number of them (always, for an M/N-contiguous B)
-  const bool deep = BKIND == kOpMN || (g.K % 64 == 0 && (g.k_splits <= 1 || g.k_split % 64 == 0));
-  void (*kern)(GemmArgs) = gemm_dma64_bf16_kernel<BKIND, EPI, BM, BN>;
+  constexpr bool kAnyMN = AKIND == kOpMN || BKIND == kOpMN;
+  // 64-deep slices when every K range is a whole number of them (always, with an M/N-contiguous operand)
+  const bool deep = kAnyMN || (g.K % 64 == 0 && (g.k_splits <= 1 || g.k_split % 64 == 0));
+  void (*kern)(GemmArgs) = gemm_dma64_bf16_kernel<AKIND, BKIND, EPI, BM, BN>;
   int smem = GemmDma64Smem<EPI, BM, BN>::BYTES;
-  if constexpr (BKIND == kOpK) {
+  if constexpr (!kAnyMN) {
     if (!deep) { kern = gemm_dma_bf16_kernel<EPI, BM, BN>; smem = GemmDmaSmem<EPI, BM, BN>::BYTES; }
   }
   if constexpr (EPI == kEpiFwd) {
@@ -101,7 +103,8 @@ hipError_t run_gemm_dma(const GemmArgs& g, hipStream_t st) {
   static bool prepared[2] = {false, false};   // one host thread drives a context
   if (!prepared[deep]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       deep ? GemmDma64Smem<EPI, BM, BN>::BYTES : GemmDmaSmem<EPI, BM, BN>::BYTES);
     if (e != hipSuccess) return e;
     prepared[deep] = true;
   }

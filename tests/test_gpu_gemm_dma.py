@@ -72,3 +72,31 @@ def test_dX_wide_layer(ctx, d_out):
         assert np.max(np.abs(host(dX) - want)) <= 2.0 ** -7 * max(1.0, np.max(np.abs(want)))
     finally:
         B.rad_store_destroy(st)
+
+
+@pytest.mark.parametrize("batch", [64, 128, 192, 320, 1024])
+def test_dense_dW_wide_layer(ctx, batch):
+    """128 output tiles of 256 x 256: dW = x^T dy from an exact store (both operands M/N contiguous), and
+    its accumulating form."""
+    from paper_2007_10412_amd import binding as B
+    from tests.gpu_util import dev, host, empty, rel_err, TOL
+    D, N = 2048, 4096
+    rng = np.random.default_rng(300 + batch)
+    x = bf16_data(rng, (batch, D))
+    dy = bf16_data(rng, (batch, N))
+    W = bf16_data(rng, (D, N), 1.0 / 64)
+    print("dense dW B=%d D=%d N=%d" % (batch, D, N), flush=True)
+    L = B.make_layer(batch, D, N, dtype=B.RAD_BF16, relu=False)
+    st = B.rad_store_create(ctx, L, B.RAD_EXACT, 1.0)
+    try:
+        y = empty((batch, N), B.RAD_BF16)
+        B.rad_forward_sample(ctx, L, B.make_sampling(B.RAD_EXACT, 1.0, 1), dev(x, B.RAD_BF16), dev(W, B.RAD_BF16), None,
+                             y, st)
+        gW = empty((D, N))
+        B.rad_backward_dW(ctx, L, st, dev(dy, B.RAD_BF16), gW, None, 0.0)
+        want = R.backward_dW(x, dy, np.ones((batch, N), dtype=bool))
+        assert rel_err(host(gW), want) < 1e-5          # fp32 sums of exact bf16 products
+        B.rad_backward_dW(ctx, L, st, dev(dy, B.RAD_BF16), gW, None, 1.0)
+        assert rel_err(host(gW), 2 * want) < 1e-5
+    finally:
+        B.rad_store_destroy(st)
