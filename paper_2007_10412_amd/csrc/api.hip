@@ -1027,11 +1027,12 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
         nv = store_view(sn, 0); next = &nv;
       }
     }
-    // Large layers run one 256x256 workgroup per CU in a single wave of workgroups, so nothing overlaps an
-    // epilogue; there the pack kernel, which re-reads y at full occupancy, costs less than packing inside
-    // the epilogue with four waves per CU (measured: 15 us against 30 us for 4096 x 4096).  Small layers keep
-    // the fused form and save the launch.
-    const bool pack_after = next != nullptr && m->dtype == kBF16 && (int64_t)B * m->dims[(size_t)l + 1] >= (int64_t(1) << 22);
+    // The epilogue packs with one thread per tile row, which walks the row's kept columns one by one: fine
+    // for a few dozen per 256 columns, slow for denser samples.  Large layers run one 256x256 workgroup per
+    // CU in a single wave of workgroups, so nothing overlaps that walk; there a dense sample is packed by the
+    // pack kernel afterwards, which re-reads y at full occupancy (measured equal at a kept fraction of 0.1).
+    const bool pack_after = next != nullptr && m->dtype == kBF16 && m->stores[(size_t)l + 1]->p > 0.125 &&
+                            (int64_t)B * m->dims[(size_t)l + 1] >= (int64_t(1) << 22);
     if (pack_after) next = nullptr;
     void* y = last ? m->logits : (m->stores[(size_t)l + 1]->scheme == RAD_EXACT ? m->stores[(size_t)l + 1]->values
                                                                                  : m->act[l & 1]);

@@ -486,23 +486,20 @@ __device__ __forceinline__ void epilogue_store_dispatch(const GemmArgs& g, float
 }
 
 // LDS of the forward epilogue: the output tile in the storage dtype (row pitch padded by one 16-byte vector,
-// which keeps rows aligned and shifts banks) followed by the plan table of the tile rows.
+// which keeps rows aligned and shifts banks).
 template <typename ElemT, int BM, int BN> struct FwdEpiLds {
   static constexpr int VPL = 16 / (int)sizeof(ElemT);     // columns per 16-byte vector
   static constexpr int CP = BN + VPL;
   static constexpr int NW = BN / 32;                      // keep words per tile row
-  static constexpr int CT_BYTES = BM * CP * (int)sizeof(ElemT);
-  static constexpr int TAB_BYTES = BM * NW * 8;           // per row and keep word: the word, position of its first entry
-  static constexpr int BYTES = CT_BYTES + TAB_BYTES + BM * 4;   // + first position of every row
+  static constexpr int BYTES = BM * CP * (int)sizeof(ElemT);
 };
 
 // Forward epilogue.  The tile goes through LDS in the storage dtype, then every thread handles 16-byte
-// vectors of it (8 bf16 or 4 fp32 columns of one row): dense y is stored as whole vectors, the (y > 0) bits
-// of the vector are merged with those of the neighbouring lanes into one word of the ReLU bit array, and the
-// entries the next layer's plan keeps are written straight into its packed store.  For the latter a table
-// in LDS holds, for every tile row and 32-column word, the keep word and the store position of its first
-// kept entry (row start + entries of the row before that word), built by one thread per row before the
-// barrier; the slot of an entry is that position plus a popcount of the keep bits below it.
+// vectors of it (8 bf16 or 4 fp32 columns of one row): dense y is stored as whole vectors and the (y > 0)
+// bits of the vector are merged with those of the neighbouring lanes into one word of the ReLU bit array.
+// If the next layer's sample is packed here, thread r then walks tile row r: it loaded the row's keep words
+// and the store position of the row's first entry in this tile before the tile was staged (so those loads
+// cost no waiting), and writes the kept entries, which are consecutive in the store, one after the other.
 template <typename ElemT, int BM, int BN, int TM, int TN>
 __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[TM][TN], ElemT* ct, int m0, int n0,
                                              int wm0, int wn0) {
@@ -510,33 +507,25 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
   constexpr int CP = E::CP, NW = E::NW, VPL = E::VPL;
   constexpr int LPR = BN / VPL;                           // lanes per tile row
   constexpr int LPW = 32 / VPL;                           // lanes per 32-column word
-  static_assert(BM <= kGemmThreads, "one thread per tile row builds the plan table");
+  static_assert(BM <= kGemmThreads, "one thread per tile row packs");
   const int lane = threadIdx.x & 63;
-  u32x2* const ptab = reinterpret_cast<u32x2*>(reinterpret_cast<unsigned char*>(ct) + E::CT_BYTES);
-  uint32_t* const rbase = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(ct) + E::CT_BYTES + E::TAB_BYTES);
 
-  if (g.pack && threadIdx.x < BM) {
-    const int r = threadIdx.x, row = m0 + r;
-    uint32_t kw[NW];
+  uint32_t kw[NW];
+  uint32_t pos = 0u, row_first = 0u;
+  const bool packs = g.pack && (int)threadIdx.x < BM && m0 + (int)threadIdx.x < g.M;
 #pragma unroll
-    for (int q = 0; q < NW; ++q) kw[q] = 0u;
-    uint32_t pos = 0u;
-    rbase[r] = row < g.M ? g.next.row_ptr[row] : 0u;
-    if (row < g.M) {
-      const int prow = row * g.next.plan_row_stride;
-      const uint32_t* bm_row = g.next.bitmap + (size_t)prow * g.next.bm_pitch;
-      const int bucket = n0 / kBucket;
-      pos = g.next.row_ptr[row] + g.next.bucket_off[(size_t)prow * (g.next.nb + 1) + bucket];
-      for (int wd = bucket * (kBucket / 32); wd < n0 / 32; ++wd) pos += __popc(bm_row[wd]);
+  for (int q = 0; q < NW; ++q) kw[q] = 0u;
+  if (packs) {
+    const int row = m0 + (int)threadIdx.x;
+    const int prow = row * g.next.plan_row_stride;
+    const uint32_t* bm_row = g.next.bitmap + (size_t)prow * g.next.bm_pitch;
+    const int bucket = n0 / kBucket;
+    row_first = g.next.row_ptr[row];
+    pos = row_first + g.next.bucket_off[(size_t)prow * (g.next.nb + 1) + bucket];
+    for (int wd = bucket * (kBucket / 32); wd < n0 / 32; ++wd) pos += __popc(bm_row[wd]);
 #pragma unroll
-      for (int q = 0; q < NW; ++q)
-        if (n0 / 32 + q < g.next.bm_pitch) kw[q] = bm_row[n0 / 32 + q];
-    }
-#pragma unroll
-    for (int q = 0; q < NW; ++q) {
-      ptab[r * NW + q] = u32x2{kw[q], pos};
-      pos += __popc(kw[q]);
-    }
+    for (int q = 0; q < NW; ++q)
+      if (n0 / 32 + q < g.next.bm_pitch) kw[q] = bm_row[n0 / 32 + q];
   }
 
 #pragma unroll
@@ -574,39 +563,52 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
       else for (int e = 0; e < valid; ++e) dst[e] = re[e];
     }
     if (g.bits) {
-      uint32_t pos = 0u;
+      uint32_t pbits = 0u;
 #pragma unroll
-      for (int e = 0; e < VPL; ++e) pos |= (e < valid && get_elem(re + e) > 0.f) ? (1u << e) : 0u;
-      uint32_t word = pos << (VPL * (ch % LPW));
+      for (int e = 0; e < VPL; ++e) pbits |= (e < valid && get_elem(re + e) > 0.f) ? (1u << e) : 0u;
+      uint32_t word = pbits << (VPL * (ch % LPW));
 #pragma unroll
       for (int d = 1; d < LPW; d <<= 1) word |= (uint32_t)__shfl_xor((int)word, d);
       const int wi = col >> 5;
       if ((ch % LPW) == 0 && row < g.M && wi < g.bits_pitch) g.bits[(size_t)row * g.bits_pitch + wi] = word;
     }
-    if (g.pack && valid > 0) {
-      const u32x2 pe = ptab[r * NW + ch / LPW];
-      const int sh = VPL * (ch % LPW);
-      uint32_t kb = (pe[0] >> sh) & ((1u << valid) - 1u);
-      uint32_t p = pe[1] + __popc(pe[0] & ((1u << sh) - 1u));
-      while (kb) {
-        const int e = __ffs(kb) - 1;
-        kb &= kb - 1u;
-        if ((int64_t)p < g.next.capacity) {
-          // weight: the scale, times the draw count of the column for draws with replacement
-          const float wgt = g.next.mult
-              ? (float)g.next.mult[(size_t)(row * g.next.plan_row_stride) * g.next.mult_pitch + (p - rbase[r])] * g.next.scale
-              : g.next.scale;
-          const float yv = get_elem(re + e) * wgt;
-          if (g.next.paired) {
-            reinterpret_cast<uint32_t*>(g.next.values)[p] = pair_make(f32_to_bf16_bits(yv), col + e);
-          } else {
-            put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv);
-            if (!g.next.indices) {}
-            else if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)(col + e);
-            else if (row == 0) g.next.indices[p - g.next.row_ptr[0]] = (uint16_t)(col + e);
-          }
+  }
+
+  if (packs) {
+    const int r = (int)threadIdx.x, row = m0 + r;
+    // weights of draws with replacement: the draw count of an entry, in entry order
+    const uint16_t* mrow = g.next.mult ? g.next.mult + (size_t)(row * g.next.plan_row_stride) * g.next.mult_pitch : nullptr;
+    uint32_t p = pos;
+    const ElemT* const crow = ct + r * CP;
+    auto emit = [&](int lc, ElemT raw) {
+      const int col = n0 + lc;
+      if (col < g.N && (int64_t)p < g.next.capacity) {
+        const float wgt = mrow ? (float)mrow[p - row_first] * g.next.scale : g.next.scale;
+        const float yv = get_elem(&raw) * wgt;
+        if (g.next.paired) {
+          reinterpret_cast<uint32_t*>(g.next.values)[p] = pair_make(f32_to_bf16_bits(yv), col);
+        } else {
+          put_elem(reinterpret_cast<ElemT*>(g.next.values) + p, yv);
+          if (!g.next.indices) {}
+          else if (!g.next.idx_shared) g.next.indices[p] = (uint16_t)col;
+          else if (row == 0) g.next.indices[p - g.next.row_ptr[0]] = (uint16_t)col;
         }
-        ++p;
+      }
+      ++p;
+    };
+#pragma unroll
+    for (int q = 0; q < NW; ++q) {
+      uint32_t kb = kw[q];
+      while (kb) {
+        // four kept columns at a time, so that their LDS reads are in flight together (__ffs(0) - 1 = -1
+        // marks a slot past the last kept column)
+        int e[4]; ElemT v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { e[i] = __ffs(kb) - 1; kb &= kb - 1u; }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = crow[q * 32 + (e[i] < 0 ? 0 : e[i])];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (e[i] >= 0) emit(q * 32 + e[i], v[i]);
       }
     }
   }

@@ -93,11 +93,6 @@ hipError_t run_gemm_dma(const GemmArgs& g, hipStream_t st) {
   if constexpr (!kAnyMN) {
     if (!deep) { kern = gemm_dma_bf16_kernel<EPI, BM, BN>; smem = GemmDmaSmem<EPI, BM, BN>::BYTES; }
   }
-  if constexpr (EPI == kEpiFwd) {
-    // the plan table behind the output tile is only used when the epilogue packs
-    const int no_table = FwdEpiLds<uint16_t, BM, BN>::CT_BYTES;
-    if (!g.pack && deep && no_table >= GemmDma64Smem<EPI, BM, BN>::MAIN) smem = no_table;
-  }
   static_assert(GemmDma64Smem<EPI, BM, BN>::BYTES <= 160 * 1024 && GemmDmaSmem<EPI, BM, BN>::BYTES <= 160 * 1024,
                 "tile does not fit the 160 KB LDS of a gfx950 CU");
   static bool prepared[2] = {false, false};   // one host thread drives a context
