@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy kernel),
 # see profiles/train_step_mlp4096_bf16_hbm_traffic.txt; only for the default workload and kernel
-MEASURED_TRAFFIC = {("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_fwd_256"): 248.5e6,
+MEASURED_TRAFFIC = {("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_fwd_dma_256"): 249.8e6,
                     ("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_dw_sparse_256x256"): 156.0e6}
 HBM_PEAK = 8000.0                          # GB/s
 
