@@ -50,6 +50,59 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const T* __restrict__ z
   if (lane == 0) row_loss[row] = lab_ok ? -(ld_elem(zr + lab) - m - logf(s)) : NAN;
 }
 
+// The same for rows that are whole 16-byte vectors and at most NV of them per lane: a lane keeps its part of
+// the row in registers, so the row is read once (16-byte loads) and every exponential is taken once.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void softmax_ce_vec_kernel(const T* __restrict__ z, const int32_t* __restrict__ labels,
+                                                             int rows, int classes, T* __restrict__ dz,
+                                                             float* __restrict__ row_loss) {
+  constexpr int VPL = 16 / (int)sizeof(T);            // elements per vector
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nvec = classes / VPL;
+  const T* zr = z + (size_t)row * classes;
+  float v[NV][VPL];
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int q = lane + i * 64;
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (q < nvec) raw = *reinterpret_cast<const u32x4*>(zr + (size_t)q * VPL);
+    const T* re = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+    for (int e = 0; e < VPL; ++e) {
+      v[i][e] = q < nvec ? ld_elem(re + e) : -INFINITY;
+      m = fmaxf(m, v[i][e]);
+    }
+  }
+  m = wave_max(m);
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int e = 0; e < VPL; ++e) { v[i][e] = expf(v[i][e] - m); s += v[i][e]; }     // exp(-inf) = 0 past the row
+  s = wave_sum(s);
+  const int lab = labels[row];
+  const bool lab_ok = lab >= 0 && lab < classes;     // a bad label poisons the loss instead of the address
+  const float inv = 1.f / s, invb = 1.f / (float)rows;
+  T* dr = dz + (size_t)row * classes;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int q = lane + i * 64;
+    u32x4 out;
+    T* oe = reinterpret_cast<T*>(&out);
+#pragma unroll
+    for (int e = 0; e < VPL; ++e) {
+      float p = v[i][e] * inv;
+      if (q * VPL + e == lab) p -= 1.f;
+      st_elem(oe + e, p * invb);
+    }
+    if (q < nvec) *reinterpret_cast<u32x4*>(dr + (size_t)q * VPL) = out;
+  }
+  if (lane == 0) row_loss[row] = lab_ok ? -(ld_elem(zr + lab) - m - logf(s)) : NAN;
+}
+
 // deterministic mean of the per-example losses
 __global__ __launch_bounds__(256) void loss_mean_kernel(const float* __restrict__ row_loss, int rows,
                                                         float* __restrict__ loss) {
@@ -244,7 +297,16 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p,
 hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows, int classes, int dtype,
                              void* dlogits, float* row_loss, float* loss, hipStream_t st) {
   dim3 grid((rows + 3) / 4), block(256);
-  if (dtype == kF32)
+  const int vpl = dtype == kF32 ? 4 : 8;
+  const bool vec = classes % vpl == 0 && classes / vpl <= 128 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0 &&
+                   (reinterpret_cast<uintptr_t>(dlogits) & 15) == 0;
+  if (vec && dtype == kF32)
+    hipLaunchKernelGGL((softmax_ce_vec_kernel<float, 2>), grid, block, 0, st, (const float*)logits, labels, rows, classes,
+                       (float*)dlogits, row_loss);
+  else if (vec)
+    hipLaunchKernelGGL((softmax_ce_vec_kernel<uint16_t, 2>), grid, block, 0, st, (const uint16_t*)logits, labels, rows,
+                       classes, (uint16_t*)dlogits, row_loss);
+  else if (dtype == kF32)
     hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, block, 0, st, (const float*)logits, labels, rows, classes,
                        (float*)dlogits, row_loss);
   else
@@ -276,7 +338,7 @@ hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int 
   // workgroups walk the segments in strides when there is work
   const int segs = rows * s.nb;
   const int blocks = (segs + 3) / 4;
-  dim3 grid(blocks < 1024 ? blocks : 1024), block(256);
+  dim3 grid(blocks < 256 ? blocks : 256), block(256);
   if (dtype == kF32)
     hipLaunchKernelGGL(dw_overflow_kernel<float>, grid, block, 0, st, s, rows, (const float*)dy, N, bits, bits_pitch,
                        dW, cap, max_seg);
