@@ -572,6 +572,27 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
   GemmArgs g = gemm_zero();
   g.M = M; g.N = N; g.K = K;
   g.A = x; g.lda = ldx; g.B = W; g.ldb = N;
+  // A narrow output (the class scores) gives too few 256x256 tiles to fill the chip, and 256x64 tiles run at a
+  // fifth of the MFMA rate: split K over several workgroups per tile; each stores fp32 partial sums to an array
+  // of its own and one reduction kernel adds them, in a fixed order, with the bias.  Plain layers only.
+  const int tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  if (dtype == kBF16 && !relu && !next && u_n == 0 && tiles < 128 && K >= 2048 && N % 4 == 0) {
+    int splits = 256 / tiles;
+    if (splits > 8) splits = 8;
+    const int ks = ((K + splits - 1) / splits + 31) / 32 * 32;
+    splits = (K + ks - 1) / ks;
+    if (splits > 1) {
+      void* part = nullptr;
+      RAD_TRY(ws_get(c, WS_SPLITK, (size_t)splits * M * N * 4, &part));
+      g.C = part; g.ldc = N; g.c_dtype = kF32;
+      g.k_split = ks; g.k_splits = splits; g.split_stride = (int64_t)M * N;
+      RAD_TRY(run_gemm_call(c, dtype, kOpK, kOpMN, kEpiStore, g));
+      HIP_TRY(c, timed(c, "splitk_bias", [&](const char**) {
+        return launch_splitk_bias(static_cast<const float*>(part), splits, M, N, bias, y, dtype, c->stream);
+      }));
+      return RAD_OK;
+    }
+  }
   g.bias = bias; g.relu = relu; g.y = y; g.ldy = N; g.bits = relu ? bits : nullptr; g.bits_pitch = bits_pitch;
   if (next) { g.pack = 1; g.next = *next; }
   g.u = u; g.u_ld = u_ld; g.u_n = u_n; g.V = V;
@@ -749,7 +770,31 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     g.A = dense; g.lda = s->cols;
     return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g, alg);
   }
+  bool split = false;
+  if (s->dtype == kBF16) {
+    // A narrow dW (few output columns) gives too few 256x256 tiles to fill the chip, and 256x64 tiles run at
+    // a fifth of the MFMA rate: split the batch over several workgroups per tile instead; each writes its
+    // partial sums to an array of its own and a reduction kernel adds them in a fixed order.
+    const int tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
+    if (tiles < 128 && g.K >= 2048) {
+      int splits = 256 / tiles;
+      if (splits > 8) splits = 8;
+      const int ks = ((g.K + splits - 1) / splits + 31) / 32 * 32;
+      splits = (g.K + ks - 1) / ks;
+      if (splits > 1) {
+        void* part = nullptr;
+        RAD_TRY(ws_get(c, WS_SPLITK, (size_t)splits * g.M * g.N * 4, &part));
+        g.k_split = ks; g.k_splits = splits; g.split_stride = (int64_t)g.M * g.N;
+        g.C = part; g.beta = 0;
+        split = true;
+      }
+    }
+  }
   RAD_TRY(run_gemm_call(c, s->dtype, kOpSparse, kOpMN, kEpiStore, g, alg));
+  if (split)
+    HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
+      return launch_splitk_reduce(static_cast<const float*>(g.C), g.k_splits, g.split_stride, dW, beta, c->stream);
+    }));
   if (s->dtype == kBF16) {
     // the bf16 kernel keeps a fixed number of entries per (row, bucket) in registers; the rest, if any, here
     const int cap = gemm_bf16_sparse_cap(g.sparse_prefetch);

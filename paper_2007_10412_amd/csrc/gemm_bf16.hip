@@ -5,6 +5,7 @@
 namespace rad {
 
 hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t st, const char** name);
+hipError_t launch_gemm_bf16_fwd_partial(const GemmArgs& g, hipStream_t st, const char** name);
 hipError_t launch_gemm_bf16_dx(const GemmArgs& g, hipStream_t st, const char** name);
 hipError_t launch_gemm_bf16_dwd(const GemmArgs& g, hipStream_t st, const char** name);
 hipError_t launch_gemm_bf16_sparse(const GemmArgs& g, hipStream_t st, const char** name);
@@ -12,6 +13,7 @@ hipError_t launch_gemm_bf16_sparse(const GemmArgs& g, hipStream_t st, const char
 hipError_t launch_gemm_bf16(int a_kind, int b_kind, int epi, const GemmArgs& g, hipStream_t st, const char** name) {
   if (a_kind == kOpSparse && b_kind == kOpMN && epi == kEpiStore) return launch_gemm_bf16_sparse(g, st, name);
   if (a_kind == kOpK && b_kind == kOpMN && epi == kEpiFwd) return launch_gemm_bf16_fwd(g, st, name);
+  if (a_kind == kOpK && b_kind == kOpMN && epi == kEpiStore) return launch_gemm_bf16_fwd_partial(g, st, name);
   if (a_kind == kOpK && b_kind == kOpK && epi == kEpiStore) return launch_gemm_bf16_dx(g, st, name);
   if (a_kind == kOpMN && b_kind == kOpMN && epi == kEpiStore) return launch_gemm_bf16_dwd(g, st, name);
   if (name) *name = "";

@@ -712,10 +712,16 @@ __global__ __launch_bounds__(kGemmThreads) void gemm3_bf16_kernel(GemmArgs g) {
     if (kt + 2 < KT) body(IntC<2>(), std::false_type(), kt + 2);
   }
 
-  if constexpr (kStaged) {
-    epilogue_dx_staged<BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
-  } else if constexpr (EPI == kEpiStore) {
-    epilogue_store_dispatch<AK, TM, TN, uint16_t, EDGE>(g, acc, m0, n0, wm0, wn0);
+  if constexpr (EPI == kEpiStore) {
+    if (g.k_splits > 1 && g.split_stride > 0) {     // this split's partial sums go, as fp32, to an array of its own
+      GemmArgs gs = g;
+      gs.C = static_cast<float*>(g.C) + (int64_t)blockIdx.y * g.split_stride;
+      epilogue_store<TM, TN, float, EDGE, false, false, false>(gs, acc, m0, n0, wm0, wn0);
+    } else if constexpr (kStaged) {
+      epilogue_dx_staged<BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
+    } else {
+      epilogue_store_dispatch<AK, TM, TN, uint16_t, EDGE>(g, acc, m0, n0, wm0, wn0);
+    }
   } else {
     epilogue_fwd<uint16_t, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
   }

@@ -6,11 +6,12 @@
 namespace rad {
 
 hipError_t launch_gemm_bf16_sparse7(const GemmArgs& g, hipStream_t st, const char** name) {
-  if (tiles_of(g, 256, 256) >= 128) {
+  // the host splits K (the batch) when a narrow dW gives few 256x256 tiles
+  if (tiles_of(g, 256, 256) * (g.k_splits > 1 ? g.k_splits : 1) >= 128) {
     if (name) *name = "gemm_bf16_dw_sparse_256x256";
     return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 256, 7, false, true>(g, st);
   }
-  if (tiles_of(g, 256, 128) >= 192) {
+  if (tiles_of(g, 256, 128) * (g.k_splits > 1 ? g.k_splits : 1) >= 192) {
     if (name) *name = "gemm_bf16_dw_sparse_256x128";
     return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 128, 7, false, true, false>(g, st);
   }

@@ -74,6 +74,7 @@ struct GemmArgs {
   // convolution geometry (im2col operand kinds, kEpiConv) and split-K
   int cv_C, cv_H, cv_W, cv_KH, cv_KW, cv_pad, cv_N;   // cv_N: channels of the kOpKBatched / kEpiConv tensor
   int k_split, k_splits;       // K range per blockIdx.y (multiple of the K slice), number of splits (0/1 = none)
+  int64_t split_stride;        // > 0: split s stores its partial sums plainly at C + s*split_stride (else fp32 atomics into C)
 };
 
 // dtype: operand element type; returns hipErrorInvalidValue for combinations
@@ -98,6 +99,8 @@ hipError_t launch_sign_matrix(void* R, void* Rt, int dtype, int d, int k, int kp
 hipError_t launch_scale_cast(const float* in, void* out, int dtype, int64_t n, float scale, hipStream_t st);
 // out[i] (+)= sum over `splits` partial arrays of n elements
 hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st);
+hipError_t launch_splitk_bias(const float* partial, int splits, int M, int N, const float* bias, void* out, int dtype,
+                              hipStream_t st);
 // 2x2/stride-2 max pool over NCHW planes; arg packs the 2-bit window position (dy*2+dx of the first maximum)
 // of 16 consecutive outputs per word
 hipError_t launch_maxpool_fwd(const float* y, int planes, int H, int W, float* pooled, uint32_t* arg, hipStream_t st);

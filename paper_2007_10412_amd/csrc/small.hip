@@ -208,6 +208,36 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   for (int s = 0; s < splits; ++s) v += partial[(size_t)s * n + i];
   out[i] = beta ? out[i] + v : v;
 }
+// the same four elements at a time (n a multiple of 4, 16-byte aligned arrays)
+__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float4* __restrict__ partial, int splits, int64_t n4,
+                                                             float4* __restrict__ out, int beta) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  float4 v = partial[i];
+  for (int s = 1; s < splits; ++s) {
+    const float4 t = partial[(size_t)s * n4 + i];
+    v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+  }
+  if (beta) { const float4 o = out[i]; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+  out[i] = v;
+}
+// Sum of the splits of a forward GEMM, plus bias, into the layer output (no activation): partial [splits][M][N]
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_bias_kernel(const float* __restrict__ partial, int splits, int M, int N,
+                                                          const float* __restrict__ bias, T* __restrict__ out) {
+  const int64_t n = (int64_t)M * N;
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  // N is a multiple of 4 here, so the four elements share a row
+  float4 v = *reinterpret_cast<const float4*>(partial + i);
+  for (int s = 1; s < splits; ++s) {
+    const float4 t = *reinterpret_cast<const float4*>(partial + (size_t)s * n + i);
+    v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+  }
+  const int col = (int)(i % N);
+  if (bias) { v.x += bias[col]; v.y += bias[col + 1]; v.z += bias[col + 2]; v.w += bias[col + 3]; }
+  st_elem(out + i, v.x); st_elem(out + i + 1, v.y); st_elem(out + i + 2, v.z); st_elem(out + i + 3, v.w);
+}
 
 // 2x2 max pool, stride 2.  One thread produces 16 consecutive outputs of a plane row-major and the word of
 // their 2-bit window positions; the first maximum in (dy, dx) row-major order wins.
@@ -349,8 +379,24 @@ hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int 
 }
 
 hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st) {
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, partial, splits, n, out,
-                     beta);
+  if (n % 4 == 0 && ((reinterpret_cast<uintptr_t>(partial) | reinterpret_cast<uintptr_t>(out)) & 15) == 0) {
+    const int64_t n4 = n / 4;
+    hipLaunchKernelGGL(splitk_reduce4_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<const float4*>(partial), splits, n4, reinterpret_cast<float4*>(out), beta);
+  } else {
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, partial, splits, n,
+                       out, beta);
+  }
+  return hipGetLastError();
+}
+
+// requires N % 4 == 0 and a 16-byte aligned partial array
+hipError_t launch_splitk_bias(const float* partial, int splits, int M, int N, const float* bias, void* out, int dtype,
+                              hipStream_t st) {
+  const int64_t n4 = (int64_t)M * N / 4;
+  dim3 grid((unsigned)((n4 + 255) / 256)), block(256);
+  if (dtype == kF32) hipLaunchKernelGGL(splitk_bias_kernel<float>, grid, block, 0, st, partial, splits, M, N, bias, (float*)out);
+  else hipLaunchKernelGGL(splitk_bias_kernel<uint16_t>, grid, block, 0, st, partial, splits, M, N, bias, (uint16_t*)out);
   return hipGetLastError();
 }
 
