@@ -1,37 +1,18 @@
 // bf16 GEMMs whose operand tiles go from global memory straight into LDS (global_load_lds_dwordx4): no
-// staging registers, no LDS store instructions, no address arithmetic in the loop.  Interior shapes of
-// 256 x 256 tiles only; everything else takes the register-staged ring kernels.  Two kernels: the main one
-// further down walks K in slices of 64 through two stages and takes K- and M/N-contiguous operands; the one
-// right below walks two K-contiguous operands in slices of 32 through four stages and serves contraction
-// lengths that are an odd multiple of 32.
+// staging registers, no LDS store instructions, no address arithmetic in the loop.  256 x 256 tiles, M and N
+// multiples of 256; everything else takes the register-staged ring kernels.
 //
 // A load instruction writes the 64 x 16 bytes of its wave to consecutive LDS addresses starting at M0,
 // so the tile layout is produced by choosing which global chunk each lane asks for: lane l of the load
-// that fills LDS units [u0, u0 + 64) fetches the (row, k chunk) whose place in the layout is unit u0 + l.
+// that fills LDS units [u0, u0 + 64) fetches the chunk whose place in the layout is unit u0 + l.
 // Per thread that is a constant 32-bit offset from a wave-uniform base that advances by one slice per
-// iteration on the scalar unit.
-//
-// Ring of four LDS stages of BK = 32.  At iteration kt the workgroup
-//   - runs the MFMAs of slice kt from stage kt%4,
-//   - issues the loads of slice kt+3 into stage (kt+3)%4 (= stage (kt-1)%4, last read before the previous
-//     barrier),
-//   - reads the first fragments of slice kt+1,
-//   - waits until its own loads of slice kt+2 have landed (the loads of slice kt+3 stay in flight) and
-//     meets the others at the one barrier of the iteration.
-// The compiler does not see these loads (they are inline assembly), so the waits on them are written out.
+// iteration on the scalar unit.  The compiler does not see these loads (they are inline assembly: its own
+// wait insertion would put vmcnt(0) before every LDS read that follows a load into LDS), so the waits on
+// them are written out.
 #pragma once
 #include "gemm_bf16.hpp"
 
 namespace rad {
-
-constexpr int kDmaStages = 4;
-
-template <int EPI, int BM, int BN> struct GemmDmaSmem {
-  static constexpr int STAGE = (BM + BN) * kBK3 * 2;
-  static constexpr int MAIN = kDmaStages * STAGE;
-  static constexpr int CT = EPI == kEpiFwd ? FwdEpiLds<uint16_t, BM, BN>::BYTES : BM * (BN + 8) * 2;
-  static constexpr int BYTES = CT > MAIN ? CT : MAIN;
-};
 
 // 16 bytes per lane from gbase + voff to LDS address lds + 16 * lane; gbase and lds are wave-uniform
 __device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds) {
@@ -45,157 +26,12 @@ __device__ __forceinline__ void dma16_aim(uint32_t lds) { asm volatile("s_mov_b3
 __device__ __forceinline__ void dma16_go(const void* gbase, uint32_t voff) {
   asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(voff), "s"(gbase) : "memory");
 }
+// the load alone with a per-lane 64-bit address (ragged last slice: lanes past K read a block of zeros)
+__device__ __forceinline__ void dma16_go_at(const void* addr) {
+  asm volatile("global_load_lds_dwordx4 %0, off" :: "v"(addr) : "memory");
+}
 template <int N> __device__ __forceinline__ void dma_wait() {   // at most N of this wave's loads still in flight
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
-
-// One operand tile of R rows x 32 k = 4R units of 16 bytes; load I of thread t fills unit I*256 + t.
-template <int R> struct DmaOperandK {
-  typedef LdsBF16<R, kBK3> L;
-  static constexpr int NI = R / 64;
-  uint32_t voff[NI];
-  const unsigned char* base;      // wave-uniform: first element of the tile's rows at the first slice
-  uint32_t wave_lds;              // wave-uniform: 1024 * wave
-  __device__ __forceinline__ void init(const void* p, int64_t ld, int r0, int kbeg) {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int u = i * kGemmThreads + (int)threadIdx.x;
-      const int row = tile_row(u >> 2), kc = (u & 3) ^ tile_swz(row);    // inverse of L::unit
-      voff[i] = (uint32_t)row * (uint32_t)ld * 2u + (uint32_t)kc * 16u;
-    }
-    base = static_cast<const unsigned char*>(p) + ((int64_t)r0 * ld + kbeg) * 2;
-    wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) * 1024u;
-  }
-  // load I of the slice that starts k elements after the first, into the tile at LDS address lds
-  template <int I> __device__ __forceinline__ void issue(uint32_t lds, int k) const {
-    if constexpr (I < NI) dma16(base + (int64_t)k * 2, voff[I], lds + wave_lds + (uint32_t)I * 4096u);
-  }
-};
-
-template <int EPI, int BM, int BN>
-__global__ __launch_bounds__(kGemmThreads) void gemm_dma_bf16_kernel(GemmArgs g) {
-  constexpr int BK = kBK3, TM = BM / 64, TN = BN / 64;
-  typedef GemmDmaSmem<EPI, BM, BN> S;
-  typedef LdsBF16<BM, BK> LYA; typedef LdsBF16<BN, BK> LYB;
-  typedef DmaOperandK<BM> LoadA; typedef DmaOperandK<BN> LoadB;
-  constexpr int kLoads = LoadA::NI + LoadB::NI;        // per thread and slice
-  static_assert(kLoads <= 8, "one load per MFMA piece");
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint16_t* const smem = reinterpret_cast<uint16_t*>(smem_raw);
-  const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw);   // low half of a flat LDS address
-  constexpr int kStageElems = S::STAGE / 2, kAElems = BM * BK;
-
-  // tile order: as in the register-staged kernels (XCD chunks, groups of 4 tile rows)
-  const int tiles_n = g.N / BN, tiles_m = g.M / BM;
-  const int T = tiles_m * tiles_n;
-  int lin = blockIdx.x;
-  if ((T & 7) == 0) lin = (lin & 7) * (T >> 3) + (lin >> 3);
-  constexpr int GM = 4;
-  const int grp = lin / (GM * tiles_n), within = lin - grp * (GM * tiles_n);
-  const int gh = min(GM, tiles_m - grp * GM);
-  const int tm = grp * GM + within % gh, tn = within / gh;
-  const int m0 = tm * BM, n0 = tn * BN;
-  const int w = threadIdx.x >> 6;
-  const int wm0 = (w >> 1) * (BM / 2), wn0 = (w & 1) * (BN / 2);
-  const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
-
-  floatx16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  const int kbeg = g.k_splits > 1 ? (int)blockIdx.y * g.k_split : 0;
-  const int kend = g.k_splits > 1 ? min(g.K, kbeg + g.k_split) : g.K;
-  const int KT = (kend - kbeg) / BK;                   // the host sends only K ranges that are whole slices
-  LoadA la; LoadB lb;
-  la.init(g.A, g.lda, m0, kbeg);
-  lb.init(g.B, g.ldb, n0, kbeg);
-
-  // load number Q (0 .. 7) of slice s into stage st
-  auto issue = [&](auto Q_, int st, int s) {
-    constexpr int Q = decltype(Q_)::value;
-    const uint32_t a_lds = smem_lds + (uint32_t)st * S::STAGE;
-    if constexpr (Q < LoadA::NI) la.template issue<Q>(a_lds, s * BK);
-    else lb.template issue<Q - LoadA::NI>(a_lds + kAElems * 2, s * BK);
-  };
-  auto issue_all = [&](int st, int s) {
-    issue(IntC<0>(), st, s); issue(IntC<1>(), st, s); issue(IntC<2>(), st, s); issue(IntC<3>(), st, s);
-    issue(IntC<4>(), st, s); issue(IntC<5>(), st, s); issue(IntC<6>(), st, s); issue(IntC<7>(), st, s);
-  };
-
-  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  auto body = [&](auto R_, auto STEADY_, int kt) {
-    constexpr int r = decltype(R_)::value;
-    constexpr bool steady = decltype(STEADY_)::value;
-    constexpr int s_nxt = (r + 1) % kDmaStages, s_fill = (r + 3) % kDmaStages;
-    const uint16_t* const curA = smem + r * kStageElems; const uint16_t* const curB = curA + kAElems;
-    const uint16_t* const nxtA = smem + s_nxt * kStageElems; const uint16_t* const nxtB = nxtA + kAElems;
-    auto ra1 = [&](int i) { if (i < TM) fa1[i] = *reinterpret_cast<const bf16x8*>(&curA[LYA::unit(wm0 + i * 32 + lr, 2 + lk) * 8]); };
-    auto rb1 = [&](int j) { if (j < TN) fb1[j] = *reinterpret_cast<const bf16x8*>(&curB[LYB::unit(wn0 + j * 32 + lr, 2 + lk) * 8]); };
-    auto ra0 = [&](int i) { if (i < TM) fa0[i] = *reinterpret_cast<const bf16x8*>(&nxtA[LYA::unit(wm0 + i * 32 + lr, lk) * 8]); };
-    auto rb0 = [&](int j) { if (j < TN) fb0[j] = *reinterpret_cast<const bf16x8*>(&nxtB[LYB::unit(wn0 + j * 32 + lr, lk) * 8]); };
-    const bool fill = steady || kt + 3 < KT;
-    const bool more = steady || kt + 1 < KT;
-#define RAD_FENCE() __builtin_amdgcn_sched_barrier(0)
-    // MFMAs of k-step 0 with the fragments of k-step 1, then MFMAs of k-step 1 with the first fragments of
-    // slice kt+1; the loads of slice kt+3 are spread over the whole iteration, one per two pieces, so the
-    // four waves do not queue at the one texture-address unit of the CU
-    mfma_piece<0, TM, TN>(fa0, fb0, acc); frag_read<0, TM, TN>(ra1, rb1); if (fill) issue(IntC<0>(), s_fill, kt + 3); RAD_FENCE();
-    mfma_piece<1, TM, TN>(fa0, fb0, acc); frag_read<1, TM, TN>(ra1, rb1); RAD_FENCE();
-    mfma_piece<2, TM, TN>(fa0, fb0, acc); frag_read<2, TM, TN>(ra1, rb1); if (fill) issue(IntC<1>(), s_fill, kt + 3); RAD_FENCE();
-    mfma_piece<3, TM, TN>(fa0, fb0, acc); frag_read<3, TM, TN>(ra1, rb1); RAD_FENCE();
-    mfma_piece<4, TM, TN>(fa0, fb0, acc); frag_read<4, TM, TN>(ra1, rb1); if (fill) issue(IntC<2>(), s_fill, kt + 3); RAD_FENCE();
-    mfma_piece<5, TM, TN>(fa0, fb0, acc); frag_read<5, TM, TN>(ra1, rb1); RAD_FENCE();
-    mfma_piece<6, TM, TN>(fa0, fb0, acc); frag_read<6, TM, TN>(ra1, rb1); if (fill) issue(IntC<3>(), s_fill, kt + 3); RAD_FENCE();
-    mfma_piece<7, TM, TN>(fa0, fb0, acc); frag_read<7, TM, TN>(ra1, rb1); RAD_FENCE();
-    mfma_piece<0, TM, TN>(fa1, fb1, acc); if (more) frag_read<0, TM, TN>(ra0, rb0); if (fill) issue(IntC<4>(), s_fill, kt + 3); RAD_FENCE();
-    mfma_piece<1, TM, TN>(fa1, fb1, acc); if (more) frag_read<1, TM, TN>(ra0, rb0); RAD_FENCE();
-    mfma_piece<2, TM, TN>(fa1, fb1, acc); if (more) frag_read<2, TM, TN>(ra0, rb0); if (fill) issue(IntC<5>(), s_fill, kt + 3); RAD_FENCE();
-    mfma_piece<3, TM, TN>(fa1, fb1, acc); if (more) frag_read<3, TM, TN>(ra0, rb0); RAD_FENCE();
-    mfma_piece<4, TM, TN>(fa1, fb1, acc); if (more) frag_read<4, TM, TN>(ra0, rb0); if (fill) issue(IntC<6>(), s_fill, kt + 3); RAD_FENCE();
-    mfma_piece<5, TM, TN>(fa1, fb1, acc); if (more) frag_read<5, TM, TN>(ra0, rb0); RAD_FENCE();
-    mfma_piece<6, TM, TN>(fa1, fb1, acc); if (more) frag_read<6, TM, TN>(ra0, rb0); if (fill) issue(IntC<7>(), s_fill, kt + 3); RAD_FENCE();
-    mfma_piece<7, TM, TN>(fa1, fb1, acc); if (more) frag_read<7, TM, TN>(ra0, rb0); RAD_FENCE();
-#undef RAD_FENCE
-    // slice kt+2 must have landed before the barrier; the loads of slice kt+3, if any, stay in flight
-    if (fill) dma_wait<kLoads>(); else dma_wait<0>();
-    __syncthreads();
-    __builtin_amdgcn_sched_barrier(0);
-  };
-
-  // prologue: slices 0, 1, 2 on their way into stages 0, 1, 2; slices 0 and 1 landed
-  if (KT > 0) issue_all(0, 0);
-  if (KT > 1) issue_all(1, 1);
-  if (KT > 2) { issue_all(2, 2); dma_wait<kLoads>(); } else dma_wait<0>();
-  __syncthreads();
-  if (KT > 0) load_frags32<TM, TN, BM, BN>(smem, smem + kAElems, 0, wm0, wn0, fa0, fb0);
-  __builtin_amdgcn_sched_barrier(0);
-
-  int kt = 0;
-  if (KT > 6) {
-    do {                                   // every iteration below loads a slice: kt + 3 + 3 < KT
-      body(IntC<0>(), std::true_type(), kt);
-      body(IntC<1>(), std::true_type(), kt + 1);
-      body(IntC<2>(), std::true_type(), kt + 2);
-      body(IntC<3>(), std::true_type(), kt + 3);
-      kt += 4;
-    } while (kt + 6 < KT);
-  }
-  for (; kt < KT; kt += 4) {               // drain; kt is a multiple of 4 here
-    body(IntC<0>(), std::false_type(), kt);
-    if (kt + 1 < KT) body(IntC<1>(), std::false_type(), kt + 1);
-    if (kt + 2 < KT) body(IntC<2>(), std::false_type(), kt + 2);
-    if (kt + 3 < KT) body(IntC<3>(), std::false_type(), kt + 3);
-  }
-
-  if constexpr (EPI == kEpiStore) {
-    epilogue_dx_staged<BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
-  } else {
-    epilogue_fwd<uint16_t, BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
-  }
 }
 
 // ------------------------------------------------------------------ 64-deep slices, two stages
@@ -237,6 +73,15 @@ template <int R> struct DmaOperandK64 {
   template <int I> __device__ __forceinline__ void go(int k) const {
     if constexpr (I < NI) dma16_go(base + (int64_t)k * 2, voff[I]);
   }
+  // last slice of a K that is not a multiple of 64: krem valid k from the slice start on
+  template <int I> __device__ __forceinline__ void go_tail(int k, int krem) const {
+    if constexpr (I < NI) {
+      const int u = I * kGemmThreads + (int)threadIdx.x;
+      const int kc = (u & 7) ^ ((u >> 4) & 7);
+      const void* src = base + (int64_t)k * 2 + voff[I];
+      dma16_go_at(kc * 8 < krem ? src : static_cast<const void*>(kZeroChunk));
+    }
+  }
 };
 
 // M/N-contiguous operand (LdsMN layout, 64 k-rows): a load instruction fills two k-rows (1 KB); load I of
@@ -264,6 +109,11 @@ template <int R> struct DmaOperandMN64 {
   }
   template <int I> __device__ __forceinline__ void aim(uint32_t lds) const { dma16_aim(lds + wave_lds + (uint32_t)I * 4096u); }
   template <int I> __device__ __forceinline__ void go(int k) const { dma16_go(base + (int64_t)(k >> 6) * slice_bytes, voff[I]); }
+  template <int I> __device__ __forceinline__ void go_tail(int k, int krem) const {
+    const int krow = 2 * (4 * I + (int)(threadIdx.x >> 6)) + (int)((threadIdx.x & 63) >> 5);
+    const void* src = base + (int64_t)(k >> 6) * slice_bytes + voff[I];
+    dma16_go_at(krow < krem ? src : static_cast<const void*>(kZeroChunk));
+  }
 };
 
 template <int EPI, int BM, int BN> struct GemmDma64Smem {
@@ -312,7 +162,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
 
   const int kbeg = g.k_splits > 1 ? (int)blockIdx.y * g.k_split : 0;
   const int kend = g.k_splits > 1 ? min(g.K, kbeg + g.k_split) : g.K;
-  const int KT = (kend - kbeg) / BK;                   // the host sends only K ranges that are whole slices
+  const int KT = (kend - kbeg + BK - 1) / BK;
+  const int krem = kend - kbeg - (KT - 1) * BK;        // valid k of the last slice
+  const bool ragged = krem < BK;                       // its loads read zeros past K; the steady loop never issues it
+  const int KTs = ragged ? KT - 1 : KT;
   LoadA la; LoadB lb;
   la.init(g.A, g.lda, m0, kbeg);
   lb.init(g.B, g.ldb, n0, kbeg);
@@ -321,17 +174,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
   auto issue = [&](auto Q_, int st, int s) {
     constexpr int Q = decltype(Q_)::value;
     const uint32_t a_lds = smem_lds + (uint32_t)st * S::STAGE;
-    if constexpr ((Q & 1) == 0) la.template issue<Q / 2>(a_lds, s * BK);
-    else lb.template issue<Q / 2>(a_lds + kAElems * 2, s * BK);
+    if (ragged && s == KT - 1) {
+      if constexpr ((Q & 1) == 0) { la.template aim<Q / 2>(a_lds); asm volatile("s_nop 0"); la.template go_tail<Q / 2>(s * BK, krem); }
+      else { lb.template aim<Q / 2>(a_lds + kAElems * 2); asm volatile("s_nop 0"); lb.template go_tail<Q / 2>(s * BK, krem); }
+    } else {
+      if constexpr ((Q & 1) == 0) la.template issue<Q / 2>(a_lds, s * BK);
+      else lb.template issue<Q / 2>(a_lds + kAElems * 2, s * BK);
+    }
   };
 
   // One load per piece: the first eight of a slice during k-step 3 of the iteration before, the other eight
   // during k-step 0 (two per piece, all in k-step 3, measured 6 % slower).  M0 is aimed before the piece's
   // MFMAs and the load issued after its fragment read.
 #define RAD_K0_AIM(Q) if (more) aim(IntC<Q>(), r ^ 1);
-#define RAD_K0_DMA(Q) if (more) go(IntC<Q>(), kt + 1);
+#define RAD_K0_DMA(Q) if (more) go(IntC<Q>(), kt + 1, tail1);
 #define RAD_K3_AIM(Q) if (more2) aim(IntC<Q>(), r);
-#define RAD_K3_DMA(Q) if (more2) go(IntC<Q>(), kt + 2);
+#define RAD_K3_DMA(Q) if (more2) go(IntC<Q>(), kt + 2, tail2);
   uint32_t afrag[TM], bfrag[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) { if constexpr (kAT) afrag[i] = mn_frag_byte<BM>(wm0 + i * 32, lane); else afrag[i] = 0u; }
@@ -342,9 +200,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
     const uint32_t a_lds = smem_lds + (uint32_t)st * S::STAGE;
     if constexpr ((Q & 1) == 0) la.template aim<Q / 2>(a_lds); else lb.template aim<Q / 2>(a_lds + kAElems * 2);
   };
-  auto go = [&](auto Q_, int s) {
+  auto go = [&](auto Q_, int s, bool tail) {
     constexpr int Q = decltype(Q_)::value;
-    if constexpr ((Q & 1) == 0) la.template go<Q / 2>(s * BK); else lb.template go<Q / 2>(s * BK);
+    if (tail) {
+      if constexpr ((Q & 1) == 0) la.template go_tail<Q / 2>(s * BK, krem); else lb.template go_tail<Q / 2>(s * BK, krem);
+    } else {
+      if constexpr ((Q & 1) == 0) la.template go<Q / 2>(s * BK); else lb.template go<Q / 2>(s * BK);
+    }
   };
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
 #define RAD_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -371,6 +233,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
     };
     const bool more = steady || kt + 1 < KT;     // slice kt+1 exists
     const bool more2 = steady || kt + 2 < KT;    // slice kt+2 exists
+    const bool tail1 = !steady && ragged && kt + 1 == KT - 1, tail2 = !steady && ragged && kt + 2 == KT - 1;
     {  // k-step 0
       auto f = rd(fa1, fb1, curA, curB, 1);
       RAD_K0_AIM(8) mfma_piece<0, TM, TN>(fa0, fb0, acc); frag_read<0, TM, TN>(f.first, f.second); RAD_K0_DMA(8) RAD_FENCE();
@@ -450,12 +313,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
   RAD_FENCE();
 
   int kt = 0;
-  if (KT > 3) {
-    do {                                   // both iterations find slices kt+1 and kt+2: kt + 1 + 2 < KT
+  if (KTs > 3) {
+    do {                                   // both iterations issue whole slices only: kt + 1 + 2 < KTs
       body(IntC<0>(), std::true_type(), kt);
       body(IntC<1>(), std::true_type(), kt + 1);
       kt += 2;
-    } while (kt + 3 < KT);
+    } while (kt + 3 < KTs);
   }
   for (; kt < KT; kt += 2) {               // drain; kt is even here
     body(IntC<0>(), std::false_type(), kt);

@@ -70,14 +70,14 @@ hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
   return hipGetLastError();
 }
 
-// ---- bf16 kernels whose K-contiguous operands go from global memory straight into LDS.  Interior shapes only:
-// whole tiles, K a whole number of slices, rows 16-byte aligned, no loader masks.
+// ---- bf16 kernels whose operands go from global memory straight into LDS: whole 256 x 256 tiles, rows that are
+// whole 16-byte vectors, no loader masks; K need not be a multiple of the 64-deep slice.
 template <int AKIND, int BKIND, int BM, int BN>
 bool gemm_dma_ok(const GemmArgs& g) {
-  if (g.a_mask || g.b_mask || g.row_map || g.m_load > g.M || !gemm_is_full<BF16Tag, AKIND, BM, BN, 32>(g)) return false;
-  if (g.k_splits > 1 && g.k_split % 32 != 0) return false;
-  // an M/N-contiguous operand only has the 64-deep kernel
-  if ((AKIND == kOpMN || BKIND == kOpMN) && (g.K % 64 != 0 || (g.k_splits > 1 && g.k_split % 64 != 0))) return false;
+  if (g.a_mask || g.b_mask || g.row_map || g.m_load > g.M) return false;
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.M % BM || g.N % BN || g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
+  if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.B)) & 15) return false;
+  if (g.k_splits > 1 && g.k_split % 64 != 0) return false;
   // per-thread offsets inside a tile are 32-bit byte offsets
   const int64_t a_rows = AKIND == kOpMN ? 64 : BM, b_rows = BKIND == kOpMN ? 64 : BN;
   return a_rows * g.lda * 2 < (int64_t(1) << 32) && b_rows * g.ldb * 2 < (int64_t(1) << 32);
@@ -85,23 +85,15 @@ bool gemm_dma_ok(const GemmArgs& g) {
 template <int AKIND, int BKIND, int EPI, int BM, int BN>
 hipError_t run_gemm_dma(const GemmArgs& g, hipStream_t st) {
   if (g.dry_run) return hipSuccess;
-  constexpr bool kAnyMN = AKIND == kOpMN || BKIND == kOpMN;
-  // 64-deep slices when every K range is a whole number of them (always, with an M/N-contiguous operand)
-  const bool deep = kAnyMN || (g.K % 64 == 0 && (g.k_splits <= 1 || g.k_split % 64 == 0));
-  void (*kern)(GemmArgs) = gemm_dma64_bf16_kernel<AKIND, BKIND, EPI, BM, BN>;
-  int smem = GemmDma64Smem<EPI, BM, BN>::BYTES;
-  if constexpr (!kAnyMN) {
-    if (!deep) { kern = gemm_dma_bf16_kernel<EPI, BM, BN>; smem = GemmDmaSmem<EPI, BM, BN>::BYTES; }
-  }
-  static_assert(GemmDma64Smem<EPI, BM, BN>::BYTES <= 160 * 1024 && GemmDmaSmem<EPI, BM, BN>::BYTES <= 160 * 1024,
-                "tile does not fit the 160 KB LDS of a gfx950 CU");
-  static bool prepared[2] = {false, false};   // one host thread drives a context
-  if (!prepared[deep]) {
+  auto kern = gemm_dma64_bf16_kernel<AKIND, BKIND, EPI, BM, BN>;
+  constexpr int smem = GemmDma64Smem<EPI, BM, BN>::BYTES;
+  static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
+  static bool prepared = false;   // one host thread drives a context
+  if (!prepared) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       deep ? GemmDma64Smem<EPI, BM, BN>::BYTES : GemmDmaSmem<EPI, BM, BN>::BYTES);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    prepared[deep] = true;
+    prepared = true;
   }
   hipLaunchKernelGGL(kern, dim3((g.M / BM) * (g.N / BN), g.k_splits > 1 ? g.k_splits : 1), dim3(kGemmThreads), smem,
                      st, g);

@@ -1,7 +1,7 @@
 """GPU parity of the bf16 GEMM kernels that load global memory straight into LDS: wide interior shapes of
 rad_forward_sample (K-contiguous x, M/N-contiguous W read through transposing LDS reads) and of
 rad_backward_dX (two K-contiguous operands) against the oracle, over contraction lengths that end the
-pipeline at every point: one slice, odd and even slice counts, 32- and 64-deep slices."""
+pipeline at every point: one slice, odd and even slice counts, whole and ragged last slices."""
 import numpy as np
 import pytest
 
@@ -23,7 +23,7 @@ def bf16_data(rng, shape, scale=1.0):
     return R.round_bf16((rng.standard_normal(shape) * scale).astype(np.float32))
 
 
-@pytest.mark.parametrize("d_in", [64, 128, 192, 320, 1024])
+@pytest.mark.parametrize("d_in", [8, 40, 64, 128, 192, 200, 320, 1024])
 @pytest.mark.parametrize("relu", [False, True])
 def test_forward_wide_layer(ctx, d_in, relu):
     """128 output tiles of 256 x 256: y, and the ReLU bits, of a 2048 x d_in x 4096 layer."""
@@ -52,7 +52,7 @@ def test_forward_wide_layer(ctx, d_in, relu):
         B.rad_store_destroy(st)
 
 
-@pytest.mark.parametrize("d_out", [32, 64, 96, 128, 160, 192, 256, 288, 448])
+@pytest.mark.parametrize("d_out", [8, 32, 40, 64, 96, 128, 160, 192, 256, 288, 448, 1000])
 def test_dX_wide_layer(ctx, d_out):
     """128 output tiles of 256 x 256: dX = dy W^T for a 2048 x 4096 x d_out layer without ReLU."""
     from paper_2007_10412_amd import binding as B
@@ -74,7 +74,7 @@ def test_dX_wide_layer(ctx, d_out):
         B.rad_store_destroy(st)
 
 
-@pytest.mark.parametrize("batch", [64, 128, 192, 320, 1024])
+@pytest.mark.parametrize("batch", [8, 64, 72, 128, 192, 200, 320, 1024])
 def test_dense_dW_wide_layer(ctx, batch):
     """128 output tiles of 256 x 256: dW = x^T dy from an exact store (both operands M/N contiguous), and
     its accumulating form."""
