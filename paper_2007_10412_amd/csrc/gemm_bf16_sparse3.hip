@@ -8,7 +8,7 @@ namespace rad {
 hipError_t launch_gemm_bf16_sparse3(const GemmArgs& g, hipStream_t st, const char** name) {
   // the host splits K (the batch) when a narrow dW gives few 256x256 tiles
   if (tiles_of(g, 256, 256) * (g.k_splits > 1 ? g.k_splits : 1) >= 128) {
-    if (name) *name = "gemm_bf16_dw_sparse_256x256";
+    if (name) *name = g.k_splits > 1 ? "gemm_bf16_dw_sparse_splitk_256" : "gemm_bf16_dw_sparse_256x256";
     return run_gemm3<kOpSparse, kOpMN, kEpiStore, 256, 256, 3, false, true>(g, st);
   }
   if (tiles_of(g, 256, 128) * (g.k_splits > 1 ? g.k_splits : 1) >= 192) {
