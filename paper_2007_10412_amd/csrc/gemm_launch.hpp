@@ -1,9 +1,23 @@
 // Launch helper shared by the GEMM instantiation files.
 #pragma once
+#include <hip/hip_ext.h>
+
 #include "gemm_bf16.hpp"
 #include "gemm_bf16_dma.hpp"
 
 namespace rad {
+
+// Launches a GEMM kernel; with timing events in the arguments the dispatch itself records them (start and end
+// of the kernel), so timing one kernel of a step puts no extra packets, and no bubbles, on the stream.
+template <class K>
+hipError_t launch_gemm_kernel(K kern, dim3 grid, int smem, hipStream_t st, const GemmArgs& g) {
+  if (g.ev_start && g.ev_stop)
+    hipExtLaunchKernelGGL(kern, grid, dim3(kGemmThreads), smem, st, static_cast<hipEvent_t>(g.ev_start),
+                          static_cast<hipEvent_t>(g.ev_stop), 0, g);
+  else
+    hipLaunchKernelGGL(kern, grid, dim3(kGemmThreads), smem, st, g);
+  return hipGetLastError();
+}
 
 template <class DT, int AK, int BKIND, int EPI, int BM, int BN, int BK, int SE, int FLAGS>
 hipError_t run_gemm_variant(const GemmArgs& g, hipStream_t st) {
@@ -19,8 +33,7 @@ hipError_t run_gemm_variant(const GemmArgs& g, hipStream_t st) {
   }
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, g.k_splits > 1 ? g.k_splits : 1), dim3(kGemmThreads), smem, st, g);
-  return hipGetLastError();
+  return launch_gemm_kernel(kern, dim3(tiles_m * tiles_n, g.k_splits > 1 ? g.k_splits : 1), smem, st, g);
 }
 
 // true when every tile is full and every operand row is 16-byte aligned: the
@@ -66,8 +79,7 @@ hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
   }
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, g.k_splits > 1 ? g.k_splits : 1), dim3(kGemmThreads), smem, st, g);
-  return hipGetLastError();
+  return launch_gemm_kernel(kern, dim3(tiles_m * tiles_n, g.k_splits > 1 ? g.k_splits : 1), smem, st, g);
 }
 
 // ---- bf16 kernels whose operands go from global memory straight into LDS: whole 256 x 256 tiles, rows that are
@@ -95,9 +107,7 @@ hipError_t run_gemm_dma(const GemmArgs& g, hipStream_t st) {
     if (e != hipSuccess) return e;
     prepared = true;
   }
-  hipLaunchKernelGGL(kern, dim3((g.M / BM) * (g.N / BN), g.k_splits > 1 ? g.k_splits : 1), dim3(kGemmThreads), smem,
-                     st, g);
-  return hipGetLastError();
+  return launch_gemm_kernel(kern, dim3((g.M / BM) * (g.N / BN), g.k_splits > 1 ? g.k_splits : 1), smem, st, g);
 }
 
 // ragged shapes whose every operand access is still a whole 16-byte vector: pitches, K and the extent along

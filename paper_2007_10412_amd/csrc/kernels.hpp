@@ -75,6 +75,9 @@ struct GemmArgs {
   int cv_C, cv_H, cv_W, cv_KH, cv_KW, cv_pad, cv_N;   // cv_N: channels of the kOpKBatched / kEpiConv tensor
   int k_split, k_splits;       // K range per blockIdx.y (multiple of the K slice), number of splits (0/1 = none)
   int64_t split_stride;        // > 0: split s stores its partial sums plainly at C + s*split_stride (else fp32 atomics into C)
+  // host side only: when set, the launch itself carries these two HIP events (start and end of the kernel),
+  // which costs no extra packets on the stream
+  void* ev_start; void* ev_stop;
 };
 
 // dtype: operand element type; returns hipErrorInvalidValue for combinations
