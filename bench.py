@@ -104,7 +104,7 @@ def main():
             if n and ms - longer > 0:
                 labels_ms[nm] = ms - longer
     big = max(labels_ms, key=labels_ms.get)
-    # the dW kernel of the widest layers (BASELINE's second number), from the same two steps
+    # the dW kernel of the widest layers, from the same two steps
     dw_labels = [k_ for k_ in labels_ms if "_dw_" in k_]
     dw_kernel = None
     if dw_labels:

@@ -5,7 +5,7 @@ import torch
 
 from paper_2007_10412_amd import binding as B
 
-TOL = {B.RAD_F32: 1e-4, B.RAD_BF16: 2e-2}   # relative Frobenius error on gradients (spec tolerance)
+TOL = {B.RAD_F32: 1e-4, B.RAD_BF16: 2e-2}   # relative Frobenius error on gradients (the tolerance the benchmark spec states)
 
 
 def dev(a, dtype=B.RAD_F32):
