@@ -100,3 +100,20 @@ def test_dense_dW_wide_layer(ctx, batch):
         assert rel_err(host(gW), 2 * want) < 1e-5
     finally:
         B.rad_store_destroy(st)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("scheme,p", [(3, 0.25), (1, 0.1), (2, 0.25)])
+def test_narrow_layer_with_long_contractions(ctx, scheme, p, relu):
+    """A narrow bf16 layer with a deep contraction (few output tiles): the forward of a layer without ReLU and
+    dW from the store split K over several workgroups per tile and reduce the partial sums afterwards.  All
+    three entry points against the oracle on identical inputs, stores compared entry by entry."""
+    from paper_2007_10412_amd import binding as B
+    from tests.test_gpu_linear import run_layer
+    Bt, D, N = 2048, 2304, 200
+    rng = np.random.default_rng(400 + scheme)
+    x = bf16_data(rng, (Bt, D))
+    W = bf16_data(rng, (D, N), 1.0 / np.sqrt(D))
+    bias = rng.standard_normal(N).astype(np.float32)
+    dy = bf16_data(rng, (Bt, N))
+    run_layer(ctx, x, W, bias, dy, scheme, p, seed=11, dtype=B.RAD_BF16, relu=relu)
