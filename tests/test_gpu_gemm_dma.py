@@ -117,3 +117,36 @@ def test_narrow_layer_with_long_contractions(ctx, scheme, p, relu):
     bias = rng.standard_normal(N).astype(np.float32)
     dy = bf16_data(rng, (Bt, N))
     run_layer(ctx, x, W, bias, dy, scheme, p, seed=11, dtype=B.RAD_BF16, relu=relu)
+
+
+@pytest.mark.parametrize("N", [256, 1000])
+def test_dW_with_segments_longer_than_the_register_budget(ctx, N):
+    """The bf16 dW kernel keeps a fixed number of entries per (store row, 256-column bucket) in registers and
+    leaves longer segments to a second kernel.  One-bit keys (test hook) make every row keep the lowest columns
+    whose key is 0, about half of the first bucket, far more than the kernel holds.  dW is compared with the
+    product formed from the store the GPU itself exports, so the check does not depend on the draw."""
+    from paper_2007_10412_amd import binding as B
+    from tests.gpu_util import dev, host, empty, rel_err, TOL
+    Bt, D, p = 256, 1024, 0.1
+    rng = np.random.default_rng(500 + N)
+    x = bf16_data(rng, (Bt, D))
+    dy = bf16_data(rng, (Bt, N))
+    L = B.make_layer(Bt, D, N, dtype=B.RAD_BF16, relu=False)
+    st = B.rad_store_create(ctx, L, B.RAD_FIXEDK_PER_EXAMPLE, p)
+    B.rad_debug_key_shift(ctx, 31)
+    try:
+        B.rad_sample_pack(ctx, B.make_sampling(B.RAD_FIXEDK_PER_EXAMPLE, p, 3), dev(x, B.RAD_BF16), st)
+        rp, col, val = B.rad_store_export_csr(ctx, st, Bt)
+        seg0 = np.array([np.count_nonzero(col[rp[b]:rp[b + 1]] < 256) for b in range(Bt)])
+        assert seg0.min() > 60, seg0.min()          # longer than the 56 entries the kernel holds
+        gW = empty((D, N))
+        B.rad_backward_dW(ctx, L, st, dev(dy, B.RAD_BF16), gW, None, 0.0)
+        xt = np.zeros((Bt, D), dtype=np.float64)
+        for b in range(Bt):
+            xt[b, col[rp[b]:rp[b + 1]]] = val[rp[b]:rp[b + 1]]
+        want = R.backward_dW(xt, dy, np.ones((Bt, N), dtype=bool))
+        assert rel_err(host(gW), want) < TOL[B.RAD_BF16]
+        assert rel_err(host(gW)[:256], want[:256]) < 1e-4        # fp32 sums of exact products
+    finally:
+        B.rad_debug_key_shift(ctx, 0)
+        B.rad_store_destroy(st)
