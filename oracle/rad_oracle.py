@@ -453,10 +453,26 @@ def maxpool2x2_backward(dout, arg):
     return win.reshape(b, c, ho * 2, wo * 2)
 
 
+def avgpool2x2_forward(a):
+    """2x2/stride-2 average pool (the pooling of the convolutional architecture
+    in Appendix A).  Its Jacobian is constant, so nothing is kept for the
+    backward pass (Appendix A, calculation of memory saved)."""
+    a = np.asarray(a, dtype=np.float64)
+    b, c, hh, ww = a.shape
+    return a.reshape(b, c, hh // 2, 2, ww // 2, 2).mean(axis=(3, 5))
+
+
+def avgpool2x2_backward(dout):
+    """Every input of a window receives a quarter of the window's gradient."""
+    dout = np.asarray(dout, dtype=np.float64)
+    return np.repeat(np.repeat(dout, 2, axis=2), 2, axis=3) / 4.0
+
+
 def cnn_train_step(x, labels, convs, fc, scheme, p, seed, stream_base=0, step=0,
                    bits_override=None, arg_override=None):
-    """convs: list of dicts(W [ci,kh,kw,co], b [co], pad, pool bool); every conv
-    is followed by ReLU and, if pool, a 2x2 max pool.  fc = (W [D,10], b).
+    """convs: list of dicts(W [ci,kh,kw,co], b [co], pad, pool); every conv is
+    followed by ReLU and then by a 2x2 max pool if pool is 1 (or True), a 2x2
+    average pool if pool is 2, nothing if 0.  fc = (W [D,10], b).
     Each conv input and the FC input is sampled (flattened per example).
     bits_override / arg_override (lists, entries may be None) replace the ReLU
     bits / pool positions used in the backward pass, for tests that feed one
@@ -470,13 +486,16 @@ def cnn_train_step(x, labels, convs, fc, scheme, p, seed, stream_base=0, step=0,
         _, y, bits = conv2d_forward(act, cv["W"], cv["b"], cv["pad"], relu=True)
         arg = None
         in_shape = act.shape
-        if cv["pool"]:
+        kind = int(cv["pool"])
+        if kind == 1:
             y, arg = maxpool2x2_forward(y)
+        elif kind == 2:
+            y = avgpool2x2_forward(y)
         if bits_override is not None and bits_override[l] is not None:
             bits = bits_override[l]
         if arg_override is not None and arg_override[l] is not None:
             arg = arg_override[l]
-        tape.append((in_shape, bits, arg))
+        tape.append((in_shape, bits, arg, kind))
         act = y.astype(np.float32)
     flat = act.reshape(B, -1)
     st_fc = sample_pack(flat, scheme, p, seed, stream_base + len(convs), step)
@@ -491,9 +510,11 @@ def cnn_train_step(x, labels, convs, fc, scheme, p, seed, stream_base=0, step=0,
     dWs, dbs = [None] * len(convs), [None] * len(convs)
     for l in range(len(convs) - 1, -1, -1):
         cv = convs[l]
-        in_shape, bits, arg = tape[l]
-        if arg is not None:
+        in_shape, bits, arg, kind = tape[l]
+        if kind == 1:
             dy = maxpool2x2_backward(dy, arg)
+        elif kind == 2:
+            dy = avgpool2x2_backward(dy)
         g = np.asarray(dy, dtype=np.float64) * bits
         kh, kw = cv["W"].shape[1:3]
         dWs[l] = conv2d_dW(stores[l][3].reshape(in_shape), g, kh, kw, cv["pad"])

@@ -58,7 +58,8 @@ def rnn(seed=1234, batch=128, T=784, d_input=1, hidden=1024, classes=10, identit
 
 
 def cnn(seed=1234, batch=150, channels=(3, 16, 32, 64), pool=(0, 1, 1), ksize=3, hw=32, classes=10):
-    """Config 3: N(0,1) images, conv weights [c_in,k,k,c_out] ~ N(0, 1/(c_in k k)), zero biases."""
+    """Config 3: N(0,1) images, conv weights [c_in,k,k,c_out] ~ N(0, 1/(c_in k k)), zero biases.
+    pool[i]: 0 none, 1 max pool, 2 average pool after conv i."""
     rng = np.random.default_rng(seed)
     x = rng.standard_normal((batch, channels[0], hw, hw)).astype(np.float32)
     convs = []
@@ -66,7 +67,7 @@ def cnn(seed=1234, batch=150, channels=(3, 16, 32, 64), pool=(0, 1, 1), ksize=3,
     for i in range(len(channels) - 1):
         ci, co = channels[i], channels[i + 1]
         W = (rng.standard_normal((ci, ksize, ksize, co)) / np.sqrt(ci * ksize * ksize)).astype(np.float32)
-        convs.append(dict(W=W, b=np.zeros(co, dtype=np.float32), pad=(ksize - 1) // 2, pool=bool(pool[i])))
+        convs.append(dict(W=W, b=np.zeros(co, dtype=np.float32), pad=(ksize - 1) // 2, pool=int(pool[i])))
         if pool[i]:
             size //= 2
     d = channels[-1] * size * size

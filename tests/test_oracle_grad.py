@@ -175,6 +175,55 @@ def test_conv_pool_fraction_one_is_autograd():
         np.testing.assert_allclose(out["db"][l], tbs[l].grad.numpy(), atol=1e-6)
 
 
+def test_paper_convnet_shape_with_average_pool_is_autograd():
+    """The convolutional architecture of Appendix A at reduced width: 5x5 convolutions with 2 zero padding,
+    average pools after the second and fourth, one linear layer; at fraction 1 the oracle's step is the exact
+    gradient, compared with torch's CPU autograd through avg_pool2d."""
+    rng = np.random.default_rng(22)
+    B = 2
+    x = rng.standard_normal((B, 3, 8, 8)).astype(np.float32)
+    shapes = [(3, 4), (4, 5), (5, 5), (5, 6)]
+    pools = [0, 2, 0, 2]
+    convs = []
+    for (ci, co), pl in zip(shapes, pools):
+        W = (rng.standard_normal((ci, 5, 5, co)) / np.sqrt(25 * ci)).astype(np.float32)
+        b = (0.1 * rng.standard_normal(co)).astype(np.float32)
+        convs.append(dict(W=W, b=b, pad=2, pool=pl))
+    fcW = (rng.standard_normal((6 * 2 * 2, 10)) / 4).astype(np.float32)
+    fcb = (0.1 * rng.standard_normal(10)).astype(np.float32)
+    labels = rng.integers(0, 10, B)
+    out = R.cnn_train_step(x, labels, convs, (fcW, fcb), R.FIXEDK_PER_EXAMPLE, 1.0, seed=1)
+    a = torch.tensor(x, dtype=torch.float64)
+    tws, tbs = [], []
+    for cv in convs:
+        w = torch.tensor(cv["W"].transpose(3, 0, 1, 2).copy(), dtype=torch.float64, requires_grad=True)
+        b = torch.tensor(cv["b"], dtype=torch.float64, requires_grad=True)
+        tws.append(w); tbs.append(b)
+        a = torch.relu(torch.nn.functional.conv2d(a, w, b, padding=2))
+        if cv["pool"] == 2:
+            a = torch.nn.functional.avg_pool2d(a, 2)
+            # the oracle hands fp32 activations from layer to layer
+            a = a + (a.detach().to(torch.float32).to(torch.float64) - a.detach())
+    tfw = torch.tensor(fcW, dtype=torch.float64, requires_grad=True)
+    tfb = torch.tensor(fcb, dtype=torch.float64, requires_grad=True)
+    z = a.reshape(B, -1) @ tfw + tfb
+    loss = torch.nn.functional.cross_entropy(z, torch.tensor(labels))
+    loss.backward()
+    assert abs(out["loss"] - loss.item()) < 1e-6
+    np.testing.assert_allclose(out["dW_fc"], tfw.grad.numpy(), atol=1e-6)
+    for l in range(4):
+        np.testing.assert_allclose(out["dW"][l], tws[l].grad.numpy().transpose(1, 2, 3, 0), atol=1e-6)
+        np.testing.assert_allclose(out["db"][l], tbs[l].grad.numpy(), atol=1e-6)
+
+
+def test_average_pool_closed_forms():
+    a = np.arange(16, dtype=np.float64).reshape(1, 1, 4, 4)
+    out = R.avgpool2x2_forward(a)
+    assert out.tolist() == [[[[2.5, 4.5], [10.5, 12.5]]]]          # (0+1+4+5)/4, (2+3+6+7)/4, ...
+    back = R.avgpool2x2_backward(np.array([[[[4.0, 8.0]]]]))
+    assert back.tolist() == [[[[1.0, 1.0, 2.0, 2.0], [1.0, 1.0, 2.0, 2.0]]]]
+
+
 def test_maxpool_first_max_and_zero_window():
     a = np.zeros((1, 1, 2, 4), dtype=np.float32)
     a[0, 0, :, 2:] = [[1.0, 5.0], [5.0, 2.0]]              # tie between (0,1) and (1,0)
