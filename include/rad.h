@@ -234,8 +234,10 @@ rad_status rad_model_create_rnn(rad_ctx* ctx, int64_t batch, int64_t T, int64_t 
                                 int64_t hidden, int64_t classes, int32_t scheme, double p,
                                 rad_model** out);
 
-/* Small CNN: n_conv stride-1 convolutions (each + bias + ReLU, and a 2x2 max
- * pool where pool[l] != 0), then one linear layer to `classes`; fp32, NCHW.
+/* Small CNN: n_conv stride-1 convolutions (each + bias + ReLU, then a 2x2 max
+ * pool where pool[l] == 1, a 2x2 average pool, for which nothing is stored,
+ * where pool[l] == 2 (Appendix A, architectures used), none where 0; other
+ * values: RAD_ERR_PARAM), then one linear layer to `classes`; fp32, NCHW.
  * channels[0..n_conv] are c_in, c_out_0, ..., ksize is the square kernel size
  * with pad (ksize-1)/2.  Every conv input and the linear input are sampled.
  * params = {W_0 [c_in,k,k,c_out], b_0, ..., W_fc [d, classes], b_fc}. */
@@ -257,7 +259,7 @@ int32_t rad_model_num_stores(const rad_model* model);
 rad_store* rad_model_store(rad_model* model, int32_t l);
 /* Synchronises.  CNN models: the 2-bit max-pool window positions (dy*2+dx of the first maximum) kept for
  * conv layer l, one byte per pooled output, to a HOST array [batch*c_out*(h/2)*(w/2)]; RAD_ERR_PARAM if the
- * layer has no pool. */
+ * layer has no max pool. */
 rad_status rad_model_export_pool_arg(rad_ctx* ctx, const rad_model* model, int32_t l, uint8_t* out);
 /* Device pointer to the logits of the last step ([batch, classes], model dtype). */
 const void* rad_model_logits(const rad_model* model);

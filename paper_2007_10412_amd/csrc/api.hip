@@ -967,7 +967,7 @@ extern "C" const void* rad_model_logits(const rad_model* m) { return m ? m->logi
 extern "C" rad_status rad_model_export_pool_arg(rad_ctx* c, const rad_model* m, int32_t l, uint8_t* out) {
   if (!c) return RAD_ERR_NULL;
   if (!m || !out) return fail(c, RAD_ERR_NULL, "null argument");
-  if (l < 0 || l >= (int32_t)m->convs.size() || !m->convs[(size_t)l].arg) return fail(c, RAD_ERR_PARAM, "layer has no pool");
+  if (l < 0 || l >= (int32_t)m->convs.size() || !m->convs[(size_t)l].arg) return fail(c, RAD_ERR_PARAM, "layer has no max pool");
   const rad_model::Conv& cv = m->convs[(size_t)l];
   const size_t n = (size_t)m->batch * cv.co * (cv.h / 2) * (cv.w / 2);
   std::vector<uint32_t> words((n + 15) / 16);
@@ -1244,6 +1244,8 @@ extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t batch, int32_t n_
   if (n_conv < 1 || n_conv > 32 || batch < 1 || classes < 1 || ksize < 1 || (ksize & 1) == 0)
     return fail(c, RAD_ERR_SHAPE, "bad CNN shape (odd kernel size, at least one conv)");
   if (scheme == RAD_PROJECT_SHARED) return fail(c, RAD_ERR_UNSUPPORTED, "the projection scheme serves MLP models only");
+  for (int l = 0; l < n_conv; ++l)
+    if (pool[l] < 0 || pool[l] > 2) return fail(c, RAD_ERR_PARAM, "pool[l] is 0 (none), 1 (max) or 2 (average)");
   rad_model* m = new rad_model();
   m->kind = kCnn; m->dtype = kF32; m->scheme = scheme; m->p = p; m->batch = batch; m->ksize = ksize;
   m->classes = classes; m->has_bias = 1;
@@ -1262,12 +1264,14 @@ extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t batch, int32_t n_
     rad_status st = rad_store_create(c, &L, scheme, p, 1, &s);
     if (st != RAD_OK) { rad_model_destroy(m); return st; }
     m->stores.push_back(s);
-    rad_model::Conv cv{channels[l], channels[l + 1], h, w, pool[l] ? 1 : 0, nullptr};
+    rad_model::Conv cv{channels[l], channels[l + 1], h, w, pool[l], nullptr};
     if ((size_t)L.d_out > widest) widest = (size_t)L.d_out;
     if (cv.pool) {
       if ((h & 1) || (w & 1)) { rad_model_destroy(m); return fail(c, RAD_ERR_SHAPE, "pooled layers need even H and W"); }
-      const size_t words = ((size_t)batch * cv.co * (h / 2) * (w / 2) + 15) / 16;
-      if (hipMalloc((void**)&cv.arg, words * 4) != hipSuccess) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+      if (cv.pool == 1) {      // max pool keeps 2-bit window positions; the average pool keeps nothing
+        const size_t words = ((size_t)batch * cv.co * (h / 2) * (w / 2) + 15) / 16;
+        if (hipMalloc((void**)&cv.arg, words * 4) != hipSuccess) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
+      }
       h /= 2; w /= 2;
     }
     m->convs.push_back(cv);
@@ -1327,10 +1331,17 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
                       static_cast<const float*>(params[2 * l + 1]), 1, static_cast<float*>(m->buf[yb]), s->bits,
                       s->bits_pitch));
     if (cv.pool) {
-      HIP_TRY(c, timed(c, "maxpool", [&](const char**) {
-        return launch_maxpool_fwd(static_cast<const float*>(m->buf[yb]), B * cv.co, cv.h, cv.w,
-                                  static_cast<float*>(m->buf[pb]), cv.arg, c->stream);
-      }));
+      if (cv.pool == 1) {
+        HIP_TRY(c, timed(c, "maxpool", [&](const char**) {
+          return launch_maxpool_fwd(static_cast<const float*>(m->buf[yb]), B * cv.co, cv.h, cv.w,
+                                    static_cast<float*>(m->buf[pb]), cv.arg, c->stream);
+        }));
+      } else {
+        HIP_TRY(c, timed(c, "avgpool", [&](const char**) {
+          return launch_avgpool_fwd(static_cast<const float*>(m->buf[yb]), B * cv.co, cv.h, cv.w,
+                                    static_cast<float*>(m->buf[pb]), c->stream);
+        }));
+      }
       act = static_cast<const float*>(m->buf[pb]); in_buf = pb;
     } else { act = static_cast<const float*>(m->buf[yb]); in_buf = yb; }
   }
@@ -1358,7 +1369,7 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
     float* g = static_cast<float*>(m->buf[gb]);
     // g = dL/dh of this layer: route through the pool, then the 1-bit ReLU Jacobian (Section 4.2)
     HIP_TRY(c, timed(c, "unpool_mask", [&](const char**) {
-      return launch_unpool_mask(static_cast<const float*>(m->buf[db_]), B, cv.co, cv.h, cv.w, cv.arg, s->bits,
+      return launch_unpool_mask(static_cast<const float*>(m->buf[db_]), B, cv.co, cv.h, cv.w, cv.pool, cv.arg, s->bits,
                                 s->bits_pitch, g, c->stream);
     }));
     // dW from the sampled input (Figure 5): x~ scattered back to a dense transient, contracted with g

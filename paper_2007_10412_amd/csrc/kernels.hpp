@@ -107,8 +107,11 @@ hipError_t launch_splitk_bias(const float* partial, int splits, int M, int N, co
 // 2x2/stride-2 max pool over NCHW planes; arg packs the 2-bit window position (dy*2+dx of the first maximum)
 // of 16 consecutive outputs per word
 hipError_t launch_maxpool_fwd(const float* y, int planes, int H, int W, float* pooled, uint32_t* arg, hipStream_t st);
-// g[b,c,y,x] = upstream gradient routed through the pool (if arg) and masked by the ReLU bits of the layer
-hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, const uint32_t* arg,
+// 2x2/stride-2 average pool over NCHW planes (even H and W)
+hipError_t launch_avgpool_fwd(const float* y, int planes, int H, int W, float* pooled, hipStream_t st);
+// g[b,c,y,x] = upstream gradient routed through the pool (pool: 0 none, 1 max pool with positions in arg,
+// 2 average pool) and masked by the ReLU bits of the layer
+hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, int pool, const uint32_t* arg,
                               const uint32_t* bits, int bits_pitch, float* g, hipStream_t st);
 // db[c] = sum over b, y, x of g[b,c,y,x]
 hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* db, hipStream_t st);

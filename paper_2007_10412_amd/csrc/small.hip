@@ -265,9 +265,26 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float* __restric
   arg[q0 / 16] = word;
 }
 
-// g = (dy routed back through the pool, if any) masked by the ReLU bits of the layer output [B][C*H*W]
+// 2x2 average pool, stride 2 (the pooling of the convolutional architecture in Appendix A): one thread per
+// output; nothing is kept for the backward pass.
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const float* __restrict__ y, int planes, int H, int W,
+                                                          float* __restrict__ pooled) {
+  const int Ho = H / 2, Wo = W / 2;
+  const int64_t total = (int64_t)planes * Ho * Wo;
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= total) return;
+  const int64_t pl = q / (Ho * Wo);
+  const int r = (int)(q - pl * (Ho * Wo));
+  const int oy = r / Wo, ox = r - oy * Wo;
+  const float* src = y + (size_t)pl * H * W + (size_t)(2 * oy) * W + 2 * ox;
+  const float2 top = *reinterpret_cast<const float2*>(src), bot = *reinterpret_cast<const float2*>(src + W);
+  pooled[q] = 0.25f * ((top.x + top.y) + (bot.x + bot.y));
+}
+
+// g = (dy routed back through the pool, if any) masked by the ReLU bits of the layer output [B][C*H*W];
+// pool: 0 none, 1 max pool (2-bit window positions in arg), 2 average pool
 __global__ __launch_bounds__(256) void unpool_mask_kernel(const float* __restrict__ dy, int batch, int C, int H, int W,
-                                                          const uint32_t* __restrict__ arg,
+                                                          int pool, const uint32_t* __restrict__ arg,
                                                           const uint32_t* __restrict__ bits, int bits_pitch,
                                                           float* __restrict__ g) {
   const int64_t per = (int64_t)C * H * W;
@@ -276,13 +293,17 @@ __global__ __launch_bounds__(256) void unpool_mask_kernel(const float* __restric
   const int b = (int)(i / per);
   const int64_t f = i - (int64_t)b * per;
   float v;
-  if (arg) {
+  if (pool) {
     const int Ho = H / 2, Wo = W / 2;
     const int c = (int)(f / (H * W)), yx = (int)(f - (int64_t)c * H * W);
     const int y = yx / W, x = yx - y * W;
     const int64_t q = ((int64_t)(b * C + c) * Ho + y / 2) * Wo + x / 2;
-    const uint32_t pos = (arg[q / 16] >> (2 * (q % 16))) & 3u;
-    v = (pos == (uint32_t)((y & 1) * 2 + (x & 1))) ? dy[q] : 0.f;
+    if (pool == 1) {
+      const uint32_t pos = (arg[q / 16] >> (2 * (q % 16))) & 3u;
+      v = (pos == (uint32_t)((y & 1) * 2 + (x & 1))) ? dy[q] : 0.f;
+    } else {
+      v = 0.25f * dy[q];
+    }
   } else {
     v = dy[i];
   }
@@ -408,10 +429,16 @@ hipError_t launch_maxpool_fwd(const float* y, int planes, int H, int W, float* p
   return hipGetLastError();
 }
 
-hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, const uint32_t* arg,
+hipError_t launch_avgpool_fwd(const float* y, int planes, int H, int W, float* pooled, hipStream_t st) {
+  const int64_t total = (int64_t)planes * (H / 2) * (W / 2);
+  hipLaunchKernelGGL(avgpool_fwd_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, y, planes, H, W, pooled);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, int pool, const uint32_t* arg,
                               const uint32_t* bits, int bits_pitch, float* g, hipStream_t st) {
   const int64_t n = (int64_t)batch * C * H * W;
-  hipLaunchKernelGGL(unpool_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dy, batch, C, H, W, arg,
+  hipLaunchKernelGGL(unpool_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dy, batch, C, H, W, pool, arg,
                      bits, bits_pitch, g);
   return hipGetLastError();
 }

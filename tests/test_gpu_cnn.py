@@ -43,6 +43,7 @@ def run_cnn(ctx, d, channels, pool, ksize, hw, classes, scheme, p, seed):
             gbits.append(bits.reshape(Bt, co, size, size))
             if pool[l]:
                 size //= 2
+            if pool[l] == 1:
                 gargs.append(B.rad_model_export_pool_arg(ctx, m, l, Bt * co * size * size).reshape(Bt, co, size, size))
             else:
                 gargs.append(None)
@@ -94,3 +95,26 @@ def test_config3_reduced_batch(ctx):
     ch, pool = (3, 16, 32, 64), (0, 1, 1)
     d = synth.cnn(seed=1234, batch=24, channels=ch, pool=pool, ksize=3, hw=32, classes=10)
     run_cnn(ctx, d, ch, pool, 3, 32, 10, 1, 0.1, seed=5)
+
+
+@pytest.mark.parametrize("scheme,p", [(1, 0.1), (3, 0.25), (0, 1.0)])
+def test_cnn_paper_architecture_with_average_pools(ctx, scheme, p):
+    """The convolutional architecture of Appendix A (5x5 convolutions with 16, 32, 32, 32 feature maps and 2
+    zero padding, 2x2 average pools after the second and fourth, linear 2048 -> 10) at batch 6: loss, stores
+    and every gradient against the oracle.  The average pool keeps nothing for the backward pass."""
+    from paper_2007_10412_amd import synth
+    ch, pool = (3, 16, 32, 32, 32), (0, 2, 0, 2)
+    d = synth.cnn(seed=9, batch=6, channels=ch, pool=pool, ksize=5, hw=32, classes=10)
+    for cv in d["convs"]:
+        cv["b"] = (0.05 * np.random.default_rng(3).standard_normal(cv["b"].shape)).astype(np.float32)
+    run_cnn(ctx, d, ch, pool, 5, 32, 10, scheme, p, seed=6)
+
+
+def test_cnn_mixed_pools_and_bad_pool_kind(ctx):
+    from paper_2007_10412_amd import binding as B, synth
+    for pool in ((2, 1, 0), (1, 2, 0)):
+        ch = (3, 8, 8, 16)
+        d = synth.cnn(seed=10, batch=4, channels=ch, pool=pool, ksize=3, hw=32, classes=5)
+        run_cnn(ctx, d, ch, pool, 3, 32, 5, 1, 0.3, seed=8)
+    with pytest.raises(B.RadError):
+        B.rad_model_create_cnn(ctx, 4, [3, 8], [3], 3, 16, 16, 5, 1, 0.3)
