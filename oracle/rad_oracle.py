@@ -33,7 +33,8 @@ pass uses x~ = z R^T / sqrt(k) (pins: E[P] = I, the closed-form variance
 Pins (tests/test_oracle_*.py): Philox against PyTorch's own Philox4_32 engine;
 k = ceil(p d) against the eight worked values of Appendix A; byte accounting
 against Appendix A and Table 1; p = 1 against torch autograd; mean and variance
-over seeds against closed forms; selection against brute force.  Convergence
+over seeds against closed forms; selection against brute force; the optimiser
+steps against torch.optim on the CPU and a closed form.  Convergence
 curves of the paper (figures only) are not reproducible: parity unpinned there.
 """
 from __future__ import annotations
@@ -572,6 +573,37 @@ def rnn_train_step(x, labels, W_ih, W_hh, b, W_ho, b_o, scheme, p, seed,
         dh = (g @ W_hh64.T).astype(np.float32)
     return dict(loss=loss, dW_hh=dW_hh, dW_ih=dW_ih, db=db, dW_ho=dW_ho,
                 db_o=db_o, h_T=h_prev, logits=z)
+
+
+# ----------------------------------------------------------------------------
+# Parameter updates (Section 5 and Appendix A, feedforward and RNN training
+# details): the feedforward networks are trained with Adam, with a tuned
+# learning rate and l2 regularisation coefficient; the RNN with plain SGD
+# without momentum.  The l2 term enters as a gradient of (l2/2)|w|^2, i.e.
+# g + l2 w (a reading: the paper names the coefficient, not the form).  Adam is
+# the algorithm the paper cites (Kingma & Ba 2015, Algorithm 1): exponential
+# moving averages of g and g^2, both divided by 1 - beta^t, step
+# lr m^ / (sqrt(v^) + eps).  Learning-rate schedules (Appendix A multiplies the
+# rate by 0.6 at fixed intervals) belong to the caller, who passes lr per step.
+# Pins (tests/test_oracle_optim.py): torch.optim's CPU SGD and Adam, and the
+# closed form under a constant gradient.
+# ----------------------------------------------------------------------------
+def sgd_step(w, g, lr, l2=0.0):
+    w = np.asarray(w, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64) + l2 * w
+    return w - lr * g
+
+
+def adam_step(w, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, l2=0.0):
+    """Step number t (1, 2, ...) from moments m, v (zeros before step 1);
+    returns the new (w, m, v), all float64."""
+    w = np.asarray(w, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64) + l2 * w
+    m = beta1 * np.asarray(m, dtype=np.float64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, dtype=np.float64) + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** t)
+    v_hat = v / (1.0 - beta2 ** t)
+    return w - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
 
 
 # ----------------------------------------------------------------------------
