@@ -215,6 +215,7 @@ def main():
                 kern[nm]["executed_tflops"] = f / (kern[nm]["ms_per_step"] * 1e-3) / 1e12
         out["kernels"] = kern
         out["pack_stream"] = pack_stream(B, ctx, torch, dtype_name)
+        out["optimizer"] = optimizer_stream(B, ctx, torch, dtype, params, grads)
         out["other_configs"] = other_configs(B, ctx, torch, synth)
         if args.workload == "mlp4096_bf16":
             out["config4_variants"] = config4_variants(B, ctx, torch, data, dims, batch)
@@ -362,6 +363,35 @@ def pack_stream(B, ctx, torch, dtype_name):
                      "unit": "GB/s", "frac": pack_bytes / t_pack / 1e9 / HBM_PEAK},
             "plan": {"bound": "alu", "ms": t_plan * 1e3, "keys_per_s": n / t_plan,
                      "write_GBps": plan_bytes / t_plan / 1e9}}
+
+
+def optimizer_stream(B, ctx, torch, dtype, params, grads):
+    """One Adam step over the workload's parameters after the step's gradients (outside the timed step: the
+    metric is the forward + backward step).  An HBM stream: per parameter 16 bytes read (fp32 master or
+    parameter, gradient, two moments), 12 written, and 2 more for the bf16 copy."""
+    bf16 = dtype == B.RAD_BF16
+    master = [p_.to(torch.float32) for p_ in params] if bf16 else None
+    m = [torch.zeros_like(g) for g in grads]
+    v = [torch.zeros_like(g) for g in grads]
+    opt = B.make_optimizer(B.RAD_ADAM, 1e-4, 1e-5)
+    keep = [p_.clone() for p_ in params]
+    B.rad_ctx_timing(ctx, None)
+    for t in (1, 2):
+        B.rad_optimizer_step(ctx, opt, t, dtype, params, grads, m, v, master)
+    B.rad_ctx_timing_reset(ctx)
+    reps = 10
+    for t in range(3, 3 + reps):
+        B.rad_optimizer_step(ctx, opt, t, dtype, params, grads, m, v, master)
+    n_l, ms = B.rad_ctx_timing_read(ctx, "optim_adam")
+    B.rad_ctx_timing(ctx, "")
+    B.rad_ctx_timing_reset(ctx)
+    for p_, k_ in zip(params, keep):      # the parameters the rest of the run uses stay as they were
+        p_.copy_(k_)
+    n = sum(int(p_.numel()) for p_ in params)
+    bytes_ = n * (30 if bf16 else 28)
+    t_step = ms / reps * 1e-3
+    return {"kind": "adam", "parameters": n, "ms_per_step": t_step * 1e3, "bound": "hbm",
+            "achieved": bytes_ / t_step / 1e9, "peak": HBM_PEAK, "unit": "GB/s", "frac": bytes_ / t_step / 1e9 / HBM_PEAK}
 
 
 def cpu_baseline(data, dims, scheme, p, dtype, batch, has_bias):

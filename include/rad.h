@@ -276,6 +276,39 @@ rad_status rad_train_step(rad_ctx* ctx, rad_model* model, const rad_sampling* sa
                           const void* x, const int32_t* labels, void* const* params,
                           void* const* grads, float* loss_host);
 
+/* ---- parameter updates ---------------------------------------------------
+ * Section 5 and Appendix A (training details): the feedforward networks are
+ * trained with Adam with a tuned learning rate and l2 regularisation, the
+ * recurrent one with SGD without momentum.  The l2 term enters the gradient
+ * as l2 * w.  Learning-rate schedules are the caller's: lr is per call. */
+typedef enum { RAD_SGD = 0, RAD_ADAM = 1 } rad_optimizer_kind;
+typedef struct {
+  int32_t kind;             /* rad_optimizer_kind */
+  double lr, l2;            /* lr > 0; l2 >= 0 */
+  double beta1, beta2, eps; /* RAD_ADAM only: 0 <= beta < 1, eps > 0 */
+} rad_optimizer;
+
+/* One optimiser step, number t = 1, 2, ... (Adam's bias correction uses it),
+ * over n_tensors tensors of counts[i] elements; all arithmetic in fp32:
+ *   g' = g + l2 w
+ *   SGD:  w -= lr g'
+ *   Adam: m = beta1 m + (1-beta1) g';  v = beta2 v + (1-beta2) g'^2;
+ *         w -= lr (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps)
+ * counts and the pointer arrays are HOST arrays; their entries are DEVICE
+ * pointers owned by the caller: grads[i] fp32 (read), m[i] and v[i] fp32
+ * moments (RAD_ADAM; updated in place, zero before step 1; the arrays may be
+ * null for RAD_SGD).  dtype RAD_F32: params[i] fp32, updated in place, master
+ * is ignored (may be null).  dtype RAD_BF16: master[i] holds the fp32 master
+ * copy that is updated in place, and params[i] (bf16) receives its rounding
+ * to nearest even.  Enqueued on the context's stream; does not wait.
+ * Errors (nothing is launched): RAD_ERR_NULL for a missing array or entry,
+ * RAD_ERR_SHAPE for a negative count or n_tensors, RAD_ERR_PARAM for an
+ * unknown kind or dtype, t < 1, or coefficients outside the ranges above. */
+rad_status rad_optimizer_step(rad_ctx* ctx, const rad_optimizer* opt, int64_t t, int32_t dtype,
+                              int32_t n_tensors, const int64_t* counts, void* const* params,
+                              const void* const* grads, void* const* m, void* const* v,
+                              void* const* master);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,6 +37,14 @@ class rad_store_stats(C.Structure):
 
 # every symbol include/rad.h declares: name -> (restype, argtypes)
 P = C.c_void_p
+RAD_SGD, RAD_ADAM = 0, 1
+
+
+class rad_optimizer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_double), ("l2", C.c_double), ("beta1", C.c_double),
+                ("beta2", C.c_double), ("eps", C.c_double)]
+
+
 SIGNATURES = {
     "rad_fixed_k": (C.c_int64, [C.c_double, C.c_int64]),
     "rad_ctx_create": (C.c_int, [C.POINTER(P), P]),
@@ -75,6 +83,9 @@ SIGNATURES = {
     "rad_model_export_pool_arg": (C.c_int, [P, P, C.c_int32, P]),
     "rad_train_step": (C.c_int, [P, P, C.POINTER(rad_sampling), P, P, C.POINTER(P), C.POINTER(P),
                                  C.POINTER(C.c_float)]),
+    "rad_optimizer_step": (C.c_int, [P, C.POINTER(rad_optimizer), C.c_int64, C.c_int32, C.c_int32,
+                                     C.POINTER(C.c_int64), C.POINTER(P), C.POINTER(P), C.POINTER(P), C.POINTER(P),
+                                     C.POINTER(P)]),
 }
 
 _lib = None
@@ -300,3 +311,18 @@ def rad_train_step(ctx, model, sampling, x, labels, params, grads, want_loss=Tru
     loss = C.c_float()
     _check(ctx, lib().rad_train_step(ctx, model, C.byref(sampling), _ptr(x), _ptr(labels), pa, ga, C.byref(loss)))
     return loss.value
+
+
+def make_optimizer(kind, lr, l2=0.0, beta1=0.9, beta2=0.999, eps=1e-8):
+    return rad_optimizer(kind, lr, l2, beta1, beta2, eps)
+
+
+def rad_optimizer_step(ctx, opt, t, dtype, params, grads, m=None, v=None, master=None):
+    """params, grads, m, v, master: lists of torch tensors (m, v for RAD_ADAM; master for RAD_BF16)."""
+    n = len(params)
+
+    def arr(ts):
+        return None if ts is None else (P * n)(*[x.data_ptr() for x in ts])
+    counts = (C.c_int64 * n)(*[int(x.numel()) for x in params])
+    _check(ctx, lib().rad_optimizer_step(ctx, C.byref(opt), int(t), dtype, n, counts, arr(params), arr(grads), arr(m),
+                                         arr(v), arr(master)))

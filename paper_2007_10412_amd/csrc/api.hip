@@ -910,6 +910,49 @@ extern "C" rad_status rad_softmax_ce(rad_ctx* c, const void* logits, const int32
   return softmax_call(c, logits, labels, (int)rows, (int)classes, dtype, dlogits, loss_dev);
 }
 
+// ------------------------------------------------------------------ parameter updates
+extern "C" rad_status rad_optimizer_step(rad_ctx* c, const rad_optimizer* opt, int64_t t, int32_t dtype,
+                                         int32_t n_tensors, const int64_t* counts, void* const* params,
+                                         const void* const* grads, void* const* m, void* const* v,
+                                         void* const* master) {
+  if (!c) return RAD_ERR_NULL;
+  if (!opt || !counts || !params || !grads) return fail(c, RAD_ERR_NULL, "null argument");
+  if (opt->kind != RAD_SGD && opt->kind != RAD_ADAM) return fail(c, RAD_ERR_PARAM, "unknown optimiser kind");
+  if (dtype != RAD_F32 && dtype != RAD_BF16) return fail(c, RAD_ERR_PARAM, "unknown dtype");
+  const bool adam = opt->kind == RAD_ADAM;
+  if (n_tensors < 0) return fail(c, RAD_ERR_SHAPE, "negative tensor count");
+  if (t < 1) return fail(c, RAD_ERR_PARAM, "step numbers start at 1");
+  if (!(opt->lr > 0.0) || !std::isfinite(opt->lr) || !(opt->l2 >= 0.0) || !std::isfinite(opt->l2))
+    return fail(c, RAD_ERR_PARAM, "lr must be positive and l2 non-negative");
+  if (adam && (!(opt->beta1 >= 0.0 && opt->beta1 < 1.0) || !(opt->beta2 >= 0.0 && opt->beta2 < 1.0) ||
+               !(opt->eps > 0.0) || !std::isfinite(opt->eps)))
+    return fail(c, RAD_ERR_PARAM, "Adam needs 0 <= beta < 1 and eps > 0");
+  if (adam && (!m || !v)) return fail(c, RAD_ERR_NULL, "Adam needs the moment arrays");
+  if (dtype == RAD_BF16 && !master) return fail(c, RAD_ERR_NULL, "bf16 parameters need fp32 master copies");
+  for (int i = 0; i < n_tensors; ++i) {
+    if (counts[i] < 0) return fail(c, RAD_ERR_SHAPE, "negative element count");
+    if (counts[i] == 0) continue;
+    if (!params[i] || !grads[i] || (adam && (!m[i] || !v[i])) || (dtype == RAD_BF16 && !master[i]))
+      return fail(c, RAD_ERR_NULL, "null tensor pointer");
+  }
+  OptimArgs a;
+  a.lr = (float)opt->lr; a.l2 = (float)opt->l2;
+  a.beta1 = adam ? (float)opt->beta1 : 0.f; a.beta2 = adam ? (float)opt->beta2 : 0.f; a.eps = adam ? (float)opt->eps : 0.f;
+  a.omb1 = adam ? (float)(1.0 - opt->beta1) : 0.f; a.omb2 = adam ? (float)(1.0 - opt->beta2) : 0.f;
+  a.inv_bc1 = adam ? (float)(1.0 / (1.0 - std::pow(opt->beta1, (double)t))) : 1.f;
+  a.inv_bc2 = adam ? (float)(1.0 / (1.0 - std::pow(opt->beta2, (double)t))) : 1.f;
+  for (int i = 0; i < n_tensors; ++i) {
+    if (counts[i] == 0) continue;
+    float* w = static_cast<float*>(dtype == RAD_BF16 ? master[i] : params[i]);
+    uint16_t* lo = dtype == RAD_BF16 ? static_cast<uint16_t*>(params[i]) : nullptr;
+    HIP_TRY(c, timed(c, adam ? "optim_adam" : "optim_sgd", [&](const char**) {
+      return launch_optim(adam, w, lo, static_cast<const float*>(grads[i]), adam ? static_cast<float*>(m[i]) : nullptr,
+                          adam ? static_cast<float*>(v[i]) : nullptr, counts[i], a, c->stream);
+    }));
+  }
+  return RAD_OK;
+}
+
 // ------------------------------------------------------------------ models
 enum ModelKind { kMlp = 0, kRnn = 1, kCnn = 2 };
 

@@ -113,6 +113,13 @@ hipError_t launch_avgpool_fwd(const float* y, int planes, int H, int W, float* p
 // 2 average pool) and masked by the ReLU bits of the layer
 hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, int pool, const uint32_t* arg,
                               const uint32_t* bits, int bits_pitch, float* g, hipStream_t st);
+// One optimiser step over n parameters: w (fp32, updated in place), g (fp32 gradient), Adam moments m, v (fp32,
+// updated in place; unused for SGD), lo: bf16 copy of w to refresh, or null.  inv_bc1 / inv_bc2 are
+// 1 / (1 - beta^t) of the step number and omb1 / omb2 are 1 - beta, all formed in double by the caller (in fp32
+// 1 - 0.9f is off by 2e-7 of its value).
+struct OptimArgs { float lr, l2, beta1, beta2, omb1, omb2, eps, inv_bc1, inv_bc2; };
+hipError_t launch_optim(bool adam, float* w, uint16_t* lo, const float* g, float* m, float* v, int64_t n,
+                        const OptimArgs& a, hipStream_t st);
 // db[c] = sum over b, y, x of g[b,c,y,x]
 hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* db, hipStream_t st);
 // Wt[(o,u,v)][c] = W[c][KH-1-u][KW-1-v][o]: the weight operand of the transposed convolution (dX)
