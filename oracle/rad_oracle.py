@@ -53,6 +53,7 @@ FIXEDK_PER_EXAMPLE = 3  # "different sample": a k-subset per minibatch element
 REPLACE_SHARED = 4      # k draws WITH replacement, one set for the whole minibatch
 REPLACE_PER_EXAMPLE = 5  # k draws WITH replacement per minibatch element
 PROJECT_SHARED = 6      # "project": x R / sqrt(k) with one Rademacher matrix R [d, k]
+PROJECT_PER_EXAMPLE = 7  # "different project": a Rademacher matrix of its own for every example
 
 F32 = 0
 BF16 = 1
@@ -181,16 +182,41 @@ def rademacher_matrix(p, seed, stream_id, step, d):
     return (1.0 - 2.0 * bit.astype(np.float64)).reshape(d, k)
 
 
-def project_store(x, p, seed, stream_id, step, dtype=F32):
+def rademacher_matrix_of_example(p, seed, stream_id, step, b, d):
+    """R_b [d, k] for example b ("different project", Appendix A, RNN
+    experiments: a different random matrix for each mini-batch element).  Row
+    (b, j) of the sign tensor owns the 4 C consecutive keys that start at flat
+    index (b d + j) 4 C, C = ceil(k / 128), i.e. whole Philox calls; sign s is
+    bit s mod 32 of the row's key number s div 32; clear is +1, set is -1.
+    """
+    k = fixed_k(p, d)
+    words_per_row = 4 * ((k + 127) // 128)
+    words = element_keys(seed, stream_id, step, b * d * words_per_row, d * words_per_row)
+    words = words.reshape(d, words_per_row)
+    sidx = np.arange(k)
+    bit = (words[:, sidx >> 5] >> (sidx & 31).astype(np.uint32)[None, :]) & np.uint32(1)
+    return 1.0 - 2.0 * bit.astype(np.float64)
+
+
+def project_store(x, p, seed, stream_id, step, dtype=F32, per_example=False):
     """z = storage(x R * fp32(1/sqrt(k))) [rows, k] and the backward operand
-    x~ = z R^T / sqrt(k) [rows, d] (fp64), so that x~ = x P with P = R R^T / k."""
+    x~ = z R^T / sqrt(k) [rows, d] (fp64), so that x~ = x P with P = R R^T / k;
+    per_example: row b uses its own R_b."""
     x = np.asarray(x, dtype=np.float32)
-    d = x.shape[1]
-    R = rademacher_matrix(p, seed, stream_id, step, d)
-    k = R.shape[1]
+    rows, d = x.shape
+    k = fixed_k(p, d)
     inv = np.float64(np.float32(1.0 / math.sqrt(k)))
-    z = to_storage((x.astype(np.float64) @ R) * inv, dtype)
-    xt = (z.astype(np.float64) @ R.T) * inv
+    if not per_example:
+        R = rademacher_matrix(p, seed, stream_id, step, d)
+        z = to_storage((x.astype(np.float64) @ R) * inv, dtype)
+        xt = (z.astype(np.float64) @ R.T) * inv
+        return z, xt
+    z = np.zeros((rows, k), dtype=np.float32)
+    xt = np.zeros((rows, d))
+    for b in range(rows):
+        R = rademacher_matrix_of_example(p, seed, stream_id, step, b, d)
+        z[b] = to_storage((x[b].astype(np.float64) @ R) * inv, dtype)
+        xt[b] = (z[b].astype(np.float64) @ R.T) * inv
     return z, xt
 
 
@@ -257,9 +283,9 @@ def sample_pack(x, scheme, p, seed, stream_id, step, dtype=F32):
     """
     x = np.asarray(x, dtype=np.float32)
     rows, d = x.shape
-    if scheme == PROJECT_SHARED:
+    if scheme in (PROJECT_SHARED, PROJECT_PER_EXAMPLE):
         # the store is the dense projection z: listed as k "columns" 0..k-1 per row
-        z, xt = project_store(x, p, seed, stream_id, step, dtype)
+        z, xt = project_store(x, p, seed, stream_id, step, dtype, scheme == PROJECT_PER_EXAMPLE)
         k = z.shape[1]
         row_ptr = np.arange(rows + 1, dtype=np.int64) * k
         col = np.tile(np.arange(k, dtype=np.int32), rows)

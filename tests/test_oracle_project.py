@@ -105,3 +105,69 @@ def test_train_step_keeps_the_exact_chain():
     for l in range(3):
         assert np.array_equal(out["dy"][l], ref["dy"][l])
         assert not np.array_equal(out["dW"][l], ref["dW"][l])
+
+
+# ------------------------------------------------------------------ a matrix of its own for every example
+def test_per_example_sign_bits_by_big_integers():
+    """Row (b, j) owns whole Philox calls: 4 ceil(k/128) keys from flat index (b d + j) 4 ceil(k/128) on."""
+    for d, p in ((21, 0.4), (400, 0.4)):            # k = 9 (one call per row), k = 160 (two)
+        k = R.fixed_k(p, d)
+        wpr = 4 * ((k + 127) // 128)
+        for b in (0, 3):
+            Rb = R.rademacher_matrix_of_example(p, 5, 2, 1, b, d)
+            assert Rb.shape == (d, k) and set(np.unique(Rb)) == {-1.0, 1.0}
+            for j in (0, 1, d - 1):
+                words = R.element_keys(5, 2, 1, (b * d + j) * wpr, wpr)
+                for s in range(k):
+                    bit = (int(words[s // 32]) >> (s % 32)) & 1
+                    assert Rb[j, s] == (1.0 if bit == 0 else -1.0)
+
+
+def test_per_example_matrices_are_unrelated():
+    d, p = 512, 0.25
+    R0 = R.rademacher_matrix_of_example(p, 1, 0, 0, 0, d)
+    R1 = R.rademacher_matrix_of_example(p, 1, 0, 0, 1, d)
+    n = R0.size
+    assert abs(R0.mean()) < 5 / np.sqrt(n) and abs((R0 * R1).mean()) < 5 / np.sqrt(n)
+    assert abs((R0[1:] * R0[:-1]).mean()) < 5 / np.sqrt(n)        # neighbouring rows
+    assert abs((R0[:, 1:] * R0[:, :-1]).mean()) < 5 / np.sqrt(n)  # neighbouring columns
+
+
+def test_per_example_store_is_x_times_its_own_P():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((5, 150)).astype(np.float32)
+    rp, col, val, xt = R.sample_pack(x, R.PROJECT_PER_EXAMPLE, 0.2, 4, 1, 0)
+    k = R.fixed_k(0.2, 150)
+    assert np.array_equal(rp, np.arange(6) * k) and len(val) == 5 * k
+    for b in range(5):
+        Rb = R.rademacher_matrix_of_example(0.2, 4, 1, 0, b, 150)
+        want = x[b].astype(np.float64) @ (Rb @ Rb.T) / k
+        assert np.abs(xt[b] - want).max() < 1e-5 * np.abs(want).max()
+
+
+def test_per_example_unbiased_and_variance_closed_form():
+    """The examples' matrices are independent, so the variances of their contributions add:
+    Var dW~[j, n] = sum_b g[b, n]^2 (|x_b|^2 - x[b, j]^2) / k."""
+    rng = np.random.default_rng(18)
+    B, D, N, p, S = 6, 32, 3, 0.25, 6000
+    x = rng.standard_normal((B, D)).astype(np.float32)
+    dy = rng.standard_normal((B, N)).astype(np.float32)
+    bits = rng.random((B, N)) > 0.3
+    g = dy.astype(np.float64) * bits
+    exact = x.astype(np.float64).T @ g
+    acc = np.zeros_like(exact); acc2 = np.zeros_like(exact)
+    for s in range(S):
+        e = R.backward_dW(R.sample_pack(x, R.PROJECT_PER_EXAMPLE, p, s, 1, 0)[3], dy, bits)
+        acc += e; acc2 += e * e
+    mean = acc / S
+    var = acc2 / S - mean**2
+    k = R.fixed_k(p, D)
+    x64 = x.astype(np.float64)
+    var_cf = (((x64**2).sum(axis=1, keepdims=True) - x64**2).T @ g**2) / k
+    err = np.linalg.norm(mean - exact)
+    assert 0 < err < 4 * np.sqrt(var_cf.sum() / S)
+    assert abs(var.sum() / var_cf.sum() - 1) < 0.08
+    assert np.abs(var / var_cf - 1).max() < 0.35
+    # and it differs from the shared-matrix variance, whose cross terms between examples do not vanish
+    var_shared = ((exact**2).sum(axis=0, keepdims=True) - exact**2) / k
+    assert abs(var_shared.sum() / var_cf.sum() - 1) > 0.1
