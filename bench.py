@@ -37,7 +37,8 @@ WORKLOADS = {
 }
 SCHEMES = {"per_example": 3, "shared": 2, "bernoulli": 1, "exact": 0,
            "replace_per_example": 5, "replace_shared": 4,      # draws with replacement
-           "project": 6}                                       # Rademacher projection, one R per layer and step
+           "project": 6,                                       # Rademacher projection, one R per layer and step
+           "project_per_example": 7}                           # a Rademacher matrix per example
 
 
 def main():

@@ -59,7 +59,13 @@ typedef enum { RAD_F32 = 0, RAD_BF16 = 1 } rad_dtype; /* accumulation is always 
  * bit (j k + s) of the key stream; clear = +1).  The store is the dense
  * z = x R / sqrt(k), k numbers per row and no indices; dW is
  * R (z^T g) / sqrt(k), with R regenerated from the sampling parameters.
- * Linear layers and MLP models only. */
+ * PROJECT_PER_EXAMPLE (Appendix A, "different project") gives every row b a
+ * matrix R_b of its own: row (b, j) of the sign tensor owns the
+ * C = ceil(k/128) Philox calls numbered (b d_in + j) C onwards, sign s is bit
+ * s mod 32 of word (s / 32) mod 4 of call s / 128 (clear = +1); the store is
+ * z_b = x_b R_b / sqrt(k), and dW = x~^T g with x~_b = z_b R_b^T / sqrt(k)
+ * rebuilt row by row (never more than one layer's worth); k <= 38400.
+ * The projection schemes serve linear layers and MLP models only. */
 typedef enum {
   RAD_EXACT = 0,
   RAD_BERNOULLI = 1,
@@ -67,7 +73,8 @@ typedef enum {
   RAD_FIXEDK_PER_EXAMPLE = 3,
   RAD_REPLACE_SHARED = 4,
   RAD_REPLACE_PER_EXAMPLE = 5,
-  RAD_PROJECT_SHARED = 6
+  RAD_PROJECT_SHARED = 6,
+  RAD_PROJECT_PER_EXAMPLE = 7
 } rad_scheme;
 
 typedef enum { RAD_LINEAR = 0, RAD_CONV2D = 1 } rad_kind;

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(HERE, "librad_hip.so")
 RAD_OK, RAD_ERR_NULL, RAD_ERR_SHAPE, RAD_ERR_PARAM, RAD_ERR_UNSUPPORTED, RAD_ERR_CAPACITY, RAD_ERR_DEVICE = range(7)
 RAD_F32, RAD_BF16 = 0, 1
 (RAD_EXACT, RAD_BERNOULLI, RAD_FIXEDK_SHARED, RAD_FIXEDK_PER_EXAMPLE, RAD_REPLACE_SHARED, RAD_REPLACE_PER_EXAMPLE,
- RAD_PROJECT_SHARED) = range(7)
+ RAD_PROJECT_SHARED, RAD_PROJECT_PER_EXAMPLE) = range(8)
 RAD_LINEAR, RAD_CONV2D = 0, 1
 STATUS_NAMES = ["RAD_OK", "RAD_ERR_NULL", "RAD_ERR_SHAPE", "RAD_ERR_PARAM", "RAD_ERR_UNSUPPORTED",
                 "RAD_ERR_CAPACITY", "RAD_ERR_DEVICE"]

@@ -216,7 +216,7 @@ struct rad_store {
   bool per_entry() const { return scheme == kBernoulli || scheme == kFixedKPerExample || replace(); }
   bool paired() const { return dtype == kBF16 && per_entry() && !index_free; }
   bool replace() const { return scheme == kReplaceShared || scheme == kReplacePerExample; }
-  bool project() const { return scheme == kProjectShared; }
+  bool project() const { return scheme == kProjectShared || scheme == kProjectPerExample; }
   bool compact() const { return scheme == kFixedKShared || project(); }   // values are [rows][k_pitch]
   // rows hold a number of entries that only the plan kernel knows
   bool counted_rows() const { return scheme == kBernoulli || replace(); }
@@ -263,7 +263,7 @@ static rad_status check_layer(rad_ctx* c, const rad_layer* L) {
 }
 
 static rad_status check_scheme(rad_ctx* c, int scheme, double p) {
-  if (scheme < RAD_EXACT || scheme > RAD_PROJECT_SHARED) return fail(c, RAD_ERR_PARAM, "unknown sampling scheme");
+  if (scheme < RAD_EXACT || scheme > RAD_PROJECT_PER_EXAMPLE) return fail(c, RAD_ERR_PARAM, "unknown sampling scheme");
   if (!(p > 0.0) || p > 1.0) return fail(c, RAD_ERR_PARAM, "p must be in (0, 1]");
   return RAD_OK;
 }
@@ -285,9 +285,12 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   RAD_TRY(check_layer(c, L));
   RAD_TRY(check_scheme(c, scheme, p));
   if (steps < 1) return fail(c, RAD_ERR_SHAPE, "steps must be >= 1");
-  if (scheme == RAD_PROJECT_SHARED && (steps != 1 || L->kind != RAD_LINEAR))
-    return fail(c, RAD_ERR_UNSUPPORTED, "the projection scheme serves single-step linear layers only");
-  if (scheme != RAD_EXACT && scheme != RAD_PROJECT_SHARED) {
+  const bool proj = scheme == RAD_PROJECT_SHARED || scheme == RAD_PROJECT_PER_EXAMPLE;
+  if (proj && (steps != 1 || L->kind != RAD_LINEAR))
+    return fail(c, RAD_ERR_UNSUPPORTED, "the projection schemes serve single-step linear layers only");
+  if (scheme == RAD_PROJECT_PER_EXAMPLE && rad_fixed_k(p, L->d_in) > 38400)
+    return fail(c, RAD_ERR_UNSUPPORTED, "a projection per example keeps at most 38400 numbers per row");
+  if (scheme != RAD_EXACT && !proj) {
     if (L->d_in > 65535) return fail(c, RAD_ERR_UNSUPPORTED, "sampled stores need d_in <= 65535 (16-bit indices)");
     if (L->d_in > plan_max_cols(scheme) || (scheme != RAD_BERNOULLI && L->d_in > 16376 && L->d_in % 4 != 0))
       return fail(c, RAD_ERR_UNSUPPORTED, "fixed-k sampling needs d_in <= 16384 (16376 unless a multiple of 4)");
@@ -298,7 +301,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   s->scheme = scheme; s->dtype = L->dtype; s->rows = (int)L->batch; s->cols = (int)L->d_in;
   s->d_out = (int)L->d_out; s->steps = steps; s->p = p;
   s->k = (int)rad_fixed_k(p, L->d_in);
-  s->k_pitch = (scheme == RAD_FIXEDK_SHARED || scheme == RAD_PROJECT_SHARED) ? (s->k + 7) / 8 * 8 : s->k;
+  s->k_pitch = (scheme == RAD_FIXEDK_SHARED || proj) ? (s->k + 7) / 8 * 8 : s->k;
   s->nb = (s->cols + kBucket - 1) / kBucket;
   s->bm_pitch = (s->cols + 31) / 32;
   const int64_t R = (int64_t)steps * s->rows;
@@ -309,7 +312,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
     double cap = std::ceil((double)n * p + 8.0 * std::sqrt((double)n * p * (1.0 - p))) + 64.0;
     s->capacity = cap > (double)n ? n : (int64_t)cap;
     s->plan_rows_per_step = s->rows;
-  } else if (scheme == RAD_PROJECT_SHARED) {
+  } else if (proj) {
     s->scale = (float)(1.0 / std::sqrt((double)s->k));
     s->capacity = R * s->k_pitch;
     s->plan_rows_per_step = 0;
@@ -324,7 +327,7 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   bool ok = alloc(&s->values, s->paired() ? (size_t)(s->capacity + kPairPad) * 4 : (size_t)s->capacity * s->elem());
   ok = ok && alloc((void**)&s->overflow, 2 * sizeof(int));   // [0] capacity overflow flag, [1] longest bucket segment
   s->max_seg = s->overflow ? s->overflow + 1 : nullptr;
-  if (scheme != RAD_EXACT && scheme != RAD_PROJECT_SHARED) {
+  if (scheme != RAD_EXACT && !proj) {
     const size_t n_idx = scheme == RAD_FIXEDK_SHARED ? (size_t)steps * s->k : (size_t)s->capacity;
     if (!s->paired()) ok = ok && alloc((void**)&s->indices, n_idx * 2);
     ok = ok && alloc((void**)&s->row_ptr, (size_t)(R + 1) * 4);
@@ -650,6 +653,14 @@ static rad_status project_signs(rad_ctx* c, const rad_store* s, uint64_t seed, u
 
 // store <- z = x R / sqrt(k): one more forward-family GEMM per layer
 static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* sm, const void* x) {
+  if (s->scheme == kProjectPerExample) {       // every example times its own matrix, signs drawn in the kernel
+    HIP_TRY(c, timed(c, "project_rows_fwd", [&](const char**) {
+      return launch_project_rows_fwd(x, s->dtype, s->rows, s->cols, s->k, s->k_pitch, s->scale, s->values,
+                                     (uint32_t)sm->seed, (uint32_t)(sm->seed >> 32), sm->stream_id, sm->step, c->stream);
+    }));
+    s->proj_seed = sm->seed; s->proj_stream = sm->stream_id; s->proj_step = sm->step; s->proj_valid = true;
+    return RAD_OK;
+  }
   void *Rm = nullptr, *Rt = nullptr;
   RAD_TRY(project_signs(c, s, sm->seed, sm->stream_id, sm->step, &Rm, &Rt));
   GemmArgs g = gemm_zero();
@@ -665,6 +676,23 @@ static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* 
 static rad_status project_dW(rad_ctx* c, const rad_store* s, const void* dy, int N, const uint32_t* bits,
                              int bits_pitch, float* dW, int beta) {
   if (!s->proj_valid) return fail(c, RAD_ERR_PARAM, "the store holds no projection yet");
+  if (s->scheme == kProjectPerExample) {
+    // x~ = z R_b^T / sqrt(k) row by row into a transient dense operand (one layer's worth, reused), then the
+    // dense contraction x~^T g
+    void* dense = nullptr;
+    RAD_TRY(ws_get(c, WS_DENSE, (size_t)s->rows * s->cols * s->elem(), &dense));
+    HIP_TRY(c, timed(c, "project_rows_bwd", [&](const char**) {
+      return launch_project_rows_bwd(s->values, s->dtype, s->rows, s->cols, s->k, s->k_pitch, s->scale, dense,
+                                     (uint32_t)s->proj_seed, (uint32_t)(s->proj_seed >> 32), s->proj_stream,
+                                     s->proj_step, c->stream);
+    }));
+    GemmArgs g = gemm_zero();
+    g.M = s->cols; g.N = N; g.K = s->rows;
+    g.A = dense; g.lda = s->cols;
+    g.B = dy; g.ldb = N; g.b_mask = bits; g.b_mask_pitch = bits_pitch;
+    g.C = dW; g.ldc = N; g.beta = beta; g.c_dtype = kF32;
+    return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
+  }
   void *Rm = nullptr, *Rt = nullptr;
   RAD_TRY(project_signs(c, s, s->proj_seed, s->proj_stream, s->proj_step, &Rm, &Rt));
   void *T = nullptr, *Tb = nullptr;
@@ -1109,7 +1137,7 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   // forward: layer l consumes the dense activation of layer l-1 (kept only
   // until then) and leaves the packed sample of its own output for layer l+1
   RAD_TRY(model_clear_max_seg(c, m));
-  const bool proj = m->scheme == RAD_PROJECT_SHARED;
+  const bool proj = m->scheme == RAD_PROJECT_SHARED || m->scheme == RAD_PROJECT_PER_EXAMPLE;
   rad_sampling s0 = *sm;
   if (!proj) {
     RAD_TRY(store_plan(c, m->stores[0], &s0, static_cast<uint32_t*>(bm), false));
@@ -1175,7 +1203,7 @@ extern "C" rad_status rad_model_create_rnn(rad_ctx* c, int64_t batch, int64_t T,
   *out = nullptr;
   RAD_TRY(check_scheme(c, scheme, p));
   if (batch < 1 || T < 1 || d_input < 1 || hidden < 1 || classes < 1) return fail(c, RAD_ERR_SHAPE, "bad RNN shape");
-  if (scheme == RAD_PROJECT_SHARED) return fail(c, RAD_ERR_UNSUPPORTED, "the projection scheme serves MLP models only");
+  if (scheme == RAD_PROJECT_SHARED || scheme == RAD_PROJECT_PER_EXAMPLE) return fail(c, RAD_ERR_UNSUPPORTED, "the projection schemes serve MLP models only");
   if (d_input > 8) return fail(c, RAD_ERR_UNSUPPORTED, "RNN input width above 8");
   if (T > (1 << 20)) return fail(c, RAD_ERR_SHAPE, "T above 2^20");
   rad_model* m = new rad_model();
@@ -1286,7 +1314,7 @@ extern "C" rad_status rad_model_create_cnn(rad_ctx* c, int64_t batch, int32_t n_
   RAD_TRY(check_scheme(c, scheme, p));
   if (n_conv < 1 || n_conv > 32 || batch < 1 || classes < 1 || ksize < 1 || (ksize & 1) == 0)
     return fail(c, RAD_ERR_SHAPE, "bad CNN shape (odd kernel size, at least one conv)");
-  if (scheme == RAD_PROJECT_SHARED) return fail(c, RAD_ERR_UNSUPPORTED, "the projection scheme serves MLP models only");
+  if (scheme == RAD_PROJECT_SHARED || scheme == RAD_PROJECT_PER_EXAMPLE) return fail(c, RAD_ERR_UNSUPPORTED, "the projection schemes serve MLP models only");
   for (int l = 0; l < n_conv; ++l)
     if (pool[l] < 0 || pool[l] > 2) return fail(c, RAD_ERR_PARAM, "pool[l] is 0 (none), 1 (max) or 2 (average)");
   rad_model* m = new rad_model();

@@ -15,7 +15,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 enum Scheme : int { kExact = 0, kBernoulli = 1, kFixedKShared = 2, kFixedKPerExample = 3, kReplaceShared = 4,
-                    kReplacePerExample = 5, kProjectShared = 6 };
+                    kReplacePerExample = 5, kProjectShared = 6, kProjectPerExample = 7 };
 enum DType : int { kF32 = 0, kBF16 = 1 };
 
 // fp32 -> bf16 bits, round to nearest even (NaN payload is not preserved; the

@@ -98,6 +98,14 @@ hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t st);
 // from the key stream (entry (j, s) = bit j*k + s), zero in the padding columns s >= k (both must be zeroed first)
 hipError_t launch_sign_matrix(void* R, void* Rt, int dtype, int d, int k, int kp, uint32_t seed_lo, uint32_t seed_hi,
                               uint32_t stream_id, uint32_t step, hipStream_t st);
+// Projection with a matrix per example: z [rows][kp] = scale * x R_b (columns k .. kp-1 are written as zeros),
+// and xt [rows][d] = scale * z R_b^T, the signs of R_b drawn in the kernels (never stored).  k <= 38400.
+hipError_t launch_project_rows_fwd(const void* x, int dtype, int rows, int d, int k, int kp, float scale, void* z,
+                                   uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id, uint32_t step,
+                                   hipStream_t st);
+hipError_t launch_project_rows_bwd(const void* z, int dtype, int rows, int d, int k, int kp, float scale, void* xt,
+                                   uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id, uint32_t step,
+                                   hipStream_t st);
 // out[i] = in[i] * scale, stored in the given dtype
 hipError_t launch_scale_cast(const float* in, void* out, int dtype, int64_t n, float scale, hipStream_t st);
 // out[i] (+)= sum over `splits` partial arrays of n elements
