@@ -24,7 +24,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void project_rows_fwd_kernel(const T* __restrict__ x, int d, int k, int kp, float scale,
                                                                T* __restrict__ z, uint32_t seed_lo, uint32_t seed_hi,
                                                                uint32_t stream_id, uint32_t step) {
-  extern __shared__ __align__(16) float red[];   // [128][kRedPitch]
+  __shared__ float red[32 * kRedPitch];
+  __shared__ float red2[256];
   const int b = blockIdx.x, c = blockIdx.y, C = gridDim.y;
   float acc[128];
 #pragma unroll
@@ -41,15 +42,26 @@ __global__ __launch_bounds__(256) void project_rows_fwd_kernel(const T* __restri
       for (int i = 0; i < 32; ++i) acc[wi * 32 + i] += __uint_as_float(((ws << (31 - i)) & 0x80000000u) | mag);
     }
   }
+  // 256 partial sums per column, added in a fixed order, 32 columns at a time (a quarter of the LDS of doing all
+  // 128 at once, so that three workgroups fit a CU): thread (part, col) adds 32 of them, then 8 parts per column
+  const int col = threadIdx.x & 31, part = threadIdx.x >> 5;
 #pragma unroll
-  for (int i = 0; i < 128; ++i) red[i * kRedPitch + threadIdx.x] = acc[i];
-  __syncthreads();
-  if (threadIdx.x < 128) {
-    const int col = c * 128 + (int)threadIdx.x;
-    if (col < kp) {
-      float s = 0.f;
-      for (int u = 0; u < 256; ++u) s += red[threadIdx.x * kRedPitch + u];
-      st_elem(z + (size_t)b * kp + col, col < k ? s * scale : 0.f);
+  for (int r = 0; r < 4; ++r) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 32; ++i) red[i * kRedPitch + threadIdx.x] = acc[r * 32 + i];
+    __syncthreads();
+    float s = 0.f;
+    for (int u = 0; u < 32; ++u) s += red[col * kRedPitch + part * 32 + u];
+    red2[part * 32 + col] = s;
+    __syncthreads();
+    if (threadIdx.x < 32) {
+      const int out = c * 128 + r * 32 + (int)threadIdx.x;
+      if (out < kp) {
+        const float t = ((red2[col] + red2[32 + col]) + (red2[64 + col] + red2[96 + col])) +
+                        ((red2[128 + col] + red2[160 + col]) + (red2[192 + col] + red2[224 + col]));
+        st_elem(z + (size_t)b * kp + out, out < k ? t * scale : 0.f);
+      }
     }
   }
 }
@@ -110,20 +122,15 @@ hipError_t launch_project_rows_fwd(const void* x, int dtype, int rows, int d, in
                                    uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id, uint32_t step,
                                    hipStream_t st) {
   const int C = (k + 127) / 128;
-  const int smem = 128 * kRedPitch * 4;
   if (C > 65535) return hipErrorInvalidValue;
   dim3 grid((unsigned)rows, (unsigned)C), block(256);
   if (dtype == kF32) {
     auto kern = project_rows_fwd_kernel<float>;
-    hipError_t e = allow_lds(kern, smem);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, block, smem, st, (const float*)x, d, k, kp, scale, (float*)z, seed_lo, seed_hi,
+    hipLaunchKernelGGL(kern, grid, block, 0, st, (const float*)x, d, k, kp, scale, (float*)z, seed_lo, seed_hi,
                        stream_id, step);
   } else {
     auto kern = project_rows_fwd_kernel<uint16_t>;
-    hipError_t e = allow_lds(kern, smem);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, block, smem, st, (const uint16_t*)x, d, k, kp, scale, (uint16_t*)z, seed_lo, seed_hi,
+    hipLaunchKernelGGL(kern, grid, block, 0, st, (const uint16_t*)x, d, k, kp, scale, (uint16_t*)z, seed_lo, seed_hi,
                        stream_id, step);
   }
   return hipGetLastError();
