@@ -1,0 +1,52 @@
+"""The gradient-noise procedure (Section 5, gradient-noise figure) run through the C ABI against the same
+procedure run on the oracle's training steps: per-layer mean squared deviations of every method agree, and
+they order as the paper reports (sampling costs less noise than the reduced minibatch of equal memory)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import rad_oracle as R
+
+
+def test_small_mlp_matches_the_oracle_procedure():
+    from paper_2007_10412_amd import gradient_noise as G
+    cfg = dict(kind="mlp", dims=(64, 48, 32, 10), batch=24, reduced=4)
+    data = G.training_set(cfg, 96, seed=3)
+    methods = G.methods_for(cfg, 0.25)
+    L = len(cfg["dims"]) - 1
+
+    def oracle_step(first, count, scheme, p, seed):
+        out = R.mlp_train_step(data["x"][first:first + count], data["labels"][first:first + count], data["Ws"], data["bs"],
+                               scheme, p, seed)
+        return out["dW"]
+    want = G.measure(oracle_step, 96, methods, draws=6)
+    step = G.GpuStep(cfg, data)
+    try:
+        got = G.measure(step, 96, methods, draws=6)
+    finally:
+        step.close()
+    print(got, flush=True)
+    for name in methods:
+        assert np.allclose(got[name], want[name], rtol=2e-3), (name, got[name], want[name])
+    # a reduced minibatch is noisier than sampling a quarter of the activations of the whole minibatch
+    for l in range(L):
+        assert got["different_sample"][l] < got["reduced_batch"][l]
+        assert got["baseline"][l] <= got["different_sample"][l]
+        assert got["different_sample_2x_batch"][l] < got["different_sample"][l]
+
+
+def test_paper_convnet_runs():
+    """The convolutional architecture of Appendix A on a 300-example synthetic set: finite numbers for every
+    method and layer, baseline below reduced batch."""
+    from paper_2007_10412_amd import gradient_noise as G
+    cfg = G.paper_arch("cnn")
+    step = G.GpuStep(cfg, G.training_set(cfg, 300))
+    try:
+        got = G.measure(step, 300, G.methods_for(cfg, 0.1), draws=3)
+    finally:
+        step.close()
+    print(got, flush=True)
+    for name, v in got.items():
+        assert len(v) == 5 and np.all(np.isfinite(v)), name
+    assert all(a < b for a, b in zip(got["baseline"], got["reduced_batch"]))
