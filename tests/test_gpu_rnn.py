@@ -76,3 +76,12 @@ def test_config5_reduced_length(ctx):
     from paper_2007_10412_amd import synth
     d = synth.rnn(seed=1234, batch=128, T=48, d_input=1, hidden=1024, classes=10, identity=True)
     run_rnn(ctx, d, 1, 0.1, seed=5)
+
+
+@pytest.mark.parametrize("scheme", [2, 3])
+def test_paper_rnn_widths(ctx, scheme):
+    """The recurrent architecture of Appendix A (hidden state 100, one-dimensional input, minibatch 150,
+    identity recurrent weights) over 40 time steps, "same sample" and "different sample" at fraction 0.1."""
+    from paper_2007_10412_amd import synth
+    d = synth.rnn(seed=77, batch=150, T=40, d_input=1, hidden=100, classes=10, identity=True)
+    run_rnn(ctx, d, scheme, 0.1, seed=9)
