@@ -633,6 +633,105 @@ def adam_step(w, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, l2=0.0):
 
 
 # ----------------------------------------------------------------------------
+# Reaction-diffusion PDE-constrained optimisation (Section 6, Appendix B).
+# phi lives on the nodes (i, j), 0 <= i, j <= n, of the unit square (x = i/n,
+# y = j/n) and is zero on the boundary; the explicit update of Appendix B is
+#   phi_{t+1} = phi_t + (D dt / dx^2) (4-neighbour sum - 4 phi_t) + dt C_t phi_t
+# with C the seven-term series in x and t of Appendix B, phi_0 =
+# sin(pi x) sin(pi y), target_t = phi_0 + (1/4) sin(pi t) sin(2 pi x) sin(pi y)
+# and L = (1/T) sum_{t=1..T} |phi_t - target_t|^2 (time t = step * dt).
+#
+# The estimator of Section 6 samples dL/dphi_t and the diagonal
+# dphi_{t+1}/dC_t = dt diag(phi_t) with the matrix P of phi_t, so that only the
+# sampled entries of phi_t are kept; the Jacobians dphi_{j+1}/dphi_j =
+# M + dt diag(C_j) are known without phi, and C is recomputed from theta and t.
+# Reading (the paper does not say how entries are drawn): every interior entry
+# of phi_t is kept independently with probability p and scaled by 1/p; entry
+# c = (i-1)(n-1) + (j-1) of step t takes the key of flat index c with
+# step = t in the element_keys addressing and is kept iff key < round(p 2^32).
+# Pins (tests/test_oracle_pde.py): the eigenfunction decay closed form, the
+# stability number of Appendix B, p = 1 against finite differences and torch
+# autograd, unbiasedness over seeds.
+# ----------------------------------------------------------------------------
+def pde_basis(n, t):
+    """[7, n+1]: the seven functions of (x, t) whose theta-weighted sum is C."""
+    x = np.arange(n + 1, dtype=np.float64) / n
+    s, c = math.sin(math.pi * t), math.cos(math.pi * t)
+    s2, c2 = np.sin(2 * np.pi * x), np.cos(2 * np.pi * x)
+    one = np.ones(n + 1)
+    return np.stack([one, s * one, c * one, s2 * s, s2 * c, c2 * s, c2 * c])
+
+
+def pde_phi0(n):
+    x = np.arange(n + 1, dtype=np.float64) / n
+    phi = np.outer(np.sin(np.pi * x), np.sin(np.pi * x))
+    phi[0, :] = phi[n, :] = 0.0
+    phi[:, 0] = phi[:, n] = 0.0
+    return phi
+
+
+def pde_target(n, t, phi0):
+    x = np.arange(n + 1, dtype=np.float64) / n
+    tg = phi0 + 0.25 * math.sin(math.pi * t) * np.outer(np.sin(2 * np.pi * x), np.sin(np.pi * x))
+    tg[0, :] = tg[n, :] = 0.0
+    tg[:, 0] = tg[:, n] = 0.0
+    return tg
+
+
+def _pde_apply(phi, r, dtC):
+    """(M + dt diag(C)) phi on the interior; the boundary stays zero.  dtC [n+1] varies along x (axis 0)."""
+    out = np.zeros_like(phi)
+    out[1:-1, 1:-1] = (phi[1:-1, 1:-1]
+                       + r * (phi[2:, 1:-1] + phi[:-2, 1:-1] + phi[1:-1, 2:] + phi[1:-1, :-2] - 4.0 * phi[1:-1, 1:-1])
+                       + dtC[1:-1, None] * phi[1:-1, 1:-1])
+    return out
+
+
+def pde_forward(theta, n, steps, D=0.25, dt=1.0 / 4096):
+    """All states phi_0 .. phi_steps [steps+1, n+1, n+1] and the loss."""
+    theta = np.asarray(theta, dtype=np.float64)
+    r = D * dt * n * n
+    phi0 = pde_phi0(n)
+    phis = np.zeros((steps + 1, n + 1, n + 1))
+    phis[0] = phi0
+    loss = 0.0
+    for t in range(steps):
+        C = theta @ pde_basis(n, t * dt)
+        phis[t + 1] = _pde_apply(phis[t], r, dt * C)
+        loss += float(((phis[t + 1] - pde_target(n, (t + 1) * dt, phi0)) ** 2).sum())
+    return phis, loss / steps
+
+
+def pde_keep_mask(n, t, p, seed, stream_id):
+    """[n+1, n+1] bool: kept entries of phi_t (interior only)."""
+    m = n - 1
+    keys = element_keys(seed, stream_id, t, 0, m * m).astype(np.uint64)
+    thr = np.uint64(int(round(p * 4294967296.0)))
+    mask = np.zeros((n + 1, n + 1), dtype=bool)
+    mask[1:-1, 1:-1] = (keys < thr).reshape(m, m)
+    return mask
+
+
+def pde_rad_gradient(theta, n, steps, p, seed, stream_id=0, D=0.25, dt=1.0 / 4096):
+    """(loss, dL/dtheta estimate [7], number of stored entries).  p = 1 keeps everything: the exact gradient."""
+    theta = np.asarray(theta, dtype=np.float64)
+    r = D * dt * n * n
+    phis, loss = pde_forward(theta, n, steps, D, dt)
+    phi0 = phis[0]
+    masks = [pde_keep_mask(n, t, p, seed, stream_id) for t in range(steps + 1)]
+    stored = int(sum(m.sum() for m in masks))
+    lam = np.zeros((n + 1, n + 1))
+    g = np.zeros(7)
+    for t in range(steps, 0, -1):
+        lam = lam + (2.0 / steps) * np.where(masks[t], (phis[t] - pde_target(n, t * dt, phi0)) / p, 0.0)
+        basis = pde_basis(n, (t - 1) * dt)
+        w = dt * np.where(masks[t - 1], phis[t - 1] / p, 0.0) * lam          # dL/dC_{t-1}, entry by entry
+        g += basis @ w.sum(axis=1)
+        lam = _pde_apply(lam, r, dt * (theta @ basis))                       # M + dt diag(C) is symmetric
+    return loss, g, stored
+
+
+# ----------------------------------------------------------------------------
 # Byte accounting, in the paper's convention (Appendix A, "Calculation of
 # memory saved from RAD"): 32-bit values for the stored (sampled) inputs,
 # ceil(p d) of them per input, one bit per un-reduced ReLU entry, the softmax
