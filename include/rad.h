@@ -316,6 +316,42 @@ rad_status rad_optimizer_step(rad_ctx* ctx, const rad_optimizer* opt, int64_t t,
                               const void* const* grads, void* const* m, void* const* v,
                               void* const* master);
 
+/* ---- reaction-diffusion PDE-constrained optimisation -----------------------
+ * Section 6 and Appendix B: phi on the nodes (i, j), 0 <= i, j <= n, of the
+ * unit square (x = i/n, y = j/n), zero on the boundary, stepped explicitly,
+ *   phi_{t+1} = phi_t + (D dt n^2)(4-neighbour sum - 4 phi_t) + dt C_t phi_t,
+ *   C = th0 + th1 sin(pi t) + th2 cos(pi t) + sin(2 pi x)(th3 sin(pi t) + th4 cos(pi t))
+ *       + cos(2 pi x)(th5 sin(pi t) + th6 cos(pi t)),
+ * from phi_0 = sin(pi x) sin(pi y); L = (1/steps) sum_{t=1..steps} |phi_t - target_t|^2,
+ * target_t = phi_0 + (1/4) sin(pi t) sin(2 pi x) sin(pi y), time t = step * dt.
+ * The gradient with respect to the seven controls is the estimator of
+ * Section 6: dL/dphi_t and dphi_{t+1}/dC_t = dt diag(phi_t) are sampled with
+ * the matrix P of phi_t, so only sampled entries of phi_t are kept: interior
+ * entry c = (i-1)(n-1) + (j-1) of step t is kept iff the key of flat index c
+ * with (stream_id, step = t) is below round(p 2^32), and weighs 1/p.  p = 1
+ * keeps every state and gives the exact gradient.  The paper's grid is n = 32,
+ * dt = 1/4096, D = 1/4, steps = 40960.  All arithmetic is fp64. */
+typedef struct {
+  int32_t n;     /* intervals per side, 2 <= n <= 32 */
+  int64_t steps; /* >= 1; steps * (n-1)^2 < 2^32 */
+  double D, dt;  /* D dt n^2 <= 1/4 (the stability bound of Appendix B), else RAD_ERR_PARAM */
+} rad_pde_grid;
+
+/* Bytes of device workspace rad_pde_gradient needs for `problems` problems at fraction p. */
+rad_status rad_pde_workspace_bytes(rad_ctx* ctx, const rad_pde_grid* grid, double p, int32_t problems,
+                                   uint64_t* bytes);
+
+/* `problems` independent problems side by side: problem q has the controls
+ * theta[q][0..6] (DEVICE, fp64) and draws with stream_id + q.  Outputs
+ * (DEVICE): loss [problems], grad [problems][7], stored [problems] (number of
+ * kept entries; nullable).  workspace: DEVICE memory of at least
+ * rad_pde_workspace_bytes, owned by the caller, contents undefined afterwards.
+ * Synchronises; RAD_ERR_CAPACITY if a draw kept more entries than the
+ * workspace provides for (8 standard deviations above the mean). */
+rad_status rad_pde_gradient(rad_ctx* ctx, const rad_pde_grid* grid, int32_t problems, const double* theta,
+                            double p, uint64_t seed, uint32_t stream_id, void* workspace,
+                            uint64_t workspace_bytes, double* loss, double* grad, int64_t* stored);
+
 #ifdef __cplusplus
 }
 #endif

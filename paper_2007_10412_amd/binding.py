@@ -45,6 +45,10 @@ class rad_optimizer(C.Structure):
                 ("beta2", C.c_double), ("eps", C.c_double)]
 
 
+class rad_pde_grid(C.Structure):
+    _fields_ = [("n", C.c_int32), ("steps", C.c_int64), ("D", C.c_double), ("dt", C.c_double)]
+
+
 SIGNATURES = {
     "rad_fixed_k": (C.c_int64, [C.c_double, C.c_int64]),
     "rad_ctx_create": (C.c_int, [C.POINTER(P), P]),
@@ -83,6 +87,9 @@ SIGNATURES = {
     "rad_model_export_pool_arg": (C.c_int, [P, P, C.c_int32, P]),
     "rad_train_step": (C.c_int, [P, P, C.POINTER(rad_sampling), P, P, C.POINTER(P), C.POINTER(P),
                                  C.POINTER(C.c_float)]),
+    "rad_pde_workspace_bytes": (C.c_int, [P, C.POINTER(rad_pde_grid), C.c_double, C.c_int32, C.POINTER(C.c_uint64)]),
+    "rad_pde_gradient": (C.c_int, [P, C.POINTER(rad_pde_grid), C.c_int32, P, C.c_double, C.c_uint64, C.c_uint32, P,
+                                   C.c_uint64, P, P, P]),
     "rad_optimizer_step": (C.c_int, [P, C.POINTER(rad_optimizer), C.c_int64, C.c_int32, C.c_int32,
                                      C.POINTER(C.c_int64), C.POINTER(P), C.POINTER(P), C.POINTER(P), C.POINTER(P),
                                      C.POINTER(P)]),
@@ -326,3 +333,22 @@ def rad_optimizer_step(ctx, opt, t, dtype, params, grads, m=None, v=None, master
     counts = (C.c_int64 * n)(*[int(x.numel()) for x in params])
     _check(ctx, lib().rad_optimizer_step(ctx, C.byref(opt), int(t), dtype, n, counts, arr(params), arr(grads), arr(m),
                                          arr(v), arr(master)))
+
+
+def make_pde_grid(n=32, steps=40960, D=0.25, dt=1.0 / 4096):
+    return rad_pde_grid(n, steps, D, dt)
+
+
+def rad_pde_workspace_bytes(ctx, grid, p, problems):
+    out = C.c_uint64()
+    _check(ctx, lib().rad_pde_workspace_bytes(ctx, C.byref(grid), p, problems, C.byref(out)))
+    return out.value
+
+
+def rad_pde_gradient(ctx, grid, theta, p, seed, stream_id, workspace, loss, grad, stored=None):
+    """theta [problems, 7] fp64 device tensor; workspace a device byte tensor; loss [problems], grad [problems, 7]
+    fp64, stored [problems] int64 or None."""
+    problems = int(theta.shape[0])
+    _check(ctx, lib().rad_pde_gradient(ctx, C.byref(grid), problems, _ptr(theta), p, seed, stream_id, _ptr(workspace),
+                                       int(workspace.numel() * workspace.element_size()), _ptr(loss), _ptr(grad),
+                                       _ptr(stored)))

@@ -981,6 +981,64 @@ extern "C" rad_status rad_optimizer_step(rad_ctx* c, const rad_optimizer* opt, i
   return RAD_OK;
 }
 
+// ------------------------------------------------------------------ reaction-diffusion study
+struct PdeLayout { int64_t cap; size_t vals_bytes, rows_bytes, flags_bytes, total; };
+
+static rad_status pde_layout(rad_ctx* c, const rad_pde_grid* g, double p, int32_t problems, PdeLayout* out) {
+  if (!g) return fail(c, RAD_ERR_NULL, "grid is null");
+  if (g->n < 2 || g->n > 32 || g->steps < 1 || problems < 1) return fail(c, RAD_ERR_SHAPE, "2 <= n <= 32, steps >= 1, problems >= 1");
+  const double cells = (double)(g->n - 1) * (g->n - 1);
+  if (cells * ((double)g->steps + 1.0) >= 4294967296.0) return fail(c, RAD_ERR_SHAPE, "steps (n-1)^2 must stay below 2^32");
+  if (!(p > 0.0) || p > 1.0) return fail(c, RAD_ERR_PARAM, "p must be in (0, 1]");
+  if (!(g->D > 0.0) || !(g->dt > 0.0) || g->D * g->dt * (double)g->n * (double)g->n > 0.25)
+    return fail(c, RAD_ERR_PARAM, "D dt n^2 must be positive and at most 1/4");
+  const double total = cells * ((double)g->steps + 1.0);
+  double cap = std::ceil(total * p + 8.0 * std::sqrt(total * p * (1.0 - p))) + 64.0;
+  if (cap > total) cap = total;
+  out->cap = (int64_t)cap;
+  auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+  out->vals_bytes = up((size_t)problems * (size_t)out->cap * 8);
+  out->rows_bytes = up((size_t)problems * (size_t)(g->steps + 2) * 4);
+  out->flags_bytes = up((size_t)problems * 4);
+  out->total = out->vals_bytes + out->rows_bytes + out->flags_bytes;
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_pde_workspace_bytes(rad_ctx* c, const rad_pde_grid* g, double p, int32_t problems,
+                                              uint64_t* bytes) {
+  if (!c) return RAD_ERR_NULL;
+  if (!bytes) return fail(c, RAD_ERR_NULL, "bytes is null");
+  PdeLayout lay;
+  RAD_TRY(pde_layout(c, g, p, problems, &lay));
+  *bytes = lay.total;
+  return RAD_OK;
+}
+
+extern "C" rad_status rad_pde_gradient(rad_ctx* c, const rad_pde_grid* g, int32_t problems, const double* theta,
+                                       double p, uint64_t seed, uint32_t stream_id, void* workspace,
+                                       uint64_t workspace_bytes, double* loss, double* grad, int64_t* stored) {
+  if (!c) return RAD_ERR_NULL;
+  if (!theta || !workspace || !loss || !grad) return fail(c, RAD_ERR_NULL, "null argument");
+  PdeLayout lay;
+  RAD_TRY(pde_layout(c, g, p, problems, &lay));
+  if (workspace_bytes < lay.total) return fail(c, RAD_ERR_CAPACITY, "workspace smaller than rad_pde_workspace_bytes");
+  if (reinterpret_cast<uintptr_t>(workspace) & 7) return fail(c, RAD_ERR_PARAM, "workspace must be 8-byte aligned");
+  char* base = static_cast<char*>(workspace);
+  double* vals = reinterpret_cast<double*>(base);
+  uint32_t* rows = reinterpret_cast<uint32_t*>(base + lay.vals_bytes);
+  int* flags = reinterpret_cast<int*>(base + lay.vals_bytes + lay.rows_bytes);
+  HIP_TRY(c, timed(c, "pde", [&](const char**) {
+    return launch_pde(problems, g->n, g->steps, g->D, g->dt, p, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, theta,
+                      vals, lay.cap, rows, flags, loss, grad, stored, c->stream);
+  }));
+  std::vector<int> host((size_t)problems);
+  HIP_TRY(c, hipMemcpyAsync(host.data(), flags, (size_t)problems * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int f : host)
+    if (f) return fail(c, RAD_ERR_CAPACITY, "a draw kept more entries than the workspace holds");
+  return RAD_OK;
+}
+
 // ------------------------------------------------------------------ models
 enum ModelKind { kMlp = 0, kRnn = 1, kCnn = 2 };
 

@@ -1,0 +1,234 @@
+// Reaction-diffusion PDE-constrained optimisation with a sampled adjoint (Section 6, Appendix B).
+// phi lives on the nodes (i, j), 0 <= i, j <= n <= 32, of the unit square, zero on the boundary; one explicit
+// step is phi += r (4-neighbour sum - 4 phi) + dt C phi with r = D dt / dx^2 and C the seven-term series in x and
+// t.  The steps depend on each other, so one problem is one workgroup of 1024 threads (a node each, the state in
+// LDS, one barrier per step) and the launch runs many problems (control vectors, sampling streams) side by
+// side, one per CU.  All arithmetic is fp64: the work is bound by the chain of barriers, not by flops.
+//
+// What is kept of phi_t for the backward pass: the interior entries whose key is below p 2^32 (entry
+// c = (i-1)(n-1) + (j-1) of step t takes word c mod 4 of the Philox call c / 4 with (stream, step = t)), written
+// one after another; the backward pass draws the same keys again and finds an entry's place from the count of
+// kept entries before it (ballot + popcount inside a wave, a 16-entry table across waves, the step's start
+// offset from a table written in the forward pass).
+#include <cmath>
+
+#include "kernels.hpp"
+#include "philox.hpp"
+
+namespace rad {
+
+namespace {
+
+constexpr int kPdeThreads = 1024, kPdePitch = 33, kPdeNodes = kPdePitch * kPdePitch;
+
+struct PdeThread {
+  int i, j, idx, cell, lane, wave;
+  bool interior;
+  double s2x, c2x, phi0, tgt_xy;
+  __device__ __forceinline__ void init(int n) {
+    i = threadIdx.x >> 5; j = threadIdx.x & 31;
+    idx = i * kPdePitch + j;
+    lane = threadIdx.x & 63; wave = threadIdx.x >> 6;
+    interior = i >= 1 && j >= 1 && i <= n - 1 && j <= n - 1;
+    cell = interior ? (i - 1) * (n - 1) + (j - 1) : 0;
+    const double x = (double)i / n, y = (double)j / n;
+    s2x = sinpi(2.0 * x); c2x = cospi(2.0 * x);
+    phi0 = interior ? sinpi(x) * sinpi(y) : 0.0;
+    tgt_xy = interior ? s2x * sinpi(y) : 0.0;
+  }
+  // is this thread's entry of step t kept; how many kept entries of the wave come before it; the wave's count
+  __device__ __forceinline__ bool draw(int64_t t, uint32_t thr_lo, bool keep_all, uint32_t seed_lo, uint32_t seed_hi,
+                                       uint32_t stream, uint32_t* before, uint32_t* in_wave) const {
+    const u32x4 k4 = element_quad_keys((uint64_t)(cell >> 2), stream, (uint32_t)t, seed_lo, seed_hi);
+    const bool keep = interior && (keep_all || k4[cell & 3] < thr_lo);
+    const uint64_t b = __ballot(keep);
+    *before = (uint32_t)__popcll(b & ((1ull << lane) - 1ull));
+    *in_wave = (uint32_t)__popcll(b);
+    return keep;
+  }
+};
+
+__device__ __forceinline__ double pde_c(const double* th, double s, double c, double s2x, double c2x) {
+  return th[0] + th[1] * s + th[2] * c + s2x * (th[3] * s + th[4] * c) + c2x * (th[5] * s + th[6] * c);
+}
+
+// sum over the workgroup in a fixed order; every thread gets the result
+__device__ __forceinline__ double block_sum(double v, double* red) {
+  __syncthreads();
+  red[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = kPdeThreads / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  return red[0];
+}
+
+struct PdeArgs {
+  int n; int64_t steps; double r, dt, p;
+  uint32_t thr; int keep_all;                 // keep iff key < thr; p = 1 keeps everything
+  uint32_t seed_lo, seed_hi, stream_id;
+  const double* theta;                        // [problems][7]
+  double* vals; int64_t cap;                  // [problems][cap] kept entries
+  uint32_t* row_ptr;                          // [problems][steps + 2] start of every step's entries
+  int* overflow;                              // [problems]
+  double* loss; double* grad; int64_t* stored;
+};
+
+__global__ __launch_bounds__(kPdeThreads) void pde_forward_kernel(PdeArgs a) {
+  __shared__ double ph[2][kPdeNodes];
+  __shared__ double red[kPdeThreads];
+  __shared__ double trig_s[kPdeThreads], trig_c[kPdeThreads];   // sin, cos of pi t for the next 1024 steps
+  __shared__ uint32_t wcnt[2][16];
+  const int pb = blockIdx.x;
+  PdeThread me; me.init(a.n);
+  double th[7];
+#pragma unroll
+  for (int k = 0; k < 7; ++k) th[k] = a.theta[(size_t)pb * 7 + k];
+  const uint32_t stream = a.stream_id + (uint32_t)pb;
+  double* const vals = a.vals + (size_t)pb * a.cap;
+  uint32_t* const row_ptr = a.row_ptr + (size_t)pb * (a.steps + 2);
+  for (int q = threadIdx.x; q < 2 * kPdeNodes; q += kPdeThreads) (&ph[0][0])[q] = 0.0;
+  __syncthreads();
+  if (me.interior) ph[0][me.idx] = me.phi0;
+  __syncthreads();
+  double mine = me.phi0, loss = 0.0, s = 0.0, c = 1.0;          // sin, cos of pi t at t = 0
+  uint32_t offset = 0;
+  bool over = false;
+  for (int64_t t = 0; t <= a.steps; ++t) {
+    const int cur = (int)(t & 1);
+    if ((t & 1023) == 0) {          // every thread works out one of the next 1024 time points
+      __syncthreads();
+      sincospi((double)(t + 1 + threadIdx.x) * a.dt, &trig_s[threadIdx.x], &trig_c[threadIdx.x]);
+      __syncthreads();
+    }
+    uint32_t before, in_wave;
+    const bool keep = me.draw(t, a.thr, a.keep_all != 0, a.seed_lo, a.seed_hi, stream, &before, &in_wave);
+    if (me.lane == 0) wcnt[cur][me.wave] = in_wave;
+    double nw = 0.0;
+    if (t < a.steps && me.interior) {
+      const double* f = ph[cur];
+      const double nb = (f[me.idx + kPdePitch] + f[me.idx - kPdePitch]) + (f[me.idx + 1] + f[me.idx - 1]);
+      nw = mine + a.r * (nb - 4.0 * mine) + a.dt * pde_c(th, s, c, me.s2x, me.c2x) * mine;
+      ph[cur ^ 1][me.idx] = nw;
+    }
+    __syncthreads();
+    uint32_t base = offset, total = 0;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) { const uint32_t v = wcnt[cur][u]; if (u < me.wave) base += v; total += v; }
+    if (keep) {
+      const int64_t pos = (int64_t)base + before;
+      if (pos < a.cap) vals[pos] = mine; else over = true;
+    }
+    if (threadIdx.x == 0) row_ptr[t] = offset;
+    offset += total;
+    if (t < a.steps) {
+      s = trig_s[t & 1023]; c = trig_c[t & 1023];
+      if (me.interior) {
+        const double d = nw - (me.phi0 + 0.25 * s * me.tgt_xy);
+        loss += d * d;
+        mine = nw;
+      }
+    }
+  }
+  if (threadIdx.x == 0) { row_ptr[a.steps + 1] = offset; if (a.stored) a.stored[pb] = (int64_t)offset; }
+  const double total_loss = block_sum(loss, red);
+  const double any_over = block_sum(over ? 1.0 : 0.0, red);
+  if (threadIdx.x == 0) { a.loss[pb] = total_loss / (double)a.steps; a.overflow[pb] = any_over > 0.0 ? 1 : 0; }
+}
+
+__global__ __launch_bounds__(kPdeThreads) void pde_backward_kernel(PdeArgs a) {
+  __shared__ double lb[2][kPdeNodes];
+  __shared__ double red[kPdeThreads];
+  __shared__ double trig_s[kPdeThreads], trig_c[kPdeThreads];   // sin, cos of pi t for 1024 time points
+  __shared__ uint32_t wcnt[2][16];
+  const int pb = blockIdx.x;
+  PdeThread me; me.init(a.n);
+  double th[7], g[7];
+#pragma unroll
+  for (int k = 0; k < 7; ++k) { th[k] = a.theta[(size_t)pb * 7 + k]; g[k] = 0.0; }
+  const uint32_t stream = a.stream_id + (uint32_t)pb;
+  const double* const vals = a.vals + (size_t)pb * a.cap;
+  const uint32_t* const row_ptr = a.row_ptr + (size_t)pb * (a.steps + 2);
+  const double inv_p = 1.0 / a.p, w_loss = 2.0 / (double)a.steps;
+  for (int q = threadIdx.x; q < 2 * kPdeNodes; q += kPdeThreads) (&lb[0][0])[q] = 0.0;
+
+  // value of this thread's entry of step t (0 if it was not kept): first half before a barrier, second after
+  bool keepN = false; uint32_t beforeN = 0;
+  auto fetch_begin = [&](int64_t t, int buf) {
+    uint32_t in_wave;
+    keepN = me.draw(t, a.thr, a.keep_all != 0, a.seed_lo, a.seed_hi, stream, &beforeN, &in_wave);
+    if (me.lane == 0) wcnt[buf][me.wave] = in_wave;
+  };
+  auto fetch_end = [&](int64_t t, int buf) -> double {
+    uint32_t base = row_ptr[t];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) { const uint32_t v = wcnt[buf][u]; if (u < me.wave) base += v; }
+    const int64_t pos = (int64_t)base + beforeN;
+    return (keepN && pos < a.cap) ? vals[pos] : 0.0;
+  };
+  // A: step t, B: step t - 1 (values are 0 where nothing was kept, so no flags are carried)
+  fetch_begin(a.steps, 0);
+  __syncthreads();
+  double valA = fetch_end(a.steps, 0); bool keepA = keepN;
+  fetch_begin(a.steps - 1, 1);
+  __syncthreads();
+  double valB = fetch_end(a.steps - 1, 1); bool keepB = keepN;
+  double lam = 0.0, s_t, c_t;
+  sincospi((double)a.steps * a.dt, &s_t, &c_t);
+  int cur = 0;                      // buffers alternate from the prologue on: 0, 1, then 0 again
+  for (int64_t t = a.steps; t >= 1; --t, cur ^= 1) {
+    const int64_t u = t - 1;        // the time point of C and of the sampled phi of this iteration
+    if (t == a.steps || (u & 1023) == 1023) {
+      __syncthreads();
+      sincospi((double)((u & ~(int64_t)1023) + threadIdx.x) * a.dt, &trig_s[threadIdx.x], &trig_c[threadIdx.x]);
+      __syncthreads();
+    }
+    if (t >= 2) fetch_begin(t - 2, cur);
+    if (keepA) lam += w_loss * inv_p * (valA - (me.phi0 + 0.25 * s_t * me.tgt_xy));
+    const double s = trig_s[u & 1023], c = trig_c[u & 1023];
+    if (keepB) {
+      const double w = a.dt * inv_p * valB * lam;
+      g[0] += w; g[1] += s * w; g[2] += c * w;
+      g[3] += me.s2x * s * w; g[4] += me.s2x * c * w; g[5] += me.c2x * s * w; g[6] += me.c2x * c * w;
+    }
+    if (me.interior) lb[cur][me.idx] = lam;
+    __syncthreads();
+    double valC = 0.0; bool keepC = false;
+    if (t >= 2) { valC = fetch_end(t - 2, cur); keepC = keepN; }
+    if (me.interior) {
+      const double* f = lb[cur];
+      const double nb = (f[me.idx + kPdePitch] + f[me.idx - kPdePitch]) + (f[me.idx + 1] + f[me.idx - 1]);
+      lam = lam + a.r * (nb - 4.0 * lam) + a.dt * pde_c(th, s, c, me.s2x, me.c2x) * lam;
+    }
+    valA = valB; keepA = keepB; valB = valC; keepB = keepC;
+    s_t = s; c_t = c;
+  }
+#pragma unroll
+  for (int k = 0; k < 7; ++k) {
+    const double tot = block_sum(g[k], red);
+    if (threadIdx.x == 0) a.grad[(size_t)pb * 7 + k] = tot;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_pde(int problems, int n, int64_t steps, double D, double dt, double p, uint32_t seed_lo,
+                      uint32_t seed_hi, uint32_t stream_id, const double* theta, double* vals, int64_t cap,
+                      uint32_t* row_ptr, int* overflow, double* loss, double* grad, int64_t* stored, hipStream_t st) {
+  PdeArgs a;
+  a.n = n; a.steps = steps; a.r = D * dt * (double)n * (double)n; a.dt = dt; a.p = p;
+  const double thr = std::floor(p * 4294967296.0 + 0.5);
+  a.keep_all = thr >= 4294967296.0 ? 1 : 0;
+  a.thr = a.keep_all ? 0xffffffffu : (uint32_t)thr;
+  a.seed_lo = seed_lo; a.seed_hi = seed_hi; a.stream_id = stream_id;
+  a.theta = theta; a.vals = vals; a.cap = cap; a.row_ptr = row_ptr; a.overflow = overflow;
+  a.loss = loss; a.grad = grad; a.stored = stored;
+  hipLaunchKernelGGL(pde_forward_kernel, dim3((unsigned)problems), dim3(kPdeThreads), 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(pde_backward_kernel, dim3((unsigned)problems), dim3(kPdeThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace rad
