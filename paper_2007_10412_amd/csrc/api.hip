@@ -992,13 +992,14 @@ static rad_status pde_layout(rad_ctx* c, const rad_pde_grid* g, double p, int32_
   if (!(p > 0.0) || p > 1.0) return fail(c, RAD_ERR_PARAM, "p must be in (0, 1]");
   if (!(g->D > 0.0) || !(g->dt > 0.0) || g->D * g->dt * (double)g->n * (double)g->n > 0.25)
     return fail(c, RAD_ERR_PARAM, "D dt n^2 must be positive and at most 1/4");
-  const double total = cells * ((double)g->steps + 1.0);
+  // each of the 16 waves of a problem (two grid rows, at most 62 interior entries) appends to a run of its own
+  const double total = 62.0 * ((double)g->steps + 1.0);
   double cap = std::ceil(total * p + 8.0 * std::sqrt(total * p * (1.0 - p))) + 64.0;
   if (cap > total) cap = total;
   out->cap = (int64_t)cap;
   auto up = [](size_t b) { return (b + 255) / 256 * 256; };
-  out->vals_bytes = up((size_t)problems * (size_t)out->cap * 8);
-  out->rows_bytes = up((size_t)problems * (size_t)(g->steps + 2) * 4);
+  out->vals_bytes = up((size_t)problems * 16 * (size_t)out->cap * 8);
+  out->rows_bytes = up((size_t)problems * 16 * 4);
   out->flags_bytes = up((size_t)problems * 4);
   out->total = out->vals_bytes + out->rows_bytes + out->flags_bytes;
   return RAD_OK;

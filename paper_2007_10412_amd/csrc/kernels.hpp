@@ -122,11 +122,11 @@ hipError_t launch_avgpool_fwd(const float* y, int planes, int H, int W, float* p
 hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, int pool, const uint32_t* arg,
                               const uint32_t* bits, int bits_pitch, float* g, hipStream_t st);
 // Reaction-diffusion study: `problems` independent (theta, sampling stream) pairs, one workgroup each; forward
-// pass keeping the sampled entries of every state in vals [problems][cap] and their per-step offsets in row_ptr
-// [problems][steps + 2], then the sampled adjoint pass.  n <= 32, steps >= 1.
+// pass keeping the sampled entries of every state in vals [problems][16][cap] (a run per wave) and the runs' lengths
+// in wave_end [problems][16], then the sampled adjoint pass.  n <= 32, steps >= 1.
 hipError_t launch_pde(int problems, int n, int64_t steps, double D, double dt, double p, uint32_t seed_lo,
                       uint32_t seed_hi, uint32_t stream_id, const double* theta, double* vals, int64_t cap,
-                      uint32_t* row_ptr, int* overflow, double* loss, double* grad, int64_t* stored, hipStream_t st);
+                      uint32_t* wave_end, int* overflow, double* loss, double* grad, int64_t* stored, hipStream_t st);
 // One optimiser step over n parameters: w (fp32, updated in place), g (fp32 gradient), Adam moments m, v (fp32,
 // updated in place; unused for SGD), lo: bf16 copy of w to refresh, or null.  inv_bc1 / inv_bc2 are
 // 1 / (1 - beta^t) of the step number and omb1 / omb2 are 1 - beta, all formed in double by the caller (in fp32

@@ -6,10 +6,9 @@
 // side, one per CU.  All arithmetic is fp64: the work is bound by the chain of barriers, not by flops.
 //
 // What is kept of phi_t for the backward pass: the interior entries whose key is below p 2^32 (entry
-// c = (i-1)(n-1) + (j-1) of step t takes word c mod 4 of the Philox call c / 4 with (stream, step = t)), written
-// one after another; the backward pass draws the same keys again and finds an entry's place from the count of
-// kept entries before it (ballot + popcount inside a wave, a 16-entry table across waves, the step's start
-// offset from a table written in the forward pass).
+// c = (i-1)(n-1) + (j-1) of step t takes word c mod 4 of the Philox call c / 4 with (stream, step = t)).  Every
+// wave appends its kept entries to a run of its own; the backward pass draws the same keys again and walks the
+// run back (ballot + popcount give a lane's place among the wave's kept entries of a step).
 #include <cmath>
 
 #include "kernels.hpp"
@@ -37,16 +36,24 @@ struct PdeThread {
     tgt_xy = interior ? s2x * sinpi(y) : 0.0;
   }
   // is this thread's entry of step t kept; how many kept entries of the wave come before it; the wave's count
-  __device__ __forceinline__ bool draw(int64_t t, uint32_t thr_lo, bool keep_all, uint32_t seed_lo, uint32_t seed_hi,
-                                       uint32_t stream, uint32_t* before, uint32_t* in_wave) const {
-    const u32x4 k4 = element_quad_keys((uint64_t)(cell >> 2), stream, (uint32_t)t, seed_lo, seed_hi);
-    const bool keep = interior && (keep_all || k4[cell & 3] < thr_lo);
+  __device__ __forceinline__ bool draw(const uint32_t* keys, uint32_t thr_lo, bool keep_all, uint32_t* before,
+                                       uint32_t* in_wave) const {
+    const bool keep = interior && (keep_all || keys[cell] < thr_lo);
     const uint64_t b = __ballot(keep);
     *before = (uint32_t)__popcll(b & ((1ull << lane) - 1ull));
     *in_wave = (uint32_t)__popcll(b);
     return keep;
   }
 };
+
+// the keys of step t for all interior entries, four per Philox call, by the first (n-1)^2 / 4 threads
+__device__ __forceinline__ void pde_fill_keys(uint32_t* keys, int cells, int64_t t, uint32_t seed_lo, uint32_t seed_hi,
+                                              uint32_t stream) {
+  if ((int)threadIdx.x * 4 < cells) {
+    const u32x4 k4 = element_quad_keys((uint64_t)threadIdx.x, stream, (uint32_t)t, seed_lo, seed_hi);
+    *reinterpret_cast<u32x4*>(keys + 4 * threadIdx.x) = k4;
+  }
+}
 
 __device__ __forceinline__ double pde_c(const double* th, double s, double c, double s2x, double c2x) {
   return th[0] + th[1] * s + th[2] * c + s2x * (th[3] * s + th[4] * c) + c2x * (th[5] * s + th[6] * c);
@@ -69,31 +76,36 @@ struct PdeArgs {
   uint32_t thr; int keep_all;                 // keep iff key < thr; p = 1 keeps everything
   uint32_t seed_lo, seed_hi, stream_id;
   const double* theta;                        // [problems][7]
-  double* vals; int64_t cap;                  // [problems][cap] kept entries
-  uint32_t* row_ptr;                          // [problems][steps + 2] start of every step's entries
+  double* vals; int64_t cap;                  // [problems][16 waves][cap] kept entries, each wave its own run
+  uint32_t* wave_end;                         // [problems][16] entries each wave kept in all
   int* overflow;                              // [problems]
   double* loss; double* grad; int64_t* stored;
 };
+
+// Each wave (two grid rows) appends its kept entries to a run of its own, so a thread's place is the wave's
+// running count plus the kept lanes below it: no exchange between waves, and the backward pass walks the run
+// back by subtracting each step's count.
 
 __global__ __launch_bounds__(kPdeThreads) void pde_forward_kernel(PdeArgs a) {
   __shared__ double ph[2][kPdeNodes];
   __shared__ double red[kPdeThreads];
   __shared__ double trig_s[kPdeThreads], trig_c[kPdeThreads];   // sin, cos of pi t for the next 1024 steps
-  __shared__ uint32_t wcnt[2][16];
+  __shared__ __align__(16) uint32_t keys[2][kPdeThreads];        // keys of this step and of the next
   const int pb = blockIdx.x;
   PdeThread me; me.init(a.n);
+  const int cells = (a.n - 1) * (a.n - 1);
   double th[7];
 #pragma unroll
   for (int k = 0; k < 7; ++k) th[k] = a.theta[(size_t)pb * 7 + k];
   const uint32_t stream = a.stream_id + (uint32_t)pb;
-  double* const vals = a.vals + (size_t)pb * a.cap;
-  uint32_t* const row_ptr = a.row_ptr + (size_t)pb * (a.steps + 2);
+  double* const vals = a.vals + ((size_t)pb * 16 + me.wave) * a.cap;
   for (int q = threadIdx.x; q < 2 * kPdeNodes; q += kPdeThreads) (&ph[0][0])[q] = 0.0;
+  pde_fill_keys(keys[0], cells, 0, a.seed_lo, a.seed_hi, stream);
   __syncthreads();
   if (me.interior) ph[0][me.idx] = me.phi0;
   __syncthreads();
   double mine = me.phi0, loss = 0.0, s = 0.0, c = 1.0;          // sin, cos of pi t at t = 0
-  uint32_t offset = 0;
+  int64_t offset = 0;                                            // entries this wave has kept so far
   bool over = false;
   for (int64_t t = 0; t <= a.steps; ++t) {
     const int cur = (int)(t & 1);
@@ -103,77 +115,75 @@ __global__ __launch_bounds__(kPdeThreads) void pde_forward_kernel(PdeArgs a) {
       __syncthreads();
     }
     uint32_t before, in_wave;
-    const bool keep = me.draw(t, a.thr, a.keep_all != 0, a.seed_lo, a.seed_hi, stream, &before, &in_wave);
-    if (me.lane == 0) wcnt[cur][me.wave] = in_wave;
+    const bool keep = me.draw(keys[cur], a.thr, a.keep_all != 0, &before, &in_wave);
+    if (keep) {
+      const int64_t pos = offset + before;
+      if (pos < a.cap) vals[pos] = mine; else over = true;
+    }
+    offset += in_wave;
+    if (t == a.steps) break;
+    pde_fill_keys(keys[cur ^ 1], cells, t + 1, a.seed_lo, a.seed_hi, stream);
     double nw = 0.0;
-    if (t < a.steps && me.interior) {
+    if (me.interior) {
       const double* f = ph[cur];
       const double nb = (f[me.idx + kPdePitch] + f[me.idx - kPdePitch]) + (f[me.idx + 1] + f[me.idx - 1]);
       nw = mine + a.r * (nb - 4.0 * mine) + a.dt * pde_c(th, s, c, me.s2x, me.c2x) * mine;
       ph[cur ^ 1][me.idx] = nw;
     }
+    s = trig_s[t & 1023]; c = trig_c[t & 1023];
+    if (me.interior) {
+      const double d = nw - (me.phi0 + 0.25 * s * me.tgt_xy);
+      loss += d * d;
+      mine = nw;
+    }
     __syncthreads();
-    uint32_t base = offset, total = 0;
-#pragma unroll
-    for (int u = 0; u < 16; ++u) { const uint32_t v = wcnt[cur][u]; if (u < me.wave) base += v; total += v; }
-    if (keep) {
-      const int64_t pos = (int64_t)base + before;
-      if (pos < a.cap) vals[pos] = mine; else over = true;
-    }
-    if (threadIdx.x == 0) row_ptr[t] = offset;
-    offset += total;
-    if (t < a.steps) {
-      s = trig_s[t & 1023]; c = trig_c[t & 1023];
-      if (me.interior) {
-        const double d = nw - (me.phi0 + 0.25 * s * me.tgt_xy);
-        loss += d * d;
-        mine = nw;
-      }
-    }
   }
-  if (threadIdx.x == 0) { row_ptr[a.steps + 1] = offset; if (a.stored) a.stored[pb] = (int64_t)offset; }
+  if (me.lane == 0) a.wave_end[(size_t)pb * 16 + me.wave] = (uint32_t)(offset < a.cap ? offset : a.cap);
   const double total_loss = block_sum(loss, red);
   const double any_over = block_sum(over ? 1.0 : 0.0, red);
-  if (threadIdx.x == 0) { a.loss[pb] = total_loss / (double)a.steps; a.overflow[pb] = any_over > 0.0 ? 1 : 0; }
+  const double kept = block_sum(me.lane == 0 ? (double)offset : 0.0, red);
+  if (threadIdx.x == 0) {
+    a.loss[pb] = total_loss / (double)a.steps;
+    a.overflow[pb] = any_over > 0.0 ? 1 : 0;
+    if (a.stored) a.stored[pb] = (int64_t)kept;
+  }
 }
 
 __global__ __launch_bounds__(kPdeThreads) void pde_backward_kernel(PdeArgs a) {
   __shared__ double lb[2][kPdeNodes];
   __shared__ double red[kPdeThreads];
   __shared__ double trig_s[kPdeThreads], trig_c[kPdeThreads];   // sin, cos of pi t for 1024 time points
-  __shared__ uint32_t wcnt[2][16];
+  __shared__ __align__(16) uint32_t keys[2][kPdeThreads];        // keys of the step being drawn and of the one before
   const int pb = blockIdx.x;
   PdeThread me; me.init(a.n);
+  const int cells = (a.n - 1) * (a.n - 1);
   double th[7], g[7];
 #pragma unroll
   for (int k = 0; k < 7; ++k) { th[k] = a.theta[(size_t)pb * 7 + k]; g[k] = 0.0; }
   const uint32_t stream = a.stream_id + (uint32_t)pb;
-  const double* const vals = a.vals + (size_t)pb * a.cap;
-  const uint32_t* const row_ptr = a.row_ptr + (size_t)pb * (a.steps + 2);
+  const double* const vals = a.vals + ((size_t)pb * 16 + me.wave) * a.cap;
+  int64_t offset = (int64_t)a.wave_end[(size_t)pb * 16 + me.wave];       // walks back one step's count at a time
   const double inv_p = 1.0 / a.p, w_loss = 2.0 / (double)a.steps;
   for (int q = threadIdx.x; q < 2 * kPdeNodes; q += kPdeThreads) (&lb[0][0])[q] = 0.0;
 
-  // value of this thread's entry of step t (0 if it was not kept): first half before a barrier, second after
-  bool keepN = false; uint32_t beforeN = 0;
-  auto fetch_begin = [&](int64_t t, int buf) {
-    uint32_t in_wave;
-    keepN = me.draw(t, a.thr, a.keep_all != 0, a.seed_lo, a.seed_hi, stream, &beforeN, &in_wave);
-    if (me.lane == 0) wcnt[buf][me.wave] = in_wave;
+  // value of this thread's entry of step t (0 if it was not kept); keys[buf] holds the keys of step t (filled
+  // before the last barrier), those of step t - 1 go to the other half
+  auto fetch = [&](int64_t t, int buf, bool& keep) -> double {
+    uint32_t before, in_wave;
+    keep = me.draw(keys[buf], a.thr, a.keep_all != 0, &before, &in_wave);
+    if (t >= 1) pde_fill_keys(keys[buf ^ 1], cells, t - 1, a.seed_lo, a.seed_hi, stream);
+    offset -= in_wave;
+    const int64_t pos = offset + before;
+    return (keep && pos >= 0 && pos < a.cap) ? vals[pos] : 0.0;
   };
-  auto fetch_end = [&](int64_t t, int buf) -> double {
-    uint32_t base = row_ptr[t];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) { const uint32_t v = wcnt[buf][u]; if (u < me.wave) base += v; }
-    const int64_t pos = (int64_t)base + beforeN;
-    return (keepN && pos < a.cap) ? vals[pos] : 0.0;
-  };
-  // A: step t, B: step t - 1 (values are 0 where nothing was kept, so no flags are carried)
-  fetch_begin(a.steps, 0);
+  // A: step t, B: step t - 1
+  pde_fill_keys(keys[0], cells, a.steps, a.seed_lo, a.seed_hi, stream);
   __syncthreads();
-  double valA = fetch_end(a.steps, 0); bool keepA = keepN;
-  fetch_begin(a.steps - 1, 1);
+  bool keepA, keepB, keepC = false;
+  double valA = fetch(a.steps, 0, keepA);
   __syncthreads();
-  double valB = fetch_end(a.steps - 1, 1); bool keepB = keepN;
+  double valB = fetch(a.steps - 1, 1, keepB);
+  __syncthreads();
   double lam = 0.0, s_t, c_t;
   sincospi((double)a.steps * a.dt, &s_t, &c_t);
   int cur = 0;                      // buffers alternate from the prologue on: 0, 1, then 0 again
@@ -184,24 +194,23 @@ __global__ __launch_bounds__(kPdeThreads) void pde_backward_kernel(PdeArgs a) {
       sincospi((double)((u & ~(int64_t)1023) + threadIdx.x) * a.dt, &trig_s[threadIdx.x], &trig_c[threadIdx.x]);
       __syncthreads();
     }
-    if (t >= 2) fetch_begin(t - 2, cur);
+    double valC = 0.0;
+    if (t >= 2) valC = fetch(t - 2, cur, keepC);                // its load is in flight during this step
     if (keepA) lam += w_loss * inv_p * (valA - (me.phi0 + 0.25 * s_t * me.tgt_xy));
     const double s = trig_s[u & 1023], c = trig_c[u & 1023];
-    if (keepB) {
+    {
       const double w = a.dt * inv_p * valB * lam;
       g[0] += w; g[1] += s * w; g[2] += c * w;
       g[3] += me.s2x * s * w; g[4] += me.s2x * c * w; g[5] += me.c2x * s * w; g[6] += me.c2x * c * w;
     }
     if (me.interior) lb[cur][me.idx] = lam;
     __syncthreads();
-    double valC = 0.0; bool keepC = false;
-    if (t >= 2) { valC = fetch_end(t - 2, cur); keepC = keepN; }
     if (me.interior) {
       const double* f = lb[cur];
       const double nb = (f[me.idx + kPdePitch] + f[me.idx - kPdePitch]) + (f[me.idx + 1] + f[me.idx - 1]);
       lam = lam + a.r * (nb - 4.0 * lam) + a.dt * pde_c(th, s, c, me.s2x, me.c2x) * lam;
     }
-    valA = valB; keepA = keepB; valB = valC; keepB = keepC;
+    valA = valB; valB = valC; keepA = keepB; keepB = keepC;
     s_t = s; c_t = c;
   }
 #pragma unroll
@@ -215,14 +224,14 @@ __global__ __launch_bounds__(kPdeThreads) void pde_backward_kernel(PdeArgs a) {
 
 hipError_t launch_pde(int problems, int n, int64_t steps, double D, double dt, double p, uint32_t seed_lo,
                       uint32_t seed_hi, uint32_t stream_id, const double* theta, double* vals, int64_t cap,
-                      uint32_t* row_ptr, int* overflow, double* loss, double* grad, int64_t* stored, hipStream_t st) {
+                      uint32_t* wave_end, int* overflow, double* loss, double* grad, int64_t* stored, hipStream_t st) {
   PdeArgs a;
   a.n = n; a.steps = steps; a.r = D * dt * (double)n * (double)n; a.dt = dt; a.p = p;
   const double thr = std::floor(p * 4294967296.0 + 0.5);
   a.keep_all = thr >= 4294967296.0 ? 1 : 0;
   a.thr = a.keep_all ? 0xffffffffu : (uint32_t)thr;
   a.seed_lo = seed_lo; a.seed_hi = seed_hi; a.stream_id = stream_id;
-  a.theta = theta; a.vals = vals; a.cap = cap; a.row_ptr = row_ptr; a.overflow = overflow;
+  a.theta = theta; a.vals = vals; a.cap = cap; a.wave_end = wave_end; a.overflow = overflow;
   a.loss = loss; a.grad = grad; a.stored = stored;
   hipLaunchKernelGGL(pde_forward_kernel, dim3((unsigned)problems), dim3(kPdeThreads), 0, st, a);
   hipError_t e = hipGetLastError();
