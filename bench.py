@@ -46,7 +46,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32"],
+                    help="pde32: the reaction-diffusion study instead of a train step (a step = one gradient of each "
+                         "of 256 problems)")
     ap.add_argument("--scheme", default="per_example", choices=sorted(SCHEMES))
     ap.add_argument("--p", type=float, default=0.1)
     ap.add_argument("--index-free", action="store_true",
@@ -60,6 +62,13 @@ def main():
     import numpy as np
     import torch
     from paper_2007_10412_amd import binding as B, synth
+
+    if args.workload == "pde32":
+        ctx = B.rad_ctx_create()
+        out = pde_study(B, ctx, torch, steps=args.steps, warmup=args.warmup, p=args.p if args.p < 1 else 0.01)
+        B.rad_ctx_destroy(ctx)
+        print(json.dumps(out))
+        return
 
     dtype_name, batch, dims, pixels, has_bias = WORKLOADS[args.workload]
     dtype = B.RAD_BF16 if dtype_name == "bf16" else B.RAD_F32
@@ -217,6 +226,7 @@ def main():
         out["kernels"] = kern
         out["pack_stream"] = pack_stream(B, ctx, torch, dtype_name)
         out["optimizer"] = optimizer_stream(B, ctx, torch, dtype, params, grads)
+        out["pde"] = pde_study(B, ctx, torch, steps=2, warmup=1, p=0.01)
         out["other_configs"] = other_configs(B, ctx, torch, synth)
         if args.workload == "mlp4096_bf16":
             out["config4_variants"] = config4_variants(B, ctx, torch, data, dims, batch)
@@ -364,6 +374,36 @@ def pack_stream(B, ctx, torch, dtype_name):
                      "unit": "GB/s", "frac": pack_bytes / t_pack / 1e9 / HBM_PEAK},
             "plan": {"bound": "alu", "ms": t_plan * 1e3, "keys_per_s": n / t_plan,
                      "write_GBps": plan_bytes / t_plan / 1e9}}
+
+
+def pde_study(B, ctx, torch, steps, warmup, p, problems=256):
+    """The reaction-diffusion study at the paper's size (32 x 32 intervals, 40960 time steps, fraction p of every
+    state kept): one call = loss and sampled gradient of `problems` control vectors, one workgroup (CU) each.
+    The time steps of a problem depend on each other, so the kernels are bound by the latency of one step
+    (instruction issue of the workgroup's 16 waves plus a barrier), not by a memory or arithmetic roofline:
+    what is reported is the time per step of the chain."""
+    grid = B.make_pde_grid(32, 40960)
+    ws = torch.empty(B.rad_pde_workspace_bytes(ctx, grid, p, problems), dtype=torch.uint8, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    theta = torch.rand(problems, 7, dtype=torch.float64, device="cuda", generator=gen) * 2 - 1
+    loss = torch.empty(problems, dtype=torch.float64, device="cuda")
+    grad = torch.empty(problems, 7, dtype=torch.float64, device="cuda")
+    stored = torch.empty(problems, dtype=torch.int64, device="cuda")
+    for i in range(warmup):
+        B.rad_pde_gradient(ctx, grid, theta, p, i, 0, ws, loss, grad, stored)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        B.rad_pde_gradient(ctx, grid, theta, p, 100 + i, 0, ws, loss, grad, stored)   # synchronises
+    dt = (time.perf_counter() - t0) / max(steps, 1)
+    kept = float(stored.double().mean())
+    return {"metric": "pde_gradients_per_sec", "value": problems / dt, "unit": "gradients/s", "n_gpus": 1,
+            "steps": steps, "warmup": warmup, "ms_per_step": dt * 1e3, "higher_is_better": True, "dtype": "f64",
+            "data": "synthetic", "config": {"workload": "reaction-diffusion 32x32, 40960 time steps, p=%g" % p,
+                                            "problems": problems},
+            "us_per_time_step_and_pass": dt / (2 * 40960) * 1e6,
+            "stored_fraction": kept / (40961 * 961), "stored_bytes_per_problem": kept * 8,
+            "dense_bytes_per_problem": 40961 * 961 * 8}
 
 
 def optimizer_stream(B, ctx, torch, dtype, params, grads):
