@@ -732,6 +732,68 @@ def pde_rad_gradient(theta, n, steps, p, seed, stream_id=0, D=0.25, dt=1.0 / 409
 
 
 # ----------------------------------------------------------------------------
+# Reverse-mode AD with path sampling on a general computational graph
+# (Appendix C, Algorithm 1).  The graph is given linearised: vertices numbered
+# in topological order, vertex v with successors succ[succ_ptr[v] :
+# succ_ptr[v+1]] and the partial derivatives d succ / d v on those edges.  In
+# topological order, every vertex that an input vertex reaches through sampled
+# edges (the inputs themselves to begin with) draws k of its d_v outgoing edges
+# uniformly with replacement and adds (d_v / k) * partial to Q of each drawn
+# edge; vertices no sampled edge leads to are skipped.  Back-propagation from y
+# with Q as the edge partials gives the estimate: v^ = sum_e Q(e) succ(e)^,
+# y^ = 1.  Draw s of vertex v takes the key of flat index v k + s and maps it
+# to edge floor(key d_v / 2^32) of v (the mapping of the with-replacement
+# schemes).  `draws`, if given, replaces the keys (tests enumerate outcomes).
+# Pins (tests/test_oracle_paths.py): the expectation over every outcome of the
+# draws on small graphs equals the exact derivative; chains are exact; the
+# mean over seeds on random layered graphs; unreached vertices stay zero.
+# ----------------------------------------------------------------------------
+def graph_exact_adjoints(succ_ptr, succ, partial, y):
+    n = len(succ_ptr) - 1
+    adj = np.zeros(n)
+    adj[y] = 1.0
+    for v in range(n - 1, -1, -1):
+        if v == y:
+            continue
+        e0, e1 = succ_ptr[v], succ_ptr[v + 1]
+        adj[v] = float(np.dot(partial[e0:e1], adj[succ[e0:e1]]))
+    return adj
+
+
+def path_sample_adjoints(succ_ptr, succ, partial, y, inputs, k, seed, stream_id=0, draws=None):
+    """Estimates v^ of dy/dv for every vertex (zero where the vertex was skipped); the gradient is v^ at the
+    input vertices.  draws: optional {vertex: [k edge numbers in 0 .. d_v - 1]}."""
+    succ_ptr = np.asarray(succ_ptr, dtype=np.int64)
+    succ = np.asarray(succ, dtype=np.int64)
+    partial = np.asarray(partial, dtype=np.float64)
+    n = len(succ_ptr) - 1
+    reached = np.zeros(n, dtype=bool)
+    reached[np.asarray(inputs, dtype=np.int64)] = True
+    picks = {}
+    for v in range(n):
+        d = int(succ_ptr[v + 1] - succ_ptr[v])
+        if not reached[v] or d == 0:
+            continue
+        if draws is not None:
+            idx = np.asarray(draws[v], dtype=np.int64)
+        else:
+            keys = element_keys(seed, stream_id, 0, v * k, k).astype(np.uint64)
+            idx = ((keys * np.uint64(d)) >> np.uint64(32)).astype(np.int64)
+        picks[v] = succ_ptr[v] + idx
+        reached[succ[picks[v]]] = True
+    adj = np.zeros(n)
+    if reached[y]:
+        adj[y] = 1.0
+    for v in range(n - 1, -1, -1):
+        if v == y or v not in picks:
+            continue
+        d = int(succ_ptr[v + 1] - succ_ptr[v])
+        e = picks[v]
+        adj[v] = (d / k) * float(np.sum(partial[e] * adj[succ[e]]))      # a drawn edge counts once per draw
+    return adj, reached
+
+
+# ----------------------------------------------------------------------------
 # Byte accounting, in the paper's convention (Appendix A, "Calculation of
 # memory saved from RAD"): 32-bit values for the stored (sampled) inputs,
 # ceil(p d) of them per input, one bit per un-reduced ReLU entry, the softmax
