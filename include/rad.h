@@ -352,6 +352,38 @@ rad_status rad_pde_gradient(rad_ctx* ctx, const rad_pde_grid* grid, int32_t prob
                             double p, uint64_t seed, uint32_t stream_id, void* workspace,
                             uint64_t workspace_bytes, double* loss, double* grad, int64_t* stored);
 
+/* ---- path sampling on a general computational graph -------------------------
+ * Appendix C, Algorithm 1.  The graph is linearised: vertices numbered in
+ * topological order, vertex v with outgoing edges succ_ptr[v] .. succ_ptr[v+1]-1,
+ * succ[e] the head of edge e and partial[e] = d succ[e] / d v.  Vertices are
+ * grouped in levels (level l = vertices level_ptr[l] .. level_ptr[l+1]-1) and
+ * every edge leads to a later level.  In topological order each vertex reached
+ * from the inputs through drawn edges draws k of its d_v outgoing edges
+ * uniformly with replacement (draw s of vertex v: the key of flat index
+ * v k + s, edge floor(key d_v / 2^32)) and each draw counts (d_v / k) partial;
+ * vertices no drawn edge leads to are skipped.  Back-propagation from y over
+ * the drawn edges gives adjoint[v], an unbiased estimate of dy/dv (0 for
+ * skipped vertices; 1 at y if y was reached); the gradient is adjoint[] at the
+ * input vertices.  Nothing is stored per edge: the draws are made again on
+ * the way back.  fp64. */
+typedef struct {
+  int32_t n_vertices, n_levels;
+  int64_t n_edges;
+  const int32_t* level_ptr; /* HOST [n_levels + 1], level_ptr[0] = 0, non-decreasing, last = n_vertices */
+  const int32_t* succ_ptr;  /* DEVICE [n_vertices + 1] */
+  const int32_t* succ;      /* DEVICE [n_edges] */
+  const double* partial;    /* DEVICE [n_edges] */
+} rad_graph;
+
+/* inputs: DEVICE [n_inputs] vertex numbers; adjoint: DEVICE [n_vertices] out;
+ * reached: DEVICE [n_vertices] out (1 where the vertex was visited).
+ * 1 <= k <= 65536.  Synchronises; RAD_ERR_PARAM if the device arrays are
+ * inconsistent (numbers out of range, an edge that does not lead to a later
+ * level): outputs are then undefined, but no access leaves the arrays. */
+rad_status rad_path_sample_gradient(rad_ctx* ctx, const rad_graph* graph, int32_t y, const int32_t* inputs,
+                                    int32_t n_inputs, int32_t k, uint64_t seed, uint32_t stream_id,
+                                    double* adjoint, uint32_t* reached);
+
 #ifdef __cplusplus
 }
 #endif

@@ -49,6 +49,11 @@ class rad_pde_grid(C.Structure):
     _fields_ = [("n", C.c_int32), ("steps", C.c_int64), ("D", C.c_double), ("dt", C.c_double)]
 
 
+class rad_graph(C.Structure):
+    _fields_ = [("n_vertices", C.c_int32), ("n_levels", C.c_int32), ("n_edges", C.c_int64), ("level_ptr", P),
+                ("succ_ptr", P), ("succ", P), ("partial", P)]
+
+
 SIGNATURES = {
     "rad_fixed_k": (C.c_int64, [C.c_double, C.c_int64]),
     "rad_ctx_create": (C.c_int, [C.POINTER(P), P]),
@@ -90,6 +95,8 @@ SIGNATURES = {
     "rad_pde_workspace_bytes": (C.c_int, [P, C.POINTER(rad_pde_grid), C.c_double, C.c_int32, C.POINTER(C.c_uint64)]),
     "rad_pde_gradient": (C.c_int, [P, C.POINTER(rad_pde_grid), C.c_int32, P, C.c_double, C.c_uint64, C.c_uint32, P,
                                    C.c_uint64, P, P, P]),
+    "rad_path_sample_gradient": (C.c_int, [P, C.POINTER(rad_graph), C.c_int32, P, C.c_int32, C.c_int32, C.c_uint64,
+                                           C.c_uint32, P, P]),
     "rad_optimizer_step": (C.c_int, [P, C.POINTER(rad_optimizer), C.c_int64, C.c_int32, C.c_int32,
                                      C.POINTER(C.c_int64), C.POINTER(P), C.POINTER(P), C.POINTER(P), C.POINTER(P),
                                      C.POINTER(P)]),
@@ -352,3 +359,13 @@ def rad_pde_gradient(ctx, grid, theta, p, seed, stream_id, workspace, loss, grad
     _check(ctx, lib().rad_pde_gradient(ctx, C.byref(grid), problems, _ptr(theta), p, seed, stream_id, _ptr(workspace),
                                        int(workspace.numel() * workspace.element_size()), _ptr(loss), _ptr(grad),
                                        _ptr(stored)))
+
+
+def rad_path_sample_gradient(ctx, level_ptr, succ_ptr, succ, partial, y, inputs, k, seed, stream_id, adjoint, reached):
+    """level_ptr: host sequence of ints; succ_ptr, succ (int32), partial (fp64), inputs (int32): device tensors;
+    adjoint (fp64) and reached (int32 storage) device tensors of n_vertices entries."""
+    lp = (C.c_int32 * len(level_ptr))(*[int(v) for v in level_ptr])
+    g = rad_graph(int(succ_ptr.numel()) - 1, len(level_ptr) - 1, int(succ.numel()), C.cast(lp, P), succ_ptr.data_ptr(),
+                  succ.data_ptr(), partial.data_ptr())
+    _check(ctx, lib().rad_path_sample_gradient(ctx, C.byref(g), int(y), _ptr(inputs), int(inputs.numel()), int(k), seed,
+                                               stream_id, _ptr(adjoint), _ptr(reached)))

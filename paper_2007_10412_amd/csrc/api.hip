@@ -1040,6 +1040,34 @@ extern "C" rad_status rad_pde_gradient(rad_ctx* c, const rad_pde_grid* g, int32_
   return RAD_OK;
 }
 
+// ------------------------------------------------------------------ path sampling on a graph
+extern "C" rad_status rad_path_sample_gradient(rad_ctx* c, const rad_graph* g, int32_t y, const int32_t* inputs,
+                                               int32_t n_inputs, int32_t k, uint64_t seed, uint32_t stream_id,
+                                               double* adjoint, uint32_t* reached) {
+  if (!c) return RAD_ERR_NULL;
+  if (!g || !inputs || !adjoint || !reached) return fail(c, RAD_ERR_NULL, "null argument");
+  if (!g->level_ptr || !g->succ_ptr || (g->n_edges > 0 && (!g->succ || !g->partial))) return fail(c, RAD_ERR_NULL, "null graph array");
+  if (g->n_vertices < 1 || g->n_vertices > (1 << 30) || g->n_levels < 1 || g->n_edges < 0 || g->n_edges > 0x7fffffffLL)
+    return fail(c, RAD_ERR_SHAPE, "bad graph size");
+  if (y < 0 || y >= g->n_vertices || n_inputs < 1 || n_inputs > g->n_vertices) return fail(c, RAD_ERR_SHAPE, "bad y or inputs");
+  if (k < 1 || k > 65536) return fail(c, RAD_ERR_PARAM, "k must be in 1 .. 65536");
+  if (g->level_ptr[0] != 0 || g->level_ptr[g->n_levels] != g->n_vertices) return fail(c, RAD_ERR_SHAPE, "levels must cover the vertices");
+  for (int l = 0; l < g->n_levels; ++l)
+    if (g->level_ptr[l + 1] < g->level_ptr[l]) return fail(c, RAD_ERR_SHAPE, "level_ptr must not decrease");
+  void* flag = nullptr;
+  RAD_TRY(ws_get(c, WS_ROWLOSS, 4, &flag));
+  HIP_TRY(c, timed(c, "path_sampling", [&](const char**) {
+    return launch_path_sampling(g->n_vertices, g->n_levels, g->level_ptr, g->n_edges, g->succ_ptr, g->succ, g->partial, y,
+                                inputs, n_inputs, k, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, adjoint, reached,
+                                static_cast<int*>(flag), c->stream);
+  }));
+  int bad = 0;
+  HIP_TRY(c, hipMemcpyAsync(&bad, flag, 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (bad) return fail(c, RAD_ERR_PARAM, "graph arrays are inconsistent");
+  return RAD_OK;
+}
+
 // ------------------------------------------------------------------ models
 enum ModelKind { kMlp = 0, kRnn = 1, kCnn = 2 };
 

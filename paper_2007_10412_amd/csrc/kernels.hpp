@@ -127,6 +127,13 @@ hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, i
 hipError_t launch_pde(int problems, int n, int64_t steps, double D, double dt, double p, uint32_t seed_lo,
                       uint32_t seed_hi, uint32_t stream_id, const double* theta, double* vals, int64_t cap,
                       uint32_t* wave_end, int* overflow, double* loss, double* grad, int64_t* stored, hipStream_t st);
+// Path sampling on a linearised graph (vertices in topological order, CSR of outgoing edges; level_ptr_host
+// [n_levels + 1] on the HOST, edges lead to later levels only): reached [n] and adj [n] are outputs, *bad is set
+// if the arrays are inconsistent (an edge or vertex number out of range, an edge inside a level).
+hipError_t launch_path_sampling(int n, int n_levels, const int32_t* level_ptr_host, int64_t n_edges,
+                                const int32_t* succ_ptr, const int32_t* succ, const double* partial, int y,
+                                const int32_t* inputs, int n_inputs, int k, uint32_t seed_lo, uint32_t seed_hi,
+                                uint32_t stream_id, double* adj, uint32_t* reached, int* bad, hipStream_t st);
 // One optimiser step over n parameters: w (fp32, updated in place), g (fp32 gradient), Adam moments m, v (fp32,
 // updated in place; unused for SGD), lo: bf16 copy of w to refresh, or null.  inv_bc1 / inv_bc2 are
 // 1 / (1 - beta^t) of the step number and omb1 / omb2 are 1 - beta, all formed in double by the caller (in fp32
