@@ -19,6 +19,7 @@ namespace rad {
 namespace {
 
 constexpr int kPdeThreads = 1024, kPdePitch = 33, kPdeNodes = kPdePitch * kPdePitch;
+constexpr int kPdeTab = 512;         // time points per refill of the per-step tables
 
 struct PdeThread {
   int i, j, idx, cell, lane, wave;
@@ -55,10 +56,6 @@ __device__ __forceinline__ void pde_fill_keys(uint32_t* keys, int cells, int64_t
   }
 }
 
-__device__ __forceinline__ double pde_c(const double* th, double s, double c, double s2x, double c2x) {
-  return th[0] + th[1] * s + th[2] * c + s2x * (th[3] * s + th[4] * c) + c2x * (th[5] * s + th[6] * c);
-}
-
 // sum over the workgroup in a fixed order; every thread gets the result
 __device__ __forceinline__ double block_sum(double v, double* red) {
   __syncthreads();
@@ -89,7 +86,8 @@ struct PdeArgs {
 __global__ __launch_bounds__(kPdeThreads) void pde_forward_kernel(PdeArgs a) {
   __shared__ double ph[2][kPdeNodes];
   __shared__ double red[kPdeThreads];
-  __shared__ double trig_s[kPdeThreads], trig_c[kPdeThreads];   // sin, cos of pi t for the next 1024 steps
+  // for each of the next kPdeTab time points: sin(pi t), and C = ca + sin(2 pi x) cb + cos(2 pi x) cc
+  __shared__ double trig_s[kPdeTab], tab_a[kPdeTab], tab_b[kPdeTab], tab_c[kPdeTab];
   __shared__ __align__(16) uint32_t keys[2][kPdeThreads];        // keys of this step and of the next
   const int pb = blockIdx.x;
   PdeThread me; me.init(a.n);
@@ -104,14 +102,22 @@ __global__ __launch_bounds__(kPdeThreads) void pde_forward_kernel(PdeArgs a) {
   __syncthreads();
   if (me.interior) ph[0][me.idx] = me.phi0;
   __syncthreads();
-  double mine = me.phi0, loss = 0.0, s = 0.0, c = 1.0;          // sin, cos of pi t at t = 0
+  double mine = me.phi0, loss = 0.0;
+  double ca = th[0] + th[2], cb = th[4], cc = th[6];             // C at t = 0: sin = 0, cos = 1
   int64_t offset = 0;                                            // entries this wave has kept so far
   bool over = false;
   for (int64_t t = 0; t <= a.steps; ++t) {
     const int cur = (int)(t & 1);
-    if ((t & 1023) == 0) {          // every thread works out one of the next 1024 time points
+    if ((t & (kPdeTab - 1)) == 0) {          // a thread each works out the next kPdeTab time points
       __syncthreads();
-      sincospi((double)(t + 1 + threadIdx.x) * a.dt, &trig_s[threadIdx.x], &trig_c[threadIdx.x]);
+      if (threadIdx.x < kPdeTab) {
+        double sn, cs;
+        sincospi((double)(t + 1 + threadIdx.x) * a.dt, &sn, &cs);
+        trig_s[threadIdx.x] = sn;
+        tab_a[threadIdx.x] = th[0] + th[1] * sn + th[2] * cs;
+        tab_b[threadIdx.x] = th[3] * sn + th[4] * cs;
+        tab_c[threadIdx.x] = th[5] * sn + th[6] * cs;
+      }
       __syncthreads();
     }
     uint32_t before, in_wave;
@@ -127,10 +133,12 @@ __global__ __launch_bounds__(kPdeThreads) void pde_forward_kernel(PdeArgs a) {
     if (me.interior) {
       const double* f = ph[cur];
       const double nb = (f[me.idx + kPdePitch] + f[me.idx - kPdePitch]) + (f[me.idx + 1] + f[me.idx - 1]);
-      nw = mine + a.r * (nb - 4.0 * mine) + a.dt * pde_c(th, s, c, me.s2x, me.c2x) * mine;
+      nw = mine + a.r * (nb - 4.0 * mine) + a.dt * (ca + me.s2x * cb + me.c2x * cc) * mine;
       ph[cur ^ 1][me.idx] = nw;
     }
-    s = trig_s[t & 1023]; c = trig_c[t & 1023];
+    const int q = (int)(t & (kPdeTab - 1));
+    const double s = trig_s[q];                                  // time t + 1
+    ca = tab_a[q]; cb = tab_b[q]; cc = tab_c[q];
     if (me.interior) {
       const double d = nw - (me.phi0 + 0.25 * s * me.tgt_xy);
       loss += d * d;
@@ -152,14 +160,18 @@ __global__ __launch_bounds__(kPdeThreads) void pde_forward_kernel(PdeArgs a) {
 __global__ __launch_bounds__(kPdeThreads) void pde_backward_kernel(PdeArgs a) {
   __shared__ double lb[2][kPdeNodes];
   __shared__ double red[kPdeThreads];
-  __shared__ double trig_s[kPdeThreads], trig_c[kPdeThreads];   // sin, cos of pi t for 1024 time points
+  // for kPdeTab time points: sin and cos of pi t, and C = ca + sin(2 pi x) cb + cos(2 pi x) cc
+  __shared__ double trig_s[kPdeTab], trig_c[kPdeTab], tab_a[kPdeTab], tab_b[kPdeTab], tab_c[kPdeTab];
   __shared__ __align__(16) uint32_t keys[2][kPdeThreads];        // keys of the step being drawn and of the one before
   const int pb = blockIdx.x;
   PdeThread me; me.init(a.n);
   const int cells = (a.n - 1) * (a.n - 1);
-  double th[7], g[7];
+  double th[7];
 #pragma unroll
-  for (int k = 0; k < 7; ++k) { th[k] = a.theta[(size_t)pb * 7 + k]; g[k] = 0.0; }
+  for (int k = 0; k < 7; ++k) th[k] = a.theta[(size_t)pb * 7 + k];
+  // dL/dC of this node summed over time with the weights 1, sin(pi t), cos(pi t): the node's factors
+  // sin(2 pi x), cos(2 pi x) of the seven basis functions are applied once at the end
+  double w1 = 0.0, ws = 0.0, wc = 0.0;
   const uint32_t stream = a.stream_id + (uint32_t)pb;
   const double* const vals = a.vals + ((size_t)pb * 16 + me.wave) * a.cap;
   int64_t offset = (int64_t)a.wave_end[(size_t)pb * 16 + me.wave];       // walks back one step's count at a time
@@ -189,30 +201,39 @@ __global__ __launch_bounds__(kPdeThreads) void pde_backward_kernel(PdeArgs a) {
   int cur = 0;                      // buffers alternate from the prologue on: 0, 1, then 0 again
   for (int64_t t = a.steps; t >= 1; --t, cur ^= 1) {
     const int64_t u = t - 1;        // the time point of C and of the sampled phi of this iteration
-    if (t == a.steps || (u & 1023) == 1023) {
+    const int q = (int)(u & (kPdeTab - 1));
+    if (t == a.steps || q == kPdeTab - 1) {
       __syncthreads();
-      sincospi((double)((u & ~(int64_t)1023) + threadIdx.x) * a.dt, &trig_s[threadIdx.x], &trig_c[threadIdx.x]);
+      if (threadIdx.x < kPdeTab) {
+        double sn, cs;
+        sincospi((double)((u & ~(int64_t)(kPdeTab - 1)) + threadIdx.x) * a.dt, &sn, &cs);
+        trig_s[threadIdx.x] = sn; trig_c[threadIdx.x] = cs;
+        tab_a[threadIdx.x] = th[0] + th[1] * sn + th[2] * cs;
+        tab_b[threadIdx.x] = th[3] * sn + th[4] * cs;
+        tab_c[threadIdx.x] = th[5] * sn + th[6] * cs;
+      }
       __syncthreads();
     }
     double valC = 0.0;
     if (t >= 2) valC = fetch(t - 2, cur, keepC);                // its load is in flight during this step
     if (keepA) lam += w_loss * inv_p * (valA - (me.phi0 + 0.25 * s_t * me.tgt_xy));
-    const double s = trig_s[u & 1023], c = trig_c[u & 1023];
+    const double s = trig_s[q], c = trig_c[q];
     {
-      const double w = a.dt * inv_p * valB * lam;
-      g[0] += w; g[1] += s * w; g[2] += c * w;
-      g[3] += me.s2x * s * w; g[4] += me.s2x * c * w; g[5] += me.c2x * s * w; g[6] += me.c2x * c * w;
+      const double w = valB * lam;                               // times dt / p at the end
+      w1 += w; ws += s * w; wc += c * w;
     }
     if (me.interior) lb[cur][me.idx] = lam;
     __syncthreads();
     if (me.interior) {
       const double* f = lb[cur];
       const double nb = (f[me.idx + kPdePitch] + f[me.idx - kPdePitch]) + (f[me.idx + 1] + f[me.idx - 1]);
-      lam = lam + a.r * (nb - 4.0 * lam) + a.dt * pde_c(th, s, c, me.s2x, me.c2x) * lam;
+      lam = lam + a.r * (nb - 4.0 * lam) + a.dt * (tab_a[q] + me.s2x * tab_b[q] + me.c2x * tab_c[q]) * lam;
     }
     valA = valB; valB = valC; keepA = keepB; keepB = keepC;
     s_t = s; c_t = c;
   }
+  const double sc = a.dt * inv_p;
+  const double g[7] = {w1 * sc, ws * sc, wc * sc, me.s2x * ws * sc, me.s2x * wc * sc, me.c2x * ws * sc, me.c2x * wc * sc};
 #pragma unroll
   for (int k = 0; k < 7; ++k) {
     const double tot = block_sum(g[k], red);
