@@ -611,6 +611,30 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
       return RAD_OK;
     }
   }
+  // fp32, few 64 x 64 tiles and a long contraction (a time step of the recurrent model: 128 x 1024 x 1024 is 32
+  // tiles, each a chain of 64 K-slices): split K eight ways; one kernel then adds the partial sums and does the
+  // epilogue's work (bias, input term, ReLU, bits), and the next store's sample is packed by the pack kernel
+  const int tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
+  if (dtype == kF32 && tiles64 <= 64 && K >= 512 && N % 64 == 0 && ldx == K) {
+    int splits = K / 128;
+    if (splits > 8) splits = 8;
+    const int ks = ((K + splits - 1) / splits + 15) / 16 * 16;
+    splits = (K + ks - 1) / ks;
+    if (splits > 1) {
+      void* part = nullptr;
+      RAD_TRY(ws_get(c, WS_SPLITK, (size_t)splits * M * N * 4, &part));
+      g.C = part; g.ldc = N; g.c_dtype = kF32;
+      g.k_split = ks; g.k_splits = splits;
+      RAD_TRY(run_gemm_call(c, dtype, kOpK, kOpMN, kEpiSplitK, g));
+      HIP_TRY(c, timed(c, "splitk_fwd", [&](const char**) {
+        return launch_splitk_fwd_f32(static_cast<const float*>(part), splits, M, N, bias, u, u_ld, u_n, V, relu,
+                                     static_cast<float*>(y), relu ? bits : nullptr, bits_pitch, c->stream);
+      }));
+      if (next)
+        HIP_TRY(c, timed(c, "pack_f32", [&](const char**) { return launch_pack(y, kF32, *next, c->stream); }));
+      return RAD_OK;
+    }
+  }
   g.bias = bias; g.relu = relu; g.y = y; g.ldy = N; g.bits = relu ? bits : nullptr; g.bits_pitch = bits_pitch;
   if (next) { g.pack = 1; g.next = *next; }
   g.u = u; g.u_ld = u_ld; g.u_n = u_n; g.V = V;
@@ -858,6 +882,26 @@ static rad_status dX_gemm(rad_ctx* c, int dtype, int M, int d_in, int d_out, con
   g.M = M; g.N = d_in; g.K = d_out;
   g.A = dy; g.lda = d_out; g.a_mask = bits; g.a_mask_pitch = bits_pitch;
   g.B = W; g.ldb = d_out;
+  // fp32 with few tiles and a long contraction: split K, then add the partial sums under the output mask
+  const int tiles64 = ((M + 63) / 64) * ((d_in + 63) / 64);
+  if (dtype == kF32 && tiles64 <= 64 && d_out >= 512) {
+    int splits = d_out / 128;
+    if (splits > 8) splits = 8;
+    const int ks = ((d_out + splits - 1) / splits + 15) / 16 * 16;
+    splits = (d_out + ks - 1) / ks;
+    if (splits > 1) {
+      void* part = nullptr;
+      RAD_TRY(ws_get(c, WS_SPLITK, (size_t)splits * M * d_in * 4, &part));
+      g.C = part; g.ldc = d_in; g.c_dtype = kF32;
+      g.k_split = ks; g.k_splits = splits;
+      RAD_TRY(run_gemm_call(c, dtype, kOpK, kOpK, kEpiSplitK, g));
+      HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
+        return launch_splitk_reduce_masked(static_cast<const float*>(part), splits, M, d_in, out_bits, out_pitch,
+                                           static_cast<float*>(dX), c->stream);
+      }));
+      return RAD_OK;
+    }
+  }
   g.C = dX; g.ldc = d_in; g.beta = 0; g.c_dtype = dtype;
   g.c_mask = out_bits; g.c_mask_pitch = out_pitch;
   return run_gemm_call(c, dtype, kOpK, kOpK, kEpiStore, g);

@@ -110,6 +110,13 @@ hipError_t launch_project_rows_bwd(const void* z, int dtype, int rows, int d, in
 hipError_t launch_scale_cast(const float* in, void* out, int dtype, int64_t n, float scale, hipStream_t st);
 // out[i] (+)= sum over `splits` partial arrays of n elements
 hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st);
+// fp32 forward GEMM finished from split-K partial sums [splits][M][N]: bias, low-rank term u V, ReLU, (h > 0) bits
+// (N a multiple of 64); and a dX finished from partial sums with the output mask of the layer below
+hipError_t launch_splitk_fwd_f32(const float* partial, int splits, int M, int N, const float* bias, const float* u,
+                                 int64_t u_ld, int u_n, const float* V, int relu, float* y, uint32_t* bits,
+                                 int bits_pitch, hipStream_t st);
+hipError_t launch_splitk_reduce_masked(const float* partial, int splits, int M, int N, const uint32_t* mask, int pitch,
+                                       float* out, hipStream_t st);
 hipError_t launch_splitk_bias(const float* partial, int splits, int M, int N, const float* bias, void* out, int dtype,
                               hipStream_t st);
 // 2x2/stride-2 max pool over NCHW planes; arg packs the 2-bit window position (dy*2+dx of the first maximum)

@@ -421,6 +421,65 @@ hipError_t launch_splitk_bias(const float* partial, int splits, int M, int N, co
   return hipGetLastError();
 }
 
+// Sum of split-K partial sums of a forward GEMM with what its fused epilogue would have done: bias, the
+// low-rank input term u V, ReLU, the (h > 0) bits.  One thread per output; a wave covers 64 consecutive columns of
+// a row (N is a multiple of 64), so a ballot gives two whole words of the bit array.
+__global__ __launch_bounds__(256) void splitk_fwd_f32_kernel(const float* __restrict__ partial, int splits, int M, int N,
+                                                             const float* __restrict__ bias, const float* __restrict__ u,
+                                                             int64_t u_ld, int u_n, const float* __restrict__ V, int relu,
+                                                             float* __restrict__ y, uint32_t* __restrict__ bits,
+                                                             int bits_pitch) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = (int64_t)M * N;
+  if (i >= total) return;                        // total is a multiple of 64: whole waves leave together
+  const int row = (int)(i / N), col = (int)(i - (int64_t)row * N);
+  float h = 0.f;
+  for (int s = 0; s < splits; ++s) h += partial[(size_t)s * total + i];
+  if (bias) h += bias[col];
+  for (int q = 0; q < u_n; ++q) h += u[(size_t)row * u_ld + q] * V[(size_t)q * N + col];
+  if (relu) h = h > 0.f ? h : 0.f;
+  y[i] = h;
+  if (bits) {
+    const uint64_t b = __ballot(h > 0.f);
+    const int lane = threadIdx.x & 63;
+    if (lane == 0) bits[(size_t)row * bits_pitch + (col >> 5)] = (uint32_t)b;
+    if (lane == 32) bits[(size_t)row * bits_pitch + (col >> 5)] = (uint32_t)(b >> 32);
+  }
+}
+
+// Sum of split-K partial sums, zeroed where the mask bit of the output entry is clear (mask: [M][pitch] words
+// over N columns, or null)
+__global__ __launch_bounds__(256) void splitk_reduce_masked_kernel(const float* __restrict__ partial, int splits, int M,
+                                                                   int N, const uint32_t* __restrict__ mask, int pitch,
+                                                                   float* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = (int64_t)M * N;
+  if (i >= total) return;
+  const int row = (int)(i / N), col = (int)(i - (int64_t)row * N);
+  float v = 0.f;
+  for (int s = 0; s < splits; ++s) v += partial[(size_t)s * total + i];
+  if (mask && !((mask[(size_t)row * pitch + (col >> 5)] >> (col & 31)) & 1u)) v = 0.f;
+  out[i] = v;
+}
+
+hipError_t launch_splitk_fwd_f32(const float* partial, int splits, int M, int N, const float* bias, const float* u,
+                                 int64_t u_ld, int u_n, const float* V, int relu, float* y, uint32_t* bits,
+                                 int bits_pitch, hipStream_t st) {
+  if (N % 64 != 0) return hipErrorInvalidValue;
+  const int64_t total = (int64_t)M * N;
+  hipLaunchKernelGGL(splitk_fwd_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, splits, M, N,
+                     bias, u, u_ld, u_n, V, relu, y, bits, bits_pitch);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce_masked(const float* partial, int splits, int M, int N, const uint32_t* mask, int pitch,
+                                       float* out, hipStream_t st) {
+  const int64_t total = (int64_t)M * N;
+  hipLaunchKernelGGL(splitk_reduce_masked_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, splits,
+                     M, N, mask, pitch, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_maxpool_fwd(const float* y, int planes, int H, int W, float* pooled, uint32_t* arg, hipStream_t st) {
   const int64_t total = (int64_t)planes * (H / 2) * (W / 2);
   const int64_t threads = (total + 15) / 16;
