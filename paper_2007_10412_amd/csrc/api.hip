@@ -3,6 +3,7 @@
 // arithmetic of the method happens in the kernels this file launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -797,11 +798,14 @@ static int sparse_prefetch_for(const rad_store* s, int lanes_per_row) {
 }
 
 // dW = beta dW + store(slot)^T (dy masked by bits)
+// n_slots > 1: the contraction runs over that many consecutive step slots of a multi-step store at once (their
+// rows lie one after another in the store; dy then holds the rows of all those steps in the same order); only for
+// stores whose rows are planned one by one and kept with their indices
 static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* dy, int N, const uint32_t* bits,
-                          int bits_pitch, float* dW, int beta) {
+                          int bits_pitch, float* dW, int beta, int n_slots = 1) {
   if (s->project()) return project_dW(c, s, dy, N, bits, bits_pitch, dW, beta);
   GemmArgs g = gemm_zero();
-  g.N = N; g.K = s->rows;
+  g.N = N; g.K = s->rows * n_slots;
   g.B = dy; g.ldb = N; g.b_mask = bits; g.b_mask_pitch = bits_pitch;
   g.C = dW; g.ldc = N; g.beta = beta; g.c_dtype = kF32;
   if (s->scheme == RAD_EXACT) {
@@ -824,10 +828,20 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
   }
   g.M = s->cols;
   RAD_TRY(backward_view(c, s, slot, &g.sa));
+  g.sa.rows = s->rows * n_slots;
   g.sparse_prefetch = sparse_prefetch_for(s, s->dtype == kBF16 ? 8 : 16);
   // 2 N flops per kept entry (expected number for Bernoulli draws)
   const double kept = s->scheme == RAD_BERNOULLI ? s->p * (double)s->rows * s->cols : (double)s->rows * s->k;
   const double alg = 2.0 * kept * N;
+  if (s->dtype == kF32 && n_slots > 1) {
+    // several steps at once (fp32, the recurrent model): the fp32 kernel's sparse loader pays per K-slice, so a
+    // long contraction is cheaper from a transient dense x~ of the chunk
+    void* dense = nullptr;
+    RAD_TRY(ws_get(c, WS_DENSE, (size_t)g.sa.rows * s->cols * 4, &dense));
+    HIP_TRY(c, timed(c, "unpack", [&](const char**) { return launch_unpack(g.sa, kF32, dense, c->stream); }));
+    g.A = dense; g.lda = s->cols;
+    return run_gemm_call(c, kF32, kOpMN, kOpMN, kEpiStore, g, alg);
+  }
   if (s->dtype == kBF16 && g.sparse_prefetch > gemm_bf16_sparse_max_prefetch()) {
     // dense enough that scattering into LDS loses to a plain contraction: rebuild x~ as a transient dense
     // operand (one layer's worth, reused) and run the dense dW kernel
@@ -1114,6 +1128,7 @@ extern "C" rad_status rad_path_sample_gradient(rad_ctx* c, const rad_graph* g, i
 
 // ------------------------------------------------------------------ models
 enum ModelKind { kMlp = 0, kRnn = 1, kCnn = 2 };
+constexpr int kRnnChunk = 8;            // time steps whose recurrent dW is one contraction over steps x batch
 
 struct rad_model {
   int kind = kMlp;
@@ -1129,6 +1144,7 @@ struct rad_model {
   // RNN
   int64_t T = 0, d_input = 0, hidden = 0, classes = 0;
   uint32_t* rnn_bits = nullptr;         // [T][batch][hidden/32]
+  float* rnn_g = nullptr;               // [kRnnChunk][batch][hidden]: g of the time steps whose dW is formed together
   uint32_t* bitmap_ws = nullptr;        // keep bitmaps of every step (transient within a step)
   // CNN
   struct Conv { int ci, co, h, w, pool; uint32_t* arg; };
@@ -1143,7 +1159,7 @@ static rad_status model_share_flags(rad_ctx* c, rad_model* m);
 extern "C" rad_status rad_model_destroy(rad_model* m) {
   if (!m) return RAD_ERR_NULL;
   for (rad_store* s : m->stores) if (s) rad_store_destroy(s);
-  for (void* p : {m->act[0], m->act[1], m->dyb[0], m->dyb[1], m->logits, (void*)m->flags, (void*)m->rnn_bits, (void*)m->bitmap_ws,
+  for (void* p : {m->act[0], m->act[1], m->dyb[0], m->dyb[1], m->logits, (void*)m->flags, (void*)m->rnn_bits, (void*)m->rnn_g, (void*)m->bitmap_ws,
                   m->buf[0], m->buf[1], m->buf[2]})
     if (p) (void)hipFree(p);
   for (auto& cv : m->convs) if (cv.arg) (void)hipFree(cv.arg);
@@ -1355,6 +1371,7 @@ extern "C" rad_status rad_model_create_rnn(rad_ctx* c, int64_t batch, int64_t T,
   for (void** p2 : {&m->act[0], &m->act[1], &m->dyb[0], &m->dyb[1]}) ok = ok && hipMalloc(p2, hb) == hipSuccess;
   ok = ok && hipMalloc(&m->logits, (size_t)batch * classes * 4) == hipSuccess;
   ok = ok && hipMalloc((void**)&m->rnn_bits, (size_t)T * batch * ((hidden + 31) / 32) * 4) == hipSuccess;
+  ok = ok && hipMalloc((void**)&m->rnn_g, (size_t)kRnnChunk * hb) == hipSuccess;
   const size_t bmw = m->stores[0]->bitmap_words() + m->stores[1]->bitmap_words();
   if (bmw) ok = ok && hipMalloc((void**)&m->bitmap_ws, bmw * 4) == hipSuccess;
   if (!ok) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
@@ -1419,19 +1436,31 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   RAD_TRY(colsum_call(c, dz, kF32, B, C, nullptr, 0, nullptr, 0, 0, db_o, nullptr, 0));
   // dyb holds g_t = dL/dh_t masked by the ReLU bits of step t (applied in the epilogue of the GEMM that
   // produces it)
-  RAD_TRY(dX_gemm(c, kF32, B, H, C, dz, nullptr, 0, W_ho, m->dyb[1], m->rnn_bits + (size_t)(T - 1) * B * bp, bp));
-  int cur = 1;
+  // g_t, t >= 2, goes to row block (t - 2) % G of rnn_g; steps 2 + jG .. 1 + (j + 1)G share a chunk, whose store
+  // slots t - 2 are consecutive, so that dW_hh of the chunk is one contraction over (steps x batch) rows instead
+  // of one short contraction per step.  Stores planned per step (shared index sets) or rebuilt before use
+  // (index-free) keep the step-by-step form (two row blocks, used in turn).  g_1 has no dW_hh and lives in dyb[1].
+  const bool per_row = s_hh->scheme == RAD_EXACT || s_hh->scheme == RAD_BERNOULLI || s_hh->scheme == RAD_FIXEDK_PER_EXAMPLE ||
+                       s_hh->scheme == RAD_REPLACE_PER_EXAMPLE;
+  const int G = (per_row && !s_hh->index_free) ? kRnnChunk : 1;
+  const int Gp = G > 1 ? G : 2;                          // row blocks in use
+  const size_t gstride = (size_t)B * H;
+  auto g_of = [&](int t) -> float* { return t >= 2 ? m->rnn_g + (size_t)((t - 2) % Gp) * gstride : static_cast<float*>(m->dyb[1]); };
+  RAD_TRY(dX_gemm(c, kF32, B, H, C, dz, nullptr, 0, W_ho, g_of(T), m->rnn_bits + (size_t)(T - 1) * B * bp, bp));
   if (T == 1) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(dW_hh), 0u, (int64_t)H * H, c->stream));
+  bool first_dw = true;
   for (int t = T; t >= 1; --t) {
     const int beta = t < T;
-    if (t >= 2) RAD_TRY(dW_gemm(c, s_hh, t - 2, m->dyb[cur], H, nullptr, 0, dW_hh, beta));
-    RAD_TRY(colsum_call(c, m->dyb[cur], kF32, B, H, nullptr, 0, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db,
-                        dW_ih, beta));
-    if (t >= 2) {
-      RAD_TRY(dX_gemm(c, kF32, B, H, H, m->dyb[cur], nullptr, 0, W_hh, m->dyb[cur ^ 1],
-                      m->rnn_bits + (size_t)(t - 2) * B * bp, bp));
-      cur ^= 1;
+    if (t >= 2 && (t - 2) % G == 0) {                     // g of the whole chunk t .. t_hi is there
+      const int t_hi = std::min(T, t + G - 1);
+      RAD_TRY(dW_gemm(c, s_hh, t - 2, g_of(t), H, nullptr, 0, dW_hh, first_dw ? 0 : 1, t_hi - t + 1));
+      first_dw = false;
     }
+    RAD_TRY(colsum_call(c, g_of(t), kF32, B, H, nullptr, 0, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db,
+                        dW_ih, beta));
+    if (t >= 2)
+      RAD_TRY(dX_gemm(c, kF32, B, H, H, g_of(t), nullptr, 0, W_hh, g_of(t - 1),
+                      m->rnn_bits + (size_t)(t - 2) * B * bp, bp));
   }
   return step_finish(c, m, loss_host);
 }
