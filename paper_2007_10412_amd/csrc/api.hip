@@ -923,7 +923,7 @@ static rad_status dX_gemm(rad_ctx* c, int dtype, int M, int d_in, int d_out, con
 
 static rad_status colsum_call(rad_ctx* c, const void* dy, int dtype, int rows, int N, const uint32_t* bits,
                               int bits_pitch, const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
-                              int beta) {
+                              int beta, int u_block_rows = 0, int64_t u_block_stride = 0) {
   int splits = rows / 64;
   if (splits < 1) splits = 1;
   if (splits > 32) splits = 32;
@@ -931,7 +931,7 @@ static rad_status colsum_call(rad_ctx* c, const void* dy, int dtype, int rows, i
   RAD_TRY(ws_get(c, WS_COLSUM, (size_t)splits * (u_n + 1) * N * 4, &part));
   HIP_TRY(c, timed(c, "colsum", [&](const char**) {
     return launch_colsum(dy, dtype, rows, N, bits, bits_pitch, u, u_ld, u_n, out_bias, out_u, beta,
-                         static_cast<float*>(part), splits, c->stream);
+                         static_cast<float*>(part), splits, c->stream, u_block_rows, u_block_stride);
   }));
   return RAD_OK;
 }
@@ -1448,16 +1448,21 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   auto g_of = [&](int t) -> float* { return t >= 2 ? m->rnn_g + (size_t)((t - 2) % Gp) * gstride : static_cast<float*>(m->dyb[1]); };
   RAD_TRY(dX_gemm(c, kF32, B, H, C, dz, nullptr, 0, W_ho, g_of(T), m->rnn_bits + (size_t)(T - 1) * B * bp, bp));
   if (T == 1) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(dW_hh), 0u, (int64_t)H * H, c->stream));
-  bool first_dw = true;
+  bool first_dw = true, first_cs = true;
   for (int t = T; t >= 1; --t) {
-    const int beta = t < T;
     if (t >= 2 && (t - 2) % G == 0) {                     // g of the whole chunk t .. t_hi is there
-      const int t_hi = std::min(T, t + G - 1);
-      RAD_TRY(dW_gemm(c, s_hh, t - 2, g_of(t), H, nullptr, 0, dW_hh, first_dw ? 0 : 1, t_hi - t + 1));
+      const int n = std::min(T, t + G - 1) - t + 1;
+      RAD_TRY(dW_gemm(c, s_hh, t - 2, g_of(t), H, nullptr, 0, dW_hh, first_dw ? 0 : 1, n));
       first_dw = false;
+      // db and dW_ih of the chunk: rows in blocks of B per step, step q weighing with x_{t+q}
+      RAD_TRY(colsum_call(c, g_of(t), kF32, n * B, H, nullptr, 0, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db,
+                          dW_ih, first_cs ? 0 : 1, B, I));
+      first_cs = false;
     }
-    RAD_TRY(colsum_call(c, g_of(t), kF32, B, H, nullptr, 0, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db,
-                        dW_ih, beta));
+    if (t == 1) {
+      RAD_TRY(colsum_call(c, g_of(1), kF32, B, H, nullptr, 0, xs, (int64_t)T * I, I, db, dW_ih, first_cs ? 0 : 1));
+      first_cs = false;
+    }
     if (t >= 2)
       RAD_TRY(dX_gemm(c, kF32, B, H, H, g_of(t), nullptr, 0, W_hh, g_of(t - 1),
                       m->rnn_bits + (size_t)(t - 2) * B * bp, bp));

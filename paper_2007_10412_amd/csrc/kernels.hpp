@@ -89,10 +89,12 @@ hipError_t launch_gemm(int dtype, int a_kind, int b_kind, int epi, const GemmArg
 hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows, int classes,
                              int dtype, void* dlogits, float* row_loss, float* loss, hipStream_t st);
 // out[i*N + n] (+)= sum_b w_i[b] * g[b,n], i = 0..n_w; w_0 = 1 (bias gradient),
-// w_i = u[b*u_ld + i-1]; g = dy masked by bits.  partial: [splits][n_w+1][N] scratch.
+// w_i = u[b*u_ld + i-1]; g = dy masked by bits.  partial: [splits][n_w+1][N] scratch.  With u_block_rows > 0 the
+// rows come in blocks of that many (time steps) and row b of block q weighs with u[b*u_ld + q*u_block_stride + i-1].
 hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint32_t* bits, int bits_pitch,
                          const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
-                         int beta, float* partial, int splits, hipStream_t st);
+                         int beta, float* partial, int splits, hipStream_t st, int u_block_rows = 0,
+                         int64_t u_block_stride = 0);
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t st);
 // Rademacher matrix of the projection scheme: R [d][kp] and its transpose Rt [kp][d] in the given dtype, +1 / -1
 // from the key stream (entry (j, s) = bit j*k + s), zero in the padding columns s >= k (both must be zeroed first)
