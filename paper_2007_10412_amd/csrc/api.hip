@@ -616,9 +616,11 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
   // tiles, each a chain of 64 K-slices): split K eight ways; one kernel then adds the partial sums and does the
   // epilogue's work (bias, input term, ReLU, bits), and the next store's sample is packed by the pack kernel
   const int tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
-  if (dtype == kF32 && tiles64 <= 64 && K >= 512 && N % 64 == 0 && ldx == K) {
-    int splits = K / 128;
-    if (splits > 8) splits = 8;
+  if (dtype == kF32 && tiles64 <= 64 && K >= 512 && (N % 64 == 0 || !relu)) {
+    int splits = K / 128, want = 256 / tiles64;            // about one workgroup per CU
+    if (want < 8) want = 8;
+    if (want > 32) want = 32;
+    if (splits > want) splits = want;
     const int ks = ((K + splits - 1) / splits + 15) / 16 * 16;
     splits = (K + ks - 1) / ks;
     if (splits > 1) {
@@ -1630,9 +1632,15 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
       return launch_splitk_reduce(static_cast<const float*>(part), a.k_splits, (int64_t)a.M * a.N,
                                   static_cast<float*>(grads[2 * l]), 0, c->stream);
     }));
-    HIP_TRY(c, timed(c, "channel_sum", [&](const char**) {
-      return launch_channel_sum(g, B, cv.co, HW, static_cast<float*>(grads[2 * l + 1]), c->stream);
-    }));
+    {
+      const int cs_splits = B < 32 ? B : 32;
+      void* cs_part = nullptr;
+      RAD_TRY(ws_get(c, WS_COLSUM, (size_t)cv.co * cs_splits * 4, &cs_part));
+      HIP_TRY(c, timed(c, "channel_sum", [&](const char**) {
+        return launch_channel_sum(g, B, cv.co, HW, static_cast<float*>(grads[2 * l + 1]), static_cast<float*>(cs_part),
+                                  cs_splits, c->stream);
+      }));
+    }
     if (l > 0) {
       // dX: the transposed convolution, exact (never sampled)
       void* wt = nullptr;

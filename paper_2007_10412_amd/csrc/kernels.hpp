@@ -150,8 +150,9 @@ hipError_t launch_path_sampling(int n, int n_levels, const int32_t* level_ptr_ho
 struct OptimArgs { float lr, l2, beta1, beta2, omb1, omb2, eps, inv_bc1, inv_bc2; };
 hipError_t launch_optim(bool adam, float* w, uint16_t* lo, const float* g, float* m, float* v, int64_t n,
                         const OptimArgs& a, hipStream_t st);
-// db[c] = sum over b, y, x of g[b,c,y,x]
-hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* db, hipStream_t st);
+// db[c] = sum over b, y, x of g[b,c,y,x]; partial: [C][splits] scratch (workgroup (c, s) adds examples s, s + splits, ...)
+hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* db, float* partial, int splits,
+                              hipStream_t st);
 // Wt[(o,u,v)][c] = W[c][KH-1-u][KW-1-v][o]: the weight operand of the transposed convolution (dX)
 hipError_t launch_flip_weights(const float* W, int Ci, int KH, int KW, int Co, float* Wt, hipStream_t st);
 // Adds to dW the entries of (row, bucket) segments beyond the first `cap`, which the MFMA kernel leaves out;

@@ -317,18 +317,28 @@ __global__ __launch_bounds__(256) void unpool_mask_kernel(const float* __restric
 
 // db[c] = sum_{b,yx} g[b,c,yx]; one workgroup per channel, fixed summation order
 __global__ __launch_bounds__(256) void channel_sum_kernel(const float* __restrict__ g, int batch, int C, int HW,
-                                                          float* __restrict__ db) {
+                                                          int splits, float* __restrict__ partial) {
+  // workgroup (channel c, split s) adds the planes of examples s, s + splits, ...; partial[c][s]
   __shared__ float s_w[4];
-  const int c = blockIdx.x;
+  const int c = blockIdx.x, sp = blockIdx.y;
   float acc = 0.f;
-  for (int b = 0; b < batch; ++b) {
+  for (int b = sp; b < batch; b += splits) {
     const float* src = g + ((size_t)b * C + c) * HW;
     for (int i = threadIdx.x; i < HW; i += 256) acc += src[i];
   }
   acc = wave_sum(acc);
   if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = acc;
   __syncthreads();
-  if (threadIdx.x == 0) db[c] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+  if (threadIdx.x == 0) partial[(size_t)c * splits + sp] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+__global__ __launch_bounds__(256) void channel_sum_final_kernel(const float* __restrict__ partial, int C, int splits,
+                                                                float* __restrict__ db) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  float v = 0.f;
+  for (int s = 0; s < splits; ++s) v += partial[(size_t)c * splits + s];      // fixed order
+  db[c] = v;
 }
 
 __global__ __launch_bounds__(256) void flip_weights_kernel(const float* __restrict__ W, int Ci, int KH, int KW, int Co,
@@ -427,8 +437,8 @@ hipError_t launch_splitk_bias(const float* partial, int splits, int M, int N, co
 }
 
 // Sum of split-K partial sums of a forward GEMM with what its fused epilogue would have done: bias, the
-// low-rank input term u V, ReLU, the (h > 0) bits.  One thread per output; a wave covers 64 consecutive columns of
-// a row (N is a multiple of 64), so a ballot gives two whole words of the bit array.
+// low-rank input term u V, ReLU, the (h > 0) bits.  One thread per output; with bits, N is a multiple of 64 and a
+// wave covers 64 consecutive columns of a row, so a ballot gives two whole words of the bit array.
 __global__ __launch_bounds__(256) void splitk_fwd_f32_kernel(const float* __restrict__ partial, int splits, int M, int N,
                                                              const float* __restrict__ bias, const float* __restrict__ u,
                                                              int64_t u_ld, int u_n, const float* __restrict__ V, int relu,
@@ -436,7 +446,7 @@ __global__ __launch_bounds__(256) void splitk_fwd_f32_kernel(const float* __rest
                                                              int bits_pitch) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t total = (int64_t)M * N;
-  if (i >= total) return;                        // total is a multiple of 64: whole waves leave together
+  if (i >= total) return;                        // with bits, total is a multiple of 64: whole waves leave together
   const int row = (int)(i / N), col = (int)(i - (int64_t)row * N);
   float h = 0.f;
   for (int s = 0; s < splits; ++s) h += partial[(size_t)s * total + i];
@@ -470,7 +480,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_masked_kernel(const float* 
 hipError_t launch_splitk_fwd_f32(const float* partial, int splits, int M, int N, const float* bias, const float* u,
                                  int64_t u_ld, int u_n, const float* V, int relu, float* y, uint32_t* bits,
                                  int bits_pitch, hipStream_t st) {
-  if (N % 64 != 0) return hipErrorInvalidValue;
+  if (bits && N % 64 != 0) return hipErrorInvalidValue;    // the bit words come from whole-wave ballots
   const int64_t total = (int64_t)M * N;
   hipLaunchKernelGGL(splitk_fwd_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, splits, M, N,
                      bias, u, u_ld, u_n, V, relu, y, bits, bits_pitch);
@@ -507,8 +517,10 @@ hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, i
   return hipGetLastError();
 }
 
-hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* db, hipStream_t st) {
-  hipLaunchKernelGGL(channel_sum_kernel, dim3(C), dim3(256), 0, st, g, batch, C, HW, db);
+hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* db, float* partial, int splits,
+                              hipStream_t st) {
+  hipLaunchKernelGGL(channel_sum_kernel, dim3(C, splits), dim3(256), 0, st, g, batch, C, HW, splits, partial);
+  hipLaunchKernelGGL(channel_sum_final_kernel, dim3((C + 255) / 256), dim3(256), 0, st, partial, C, splits, db);
   return hipGetLastError();
 }
 
