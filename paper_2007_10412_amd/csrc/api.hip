@@ -616,7 +616,7 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
   // tiles, each a chain of 64 K-slices): split K eight ways; one kernel then adds the partial sums and does the
   // epilogue's work (bias, input term, ReLU, bits), and the next store's sample is packed by the pack kernel
   const int tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
-  if (dtype == kF32 && tiles64 <= 64 && K >= 512 && (N % 64 == 0 || !relu)) {
+  if (dtype == kF32 && tiles64 <= 64 && K >= 512) {
     int splits = K / 128, want = 256 / tiles64;            // about one workgroup per CU
     if (want < 8) want = 8;
     if (want > 32) want = 32;

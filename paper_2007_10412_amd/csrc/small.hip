@@ -462,6 +462,36 @@ __global__ __launch_bounds__(256) void splitk_fwd_f32_kernel(const float* __rest
   }
 }
 
+// The same for any N: a wave per output row walks the row 64 columns at a time, so that its ballots are whole
+// words of the row's bits wherever the row ends.
+__global__ __launch_bounds__(256) void splitk_fwd_f32_rows_kernel(const float* __restrict__ partial, int splits, int M,
+                                                                  int N, const float* __restrict__ bias,
+                                                                  const float* __restrict__ u, int64_t u_ld, int u_n,
+                                                                  const float* __restrict__ V, int relu,
+                                                                  float* __restrict__ y, uint32_t* __restrict__ bits,
+                                                                  int bits_pitch) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= M) return;                          // whole waves
+  const int64_t total = (int64_t)M * N;
+  for (int c0 = 0; c0 < N; c0 += 64) {
+    const int col = c0 + lane;
+    float h = 0.f;
+    if (col < N) {
+      const int64_t i = (int64_t)row * N + col;
+      for (int s = 0; s < splits; ++s) h += partial[(size_t)s * total + i];
+      if (bias) h += bias[col];
+      for (int q = 0; q < u_n; ++q) h += u[(size_t)row * u_ld + q] * V[(size_t)q * N + col];
+      if (relu) h = h > 0.f ? h : 0.f;
+      y[i] = h;
+    }
+    if (bits) {
+      const uint64_t b = __ballot(col < N && h > 0.f);
+      if (lane == 0) bits[(size_t)row * bits_pitch + (c0 >> 5)] = (uint32_t)b;
+      if (lane == 32 && c0 + 32 < N) bits[(size_t)row * bits_pitch + (c0 >> 5) + 1] = (uint32_t)(b >> 32);
+    }
+  }
+}
+
 // Sum of split-K partial sums, zeroed where the mask bit of the output entry is clear (mask: [M][pitch] words
 // over N columns, or null)
 __global__ __launch_bounds__(256) void splitk_reduce_masked_kernel(const float* __restrict__ partial, int splits, int M,
@@ -480,7 +510,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_masked_kernel(const float* 
 hipError_t launch_splitk_fwd_f32(const float* partial, int splits, int M, int N, const float* bias, const float* u,
                                  int64_t u_ld, int u_n, const float* V, int relu, float* y, uint32_t* bits,
                                  int bits_pitch, hipStream_t st) {
-  if (bits && N % 64 != 0) return hipErrorInvalidValue;    // the bit words come from whole-wave ballots
+  if (bits && N % 64 != 0) {                               // rows that do not end on a wave boundary
+    hipLaunchKernelGGL(splitk_fwd_f32_rows_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, partial, splits, M, N,
+                       bias, u, u_ld, u_n, V, relu, y, bits, bits_pitch);
+    return hipGetLastError();
+  }
   const int64_t total = (int64_t)M * N;
   hipLaunchKernelGGL(splitk_fwd_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, splits, M, N,
                      bias, u, u_ld, u_n, V, relu, y, bits, bits_pitch);
