@@ -209,8 +209,9 @@ def main():
         for i in range(reps):
             step(10_000 + i)
         kern = {}
-        names = ["plan", "row_scan", "pack", "reindex", "sign_matrix", "scale_cast", "unpack", "fwd", "dx", "dw_sparse",
-                 "dw_dense", "dw_overflow", "softmax_ce", "colsum", "fill"]
+        names = ["plan", "row_scan", "pack", "reindex", "sign_matrix", "scale_cast", "unpack", "project_rows_fwd",
+                 "project_rows_bwd", "fwd", "dx", "dw_sparse", "dw_dense", "dw_overflow", "splitk_fwd", "splitk_bias",
+                 "splitk_reduce", "softmax_ce", "colsum", "fill"]
         for nm in names:
             n, ms = B.rad_ctx_timing_read(ctx, nm)
             if n:
