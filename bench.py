@@ -212,8 +212,11 @@ def main():
         names = ["plan", "row_scan", "pack", "reindex", "sign_matrix", "scale_cast", "unpack", "project_rows_fwd",
                  "project_rows_bwd", "fwd", "dx", "dw_sparse", "dw_dense", "dw_overflow", "splitk_fwd", "splitk_bias",
                  "splitk_reduce", "softmax_ce", "colsum", "fill"]
+        # labels are matched as substrings: the GEMM families by "_fwd_" / "_dx_", which the finishing and projection
+        # kernels (…_fwd at the end of their names) do not contain
+        pattern = {"fwd": "_fwd_", "dx": "_dx_"}
         for nm in names:
-            n, ms = B.rad_ctx_timing_read(ctx, nm)
+            n, ms = B.rad_ctx_timing_read(ctx, pattern.get(nm, nm))
             if n:
                 kern[nm] = {"launches_per_step": n / reps, "ms_per_step": ms / reps}
         B.rad_ctx_timing(ctx, "")
