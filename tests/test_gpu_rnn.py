@@ -85,3 +85,14 @@ def test_paper_rnn_widths(ctx, scheme):
     from paper_2007_10412_amd import synth
     d = synth.rnn(seed=77, batch=150, T=40, d_input=1, hidden=100, classes=10, identity=True)
     run_rnn(ctx, d, scheme, 0.1, seed=9)
+
+
+@pytest.mark.parametrize("T", [2, 10, 17])
+@pytest.mark.parametrize("scheme,p", [(1, 0.3), (3, 0.25), (0, 1.0), (2, 0.25)])
+def test_rnn_lengths_around_the_chunks_of_the_recurrent_dW(ctx, T, scheme, p):
+    """The recurrent dW, the bias gradient and the input-weight gradient are formed over chunks of eight time
+    steps (T - 1 = 1: a single short chunk; 9: one whole chunk and one step; 16: two whole chunks); the shared
+    scheme keeps the step-by-step form.  Every gradient against the oracle."""
+    from paper_2007_10412_amd import synth
+    d = synth.rnn(seed=20 + T, batch=8, T=T, d_input=2, hidden=64, classes=5, identity=False)
+    run_rnn(ctx, d, scheme, p, seed=T)
