@@ -83,7 +83,8 @@ def test_dX_does_not_depend_on_the_sample(ctx):
     assert np.array_equal(a["dX"], b["dX"])
 
 
-@pytest.mark.parametrize("Bt,D,N", [(1, 5, 3), (7, 37, 10), (150, 300, 10), (130, 260, 70), (64, 1030, 129)])
+@pytest.mark.parametrize("Bt,D,N", [(1, 5, 3), (7, 37, 10), (150, 300, 10), (130, 260, 70), (64, 1030, 129),
+                                    (70, 600, 640), (100, 520, 270)])     # the last two: split-K forward and dX
 @pytest.mark.parametrize("scheme", [1, 2, 3])
 def test_ragged_shapes_f32(ctx, Bt, D, N, scheme):
     from paper_2007_10412_amd import binding as B
