@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <utility>
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -21,6 +22,10 @@ struct rad_ctx {
   int device = 0;
   std::string err;
   int key_shift = 0;
+  // side stream of the recurrent model's backward pass (created on first use): the gradients formed per chunk of
+  // time steps run there, beside the chain of dX GEMMs
+  hipStream_t side = nullptr;
+  hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_done[2] = {nullptr, nullptr}, ev_join = nullptr;
   // timing
   bool timing = false;
   std::string filter;
@@ -119,6 +124,8 @@ extern "C" rad_status rad_ctx_destroy(rad_ctx* c) {
   if (!c) return RAD_ERR_NULL;
   (void)hipStreamSynchronize(c->stream);
   for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
+  for (hipEvent_t e : {c->ev_ready[0], c->ev_ready[1], c->ev_done[0], c->ev_done[1], c->ev_join}) if (e) (void)hipEventDestroy(e);
   for (auto& e : c->pool) (void)hipEventDestroy(e);
   for (int i = 0; i < 10; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
   if (c->loss_dev) (void)hipFree(c->loss_dev);
@@ -1146,7 +1153,8 @@ struct rad_model {
   // RNN
   int64_t T = 0, d_input = 0, hidden = 0, classes = 0;
   uint32_t* rnn_bits = nullptr;         // [T][batch][hidden/32]
-  float* rnn_g = nullptr;               // [kRnnChunk][batch][hidden]: g of the time steps whose dW is formed together
+  float* rnn_g = nullptr;               // [2][kRnnChunk][batch][hidden]: g of the time steps whose dW is formed together,
+                                        // two chunks: one being read by the side stream, one being filled
   uint32_t* bitmap_ws = nullptr;        // keep bitmaps of every step (transient within a step)
   // CNN
   struct Conv { int ci, co, h, w, pool; uint32_t* arg; };
@@ -1373,7 +1381,7 @@ extern "C" rad_status rad_model_create_rnn(rad_ctx* c, int64_t batch, int64_t T,
   for (void** p2 : {&m->act[0], &m->act[1], &m->dyb[0], &m->dyb[1]}) ok = ok && hipMalloc(p2, hb) == hipSuccess;
   ok = ok && hipMalloc(&m->logits, (size_t)batch * classes * 4) == hipSuccess;
   ok = ok && hipMalloc((void**)&m->rnn_bits, (size_t)T * batch * ((hidden + 31) / 32) * 4) == hipSuccess;
-  ok = ok && hipMalloc((void**)&m->rnn_g, (size_t)kRnnChunk * hb) == hipSuccess;
+  ok = ok && hipMalloc((void**)&m->rnn_g, (size_t)2 * kRnnChunk * hb) == hipSuccess;
   const size_t bmw = m->stores[0]->bitmap_words() + m->stores[1]->bitmap_words();
   if (bmw) ok = ok && hipMalloc((void**)&m->bitmap_ws, bmw * 4) == hipSuccess;
   if (!ok) { rad_model_destroy(m); return fail(c, RAD_ERR_DEVICE, "model allocation failed"); }
@@ -1445,30 +1453,69 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   const bool per_row = s_hh->scheme == RAD_EXACT || s_hh->scheme == RAD_BERNOULLI || s_hh->scheme == RAD_FIXEDK_PER_EXAMPLE ||
                        s_hh->scheme == RAD_REPLACE_PER_EXAMPLE;
   const int G = (per_row && !s_hh->index_free) ? kRnnChunk : 1;
-  const int Gp = G > 1 ? G : 2;                          // row blocks in use
+  const int Gp = G > 1 ? 2 * G : 2;                      // row blocks in use: two chunks, or two single steps
   const size_t gstride = (size_t)B * H;
   auto g_of = [&](int t) -> float* { return t >= 2 ? m->rnn_g + (size_t)((t - 2) % Gp) * gstride : static_cast<float*>(m->dyb[1]); };
+  // With chunks, their gradients (dW_hh, db, dW_ih: nothing downstream waits for them) are enqueued on a side
+  // stream while the main stream goes on with the chain of dX GEMMs into the other chunk's rows; the main stream
+  // waits before it writes into a chunk whose last reader may still be running, and at the end.
+  bool side = G > 1 && !(c->timing && c->filter.empty());
+  if (side && !c->side) {
+    bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess;
+    for (hipEvent_t* e : {&c->ev_ready[0], &c->ev_ready[1], &c->ev_done[0], &c->ev_done[1], &c->ev_join})
+      ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
+    if (!ok) return fail(c, RAD_ERR_DEVICE, "side stream");
+  }
+  bool done_pending[2] = {false, false};
   RAD_TRY(dX_gemm(c, kF32, B, H, C, dz, nullptr, 0, W_ho, g_of(T), m->rnn_bits + (size_t)(T - 1) * B * bp, bp));
   if (T == 1) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(dW_hh), 0u, (int64_t)H * H, c->stream));
   bool first_dw = true, first_cs = true;
-  for (int t = T; t >= 1; --t) {
+  rad_status rs = RAD_OK;
+  for (int t = T; t >= 1 && rs == RAD_OK; --t) {
     if (t >= 2 && (t - 2) % G == 0) {                     // g of the whole chunk t .. t_hi is there
       const int n = std::min(T, t + G - 1) - t + 1;
-      RAD_TRY(dW_gemm(c, s_hh, t - 2, g_of(t), H, nullptr, 0, dW_hh, first_dw ? 0 : 1, n));
+      const int half = ((t - 2) / G) & 1;
+      if (side) {
+        HIP_TRY(c, hipEventRecord(c->ev_ready[half], c->stream));
+        HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_ready[half], 0));
+        std::swap(c->stream, c->side);
+      }
+      rs = dW_gemm(c, s_hh, t - 2, g_of(t), H, nullptr, 0, dW_hh, first_dw ? 0 : 1, n);
       first_dw = false;
       // db and dW_ih of the chunk: rows in blocks of B per step, step q weighing with x_{t+q}
-      RAD_TRY(colsum_call(c, g_of(t), kF32, n * B, H, nullptr, 0, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db,
-                          dW_ih, first_cs ? 0 : 1, B, I));
+      if (rs == RAD_OK)
+        rs = colsum_call(c, g_of(t), kF32, n * B, H, nullptr, 0, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, db,
+                         dW_ih, first_cs ? 0 : 1, B, I);
       first_cs = false;
+      if (side) {
+        std::swap(c->stream, c->side);
+        if (rs == RAD_OK) { HIP_TRY(c, hipEventRecord(c->ev_done[half], c->side)); done_pending[half] = true; }
+        // the dX below starts the other chunk's rows: their last reader must be through
+        if (rs == RAD_OK && done_pending[half ^ 1]) {
+          HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_done[half ^ 1], 0));
+          done_pending[half ^ 1] = false;
+        }
+      }
+      if (rs != RAD_OK) break;
     }
     if (t == 1) {
-      RAD_TRY(colsum_call(c, g_of(1), kF32, B, H, nullptr, 0, xs, (int64_t)T * I, I, db, dW_ih, first_cs ? 0 : 1));
+      if (side) {                                         // db and dW_ih accumulate in stream order: join first
+        HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
+        HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
+        side = false;
+      }
+      rs = colsum_call(c, g_of(1), kF32, B, H, nullptr, 0, xs, (int64_t)T * I, I, db, dW_ih, first_cs ? 0 : 1);
       first_cs = false;
     }
-    if (t >= 2)
-      RAD_TRY(dX_gemm(c, kF32, B, H, H, g_of(t), nullptr, 0, W_hh, g_of(t - 1),
-                      m->rnn_bits + (size_t)(t - 2) * B * bp, bp));
+    if (t >= 2 && rs == RAD_OK)
+      rs = dX_gemm(c, kF32, B, H, H, g_of(t), nullptr, 0, W_hh, g_of(t - 1),
+                   m->rnn_bits + (size_t)(t - 2) * B * bp, bp);
   }
+  if (c->side && G > 1) {                                 // whatever happened, the main stream ends behind the side stream
+    (void)hipEventRecord(c->ev_join, c->side);
+    (void)hipStreamWaitEvent(c->stream, c->ev_join, 0);
+  }
+  RAD_TRY(rs);
   return step_finish(c, m, loss_host);
 }
 
