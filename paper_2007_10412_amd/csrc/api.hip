@@ -1421,20 +1421,33 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   rad_sampling s2 = *sm; s2.stream_id = sm->stream_id + 1; s2.step = 0;
   RAD_TRY(store_plan(c, s_ho, &s2, m->bitmap_ws ? m->bitmap_ws + s_hh->bitmap_words() : nullptr, false));
 
-  // forward: h_t = ReLU(x_t W_ih + h_{t-1} W_hh + b); h_0 = 0 so step 1 has no contraction
+  // forward: h_t = ReLU(x_t W_ih + h_{t-1} W_hh + b); h_0 = 0 so step 1 has no contraction.
+  // Stores whose rows are planned one by one take the samples of h_1 .. h_{T-1} eight steps at a time: the steps'
+  // outputs go to a ring of eight row blocks (the chunk buffer of the backward pass, idle now) and one pack launch
+  // covers their consecutive store slots.
+  const bool chunk_pack = T > 1 && (s_hh->scheme == RAD_BERNOULLI || s_hh->scheme == RAD_FIXEDK_PER_EXAMPLE ||
+                                    s_hh->scheme == RAD_REPLACE_PER_EXAMPLE);
+  auto ring = [&](int t) -> float* { return m->rnn_g + (size_t)((t - 1) % kRnnChunk) * B * H; };     // h_t, t < T
   for (int t = 1; t <= T; ++t) {
     StoreView nv; const StoreView* next = nullptr;
     rad_store* target = t < T ? s_hh : s_ho;
     void* y = m->act[t & 1];
     if (target->scheme == RAD_EXACT) {
       y = static_cast<char*>(target->values) + (t < T ? (size_t)(t - 1) * B * H * 4 : 0);
+    } else if (t < T && chunk_pack) {
+      y = ring(t);
     } else { nv = store_view(target, t < T ? t - 1 : 0); next = &nv; }
     const void* hin = t == 1 ? m->act[0] : (s_hh->scheme == RAD_EXACT
                           ? static_cast<const void*>(static_cast<char*>(s_hh->values) + (size_t)(t - 2) * B * H * 4)
-                          : m->act[(t - 1) & 1]);
+                          : chunk_pack ? static_cast<const void*>(ring(t - 1)) : m->act[(t - 1) & 1]);
     RAD_TRY(forward_gemm(c, kF32, B, H, t == 1 ? 0 : H, hin, H, W_hh, b, 1, y, m->rnn_bits + (size_t)(t - 1) * B * bp,
                          bp, next, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, W_ih));
-    if (t == T && target->scheme == RAD_EXACT) { /* h_T already sits in the output layer's store */ }
+    if (t < T && chunk_pack && (t % kRnnChunk == 0 || t == T - 1)) {
+      const int t0 = (t - 1) / kRnnChunk * kRnnChunk + 1;          // first step of the chunk; its output is ring block 0
+      StoreView v = store_view(s_hh, t0 - 1);
+      v.rows = (t - t0 + 1) * B;
+      HIP_TRY(c, timed(c, "pack_f32", [&](const char**) { return launch_pack(ring(t0), kF32, v, c->stream); }));
+    }
   }
   const void* hT = s_ho->scheme == RAD_EXACT ? s_ho->values : m->act[T & 1];
   RAD_TRY(forward_gemm(c, kF32, B, C, H, hT, H, W_ho, b_o, 0, m->logits, nullptr, 0, nullptr, nullptr, 0, 0, nullptr));
