@@ -46,9 +46,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32"],
+    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32", "other"],
                     help="pde32: the reaction-diffusion study instead of a train step (a step = one gradient of each "
-                         "of 256 problems)")
+                         "of 256 problems); other: only the small configurations 1, 2, 3 and 5 (ms per train step)")
     ap.add_argument("--scheme", default="per_example", choices=sorted(SCHEMES))
     ap.add_argument("--p", type=float, default=0.1)
     ap.add_argument("--index-free", action="store_true",
@@ -63,6 +63,12 @@ def main():
     import torch
     from paper_2007_10412_amd import binding as B, synth
 
+    if args.workload == "other":
+        ctx = B.rad_ctx_create()
+        print(json.dumps({"metric": "ms_per_train_step", "data": "synthetic", "n_gpus": 1,
+                          "other_configs": other_configs(B, ctx, torch, synth)}))
+        B.rad_ctx_destroy(ctx)
+        return
     if args.workload == "pde32":
         ctx = B.rad_ctx_create()
         out = pde_study(B, ctx, torch, steps=args.steps, warmup=args.warmup, p=args.p if args.p < 1 else 0.01)
