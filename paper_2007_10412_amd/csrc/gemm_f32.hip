@@ -29,9 +29,9 @@ hipError_t launch_gemm_f32(int a_kind, int b_kind, int epi, const GemmArgs& g, h
   }
   else if (a_kind == kOpK && b_kind == kOpMN && epi == kEpiSplitK) {
     // few output tiles and a long contraction (one step of the recurrent model): partial sums per K range
-    nm = "gemm_f32_fwd_splitk_64"; e = run_gemm<F32Tag, kOpK, kOpMN, kEpiSplitK, 64, 64, 16, 0, false, false>(g, st);
+    nm = "gemm_f32_fwd_splitk_64"; e = run_gemm<F32Tag, kOpK, kOpMN, kEpiSplitK, 64, 64, 32, 0, false, false>(g, st);
   } else if (a_kind == kOpK && b_kind == kOpK && epi == kEpiSplitK) {
-    nm = "gemm_f32_dx_splitk_64"; e = run_gemm<F32Tag, kOpK, kOpK, kEpiSplitK, 64, 64, 16, 0, true, false>(g, st);
+    nm = "gemm_f32_dx_splitk_64"; e = run_gemm<F32Tag, kOpK, kOpK, kEpiSplitK, 64, 64, 32, 0, true, false>(g, st);
   }
   else if (a_kind == kOpIm2colRows && b_kind == kOpMN && epi == kEpiConv) {
     // convolution forward / dX: positions x channels, channels fit one 64-wide tile column
