@@ -568,13 +568,14 @@ def rnn_train_step(x, labels, W_ih, W_hh, b, W_ho, b_o, scheme, p, seed,
     B, T, _ = x.shape
     H = W_hh.shape[0]
     h_prev = np.zeros((B, H), dtype=np.float32)
-    xts, bits_t = [None] * (T + 1), [None] * (T + 1)
+    xts, bits_t, stores_t = [None] * (T + 1), [None] * (T + 1), [None] * (T + 1)
     W_ih64 = np.asarray(W_ih, dtype=np.float64)
     W_hh64 = np.asarray(W_hh, dtype=np.float64)
     b64 = np.asarray(b, dtype=np.float64)
     for t in range(1, T + 1):
         if t > 1:
-            xts[t] = sample_pack(h_prev, scheme, p, seed, stream_base, t)[3]
+            sp = sample_pack(h_prev, scheme, p, seed, stream_base, t)
+            stores_t[t], xts[t] = sp[:3], sp[3]
         pre = (x[:, t - 1, :].astype(np.float64) @ W_ih64
                + h_prev.astype(np.float64) @ W_hh64 + b64[None, :])
         bits_t[t] = pre > 0.0
@@ -598,7 +599,7 @@ def rnn_train_step(x, labels, W_ih, W_hh, b, W_ho, b_o, scheme, p, seed,
         db += g.sum(axis=0)
         dh = (g @ W_hh64.T).astype(np.float32)
     return dict(loss=loss, dW_hh=dW_hh, dW_ih=dW_ih, db=db, dW_ho=dW_ho,
-                db_o=db_o, h_T=h_prev, logits=z)
+                db_o=db_o, h_T=h_prev, logits=z, stores=stores_t, store_o=st_o[:3])
 
 
 # ----------------------------------------------------------------------------

@@ -64,7 +64,9 @@ static rad_status hip_fail(rad_ctx* c, hipError_t e, const char* what) {
 static rad_status ws_get(rad_ctx* c, int which, size_t bytes, void** out) {
   if (bytes > c->ws_bytes[which]) {
     if (c->ws[which]) {
+      // either stream may still read the old buffer (the recurrent model's backward pass swaps the two)
       HIP_TRY(c, hipStreamSynchronize(c->stream));
+      if (c->side) HIP_TRY(c, hipStreamSynchronize(c->side));
       HIP_TRY(c, hipFree(c->ws[which]));
       c->ws[which] = nullptr; c->ws_bytes[which] = 0;
     }
@@ -628,7 +630,7 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
     if (want < 8) want = 8;
     if (want > 32) want = 32;
     if (splits > want) splits = want;
-    const int ks = ((K + splits - 1) / splits + 15) / 16 * 16;
+    const int ks = ((K + splits - 1) / splits + 31) / 32 * 32;   // whole K slices of the split kernels (32 deep)
     splits = (K + ks - 1) / ks;
     if (splits > 1) {
       void* part = nullptr;
@@ -652,18 +654,35 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
 }
 
 // A k x N output gives few tiles when k is a small fraction of the layer width: split the K dimension (the
-// batch) over several workgroups per tile, which add their partial sums atomically into an output that the
-// caller has zeroed or is accumulating into (bf16 ring kernels only).
-static void split_k_for_few_tiles(GemmArgs* g) {
-  if (g->K < 512) return;
+// batch) over several workgroups per tile; each stores its partial sums to an array of its own in a context
+// workspace and launch_splitk_reduce_rows adds them in split order, so the result does not vary from run to run
+// (bf16 ring kernels only).  The caller runs the GEMM on g and, when g->k_splits > 1, the reduction into the
+// real output (*out, row_map, beta as recorded here).
+struct SplitPlan { float* out = nullptr; int64_t ld = 0; const uint16_t* row_map = nullptr; int beta = 0; };
+static rad_status split_k_for_few_tiles(rad_ctx* c, GemmArgs* g, SplitPlan* sp) {
+  if (g->K < 512) return RAD_OK;
   const int tiles = ((g->M + 127) / 128) * ((g->N + 127) / 128);
-  if (tiles >= 192) return;
+  if (tiles >= 192) return RAD_OK;
   int splits = (512 + tiles - 1) / tiles;
   if (splits > 8) splits = 8;
   int ks = ((g->K + splits - 1) / splits + 31) / 32 * 32;
   if (ks < 256) ks = 256;
   splits = (g->K + ks - 1) / ks;
-  if (splits > 1) { g->k_split = ks; g->k_splits = splits; }
+  if (splits <= 1) return RAD_OK;
+  void* part = nullptr;
+  RAD_TRY(ws_get(c, WS_SPLITK, (size_t)splits * g->M * g->N * 4, &part));
+  sp->out = static_cast<float*>(g->C); sp->ld = g->ldc; sp->row_map = g->row_map; sp->beta = g->beta;
+  g->k_split = ks; g->k_splits = splits; g->split_stride = (int64_t)g->M * g->N;
+  g->C = part; g->ldc = g->N; g->row_map = nullptr; g->beta = 0;
+  return RAD_OK;
+}
+static rad_status split_k_finish(rad_ctx* c, const GemmArgs& g, const SplitPlan& sp) {
+  if (g.k_splits <= 1) return RAD_OK;
+  HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
+    return launch_splitk_reduce_rows(static_cast<const float*>(g.C), g.k_splits, g.split_stride, g.M, g.N, sp.row_map,
+                                     sp.out, sp.ld, sp.beta, c->stream);
+  }));
+  return RAD_OK;
 }
 
 // ---- projection scheme (Section 3.2, P = R R^T / k; Appendix "Random projections for RAD")
@@ -737,14 +756,10 @@ static rad_status project_dW(rad_ctx* c, const rad_store* s, const void* dy, int
   g.A = s->values; g.lda = s->k_pitch;
   g.B = dy; g.ldb = N; g.b_mask = bits; g.b_mask_pitch = bits_pitch;
   g.C = T; g.ldc = N; g.beta = 0; g.c_dtype = kF32;
-  if (s->dtype == kBF16) split_k_for_few_tiles(&g);
-  if (g.k_splits > 1) {                    // partial sums are added atomically: start from zero
-    g.beta = 1;
-    HIP_TRY(c, timed(c, "fill", [&](const char**) {
-      return launch_fill_u32(static_cast<uint32_t*>(T), 0u, (int64_t)s->k_pitch * N, c->stream);
-    }));
-  }
+  SplitPlan sp;
+  if (s->dtype == kBF16) RAD_TRY(split_k_for_few_tiles(c, &g, &sp));
   RAD_TRY(run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g));
+  RAD_TRY(split_k_finish(c, g, sp));
   HIP_TRY(c, timed(c, "scale_cast", [&](const char**) {
     return launch_scale_cast(static_cast<const float*>(T), Tb, s->dtype, (int64_t)s->k_pitch * N, s->scale, c->stream);
   }));
@@ -832,8 +847,10 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     g.A = static_cast<const char*>(s->values) + (size_t)slot * s->rows * s->k_pitch * s->elem(); g.lda = s->k_pitch;
     g.row_map = s->indices + (size_t)slot * s->k;
     g.beta = 1;
-    if (s->dtype == kBF16) split_k_for_few_tiles(&g);
-    return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
+    SplitPlan sp;
+    if (s->dtype == kBF16) RAD_TRY(split_k_for_few_tiles(c, &g, &sp));
+    RAD_TRY(run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g));
+    return split_k_finish(c, g, sp);
   }
   g.M = s->cols;
   RAD_TRY(backward_view(c, s, slot, &g.sa));
@@ -910,7 +927,7 @@ static rad_status dX_gemm(rad_ctx* c, int dtype, int M, int d_in, int d_out, con
   if (dtype == kF32 && tiles64 <= 64 && d_out >= 512) {
     int splits = d_out / 128;
     if (splits > 8) splits = 8;
-    const int ks = ((d_out + splits - 1) / splits + 15) / 16 * 16;
+    const int ks = ((d_out + splits - 1) / splits + 31) / 32 * 32;   // whole K slices of the split kernels (32 deep)
     splits = (d_out + ks - 1) / ks;
     if (splits > 1) {
       void* part = nullptr;
@@ -1484,13 +1501,18 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   if (T == 1) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(dW_hh), 0u, (int64_t)H * H, c->stream));
   bool first_dw = true, first_cs = true;
   rad_status rs = RAD_OK;
+  // a failing call inside the loop records its status and leaves through the join below, never past it
+  auto ok = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && rs == RAD_OK) rs = hip_fail(c, e, what);
+    return rs == RAD_OK;
+  };
   for (int t = T; t >= 1 && rs == RAD_OK; --t) {
     if (t >= 2 && (t - 2) % G == 0) {                     // g of the whole chunk t .. t_hi is there
       const int n = std::min(T, t + G - 1) - t + 1;
       const int half = ((t - 2) / G) & 1;
       if (side) {
-        HIP_TRY(c, hipEventRecord(c->ev_ready[half], c->stream));
-        HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_ready[half], 0));
+        if (!ok(hipEventRecord(c->ev_ready[half], c->stream), "event record")) break;
+        if (!ok(hipStreamWaitEvent(c->side, c->ev_ready[half], 0), "stream wait")) break;
         std::swap(c->stream, c->side);
       }
       rs = dW_gemm(c, s_hh, t - 2, g_of(t), H, nullptr, 0, dW_hh, first_dw ? 0 : 1, n);
@@ -1502,19 +1524,18 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
       first_cs = false;
       if (side) {
         std::swap(c->stream, c->side);
-        if (rs == RAD_OK) { HIP_TRY(c, hipEventRecord(c->ev_done[half], c->side)); done_pending[half] = true; }
+        if (rs == RAD_OK && ok(hipEventRecord(c->ev_done[half], c->side), "event record")) done_pending[half] = true;
         // the dX below starts the other chunk's rows: their last reader must be through
         if (rs == RAD_OK && done_pending[half ^ 1]) {
-          HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_done[half ^ 1], 0));
-          done_pending[half ^ 1] = false;
+          if (ok(hipStreamWaitEvent(c->stream, c->ev_done[half ^ 1], 0), "stream wait")) done_pending[half ^ 1] = false;
         }
       }
       if (rs != RAD_OK) break;
     }
     if (t == 1) {
       if (side) {                                         // db and dW_ih accumulate in stream order: join first
-        HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
-        HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
+        if (!ok(hipEventRecord(c->ev_join, c->side), "event record")) break;
+        if (!ok(hipStreamWaitEvent(c->stream, c->ev_join, 0), "stream wait")) break;
         side = false;
       }
       rs = colsum_call(c, g_of(1), kF32, B, H, nullptr, 0, xs, (int64_t)T * I, I, db, dW_ih, first_cs ? 0 : 1);

@@ -433,9 +433,9 @@ __device__ __forceinline__ int acc_row(int i, int lane) { return (i >> 2) * 8 + 
 // Plain store epilogue.  Everything that varies per call is a template flag so that each copy is straight
 // code over the 16*TM*TN accumulator registers (runtime branches per element made the register allocator
 // spill the accumulators): EDGE guards ragged tiles, MASK zeroes outputs whose ReLU bit is 0, BETA adds to
-// what is there, MAP sends tile row r to output row row_map[r], ATOMIC adds with fp32 atomics (split K:
-// several workgroups hold partial sums of one tile; the order of the additions then varies run to run).
-template <int TM, int TN, typename OutT, bool EDGE, bool MASK, bool BETA, bool MAP, bool ATOMIC = false>
+// what is there, MAP sends tile row r to output row row_map[r].  (Split-K partial sums never meet here: every
+// split stores to an array of its own and a reduction kernel adds them in a fixed order.)
+template <int TM, int TN, typename OutT, bool EDGE, bool MASK, bool BETA, bool MAP>
 __device__ __forceinline__ void epilogue_store(const GemmArgs& g, floatx16 (&acc)[TM][TN], int m0, int n0,
                                                int wm0, int wn0) {
   const int lane = threadIdx.x & 63;
@@ -454,12 +454,8 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& g, floatx16 (&acc
           OutT* dst = C + (size_t)orow * g.ldc + col;
           float v = acc[i][j][e];
           if (MASK && !((g.c_mask[(size_t)orow * g.c_mask_pitch + (col >> 5)] >> (col & 31)) & 1u)) v = 0.f;
-          if constexpr (ATOMIC) {
-            atomicAdd(reinterpret_cast<float*>(dst), v);
-          } else {
-            if (BETA) v += get_elem(dst);
-            put_elem(dst, v);
-          }
+          if (BETA) v += get_elem(dst);
+          put_elem(dst, v);
         }
       }
     }
@@ -476,10 +472,7 @@ __device__ __forceinline__ void epilogue_store_dispatch(const GemmArgs& g, float
     if (g.beta) epilogue_store<TM, TN, float, EDGE, false, true, false>(g, acc, m0, n0, wm0, wn0);
     else epilogue_store<TM, TN, float, EDGE, false, false, false>(g, acc, m0, n0, wm0, wn0);
   } else {                                // dW from a dense or compact store: row map for the shared scheme
-    if (g.k_splits > 1) {
-      if (g.row_map) epilogue_store<TM, TN, float, EDGE, false, true, true, true>(g, acc, m0, n0, wm0, wn0);
-      else epilogue_store<TM, TN, float, EDGE, false, true, false, true>(g, acc, m0, n0, wm0, wn0);
-    } else if (g.row_map) epilogue_store<TM, TN, float, EDGE, false, true, true>(g, acc, m0, n0, wm0, wn0);
+    if (g.row_map) epilogue_store<TM, TN, float, EDGE, false, true, true>(g, acc, m0, n0, wm0, wn0);
     else if (g.beta) epilogue_store<TM, TN, float, EDGE, false, true, false>(g, acc, m0, n0, wm0, wn0);
     else epilogue_store<TM, TN, float, EDGE, false, false, false>(g, acc, m0, n0, wm0, wn0);
   }

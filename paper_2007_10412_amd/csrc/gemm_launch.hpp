@@ -42,6 +42,7 @@ template <class DT, int AK, int BM, int BN, int BK>
 bool gemm_is_full(const GemmArgs& g) {
   const int vec = sizeof(typename ElemOf<DT>::type) == 2 ? 8 : 4;
   bool full = g.M % BM == 0 && g.N % BN == 0 && g.K % BK == 0 && g.K > 0;
+  if (g.k_splits > 1) full = full && g.k_split % BK == 0;       // every split's range is whole K slices
   if (AK != kOpSparse) full = full && g.lda % vec == 0 && (reinterpret_cast<uintptr_t>(g.A) & 15) == 0;
   return full && g.ldb % vec == 0 && (reinterpret_cast<uintptr_t>(g.B) & 15) == 0;
 }

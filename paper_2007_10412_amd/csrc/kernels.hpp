@@ -112,6 +112,10 @@ hipError_t launch_project_rows_bwd(const void* z, int dtype, int rows, int d, in
 hipError_t launch_scale_cast(const float* in, void* out, int dtype, int64_t n, float scale, hipStream_t st);
 // out[i] (+)= sum over `splits` partial arrays of n elements
 hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st);
+// out[row_map[r] * ld + n] (+)= sum over `splits` arrays (stride elements apart) of partial[r * N + n], r < rows,
+// added in split order; row_map may be null (row r)
+hipError_t launch_splitk_reduce_rows(const float* partial, int splits, int64_t stride, int rows, int N,
+                                     const uint16_t* row_map, float* out, int64_t ld, int beta, hipStream_t st);
 // fp32 forward GEMM finished from split-K partial sums [splits][M][N]: bias, low-rank term u V, ReLU, (h > 0) bits
 // (N a multiple of 64); and a dX finished from partial sums with the output mask of the layer below
 hipError_t launch_splitk_fwd_f32(const float* partial, int splits, int M, int N, const float* bias, const float* u,

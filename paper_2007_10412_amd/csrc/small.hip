@@ -225,6 +225,35 @@ __global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float4* __res
   if (beta) { const float4 o = out[i]; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
   out[i] = v;
 }
+// Sum of the splits of a compact dW (shared index set): partial [splits][rows][N] in a fixed order, tile row r
+// goes to output row row_map[r] (or r); V = float4 when N and ld are multiples of 4, else float
+template <typename V>
+__global__ __launch_bounds__(256) void splitk_reduce_rows_kernel(const V* __restrict__ partial, int splits, int64_t stride,
+                                                                 int rows, int NV, const uint16_t* __restrict__ row_map,
+                                                                 V* __restrict__ out, int64_t ldv, int beta) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)rows * NV) return;
+  const int r = (int)(i / NV), n = (int)(i - (int64_t)r * NV);
+  float acc[sizeof(V) / 4];
+  const V first = partial[i];
+#pragma unroll
+  for (int e = 0; e < (int)(sizeof(V) / 4); ++e) acc[e] = reinterpret_cast<const float*>(&first)[e];
+  for (int s = 1; s < splits; ++s) {
+    const V t = partial[(size_t)s * stride + i];
+#pragma unroll
+    for (int e = 0; e < (int)(sizeof(V) / 4); ++e) acc[e] += reinterpret_cast<const float*>(&t)[e];
+  }
+  V* dst = out + (size_t)(row_map ? (int)row_map[r] : r) * ldv + n;
+  if (beta) {
+    const V o = *dst;
+#pragma unroll
+    for (int e = 0; e < (int)(sizeof(V) / 4); ++e) acc[e] += reinterpret_cast<const float*>(&o)[e];
+  }
+  V res;
+#pragma unroll
+  for (int e = 0; e < (int)(sizeof(V) / 4); ++e) reinterpret_cast<float*>(&res)[e] = acc[e];
+  *dst = res;
+}
 // Sum of the splits of a forward GEMM, plus bias, into the layer output (no activation): partial [splits][M][N]
 template <typename T>
 __global__ __launch_bounds__(256) void splitk_bias_kernel(const float* __restrict__ partial, int splits, int M, int N,
@@ -422,6 +451,23 @@ hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, flo
   } else {
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, partial, splits, n,
                        out, beta);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce_rows(const float* partial, int splits, int64_t stride, int rows, int N,
+                                     const uint16_t* row_map, float* out, int64_t ld, int beta, hipStream_t st) {
+  const bool vec = N % 4 == 0 && ld % 4 == 0 && stride % 4 == 0 &&
+                   ((reinterpret_cast<uintptr_t>(partial) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+  if (vec) {
+    const int64_t total = (int64_t)rows * (N / 4);
+    hipLaunchKernelGGL(splitk_reduce_rows_kernel<float4>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<const float4*>(partial), splits, stride / 4, rows, N / 4, row_map,
+                       reinterpret_cast<float4*>(out), ld / 4, beta);
+  } else {
+    const int64_t total = (int64_t)rows * N;
+    hipLaunchKernelGGL(splitk_reduce_rows_kernel<float>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial,
+                       splits, stride, rows, N, row_map, out, ld, beta);
   }
   return hipGetLastError();
 }

@@ -24,8 +24,10 @@ def test_config3_full(ctx):
     print("config 3: %d ReLU-bit flips, %d pool swaps taken from the GPU" % (flips, swaps))
 
 
-@pytest.mark.parametrize("scheme,p", [(3, 0.1), (2, 0.02)])
+@pytest.mark.parametrize("scheme", [3, 2])
+@pytest.mark.parametrize("p", [0.5, 0.1, 0.02])
 def test_config4_full(ctx, scheme, p):
+    """All six fraction x scheme variants of the wide bf16 MLP at full size."""
     from paper_2007_10412_amd import binding as B, synth
     from tests.test_gpu_mlp import run_mlp
     dims = (4096, 4096, 4096, 1000)

@@ -17,7 +17,8 @@ def ctx():
 
 def run_mlp(ctx, data, dims, scheme, p, seed, dtype, has_bias):
     from paper_2007_10412_amd import binding as B
-    from tests.gpu_util import dev, host, empty, unpack_bits, rel_err, assert_bits_match, TOL
+    from tests.gpu_util import (dev, host, empty, unpack_bits, rel_err, assert_bits_match, assert_grad_close, TOL,
+                                U_F32, U_BF16)
     Bt = data["x"].shape[0]
     L = len(dims) - 1
     print("mlp B=%d dims=%s scheme=%d p=%g dtype=%d" % (Bt, dims, scheme, p, dtype), flush=True)
@@ -48,22 +49,25 @@ def run_mlp(ctx, data, dims, scheme, p, seed, dtype, has_bias):
                 h = np.asarray(ref["acts"][l], np.float64) @ np.asarray(data["Ws"][l], np.float64)
                 if bs is not None:
                     h = h + bs[l][None, :]
-                if dtype == B.RAD_F32:
-                    flips += assert_bits_match(hb, h, "layer %d" % l)
-                else:
-                    flips += int((hb != ref["bits"][l]).sum())
+                # fp32: a flip needs |h| within accumulation rounding of zero.  bf16: the layer input is the
+                # rounded output of the layer below, which the two sides may round to neighbouring bf16 values, so
+                # h differs by a few 2^-9 |a W| terms: flips stay within 2e-3 rms(h) of zero, and below 1 % of entries
+                flips += assert_bits_match(hb, h, "layer %d" % l, near=1e-5 if dtype == B.RAD_F32 else 2e-3)
                 gbits.append(hb)
         assert abs(loss - ref["loss"]) < (1e-5 if dtype == B.RAD_F32 else 2e-2) * max(1.0, abs(ref["loss"]))
         if flips:   # rerun the oracle backward with the GPU's ReLU bits
             ref = R.mlp_train_step(data["x"], data["labels"], data["Ws"], bs, scheme, p, seed, stream_base=10,
                                    dtype=dtype, bits_override=gbits)
         per = 2 if has_bias else 1
+        # a whole step: rounded intermediates (layer outputs, dX) feed every gradient, so the element-wise bound
+        # takes the unit roundoff of the storage type
+        u, cc = (U_F32, 32.0) if dtype == B.RAD_F32 else (U_BF16, 0.25)     # observed at most 4e-3 of max|dW| at full size
+        ratios = []
         for l in range(L):
-            e = rel_err(host(grads[l * per]), ref["dW"][l])
-            assert e < tol, ("dW", l, e)
+            ratios.append(assert_grad_close(host(grads[l * per]), ref["dW"][l], tol, Bt, "dW %d" % l, acc_u=u, c=cc)[1])
             if has_bias:
-                e = rel_err(host(grads[l * per + 1]), ref["db"][l])
-                assert e < tol, ("db", l, e)
+                assert_grad_close(host(grads[l * per + 1]), ref["db"][l], tol, Bt, "db %d" % l, acc_u=u, c=cc)
+        print("  flips %d; dW max element error / max|want|: %s" % (flips, " ".join("%.1e" % r for r in ratios)), flush=True)
         return dict(loss=loss, grads=[host(g) for g in grads], flips=flips)
     finally:
         B.rad_model_destroy(m)
