@@ -188,6 +188,27 @@ rad_status rad_store_import_bits(rad_ctx* ctx, rad_store* store, const uint32_t*
 rad_status rad_sample_pack(rad_ctx* ctx, const rad_sampling* sampling, const void* x,
                            rad_store* store, int32_t step_slot);
 
+/* rad_sample_pack for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * rad_sample_pack keeps its transient keep bitmap (1 bit per element of x) in
+ * a context workspace that it allocates on first use and when a larger store
+ * comes along; this variant keeps it in a static device array of
+ * RAD_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on from
+ * load until the process ends, and calls no hipMalloc, hipFree or other
+ * allocating routine.  Same kernels, identical results.  `store` (created
+ * beforehand with rad_store_create, single-step) receives the output as in
+ * rad_sample_pack.  Limits: rows * ceil(cols/32) * 4 bytes of keep words must
+ * fit the array (RAD_ERR_CAPACITY otherwise, nothing launched); the projection
+ * schemes are RAD_ERR_UNSUPPORTED (they need further workspaces).  Every call
+ * on a GPU, from any context or stream, uses that GPU's one array: calls that
+ * overlap on one GPU race, so issue them on one stream or order them yourself.
+ * The array keeps the last call's contents and needs no clearing (each call
+ * writes every word it later reads).  Launches are not timed by
+ * rad_ctx_timing. */
+#define RAD_STATIC_SCRATCH_BYTES (2u << 20)   /* 2 MiB: 16.7 M elements, e.g. 4096 x 4096 */
+rad_status rad_sample_pack_static(rad_ctx* ctx, const rad_sampling* sampling, const void* x,
+                                  rad_store* store);
+
 /* Forward of one layer with the exact x (Section 3: the forward pass uses the
  * original graph): y = act(x W + bias); stores the sample of x drawn by
  * `sampling` and, if layer.relu, the bits 1[h > 0] into `store`.  bias may be

@@ -72,6 +72,7 @@ SIGNATURES = {
     "rad_store_export_bits": (C.c_int, [P, P, P]),
     "rad_store_import_bits": (C.c_int, [P, P, P]),
     "rad_sample_pack": (C.c_int, [P, C.POINTER(rad_sampling), P, P, C.c_int32]),
+    "rad_sample_pack_static": (C.c_int, [P, C.POINTER(rad_sampling), P, P]),
     "rad_forward_sample": (C.c_int, [P, C.POINTER(rad_layer), C.POINTER(rad_sampling), P, P, P, P, P]),
     "rad_backward_dW": (C.c_int, [P, C.POINTER(rad_layer), P, P, P, P, C.c_float]),
     "rad_backward_dX": (C.c_int, [P, C.POINTER(rad_layer), P, P, P, P]),
@@ -238,6 +239,10 @@ def rad_store_import_bits(ctx, store, words):
 
 def rad_sample_pack(ctx, sampling, x, store, step_slot=0):
     _check(ctx, lib().rad_sample_pack(ctx, C.byref(sampling), _ptr(x), store, step_slot))
+
+
+def rad_sample_pack_static(ctx, sampling, x, store):
+    _check(ctx, lib().rad_sample_pack_static(ctx, C.byref(sampling), _ptr(x), store))
 
 
 def rad_forward_sample(ctx, layer, sampling, x, W, bias, y, store):

@@ -43,6 +43,27 @@ enum { WS_BITMAP = 0, WS_DENSE = 1, WS_ROWLOSS = 2, WS_COLSUM = 3, WS_SPLITK = 4
 
 static const char* kNoCtx = "no context";
 
+// Keep bitmap of rad_sample_pack_static: device memory this library owns from load to exit on every GPU it runs
+// on, so that the call has nothing to allocate.  The name `scratch` is the host-side stand-in of the symbol, not
+// a device address: host code uses the address hipGetSymbolAddress returns for the current device, kept per
+// device in g_scratch (each GPU holds a copy of the array at an address of its own).
+constexpr size_t kScratchWords = RAD_STATIC_SCRATCH_BYTES / 4;
+static __device__ __align__(256) uint32_t scratch[kScratchWords];
+constexpr int kMaxDevices = 64;
+static uint32_t* g_scratch[kMaxDevices] = {};
+
+// with `device` current: the device address of `scratch` on it (looked up once per device)
+static hipError_t scratch_resolve(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (g_scratch[device]) return hipSuccess;
+  void* ptr = nullptr;
+  hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!ptr) return hipErrorInvalidSymbol;
+  g_scratch[device] = static_cast<uint32_t*>(ptr);
+  return hipSuccess;
+}
+
 static rad_status fail(rad_ctx* c, rad_status s, const std::string& msg) {
   if (c) c->err = msg;
   return s;
@@ -118,6 +139,7 @@ extern "C" rad_status rad_ctx_create(rad_ctx** out, void* hip_stream) {
   if (hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return RAD_ERR_DEVICE; }
   if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) { delete c; return RAD_ERR_UNSUPPORTED; }
   if (hipMalloc(reinterpret_cast<void**>(&c->loss_dev), sizeof(float)) != hipSuccess) { delete c; return RAD_ERR_DEVICE; }
+  if (scratch_resolve(c->device) != hipSuccess) { (void)hipFree(c->loss_dev); delete c; return RAD_ERR_DEVICE; }
   *out = c;
   return RAD_OK;
 }
@@ -486,7 +508,7 @@ extern "C" rad_status rad_store_import_bits(rad_ctx* c, rad_store* s, const uint
 // draws the keep sets of every row and step of `s` into `bitmap`
 // clear_max_seg = false when the caller has already zeroed the segment maxima of all its stores at once
 static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, uint32_t* bitmap,
-                             bool clear_max_seg = true) {
+                             bool clear_max_seg = true, bool untimed = false) {
   if (s->scheme == RAD_EXACT || s->project()) return RAD_OK;
   PlanArgs a;
   a.seed_lo = (uint32_t)sm->seed; a.seed_hi = (uint32_t)(sm->seed >> 32);
@@ -505,6 +527,12 @@ static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, u
   s->last_plan = *sm; s->planned = true;
   s->bitmap = bitmap;
   if (clear_max_seg) HIP_TRY(c, launch_fill_u32(reinterpret_cast<uint32_t*>(s->max_seg), 0u, 1, c->stream));
+  if (untimed) {              // launches only: the timing wrapper may create events
+    HIP_TRY(c, launch_plan(a, c->stream));
+    if (s->counted_rows())
+      HIP_TRY(c, launch_row_scan(s->row_cnt, s->row_ptr, s->steps * s->rows, s->capacity, s->overflow, c->stream));
+    return RAD_OK;
+  }
   HIP_TRY(c, timed(c, "plan", [&](const char**) { return launch_plan(a, c->stream); }));
   if (s->counted_rows()) {
     HIP_TRY(c, timed(c, "row_scan", [&](const char**) {
@@ -548,6 +576,33 @@ extern "C" rad_status rad_sample_pack(rad_ctx* c, const rad_sampling* sm, const 
   if (s->scheme != RAD_EXACT) RAD_TRY(ws_get(c, WS_BITMAP, s->bitmap_words() * 4, &bm));
   RAD_TRY(store_plan(c, s, sm, static_cast<uint32_t*>(bm)));
   return store_pack(c, s, x, step_slot);
+}
+
+// rad_sample_pack for callers that must not allocate: the keep bitmap, which rad_sample_pack takes from a
+// grow-only context workspace (hipMalloc on first use or growth), lies in the library's static device array.
+// Same kernels, same results.  Nothing in the array has to start at zero: the plan kernel writes every word of
+// every row that the pack kernel reads.
+extern "C" rad_status rad_sample_pack_static(rad_ctx* c, const rad_sampling* sm, const void* x, rad_store* s) {
+  if (!c) return RAD_ERR_NULL;
+  if (!s || !x) return fail(c, RAD_ERR_NULL, "null argument");
+  RAD_TRY(check_sampling(c, sm, s));
+  if (s->steps != 1) return fail(c, RAD_ERR_UNSUPPORTED, "rad_sample_pack_static draws single-step stores only");
+  if (s->project())
+    return fail(c, RAD_ERR_UNSUPPORTED, "the projection schemes need workspaces that rad_sample_pack_static does not have");
+  if (s->bitmap_words() > kScratchWords)
+    return fail(c, RAD_ERR_CAPACITY, "rad_sample_pack_static: rows x ceil(cols/32) keep words exceed the static scratch (" +
+                                     std::to_string(s->bitmap_words() * 4) + " > " +
+                                     std::to_string((size_t)RAD_STATIC_SCRATCH_BYTES) + " bytes)");
+  if (c->device < 0 || c->device >= kMaxDevices || !g_scratch[c->device])
+    return fail(c, RAD_ERR_DEVICE, "static scratch was not resolved on this device");
+  uint32_t* bm = g_scratch[c->device];
+  if (s->scheme == RAD_EXACT) {
+    HIP_TRY(c, hipMemcpyAsync(s->values, x, (size_t)s->rows * s->cols * s->elem(), hipMemcpyDeviceToDevice, c->stream));
+    return RAD_OK;
+  }
+  RAD_TRY(store_plan(c, s, sm, bm, true, true));
+  HIP_TRY(c, launch_pack(x, s->dtype, store_view(s, 0), c->stream));
+  return RAD_OK;
 }
 
 // ------------------------------------------------------------ layer calls
