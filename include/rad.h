@@ -150,9 +150,12 @@ rad_status rad_ctx_timing_reset(rad_ctx* ctx);
  * are not GEMMs count zero. */
 rad_status rad_ctx_timing_read_flops(rad_ctx* ctx, const char* name, double* algorithmic, double* executed);
 
-/* Test hook: keys are shifted right by `shift` bits (and the Bernoulli
- * threshold likewise) before selection, which makes equal keys frequent and
- * so exercises the tie rule of the fixed-k draw.  0 restores normal keys. */
+/* Test hook, not part of the method: the keys of the NEXT draw only (the next
+ * call that samples one store) are shifted right by `shift` bits (and the
+ * Bernoulli threshold likewise) before selection, which makes equal keys
+ * frequent and so exercises the tie rule of the fixed-k draw.  The library
+ * returns to normal keys after that one draw, so the hook cannot be left on;
+ * 0 cancels it.  Not for index-free stores (their backward pass draws again). */
 rad_status rad_debug_key_shift(rad_ctx* ctx, int32_t shift);
 
 /* Allocates the store for `layer` under `scheme`/`p`: value and index arrays
@@ -305,7 +308,7 @@ rad_status rad_train_step(rad_ctx* ctx, rad_model* model, const rad_sampling* sa
                           void* const* grads, float* loss_host);
 
 /* ---- parameter updates ---------------------------------------------------
- * Section 5 and Appendix A (training details): the feedforward networks are
+ * Section 4.3 and Appendix A (training details): the feedforward networks are
  * trained with Adam with a tuned learning rate and l2 regularisation, the
  * recurrent one with SGD without momentum.  The l2 term enters the gradient
  * as l2 * w.  Learning-rate schedules are the caller's: lr is per call. */
@@ -338,7 +341,7 @@ rad_status rad_optimizer_step(rad_ctx* ctx, const rad_optimizer* opt, int64_t t,
                               void* const* master);
 
 /* ---- reaction-diffusion PDE-constrained optimisation -----------------------
- * Section 6 and Appendix B: phi on the nodes (i, j), 0 <= i, j <= n, of the
+ * Section 5 and Appendix B: phi on the nodes (i, j), 0 <= i, j <= n, of the
  * unit square (x = i/n, y = j/n), zero on the boundary, stepped explicitly,
  *   phi_{t+1} = phi_t + (D dt n^2)(4-neighbour sum - 4 phi_t) + dt C_t phi_t,
  *   C = th0 + th1 sin(pi t) + th2 cos(pi t) + sin(2 pi x)(th3 sin(pi t) + th4 cos(pi t))
@@ -346,7 +349,7 @@ rad_status rad_optimizer_step(rad_ctx* ctx, const rad_optimizer* opt, int64_t t,
  * from phi_0 = sin(pi x) sin(pi y); L = (1/steps) sum_{t=1..steps} |phi_t - target_t|^2,
  * target_t = phi_0 + (1/4) sin(pi t) sin(2 pi x) sin(pi y), time t = step * dt.
  * The gradient with respect to the seven controls is the estimator of
- * Section 6: dL/dphi_t and dphi_{t+1}/dC_t = dt diag(phi_t) are sampled with
+ * Section 5: dL/dphi_t and dphi_{t+1}/dC_t = dt diag(phi_t) are sampled with
  * the matrix P of phi_t, so only sampled entries of phi_t are kept: interior
  * entry c = (i-1)(n-1) + (j-1) of step t is kept iff the key of flat index c
  * with (stream_id, step = t) is below round(p 2^32), and weighs 1/p.  p = 1

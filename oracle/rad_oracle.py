@@ -603,7 +603,7 @@ def rnn_train_step(x, labels, W_ih, W_hh, b, W_ho, b_o, scheme, p, seed,
 
 
 # ----------------------------------------------------------------------------
-# Parameter updates (Section 5 and Appendix A, feedforward and RNN training
+# Parameter updates (Section 4.3 and Appendix A, feedforward and RNN training
 # details): the feedforward networks are trained with Adam, with a tuned
 # learning rate and l2 regularisation coefficient; the RNN with plain SGD
 # without momentum.  The l2 term enters as a gradient of (l2/2)|w|^2, i.e.
@@ -634,7 +634,7 @@ def adam_step(w, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, l2=0.0):
 
 
 # ----------------------------------------------------------------------------
-# Reaction-diffusion PDE-constrained optimisation (Section 6, Appendix B).
+# Reaction-diffusion PDE-constrained optimisation (Section 5, Appendix B).
 # phi lives on the nodes (i, j), 0 <= i, j <= n, of the unit square (x = i/n,
 # y = j/n) and is zero on the boundary; the explicit update of Appendix B is
 #   phi_{t+1} = phi_t + (D dt / dx^2) (4-neighbour sum - 4 phi_t) + dt C_t phi_t
@@ -642,7 +642,7 @@ def adam_step(w, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, l2=0.0):
 # sin(pi x) sin(pi y), target_t = phi_0 + (1/4) sin(pi t) sin(2 pi x) sin(pi y)
 # and L = (1/T) sum_{t=1..T} |phi_t - target_t|^2 (time t = step * dt).
 #
-# The estimator of Section 6 samples dL/dphi_t and the diagonal
+# The estimator of Section 5 samples dL/dphi_t and the diagonal
 # dphi_{t+1}/dC_t = dt diag(phi_t) with the matrix P of phi_t, so that only the
 # sampled entries of phi_t are kept; the Jacobians dphi_{j+1}/dphi_j =
 # M + dt diag(C_j) are known without phi, and C is recomputed from theta and t.

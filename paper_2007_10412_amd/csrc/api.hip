@@ -206,8 +206,8 @@ extern "C" rad_status rad_ctx_timing_read_flops(rad_ctx* c, const char* name, do
   return RAD_OK;
 }
 
-// test hook: keys are shifted right by `shift` bits before selection, which
-// makes equal keys frequent and so exercises the tie rule of the fixed-k draw
+// test hook: the keys of the next draw (one store_plan) are shifted right by `shift` bits before selection,
+// which makes equal keys frequent and so exercises the tie rule of the fixed-k draw; the draw resets it
 extern "C" rad_status rad_debug_key_shift(rad_ctx* c, int32_t shift) {
   if (!c) return RAD_ERR_NULL;
   if (shift < 0 || shift > 31) return fail(c, RAD_ERR_PARAM, "key shift must be in [0, 31]");
@@ -519,6 +519,7 @@ static rad_status store_plan(rad_ctx* c, rad_store* s, const rad_sampling* sm, u
   a.cols = s->cols; a.k = s->k; a.k_pitch = s->k_pitch;
   a.thresh = (uint64_t)std::llround(s->p * 4294967296.0) >> c->key_shift;
   a.key_shift = c->key_shift;
+  c->key_shift = 0;                 // the test hook serves one draw: it cannot be left on
   a.bitmap = bitmap; a.bm_pitch = s->bm_pitch;
   a.bucket_off = s->bucket_off; a.nb = s->nb;
   a.row_cnt = s->row_cnt; a.row_ptr = s->row_ptr;

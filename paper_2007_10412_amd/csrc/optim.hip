@@ -1,4 +1,4 @@
-// Parameter updates (Section 5 and Appendix A, training details): plain SGD for the recurrent model, Adam for the
+// Parameter updates (Section 4.3 and Appendix A, training details): plain SGD for the recurrent model, Adam for the
 // feedforward ones, each with an l2 term added to the gradient as l2 * w.  One pass over a tensor: every operand
 // is read once and every result written once, so the kernels are HBM streams (SGD 8 bytes read + 4 written per
 // fp32 parameter; Adam 16 read + 12 written, 2 more written when a bf16 copy of the parameter is kept).

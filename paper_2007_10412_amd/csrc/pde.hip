@@ -1,4 +1,4 @@
-// Reaction-diffusion PDE-constrained optimisation with a sampled adjoint (Section 6, Appendix B).
+// Reaction-diffusion PDE-constrained optimisation with a sampled adjoint (Section 5, Appendix B).
 // phi lives on the nodes (i, j), 0 <= i, j <= n <= 32, of the unit square, zero on the boundary; one explicit
 // step is phi += r (4-neighbour sum - 4 phi) + dt C phi with r = D dt / dx^2 and C the seven-term series in x and
 // t.  The steps depend on each other, so one problem is one workgroup of 1024 threads (a node each, the state in

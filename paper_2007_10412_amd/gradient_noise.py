@@ -1,4 +1,4 @@
-"""Gradient noise per layer of each stochastic gradient method (Section 5, the figure on gradient noise): the full
+"""Gradient noise per layer of each stochastic gradient method (Section 4.3, the figure on gradient noise): the full
 gradient over a training set is computed once, then each method's estimate on single minibatches is compared
 with it, and the mean squared deviation is reported layer by layer.  Methods: the baseline minibatch, RAD with
 the same sample for every example, RAD with a different sample per example, a reduced minibatch of about the

@@ -1,4 +1,4 @@
-"""The gradient-noise procedure (Section 5, gradient-noise figure) run through the C ABI against the same
+"""The gradient-noise procedure (Section 4.3, gradient-noise figure) run through the C ABI against the same
 procedure run on the oracle's training steps: per-layer mean squared deviations of every method agree, and
 they order as the paper reports (sampling costs less noise than the reduced minibatch of equal memory)."""
 import numpy as np

@@ -1,4 +1,4 @@
-"""GPU parity of the reaction-diffusion study (Section 6, Appendix B) against the oracle: loss, the sampled
+"""GPU parity of the reaction-diffusion study (Section 5, Appendix B) against the oracle: loss, the sampled
 gradient estimate for the same keys, and the number of kept entries, over grids, step counts on both sides of the
 kernels' 1024-step tables, fractions, and several problems per launch.  Both sides compute in fp64; they differ
 in the order of sums (stencil neighbours, the reduction over nodes), so values agree to about 1e-12 relative and

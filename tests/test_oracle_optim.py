@@ -1,4 +1,4 @@
-"""Pins of the oracle's parameter updates (Section 5 / Appendix A: Adam with l2 regularisation for the
+"""Pins of the oracle's parameter updates (Section 4.3 / Appendix A: Adam with l2 regularisation for the
 feedforward networks, SGD without momentum for the RNN): torch.optim on the CPU as an independent
 implementation, and the closed form of Adam under a constant gradient."""
 import numpy as np

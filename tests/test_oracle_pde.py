@@ -1,4 +1,4 @@
-"""Pins of the oracle's reaction-diffusion study (Section 6, Appendix B)."""
+"""Pins of the oracle's reaction-diffusion study (Section 5, Appendix B)."""
 import numpy as np
 import torch
 
