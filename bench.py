@@ -46,7 +46,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32", "other"],
+    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32", "other", "pack_stream"],
                     help="pde32: the reaction-diffusion study instead of a train step (a step = one gradient of each "
                          "of 256 problems); other: only the small configurations 1, 2, 3 and 5 (ms per train step)")
     ap.add_argument("--scheme", default="per_example", choices=sorted(SCHEMES))
@@ -67,6 +67,12 @@ def main():
         ctx = B.rad_ctx_create()
         print(json.dumps({"metric": "ms_per_train_step", "data": "synthetic", "n_gpus": 1,
                           "other_configs": other_configs(B, ctx, torch, synth)}))
+        B.rad_ctx_destroy(ctx)
+        return
+    if args.workload == "pack_stream":     # the stand-alone sampler on a 1 GiB stream, alone
+        ctx = B.rad_ctx_create()
+        print(json.dumps({"metric": "sampler_stream_GBps", "data": "synthetic", "n_gpus": 1,
+                          "pack_stream": pack_stream(B, ctx, torch, "f32")}))
         B.rad_ctx_destroy(ctx)
         return
     if args.workload == "pde32":
@@ -354,36 +360,46 @@ def other_configs(B, ctx, torch, synth):
 
 
 def pack_stream(B, ctx, torch, dtype_name):
-    """Sampling kernels on a >= 1 GiB stream of 4096-wide rows (Bernoulli p = 0.1, fp32): the pack kernel
-    is an HBM stream (read x and the keep bitmap, write values and indices); the plan kernel reads nothing
-    and is bound by Philox integer arithmetic."""
+    """The stand-alone sampler (key generation, selection, scale + pack: rad_sample_pack) on a 1 GiB stream of
+    4096-wide fp32 rows, fraction 0.1, under the Bernoulli and the per-example fixed-k rule.  Two kernels: the plan
+    kernel reads nothing and is bound by the integer arithmetic of the Philox keys (plus the k-select for fixed-k)
+    and writes a keep bitmap; the pack kernel is an HBM stream (x and the bitmap in, values and indices out).
+    `whole` is both kernels (and the row scan) against the algorithmic bytes: read 4 B per element, write 6 B per
+    kept entry."""
     rows, cols, p = 65536, 4096, 0.1
-    L = B.make_layer(rows, cols, 8, dtype=B.RAD_F32, relu=False)
-    st = B.rad_store_create(ctx, L, B.RAD_BERNOULLI, p)
-    x = torch.randn(rows, cols, device="cuda", dtype=torch.float32)
-    B.rad_ctx_timing(ctx, None)
-    for i in range(2):
-        B.rad_sample_pack(ctx, B.make_sampling(B.RAD_BERNOULLI, p, i), x, st)
-    B.rad_ctx_timing_reset(ctx)
-    reps = 5
-    for i in range(reps):
-        B.rad_sample_pack(ctx, B.make_sampling(B.RAD_BERNOULLI, p, 10 + i), x, st)
-    n_pack, ms_pack = B.rad_ctx_timing_read(ctx, "pack")
-    n_plan, ms_plan = B.rad_ctx_timing_read(ctx, "plan")
-    B.rad_ctx_timing(ctx, "")
-    B.rad_ctx_timing_reset(ctx)
-    nnz = B.rad_store_get_stats(ctx, st)["nnz"]
-    B.rad_store_destroy(st)
     n = rows * cols
-    pack_bytes = n * 4 + n / 8 + nnz * 6          # x + keep bitmap read, value + index written
-    plan_bytes = n / 8                            # bitmap written
-    t_pack = ms_pack / n_pack * 1e-3
-    t_plan = ms_plan / n_plan * 1e-3
-    return {"rows": rows, "cols": cols, "p": p, "dtype": "f32",
+    x = torch.randn(rows, cols, device="cuda", dtype=torch.float32)
+    res = {"rows": rows, "cols": cols, "p": p, "dtype": "f32"}
+    reps = 5
+    for name, scheme in (("bernoulli", B.RAD_BERNOULLI), ("fixed_k_per_example", B.RAD_FIXEDK_PER_EXAMPLE)):
+        L = B.make_layer(rows, cols, 8, dtype=B.RAD_F32, relu=False)
+        st = B.rad_store_create(ctx, L, scheme, p)
+        B.rad_ctx_timing(ctx, None)
+        for i in range(2):
+            B.rad_sample_pack(ctx, B.make_sampling(scheme, p, i), x, st)
+        B.rad_ctx_timing_reset(ctx)
+        for i in range(reps):
+            B.rad_sample_pack(ctx, B.make_sampling(scheme, p, 10 + i), x, st)
+        n_plan, ms_plan = B.rad_ctx_timing_read(ctx, "plan")
+        n_pack, ms_pack = B.rad_ctx_timing_read(ctx, "pack_f32")
+        n_scan, ms_scan = B.rad_ctx_timing_read(ctx, "row_scan")
+        B.rad_ctx_timing(ctx, "")
+        B.rad_ctx_timing_reset(ctx)
+        nnz = B.rad_store_get_stats(ctx, st)["nnz"]
+        B.rad_store_destroy(st)
+        t_plan, t_pack, t_scan = ms_plan / n_plan * 1e-3, ms_pack / n_pack * 1e-3, (ms_scan / n_scan * 1e-3 if n_scan else 0.0)
+        alg = n * 4 + nnz * 6                         # read s per element, write (s + 2) per kept entry
+        pack_bytes = alg + n / 8                      # the pack kernel also reads the keep bitmap
+        t_whole = t_plan + t_pack + t_scan
+        res[name] = {
+            "whole": {"bound": "hbm", "ms": t_whole * 1e3, "achieved": alg / t_whole / 1e9, "peak": HBM_PEAK,
+                      "unit": "GB/s", "frac": alg / t_whole / 1e9 / HBM_PEAK, "keys_per_s": n / t_whole},
+            "plan": {"bound": "alu", "ms": t_plan * 1e3, "keys_per_s": n / t_plan, "write_GBps": n / 8 / t_plan / 1e9},
+            "row_scan_ms": t_scan * 1e3,
             "pack": {"bound": "hbm", "ms": t_pack * 1e3, "achieved": pack_bytes / t_pack / 1e9, "peak": HBM_PEAK,
-                     "unit": "GB/s", "frac": pack_bytes / t_pack / 1e9 / HBM_PEAK},
-            "plan": {"bound": "alu", "ms": t_plan * 1e3, "keys_per_s": n / t_plan,
-                     "write_GBps": plan_bytes / t_plan / 1e9}}
+                     "unit": "GB/s", "frac": pack_bytes / t_pack / 1e9 / HBM_PEAK,
+                     "frac_algorithmic_bytes": alg / t_pack / 1e9 / HBM_PEAK}}
+    return res
 
 
 def pde_study(B, ctx, torch, steps, warmup, p, problems=256):
