@@ -83,7 +83,11 @@ typedef enum { RAD_LINEAR = 0, RAD_CONV2D = 1 } rad_kind;
  * stride-1 convolution computed as an implicit im2col GEMM: x is NCHW
  * [batch, c_in, h, w] (d_in = c_in*h*w, the flattened tensor is what is
  * sampled), W is [c_in, kh, kw, c_out], y is NCHW [batch, c_out, h, w]
- * (d_out = c_out*h*w; pad must keep the spatial size: 2*pad = kh-1 = kw-1). */
+ * (d_out = c_out*h*w; pad must keep the spatial size: 2*pad = kh-1 = kw-1).
+ * dW is [c_in, kh, kw, c_out] and dbias [c_out]; dX is NCHW like x.  Conv
+ * layers are fp32, with at most 64 input and 64 output channels and h*w a
+ * multiple of 64 (RAD_ERR_UNSUPPORTED otherwise); rad_backward_dW writes conv
+ * gradients (beta = 0 only).  The projection schemes do not serve them. */
 typedef struct {
   int32_t kind;     /* rad_kind */
   int32_t dtype;    /* rad_dtype */

@@ -33,13 +33,13 @@ struct rad_ctx {
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
   // grow-only workspaces
-  void* ws[10] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-  size_t ws_bytes[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  void* ws[11] = {};
+  size_t ws_bytes[11] = {};
   float* loss_dev = nullptr;
 };
 
 enum { WS_BITMAP = 0, WS_DENSE = 1, WS_ROWLOSS = 2, WS_COLSUM = 3, WS_SPLITK = 4, WS_WT = 5, WS_PROJ_R = 6, WS_PROJ_T = 7,
-       WS_PROJ_TB = 8, WS_REINDEX = 9 };
+       WS_PROJ_TB = 8, WS_REINDEX = 9, WS_CONVG = 10 };
 
 static const char* kNoCtx = "no context";
 
@@ -151,7 +151,7 @@ extern "C" rad_status rad_ctx_destroy(rad_ctx* c) {
   if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
   for (hipEvent_t e : {c->ev_ready[0], c->ev_ready[1], c->ev_done[0], c->ev_done[1], c->ev_join}) if (e) (void)hipEventDestroy(e);
   for (auto& e : c->pool) (void)hipEventDestroy(e);
-  for (int i = 0; i < 10; ++i) if (c->ws[i]) (void)hipFree(c->ws[i]);
+  for (void* w : c->ws) if (w) (void)hipFree(w);
   if (c->loss_dev) (void)hipFree(c->loss_dev);
   delete c;
   return RAD_OK;
@@ -429,7 +429,10 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
   const void* vsrc = s->values;
   const uint16_t* isrc = s->indices;
   bool paired = s->paired();
-  if (s->index_free) {
+  const bool from_bitmap = s->index_free && s->steps > 1;     // columns are enumerated from the keep bitmap below
+  if (from_bitmap && (!s->bitmap || s->dtype != kF32))
+    return fail(c, RAD_ERR_PARAM, "the index-free store has no current draw to export");
+  if (s->index_free && !from_bitmap) {
     StoreView bv;
     RAD_TRY(backward_view(c, s, 0, &bv));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -466,6 +469,15 @@ extern "C" rad_status rad_store_export_csr(rad_ctx* c, const rad_store* s, int64
     HIP_TRY(c, hipMemcpy(idx.data(), s->indices, idx.size() * 2, hipMemcpyDeviceToHost));
     for (int64_t r = 0; r < R; ++r)
       for (int j = 0; j < s->k; ++j) col[r * s->k + j] = idx[(size_t)(r / s->rows) * s->k + j];
+  } else if (from_bitmap) {
+    std::vector<uint32_t> bm(s->bitmap_words());
+    HIP_TRY(c, hipMemcpy(bm.data(), s->bitmap, bm.size() * 4, hipMemcpyDeviceToHost));
+    for (int64_t r = 0; r < R; ++r) {
+      const int64_t prow = s->plan_rows_per_step == s->rows ? r : r / s->rows;
+      int64_t e = (int64_t)rp[(size_t)r];
+      for (int j = 0; j < s->cols && e < nnz; ++j)
+        if ((bm[(size_t)prow * s->bm_pitch + (j >> 5)] >> (j & 31)) & 1u) col[e++] = j;
+    }
   } else if (paired) {
     // the bucket of an entry follows from its position in the row
     std::vector<uint16_t> bo((size_t)s->steps * s->plan_rows_per_step * (s->nb + 1));
@@ -835,6 +847,7 @@ static rad_status backward_view(rad_ctx* c, const rad_store* cs, int slot, Store
   if (!cs->index_free) return RAD_OK;
   rad_store* s = const_cast<rad_store*>(cs);       // the plan tables are rewritten with the values they hold
   if (!s->planned) return fail(c, RAD_ERR_PARAM, "the index-free store has not been sampled yet");
+  if (s->steps != 1) return fail(c, RAD_ERR_UNSUPPORTED, "index-free multi-step stores are read inside rad_train_step only");
   void* bm = nullptr;
   RAD_TRY(ws_get(c, WS_BITMAP, s->bitmap_words() * 4, &bm));
   const rad_sampling sm = s->last_plan;
@@ -855,8 +868,9 @@ static rad_status backward_view(rad_ctx* c, const rad_store* cs, int slot, Store
 extern "C" rad_status rad_store_set_index_free(rad_ctx* c, rad_store* s, int32_t on) {
   if (!c) return RAD_ERR_NULL;
   if (!s) return fail(c, RAD_ERR_NULL, "store is null");
-  if (!s->per_entry() || s->steps != 1)
-    return fail(c, RAD_ERR_UNSUPPORTED, "index-free storage serves single-step stores with per-entry columns");
+  if (!s->per_entry()) return fail(c, RAD_ERR_UNSUPPORTED, "index-free storage serves stores with per-entry columns");
+  if (s->steps != 1 && s->dtype != kF32)
+    return fail(c, RAD_ERR_UNSUPPORTED, "index-free multi-step stores are fp32 only");
   if ((on != 0) == s->index_free) return RAD_OK;
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   if (s->values) (void)hipFree(s->values);
@@ -909,6 +923,19 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     return split_k_finish(c, g, sp);
   }
   g.M = s->cols;
+  if (s->index_free && s->steps > 1) {
+    // a multi-step store that keeps values only (the recurrent model): the keep bitmap of the step's own plan is
+    // still there, and x~ of the chunk is rebuilt from it as a transient dense operand
+    if (!s->bitmap || s->dtype != kF32) return fail(c, RAD_ERR_PARAM, "the index-free store has no current draw");
+    StoreView v = store_view(s, slot);
+    v.rows = s->rows * n_slots;
+    void* dense = nullptr;
+    RAD_TRY(ws_get(c, WS_DENSE, (size_t)v.rows * s->cols * 4, &dense));
+    HIP_TRY(c, timed(c, "unpack", [&](const char**) { return launch_unpack_bitmap(v, kF32, dense, c->stream); }));
+    g.K = v.rows; g.A = dense; g.lda = s->cols;
+    const double kept = s->scheme == RAD_BERNOULLI ? s->p * (double)v.rows * s->cols : (double)v.rows * s->k;
+    return run_gemm_call(c, kF32, kOpMN, kOpMN, kEpiStore, g, 2.0 * kept * N);
+  }
   RAD_TRY(backward_view(c, s, slot, &g.sa));
   g.sa.rows = s->rows * n_slots;
   g.sparse_prefetch = sparse_prefetch_for(s, s->dtype == kBF16 ? 8 : 16);
@@ -1018,6 +1045,17 @@ static rad_status colsum_call(rad_ctx* c, const void* dy, int dtype, int rows, i
   return RAD_OK;
 }
 
+// convolution pieces (defined with the CNN model below)
+static rad_status conv_limits(rad_ctx* c, const rad_layer* L);
+static rad_status conv_gemm(rad_ctx* c, int B, int ci, int co, int h, int w, int ks, const float* src, const float* W,
+                            const float* bias, int relu, float* y, uint32_t* bits, int bits_pitch);
+static rad_status conv_dW_call(rad_ctx* c, const rad_store* s, int B, int ci, int co, int h, int w, int ks, const float* g,
+                               float* dW, float* dbias);
+static rad_status conv_dX_call(rad_ctx* c, int B, int ci, int co, int h, int w, int ks, const float* g, const float* W,
+                               float* dX);
+// g = dy masked by the store's ReLU bits (dy itself for a layer without ReLU), in a context workspace
+static rad_status conv_masked_dy(rad_ctx* c, const rad_layer* L, const rad_store* s, const void* dy, const float** g);
+
 extern "C" rad_status rad_forward_sample(rad_ctx* c, const rad_layer* L, const rad_sampling* sm, const void* x,
                                          const void* W, const void* bias, void* y, rad_store* s) {
   if (!c) return RAD_ERR_NULL;
@@ -1025,7 +1063,14 @@ extern "C" rad_status rad_forward_sample(rad_ctx* c, const rad_layer* L, const r
   if (!x || !W || !y || !s) return fail(c, RAD_ERR_NULL, "null argument");
   if ((L->has_bias != 0) != (bias != nullptr)) return fail(c, RAD_ERR_NULL, "bias pointer does not match has_bias");
   if (!layer_matches(L, s)) return fail(c, RAD_ERR_SHAPE, "store was created for a different layer");
-  if (L->kind != RAD_LINEAR) return fail(c, RAD_ERR_UNSUPPORTED, "stand-alone conv layers are not built yet");
+  if (L->kind == RAD_CONV2D) {
+    // Section 4.2 (convolutional layers): the flattened input is sampled, the convolution itself is exact
+    RAD_TRY(conv_limits(c, L));
+    RAD_TRY(rad_sample_pack(c, sm, x, s, 0));
+    return conv_gemm(c, (int)L->batch, L->c_in, L->c_out, L->h, L->w, L->kh, static_cast<const float*>(x),
+                     static_cast<const float*>(W), static_cast<const float*>(bias), L->relu, static_cast<float*>(y),
+                     s->bits, s->bits_pitch);
+  }
   RAD_TRY(rad_sample_pack(c, sm, x, s, 0));
   return forward_gemm(c, L->dtype, (int)L->batch, (int)L->d_out, (int)L->d_in, x, L->d_in, W,
                       static_cast<const float*>(bias), L->relu, y, s->bits, s->bits_pitch, nullptr, nullptr, 0, 0,
@@ -1039,8 +1084,15 @@ extern "C" rad_status rad_backward_dW(rad_ctx* c, const rad_layer* L, const rad_
   if (!s || !dy || !dW) return fail(c, RAD_ERR_NULL, "null argument");
   if (!layer_matches(L, s)) return fail(c, RAD_ERR_SHAPE, "store was created for a different layer");
   if (beta != 0.f && beta != 1.f) return fail(c, RAD_ERR_PARAM, "beta must be 0 or 1");
-  if (L->kind != RAD_LINEAR) return fail(c, RAD_ERR_UNSUPPORTED, "stand-alone conv layers are not built yet");
   if (s->steps != 1) return fail(c, RAD_ERR_UNSUPPORTED, "multi-step stores belong to rad_train_step");
+  if (L->kind == RAD_CONV2D) {
+    RAD_TRY(conv_limits(c, L));
+    if (beta != 0.f) return fail(c, RAD_ERR_UNSUPPORTED, "conv gradients are written, not accumulated (beta = 0)");
+    if (s->project()) return fail(c, RAD_ERR_UNSUPPORTED, "the projection schemes serve linear layers only");
+    const float* g = nullptr;
+    RAD_TRY(conv_masked_dy(c, L, s, dy, &g));
+    return conv_dW_call(c, s, (int)L->batch, L->c_in, L->c_out, L->h, L->w, L->kh, g, dW, dbias);
+  }
   RAD_TRY(dW_gemm(c, s, 0, dy, (int)L->d_out, s->bits, s->bits_pitch, dW, beta != 0.f));
   if (dbias)
     RAD_TRY(colsum_call(c, dy, L->dtype, (int)L->batch, (int)L->d_out, s->bits, s->bits_pitch, nullptr, 0, 0, dbias,
@@ -1054,7 +1106,13 @@ extern "C" rad_status rad_backward_dX(rad_ctx* c, const rad_layer* L, const rad_
   RAD_TRY(check_layer(c, L));
   if (!s || !dy || !W || !dX) return fail(c, RAD_ERR_NULL, "null argument");
   if (!layer_matches(L, s)) return fail(c, RAD_ERR_SHAPE, "store was created for a different layer");
-  if (L->kind != RAD_LINEAR) return fail(c, RAD_ERR_UNSUPPORTED, "stand-alone conv layers are not built yet");
+  if (L->kind == RAD_CONV2D) {
+    RAD_TRY(conv_limits(c, L));
+    const float* g = nullptr;
+    RAD_TRY(conv_masked_dy(c, L, s, dy, &g));
+    return conv_dX_call(c, (int)L->batch, L->c_in, L->c_out, L->h, L->w, L->kh, g, static_cast<const float*>(W),
+                        static_cast<float*>(dX));
+  }
   return dX_gemm(c, L->dtype, (int)L->batch, (int)L->d_in, (int)L->d_out, dy, s->bits, s->bits_pitch, W, dX);
 }
 
@@ -1253,7 +1311,6 @@ extern "C" rad_status rad_model_destroy(rad_model* m) {
 extern "C" rad_status rad_model_set_index_free(rad_ctx* c, rad_model* m, int32_t on) {
   if (!c) return RAD_ERR_NULL;
   if (!m) return fail(c, RAD_ERR_NULL, "model is null");
-  if (m->kind != kMlp) return fail(c, RAD_ERR_UNSUPPORTED, "index-free storage serves MLP models only");
   for (rad_store* s : m->stores)
     if (s->per_entry()) RAD_TRY(rad_store_set_index_free(c, s, on));
   return RAD_OK;
@@ -1538,7 +1595,7 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   // (index-free) keep the step-by-step form (two row blocks, used in turn).  g_1 has no dW_hh and lives in dyb[1].
   const bool per_row = s_hh->scheme == RAD_EXACT || s_hh->scheme == RAD_BERNOULLI || s_hh->scheme == RAD_FIXEDK_PER_EXAMPLE ||
                        s_hh->scheme == RAD_REPLACE_PER_EXAMPLE;
-  const int G = (per_row && !s_hh->index_free) ? kRnnChunk : 1;
+  const int G = per_row ? kRnnChunk : 1;
   const int Gp = G > 1 ? 2 * G : 2;                      // row blocks in use: two chunks, or two single steps
   const size_t gstride = (size_t)B * H;
   auto g_of = [&](int t) -> float* { return t >= 2 ? m->rnn_g + (size_t)((t - 2) % Gp) * gstride : static_cast<float*>(m->dyb[1]); };
@@ -1679,6 +1736,75 @@ static rad_status conv_gemm(rad_ctx* c, int B, int ci, int co, int h, int w, int
   return run_gemm_call(c, kF32, kOpIm2colRows, kOpMN, kEpiConv, g);
 }
 
+// what the convolution kernels serve: fp32, square odd kernels, at most 64 output channels (one tile column),
+// H*W a multiple of the 64-row tile (a tile never straddles two images)
+static rad_status conv_limits(rad_ctx* c, const rad_layer* L) {
+  if (L->kh != L->kw) return fail(c, RAD_ERR_UNSUPPORTED, "conv kernels must be square");
+  if (L->c_out > 64 || (L->h * L->w) % 64 != 0 || L->c_in > 64)
+    return fail(c, RAD_ERR_UNSUPPORTED, "conv layers need H*W a multiple of 64 and at most 64 input and output channels");
+  return RAD_OK;
+}
+
+static rad_status conv_masked_dy(rad_ctx* c, const rad_layer* L, const rad_store* s, const void* dy, const float** g) {
+  if (!L->relu) { *g = static_cast<const float*>(dy); return RAD_OK; }
+  void* buf = nullptr;
+  RAD_TRY(ws_get(c, WS_CONVG, (size_t)L->batch * L->d_out * 4, &buf));
+  HIP_TRY(c, timed(c, "unpool_mask", [&](const char**) {
+    return launch_unpool_mask(static_cast<const float*>(dy), (int)L->batch, L->c_out, L->h, L->w, 0, nullptr, s->bits,
+                              s->bits_pitch, static_cast<float*>(buf), c->stream);
+  }));
+  *g = static_cast<const float*>(buf);
+  return RAD_OK;
+}
+
+// dW [ci*ks*ks][co] (and dbias [co], if given) of a convolution from the sampled input in `s` and g = dL/dh
+// [B][co][h][w] (Figure 5: the sampled x~ is scattered back to a dense transient and contracted with g)
+static rad_status conv_dW_call(rad_ctx* c, const rad_store* s, int B, int ci, int co, int h, int w, int ks, const float* g,
+                               float* dW, float* dbias) {
+  const int HW = h * w;
+  const void* xt = s->values;
+  if (s->scheme != RAD_EXACT) {
+    void* dense = nullptr;
+    RAD_TRY(ws_get(c, WS_DENSE, (size_t)B * s->cols * 4, &dense));
+    StoreView v;                                   // an index-free store is read through its rebuild
+    RAD_TRY(backward_view(c, s, 0, &v));
+    HIP_TRY(c, timed(c, "unpack", [&](const char**) { return launch_unpack(v, kF32, dense, c->stream); }));
+    xt = dense;
+  }
+  GemmArgs a = gemm_zero();
+  a.M = ci * ks * ks; a.N = co; a.K = B * HW;
+  a.A = xt; a.B = g;
+  a.cv_C = ci; a.cv_H = h; a.cv_W = w; a.cv_KH = ks; a.cv_KW = ks; a.cv_pad = (ks - 1) / 2; a.cv_N = co;
+  a.k_split = 1024; a.k_splits = (a.K + a.k_split - 1) / a.k_split;
+  void* part = nullptr;
+  RAD_TRY(ws_get(c, WS_SPLITK, (size_t)a.k_splits * a.M * a.N * 4, &part));
+  a.C = part; a.ldc = a.N;
+  RAD_TRY(run_gemm_call(c, kF32, kOpIm2colK, kOpKBatched, kEpiSplitK, a));
+  HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
+    return launch_splitk_reduce(static_cast<const float*>(part), a.k_splits, (int64_t)a.M * a.N, dW, 0, c->stream);
+  }));
+  if (dbias) {
+    const int cs_splits = B < 32 ? B : 32;
+    void* cs_part = nullptr;
+    RAD_TRY(ws_get(c, WS_COLSUM, (size_t)co * cs_splits * 4, &cs_part));
+    HIP_TRY(c, timed(c, "channel_sum", [&](const char**) {
+      return launch_channel_sum(g, B, co, HW, dbias, static_cast<float*>(cs_part), cs_splits, c->stream);
+    }));
+  }
+  return RAD_OK;
+}
+
+// dX [B][ci][h][w] = the transposed convolution of g with W, exact (never sampled)
+static rad_status conv_dX_call(rad_ctx* c, int B, int ci, int co, int h, int w, int ks, const float* g, const float* W,
+                               float* dX) {
+  void* wt = nullptr;
+  RAD_TRY(ws_get(c, WS_WT, (size_t)co * ks * ks * ci * 4, &wt));
+  HIP_TRY(c, timed(c, "flip_weights", [&](const char**) {
+    return launch_flip_weights(W, ci, ks, ks, co, static_cast<float*>(wt), c->stream);
+  }));
+  return conv_gemm(c, B, co, ci, h, w, ks, g, static_cast<const float*>(wt), nullptr, 0, dX, nullptr, 0);
+}
+
 // params/grads order: W_0, b_0, ..., W_{n-1}, b_{n-1}, W_fc, b_fc
 static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, const void* x, const int32_t* labels,
                            void* const* params, void* const* grads, float* loss_host) {
@@ -1739,7 +1865,6 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   for (int l = nc - 1; l >= 0; --l) {
     const rad_model::Conv& cv = m->convs[(size_t)l];
     rad_store* s = m->stores[(size_t)l];
-    const int HW = cv.h * cv.w;
     const int gb = (db_ + 1) % 3, nb_ = (db_ + 2) % 3;
     float* g = static_cast<float*>(m->buf[gb]);
     // g = dL/dh of this layer: route through the pool, then the 1-bit ReLU Jacobian (Section 4.2)
@@ -1747,47 +1872,11 @@ static rad_status cnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
       return launch_unpool_mask(static_cast<const float*>(m->buf[db_]), B, cv.co, cv.h, cv.w, cv.pool, cv.arg, s->bits,
                                 s->bits_pitch, g, c->stream);
     }));
-    // dW from the sampled input (Figure 5): x~ scattered back to a dense transient, contracted with g
-    const void* xt = s->values;
-    if (s->scheme != RAD_EXACT) {
-      void* dense = nullptr;
-      RAD_TRY(ws_get(c, WS_DENSE, (size_t)B * s->cols * 4, &dense));
-      const StoreView v = store_view(s, 0);
-      HIP_TRY(c, timed(c, "unpack", [&](const char**) { return launch_unpack(v, kF32, dense, c->stream); }));
-      xt = dense;
-    }
-    GemmArgs a = gemm_zero();
-    a.M = cv.ci * ks * ks; a.N = cv.co; a.K = B * HW;
-    a.A = xt; a.B = g;
-    a.cv_C = cv.ci; a.cv_H = cv.h; a.cv_W = cv.w; a.cv_KH = ks; a.cv_KW = ks; a.cv_pad = (ks - 1) / 2; a.cv_N = cv.co;
-    a.k_split = 1024; a.k_splits = (a.K + a.k_split - 1) / a.k_split;
-    void* part = nullptr;
-    RAD_TRY(ws_get(c, WS_SPLITK, (size_t)a.k_splits * a.M * a.N * 4, &part));
-    a.C = part; a.ldc = a.N;
-    RAD_TRY(run_gemm_call(c, kF32, kOpIm2colK, kOpKBatched, kEpiSplitK, a));
-    HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
-      return launch_splitk_reduce(static_cast<const float*>(part), a.k_splits, (int64_t)a.M * a.N,
-                                  static_cast<float*>(grads[2 * l]), 0, c->stream);
-    }));
-    {
-      const int cs_splits = B < 32 ? B : 32;
-      void* cs_part = nullptr;
-      RAD_TRY(ws_get(c, WS_COLSUM, (size_t)cv.co * cs_splits * 4, &cs_part));
-      HIP_TRY(c, timed(c, "channel_sum", [&](const char**) {
-        return launch_channel_sum(g, B, cv.co, HW, static_cast<float*>(grads[2 * l + 1]), static_cast<float*>(cs_part),
-                                  cs_splits, c->stream);
-      }));
-    }
+    RAD_TRY(conv_dW_call(c, s, B, cv.ci, cv.co, cv.h, cv.w, ks, g, static_cast<float*>(grads[2 * l]),
+                         static_cast<float*>(grads[2 * l + 1])));
     if (l > 0) {
-      // dX: the transposed convolution, exact (never sampled)
-      void* wt = nullptr;
-      RAD_TRY(ws_get(c, WS_WT, (size_t)cv.co * ks * ks * cv.ci * 4, &wt));
-      HIP_TRY(c, timed(c, "flip_weights", [&](const char**) {
-        return launch_flip_weights(static_cast<const float*>(params[2 * l]), cv.ci, ks, ks, cv.co, static_cast<float*>(wt),
-                                   c->stream);
-      }));
-      RAD_TRY(conv_gemm(c, B, cv.co, cv.ci, cv.h, cv.w, ks, g, static_cast<const float*>(wt), nullptr, 0,
-                        static_cast<float*>(m->buf[nb_]), nullptr, 0));
+      RAD_TRY(conv_dX_call(c, B, cv.ci, cv.co, cv.h, cv.w, ks, g, static_cast<const float*>(params[2 * l]),
+                           static_cast<float*>(m->buf[nb_])));
       db_ = nb_;
     }
   }

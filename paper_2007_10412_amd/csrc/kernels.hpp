@@ -168,6 +168,8 @@ int gemm_bf16_sparse_cap(int sparse_prefetch);
 int gemm_bf16_sparse_max_prefetch();
 // dense[rows, cols] = the store's rows scattered back (zeros elsewhere): x~ as a dense operand
 hipError_t launch_unpack(const StoreView& s, int dtype, void* dense, hipStream_t st);
+// the same for a store that keeps values only, from the keep bitmap of its current draw (s.bitmap)
+hipError_t launch_unpack_bitmap(const StoreView& s, int dtype, void* dense, hipStream_t st);
 // index-free stores: rebuild the (value, column) entries (bf16: out_pairs) or the columns (fp32: out_idx) from
 // the values in `s` and the keep bitmap / offsets of a fresh plan
 hipError_t launch_reindex(const StoreView& s, int dtype, uint32_t* out_pairs, uint16_t* out_idx, hipStream_t st);

@@ -593,7 +593,41 @@ __global__ __launch_bounds__(256) void unpack_kernel(StoreView s, T* __restrict_
   for (int64_t e = beg + threadIdx.x; e < end; e += 256) out[s.indices[s.idx_shared ? e - beg : e]] = vals[e];
 }
 
+// The same from the keep bitmap instead of stored columns (index-free stores whose bitmap of the current draw is
+// still there): entry e of a row belongs to the row's e-th kept column.
+template <typename T>
+__global__ __launch_bounds__(256) void unpack_bitmap_kernel(StoreView s, T* __restrict__ dense) {
+  __shared__ int s_scan[8];
+  const int row = blockIdx.x;
+  T* out = dense + (size_t)row * s.cols;
+  const uint32_t* bm = s.bitmap + (size_t)(row * s.plan_row_stride) * s.bm_pitch;
+  const T* vals = reinterpret_cast<const T*>(s.values);
+  int64_t pos = s.row_ptr[row];
+  for (int w0 = 0; w0 < s.bm_pitch; w0 += 256) {
+    const int wi = w0 + (int)threadIdx.x;
+    uint32_t word = wi < s.bm_pitch ? bm[wi] : 0u;
+    int total;
+    int64_t e = pos + block_excl_scan(__popc(word), &total, s_scan);
+    for (int b = 0; b < 32; ++b) {
+      const int col = wi * 32 + b;
+      if (col < s.cols) {
+        T v = T(0);
+        if ((word >> b) & 1u) { if (e < s.capacity) v = vals[e]; ++e; }
+        out[col] = v;
+      }
+    }
+    pos += total;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_unpack_bitmap(const StoreView& s, int dtype, void* dense, hipStream_t st) {
+  if (!s.bitmap || s.paired) return hipErrorInvalidValue;
+  if (dtype == kF32) hipLaunchKernelGGL(unpack_bitmap_kernel<float>, dim3(s.rows), dim3(256), 0, st, s, (float*)dense);
+  else hipLaunchKernelGGL(unpack_bitmap_kernel<uint16_t>, dim3(s.rows), dim3(256), 0, st, s, (uint16_t*)dense);
+  return hipGetLastError();
+}
 
 hipError_t launch_unpack(const StoreView& s, int dtype, void* dense, hipStream_t st) {
   if (dtype == kF32) hipLaunchKernelGGL(unpack_kernel<float>, dim3(s.rows), dim3(256), 0, st, s, (float*)dense);

@@ -7,7 +7,7 @@ same memory, and RAD on a larger minibatch.
 The training set is synthetic (seeded, the shapes and value statistics of the paper's datasets, which are not
 available here); everything is computed by rad_train_step through the C ABI.
 
-    python -m paper_2007_10412_amd.gradient_noise --arch cnn --train 1200 --draws 16
+    python -m paper_2007_10412_amd.gradient_noise --arch cnn --train 1200 --draws 16      (or --arch mlp, --arch rnn)
 
 prints one JSON object.  `measure` takes the step function as an argument, so that a test can run the same
 procedure on another implementation of the step."""
@@ -21,6 +21,8 @@ def paper_arch(arch):
     """Appendix A, architectures used."""
     if arch == "mlp":
         return dict(kind="mlp", dims=(784, 300, 300, 300, 10), batch=150, reduced=22)
+    if arch == "rnn":      # reduced minibatch of 21 (Appendix A, RNN training details)
+        return dict(kind="rnn", T=784, d_input=1, hidden=100, classes=10, batch=150, reduced=21)
     return dict(kind="cnn", channels=(3, 16, 32, 32, 32), pool=(0, 2, 0, 2), ksize=5, hw=32, classes=10, batch=150,
                 reduced=20)
 
@@ -72,6 +74,9 @@ class GpuStep:
         if cfg["kind"] == "mlp":
             ws = [a for pair in zip(data["Ws"], data["bs"]) for a in pair]
             self.weight_slots = list(range(0, len(ws), 2))
+        elif cfg["kind"] == "rnn":      # "layers" of the recurrent model: input, recurrent and output weights
+            ws = [data[n] for n in ("W_ih", "W_hh", "b", "W_ho", "b_o")]
+            self.weight_slots = [0, 1, 3]
         else:
             ws = [a for cv in data["convs"] for a in (cv["W"], cv["b"])] + [data["fc"][0], data["fc"][1]]
             self.weight_slots = list(range(0, len(ws), 2))
@@ -85,6 +90,9 @@ class GpuStep:
             B, c = self.B, self.cfg
             if c["kind"] == "mlp":
                 self.models[key] = B.rad_model_create_mlp(self.ctx, B.RAD_F32, size, list(c["dims"]), True, scheme, p)
+            elif c["kind"] == "rnn":
+                self.models[key] = B.rad_model_create_rnn(self.ctx, size, c["T"], c["d_input"], c["hidden"], c["classes"],
+                                                          scheme, p)
             else:
                 self.models[key] = B.rad_model_create_cnn(self.ctx, size, list(c["channels"]), list(c["pool"]), c["ksize"],
                                                           c["hw"], c["hw"], c["classes"], scheme, p)
@@ -106,13 +114,16 @@ def training_set(cfg, n_train, seed=1234):
     from . import synth
     if cfg["kind"] == "mlp":
         return synth.mlp(seed=seed, batch=n_train, dims=cfg["dims"], bias_scale=0.0)
+    if cfg["kind"] == "rnn":
+        return synth.rnn(seed=seed, batch=n_train, T=cfg["T"], d_input=cfg["d_input"], hidden=cfg["hidden"],
+                         classes=cfg["classes"], identity=True)
     return synth.cnn(seed=seed, batch=n_train, channels=cfg["channels"], pool=cfg["pool"], ksize=cfg["ksize"],
                      hw=cfg["hw"], classes=cfg["classes"])
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--arch", default="cnn", choices=["cnn", "mlp"])
+    ap.add_argument("--arch", default="cnn", choices=["cnn", "mlp", "rnn"])
     ap.add_argument("--train", type=int, default=1200, help="training-set size (a multiple of 300)")
     ap.add_argument("--draws", type=int, default=16)
     ap.add_argument("--p", type=float, default=0.1)
