@@ -65,7 +65,7 @@ typedef enum { RAD_F32 = 0, RAD_BF16 = 1 } rad_dtype; /* accumulation is always 
  * s mod 32 of word (s / 32) mod 4 of call s / 128 (clear = +1); the store is
  * z_b = x_b R_b / sqrt(k), and dW = x~^T g with x~_b = z_b R_b^T / sqrt(k)
  * rebuilt row by row (never more than one layer's worth); k <= 38400.
- * The projection schemes serve linear layers and MLP models only. */
+ * The projection schemes serve linear layers and MLP and RNN models only. */
 typedef enum {
   RAD_EXACT = 0,
   RAD_BERNOULLI = 1,

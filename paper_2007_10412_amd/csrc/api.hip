@@ -318,8 +318,8 @@ extern "C" rad_status rad_store_create(rad_ctx* c, const rad_layer* L, int32_t s
   RAD_TRY(check_scheme(c, scheme, p));
   if (steps < 1) return fail(c, RAD_ERR_SHAPE, "steps must be >= 1");
   const bool proj = scheme == RAD_PROJECT_SHARED || scheme == RAD_PROJECT_PER_EXAMPLE;
-  if (proj && (steps != 1 || L->kind != RAD_LINEAR))
-    return fail(c, RAD_ERR_UNSUPPORTED, "the projection schemes serve single-step linear layers only");
+  if (proj && L->kind != RAD_LINEAR)
+    return fail(c, RAD_ERR_UNSUPPORTED, "the projection schemes serve linear layers only");
   if (scheme == RAD_PROJECT_PER_EXAMPLE && rad_fixed_k(p, L->d_in) > 38400)
     return fail(c, RAD_ERR_UNSUPPORTED, "a projection per example keeps at most 38400 numbers per row");
   if (scheme != RAD_EXACT && !proj) {
@@ -575,7 +575,7 @@ static rad_status store_pack(rad_ctx* c, rad_store* s, const void* x, int slot) 
   return RAD_OK;
 }
 
-static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* sm, const void* x);
+static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* sm, const void* x, int slot = 0);
 
 extern "C" rad_status rad_sample_pack(rad_ctx* c, const rad_sampling* sm, const void* x, rad_store* s,
                                       int32_t step_slot) {
@@ -772,14 +772,17 @@ static rad_status project_signs(rad_ctx* c, const rad_store* s, uint64_t seed, u
   return RAD_OK;
 }
 
-// store <- z = x R / sqrt(k): one more forward-family GEMM per layer
-static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* sm, const void* x) {
+// store (step slot `slot`) <- z = x R / sqrt(k): one more forward-family GEMM per layer.  The slots of a multi-step
+// store are drawn with consecutive step numbers: slot q with the step of slot 0 plus q, which is what the backward
+// pass regenerates R from.
+static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* sm, const void* x, int slot) {
+  void* zdst = static_cast<char*>(s->values) + (size_t)slot * s->rows * s->k_pitch * s->elem();
   if (s->scheme == kProjectPerExample) {       // every example times its own matrix, signs drawn in the kernel
     HIP_TRY(c, timed(c, "project_rows_fwd", [&](const char**) {
-      return launch_project_rows_fwd(x, s->dtype, s->rows, s->cols, s->k, s->k_pitch, s->scale, s->values,
+      return launch_project_rows_fwd(x, s->dtype, s->rows, s->cols, s->k, s->k_pitch, s->scale, zdst,
                                      (uint32_t)sm->seed, (uint32_t)(sm->seed >> 32), sm->stream_id, sm->step, c->stream);
     }));
-    s->proj_seed = sm->seed; s->proj_stream = sm->stream_id; s->proj_step = sm->step; s->proj_valid = true;
+    s->proj_seed = sm->seed; s->proj_stream = sm->stream_id; s->proj_step = sm->step - (uint32_t)slot; s->proj_valid = true;
     return RAD_OK;
   }
   void *Rm = nullptr, *Rt = nullptr;
@@ -787,25 +790,27 @@ static rad_status project_forward(rad_ctx* c, rad_store* s, const rad_sampling* 
   GemmArgs g = gemm_zero();
   g.M = s->rows; g.N = s->k_pitch; g.K = s->cols;
   g.A = x; g.lda = s->cols; g.B = Rm; g.ldb = s->k_pitch;
-  g.y = s->values; g.ldy = s->k_pitch; g.out_scale = s->scale;
+  g.y = zdst; g.ldy = s->k_pitch; g.out_scale = s->scale;
   RAD_TRY(run_gemm_call(c, s->dtype, kOpK, kOpMN, kEpiFwd, g));
-  s->proj_seed = sm->seed; s->proj_stream = sm->stream_id; s->proj_step = sm->step; s->proj_valid = true;
+  s->proj_seed = sm->seed; s->proj_stream = sm->stream_id; s->proj_step = sm->step - (uint32_t)slot; s->proj_valid = true;
   return RAD_OK;
 }
 
 // dW = beta dW + R (z^T g) / sqrt(k): the k x N product first, then R times it
 static rad_status project_dW(rad_ctx* c, const rad_store* s, const void* dy, int N, const uint32_t* bits,
-                             int bits_pitch, float* dW, int beta) {
+                             int bits_pitch, float* dW, int beta, int slot = 0) {
   if (!s->proj_valid) return fail(c, RAD_ERR_PARAM, "the store holds no projection yet");
+  const void* zsrc = static_cast<const char*>(s->values) + (size_t)slot * s->rows * s->k_pitch * s->elem();
+  const uint32_t step = s->proj_step + (uint32_t)slot;
   if (s->scheme == kProjectPerExample) {
     // x~ = z R_b^T / sqrt(k) row by row into a transient dense operand (one layer's worth, reused), then the
     // dense contraction x~^T g
     void* dense = nullptr;
     RAD_TRY(ws_get(c, WS_DENSE, (size_t)s->rows * s->cols * s->elem(), &dense));
     HIP_TRY(c, timed(c, "project_rows_bwd", [&](const char**) {
-      return launch_project_rows_bwd(s->values, s->dtype, s->rows, s->cols, s->k, s->k_pitch, s->scale, dense,
+      return launch_project_rows_bwd(zsrc, s->dtype, s->rows, s->cols, s->k, s->k_pitch, s->scale, dense,
                                      (uint32_t)s->proj_seed, (uint32_t)(s->proj_seed >> 32), s->proj_stream,
-                                     s->proj_step, c->stream);
+                                     step, c->stream);
     }));
     GemmArgs g = gemm_zero();
     g.M = s->cols; g.N = N; g.K = s->rows;
@@ -815,13 +820,13 @@ static rad_status project_dW(rad_ctx* c, const rad_store* s, const void* dy, int
     return run_gemm_call(c, s->dtype, kOpMN, kOpMN, kEpiStore, g);
   }
   void *Rm = nullptr, *Rt = nullptr;
-  RAD_TRY(project_signs(c, s, s->proj_seed, s->proj_stream, s->proj_step, &Rm, &Rt));
+  RAD_TRY(project_signs(c, s, s->proj_seed, s->proj_stream, step, &Rm, &Rt));
   void *T = nullptr, *Tb = nullptr;
   RAD_TRY(ws_get(c, WS_PROJ_T, (size_t)s->k_pitch * N * 4, &T));
   RAD_TRY(ws_get(c, WS_PROJ_TB, (size_t)s->k_pitch * N * s->elem(), &Tb));
   GemmArgs g = gemm_zero();
   g.M = s->k_pitch; g.N = N; g.K = s->rows;
-  g.A = s->values; g.lda = s->k_pitch;
+  g.A = zsrc; g.lda = s->k_pitch;
   g.B = dy; g.ldb = N; g.b_mask = bits; g.b_mask_pitch = bits_pitch;
   g.C = T; g.ldc = N; g.beta = 0; g.c_dtype = kF32;
   SplitPlan sp;
@@ -897,7 +902,7 @@ static int sparse_prefetch_for(const rad_store* s, int lanes_per_row) {
 // stores whose rows are planned one by one and kept with their indices
 static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* dy, int N, const uint32_t* bits,
                           int bits_pitch, float* dW, int beta, int n_slots = 1) {
-  if (s->project()) return project_dW(c, s, dy, N, bits, bits_pitch, dW, beta);
+  if (s->project()) return project_dW(c, s, dy, N, bits, bits_pitch, dW, beta, slot);
   GemmArgs g = gemm_zero();
   g.N = N; g.K = s->rows * n_slots;
   g.B = dy; g.ldb = N; g.b_mask = bits; g.b_mask_pitch = bits_pitch;
@@ -1490,7 +1495,6 @@ extern "C" rad_status rad_model_create_rnn(rad_ctx* c, int64_t batch, int64_t T,
   *out = nullptr;
   RAD_TRY(check_scheme(c, scheme, p));
   if (batch < 1 || T < 1 || d_input < 1 || hidden < 1 || classes < 1) return fail(c, RAD_ERR_SHAPE, "bad RNN shape");
-  if (scheme == RAD_PROJECT_SHARED || scheme == RAD_PROJECT_PER_EXAMPLE) return fail(c, RAD_ERR_UNSUPPORTED, "the projection schemes serve MLP models only");
   if (d_input > 8) return fail(c, RAD_ERR_UNSUPPORTED, "RNN input width above 8");
   if (T > (1 << 20)) return fail(c, RAD_ERR_SHAPE, "T above 2^20");
   rad_model* m = new rad_model();
@@ -1564,6 +1568,8 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
     void* y = m->act[t & 1];
     if (target->scheme == RAD_EXACT) {
       y = static_cast<char*>(target->values) + (t < T ? (size_t)(t - 1) * B * H * 4 : 0);
+    } else if (target->project()) {
+      // the projection of h_t is a GEMM of its own after the step (Appendix A, RNN details: "project")
     } else if (t < T && chunk_pack) {
       y = ring(t);
     } else { nv = store_view(target, t < T ? t - 1 : 0); next = &nv; }
@@ -1572,6 +1578,11 @@ static rad_status rnn_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
                           : chunk_pack ? static_cast<const void*>(ring(t - 1)) : m->act[(t - 1) & 1]);
     RAD_TRY(forward_gemm(c, kF32, B, H, t == 1 ? 0 : H, hin, H, W_hh, b, 1, y, m->rnn_bits + (size_t)(t - 1) * B * bp,
                          bp, next, xs + (size_t)(t - 1) * I, (int64_t)T * I, I, W_ih));
+    if (target->project()) {
+      rad_sampling sp = t < T ? *sm : s2;
+      if (t < T) sp.step = sm->step + (uint32_t)t + 1;      // slot t - 1 holds h_t, drawn with step = t + 1
+      RAD_TRY(project_forward(c, target, &sp, y, t < T ? t - 1 : 0));
+    }
     if (t < T && chunk_pack && (t % kRnnChunk == 0 || t == T - 1)) {
       const int t0 = (t - 1) / kRnnChunk * kRnnChunk + 1;          // first step of the chunk; its output is ring block 0
       StoreView v = store_view(s_hh, t0 - 1);

@@ -162,7 +162,7 @@ def test_unbiased_over_seeds(ctx):
 def test_unsupported_uses_are_status_codes(ctx):
     from paper_2007_10412_amd import binding as B
     with pytest.raises(B.RadError) as e:
-        B.rad_model_create_rnn(ctx, 8, 4, 1, 32, 10, SCHEME, 0.5)
+        B.rad_model_create_cnn(ctx, 4, [3, 8], [0], 3, 8, 8, 10, SCHEME, 0.5)      # linear layers and MLP / RNN models only
     assert e.value.status == B.RAD_ERR_UNSUPPORTED
     with pytest.raises(B.RadError) as e:
         B.rad_store_create(ctx, B.make_layer(8, 65000, 8, relu=False), SCHEME, 0.9)     # k above the limit

@@ -107,3 +107,20 @@ def test_rnn_hidden_width_whose_split_ranges_need_rounding(ctx):
     from paper_2007_10412_amd import synth
     d = synth.rnn(seed=6, batch=64, T=6, d_input=1, hidden=576, classes=10, identity=False)
     run_rnn(ctx, d, 1, 0.2, seed=3)
+
+
+@pytest.mark.parametrize("scheme", [6, 7])
+@pytest.mark.parametrize("T", [1, 7])
+def test_rnn_random_projections(ctx, scheme, T):
+    """"project" and "different project" of the recurrent experiments (Appendix A, RNN training details): every
+    step stores z_t = h_{t-1} R_t / sqrt(k) with a sign matrix drawn afresh per step (one per example for scheme
+    7), and dW_hh is formed from z_t and the regenerated R_t."""
+    from paper_2007_10412_amd import synth
+    d = synth.rnn(seed=30 + T, batch=8, T=T, d_input=1, hidden=64, classes=10, identity=False)
+    run_rnn(ctx, d, scheme, 0.25, seed=5)
+
+
+def test_paper_rnn_widths_projected(ctx):
+    from paper_2007_10412_amd import synth
+    d = synth.rnn(seed=78, batch=150, T=12, d_input=1, hidden=100, classes=10, identity=True)
+    run_rnn(ctx, d, 6, 0.1, seed=9)
