@@ -23,10 +23,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X published
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy kernel),
-# see profiles/train_step_mlp4096_bf16_hbm_traffic.txt; only for the default workload and kernel
-MEASURED_TRAFFIC = {("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_fwd_dma_256"): 249.8e6,
-                    ("mlp4096_bf16", "per_example", 0.1, "gemm_bf16_dw_sparse_256x256"): 156.0e6}
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy kernel): read
+# from the `traffic_bytes <workload> <scheme> <p> <kernel label> <bytes>` lines of this counter summary
+TRAFFIC_FILE = os.path.join("profiles", "train_step_mlp4096_bf16_hbm_traffic.txt")
+
+
+def measured_traffic(workload, scheme, p, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary, or None if it has no line for it."""
+    try:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
+            for ln in f:
+                w = ln.split()
+                if len(w) == 6 and w[0] == "traffic_bytes" and w[1:5] == [workload, scheme, "%g" % p, kernel]:
+                    return float(w[5])
+    except OSError:
+        pass
+    return None
+
+
 HBM_PEAK = 8000.0                          # GB/s
 TIMED_EVERY = 4                            # steps between two in which the dominant kernel is event-timed
 
@@ -46,7 +60,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32", "other", "pack_stream"],
+    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32", "other", "pack_stream", "ceilings"],
                     help="pde32: the reaction-diffusion study instead of a train step (a step = one gradient of each "
                          "of 256 problems); other: only the small configurations 1, 2, 3 and 5 (ms per train step)")
     ap.add_argument("--scheme", default="per_example", choices=sorted(SCHEMES))
@@ -67,6 +81,12 @@ def main():
         ctx = B.rad_ctx_create()
         print(json.dumps({"metric": "ms_per_train_step", "data": "synthetic", "n_gpus": 1,
                           "other_configs": other_configs(B, ctx, torch, synth)}))
+        B.rad_ctx_destroy(ctx)
+        return
+    if args.workload == "ceilings":        # what plain kernels reach on this device (HBM, MFMA, integer multiply)
+        ctx = B.rad_ctx_create()
+        print(json.dumps({"metric": "measured_ceilings", "data": "synthetic", "n_gpus": 1,
+                          "ceilings": ceilings(B, ctx, torch)}))
         B.rad_ctx_destroy(ctx)
         return
     if args.workload == "pack_stream":     # the stand-alone sampler on a 1 GiB stream, alone
@@ -185,7 +205,7 @@ def main():
         "avg_launch_ms": avg_ms, "launches": n_launch, "launches_per_step": per_step, "timed_every_steps": TIMED_EVERY,
         "share_of_step": avg_ms * per_step / ms_per_step if ms_per_step > 0 else None,
         "algorithmic_flops_per_launch": alg_flops, "executed_flops_per_launch": exe_flops,
-        "traffic": MEASURED_TRAFFIC.get((args.workload, args.scheme, p, big)),
+        "traffic": measured_traffic(args.workload, args.scheme, p, big), "traffic_source": TRAFFIC_FILE,
         "step_share_by_kernel_ms": {k_: v_ / 2 for k_, v_ in sorted(labels_ms.items())},
     }
 
@@ -240,7 +260,21 @@ def main():
             if nm in kern and kern[nm]["ms_per_step"] > 0:
                 kern[nm]["executed_tflops"] = f / (kern[nm]["ms_per_step"] * 1e-3) / 1e12
         out["kernels"] = kern
+        # the published peaks are what every `frac` above is against; beside them, what plain kernels reach on
+        # this very device, and the same fractions against those
+        ceil = ceilings(B, ctx, torch)
+        out["ceilings"] = ceil
+        mf = ceil["mfma_bf16_32x32x16_random_TFLOPs"] if dtype_name == "bf16" else ceil["mfma_f32_32x32x2_random_TFLOPs"]
+        if roofline["executed"]:
+            roofline["frac_of_measured_mfma_loop"] = roofline["executed"] / mf
+        if dw_kernel:
+            dw_kernel["executed_frac_of_measured_mfma_loop"] = dw_kernel["executed_tflops"] / mf
         out["pack_stream"] = pack_stream(B, ctx, torch, dtype_name)
+        for rule in ("bernoulli", "fixed_k_per_example"):
+            ps = out["pack_stream"][rule]
+            ps["pack"]["frac_of_measured_read"] = ps["pack"]["achieved"] / ceil["hbm_read_GBps"]
+            ps["whole"]["frac_of_measured_read"] = ps["whole"]["achieved"] / ceil["hbm_read_GBps"]
+            ps["plan"]["philox_mad_share_of_measured_int_rate"] = ps["plan"]["keys_per_s"] * 5 / (ceil["int_mad64_Tops"] * 1e12)
         out["optimizer"] = optimizer_stream(B, ctx, torch, dtype, params, grads)
         out["pde"] = pde_study(B, ctx, torch, steps=2, warmup=1, p=0.01)
         out["other_configs"] = other_configs(B, ctx, torch, synth)
@@ -356,6 +390,31 @@ def other_configs(B, ctx, torch, synth):
     res["config5_rnn_h1024_T784_f32_bernoulli"] = timed(
         lambda i: B.rad_train_step(ctx, m, B.make_sampling(B.RAD_BERNOULLI, 0.1, i), x, lab, params, grads), 3, 128)
     B.rad_model_destroy(m)
+    return res
+
+
+def ceilings(B, ctx, torch):
+    """Measured ceilings of this device (rad_probe_ceiling): HBM streaming read and copy of 1 GiB, register-resident
+    loops of the matrix instructions on random and on zero operands, independent integer multiply-adds."""
+    n = 1 << 28                                        # 1 GiB of fp32
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    a = torch.randn(n, device="cuda", dtype=torch.float32, generator=gen)
+    b = torch.empty(n, device="cuda", dtype=torch.float32)
+    ab = a[: 1 << 23].to(torch.bfloat16).contiguous()  # 16 MiB of random bf16 operands
+    zeros = torch.zeros(1 << 23, device="cuda", dtype=torch.bfloat16)
+    res = {"hbm_read_GBps": B.rad_probe_ceiling(ctx, 0, a, b, n * 4, 10) / 1e9,
+           "hbm_copy_GBps": B.rad_probe_ceiling(ctx, 1, a, b, n * 4, 10) / 1e9}
+    for name, kind in (("mfma_bf16_32x32x16", 2), ("mfma_bf16_16x16x32", 3)):
+        # alternate random and zero operands a few times: the clock follows the power drawn, with some lag
+        r, z = [], []
+        for _ in range(3):
+            r.append(B.rad_probe_ceiling(ctx, kind, ab, b, ab.numel() * 2, 100))
+            z.append(B.rad_probe_ceiling(ctx, kind, zeros, b, zeros.numel() * 2, 100))
+        res[name + "_random_TFLOPs"] = sum(r) / len(r) / 1e12
+        res[name + "_zeros_TFLOPs"] = sum(z) / len(z) / 1e12
+    res["mfma_f32_32x32x2_random_TFLOPs"] = B.rad_probe_ceiling(ctx, 4, a, b, 1 << 24, 100) / 1e12
+    res["int_mad64_Tops"] = B.rad_probe_ceiling(ctx, 5, a, b, 1 << 25, 100) / 1e12
+    res["published"] = {"hbm_GBps": HBM_PEAK, "mfma_bf16_TFLOPs": PEAK["bf16"], "mfma_f32_TFLOPs": PEAK["f32"]}
     return res
 
 

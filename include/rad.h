@@ -154,6 +154,22 @@ rad_status rad_ctx_timing_reset(rad_ctx* ctx);
  * are not GEMMs count zero. */
 rad_status rad_ctx_timing_read_flops(rad_ctx* ctx, const char* name, double* algorithmic, double* executed);
 
+/* Synchronises.  Measurement aid, not part of the method: what a kernel with
+ * nothing else to do reaches on this device for the three resources the hot
+ * path is bound by, so that a benchmark can quote its kernels against measured
+ * ceilings beside the published peaks.  kind: 0 streaming HBM read of `bytes`
+ * from `operands` (units: bytes), 1 copy of `bytes` from `operands` to `sink`
+ * (units: bytes read + written), 2 / 3 register-resident loops of the bf16
+ * matrix instructions 32x32x16 / 16x16x32 and 4 of the fp32 one (32x32x2) on
+ * the values found in `operands` (units: flop; random values run at a lower
+ * clock than zeros), 5 independent 32 x 32 + 64 -> 64-bit integer multiply-adds
+ * (units: multiply-adds).  operands / sink: DEVICE, 16-byte aligned; sink holds
+ * `bytes` for the copy and 1 KiB otherwise; `bytes` a multiple of 16 and at
+ * least 16 MiB.  Runs `reps` launches between two events and returns
+ * units per second. */
+rad_status rad_probe_ceiling(rad_ctx* ctx, int32_t kind, const void* operands, void* sink,
+                             uint64_t bytes, int32_t reps, double* units_per_s);
+
 /* Test hook, not part of the method: the keys of the NEXT draw only (the next
  * call that samples one store) are shifted right by `shift` bits (and the
  * Bernoulli threshold likewise) before selection, which makes equal keys

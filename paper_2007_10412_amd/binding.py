@@ -65,6 +65,7 @@ SIGNATURES = {
     "rad_ctx_timing_read_flops": (C.c_int, [P, C.c_char_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "rad_ctx_timing_reset": (C.c_int, [P]),
     "rad_debug_key_shift": (C.c_int, [P, C.c_int32]),
+    "rad_probe_ceiling": (C.c_int, [P, C.c_int32, P, P, C.c_uint64, C.c_int32, C.POINTER(C.c_double)]),
     "rad_store_create": (C.c_int, [P, C.POINTER(rad_layer), C.c_int32, C.c_double, C.c_int32, C.POINTER(P)]),
     "rad_store_destroy": (C.c_int, [P]),
     "rad_store_get_stats": (C.c_int, [P, P, C.POINTER(rad_store_stats)]),
@@ -194,6 +195,12 @@ def rad_ctx_timing_read_flops(ctx, name):
     a, x = C.c_double(), C.c_double()
     _check(ctx, lib().rad_ctx_timing_read_flops(ctx, None if name is None else name.encode(), C.byref(a), C.byref(x)))
     return a.value, x.value
+
+
+def rad_probe_ceiling(ctx, kind, operands, sink, nbytes, reps=10):
+    out = C.c_double(0.0)
+    _check(ctx, lib().rad_probe_ceiling(ctx, kind, _ptr(operands), _ptr(sink), nbytes, reps, C.byref(out)))
+    return out.value
 
 
 def rad_debug_key_shift(ctx, shift):

@@ -215,6 +215,35 @@ extern "C" rad_status rad_debug_key_shift(rad_ctx* c, int32_t shift) {
   return RAD_OK;
 }
 
+// measured ceilings: `reps` launches of one probe kernel between two events on the context's stream
+extern "C" rad_status rad_probe_ceiling(rad_ctx* c, int32_t kind, const void* operands, void* sink, uint64_t bytes,
+                                        int32_t reps, double* units_per_s) {
+  if (!c) return RAD_ERR_NULL;
+  if (!operands || !sink || !units_per_s) return fail(c, RAD_ERR_NULL, "null argument");
+  if (kind < 0 || kind > 5) return fail(c, RAD_ERR_PARAM, "unknown probe kind");
+  if (reps < 1 || reps > 10000) return fail(c, RAD_ERR_PARAM, "reps must be in [1, 10000]");
+  if (bytes < probe_min_bytes(kind) || bytes % 16 != 0 || bytes > (uint64_t(1) << 36))
+    return fail(c, RAD_ERR_SHAPE, "operand buffer too small for this probe, not a multiple of 16 bytes, or above 64 GiB");
+  if ((reinterpret_cast<uintptr_t>(operands) | reinterpret_cast<uintptr_t>(sink)) & 15)
+    return fail(c, RAD_ERR_PARAM, "buffers must be 16-byte aligned");
+  const int iters = 128;                 // MFMA loops: 128 iterations = the flops of one 4096^3 GEMM over the chip
+  hipEvent_t e0, e1;
+  HIP_TRY(c, hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(c, RAD_ERR_DEVICE, "event"); }
+  hipError_t e = hipSuccess;
+  for (int w = 0; w < 3 && e == hipSuccess; ++w) e = launch_probe(kind, operands, sink, bytes, iters, c->stream);
+  if (e == hipSuccess) e = hipEventRecord(e0, c->stream);
+  for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_probe(kind, operands, sink, bytes, iters, c->stream);
+  if (e == hipSuccess) e = hipEventRecord(e1, c->stream);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return hip_fail(c, e, "ceiling probe");
+  *units_per_s = probe_units(kind, bytes, iters) * reps / ((double)ms * 1e-3);
+  return RAD_OK;
+}
+
 // ------------------------------------------------------------------- store
 struct rad_store {
   int scheme = 0, dtype = 0;

@@ -174,4 +174,11 @@ hipError_t launch_unpack_bitmap(const StoreView& s, int dtype, void* dense, hipS
 // the values in `s` and the keep bitmap / offsets of a fresh plan
 hipError_t launch_reindex(const StoreView& s, int dtype, uint32_t* out_pairs, uint16_t* out_idx, hipStream_t st);
 
+// Ceiling probes (ceilings.hip): kind 0 HBM read, 1 HBM copy, 2 / 3 bf16 MFMA 32x32x16 / 16x16x32 register loops,
+// 4 fp32 MFMA 32x32x2, 5 integer 32 x 32 -> 64 multiply-adds.  a: operands (probe_min_bytes at least), b: sink
+// (copy: destination of `bytes`; else 1 KiB).
+double probe_units(int kind, uint64_t bytes, int iters);
+uint64_t probe_min_bytes(int kind);
+hipError_t launch_probe(int kind, const void* a, void* b, uint64_t bytes, int iters, hipStream_t st);
+
 }  // namespace rad
