@@ -1773,6 +1773,14 @@ static rad_status conv_gemm(rad_ctx* c, int B, int ci, int co, int h, int w, int
   g.A = src; g.B = W; g.ldb = co;
   g.cv_C = ci; g.cv_H = h; g.cv_W = w; g.cv_KH = ks; g.cv_KW = ks; g.cv_pad = (ks - 1) / 2; g.cv_N = co;
   g.bias = bias; g.relu = relu; g.y = y; g.bits = relu ? bits : nullptr; g.bits_pitch = bits_pitch;
+  // the patch-staged kernel where it serves the shape, else the general im2col GEMM
+  bool served = true;
+  HIP_TRY(c, timed(c, "conv_fwd_direct", [&](const char**) {
+    const hipError_t e = launch_conv_fwd_direct(g, c->stream);
+    if (e == hipErrorInvalidValue) { served = false; return hipSuccess; }
+    return e;
+  }));
+  if (served) return RAD_OK;
   return run_gemm_call(c, kF32, kOpIm2colRows, kOpMN, kEpiConv, g);
 }
 
@@ -1811,6 +1819,17 @@ static rad_status conv_dW_call(rad_ctx* c, const rad_store* s, int B, int ci, in
     HIP_TRY(c, timed(c, "unpack", [&](const char**) { return launch_unpack(v, kF32, dense, c->stream); }));
     xt = dense;
   }
+  if (const int splits = conv_dw_direct_splits(B, ci, co, h, w, ks)) {
+    const int64_t mn = (int64_t)ci * ks * ks * co;
+    void* part = nullptr;
+    RAD_TRY(ws_get(c, WS_SPLITK, (size_t)splits * mn * 4, &part));
+    HIP_TRY(c, timed(c, "conv_dw_direct", [&](const char**) {
+      return launch_conv_dw_direct(static_cast<const float*>(xt), g, static_cast<float*>(part), B, ci, co, h, w, ks, c->stream);
+    }));
+    HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
+      return launch_splitk_reduce(static_cast<const float*>(part), splits, mn, dW, 0, c->stream);
+    }));
+  } else {
   GemmArgs a = gemm_zero();
   a.M = ci * ks * ks; a.N = co; a.K = B * HW;
   a.A = xt; a.B = g;
@@ -1823,6 +1842,7 @@ static rad_status conv_dW_call(rad_ctx* c, const rad_store* s, int B, int ci, in
   HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
     return launch_splitk_reduce(static_cast<const float*>(part), a.k_splits, (int64_t)a.M * a.N, dW, 0, c->stream);
   }));
+  }
   if (dbias) {
     const int cs_splits = B < 32 ? B : 32;
     void* cs_part = nullptr;

@@ -174,6 +174,15 @@ hipError_t launch_unpack_bitmap(const StoreView& s, int dtype, void* dense, hipS
 // the values in `s` and the keep bitmap / offsets of a fresh plan
 hipError_t launch_reindex(const StoreView& s, int dtype, uint32_t* out_pairs, uint16_t* out_idx, hipStream_t st);
 
+// Convolutions through an LDS-staged input patch (conv.hip).  launch_conv_fwd_direct takes the arguments of the
+// im2col GEMM (A = NCHW input, B = W [(c,u,v)][co], cv_* geometry, the kEpiConv fields) and serves forward and dX;
+// launch_conv_dw_direct writes conv_dw_direct_splits(...) partial sums [ci*ks*ks][co] of dW from the dense x~ and
+// g = dL/dh (both NCHW).  hipErrorInvalidValue / 0 splits: shape not served, take the general im2col kernels.
+hipError_t launch_conv_fwd_direct(const GemmArgs& g, hipStream_t st);
+int conv_dw_direct_splits(int batch, int ci, int co, int H, int W, int ks);
+hipError_t launch_conv_dw_direct(const float* xt, const float* g, float* part, int batch, int ci, int co, int H, int W,
+                                 int ks, hipStream_t st);
+
 // Ceiling probes (ceilings.hip): kind 0 HBM read, 1 HBM copy, 2 / 3 bf16 MFMA 32x32x16 / 16x16x32 register loops,
 // 4 fp32 MFMA 32x32x2, 5 integer 32 x 32 -> 64 multiply-adds.  a: operands (probe_min_bytes at least), b: sink
 // (copy: destination of `bytes`; else 1 KiB).

@@ -225,6 +225,35 @@ __global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float4* __res
   if (beta) { const float4 o = out[i]; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
   out[i] = v;
 }
+// Many splits, few outputs (a convolution's dW: a few thousand numbers, a partial sum per workgroup of the kernel
+// before): 16 threads share an output vector, thread j adds splits j, j + 16, ... in order, and the 16 sums are
+// added pairwise in a fixed tree.  The result depends on `splits` alone, never on timing.
+__global__ __launch_bounds__(256) void splitk_reduce_wide_kernel(const float4* __restrict__ partial, int splits, int64_t n4,
+                                                                 float4* __restrict__ out, int beta) {
+  __shared__ float4 s_sum[16][17];
+  const int o = threadIdx.x & 15, j = threadIdx.x >> 4;
+  const int64_t i = (int64_t)blockIdx.x * 16 + o;
+  float4 v = {0.f, 0.f, 0.f, 0.f};
+  if (i < n4)
+    for (int s = j; s < splits; s += 16) {
+      const float4 t = partial[(size_t)s * n4 + i];
+      v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+    }
+  s_sum[j][o] = v;
+  __syncthreads();
+  for (int half = 8; half > 0; half >>= 1) {
+    if (j < half) {
+      const float4 a = s_sum[j][o], b = s_sum[j + half][o];
+      s_sum[j][o] = float4{a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w};
+    }
+    __syncthreads();
+  }
+  if (j == 0 && i < n4) {
+    float4 r = s_sum[0][o];
+    if (beta) { const float4 p = out[i]; r.x += p.x; r.y += p.y; r.z += p.z; r.w += p.w; }
+    out[i] = r;
+  }
+}
 // Sum of the splits of a compact dW (shared index set): partial [splits][rows][N] in a fixed order, tile row r
 // goes to output row row_map[r] (or r); V = float4 when N and ld are multiples of 4, else float
 template <typename V>
@@ -446,6 +475,11 @@ hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int 
 hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st) {
   if (n % 4 == 0 && ((reinterpret_cast<uintptr_t>(partial) | reinterpret_cast<uintptr_t>(out)) & 15) == 0) {
     const int64_t n4 = n / 4;
+    if (splits >= 32 && n4 < (int64_t)splits * 256) {      // too few outputs to fill the chip with a thread each
+      hipLaunchKernelGGL(splitk_reduce_wide_kernel, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, st,
+                         reinterpret_cast<const float4*>(partial), splits, n4, reinterpret_cast<float4*>(out), beta);
+      return hipGetLastError();
+    }
     hipLaunchKernelGGL(splitk_reduce4_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st,
                        reinterpret_cast<const float4*>(partial), splits, n4, reinterpret_cast<float4*>(out), beta);
   } else {
