@@ -10,7 +10,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librad_hip.so")
 SOURCES = ["api.hip", "plan.hip", "small.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_fwd.hip",
            "gemm_bf16_dx.hip", "gemm_bf16_dwd.hip", "gemm_bf16_sparse.hip", "gemm_bf16_sparse3.hip",
-           "gemm_bf16_sparse7.hip", "optim.hip", "project.hip", "pde.hip", "paths.hip", "ceilings.hip", "conv.hip"]
+           "gemm_bf16_sparse7.hip", "optim.hip", "project.hip", "pde.hip", "paths.hip", "ceilings.hip", "conv.hip", "gemm_f32_ks.hip"]
 # packed fp32 VALU forms are switched off: hipcc -O3 otherwise forms them on its own
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -723,6 +723,16 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
   // epilogue's work (bias, input term, ReLU, bits), and the next store's sample is packed by the pack kernel
   const int tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
   if (dtype == kF32 && tiles64 <= 64 && K >= 512) {
+    // whole 32 x 32 tiles: one launch, K split over the waves of a workgroup and added in LDS
+    GemmArgs gk = g;
+    gk.bias = bias; gk.relu = relu; gk.y = y; gk.ldy = N; gk.bits = relu ? bits : nullptr; gk.bits_pitch = bits_pitch;
+    gk.u = u; gk.u_ld = u_ld; gk.u_n = u_n; gk.V = V;
+    if (gemm_f32_ks_ok(gk, false)) {
+      HIP_TRY(c, timed(c, "gemm_f32_fwd_ks", [&](const char**) { return launch_gemm_f32_ks(gk, 1, c->stream); }));
+      if (next)
+        HIP_TRY(c, timed(c, "pack_f32", [&](const char**) { return launch_pack(y, kF32, *next, c->stream); }));
+      return RAD_OK;
+    }
     int splits = K / 128, want = 256 / tiles64;            // about one workgroup per CU
     if (want < 8) want = 8;
     if (want > 32) want = 32;
@@ -1042,6 +1052,12 @@ static rad_status dX_gemm(rad_ctx* c, int dtype, int M, int d_in, int d_out, con
   // fp32 with few tiles and a long contraction: split K, then add the partial sums under the output mask
   const int tiles64 = ((M + 63) / 64) * ((d_in + 63) / 64);
   if (dtype == kF32 && tiles64 <= 64 && d_out >= 512) {
+    GemmArgs gk = g;
+    gk.y = dX; gk.ldy = d_in; gk.c_mask = out_bits; gk.c_mask_pitch = out_pitch;
+    if (gemm_f32_ks_ok(gk, true)) {
+      HIP_TRY(c, timed(c, "gemm_f32_dx_ks", [&](const char**) { return launch_gemm_f32_ks(gk, 2, c->stream); }));
+      return RAD_OK;
+    }
     int splits = d_out / 128;
     if (splits > 8) splits = 8;
     const int ks = ((d_out + splits - 1) / splits + 31) / 32 * 32;   // whole K slices of the split kernels (32 deep)

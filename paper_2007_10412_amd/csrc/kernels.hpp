@@ -174,6 +174,12 @@ hipError_t launch_unpack_bitmap(const StoreView& s, int dtype, void* dense, hipS
 // the values in `s` and the keep bitmap / offsets of a fresh plan
 hipError_t launch_reindex(const StoreView& s, int dtype, uint32_t* out_pairs, uint16_t* out_idx, hipStream_t st);
 
+// fp32 GEMM with K split over the eight waves of a workgroup (gemm_f32_ks.hip), whole epilogue in the same launch.
+// finish 1: forward (A K-contiguous, B N-contiguous; bias, u V, ReLU, bits -> y); finish 2: dX (A and B K-contiguous;
+// c_mask -> y).  gemm_f32_ks_ok: whole 16 x 32 tiles, K % 64 == 0, 16-byte aligned rows, no loader masks.
+bool gemm_f32_ks_ok(const GemmArgs& g, bool b_k_contig);
+hipError_t launch_gemm_f32_ks(const GemmArgs& g, int finish, hipStream_t st);
+
 // Convolutions through an LDS-staged input patch (conv.hip).  launch_conv_fwd_direct takes the arguments of the
 // im2col GEMM (A = NCHW input, B = W [(c,u,v)][co], cv_* geometry, the kEpiConv fields) and serves forward and dX;
 // launch_conv_dw_direct writes conv_dw_direct_splits(...) partial sums [ci*ks*ks][co] of dW from the dense x~ and
