@@ -60,7 +60,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32", "other", "pack_stream", "ceilings"],
+    ap.add_argument("--workload", default="mlp4096_bf16", choices=sorted(WORKLOADS) + ["pde32", "other", "pack_stream", "ceilings", "library_gemm"],
                     help="pde32: the reaction-diffusion study instead of a train step (a step = one gradient of each "
                          "of 256 problems); other: only the small configurations 1, 2, 3 and 5 (ms per train step)")
     ap.add_argument("--scheme", default="per_example", choices=sorted(SCHEMES))
@@ -87,6 +87,12 @@ def main():
         ctx = B.rad_ctx_create()
         print(json.dumps({"metric": "measured_ceilings", "data": "synthetic", "n_gpus": 1,
                           "ceilings": ceilings(B, ctx, torch)}))
+        B.rad_ctx_destroy(ctx)
+        return
+    if args.workload == "library_gemm":    # the 4096^3 dX GEMM alone, next to the vendor library's GEMM of that shape
+        ctx = B.rad_ctx_create()
+        print(json.dumps({"metric": "gemm_4096_us", "data": "synthetic", "n_gpus": 1,
+                          "library_gemm": library_gemm(B, ctx, torch)}))
         B.rad_ctx_destroy(ctx)
         return
     if args.workload == "pack_stream":     # the stand-alone sampler on a 1 GiB stream, alone
@@ -264,6 +270,8 @@ def main():
         # this very device, and the same fractions against those
         ceil = ceilings(B, ctx, torch)
         out["ceilings"] = ceil
+        if dtype_name == "bf16":
+            out["library_gemm"] = library_gemm(B, ctx, torch)
         mf = ceil["mfma_bf16_32x32x16_random_TFLOPs"] if dtype_name == "bf16" else ceil["mfma_f32_32x32x2_random_TFLOPs"]
         if roofline["executed"]:
             roofline["frac_of_measured_mfma_loop"] = roofline["executed"] / mf
@@ -415,6 +423,46 @@ def ceilings(B, ctx, torch):
     res["mfma_f32_32x32x2_random_TFLOPs"] = B.rad_probe_ceiling(ctx, 4, a, b, 1 << 24, 100) / 1e12
     res["int_mad64_Tops"] = B.rad_probe_ceiling(ctx, 5, a, b, 1 << 25, 100) / 1e12
     res["published"] = {"hbm_GBps": HBM_PEAK, "mfma_bf16_TFLOPs": PEAK["bf16"], "mfma_f32_TFLOPs": PEAK["f32"]}
+    return res
+
+
+def library_gemm(B, ctx, torch):
+    """Context for the GEMM kernels, not a target: rad_backward_dX on a 4096 x 4096 x 4096 bf16 layer (no ReLU mask)
+    called alone in a loop, next to the vendor library's GEMM of the same shape and layout (torch.matmul), each on
+    the same buffers every call ("warm": operands stay in the last-level cache) and on ten rotating sets ("cold":
+    every call reads its operands from HBM, as a kernel inside a train step does)."""
+    n, sets = 4096, []
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for _ in range(10):
+        dy = torch.randn(n, n, device="cuda", generator=gen).to(torch.bfloat16)
+        W = (torch.randn(n, n, device="cuda", generator=gen) / 64.0).to(torch.bfloat16)
+        sets.append((dy, W, torch.empty(n, n, device="cuda", dtype=torch.bfloat16)))
+    L = B.make_layer(n, n, n, dtype=B.RAD_BF16, relu=False)
+    st = B.rad_store_create(ctx, L, B.RAD_FIXEDK_PER_EXAMPLE, 0.1)
+
+    def us_per_call(f, reps=1000):
+        for i in range(20):
+            f(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            f(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    res = {"shape": "dX[4096,4096] = dy[4096,4096] W[4096,4096]^T, bf16 in, fp32 accumulate, bf16 out",
+           "rad_backward_dX_warm_us": us_per_call(lambda i: B.rad_backward_dX(ctx, L, st, *sets[0])),
+           "rad_backward_dX_cold_us": us_per_call(lambda i: B.rad_backward_dX(ctx, L, st, *sets[i % 10])),
+           "library_warm_us": us_per_call(lambda i: torch.matmul(sets[0][0], sets[0][1].t(), out=sets[0][2])),
+           "library_cold_us": us_per_call(lambda i: torch.matmul(sets[i % 10][0], sets[i % 10][1].t(),
+                                                                 out=sets[i % 10][2]))}
+    B.rad_store_destroy(st)
+    flop = 2.0 * n ** 3
+    for k in list(res):
+        if k.endswith("_us"):
+            res[k.replace("_us", "_TFLOPs")] = flop / res[k] / 1e6
     return res
 
 

@@ -16,6 +16,8 @@
 // keeps both the MFMA fragment reads (32 consecutive rows, one unit column)
 // and the transposing loader's writes (rows 8 apart) spread over the banks.
 #pragma once
+#include <type_traits>
+#include <utility>
 #include "kernels.hpp"
 
 namespace rad {
@@ -422,8 +424,28 @@ template <int BM, int BN, int BK> struct Mma<F32Tag, BM, BN, BK> {
 };
 
 // ============================================================== epilogues
+// what the lane at quad position CTRL (a quad_perm pattern: 0xB1 = lane ^ 1, 0x4E = lane ^ 2) holds; and what
+// lane + 4 of the same row of 16 holds (zero for the last four)
+template <int CTRL> __device__ __forceinline__ uint32_t quad_perm(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, true);
+}
+__device__ __forceinline__ uint32_t row_shl4(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xF, 0xF, true);
+}
+
 __device__ __forceinline__ void put_elem(float* p, float v) { *p = v; }
 __device__ __forceinline__ void put_elem(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
+// two values to the storage dtype: bf16 pairs take the hardware conversion (round to nearest even, one
+// instruction for both)
+__device__ __forceinline__ void put_pair(float* p, float a, float b) { p[0] = a; p[1] = b; }
+__device__ __forceinline__ void put_pair(uint16_t* p, float a, float b) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  union { bf16x2 v; uint16_t h[2]; } u;
+  const f32x2 f = {a, b};
+  u.v = __builtin_convertvector(f, bf16x2);
+  p[0] = u.h[0]; p[1] = u.h[1];
+}
 __device__ __forceinline__ float get_elem(const float* p) { return *p; }
 __device__ __forceinline__ float get_elem(const uint16_t* p) { return bf16_bits_to_f32(*p); }
 
@@ -487,9 +509,10 @@ template <typename ElemT, int BM, int BN> struct FwdEpiLds {
   static constexpr int BYTES = BM * CP * (int)sizeof(ElemT);
 };
 
-// Forward epilogue.  The tile goes through LDS in the storage dtype, then every thread handles 16-byte
-// vectors of it (8 bf16 or 4 fp32 columns of one row): dense y is stored as whole vectors and the (y > 0)
-// bits of the vector are merged with those of the neighbouring lanes into one word of the ReLU bit array.
+// Forward epilogue.  Bias, low-rank term and ReLU are applied to the accumulators, which go through LDS in the
+// storage dtype; every thread then handles 16-byte vectors of the tile (8 bf16 or 4 fp32 columns of one row):
+// dense y is stored as whole vectors and the (y > 0) bits of the vector are merged with those of the
+// neighbouring lanes into one word of the ReLU bit array.
 // If the next layer's sample is packed here, thread r then walks tile row r: it loaded the row's keep words
 // and the store position of the row's first entry in this tile before the tile was staged (so those loads
 // cost no waiting), and writes the kept entries, which are consecutive in the store, one after the other.
@@ -503,6 +526,13 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
   static_assert(BM <= kGemmThreads, "one thread per tile row packs");
   const int lane = threadIdx.x & 63;
 
+  // everything the epilogue reads from global memory is asked for first
+  float bv[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn0 + j * 32 + (lane & 31);
+    bv[j] = (g.bias && col < g.N) ? g.bias[col] : 0.f;
+  }
   uint32_t kw[NW];
   uint32_t pos = 0u, row_first = 0u;
   const bool packs = g.pack && (int)threadIdx.x < BM && m0 + (int)threadIdx.x < g.M;
@@ -521,47 +551,76 @@ __device__ __forceinline__ void epilogue_fwd(const GemmArgs& g, floatx16 (&acc)[
       if (n0 / 32 + q < g.next.bm_pitch) kw[q] = bm_row[n0 / 32 + q];
   }
 
+  // The staging loop is the epilogue's arithmetic: per accumulator element it is kept to a multiply-add, a
+  // maximum, half a conversion and an LDS write at a constant offset from one base address per lane (the ReLU
+  // choice is a compile-time copy of the loop; the low-rank term exists in the fp32 build only, where the recurrent
+  // model uses it).
+  ElemT* const cbase = ct + (wm0 + 4 * (lane >> 5)) * CP + wn0 + (lane & 31);
+  const int row_base = m0 + wm0 + 4 * (lane >> 5);
+  auto stage = [&](auto RELU_) {
+    constexpr bool kRelu = decltype(RELU_)::value;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int lc = wn0 + j * 32 + (lane & 31);
-      const int col = n0 + lc;
-      const float bv = (g.bias && col < g.N) ? g.bias[col] : 0.f;
+      const int col = n0 + wn0 + j * 32 + (lane & 31);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int lrow = wm0 + i * 32 + acc_row(e, lane);
-        const int row = m0 + lrow;
-        float h = (g.out_scale != 0.f ? acc[i][j][e] * g.out_scale : acc[i][j][e]) + bv;
-        if (g.u_n > 0 && row < g.M && col < g.N)
-          for (int q = 0; q < g.u_n; ++q) h += g.u[(size_t)row * g.u_ld + q] * g.V[(size_t)q * g.N + col];
-        if (g.relu) h = h > 0.f ? h : 0.f;
-        put_elem(&ct[lrow * CP + lc], h);
+      for (int e0 = 0; e0 < 16; e0 += 2) {                // elements e0 and e0 + 1: rows r0 and r0 + 1 of this column
+        const int r0 = i * 32 + (e0 >> 2) * 8 + (e0 & 3);
+        float h[2];
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+          h[d] = (g.out_scale != 0.f ? acc[i][j][e0 + d] * g.out_scale : acc[i][j][e0 + d]) + bv[j];
+          if constexpr (std::is_same<ElemT, float>::value) {
+            const int row = row_base + r0 + d;
+            if (g.u_n > 0 && row < g.M && col < g.N)
+              for (int q = 0; q < g.u_n; ++q) h[d] += g.u[(size_t)row * g.u_ld + q] * g.V[(size_t)q * g.N + col];
+          }
+          if (kRelu) h[d] = h[d] > 0.f ? h[d] : 0.f;
+        }
+        ElemT st[2];
+        put_pair(st, h[0], h[1]);
+        cbase[r0 * CP + j * 32] = st[0];
+        cbase[(r0 + 1) * CP + j * 32] = st[1];
       }
     }
+  };
+  if (g.relu) stage(std::true_type()); else stage(std::false_type());
   __syncthreads();
 
+  // Every thread takes 16-byte vectors of the staged tile (VPL columns of one row): dense y is stored as whole
+  // vectors, and the (y > 0) bits of the vector, taken from the values as stored, are merged with those of the
+  // neighbouring lanes (the LPW lanes of a 32-column word are neighbours) by lane-permuting moves.
   ElemT* Y = reinterpret_cast<ElemT*>(g.y);
   const bool yvec = Y && (g.ldy % VPL) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
-  for (int c = threadIdx.x; c < BM * LPR; c += kGemmThreads) {      // same trip count for every lane
+  constexpr int NV = BM * LPR / kGemmThreads;
+  static_assert(BM * LPR % kGemmThreads == 0, "every thread takes the same number of vectors");
+#pragma unroll
+  for (int it = 0; it < NV; ++it) {
+    const int c = (int)threadIdx.x + it * kGemmThreads;
     const int r = c / LPR, ch = c % LPR;
     const int row = m0 + r, col = n0 + ch * VPL;
-    const bool live = row < g.M && col < g.N;
-    const int valid = live ? min(VPL, g.N - col) : 0;                // columns of this vector inside the output
+    const int valid = (row < g.M && col < g.N) ? min(VPL, g.N - col) : 0;   // columns of this vector inside the output
     const u32x4 raw = *reinterpret_cast<const u32x4*>(&ct[r * CP + ch * VPL]);
     const ElemT* re = reinterpret_cast<const ElemT*>(&raw);
     if (Y && valid > 0) {
       ElemT* dst = Y + (size_t)row * g.ldy + col;
-      if (yvec && valid == VPL) *reinterpret_cast<u32x4*>(dst) = raw;
-      else for (int e = 0; e < valid; ++e) dst[e] = re[e];
+      if (yvec && valid == VPL) {
+        *reinterpret_cast<u32x4*>(dst) = raw;
+      } else {                                             // (constant element numbers: the vector stays in registers)
+#pragma unroll
+        for (int e = 0; e < VPL; ++e) if (e < valid) dst[e] = re[e];
+      }
     }
     if (g.bits) {
-      uint32_t pbits = 0u;
+      uint32_t pbits = 0u;                                 // no branches: a bit per element, then the valid ones
 #pragma unroll
-      for (int e = 0; e < VPL; ++e) pbits |= (e < valid && get_elem(re + e) > 0.f) ? (1u << e) : 0u;
+      for (int e = 0; e < VPL; ++e) pbits |= (get_elem(re + e) > 0.f ? 1u : 0u) << e;
+      pbits &= (1u << valid) - 1u;
       uint32_t word = pbits << (VPL * (ch % LPW));
-#pragma unroll
-      for (int d = 1; d < LPW; d <<= 1) word |= (uint32_t)__shfl_xor((int)word, d);
+      word |= quad_perm<0xB1>(word);                       // lane ^ 1
+      word |= quad_perm<0x4E>(word);                       // lane ^ 2
+      if (LPW == 8) word |= row_shl4(word);                // lanes 0 .. 3 of the eight: the other quad's bits
       const int wi = col >> 5;
       if ((ch % LPW) == 0 && row < g.M && wi < g.bits_pitch) g.bits[(size_t)row * g.bits_pitch + wi] = word;
     }

@@ -466,36 +466,62 @@ struct Gemm3Smem {
 
 // Store epilogue of the dX family: the tile goes through LDS as bf16 so that global memory is written in
 // whole 16-byte vectors (a lane's accumulators are 4 rows of one column, which would be 2-byte stores), and
-// the ReLU bits of the layer below are applied eight columns at a time from one mask word per vector.
+// the ReLU bits of the layer below are applied eight columns at a time from one mask word per vector.  The mask
+// words of the vectors a thread will store are asked for before the staging, so they have arrived by then; the
+// staging itself is a conversion per two elements and LDS writes at constant offsets from one base per lane.
 template <int BM, int BN, int TM, int TN>
 __device__ __forceinline__ void epilogue_dx_staged(const GemmArgs& g, floatx16 (&acc)[TM][TN], uint16_t* ct,
                                                    int m0, int n0, int wm0, int wn0) {
   constexpr int CP = BN + 8;               // row pitch in elements: rows stay 16-byte aligned, banks shift by 4
+  constexpr int CPR = BN / 8;              // 16-byte vectors per tile row
+  constexpr int NV = BM * CPR / kGemmThreads;
+  static_assert(BM * CPR % kGemmThreads == 0, "every thread stores the same number of vectors");
   const int lane = threadIdx.x & 63;
+  uint32_t mw[(NV + 3) / 4];               // eight mask bits per vector, four vectors per register
+#pragma unroll
+  for (int q = 0; q < (NV + 3) / 4; ++q) mw[q] = 0u;
+  if (g.c_mask) {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int c = (int)threadIdx.x + it * kGemmThreads;
+      const int row = m0 + c / CPR, col = n0 + (c % CPR) * 8;
+      uint32_t wd = 0u;
+      if (row < g.M && col < g.N) wd = g.c_mask[(size_t)row * g.c_mask_pitch + (col >> 5)];
+      mw[it / 4] |= ((wd >> (col & 31)) & 0xFFu) << (8 * (it % 4));
+    }
+  }
   // the main loop ended with a barrier: no wave reads the operand stages any more
+  uint16_t* const cbase = ct + (wm0 + 4 * (lane >> 5)) * CP + wn0 + (lane & 31);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int e = 0; e < 16; ++e)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        ct[(wm0 + i * 32 + acc_row(e, lane)) * CP + wn0 + j * 32 + (lane & 31)] = f32_to_bf16_bits(acc[i][j][e]);
+      for (int e = 0; e < 16; e += 2) {
+        const int r0 = i * 32 + (e >> 2) * 8 + (e & 3);
+        uint16_t st[2];
+        put_pair(st, acc[i][j][e], acc[i][j][e + 1]);
+        cbase[r0 * CP + j * 32] = st[0];
+        cbase[(r0 + 1) * CP + j * 32] = st[1];
+      }
   __syncthreads();
-  constexpr int CPR = BN / 8;              // 16-byte vectors per tile row
   uint16_t* C = reinterpret_cast<uint16_t*>(g.C);
   const bool vec = (g.ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(g.C) & 15) == 0;
-  for (int c = threadIdx.x; c < BM * CPR; c += kGemmThreads) {
+#pragma unroll
+  for (int it = 0; it < NV; ++it) {
+    const int c = (int)threadIdx.x + it * kGemmThreads;
     const int r = c / CPR, ch = c % CPR;
     const int row = m0 + r, col = n0 + ch * 8;
     if (row >= g.M || col >= g.N) continue;
     u32x4 v = *reinterpret_cast<const u32x4*>(&ct[r * CP + ch * 8]);
-    if (g.c_mask) mask_bf16x8(v, g.c_mask[(size_t)row * g.c_mask_pitch + (col >> 5)] >> (col & 31));
+    if (g.c_mask) mask_bf16x8(v, mw[it / 4] >> (8 * (it % 4)));
     uint16_t* dst = C + (size_t)row * g.ldc + col;
     if (vec && col + 8 <= g.N) {
       *reinterpret_cast<u32x4*>(dst) = v;
     } else {
       const uint16_t* ve = reinterpret_cast<const uint16_t*>(&v);
-      for (int e = 0; e < 8 && col + e < g.N; ++e) dst[e] = ve[e];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) if (col + e < g.N) dst[e] = ve[e];    // (constant element numbers: v stays in registers)
     }
   }
 }
