@@ -257,11 +257,16 @@ def main():
             n, ms = B.rad_ctx_timing_read(ctx, pattern.get(nm, nm))
             if n:
                 kern[nm] = {"launches_per_step": n / reps, "ms_per_step": ms / reps}
+        if "pack" in kern and "unpack" in kern:        # "pack" also matched the unpack launches
+            kern["pack"] = {k_: kern["pack"][k_] - kern["unpack"][k_] for k_ in kern["pack"]}
+            if kern["pack"]["launches_per_step"] <= 0:
+                del kern["pack"]
         B.rad_ctx_timing(ctx, "")
         B.rad_ctx_timing_reset(ctx)
         fl = {"fwd": sum(2.0 * batch * dims[l] * dims[l + 1] for l in range(L)),
               "dx": sum(2.0 * batch * dims[l] * dims[l + 1] for l in range(1, L)),
-              "dw_sparse": sum(2.0 * batch * dims[l] * dims[l + 1] for l in range(L))}
+              "dw_sparse": sum(2.0 * batch * dims[l] * dims[l + 1] for l in range(L) if dims[l + 1] % 256 or "dw_dense" not in kern),
+              "dw_dense": sum(2.0 * batch * dims[l] * dims[l + 1] for l in range(L) if dims[l + 1] % 256 == 0)}
         for nm, f in fl.items():
             if nm in kern and kern[nm]["ms_per_step"] > 0:
                 kern[nm]["executed_tflops"] = f / (kern[nm]["ms_per_step"] * 1e-3) / 1e12

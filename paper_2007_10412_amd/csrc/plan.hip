@@ -593,6 +593,51 @@ __global__ __launch_bounds__(256) void unpack_kernel(StoreView s, T* __restrict_
   for (int64_t e = beg + threadIdx.x; e < end; e += 256) out[s.indices[s.idx_shared ? e - beg : e]] = vals[e];
 }
 
+// The same with the row assembled in LDS (cleared and scattered there) and written out once, in 16-byte vectors:
+// rows of up to 64 KB whose length is a whole number of vectors.
+template <typename T>
+__global__ __launch_bounds__(256) void unpack_lds_kernel(StoreView s, T* __restrict__ dense) {
+  extern __shared__ __align__(16) unsigned char s_row_raw[];
+  T* const srow = reinterpret_cast<T*>(s_row_raw);
+  const int row = blockIdx.x;
+  const int nvec = (int)((size_t)s.cols * sizeof(T) / 16);
+  u32x4* const svec = reinterpret_cast<u32x4*>(s_row_raw);
+  __shared__ int s_bo[260];                // bucket offsets of the row (cols <= 65535: at most 256 buckets + 1)
+  if (s.paired && (int)threadIdx.x <= s.nb)
+    s_bo[threadIdx.x] = s.bucket_off[(size_t)(row * s.plan_row_stride) * (s.nb + 1) + threadIdx.x];
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (int v = threadIdx.x; v < nvec; v += 256) svec[v] = z;
+  int64_t beg = s.row_ptr[row], end = s.row_ptr[row + 1];
+  if (end > s.capacity) end = s.capacity;
+  __syncthreads();
+  if (s.paired) {
+    const uint32_t* ent = reinterpret_cast<const uint32_t*>(s.values);
+    // entry e of the row lies in the bucket t with bo[t] <= e - beg < bo[t + 1]: every thread takes entries
+    // e = beg + tid, beg + tid + 256, ... (their loads go out first) and finds their buckets by walking the
+    // row's offsets, which are in LDS by then
+    int t = 0;
+    for (int64_t e0 = beg + threadIdx.x; e0 < end; e0 += 1024) {
+      uint32_t u[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) u[q] = e0 + 256 * q < end ? ent[e0 + 256 * q] : 0u;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int rel = (int)(e0 + 256 * q - beg);
+        if (e0 + 256 * q >= end) break;
+        while (t + 1 < s.nb && rel >= s_bo[t + 1]) ++t;
+        reinterpret_cast<uint16_t*>(srow)[pair_col(u[q], t)] = (uint16_t)(u[q] >> 16);
+      }
+    }
+  } else {
+    const T* vals = reinterpret_cast<const T*>(s.values);
+    if (s.idx_shared && end > beg + s.shared_k) end = beg + s.shared_k;
+    for (int64_t e = beg + threadIdx.x; e < end; e += 256) srow[s.indices[s.idx_shared ? e - beg : e]] = vals[e];
+  }
+  __syncthreads();
+  u32x4* const out = reinterpret_cast<u32x4*>(dense + (size_t)row * s.cols);
+  for (int v = threadIdx.x; v < nvec; v += 256) out[v] = svec[v];
+}
+
 // The same from the keep bitmap instead of stored columns (index-free stores whose bitmap of the current draw is
 // still there): entry e of a row belongs to the row's e-th kept column.
 template <typename T>
@@ -630,6 +675,12 @@ hipError_t launch_unpack_bitmap(const StoreView& s, int dtype, void* dense, hipS
 }
 
 hipError_t launch_unpack(const StoreView& s, int dtype, void* dense, hipStream_t st) {
+  const size_t row_bytes = (size_t)s.cols * (dtype == kF32 ? 4 : 2);
+  if (row_bytes % 16 == 0 && row_bytes <= 65536 && (reinterpret_cast<uintptr_t>(dense) & 15) == 0) {
+    if (dtype == kF32) hipLaunchKernelGGL(unpack_lds_kernel<float>, dim3(s.rows), dim3(256), row_bytes, st, s, (float*)dense);
+    else hipLaunchKernelGGL(unpack_lds_kernel<uint16_t>, dim3(s.rows), dim3(256), row_bytes, st, s, (uint16_t*)dense);
+    return hipGetLastError();
+  }
   if (dtype == kF32) hipLaunchKernelGGL(unpack_kernel<float>, dim3(s.rows), dim3(256), 0, st, s, (float*)dense);
   else hipLaunchKernelGGL(unpack_kernel<uint16_t>, dim3(s.rows), dim3(256), 0, st, s, (uint16_t*)dense);
   return hipGetLastError();
