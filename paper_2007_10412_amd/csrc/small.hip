@@ -327,6 +327,41 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float* __restric
   arg[q0 / 16] = word;
 }
 
+// The same for planes whose output rows are WO = 4, 8 or 16 wide: a thread's 16 consecutive outputs are whole
+// output rows, and their 64 inputs lie in one contiguous run of the plane, read as sixteen 16-byte vectors.
+template <int WO>
+__global__ __launch_bounds__(256) void maxpool_rows_kernel(const float* __restrict__ y, int64_t total,
+                                                           float* __restrict__ pooled, uint32_t* __restrict__ arg) {
+  const int64_t q0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 16;
+  if (q0 >= total) return;
+  // output q = (plane, oy, ox) row-major with rows of WO; its window starts at input offset 4 q - 2 (q % WO)
+  const floatx4* src = reinterpret_cast<const floatx4*>(y + 4 * q0);
+  float f[64];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const floatx4 v = src[i];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) f[4 * i + e] = v[e];
+  }
+  uint32_t word = 0;
+  float out[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    constexpr int W = 2 * WO;
+    const int i00 = (2 * (e / WO)) * W + 2 * (e % WO);
+    float best = f[i00]; uint32_t pos = 0;
+    if (f[i00 + 1] > best) { best = f[i00 + 1]; pos = 1; }
+    if (f[i00 + W] > best) { best = f[i00 + W]; pos = 2; }
+    if (f[i00 + W + 1] > best) { best = f[i00 + W + 1]; pos = 3; }
+    out[e] = best;
+    word |= pos << (2 * e);
+  }
+  floatx4* dst = reinterpret_cast<floatx4*>(pooled + q0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) dst[i] = floatx4{out[4 * i], out[4 * i + 1], out[4 * i + 2], out[4 * i + 3]};
+  arg[q0 / 16] = word;
+}
+
 // 2x2 average pool, stride 2 (the pooling of the convolutional architecture in Appendix A): one thread per
 // output; nothing is kept for the backward pass.
 __global__ __launch_bounds__(256) void avgpool_fwd_kernel(const float* __restrict__ y, int planes, int H, int W,
@@ -371,6 +406,42 @@ __global__ __launch_bounds__(256) void unpool_mask_kernel(const float* __restric
   }
   if (bits && !((bits[(size_t)b * bits_pitch + (f >> 5)] >> (f & 31)) & 1u)) v = 0.f;
   g[i] = v;
+}
+
+// The same, four consecutive x per thread (W a multiple of 4): one index decomposition, one mask word, one
+// 16-byte store.
+__global__ __launch_bounds__(256) void unpool_mask4_kernel(const float* __restrict__ dy, int batch, int C, int H, int W,
+                                                           int pool, const uint32_t* __restrict__ arg,
+                                                           const uint32_t* __restrict__ bits, int bits_pitch,
+                                                           float* __restrict__ g) {
+  const int64_t per = (int64_t)C * H * W;
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= batch * per) return;
+  const int b = (int)(i / per);
+  const int64_t f = i - (int64_t)b * per;
+  floatx4 v;
+  if (pool) {
+    const int Ho = H / 2, Wo = W / 2;
+    const int c = (int)(f / (H * W)), yx = (int)(f - (int64_t)c * H * W);
+    const int y = yx / W, x = yx - y * W;                  // x is a multiple of 4
+    const int64_t q = ((int64_t)(b * C + c) * Ho + y / 2) * Wo + x / 2;      // even: q and q + 1 share an arg word
+    const float d0 = dy[q], d1 = dy[q + 1];
+    if (pool == 1) {
+      const uint32_t pw = arg[q / 16] >> (2 * (q % 16));
+      const uint32_t p0 = pw & 3u, p1 = (pw >> 2) & 3u, top = (uint32_t)((y & 1) * 2);
+      v = floatx4{p0 == top ? d0 : 0.f, p0 == top + 1 ? d0 : 0.f, p1 == top ? d1 : 0.f, p1 == top + 1 ? d1 : 0.f};
+    } else {
+      v = floatx4{0.25f * d0, 0.25f * d0, 0.25f * d1, 0.25f * d1};
+    }
+  } else {
+    v = *reinterpret_cast<const floatx4*>(dy + i);
+  }
+  if (bits) {
+    const uint32_t m = bits[(size_t)b * bits_pitch + (f >> 5)] >> (f & 31);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) if (!((m >> e) & 1u)) v[e] = 0.f;
+  }
+  *reinterpret_cast<floatx4*>(g + i) = v;
 }
 
 // db[c] = sum_{b,yx} g[b,c,yx]; one workgroup per channel, fixed summation order
@@ -612,6 +683,15 @@ hipError_t launch_splitk_reduce_masked(const float* partial, int splits, int M, 
 hipError_t launch_maxpool_fwd(const float* y, int planes, int H, int W, float* pooled, uint32_t* arg, hipStream_t st) {
   const int64_t total = (int64_t)planes * (H / 2) * (W / 2);
   const int64_t threads = (total + 15) / 16;
+  const int Wo = W / 2;
+  const bool aligned = ((reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(pooled)) & 15) == 0;
+  if (aligned && H % 2 == 0 && W == 2 * Wo && total % 16 == 0 && (Wo == 4 || Wo == 8 || Wo == 16)) {
+    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    if (Wo == 4) hipLaunchKernelGGL(maxpool_rows_kernel<4>, grid, block, 0, st, y, total, pooled, arg);
+    else if (Wo == 8) hipLaunchKernelGGL(maxpool_rows_kernel<8>, grid, block, 0, st, y, total, pooled, arg);
+    else hipLaunchKernelGGL(maxpool_rows_kernel<16>, grid, block, 0, st, y, total, pooled, arg);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(maxpool_fwd_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, y, planes, H, W,
                      pooled, arg);
   return hipGetLastError();
@@ -626,6 +706,11 @@ hipError_t launch_avgpool_fwd(const float* y, int planes, int H, int W, float* p
 hipError_t launch_unpool_mask(const float* dy, int batch, int C, int H, int W, int pool, const uint32_t* arg,
                               const uint32_t* bits, int bits_pitch, float* g, hipStream_t st) {
   const int64_t n = (int64_t)batch * C * H * W;
+  if (W % 4 == 0 && H % 2 == 0 && ((reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(dy)) & 15) == 0) {
+    hipLaunchKernelGGL(unpool_mask4_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st, dy, batch, C, H, W,
+                       pool, arg, bits, bits_pitch, g);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(unpool_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dy, batch, C, H, W, pool, arg,
                      bits, bits_pitch, g);
   return hipGetLastError();
