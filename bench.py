@@ -143,7 +143,7 @@ def main():
     for i in range(2):
         step(500 + i)
     labels_ms = {}
-    for fam in ("fwd", "fwd_dma", "fwd_partial", "dx", "dx_dma", "dw_sparse", "dw_sparse_splitk", "dw_dense", "dw_dense_dma"):
+    for fam in ("fwd", "fwd_dma", "fwd_partial", "fwd_partial_dma", "dx", "dx_dma", "dw_sparse", "dw_sparse_splitk", "dw_dense", "dw_dense_dma"):
         for tile in ("64", "128", "256", "256x64", "256x128", "256x256"):
             nm = "gemm_%s_%s_%s" % (dtype_name, fam, tile)
             n, ms = B.rad_ctx_timing_read(ctx, nm)

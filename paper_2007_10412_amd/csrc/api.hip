@@ -995,12 +995,13 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     g.A = dense; g.lda = s->cols;
     return run_gemm_call(c, kF32, kOpMN, kOpMN, kEpiStore, g, alg);
   }
-  // Wide bf16 layers whose shape the direct-to-LDS dense kernel takes (whole 256 x 256 tiles, no loader mask): the
+  // Wide bf16 layers whose shape the direct-to-LDS dense kernel takes (whole 256-row tiles of x~, an output width
+  // of whole 16-byte vectors, no loader mask): the
   // store is unpacked into a transient dense x~ (one pass over 2 B D bytes) and contracted by that kernel, which
   // beats scattering every tile's entries into LDS in each of the N / 256 workgroups that need them (4096 x 4096,
-  // fraction 0.1: 10 + 88 us against 121 us).
-  const bool dense_pays = s->dtype == kBF16 && n_slots == 1 && !bits && s->cols % 256 == 0 && N % 256 == 0 &&
-                          (s->cols / 256) * (int64_t)(N / 256) >= 128 && s->rows % 8 == 0 && s->rows >= 1024 &&
+  // fraction 0.1: 14 + 92 us against 121 us).
+  const bool dense_pays = s->dtype == kBF16 && n_slots == 1 && !bits && s->cols % 256 == 0 && N % 8 == 0 &&
+                          (s->cols / 256) * (int64_t)((N + 255) / 256) >= 128 && s->rows % 8 == 0 && s->rows >= 1024 &&
                           (size_t)s->cols * 2 <= 65536 && (reinterpret_cast<uintptr_t>(dy) & 15) == 0;
   if (s->dtype == kBF16 && (dense_pays || g.sparse_prefetch > gemm_bf16_sparse_max_prefetch())) {
     // (also: stores dense enough that scattering into LDS loses to a plain contraction whatever the shape.)

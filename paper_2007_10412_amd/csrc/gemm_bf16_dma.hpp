@@ -1,6 +1,7 @@
 // bf16 GEMMs whose operand tiles go from global memory straight into LDS (global_load_lds_dwordx4): no
-// staging registers, no LDS store instructions, no address arithmetic in the loop.  256 x 256 tiles, M and N
-// multiples of 256; everything else takes the register-staged ring kernels.
+// staging registers, no LDS store instructions, no address arithmetic in the loop.  256 x 256 tiles, M a
+// multiple of 256 and N too unless B is M/N-contiguous (then N may end inside the last tile column, in whole
+// 16-byte vectors); everything else takes the register-staged ring kernels.
 //
 // A load instruction writes the 64 x 16 bytes of its wave to consecutive LDS addresses starting at M0,
 // so the tile layout is produced by choosing which global chunk each lane asks for: lane l of the load
@@ -54,7 +55,7 @@ template <int R> struct DmaOperandK64 {
   uint32_t voff[NI];
   const unsigned char* base;
   uint32_t wave_lds;
-  __device__ __forceinline__ void init(const void* p, int64_t ld, int r0, int kbeg) {
+  __device__ __forceinline__ void init(const void* p, int64_t ld, int r0, int kbeg, int) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int u = i * kGemmThreads + (int)threadIdx.x;
@@ -92,12 +93,15 @@ template <int R> struct DmaOperandMN64 {
   const unsigned char* base;
   int64_t slice_bytes;            // 64 k-rows
   uint32_t wave_lds;
-  __device__ __forceinline__ void init(const void* p, int64_t ld, int r0, int kbeg) {
+  // rmax: rows (columns of the matrix) the operand has, a multiple of 8.  A tile that reaches past them reads its
+  // last whole chunk again instead: those LDS columns only feed outputs that are never stored.
+  __device__ __forceinline__ void init(const void* p, int64_t ld, int r0, int kbeg, int rmax) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int cmax = (rmax - r0) / 8 - 1;                              // last whole chunk of this tile (>= 0)
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int k = 2 * (4 * i + w) + (lane >> 5);
-      const int c = (lane & 31) ^ (4 * (k & 3));                       // logical chunk at this LDS position
+      const int c = min((lane & 31) ^ (4 * (k & 3)), cmax);            // logical chunk at this LDS position
       voff[i] = (uint32_t)k * (uint32_t)ld * 2u + (uint32_t)c * 16u;
     }
     base = static_cast<const unsigned char*>(p) + ((int64_t)kbeg * ld + r0) * 2;
@@ -139,7 +143,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
   const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw);
   constexpr int kStageElems = S::STAGE / 2, kAElems = BM * BK;
 
-  const int tiles_n = g.N / BN, tiles_m = g.M / BM;
+  const int tiles_n = (g.N + BN - 1) / BN, tiles_m = g.M / BM;     // (N may be ragged for an M/N-contiguous B)
   const int T = tiles_m * tiles_n;
   int lin = blockIdx.x;
   if ((T & 7) == 0) lin = (lin & 7) * (T >> 3) + (lin >> 3);
@@ -167,8 +171,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
   const bool ragged = krem < BK;                       // its loads read zeros past K; the steady loop never issues it
   const int KTs = ragged ? KT - 1 : KT;
   LoadA la; LoadB lb;
-  la.init(g.A, g.lda, m0, kbeg);
-  lb.init(g.B, g.ldb, n0, kbeg);
+  la.init(g.A, g.lda, m0, kbeg, g.M);
+  lb.init(g.B, g.ldb, n0, kbeg, g.N);
 
   // load number Q (0 .. 15) of slice s into stage st: A and B alternate
   auto issue = [&](auto Q_, int st, int s) {
@@ -331,8 +335,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dma64_bf16_kernel(GemmArgs 
 #undef RAD_K3_DMA
   // every wave is past the last barrier only after all its reads of the stages; nothing is in flight
   __syncthreads();
+  if constexpr (EPI == kEpiStore) {
+    if (g.k_splits > 1 && g.split_stride > 0) {            // this split's partial sums go, as fp32, to an array of its own
+      GemmArgs gs = g;
+      gs.C = static_cast<float*>(g.C) + (int64_t)blockIdx.y * g.split_stride;
+      if (g.N % BN) epilogue_store<TM, TN, float, true, false, false, false>(gs, acc, m0, n0, wm0, wn0);
+      else epilogue_store<TM, TN, float, false, false, false, false>(gs, acc, m0, n0, wm0, wn0);
+      return;
+    }
+  }
   if constexpr (EPI == kEpiStore && AKIND == kOpMN) {      // dW from a dense store: fp32 out
-    epilogue_store_dispatch<kOpMN, TM, TN, uint16_t, false>(g, acc, m0, n0, wm0, wn0);
+    if (g.N % BN) epilogue_store_dispatch<kOpMN, TM, TN, uint16_t, true>(g, acc, m0, n0, wm0, wn0);
+    else epilogue_store_dispatch<kOpMN, TM, TN, uint16_t, false>(g, acc, m0, n0, wm0, wn0);
   } else if constexpr (EPI == kEpiStore) {
     epilogue_dx_staged<BM, BN, TM, TN>(g, acc, smem, m0, n0, wm0, wn0);
   } else {

@@ -4,12 +4,12 @@
 namespace rad {
 
 hipError_t launch_gemm_bf16_dwd(const GemmArgs& g, hipStream_t st, const char** name) {
-  // a split K needs an array per split (the ring kernels' epilogue; the direct-to-LDS kernel has none)
+  // a split K needs an array per split
   if (g.k_splits > 1 && g.split_stride <= 0) { if (name) *name = ""; return hipErrorInvalidValue; }
   // 256x256 tiles (one workgroup per CU) when they give at least half a wave of workgroups; otherwise the
   // widest tile that still gives every CU a workgroup
   if (tiles_of(g, 256, 256) >= 128) {
-    if (g.k_splits <= 1 && gemm_dma_ok<kOpMN, kOpMN, 256, 256>(g)) {
+    if (gemm_dma_ok<kOpMN, kOpMN, 256, 256>(g)) {
       if (name) *name = "gemm_bf16_dw_dense_dma_256";
       return run_gemm_dma<kOpMN, kOpMN, kEpiStore, 256, 256>(g, st);
     }

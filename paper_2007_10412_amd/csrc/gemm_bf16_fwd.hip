@@ -25,8 +25,12 @@ hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t st, const char** 
 // x W for a narrow layer whose K range is split over several workgroups per 256x256 tile: fp32 partial sums,
 // one array per split (bias and the cast to the layer's dtype happen in the reduction kernel)
 hipError_t launch_gemm_bf16_fwd_partial(const GemmArgs& g, hipStream_t st, const char** name) {
+  if (g.k_splits <= 1 || g.split_stride <= 0) { if (name) *name = ""; return hipErrorInvalidValue; }
+  if (gemm_dma_ok<kOpK, kOpMN, 256, 256>(g)) {
+    if (name) *name = "gemm_bf16_fwd_partial_dma_256";
+    return run_gemm_dma<kOpK, kOpMN, kEpiStore, 256, 256>(g, st);
+  }
   if (name) *name = "gemm_bf16_fwd_partial_256";
-  if (g.k_splits <= 1 || g.split_stride <= 0) return hipErrorInvalidValue;
   return run_gemm3<kOpK, kOpMN, kEpiStore, 256, 256, 0, false, false>(g, st);
 }
 

@@ -83,12 +83,16 @@ hipError_t run_gemm3_variant(const GemmArgs& g, hipStream_t st) {
   return launch_gemm_kernel(kern, dim3(tiles_m * tiles_n, g.k_splits > 1 ? g.k_splits : 1), smem, st, g);
 }
 
-// ---- bf16 kernels whose operands go from global memory straight into LDS: whole 256 x 256 tiles, rows that are
-// whole 16-byte vectors, no loader masks; K need not be a multiple of the 64-deep slice.
+// ---- bf16 kernels whose operands go from global memory straight into LDS: whole 256-row tiles (a ragged last
+// tile column only for an M/N-contiguous B), rows that are whole 16-byte vectors, no loader masks; K need not be
+// a multiple of the 64-deep slice; a split K (whole slices per split) stores fp32 partial sums per split.
 template <int AKIND, int BKIND, int BM, int BN>
 bool gemm_dma_ok(const GemmArgs& g) {
   if (g.a_mask || g.b_mask || g.row_map || g.m_load > g.M) return false;
-  if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.M % BM || g.N % BN || g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
+  // whole tiles; an M/N-contiguous B may end inside its last tile column (whole 16-byte chunks), the loads there
+  // are clamped and the epilogues guard the stores
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.M % BM || g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
+  if (BKIND == kOpMN ? g.N % 8 != 0 : g.N % BN != 0) return false;
   if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.B)) & 15) return false;
   if (g.k_splits > 1 && g.k_split % 64 != 0) return false;
   // per-thread offsets inside a tile are 32-bit byte offsets
@@ -108,7 +112,7 @@ hipError_t run_gemm_dma(const GemmArgs& g, hipStream_t st) {
     if (e != hipSuccess) return e;
     prepared = true;
   }
-  return launch_gemm_kernel(kern, dim3((g.M / BM) * (g.N / BN), g.k_splits > 1 ? g.k_splits : 1), smem, st, g);
+  return launch_gemm_kernel(kern, dim3((g.M / BM) * ((g.N + BN - 1) / BN), g.k_splits > 1 ? g.k_splits : 1), smem, st, g);
 }
 
 // ragged shapes whose every operand access is still a whole 16-byte vector: pitches, K and the extent along

@@ -150,3 +150,63 @@ def test_dW_with_segments_longer_than_the_register_budget(ctx, N):
     finally:
         B.rad_debug_key_shift(ctx, 0)
         B.rad_store_destroy(st)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_forward_wide_layer_ragged_width(ctx, relu):
+    """A 2048 x 320 x 4040 layer: 128 tile columns' worth of workgroups whose last tile column ends after 200 of
+    its 256 columns (whole 16-byte vectors).  The loads of that tile are clamped to the operand and the epilogue
+    guards its stores: y element by element, the ReLU bits, and the packed sample of x."""
+    from paper_2007_10412_amd import binding as B
+    from tests.gpu_util import dev, host, empty, unpack_bits, rel_err, assert_bits_match, TOL
+    Bt, d_in, N = 2048, 320, 4040
+    rng = np.random.default_rng(77)
+    x = bf16_data(rng, (Bt, d_in))
+    W = bf16_data(rng, (d_in, N), 1.0 / np.sqrt(d_in))
+    bias = rng.standard_normal(N).astype(np.float32)
+    print("forward B=%d D=%d N=%d relu=%d" % (Bt, d_in, N, relu), flush=True)
+    L = B.make_layer(Bt, d_in, N, dtype=B.RAD_BF16, relu=relu, has_bias=True)
+    st = B.rad_store_create(ctx, L, B.RAD_FIXEDK_PER_EXAMPLE, 0.25)
+    try:
+        y = empty((Bt, N), B.RAD_BF16)
+        y.fill_(7.0)        # nothing outside the N columns of a row may be written: the buffer is exactly [Bt, N]
+        B.rad_forward_sample(ctx, L, B.make_sampling(B.RAD_FIXEDK_PER_EXAMPLE, 0.25, 7), dev(x, B.RAD_BF16),
+                             dev(W, B.RAD_BF16), dev(bias), y, st)
+        h, oy, _ = R.linear_forward(x, W, bias, relu, B.RAD_BF16)
+        assert rel_err(host(y), oy) < TOL[B.RAD_BF16]
+        assert np.max(np.abs(host(y) - oy)) <= 2.0 ** -7 * max(1.0, np.max(np.abs(oy)))
+        if relu:
+            bits = unpack_bits(B.rad_store_export_bits(ctx, st, Bt, N), N)
+            assert_bits_match(bits, h, "relu bits")
+    finally:
+        B.rad_store_destroy(st)
+
+
+@pytest.mark.parametrize("N,beta", [(2048, 0.0), (2048, 1.0), (2040, 0.0)])
+def test_dW_from_a_wide_store_through_the_dense_operand(ctx, N, beta):
+    """dW of a 1024 x 4096 x N layer without ReLU from a sampled store (fraction 0.1): wide enough that the store is
+    unpacked into a transient dense operand and contracted by the dense kernel (N = 2040: its last tile column is
+    ragged; beta = 1: the accumulating form).  Against the oracle on the store the GPU itself packed."""
+    from paper_2007_10412_amd import binding as B
+    from tests.gpu_util import dev, host, empty, assert_grad_close, TOL
+    Bt, D = 1024, 4096
+    rng = np.random.default_rng(500 + N)
+    x = bf16_data(rng, (Bt, D))
+    W = bf16_data(rng, (D, N), 1.0 / 64)
+    dy = bf16_data(rng, (Bt, N))
+    print("dW dense route B=%d D=%d N=%d beta=%g" % (Bt, D, N, beta), flush=True)
+    L = B.make_layer(Bt, D, N, dtype=B.RAD_BF16, relu=False)
+    st = B.rad_store_create(ctx, L, B.RAD_FIXEDK_PER_EXAMPLE, 0.1)
+    try:
+        y = empty((Bt, N), B.RAD_BF16)
+        B.rad_forward_sample(ctx, L, B.make_sampling(B.RAD_FIXEDK_PER_EXAMPLE, 0.1, 3), dev(x, B.RAD_BF16),
+                             dev(W, B.RAD_BF16), None, y, st)
+        _, _, _, xt = R.sample_pack(x, B.RAD_FIXEDK_PER_EXAMPLE, 0.1, 3, 0, 0, B.RAD_BF16)
+        want = R.backward_dW(xt, dy, np.ones((Bt, N), dtype=bool))
+        gW = empty((D, N))
+        start = rng.standard_normal((D, N)).astype(np.float32)
+        gW.copy_(dev(start))
+        B.rad_backward_dW(ctx, L, st, dev(dy, B.RAD_BF16), gW, None, beta)
+        assert_grad_close(host(gW), want + beta * start, TOL[B.RAD_BF16], Bt, "dW")
+    finally:
+        B.rad_store_destroy(st)
