@@ -707,13 +707,15 @@ static rad_status forward_gemm(rad_ctx* c, int dtype, int M, int N, int K, const
     const int ks = ((K + splits - 1) / splits + 31) / 32 * 32;
     splits = (K + ks - 1) / ks;
     if (splits > 1) {
+      // the rows of a partial array are padded to whole 256-column tiles: aligned stores whatever N is
+      const int64_t pld = (int64_t)(N + 255) / 256 * 256;
       void* part = nullptr;
-      RAD_TRY(ws_get(c, WS_SPLITK, (size_t)splits * M * N * 4, &part));
-      g.C = part; g.ldc = N; g.c_dtype = kF32;
-      g.k_split = ks; g.k_splits = splits; g.split_stride = (int64_t)M * N;
+      RAD_TRY(ws_get(c, WS_SPLITK, (size_t)splits * M * pld * 4, &part));
+      g.C = part; g.ldc = pld; g.c_dtype = kF32;
+      g.k_split = ks; g.k_splits = splits; g.split_stride = (int64_t)M * pld;
       RAD_TRY(run_gemm_call(c, dtype, kOpK, kOpMN, kEpiStore, g));
       HIP_TRY(c, timed(c, "splitk_bias", [&](const char**) {
-        return launch_splitk_bias(static_cast<const float*>(part), splits, M, N, bias, y, dtype, c->stream);
+        return launch_splitk_bias(static_cast<const float*>(part), splits, M, N, bias, y, dtype, c->stream, pld);
       }));
       return RAD_OK;
     }
@@ -935,12 +937,29 @@ static int sparse_prefetch_for(const rad_store* s, int lanes_per_row) {
   return (int)std::ceil((mean + 6.0 * std::sqrt(mean)) / lanes_per_row);   // overflow beyond this is rare and handled apart
 }
 
+// whether dW_gemm with rows of dy dy_ld apart runs the store-fed kernel with a split K (the one path that takes a
+// pitched dy): a bf16 store with its own columns per row, sparse enough for that kernel, too few tiles to fill the chip
+static bool dw_pitched_ok(const rad_store* s, int N, int dy_ld) {
+  if (dy_ld <= N || dy_ld % 256 || s->dtype != kBF16 || s->project() || s->steps != 1) return false;
+  if (s->scheme == RAD_EXACT || s->scheme == RAD_FIXEDK_SHARED) return false;
+  if (sparse_prefetch_for(s, 8) > gemm_bf16_sparse_max_prefetch()) return false;
+  const int64_t tiles = ((s->cols + 255) / 256) * (int64_t)(dy_ld / 256);
+  return tiles < 128 && 256 / tiles >= 2 && s->rows >= 2048;
+}
+
 // dW = beta dW + store(slot)^T (dy masked by bits)
 // n_slots > 1: the contraction runs over that many consecutive step slots of a multi-step store at once (their
 // rows lie one after another in the store; dy then holds the rows of all those steps in the same order); only for
 // stores whose rows are planned one by one and kept with their indices
+// dy_ld > N (see dw_pitched_ok): the rows of dy are dy_ld apart, a multiple of 256, and zero past column N; the
+// contraction then runs on whole tiles of dy_ld columns and only the reduction of its split-K partial sums knows N
+static bool dw_pitched_ok(const rad_store* s, int N, int dy_ld);
 static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* dy, int N, const uint32_t* bits,
-                          int bits_pitch, float* dW, int beta, int n_slots = 1) {
+                          int bits_pitch, float* dW, int beta, int n_slots = 1, int dy_ld = 0) {
+  if (dy_ld > 0 && dy_ld != N && (n_slots != 1 || bits || !dw_pitched_ok(s, N, dy_ld)))
+    return fail(c, RAD_ERR_PARAM, "pitched dy outside the split-K path of dW");
+  const int n_out = N;
+  if (dy_ld > N) N = dy_ld;
   if (s->project()) return project_dW(c, s, dy, N, bits, bits_pitch, dW, beta, slot);
   GemmArgs g = gemm_zero();
   g.N = N; g.K = s->rows * n_slots;
@@ -1033,7 +1052,12 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     }
   }
   RAD_TRY(run_gemm_call(c, s->dtype, kOpSparse, kOpMN, kEpiStore, g, alg));
-  if (split)
+  if (split && n_out != N)
+    HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
+      return launch_splitk_reduce_rows(static_cast<const float*>(g.C), g.k_splits, g.split_stride, g.M, n_out, nullptr, dW,
+                                       n_out, beta, c->stream, N);
+    }));
+  else if (split)
     HIP_TRY(c, timed(c, "splitk_reduce", [&](const char**) {
       return launch_splitk_reduce(static_cast<const float*>(g.C), g.k_splits, g.split_stride, dW, beta, c->stream);
     }));
@@ -1041,7 +1065,7 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
     // the bf16 kernel keeps a fixed number of entries per (row, bucket) in registers; the rest, if any, here
     const int cap = gemm_bf16_sparse_cap(g.sparse_prefetch);
     HIP_TRY(c, timed(c, "dw_overflow", [&](const char**) {
-      return launch_dw_overflow(g.sa, s->rows, dy, s->dtype, N, bits, bits_pitch, dW, cap, s->max_seg, c->stream);
+      return launch_dw_overflow(g.sa, s->rows, dy, s->dtype, n_out, bits, bits_pitch, dW, cap, s->max_seg, c->stream, N);
     }));
   }
   return RAD_OK;
@@ -1052,10 +1076,10 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
 // the chain hands g = dL/dh to the next dW and dX without loader masks
 static rad_status dX_gemm(rad_ctx* c, int dtype, int M, int d_in, int d_out, const void* dy, const uint32_t* bits,
                           int bits_pitch, const void* W, void* dX, const uint32_t* out_bits = nullptr,
-                          int out_pitch = 0) {
+                          int out_pitch = 0, int dy_ld = 0) {
   GemmArgs g = gemm_zero();
   g.M = M; g.N = d_in; g.K = d_out;
-  g.A = dy; g.lda = d_out; g.a_mask = bits; g.a_mask_pitch = bits_pitch;
+  g.A = dy; g.lda = dy_ld > 0 ? dy_ld : d_out; g.a_mask = bits; g.a_mask_pitch = bits_pitch;
   g.B = W; g.ldb = d_out;
   // fp32 with few tiles and a long contraction: split K, then add the partial sums under the output mask
   const int tiles64 = ((M + 63) / 64) * ((d_in + 63) / 64);
@@ -1175,12 +1199,12 @@ extern "C" rad_status rad_backward_dX(rad_ctx* c, const rad_layer* L, const rad_
 }
 
 static rad_status softmax_call(rad_ctx* c, const void* logits, const int32_t* labels, int rows, int classes, int dtype,
-                               void* dlogits, float* loss_dev) {
+                               void* dlogits, float* loss_dev, int dz_ld = 0) {
   void* rl = nullptr;
   RAD_TRY(ws_get(c, WS_ROWLOSS, (size_t)rows * 4, &rl));
   HIP_TRY(c, timed(c, "softmax_ce", [&](const char**) {
     return launch_softmax_ce(logits, labels, rows, classes, dtype, dlogits, static_cast<float*>(rl), loss_dev,
-                             c->stream);
+                             c->stream, dz_ld);
   }));
   return RAD_OK;
 }
@@ -1338,6 +1362,7 @@ struct rad_model {
   void* act[2] = {nullptr, nullptr};    // transient dense activations (ping-pong)
   void* dyb[2] = {nullptr, nullptr};    // transient upstream gradients (ping-pong)
   void* logits = nullptr;
+  int last_pitch = 0;                   // MLP: row pitch of the loss gradient when it is padded to whole tiles, else 0
   int* flags = nullptr;                 // [n stores] overflow flags, then [n stores] segment maxima
   // RNN
   int64_t T = 0, d_input = 0, hidden = 0, classes = 0;
@@ -1414,6 +1439,18 @@ extern "C" rad_status rad_model_create_mlp(rad_ctx* c, int32_t dtype, int64_t ba
     if (st != RAD_OK) { rad_model_destroy(m); return st; }
     m->stores.push_back(s);
     if (dims[l + 1] > widest) widest = dims[l + 1];
+  }
+  // A last layer whose width is not a multiple of 256 (class scores): its loss gradient is kept with rows padded to
+  // whole tiles (zeros), so that dW of that layer runs on whole 256-column tiles of aligned rows; dX reads the same
+  // rows and only the reduction of dW's split-K partial sums knows the real width.
+  {
+    const int64_t n_last = dims[n_layers], np = (n_last + 255) / 256 * 256;
+    // (models with biases keep the plain layout: the bias gradient's column sums read rows of the real width)
+    if (!has_bias && n_last % 256 != 0 && n_last % 8 == 0 && np / 8 <= 128 &&
+        dw_pitched_ok(m->stores.back(), (int)n_last, (int)np)) {
+      m->last_pitch = (int)np;
+      if (np > widest) widest = np;
+    }
   }
   const size_t bytes = (size_t)batch * widest * m->elem();
   bool ok = true;
@@ -1518,7 +1555,8 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
     if (pack_after) RAD_TRY(store_pack(c, m->stores[(size_t)l + 1], y, 0));
     a_in = y;
   }
-  RAD_TRY(softmax_call(c, m->logits, labels, B, (int)m->dims[(size_t)Lc], m->dtype, m->dyb[0], loss_host ? c->loss_dev : nullptr));
+  RAD_TRY(softmax_call(c, m->logits, labels, B, (int)m->dims[(size_t)Lc], m->dtype, m->dyb[0], loss_host ? c->loss_dev : nullptr,
+                       m->last_pitch));
 
   // backward from the stores.  dyb holds g = dL/dh of the layer at hand: the loss gradient for the last
   // layer (no ReLU), and below it the dX of the layer above, masked by this layer's ReLU bits in that
@@ -1527,14 +1565,15 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
   for (int l = Lc - 1; l >= 0; --l) {
     rad_store* s = m->stores[(size_t)l];
     const int N = (int)m->dims[(size_t)l + 1], D = (int)m->dims[(size_t)l];
-    RAD_TRY(dW_gemm(c, s, 0, m->dyb[cur], N, nullptr, 0, static_cast<float*>(grads[l * per]), 0));
+    const int g_ld = (l == Lc - 1 && m->last_pitch) ? m->last_pitch : 0;      // row pitch of this layer's g, if padded
+    RAD_TRY(dW_gemm(c, s, 0, m->dyb[cur], N, nullptr, 0, static_cast<float*>(grads[l * per]), 0, 1, g_ld));
     if (m->has_bias)
       RAD_TRY(colsum_call(c, m->dyb[cur], m->dtype, B, N, nullptr, 0, nullptr, 0, 0,
                           static_cast<float*>(grads[l * per + 1]), nullptr, 0));
     if (l > 0) {
       rad_store* below = m->stores[(size_t)l - 1];
       RAD_TRY(dX_gemm(c, m->dtype, B, D, N, m->dyb[cur], nullptr, 0, Wp(l), m->dyb[cur ^ 1], below->bits,
-                      below->bits_pitch));
+                      below->bits_pitch, g_ld));
       cur ^= 1;
     }
   }

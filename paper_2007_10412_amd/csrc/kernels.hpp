@@ -86,8 +86,10 @@ hipError_t launch_gemm(int dtype, int a_kind, int b_kind, int epi, const GemmArg
                        hipStream_t st, const char** name);
 
 // ------------------------------------------------------------- small kernels
+// dz_ld > classes: rows of dlogits are dz_ld apart and their columns past `classes` are written as zeros (whole
+// 16-byte vectors only)
 hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows, int classes,
-                             int dtype, void* dlogits, float* row_loss, float* loss, hipStream_t st);
+                             int dtype, void* dlogits, float* row_loss, float* loss, hipStream_t st, int dz_ld = 0);
 // out[i*N + n] (+)= sum_b w_i[b] * g[b,n], i = 0..n_w; w_0 = 1 (bias gradient),
 // w_i = u[b*u_ld + i-1]; g = dy masked by bits.  partial: [splits][n_w+1][N] scratch.  With u_block_rows > 0 the
 // rows come in blocks of that many (time steps) and row b of block q weighs with u[b*u_ld + q*u_block_stride + i-1].
@@ -113,9 +115,10 @@ hipError_t launch_scale_cast(const float* in, void* out, int dtype, int64_t n, f
 // out[i] (+)= sum over `splits` partial arrays of n elements
 hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, int beta, hipStream_t st);
 // out[row_map[r] * ld + n] (+)= sum over `splits` arrays (stride elements apart) of partial[r * N + n], r < rows,
-// added in split order; row_map may be null (row r)
+// added in split order; row_map may be null (row r); in_ld > 0: the rows of a partial array are in_ld apart
 hipError_t launch_splitk_reduce_rows(const float* partial, int splits, int64_t stride, int rows, int N,
-                                     const uint16_t* row_map, float* out, int64_t ld, int beta, hipStream_t st);
+                                     const uint16_t* row_map, float* out, int64_t ld, int beta, hipStream_t st,
+                                     int64_t in_ld = 0);
 // fp32 forward GEMM finished from split-K partial sums [splits][M][N]: bias, low-rank term u V, ReLU, (h > 0) bits
 // (N a multiple of 64); and a dX finished from partial sums with the output mask of the layer below
 hipError_t launch_splitk_fwd_f32(const float* partial, int splits, int M, int N, const float* bias, const float* u,
@@ -124,7 +127,7 @@ hipError_t launch_splitk_fwd_f32(const float* partial, int splits, int M, int N,
 hipError_t launch_splitk_reduce_masked(const float* partial, int splits, int M, int N, const uint32_t* mask, int pitch,
                                        float* out, hipStream_t st);
 hipError_t launch_splitk_bias(const float* partial, int splits, int M, int N, const float* bias, void* out, int dtype,
-                              hipStream_t st);
+                              hipStream_t st, int64_t pld = 0);
 // 2x2/stride-2 max pool over NCHW planes; arg packs the 2-bit window position (dy*2+dx of the first maximum)
 // of 16 consecutive outputs per word
 hipError_t launch_maxpool_fwd(const float* y, int planes, int H, int W, float* pooled, uint32_t* arg, hipStream_t st);
@@ -161,8 +164,9 @@ hipError_t launch_channel_sum(const float* g, int batch, int C, int HW, float* d
 hipError_t launch_flip_weights(const float* W, int Ci, int KH, int KW, int Co, float* Wt, hipStream_t st);
 // Adds to dW the entries of (row, bucket) segments beyond the first `cap`, which the MFMA kernel leaves out;
 // exits at once when *max_seg <= cap (the plan's running maximum), which is the normal case.
+// (ldy > 0: the rows of dy are ldy apart)
 hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int dtype, int N, const uint32_t* bits,
-                              int bits_pitch, float* dW, int cap, const int* max_seg, hipStream_t st);
+                              int bits_pitch, float* dW, int cap, const int* max_seg, hipStream_t st, int64_t ldy = 0);
 // entries per (row, bucket) the bf16 sparse dW kernel chosen for `sparse_prefetch` handles itself
 int gemm_bf16_sparse_cap(int sparse_prefetch);
 int gemm_bf16_sparse_max_prefetch();

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const T* __restrict__ z
 // the row in registers, so the row is read once (16-byte loads) and every exponential is taken once.
 template <typename T, int NV>
 __global__ __launch_bounds__(256) void softmax_ce_vec_kernel(const T* __restrict__ z, const int32_t* __restrict__ labels,
-                                                             int rows, int classes, T* __restrict__ dz,
+                                                             int rows, int classes, T* __restrict__ dz, int dz_ld,
                                                              float* __restrict__ row_loss) {
   constexpr int VPL = 16 / (int)sizeof(T);            // elements per vector
   const int lane = threadIdx.x & 63;
@@ -86,7 +86,9 @@ __global__ __launch_bounds__(256) void softmax_ce_vec_kernel(const T* __restrict
   const int lab = labels[row];
   const bool lab_ok = lab >= 0 && lab < classes;     // a bad label poisons the loss instead of the address
   const float inv = 1.f / s, invb = 1.f / (float)rows;
-  T* dr = dz + (size_t)row * classes;
+  // dz rows are dz_ld apart (a multiple of VPL, at most 64 NV vectors); columns past `classes` are written as zeros
+  T* dr = dz + (size_t)row * dz_ld;
+  const int nvec_out = dz_ld / VPL;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int q = lane + i * 64;
@@ -99,6 +101,7 @@ __global__ __launch_bounds__(256) void softmax_ce_vec_kernel(const T* __restrict
       st_elem(oe + e, p * invb);
     }
     if (q < nvec) *reinterpret_cast<u32x4*>(dr + (size_t)q * VPL) = out;
+    else if (q < nvec_out) *reinterpret_cast<u32x4*>(dr + (size_t)q * VPL) = u32x4{0u, 0u, 0u, 0u};
   }
   if (lane == 0) row_loss[row] = lab_ok ? -(ld_elem(zr + lab) - m - logf(s)) : NAN;
 }
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 // when no segment is that long, which is the normal case (cap sits six standard deviations above the mean).
 template <typename T>
 __global__ __launch_bounds__(256) void dw_overflow_kernel(StoreView s, int rows, const T* __restrict__ dy, int N,
-                                                          const uint32_t* __restrict__ bits, int bits_pitch,
+                                                          int64_t ldy, const uint32_t* __restrict__ bits, int bits_pitch,
                                                           float* __restrict__ dW, int cap,
                                                           const int* __restrict__ max_seg) {
   if (*max_seg <= cap) return;
@@ -196,7 +199,7 @@ __global__ __launch_bounds__(256) void dw_overflow_kernel(StoreView s, int rows,
       j = s.indices[e]; v = ld_elem(vals + e);
     }
     for (int n = lane; n < N; n += 64) {
-      float g = ld_elem(dy + (size_t)b * N + n);
+      float g = ld_elem(dy + (size_t)b * ldy + n);
       if (bits && !((bits[(size_t)b * bits_pitch + (n >> 5)] >> (n & 31)) & 1u)) g = 0.f;
       atomicAdd(&dW[(size_t)j * N + n], v * g);
     }
@@ -259,10 +262,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_wide_kernel(const float4* _
 template <typename V>
 __global__ __launch_bounds__(256) void splitk_reduce_rows_kernel(const V* __restrict__ partial, int splits, int64_t stride,
                                                                  int rows, int NV, const uint16_t* __restrict__ row_map,
-                                                                 V* __restrict__ out, int64_t ldv, int beta) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= (int64_t)rows * NV) return;
-  const int r = (int)(i / NV), n = (int)(i - (int64_t)r * NV);
+                                                                 V* __restrict__ out, int64_t ldv, int beta, int64_t in_ldv) {
+  const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i0 >= (int64_t)rows * NV) return;
+  const int r = (int)(i0 / NV), n = (int)(i0 - (int64_t)r * NV);
+  const int64_t i = (int64_t)r * in_ldv + n;             // rows of a partial array are in_ldv apart
   float acc[sizeof(V) / 4];
   const V first = partial[i];
 #pragma unroll
@@ -286,17 +290,20 @@ __global__ __launch_bounds__(256) void splitk_reduce_rows_kernel(const V* __rest
 // Sum of the splits of a forward GEMM, plus bias, into the layer output (no activation): partial [splits][M][N]
 template <typename T>
 __global__ __launch_bounds__(256) void splitk_bias_kernel(const float* __restrict__ partial, int splits, int M, int N,
-                                                          const float* __restrict__ bias, T* __restrict__ out) {
+                                                          int64_t pld, int64_t pstride, const float* __restrict__ bias,
+                                                          T* __restrict__ out) {
   const int64_t n = (int64_t)M * N;
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= n) return;
-  // N is a multiple of 4 here, so the four elements share a row
-  float4 v = *reinterpret_cast<const float4*>(partial + i);
+  // N is a multiple of 4 here, so the four elements share a row; the rows of a partial array are pld apart
+  const int64_t row = i / N;
+  const int col = (int)(i - row * N);
+  const float* src = partial + row * pld + col;
+  float4 v = *reinterpret_cast<const float4*>(src);
   for (int s = 1; s < splits; ++s) {
-    const float4 t = *reinterpret_cast<const float4*>(partial + (size_t)s * n + i);
+    const float4 t = *reinterpret_cast<const float4*>(src + (size_t)s * pstride);
     v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
   }
-  const int col = (int)(i % N);
   if (bias) { v.x += bias[col]; v.y += bias[col + 1]; v.z += bias[col + 2]; v.w += bias[col + 3]; }
   st_elem(out + i, v.x); st_elem(out + i + 1, v.y); st_elem(out + i + 2, v.z); st_elem(out + i + 3, v.w);
 }
@@ -489,17 +496,19 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p,
 }  // namespace
 
 hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows, int classes, int dtype,
-                             void* dlogits, float* row_loss, float* loss, hipStream_t st) {
+                             void* dlogits, float* row_loss, float* loss, hipStream_t st, int dz_ld) {
   dim3 grid((rows + 3) / 4), block(256);
   const int vpl = dtype == kF32 ? 4 : 8;
-  const bool vec = classes % vpl == 0 && classes / vpl <= 128 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0 &&
-                   (reinterpret_cast<uintptr_t>(dlogits) & 15) == 0;
+  if (dz_ld <= 0) dz_ld = classes;
+  const bool vec = classes % vpl == 0 && dz_ld % vpl == 0 && dz_ld / vpl <= 128 &&
+                   (reinterpret_cast<uintptr_t>(logits) & 15) == 0 && (reinterpret_cast<uintptr_t>(dlogits) & 15) == 0;
+  if (dz_ld != classes && !vec) return hipErrorInvalidValue;      // only the vector kernels write pitched rows
   if (vec && dtype == kF32)
     hipLaunchKernelGGL((softmax_ce_vec_kernel<float, 2>), grid, block, 0, st, (const float*)logits, labels, rows, classes,
-                       (float*)dlogits, row_loss);
+                       (float*)dlogits, dz_ld, row_loss);
   else if (vec)
     hipLaunchKernelGGL((softmax_ce_vec_kernel<uint16_t, 2>), grid, block, 0, st, (const uint16_t*)logits, labels, rows,
-                       classes, (uint16_t*)dlogits, row_loss);
+                       classes, (uint16_t*)dlogits, dz_ld, row_loss);
   else if (dtype == kF32)
     hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, block, 0, st, (const float*)logits, labels, rows, classes,
                        (float*)dlogits, row_loss);
@@ -528,17 +537,18 @@ hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint3
 }
 
 hipError_t launch_dw_overflow(const StoreView& s, int rows, const void* dy, int dtype, int N, const uint32_t* bits,
-                              int bits_pitch, float* dW, int cap, const int* max_seg, hipStream_t st) {
+                              int bits_pitch, float* dW, int cap, const int* max_seg, hipStream_t st, int64_t ldy) {
+  if (ldy <= 0) ldy = N;
   // almost always the kernel only reads *max_seg and leaves: a small grid keeps that cheap, and the
   // workgroups walk the segments in strides when there is work
   const int segs = rows * s.nb;
   const int blocks = (segs + 3) / 4;
   dim3 grid(blocks < 256 ? blocks : 256), block(256);
   if (dtype == kF32)
-    hipLaunchKernelGGL(dw_overflow_kernel<float>, grid, block, 0, st, s, rows, (const float*)dy, N, bits, bits_pitch,
+    hipLaunchKernelGGL(dw_overflow_kernel<float>, grid, block, 0, st, s, rows, (const float*)dy, N, ldy, bits, bits_pitch,
                        dW, cap, max_seg);
   else
-    hipLaunchKernelGGL(dw_overflow_kernel<uint16_t>, grid, block, 0, st, s, rows, (const uint16_t*)dy, N, bits,
+    hipLaunchKernelGGL(dw_overflow_kernel<uint16_t>, grid, block, 0, st, s, rows, (const uint16_t*)dy, N, ldy, bits,
                        bits_pitch, dW, cap, max_seg);
   return hipGetLastError();
 }
@@ -561,29 +571,36 @@ hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, flo
 }
 
 hipError_t launch_splitk_reduce_rows(const float* partial, int splits, int64_t stride, int rows, int N,
-                                     const uint16_t* row_map, float* out, int64_t ld, int beta, hipStream_t st) {
-  const bool vec = N % 4 == 0 && ld % 4 == 0 && stride % 4 == 0 &&
+                                     const uint16_t* row_map, float* out, int64_t ld, int beta, hipStream_t st,
+                                     int64_t in_ld) {
+  if (in_ld <= 0) in_ld = N;
+  const bool vec = N % 4 == 0 && ld % 4 == 0 && stride % 4 == 0 && in_ld % 4 == 0 &&
                    ((reinterpret_cast<uintptr_t>(partial) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
   if (vec) {
     const int64_t total = (int64_t)rows * (N / 4);
     hipLaunchKernelGGL(splitk_reduce_rows_kernel<float4>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        reinterpret_cast<const float4*>(partial), splits, stride / 4, rows, N / 4, row_map,
-                       reinterpret_cast<float4*>(out), ld / 4, beta);
+                       reinterpret_cast<float4*>(out), ld / 4, beta, in_ld / 4);
   } else {
     const int64_t total = (int64_t)rows * N;
     hipLaunchKernelGGL(splitk_reduce_rows_kernel<float>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial,
-                       splits, stride, rows, N, row_map, out, ld, beta);
+                       splits, stride, rows, N, row_map, out, ld, beta, in_ld);
   }
   return hipGetLastError();
 }
 
-// requires N % 4 == 0 and a 16-byte aligned partial array
+// requires N % 4 == 0 and a 16-byte aligned partial array; pld (a multiple of 4; 0: N) is the row pitch of a
+// partial array
 hipError_t launch_splitk_bias(const float* partial, int splits, int M, int N, const float* bias, void* out, int dtype,
-                              hipStream_t st) {
-  const int64_t n4 = (int64_t)M * N / 4;
+                              hipStream_t st, int64_t pld) {
+  if (pld <= 0) pld = N;
+  const int64_t n4 = (int64_t)M * N / 4, pstride = (int64_t)M * pld;
   dim3 grid((unsigned)((n4 + 255) / 256)), block(256);
-  if (dtype == kF32) hipLaunchKernelGGL(splitk_bias_kernel<float>, grid, block, 0, st, partial, splits, M, N, bias, (float*)out);
-  else hipLaunchKernelGGL(splitk_bias_kernel<uint16_t>, grid, block, 0, st, partial, splits, M, N, bias, (uint16_t*)out);
+  if (dtype == kF32)
+    hipLaunchKernelGGL(splitk_bias_kernel<float>, grid, block, 0, st, partial, splits, M, N, pld, pstride, bias, (float*)out);
+  else
+    hipLaunchKernelGGL(splitk_bias_kernel<uint16_t>, grid, block, 0, st, partial, splits, M, N, pld, pstride, bias,
+                       (uint16_t*)out);
   return hipGetLastError();
 }
 
