@@ -1021,7 +1021,7 @@ static rad_status dW_gemm(rad_ctx* c, const rad_store* s, int slot, const void* 
   // fraction 0.1: 14 + 92 us against 121 us).
   const bool dense_pays = s->dtype == kBF16 && n_slots == 1 && !bits && s->cols % 256 == 0 && N % 8 == 0 &&
                           (s->cols / 256) * (int64_t)((N + 255) / 256) >= 128 && s->rows % 8 == 0 && s->rows >= 1024 &&
-                          (size_t)s->cols * 2 <= 65536 && (reinterpret_cast<uintptr_t>(dy) & 15) == 0;
+                          (size_t)s->cols * 2 <= 60 * 1024 && (reinterpret_cast<uintptr_t>(dy) & 15) == 0;
   if (s->dtype == kBF16 && (dense_pays || g.sparse_prefetch > gemm_bf16_sparse_max_prefetch())) {
     // (also: stores dense enough that scattering into LDS loses to a plain contraction whatever the shape.)
     // x~ is a transient dense operand, one layer's worth, reused by the next layer

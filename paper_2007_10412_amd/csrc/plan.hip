@@ -594,7 +594,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(StoreView s, T* __restrict_
 }
 
 // The same with the row assembled in LDS (cleared and scattered there) and written out once, in 16-byte vectors:
-// rows of up to 64 KB whose length is a whole number of vectors.
+// rows of up to 60 KB whose length is a whole number of vectors.
 template <typename T>
 __global__ __launch_bounds__(256) void unpack_lds_kernel(StoreView s, T* __restrict__ dense) {
   extern __shared__ __align__(16) unsigned char s_row_raw[];
@@ -676,7 +676,8 @@ hipError_t launch_unpack_bitmap(const StoreView& s, int dtype, void* dense, hipS
 
 hipError_t launch_unpack(const StoreView& s, int dtype, void* dense, hipStream_t st) {
   const size_t row_bytes = (size_t)s.cols * (dtype == kF32 ? 4 : 2);
-  if (row_bytes % 16 == 0 && row_bytes <= 65536 && (reinterpret_cast<uintptr_t>(dense) & 15) == 0) {
+  // (the row and the bucket offsets share the 64 KB of LDS a launch gets without asking for more)
+  if (row_bytes % 16 == 0 && row_bytes <= 60 * 1024 && (reinterpret_cast<uintptr_t>(dense) & 15) == 0) {
     if (dtype == kF32) hipLaunchKernelGGL(unpack_lds_kernel<float>, dim3(s.rows), dim3(256), row_bytes, st, s, (float*)dense);
     else hipLaunchKernelGGL(unpack_lds_kernel<uint16_t>, dim3(s.rows), dim3(256), row_bytes, st, s, (uint16_t*)dense);
     return hipGetLastError();
