@@ -1116,6 +1116,7 @@ static rad_status colsum_call(rad_ctx* c, const void* dy, int dtype, int rows, i
                               int bits_pitch, const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
                               int beta, int u_block_rows = 0, int64_t u_block_stride = 0) {
   int splits = rows / 64;
+  if (rows <= 512) splits = 1;          // few rows: one launch that writes the sums itself
   if (splits < 1) splits = 1;
   if (splits > 32) splits = 32;
   void* part = nullptr;

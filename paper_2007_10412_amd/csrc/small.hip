@@ -126,7 +126,9 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
                                                              const uint32_t* __restrict__ bits, int bits_pitch,
                                                              const float* __restrict__ u, int64_t u_ld, int u_n,
                                                              int u_block_rows, int64_t u_block_stride,
-                                                             float* __restrict__ partial, int splits) {
+                                                             float* __restrict__ partial, int splits,
+                                                             float* __restrict__ out_bias, float* __restrict__ out_u,
+                                                             int beta) {
   __shared__ float s_red[4][kMaxU + 1][64];
   const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
   const int col = blockIdx.x * 64 + cx;
@@ -154,7 +156,10 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
   if (ry == 0 && col < N) {
     for (int i = 0; i <= u_n; ++i) {
       const float v = s_red[0][i][cx] + s_red[1][i][cx] + s_red[2][i][cx] + s_red[3][i][cx];
-      partial[((size_t)split * (u_n + 1) + i) * N + col] = v;
+      if (splits > 1) { partial[((size_t)split * (u_n + 1) + i) * N + col] = v; continue; }
+      // one split: this is the result (few rows: a second launch would cost more than it adds)
+      float* dst = i == 0 ? (out_bias ? out_bias + col : nullptr) : (out_u ? out_u + (size_t)(i - 1) * N + col : nullptr);
+      if (dst) *dst = beta ? *dst + v : v;
     }
   }
 }
@@ -527,11 +532,12 @@ hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint3
   dim3 grid((N + 63) / 64, splits), block(256);
   if (dtype == kF32)
     hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, block, 0, st, (const float*)dy, rows, N, bits, bits_pitch,
-                       u, u_ld, u_n, u_block_rows, u_block_stride, partial, splits);
+                       u, u_ld, u_n, u_block_rows, u_block_stride, partial, splits, out_bias, out_u, beta);
   else
     hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)dy, rows, N, bits,
-                       bits_pitch, u, u_ld, u_n, u_block_rows, u_block_stride, partial, splits);
-  hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 255) / 256), dim3(256), 0, st, partial, splits, N, u_n, out_bias,
+                       bits_pitch, u, u_ld, u_n, u_block_rows, u_block_stride, partial, splits, out_bias, out_u, beta);
+  if (splits > 1)
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 255) / 256), dim3(256), 0, st, partial, splits, N, u_n, out_bias,
                      out_u, beta);
   return hipGetLastError();
 }
