@@ -1114,7 +1114,7 @@ static rad_status dX_gemm(rad_ctx* c, int dtype, int M, int d_in, int d_out, con
 
 static rad_status colsum_call(rad_ctx* c, const void* dy, int dtype, int rows, int N, const uint32_t* bits,
                               int bits_pitch, const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
-                              int beta, int u_block_rows = 0, int64_t u_block_stride = 0) {
+                              int beta, int u_block_rows = 0, int64_t u_block_stride = 0, int64_t dy_ld = 0) {
   int splits = rows / 64;
   if (rows <= 512) splits = 1;          // few rows: one launch that writes the sums itself
   if (splits < 1) splits = 1;
@@ -1123,7 +1123,7 @@ static rad_status colsum_call(rad_ctx* c, const void* dy, int dtype, int rows, i
   RAD_TRY(ws_get(c, WS_COLSUM, (size_t)splits * (u_n + 1) * N * 4, &part));
   HIP_TRY(c, timed(c, "colsum", [&](const char**) {
     return launch_colsum(dy, dtype, rows, N, bits, bits_pitch, u, u_ld, u_n, out_bias, out_u, beta,
-                         static_cast<float*>(part), splits, c->stream, u_block_rows, u_block_stride);
+                         static_cast<float*>(part), splits, c->stream, u_block_rows, u_block_stride, dy_ld);
   }));
   return RAD_OK;
 }
@@ -1446,8 +1446,7 @@ extern "C" rad_status rad_model_create_mlp(rad_ctx* c, int32_t dtype, int64_t ba
   // rows and only the reduction of dW's split-K partial sums knows the real width.
   {
     const int64_t n_last = dims[n_layers], np = (n_last + 255) / 256 * 256;
-    // (models with biases keep the plain layout: the bias gradient's column sums read rows of the real width)
-    if (!has_bias && n_last % 256 != 0 && n_last % 8 == 0 && np / 8 <= 128 &&
+    if (n_last % 256 != 0 && n_last % 8 == 0 && np / 8 <= 128 &&
         dw_pitched_ok(m->stores.back(), (int)n_last, (int)np)) {
       m->last_pitch = (int)np;
       if (np > widest) widest = np;
@@ -1570,7 +1569,7 @@ static rad_status mlp_step(rad_ctx* c, rad_model* m, const rad_sampling* sm, con
     RAD_TRY(dW_gemm(c, s, 0, m->dyb[cur], N, nullptr, 0, static_cast<float*>(grads[l * per]), 0, 1, g_ld));
     if (m->has_bias)
       RAD_TRY(colsum_call(c, m->dyb[cur], m->dtype, B, N, nullptr, 0, nullptr, 0, 0,
-                          static_cast<float*>(grads[l * per + 1]), nullptr, 0));
+                          static_cast<float*>(grads[l * per + 1]), nullptr, 0, 0, 0, g_ld));
     if (l > 0) {
       rad_store* below = m->stores[(size_t)l - 1];
       RAD_TRY(dX_gemm(c, m->dtype, B, D, N, m->dyb[cur], nullptr, 0, Wp(l), m->dyb[cur ^ 1], below->bits,

@@ -96,7 +96,7 @@ hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows
 hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint32_t* bits, int bits_pitch,
                          const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u,
                          int beta, float* partial, int splits, hipStream_t st, int u_block_rows = 0,
-                         int64_t u_block_stride = 0);
+                         int64_t u_block_stride = 0, int64_t ldy = 0);       // ldy > 0: the rows of dy are ldy apart
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t st);
 // Rademacher matrix of the projection scheme: R [d][kp] and its transpose Rt [kp][d] in the given dtype, +1 / -1
 // from the key stream (entry (j, s) = bit j*k + s), zero in the padding columns s >= k (both must be zeroed first)

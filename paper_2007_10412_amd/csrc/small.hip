@@ -122,7 +122,7 @@ constexpr int kMaxU = 8;
 
 // stage 1 of the weighted column sums of g = dy * bits
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ dy, int rows, int N,
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ dy, int rows, int N, int64_t ldy,
                                                              const uint32_t* __restrict__ bits, int bits_pitch,
                                                              const float* __restrict__ u, int64_t u_ld, int u_n,
                                                              int u_block_rows, int64_t u_block_stride,
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
   for (int i = 0; i <= kMaxU; ++i) acc[i] = 0.f;
   if (col < N) {
     for (int r = rbeg + ry; r < rend; r += 4) {
-      float g = ld_elem(dy + (size_t)r * N + col);
+      float g = ld_elem(dy + (size_t)r * ldy + col);
       if (bits && !((bits[(size_t)r * bits_pitch + (col >> 5)] >> (col & 31)) & 1u)) g = 0.f;
       acc[0] += g;
       // rows come in blocks of u_block_rows (time steps): row b of block q weighs with u[b u_ld + q u_block_stride + i]
@@ -526,15 +526,17 @@ hipError_t launch_softmax_ce(const void* logits, const int32_t* labels, int rows
 
 hipError_t launch_colsum(const void* dy, int dtype, int rows, int N, const uint32_t* bits, int bits_pitch,
                          const float* u, int64_t u_ld, int u_n, float* out_bias, float* out_u, int beta,
-                         float* partial, int splits, hipStream_t st, int u_block_rows, int64_t u_block_stride) {
+                         float* partial, int splits, hipStream_t st, int u_block_rows, int64_t u_block_stride,
+                         int64_t ldy) {
   if (u_n > kMaxU) return hipErrorInvalidValue;
+  if (ldy <= 0) ldy = N;
   if (u_block_rows <= 0) { u_block_rows = rows > 0 ? rows : 1; u_block_stride = 0; }
   dim3 grid((N + 63) / 64, splits), block(256);
   if (dtype == kF32)
-    hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, block, 0, st, (const float*)dy, rows, N, bits, bits_pitch,
+    hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, block, 0, st, (const float*)dy, rows, N, ldy, bits, bits_pitch,
                        u, u_ld, u_n, u_block_rows, u_block_stride, partial, splits, out_bias, out_u, beta);
   else
-    hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)dy, rows, N, bits,
+    hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)dy, rows, N, ldy, bits,
                        bits_pitch, u, u_ld, u_n, u_block_rows, u_block_stride, partial, splits, out_bias, out_u, beta);
   if (splits > 1)
     hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 255) / 256), dim3(256), 0, st, partial, splits, N, u_n, out_bias,

@@ -35,6 +35,16 @@ def test_config4_full(ctx, scheme, p):
     run_mlp(ctx, data, dims, scheme, p, seed=1000, dtype=B.RAD_BF16, has_bias=False)
 
 
+def test_config4_full_with_biases(ctx):
+    """The same network with biases (per-example fixed-k, fraction 0.1): the bias gradients are column sums of the
+    loss gradient, which this model keeps with rows padded to 1024 for its 1000-wide last layer."""
+    from paper_2007_10412_amd import binding as B, synth
+    from tests.test_gpu_mlp import run_mlp
+    dims = (4096, 4096, 4096, 1000)
+    data = synth.mlp(seed=4321, batch=4096, dims=dims, pixels=False, bf16=True, bias_scale=0.1)
+    run_mlp(ctx, data, dims, 3, 0.1, seed=1001, dtype=B.RAD_BF16, has_bias=True)
+
+
 def test_config5_full(ctx):
     from paper_2007_10412_amd import synth
     from tests.test_gpu_rnn import run_rnn
